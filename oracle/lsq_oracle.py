@@ -1,0 +1,410 @@
+"""CPU oracle for beam-search Transformer decoding.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this file.  It shares no code with the HIP library and never calls it.
+
+What it computes.  Given the logits, the paper's hierarchical search (sec. 2.2:
+retrieve, then re-rank) reaches exactly the result of the plain procedure it
+replaces (sec. 2.2, the two enumerated whole-vocabulary calculations): softmax
+over the vocabulary, add the hypothesis score, keep the k best (beam, token)
+pairs.  Operator fusion (sec. 2.1) and memory reuse (sec. 2.3) change no value.
+So this oracle is the plain definition written out: a Transformer
+encoder-decoder forward pass (the paper defers the model to Vaswani et al.,
+sec. 3.1) and textbook beam search with a full sort.  Plain numpy, one
+operation per line, no blocking or fusion; ``@`` (matmul), ``einsum`` and
+``lexsort`` are the library primitives used as steps.
+
+Precision.  Arithmetic is IEEE fp32 (``ctype``; fp64 can be asked for).  With
+``storage='blob'`` and an fp16 blob, every tensor the model *stores* between
+operations (embedding sum, each projection after its bias/activation, attention
+context, LayerNorm output, K/V cache entries, logits) is rounded to fp16 and
+widened again, which is what "fp16 weights and activations, fp32 accumulate"
+means; softmax statistics, probabilities, log-probabilities and hypothesis
+scores are never rounded below fp32.  ``storage='wide'`` rounds nothing.
+
+Readings of points the paper leaves open (it gives no model equations):
+  * one embedding table shared by source, target and the output projection;
+    inputs scaled by sqrt(d); no output bias;
+  * sinusoidal positions PE(p,2i)=sin(p/10000^(2i/d)), PE(p,2i+1)=cos(same),
+    positions from 0, evaluated in double precision;
+  * post-LN residual blocks, ReLU, LayerNorm with biased variance and eps from
+    the blob; attention scale 1/sqrt(dh) applied to q.k; masked keys excluded;
+  * beam search prunes on the raw cumulative log-probability; candidates are
+    ordered by (score descending, flat index beam*V+token ascending); a finished
+    hypothesis stays in the beam with a frozen score and offers one candidate
+    (its score, token EOS); a hypothesis finishes on EOS or on reaching
+    cap = min(src_len + cap_extra, max_len); the returned score is
+    score / len^alpha (len counts EOS), beams sorted by (that descending, beam
+    index ascending).
+
+Pins (tests/test_oracle_*.py): softmax rows sum to one and are shift invariant;
+LayerNorm gives mean 0 / variance 1 and agrees with torch; PE closed forms; one
+encoder and one decoder layer agree with torch.nn.TransformerEncoderLayer /
+TransformerDecoderLayer loaded with the same weights; cached decoding equals
+full recomputation of the prefix; top-k equals a brute-force scan; beam 1 equals
+greedy; a beam at least vocab^len wide equals exhaustive enumeration; the
+paper's retrieve threshold keeps a superset of the top-k.  The readings listed
+above are pinned only by those library routines and invariants, not by the
+paper, which prints no worked value: parity unpinned against the paper for them.
+"""
+from __future__ import annotations
+
+import struct
+
+import numpy as np
+
+_MAGIC = b"LSQBLOB1"
+
+
+# ----------------------------------------------------------------------------
+# blob reader (own statement of the format; the writer lives elsewhere)
+# ----------------------------------------------------------------------------
+class Model:
+    """Hyper-parameters and tensors of one blob, tensors widened to ``ctype``."""
+
+    def __init__(self, blob: bytes, ctype=np.float32, storage: str = "blob"):
+        if len(blob) < 256 or blob[:8] != _MAGIC:
+            raise ValueError("not a model blob")
+        (ver, self.arch, self.n_enc, self.n_dec, self.d, self.H, self.F, self.V, self.max_pos,
+         self.act, self.norm, self.dtype, self.pad, self.bos, self.eos, self.cap_extra,
+         self.sample_topk) = struct.unpack_from("<17i", blob, 8)
+        self.alpha, self.eps = struct.unpack_from("<2f", blob, 76)
+        self.seed, total = struct.unpack_from("<2Q", blob, 88)
+        if ver != 1 or total != len(blob) or self.arch != 0 or self.norm != 0 or self.act != 0:
+            raise ValueError("unsupported blob")
+        if self.d % self.H:
+            raise ValueError("d_model not divisible by heads")
+        self.dh = self.d // self.H
+        self.ctype = ctype
+        assert storage in ("blob", "wide")
+        self.round16 = (storage == "blob" and self.dtype == 1)
+        src_dt = np.float16 if self.dtype == 1 else np.float32
+        esz = 2 if self.dtype == 1 else 4
+        pos = 256
+        d, F, V = self.d, self.F, self.V
+
+        def take(*shape):
+            nonlocal pos
+            pos = (pos + 255) // 256 * 256
+            n = int(np.prod(shape))
+            a = np.frombuffer(blob, src_dt, n, pos).reshape(shape).astype(ctype)
+            pos += n * esz
+            return a
+
+        self.E = take(V, d)
+        self.enc = []
+        for _ in range(self.n_enc):
+            L = {}
+            L["Wqkv"], L["bqkv"], L["Wo"], L["bo"] = take(d, 3 * d), take(3 * d), take(d, d), take(d)
+            L["ln1_g"], L["ln1_b"] = take(d), take(d)
+            L["W1"], L["b1"], L["W2"], L["b2"] = take(d, F), take(F), take(F, d), take(d)
+            L["ln2_g"], L["ln2_b"] = take(d), take(d)
+            self.enc.append(L)
+        self.dec = []
+        for _ in range(self.n_dec):
+            L = {}
+            L["Wqkv"], L["bqkv"], L["Wo"], L["bo"] = take(d, 3 * d), take(3 * d), take(d, d), take(d)
+            L["ln1_g"], L["ln1_b"] = take(d), take(d)
+            L["Wq_c"], L["bq_c"] = take(d, d), take(d)
+            L["Wkv_c"], L["bkv_c"] = take(d, 2 * d), take(2 * d)
+            L["Wo_c"], L["bo_c"] = take(d, d), take(d)
+            L["ln2_g"], L["ln2_b"] = take(d), take(d)
+            L["W1"], L["b1"], L["W2"], L["b2"] = take(d, F), take(F), take(F, d), take(d)
+            L["ln3_g"], L["ln3_b"] = take(d), take(d)
+            self.dec.append(L)
+        if pos != len(blob):
+            raise ValueError("blob size does not match its header")
+
+    def store(self, x):
+        """Rounding applied where the model stores a tensor (see module docstring)."""
+        x = np.asarray(x, self.ctype)
+        if self.round16:
+            return x.astype(np.float16).astype(self.ctype)
+        return x
+
+
+# ----------------------------------------------------------------------------
+# elementary operations
+# ----------------------------------------------------------------------------
+def positional_encoding(p, d, ctype=np.float32):
+    """Sinusoidal position vector(s) for position(s) p (Vaswani et al. form; the
+    paper's configuration only says "sinusoidal")."""
+    p = np.atleast_1d(np.asarray(p, np.float64))
+    i = np.arange(0, d, 2, dtype=np.float64)
+    ang = p[:, None] / np.power(10000.0, i / d)[None, :]
+    pe = np.zeros((p.shape[0], d), np.float64)
+    pe[:, 0::2] = np.sin(ang)
+    pe[:, 1::2] = np.cos(ang)[:, : d // 2]
+    return pe.astype(ctype)
+
+
+def softmax(s):
+    """Softmax over the last axis; entries equal to -inf get probability 0."""
+    m = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def log_softmax(x):
+    """log of the vocabulary softmax (sec. 2.2, calculation 1), last axis."""
+    m = np.max(x, axis=-1, keepdims=True)
+    z = np.sum(np.exp(x - m), axis=-1, keepdims=True)
+    return (x - m) - np.log(z)
+
+
+def layer_norm(v, g, b, eps):
+    """Layer normalisation (the reduce operation of sec. 2.1): biased variance."""
+    mean = np.mean(v, axis=-1, keepdims=True)
+    c = v - mean
+    var = np.mean(c * c, axis=-1, keepdims=True)
+    return g * (c / np.sqrt(var + v.dtype.type(eps))) + b
+
+
+def attention(q, K, V, H, allowed=None):
+    """Multi-head scaled dot-product attention of queries q[nq,d] over keys
+    K[nk,d] / values V[nk,d]; ``allowed[nq,nk]`` (bool) masks keys out."""
+    nq, d = q.shape
+    nk = K.shape[0]
+    dh = d // H
+    qh = q.reshape(nq, H, dh)
+    Kh = K.reshape(nk, H, dh)
+    Vh = V.reshape(nk, H, dh)
+    s = np.einsum("qhd,khd->hqk", qh, Kh) * q.dtype.type(1.0 / np.sqrt(dh))
+    if allowed is not None:
+        s = np.where(allowed[None, :, :], s, -np.inf).astype(q.dtype)
+    p = softmax(s)
+    return np.einsum("hqk,khd->qhd", p, Vh).reshape(nq, d)
+
+
+def topk_by_full_sort(scores, flat, k):
+    """Indices (into the candidate arrays) of the k best candidates under the
+    total order (score descending, flat index ascending), by sorting them all
+    (sec. 2.2, calculation 2)."""
+    order = np.lexsort((flat, -scores))
+    return order[:k]
+
+
+def hars_retrieve(logits, k, groups):
+    """The paper's retrieve stage (sec. 2.2, the four enumerated steps) for one
+    beam: ``groups`` assigns each logit to one of k groups; the threshold R is
+    the smallest of the k group maxima; logits not below R survive.  ("Larger
+    than R" is read as >= R: R is itself a logit, and with k disjoint groups
+    the k-th largest logit is >= R, so the survivors contain the top k.)"""
+    m = np.array([logits[groups == g].max() for g in range(k)])
+    R = m.min()
+    return np.nonzero(logits >= R)[0], R
+
+
+# ----------------------------------------------------------------------------
+# encoder
+# ----------------------------------------------------------------------------
+def embed(model, ids, positions):
+    x = model.E[ids] * model.ctype(np.sqrt(model.d)) + positional_encoding(positions, model.d, model.ctype)
+    return model.store(x)
+
+
+def encoder_layer(model, L, x):
+    d = model.d
+    qkv = model.store(x @ L["Wqkv"] + L["bqkv"])
+    ctx = model.store(attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], model.H))
+    a = model.store(ctx @ L["Wo"] + L["bo"])
+    x = model.store(layer_norm(x + a, L["ln1_g"], L["ln1_b"], model.eps))
+    h = model.store(np.maximum(x @ L["W1"] + L["b1"], 0))
+    f = model.store(h @ L["W2"] + L["b2"])
+    return model.store(layer_norm(x + f, L["ln2_g"], L["ln2_b"], model.eps))
+
+
+def encode(model, src_ids, src_lens):
+    """Encoder memory of every sentence (its real tokens only) and, per decoder
+    layer, the cross-attention keys and values projected from it."""
+    memory, cross = [], []
+    for b, s in enumerate(src_lens):
+        s = int(s)
+        x = embed(model, np.asarray(src_ids[b][:s]), np.arange(s))
+        for L in model.enc:
+            x = encoder_layer(model, L, x)
+        memory.append(x)
+        kv = []
+        for L in model.dec:
+            t = model.store(x @ L["Wkv_c"] + L["bkv_c"])
+            kv.append((t[:, :model.d], t[:, model.d:]))
+        cross.append(kv)
+    return memory, cross
+
+
+# ----------------------------------------------------------------------------
+# decoder, one position for every hypothesis row, K/V cached
+# ----------------------------------------------------------------------------
+class DecodeState:
+    def __init__(self, model, src_lens, beam, max_len):
+        B = len(src_lens)
+        self.B, self.k, self.T = B, beam, max_len
+        M = B * beam
+        self.t = 0
+        self.tokens = np.full((M, max_len + 1), model.pad, np.int32)
+        self.tokens[:, 0] = model.bos
+        self.len = np.zeros(M, np.int32)
+        self.finished = np.zeros(M, bool)
+        self.score = np.full((B, beam), -np.inf, model.ctype)
+        self.score[:, 0] = 0
+        self.cap = np.minimum(np.asarray(src_lens, np.int64) + model.cap_extra, max_len).astype(np.int32)
+        self.Kc = [np.zeros((M, max_len, model.d), model.ctype) for _ in model.dec]
+        self.Vc = [np.zeros((M, max_len, model.d), model.ctype) for _ in model.dec]
+
+
+def decoder_logits_cached(model, st, cross):
+    """Logits of step st.t for all rows; appends this position's self-attention
+    key and value to the cache."""
+    d, k, t = model.d, st.k, st.t
+    M = st.B * k
+    last = st.tokens[np.arange(M), st.len]
+    y = embed(model, last, np.full(M, t))
+    for l, L in enumerate(model.dec):
+        qkv = model.store(y @ L["Wqkv"] + L["bqkv"])
+        st.Kc[l][:, t] = qkv[:, d:2 * d]
+        st.Vc[l][:, t] = qkv[:, 2 * d:]
+        ctx = np.empty((M, d), model.ctype)
+        for r in range(M):
+            ctx[r] = attention(qkv[r:r + 1, :d], st.Kc[l][r, :t + 1], st.Vc[l][r, :t + 1], model.H)[0]
+        a = model.store(model.store(ctx) @ L["Wo"] + L["bo"])
+        y = model.store(layer_norm(y + a, L["ln1_g"], L["ln1_b"], model.eps))
+        q = model.store(y @ L["Wq_c"] + L["bq_c"])
+        ctx = np.empty((M, d), model.ctype)
+        for b in range(st.B):
+            Ke, Ve = cross[b][l]
+            ctx[b * k:(b + 1) * k] = attention(q[b * k:(b + 1) * k], Ke, Ve, model.H)
+        a = model.store(model.store(ctx) @ L["Wo_c"] + L["bo_c"])
+        y = model.store(layer_norm(y + a, L["ln2_g"], L["ln2_b"], model.eps))
+        h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
+        f = model.store(h @ L["W2"] + L["b2"])
+        y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
+    return model.store(y @ model.E.T)
+
+
+def decoder_logits_full(model, prefix, Ke_Ve_per_layer):
+    """Logits after the last token of ``prefix`` (starting with BOS) for ONE
+    hypothesis, recomputing every position with a causal mask and no cache.
+    Must agree with the cached path (the K/V-cache invariant)."""
+    n = len(prefix)
+    d = model.d
+    y = embed(model, np.asarray(prefix), np.arange(n))
+    causal = np.tril(np.ones((n, n), bool))
+    for l, L in enumerate(model.dec):
+        qkv = model.store(y @ L["Wqkv"] + L["bqkv"])
+        ctx = model.store(attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], model.H, causal))
+        a = model.store(ctx @ L["Wo"] + L["bo"])
+        y = model.store(layer_norm(y + a, L["ln1_g"], L["ln1_b"], model.eps))
+        q = model.store(y @ L["Wq_c"] + L["bq_c"])
+        Ke, Ve = Ke_Ve_per_layer[l]
+        ctx = model.store(attention(q, Ke, Ve, model.H))
+        a = model.store(ctx @ L["Wo_c"] + L["bo_c"])
+        y = model.store(layer_norm(y + a, L["ln2_g"], L["ln2_b"], model.eps))
+        h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
+        f = model.store(h @ L["W2"] + L["b2"])
+        y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
+    return model.store(y[-1] @ model.E.T)
+
+
+# ----------------------------------------------------------------------------
+# beam search
+# ----------------------------------------------------------------------------
+def beam_select(model, st, logits):
+    """One pruning step on given logits [M,V]: per sentence, softmax over the
+    vocabulary, add the hypothesis score, keep the k best (beam, token) pairs
+    (sec. 2.2).  Returns token, parent, score arrays [B,k] and, per sentence,
+    the smallest gap between consecutive candidates among the k kept and the
+    first one dropped (inf when nothing was dropped)."""
+    B, k, V = st.B, st.k, model.V
+    logp = log_softmax(np.asarray(logits, model.ctype))
+    token = np.zeros((B, k), np.int32)
+    parent = np.zeros((B, k), np.int32)
+    score = np.zeros((B, k), model.ctype)
+    margin = np.full(B, np.inf)
+    for b in range(B):
+        cs, cf = [], []
+        for j in range(k):
+            r = b * k + j
+            if st.finished[r]:
+                cs.append(np.array([st.score[b, j]], model.ctype))
+                cf.append(np.array([j * V + model.eos], np.int64))
+            else:
+                cs.append(st.score[b, j] + logp[r])
+                cf.append(j * V + np.arange(V, dtype=np.int64))
+        cs = np.concatenate(cs)
+        cf = np.concatenate(cf)
+        order = np.lexsort((cf, -cs))
+        best = order[:k]
+        token[b] = cf[best] % V
+        parent[b] = cf[best] // V
+        score[b] = cs[best]
+        top = cs[order[:k + 1]].astype(np.float64)
+        fin = np.isfinite(top)
+        gaps = [top[i] - top[i + 1] for i in range(len(top) - 1) if fin[i] and fin[i + 1]]
+        if gaps:
+            margin[b] = min(gaps)
+    return token, parent, score, margin
+
+
+def beam_advance(model, st, token, parent, score):
+    """Adopt the selected candidates: gather histories and caches from the
+    parents ("cache refreshing", sec. 3.2), append tokens, update flags."""
+    B, k = st.B, st.k
+    rows = (np.arange(B)[:, None] * k + parent).reshape(-1)
+    st.tokens = st.tokens[rows].copy()
+    old_len = st.len[rows].copy()
+    old_fin = st.finished[rows].copy()
+    for l in range(len(st.Kc)):
+        st.Kc[l] = st.Kc[l][rows].copy()
+        st.Vc[l] = st.Vc[l][rows].copy()
+    tok = token.reshape(-1)
+    grow = ~old_fin
+    new_len = old_len + grow.astype(np.int32)
+    r = np.nonzero(grow)[0]
+    st.tokens[r, new_len[r]] = tok[r]
+    cap = np.repeat(st.cap, k)
+    st.finished = old_fin | (grow & ((tok == model.eos) | (new_len >= cap)))
+    st.len = new_len
+    st.score = score.copy()
+    st.t += 1
+    active = (~st.finished).reshape(B, k).any(axis=1)
+    return int(active.sum())
+
+
+def finalize(model, st):
+    """Length-normalised scores and best-first hypotheses per sentence."""
+    B, k = st.B, st.k
+    ln = st.len.reshape(B, k)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        norm = np.where(ln > 0, np.power(np.maximum(ln, 1).astype(model.ctype), model.ctype(model.alpha)), 1)
+        final = (st.score / norm).astype(model.ctype)
+    ids = np.full((B, k, st.T), model.pad, np.int32)
+    lens = np.zeros((B, k), np.int32)
+    scores = np.zeros((B, k), model.ctype)
+    for b in range(B):
+        order = np.lexsort((np.arange(k), -final[b]))
+        for i, j in enumerate(order):
+            r = b * k + j
+            n = int(st.len[r])
+            ids[b, i, :n] = st.tokens[r, 1:n + 1]
+            lens[b, i] = n
+            scores[b, i] = final[b, j]
+    return ids, lens, scores
+
+
+def translate(model, src_ids, src_lens, beam, max_len, max_steps=None, trace=None):
+    """Whole path: encode, then decode steps until every sentence is finished
+    (or ``max_steps``).  ``trace``, if a list, receives one dict per step."""
+    memory, cross = encode(model, src_ids, src_lens)
+    st = DecodeState(model, src_lens, beam, max_len)
+    steps = 0
+    while True:
+        logits = decoder_logits_cached(model, st, cross)
+        token, parent, score, margin = beam_select(model, st, logits)
+        active = beam_advance(model, st, token, parent, score)
+        steps += 1
+        if trace is not None:
+            trace.append(dict(logits=logits, token=token, parent=parent, score=score, margin=margin,
+                              active=active, finished=st.finished.copy(), len=st.len.copy()))
+        if active == 0 or (max_steps is not None and steps >= max_steps):
+            break
+    return finalize(model, st), st
