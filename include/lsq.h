@@ -1,0 +1,183 @@
+/*
+ * lsq -- beam-search Transformer decoding on one AMD MI355X (gfx950).
+ *
+ * C ABI of liblsq.so.  Plain pointers and sizes only.  "host" / "device" in a
+ * comment says where the pointed-to memory must live.  Every function returns
+ * LSQ_OK (0) or a non-negative count on success and a negative lsq_status on
+ * failure; nothing aborts or throws.  Argument, state and blob errors are
+ * detected before any device work is issued.  lsq_last_error() describes the
+ * most recent failure.
+ *
+ * There is one process-global context (the four principal calls carry no
+ * handle).  The library allocates no device memory at all: the caller hands
+ * over ONE device workspace (lsq_set_workspace) which lsq_init carves into
+ * weights, K/V caches and every intermediate, each at its maximum shape, with
+ * intermediates that are never live together sharing bytes -- the paper's
+ * dynamic-memory-reuse scheme (sec. 2.3).  Calls are not thread safe and all
+ * device work is issued on the one stream given to lsq_set_workspace.
+ *
+ * Call order:
+ *   lsq_workspace_bytes -> lsq_set_workspace -> lsq_init ->
+ *   ( lsq_encode -> lsq_decode_step* -> lsq_get_beams )* -> lsq_free
+ */
+#ifndef LSQ_H
+#define LSQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LSQ_OK = 0,
+  LSQ_E_ARG = -1,   /* null pointer, size out of range, id outside the vocabulary ... */
+  LSQ_E_STATE = -2, /* call out of order                                            */
+  LSQ_E_BLOB = -3,  /* weight blob: magic / version / size / unsupported variant     */
+  LSQ_E_NOMEM = -4, /* workspace smaller than lsq_workspace_bytes reports            */
+  LSQ_E_HIP = -5    /* a HIP runtime call failed; text in lsq_last_error()           */
+} lsq_status;
+
+#define LSQ_MAX_BEAM 8
+
+/* Bytes of device workspace that lsq_init will need for this model blob and
+ * these maxima (sec. 2.3: every dynamic shape is bounded when the service
+ * starts).  weights: host, the serialized model (format: 256-byte header, then
+ * tensors, see the blob writer); only its header is read here.
+ * max_batch >= 1 sentences, 1 <= beam <= LSQ_MAX_BEAM, max_len >= 1 bounds both
+ * the source length and the target length (= K/V cache positions). */
+int lsq_workspace_bytes(const void* weights, size_t weights_bytes, int max_batch, int beam,
+                        int max_len, size_t* out_bytes);
+
+/* Hands over the workspace (device, 256-byte aligned, `bytes` long) and the HIP
+ * stream (a hipStream_t passed as void*, NULL = the default stream).  The
+ * caller keeps ownership and must keep both alive until lsq_free. */
+int lsq_set_workspace(void* dev_ptr, size_t bytes, void* hip_stream);
+
+/* Parses the blob (host), lays out the workspace, uploads the weights (stored
+ * in their compute type already -- the paper folds the cast into weight loading,
+ * sec. 3.2) and builds the position table.  The blob may be freed afterwards.
+ * Synchronizes the stream before returning. */
+int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam, int max_len);
+
+/* Runs the encoder over a batch of variable-length sentences and resets the
+ * beams (the paper's problem statement: batched sequence-to-sequence generation
+ * with variable-length inputs, sec. 1 and Fig. 1).
+ * src_ids: host, int32 [batch, src_stride], sentence i uses its first
+ * src_lens[i] entries; src_lens: host, int32 [batch].
+ * 1 <= batch <= max_batch, 1 <= src_lens[i] <= src_stride <= max_len,
+ * 0 <= id < vocab.  Device work is enqueued; the call does not wait for it. */
+int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int src_stride);
+
+/* One auto-regressive step for every hypothesis of every sentence: decoder
+ * layers over the cached keys/values, vocabulary logits, log-softmax plus
+ * hypothesis score, the k best (beam, token) pairs per sentence, K/V-cache
+ * reorder by parent beam (sec. 2.2 and the "cache refreshing" of sec. 3.2).
+ * Returns the number of sentences that still have an unfinished hypothesis
+ * (0 = done); waits for the step to finish to read that count back.
+ * A step after every sentence finished, or after max_len steps, changes
+ * nothing and returns 0. */
+int lsq_decode_step(void);
+
+/* Enqueues up to n steps without waiting between them, then waits once and
+ * returns the active count after the last one.  Steps issued after everything
+ * finished leave the state unchanged. */
+int lsq_decode_steps(int n);
+
+/* Copies the hypotheses out, best first per sentence by length-normalised
+ * score = score / len^alpha.  All outputs are host memory:
+ * out_ids int32 [batch, beam, max_len] (tokens after BOS, through EOS if one
+ * was produced; pad_id beyond), out_lens int32 [batch, beam],
+ * out_scores float [batch, beam].  Legal after any number of steps. */
+int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores);
+
+/* Forgets the workspace and the model.  Frees only host-side bookkeeping. */
+void lsq_free(void);
+
+const char* lsq_last_error(void);
+
+/* Number of decode steps taken since the last lsq_encode. */
+int lsq_step_index(void);
+
+/* ------------------------------------------------------------------------- */
+/* Debug / test hooks: copy library state to host memory.  Floating-point data
+ * is always delivered as float32 whatever the model's storage type. `bytes`
+ * must equal the size of the item.  M = batch*beam rows, T = max_len.          */
+enum {
+  LSQ_DBG_LOGITS = 0,     /* float [M, vocab]  logits of the last step (always fp32)   */
+  LSQ_DBG_SCORE = 1,      /* float [M]         raw hypothesis scores                   */
+  LSQ_DBG_TOKENS = 2,     /* int32 [M, T+1]    token histories, BOS first              */
+  LSQ_DBG_LEN = 3,        /* int32 [M]                                                 */
+  LSQ_DBG_FINISHED = 4,   /* int32 [M]                                                 */
+  LSQ_DBG_PARENT = 5,     /* int32 [M]         parent beam (0..beam-1) of the last step */
+  LSQ_DBG_CAND_SCORE = 6, /* float [M, beam]   per-row top-k scores of the last step   */
+  LSQ_DBG_CAND_IDX = 7,   /* int32 [M, beam]   per-row top-k tokens (-1 = none)        */
+  LSQ_DBG_HIDDEN = 8,     /* float [M, d]      decoder output of the last step         */
+  LSQ_DBG_MEMORY = 9,     /* float [sum(src_lens), d] encoder output, sentences packed */
+  LSQ_DBG_CROSS_KV = 100, /* +layer: float [sum(src_lens), 2d]                          */
+  LSQ_DBG_CACHE_K = 200,  /* +layer: float [M, T, d]                                    */
+  LSQ_DBG_CACHE_V = 300   /* +layer: float [M, T, d]                                    */
+};
+int lsq_debug_read(int what, void* host_dst, size_t bytes);
+
+/* ------------------------------------------------------------------------- */
+/* Single-kernel entry points on caller-provided DEVICE buffers, for kernel-level
+ * parity tests and bandwidth / MFMA measurements.  dtype: 0 = float32,
+ * 1 = float16 storage (fp32 accumulation in both).  stream: hipStream_t as
+ * void*.  They need no context and enqueue without waiting.                    */
+
+/* C[M,N] = act(A[M,K] . B[N,K]^T + bias[N]); bias may be NULL.  The dense
+ * contractions of sec. 2.1.  flags: LSQ_GEMM_RELU applies max(.,0);
+ * LSQ_GEMM_F32_OUT (float16 inputs only) makes C float32, the accumulators
+ * unrounded, as the vocabulary-logit GEMM does.  K % 8 == 0 for float16. */
+#define LSQ_GEMM_RELU 1
+#define LSQ_GEMM_F32_OUT 2
+int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* C, int M, int N,
+               int K, int flags, void* stream);
+
+/* x[r,:] = LayerNorm(x[r,:] + a[r,:]) * gamma + beta, in place on x, biased
+ * variance, one launch and no intermediate (sec. 2.1).  a already holds the
+ * sublayer bias. */
+int lsq_k_add_layernorm(int dtype, void* x, const void* a, const void* gamma, const void* beta,
+                        int rows, int d, float eps, void* stream);
+
+/* Decoder self-attention of one new position per row over its cached keys:
+ * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions
+ * 0..nkeys-1 of Kc/Vc [rows, T, d]. */
+int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
+                         int rows, int heads, int d, int T, int nkeys, void* stream);
+
+/* Cross-attention: the `beam` rows of sentence b attend over that sentence's
+ * src_len[b] encoder positions, kv packed as [sum(src_len), 2d] = [K | V] with
+ * sentence b starting at row src_off[b] (both int32, device). */
+int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off,
+                          const int32_t* src_len, void* out, int batch, int beam, int heads, int d,
+                          void* stream);
+
+/* Retrieve stage of the hierarchical search (sec. 2.2) made exact: per row r of
+ * logits [M,V], cand = score[r] + log_softmax(logits[r,:]) and the k best
+ * (cand descending, token ascending) are written to out_score/out_idx [M,k].
+ * A finished row yields the single candidate (score[r], eos) and k-1 empty
+ * slots (idx -1).  score float32, finished int32. */
+int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int32_t* finished,
+                   int M, int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream);
+
+/* Re-rank stage: per sentence the k best of its k*k row candidates by
+ * (score descending, beam*V+token ascending); updates score, tokens [M,T+1],
+ * len, finished in place, writes parent [M] and adds the number of still-active
+ * sentences to *active (int32, device; caller zeroes it).  cap int32 [batch]. */
+int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
+                      int32_t* tokens, int32_t* len, int32_t* finished, int32_t* parent,
+                      const int32_t* cap, int32_t* active, int batch, int k, int V, int T, int t,
+                      int eos, void* stream);
+
+/* Cache refreshing (sec. 3.2): cache[l, b*k+i, 0:npos, :] <- cache[l, b*k+parent[b*k+i], 0:npos, :]
+ * for all layers, in place.  cache [layers, M, T, d]. */
+int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k,
+                        int T, int d, int npos, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSQ_H */

@@ -17,10 +17,12 @@ operation per line, no blocking or fusion; ``@`` (matmul), ``einsum`` and
 Precision.  Arithmetic is IEEE fp32 (``ctype``; fp64 can be asked for).  With
 ``storage='blob'`` and an fp16 blob, every tensor the model *stores* between
 operations (embedding sum, each projection after its bias/activation, attention
-context, LayerNorm output, K/V cache entries, logits) is rounded to fp16 and
-widened again, which is what "fp16 weights and activations, fp32 accumulate"
-means; softmax statistics, probabilities, log-probabilities and hypothesis
-scores are never rounded below fp32.  ``storage='wide'`` rounds nothing.
+context, LayerNorm output, K/V cache entries) is rounded to fp16 and widened
+again, which is what "fp16 weights and activations, fp32 accumulate" means; the
+vocabulary logits, softmax statistics, probabilities, log-probabilities and
+hypothesis scores are never rounded below fp32 (a logit rounded to fp16 moves by
+up to 2e-3 near |x| = 2..4, more than the 1e-3 score margin at which token ids
+must already agree).  ``storage='wide'`` rounds nothing.
 
 Readings of points the paper leaves open (it gives no model equations):
   * one embedding table shared by source, target and the output projection;
@@ -278,7 +280,7 @@ def decoder_logits_cached(model, st, cross):
         h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
         f = model.store(h @ L["W2"] + L["b2"])
         y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
-    return model.store(y @ model.E.T)
+    return y @ model.E.T
 
 
 def decoder_logits_full(model, prefix, Ke_Ve_per_layer):
@@ -302,7 +304,7 @@ def decoder_logits_full(model, prefix, Ke_Ve_per_layer):
         h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
         f = model.store(h @ L["W2"] + L["b2"])
         y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
-    return model.store(y[-1] @ model.E.T)
+    return y[-1] @ model.E.T
 
 
 # ----------------------------------------------------------------------------

@@ -1,0 +1,12 @@
+"""MI355X-native beam-search Transformer decoding (LightSeq's hot path, arxiv 2010.13887).
+
+The product is ``liblsq.so`` (hand-written HIP for gfx950 behind a C ABI, see include/lsq.h).
+This package is a thin ctypes binding with the same call names; PyTorch is used only to own
+the device workspace and the stream.  There is no CPU fallback: without the built library every
+call raises.
+"""
+from .binding import (LsqError, Engine, load_library, library_path, lsq_workspace_bytes,  # noqa: F401
+                      lsq_set_workspace, lsq_init, lsq_encode, lsq_decode_step, lsq_decode_steps,
+                      lsq_get_beams, lsq_free, lsq_last_error, lsq_step_index, lsq_debug_read,
+                      k_gemm, k_add_layernorm, k_self_attention, k_cross_attention, k_row_topk,
+                      k_beam_refine, k_cache_reorder, DBG)

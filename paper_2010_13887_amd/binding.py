@@ -1,0 +1,254 @@
+"""ctypes binding of liblsq.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class LsqError(RuntimeError):
+    pass
+
+
+class DBG:
+    LOGITS, SCORE, TOKENS, LEN, FINISHED, PARENT, CAND_SCORE, CAND_IDX, HIDDEN, MEMORY = range(10)
+    CROSS_KV, CACHE_K, CACHE_V = 100, 200, 300
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "liblsq.so")
+
+
+def load_library() -> C.CDLL:
+    """Loads the in-tree liblsq.so; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise LsqError(f"{path} is missing: build it with `python -m paper_2010_13887_amd.build` "
+                       "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(path)
+    vp, sz, i32, f32 = C.c_void_p, C.c_size_t, C.c_int, C.c_float
+    sig = {
+        "lsq_workspace_bytes": [vp, sz, i32, i32, i32, C.POINTER(sz)],
+        "lsq_set_workspace": [vp, sz, vp],
+        "lsq_init": [vp, sz, i32, i32, i32],
+        "lsq_encode": [vp, vp, i32, i32],
+        "lsq_decode_step": [],
+        "lsq_decode_steps": [i32],
+        "lsq_get_beams": [vp, vp, vp],
+        "lsq_step_index": [],
+        "lsq_debug_read": [i32, vp, sz],
+        "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_add_layernorm": [i32, vp, vp, vp, vp, i32, i32, f32, vp],
+        "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_row_topk": [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
+        "lsq_k_beam_refine": [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
+        "lsq_k_cache_reorder": [i32, vp, vp, i32, i32, i32, i32, i32, i32, vp],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.lsq_free.argtypes = []
+    lib.lsq_free.restype = None
+    lib.lsq_last_error.argtypes = []
+    lib.lsq_last_error.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+def lsq_last_error() -> str:
+    return load_library().lsq_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise LsqError(f"lsq error {rc}: {lsq_last_error()}")
+    return rc
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+# ---- the C calls, same names ---------------------------------------------------------------
+def lsq_workspace_bytes(blob: bytes, max_batch: int, beam: int, max_len: int) -> int:
+    n = C.c_size_t()
+    _check(load_library().lsq_workspace_bytes(blob, len(blob), max_batch, beam, max_len, C.byref(n)))
+    return n.value
+
+
+def lsq_set_workspace(dev_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(load_library().lsq_set_workspace(dev_ptr, nbytes, stream))
+
+
+def lsq_init(blob: bytes, max_batch: int, beam: int, max_len: int) -> None:
+    _check(load_library().lsq_init(blob, len(blob), max_batch, beam, max_len))
+
+
+def lsq_encode(src_ids, src_lens) -> None:
+    ids, lens = _host_i32(src_ids), _host_i32(src_lens)
+    if ids.ndim != 2 or lens.ndim != 1 or ids.shape[0] != lens.shape[0]:
+        raise LsqError("src_ids must be [batch, stride] and src_lens [batch]")
+    _check(load_library().lsq_encode(ids.ctypes.data, lens.ctypes.data, ids.shape[0], ids.shape[1]))
+
+
+def lsq_decode_step() -> int:
+    return _check(load_library().lsq_decode_step())
+
+
+def lsq_decode_steps(n: int) -> int:
+    return _check(load_library().lsq_decode_steps(n))
+
+
+def lsq_step_index() -> int:
+    return _check(load_library().lsq_step_index())
+
+
+def lsq_get_beams(batch: int, beam: int, max_len: int):
+    ids = np.empty((batch, beam, max_len), np.int32)
+    lens = np.empty((batch, beam), np.int32)
+    scores = np.empty((batch, beam), np.float32)
+    _check(load_library().lsq_get_beams(ids.ctypes.data, lens.ctypes.data, scores.ctypes.data))
+    return ids, lens, scores
+
+
+def lsq_free() -> None:
+    load_library().lsq_free()
+
+
+def lsq_debug_read(what: int, shape, dtype=np.float32) -> np.ndarray:
+    out = np.empty(shape, dtype)
+    _check(load_library().lsq_debug_read(what, out.ctypes.data, out.nbytes))
+    return out
+
+
+# ---- single-kernel entry points on torch tensors ----------------------------------------------
+def _dt(t) -> int:
+    import torch
+    if t.dtype == torch.float16:
+        return 1
+    if t.dtype == torch.float32:
+        return 0
+    raise LsqError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _p(t) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def k_gemm(A, B, bias, C_out, relu: bool = False) -> None:
+    """C_out = act(A . B^T + bias); a float32 C_out with float16 inputs keeps the accumulators unrounded."""
+    import torch
+    M, K = A.shape
+    N = B.shape[0]
+    assert B.shape[1] == K and tuple(C_out.shape) == (M, N)
+    flags = int(relu) | (2 if (A.dtype == torch.float16 and C_out.dtype == torch.float32) else 0)
+    assert flags & 2 or C_out.dtype == A.dtype
+    _check(load_library().lsq_k_gemm(_dt(A), _p(A), _p(B), _p(bias), _p(C_out), M, N, K, flags, _stream()))
+
+
+def k_add_layernorm(x, a, gamma, beta, eps: float) -> None:
+    rows, d = x.shape
+    _check(load_library().lsq_k_add_layernorm(_dt(x), _p(x), _p(a), _p(gamma), _p(beta), rows, d, eps, _stream()))
+
+
+def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:
+    rows, d = q.shape
+    T = Kc.shape[1]
+    _check(load_library().lsq_k_self_attention(_dt(q), _p(q), _p(Kc), _p(Vc), _p(out), rows, heads, d, T, nkeys,
+                                               _stream()))
+
+
+def k_cross_attention(q, kv, src_off, src_len, out, batch: int, beam: int, heads: int) -> None:
+    d = q.shape[1]
+    _check(load_library().lsq_k_cross_attention(_dt(q), _p(q), _p(kv), _p(src_off), _p(src_len), _p(out), batch,
+                                                beam, heads, d, _stream()))
+
+
+def k_row_topk(logits, score, finished, k: int, eos: int, out_score, out_idx) -> None:
+    M, V = logits.shape
+    _check(load_library().lsq_k_row_topk(_dt(logits), _p(logits), _p(score), _p(finished), M, V, k, eos,
+                                         _p(out_score), _p(out_idx), _stream()))
+
+
+def k_beam_refine(cand_score, cand_idx, score, tokens, length, finished, parent, cap, active, batch: int, k: int,
+                  V: int, T: int, t: int, eos: int) -> None:
+    _check(load_library().lsq_k_beam_refine(_p(cand_score), _p(cand_idx), _p(score), _p(tokens), _p(length),
+                                            _p(finished), _p(parent), _p(cap), _p(active), batch, k, V, T, t, eos,
+                                            _stream()))
+
+
+def k_cache_reorder(cache, parent, layers: int, batch: int, k: int, T: int, d: int, npos: int) -> None:
+    _check(load_library().lsq_k_cache_reorder(_dt(cache), _p(cache), _p(parent), layers, batch, k, T, d, npos,
+                                              _stream()))
+
+
+# ---- convenience: one object that owns the workspace -------------------------------------------
+class Engine:
+    """Owns the device workspace (a torch uint8 tensor) for one loaded model.  One per process."""
+
+    def __init__(self, blob: bytes, max_batch: int, beam: int, max_len: int, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise LsqError("no GPU visible; this library has no CPU path")
+        load_library()
+        self.max_batch, self.beam, self.max_len = max_batch, beam, max_len
+        nbytes = lsq_workspace_bytes(blob, max_batch, beam, max_len)
+        torch.cuda.set_device(device)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        lsq_set_workspace(self.workspace.data_ptr(), nbytes, self.stream)
+        try:
+            lsq_init(blob, max_batch, beam, max_len)
+        except Exception:
+            lsq_free()
+            raise
+        self.batch = 0
+
+    def encode(self, src_ids, src_lens) -> None:
+        lsq_encode(src_ids, src_lens)
+        self.batch = len(src_lens)
+
+    def decode_step(self) -> int:
+        return lsq_decode_step()
+
+    def decode_steps(self, n: int) -> int:
+        return lsq_decode_steps(n)
+
+    def get_beams(self):
+        return lsq_get_beams(self.batch, self.beam, self.max_len)
+
+    def debug(self, what: int, shape, dtype=np.float32):
+        return lsq_debug_read(what, shape, dtype)
+
+    def translate(self, src_ids, src_lens, sync_every: int = 1):
+        self.encode(src_ids, src_lens)
+        while self.decode_steps(sync_every) > 0:
+            pass
+        return self.get_beams()
+
+    def close(self) -> None:
+        lsq_free()
+        self.workspace = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -1,0 +1,178 @@
+// Memory-bound fused kernels between the GEMMs (paper sec. 2.1): token embedding + position,
+// and bias-free residual add + LayerNorm in one launch with no intermediate.
+#include "lsq_internal.h"
+
+namespace lsq {
+
+// ---------------------------------------------------------------------------------------------
+// x[r,:] = store(E[id_r,:] * sqrt(d) + PE[pos_r,:]).  Product and sum are rounded separately
+// (no fused multiply-add) so the fp32 value before storage is the textbook one.
+template <typename T>
+__device__ __forceinline__ void embed_row(const T* __restrict__ e, const float* __restrict__ pe,
+                                          T* __restrict__ x, int d, float scale, int lane, int nl) {
+  if ((d & 7) == 0) {
+    for (int c = lane * 8; c < d; c += nl * 8) {
+      float v[8];
+      Vec8<T>::load(e + c, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = __fadd_rn(__fmul_rn(v[i], scale), pe[c + i]);
+      Vec8<T>::store(x + c, v);
+    }
+  } else {
+    for (int c = lane; c < d; c += nl) x[c] = (T)__fadd_rn(__fmul_rn((float)e[c], scale), pe[c]);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ E, const float* __restrict__ pe,
+                                                         const int32_t* __restrict__ ids,
+                                                         const int32_t* __restrict__ pos, T* __restrict__ x,
+                                                         int rows, int d, float scale) {
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  embed_row<T>(E + (size_t)ids[r] * d, pe + (size_t)pos[r] * d, x + (size_t)r * d, d, scale,
+               threadIdx.x & 63, 64);
+}
+
+// Decoder input of step t: the last token of every hypothesis row.
+template <typename T>
+__global__ void __launch_bounds__(256) embed_last_kernel(const T* __restrict__ E, const float* __restrict__ pe,
+                                                         const int32_t* __restrict__ tokens,
+                                                         const int32_t* __restrict__ len, T* __restrict__ x,
+                                                         int rows, int d, int T1, int t, float scale) {
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  int id = tokens[(size_t)r * T1 + len[r]];
+  embed_row<T>(E + (size_t)id * d, pe + (size_t)t * d, x + (size_t)r * d, d, scale, threadIdx.x & 63, 64);
+}
+
+hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
+                             const int32_t* pos, void* x, int rows, int d, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  float scale = sqrtf((float)d);
+  dim3 g((rows + 3) / 4), b(256);
+  if (dtype == DT_F16)
+    embed_rows_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, ids, pos, (half_t*)x, rows, d, scale);
+  else
+    embed_rows_kernel<float><<<g, b, 0, s>>>((const float*)E, pe, ids, pos, (float*)x, rows, d, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
+                             const int32_t* len, void* x, int rows, int d, int T, int t, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  float scale = sqrtf((float)d);
+  dim3 g((rows + 3) / 4), b(256);
+  if (dtype == DT_F16)
+    embed_last_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, tokens, len, (half_t*)x, rows, d, T + 1, t, scale);
+  else
+    embed_last_kernel<float><<<g, b, 0, s>>>((const float*)E, pe, tokens, len, (float*)x, rows, d, T + 1, t, scale);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// x <- store(LayerNorm(x + a) * g + b): one wavefront per row, the row held in registers
+// (NV vectors of 8 per lane), mean then centred variance (biased), both by wave shuffles.
+template <typename T, int NV>
+__global__ void __launch_bounds__(256) add_layernorm_kernel(T* __restrict__ x, const T* __restrict__ a,
+                                                            const T* __restrict__ g, const T* __restrict__ b,
+                                                            int rows, int d, float eps) {
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  int lane = threadIdx.x & 63;
+  T* xr = x + (size_t)r * d;
+  const T* ar = a + (size_t)r * d;
+  float v[NV][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int c = (j * 64 + lane) * 8;
+    if (c < d) {
+      float av[8];
+      Vec8<T>::load(xr + c, v[j]);
+      Vec8<T>::load(ar + c, av);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] += av[i]; sum += v[j][i]; }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[j][i] = 0.f;
+    }
+  }
+  float mean = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int c = (j * 64 + lane) * 8;
+    if (c < d) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] -= mean; sq += v[j][i] * v[j][i]; }
+    }
+  }
+  float var = wave_sum(sq) / (float)d;
+  float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    int c = (j * 64 + lane) * 8;
+    if (c < d) {
+      float gv[8], bv[8], o[8];
+      Vec8<T>::load(g + c, gv);
+      Vec8<T>::load(b + c, bv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = gv[i] * (v[j][i] * rstd) + bv[i];
+      Vec8<T>::store(xr + c, o);
+    }
+  }
+}
+
+// Any d (not a multiple of 8, or longer than the register variant holds): three passes over memory.
+template <typename T>
+__global__ void __launch_bounds__(256) add_layernorm_generic_kernel(T* __restrict__ x, const T* __restrict__ a,
+                                                                    const T* __restrict__ g,
+                                                                    const T* __restrict__ b, int rows, int d,
+                                                                    float eps) {
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  int lane = threadIdx.x & 63;
+  T* xr = x + (size_t)r * d;
+  const T* ar = a + (size_t)r * d;
+  float sum = 0.f;
+  for (int c = lane; c < d; c += 64) sum += (float)xr[c] + (float)ar[c];
+  float mean = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    float t = ((float)xr[c] + (float)ar[c]) - mean;
+    sq += t * t;
+  }
+  float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
+  for (int c = lane; c < d; c += 64) {
+    float t = ((float)xr[c] + (float)ar[c]) - mean;
+    xr[c] = (T)((float)g[c] * (t * rstd) + (float)b[c]);
+  }
+}
+
+template <typename T>
+static hipError_t add_layernorm_t(T* x, const T* a, const T* g, const T* b, int rows, int d, float eps,
+                                  hipStream_t s) {
+  dim3 grid((rows + 3) / 4), blk(256);
+  if ((d & 7) != 0 || d > 4096)
+    add_layernorm_generic_kernel<T><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  else if (d <= 512)
+    add_layernorm_kernel<T, 1><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  else if (d <= 1024)
+    add_layernorm_kernel<T, 2><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  else if (d <= 2048)
+    add_layernorm_kernel<T, 4><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  else
+    add_layernorm_kernel<T, 8><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_add_layernorm(int dtype, void* x, const void* a, const void* g, const void* b, int rows,
+                                int d, float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dtype == DT_F16)
+    return add_layernorm_t<half_t>((half_t*)x, (const half_t*)a, (const half_t*)g, (const half_t*)b, rows, d, eps, s);
+  return add_layernorm_t<float>((float*)x, (const float*)a, (const float*)g, (const float*)b, rows, d, eps, s);
+}
+
+}  // namespace lsq

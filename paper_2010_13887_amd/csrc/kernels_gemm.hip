@@ -1,0 +1,231 @@
+// Dense contractions of the layer (paper sec. 2.1: "GEMM"), hand written for gfx950.
+//   C[M,N] = act(A[M,K] . B[N,K]^T + bias[N]),  A and B both K-contiguous, fp32 accumulation.
+// fp16: MFMA v_mfma_f32_32x32x16_f16 on LDS-staged tiles.  fp32: a plain LDS-tiled FMA kernel
+// (only the small fp32 configuration uses it).  Bias, ReLU and the output scatter (Q to the
+// activation buffer, K and V straight into the caches) are fused into the epilogue.
+#include "lsq_internal.h"
+
+namespace lsq {
+
+template <typename T>
+__device__ __forceinline__ void store_one(const GemmOut& o, int m, int n, float v) {
+  int s = n / o.seg_n;
+  reinterpret_cast<T*>(o.ptr[s])[(long)m * o.ld[s] + (n - s * o.seg_n)] = (T)v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32: 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread.
+__global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                       const float* __restrict__ bias, GemmOut out, int M,
+                                                       int N, int K, int relu) {
+  __shared__ float As[16][64 + 4];
+  __shared__ float Bs[16][64 + 4];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[4][4] = {};
+  const int lr = tid >> 2, lk = (tid & 3) * 4;   // this thread stages row lr, k-columns lk..lk+3
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int k = k0 + lk + i;
+      int m = m0 + lr, n = n0 + lr;
+      As[lk + i][lr] = (m < M && k < K) ? A[(size_t)m * K + k] : 0.f;
+      Bs[lk + i][lr] = (n < N && k < K) ? B[(size_t)n * K + k] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      float v = acc[i][j] + (bias ? bias[n] : 0.f);
+      if (relu) v = fmaxf(v, 0.f);
+      store_one<float>(out, m, n, v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp16 MFMA.  Block tile BM x BN, BK = 64, four wavefronts each owning a WM x WN sub-tile made of
+// 32x32 MFMA blocks.  Global -> registers (next tile) overlaps the MFMAs on the current LDS tile.
+// LDS rows are padded by 8 halves so the 16-byte fragment reads of 32 consecutive rows hit
+// distinct banks.  The MFMA is issued as D = Bfrag x Afrag, i.e. D[n][m]: a lane then owns four
+// consecutive n of one m, which makes the epilogue store an aligned 8-byte vector.
+template <int BM, int BN, int WM, int WN, typename OutT>
+__global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
+                                                       const half_t* __restrict__ bias, GemmOut out, int M,
+                                                       int N, int K, int relu, int vec_ok) {
+  constexpr int BK = 64, LDK = BK + 8;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int WAVES_N = BN / WN;
+  static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
+  constexpr int AV = BM * BK / 8 / 256, BV = BN * BK / 8 / 256;   // 16-byte vectors per thread
+  static_assert(AV >= 1 && BV >= 1, "tile too small");
+  __shared__ __attribute__((aligned(16))) half_t As[BM * LDK];
+  __shared__ __attribute__((aligned(16))) half_t Bs[BN * LDK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
+
+  half8_t ra[AV], rb[BV];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      int m = min(m0 + row, M - 1);
+      if (k0 + kc < K) ra[i] = *reinterpret_cast<const half8_t*>(A + (size_t)m * K + k0 + kc);
+      else ra[i] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      int n = min(n0 + row, N - 1);
+      if (k0 + kc < K) rb[i] = *reinterpret_cast<const half8_t*>(B + (size_t)n * K + k0 + kc);
+      else rb[i] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+  };
+  auto sstore = [&]() {
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      *reinterpret_cast<half8_t*>(&As[row * LDK + kc]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      *reinterpret_cast<half8_t*>(&Bs[row * LDK + kc]) = rb[i];
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  gload(0);
+  sstore();
+  __syncthreads();
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    const bool more = k0 + BK < K;
+    if (more) gload(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      half8_t af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const half8_t*>(&As[(wm + i * 32 + fr) * LDK + ks + fk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bf[j] = *reinterpret_cast<const half8_t*>(&Bs[(wn + j * 32 + fr) * LDK + ks + fk]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+    if (more) {
+      sstore();
+      __syncthreads();
+    }
+  }
+
+  // epilogue: lane owns m = .. + (lane & 31) and, per group vg, n = .. + vg*8 + (lane>>5)*4 + 0..3
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm + i * 32 + (lane & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int n = n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4;
+        if (n >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = acc[i][j][vg * 4 + e];
+          if (bias && n + e < N) v[e] += (float)bias[n + e];
+          if (relu) v[e] = fmaxf(v[e], 0.f);
+        }
+        if (vec_ok && n + 3 < N) {
+          int s = n / out.seg_n;
+          OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + (n - s * out.seg_n);
+          if constexpr (sizeof(OutT) == 2) {
+            half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
+            *reinterpret_cast<half4_t*>(dst) = h;
+          } else {
+            floatx4 f = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<floatx4*>(dst) = f;
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < N) store_one<OutT>(out, m, n + e, v[e]);
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN>
+static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
+                    int K, int relu, int vec_ok, hipStream_t s) {
+  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), blk(256);
+  if (out.f32_out)
+    gemm_f16_kernel<BM, BN, WM, WN, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  else
+    gemm_f16_kernel<BM, BN, WM, WN, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+}
+
+hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
+                       int N, int K, bool relu, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (K <= 0) return hipErrorInvalidValue;
+  if (dtype == DT_F32) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);
+    gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, (const float*)bias, out, M, N, K,
+                                         relu ? 1 : 0);
+    return hipGetLastError();
+  }
+  if (K % 8 != 0) return hipErrorInvalidValue;
+  int nseg = (N + out.seg_n - 1) / out.seg_n;
+  if (nseg > 3) return hipErrorInvalidValue;
+  int vec_ok = (out.seg_n % 4 == 0);
+  for (int i = 0; i < nseg; ++i)
+    if (out.ld[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & (out.f32_out ? 15 : 7)) != 0) vec_ok = 0;
+  const half_t* a = (const half_t*)A;
+  const half_t* b = (const half_t*)B;
+  const half_t* bi = (const half_t*)bias;
+  long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (M <= 32)
+    run_f16<32, 128, 32, 32>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+  else if (tiles128 >= 256)
+    run_f16<128, 128, 64, 64>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+  else
+    run_f16<64, 64, 32, 32>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+  return hipGetLastError();
+}
+
+}  // namespace lsq

@@ -1,0 +1,370 @@
+// Output layer of the auto-regressive search (paper sec. 2.2) and cache refreshing (sec. 3.2).
+//
+//  row_topk   -- "retrieve", made exact: one workgroup reads one row of logits ONCE into
+//                registers, computes the full-vocabulary max and sum-of-exponentials, forms
+//                cand = score + ((x - max) - log sum) for every token and keeps the row's k best
+//                by (cand descending, token ascending).  Nothing but k pairs per row is written.
+//  beam_refine-- "re-rank": per sentence the k best of the k*k survivors by (cand descending,
+//                beam*V + token ascending), then the hypothesis bookkeeping.
+//  cache_reorder -- gathers K/V cache rows by parent beam, in place.
+#include "lsq_internal.h"
+
+namespace lsq {
+
+// Total order used everywhere: higher score first, lower index first among equal scores.
+__device__ __forceinline__ bool precedes(float s1, int i1, float s2, int i2) {
+  return s1 > s2 || (s1 == s2 && i1 < i2);
+}
+
+template <int BLOCK>
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < BLOCK / 64; ++w) r = fmaxf(r, red[w]);
+  return r;
+}
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < BLOCK / 64; ++w) r += red[w];
+  return r;
+}
+
+// One workgroup of BLOCK threads per row; each thread holds NV*8 tokens in registers.
+// Token held in slot (j, e) of thread tid:  vectorised rows (V % 8 == 0): (j*BLOCK + tid)*8 + e;
+// otherwise (j*8 + e)*BLOCK + tid.
+template <typename T, int BLOCK, int NV>
+__global__ void __launch_bounds__(BLOCK) row_topk_kernel(const T* __restrict__ logits,
+                                                         const float* __restrict__ score,
+                                                         const int32_t* __restrict__ fin, int V, int k, int eos,
+                                                         float* __restrict__ out_score,
+                                                         int32_t* __restrict__ out_idx) {
+  __shared__ float red[BLOCK / 64];
+  __shared__ float reds[BLOCK / 64];
+  __shared__ int redi[BLOCK / 64];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float bs = score[r];
+  float* os = out_score + (size_t)r * k;
+  int32_t* oi = out_idx + (size_t)r * k;
+  if (fin[r]) {   // a finished hypothesis offers itself once
+    if (tid < k) { os[tid] = tid == 0 ? bs : -INFINITY; oi[tid] = tid == 0 ? eos : -1; }
+    return;
+  }
+  if (bs == -INFINITY) {   // every candidate is -inf: the order is by token alone
+    if (tid < k) { os[tid] = -INFINITY; oi[tid] = tid < V ? tid : -1; }
+    return;
+  }
+  const T* row = logits + (size_t)r * V;
+  const bool vec = (V & 7) == 0;
+  float x[NV * 8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    if (vec) {
+      int base = (j * BLOCK + tid) * 8;
+      if (base < V) {
+        float t[8];
+        Vec8<T>::load(row + base, t);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[j * 8 + e] = t[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[j * 8 + e] = -INFINITY;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int v = (j * 8 + e) * BLOCK + tid;
+        x[j * 8 + e] = v < V ? (float)row[v] : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, x[j * 8 + e]);
+  }
+  const float m = block_max<BLOCK>(mx, red);
+  float z = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) z += expf(x[i] - m);   // padding slots: exp(-inf) = 0
+  const float logz = logf(block_sum<BLOCK>(z, red));
+  // candidate scores, rounded exactly as (score + ((x - m) - logz)) with no fused operation
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
+
+  // k rounds: best candidate that comes strictly after the previous winner in the total order
+  float ps = INFINITY;
+  int pi = -1;
+  for (int round = 0; round < k; ++round) {
+    float cs = -INFINITY;
+    int ci = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int v = vec ? (j * BLOCK + tid) * 8 + e : (j * 8 + e) * BLOCK + tid;
+        float s = x[j * 8 + e];
+        bool ok = v < V && precedes(ps, pi, s, v) && (ci == 0x7fffffff || precedes(s, v, cs, ci));
+        if (ok) { cs = s; ci = v; }
+      }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      float s2 = __shfl_xor(cs, o, kWave);
+      int i2 = __shfl_xor(ci, o, kWave);
+      if (i2 != 0x7fffffff && (ci == 0x7fffffff || precedes(s2, i2, cs, ci))) { cs = s2; ci = i2; }
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) { reds[tid >> 6] = cs; redi[tid >> 6] = ci; }
+    __syncthreads();
+    cs = reds[0];
+    ci = redi[0];
+#pragma unroll
+    for (int w = 1; w < BLOCK / 64; ++w) {
+      float s2 = reds[w];
+      int i2 = redi[w];
+      if (i2 != 0x7fffffff && (ci == 0x7fffffff || precedes(s2, i2, cs, ci))) { cs = s2; ci = i2; }
+    }
+    if (ci == 0x7fffffff) {   // fewer than k tokens in the vocabulary
+      if (tid == 0) { os[round] = -INFINITY; oi[round] = -1; }
+    } else {
+      if (tid == 0) { os[round] = cs; oi[round] = ci; }
+      ps = cs;
+      pi = ci;
+    }
+  }
+}
+
+bool topk_supported(int V) { return V >= 1 && V <= 65536; }
+
+template <typename T>
+static hipError_t row_topk_t(const T* logits, const float* score, const int32_t* fin, int M, int V, int k,
+                             int eos, float* os, int32_t* oi, hipStream_t s) {
+  if (V <= 2048)
+    row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+  else if (V <= 8192)
+    row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+  else if (V <= 32768)
+    row_topk_kernel<T, 1024, 4><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+  else if (V <= 65536)
+    row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin, int M,
+                           int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, out_score, out_idx, s);
+  return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, out_score, out_idx, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One wavefront per sentence.  Lane c < k*k owns survivor (beam c / k, slot c % k).
+__global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict__ cand_score,
+                                                         const int32_t* __restrict__ cand_idx,
+                                                         float* __restrict__ score, int32_t* __restrict__ tokens,
+                                                         int32_t* __restrict__ len, int32_t* __restrict__ fin,
+                                                         int32_t* __restrict__ parent,
+                                                         const int32_t* __restrict__ cap,
+                                                         int32_t* __restrict__ active, int k, int V, int T1, int t,
+                                                         int eos) {
+  __shared__ int sh_parent[LSQ_MAX_BEAM_];
+  __shared__ int sh_unfinished;
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int kk = k * k;
+  if (lane == 0) sh_unfinished = 0;
+  float s = -INFINITY;
+  long flat = -1;
+  int tok = -1, j = 0;
+  if (lane < kk) {
+    j = lane / k;
+    s = cand_score[(size_t)b * kk + lane];
+    tok = cand_idx[(size_t)b * kk + lane];
+    if (tok >= 0) flat = (long)j * V + tok;
+  }
+  int rank = 0;
+  for (int c = 0; c < kk; ++c) {
+    float s2 = __shfl(s, c, kWave);
+    int t2 = __shfl(tok, c, kWave);
+    long f2 = t2 >= 0 ? (long)(c / k) * V + t2 : -1;
+    if (f2 >= 0 && (s2 > s || (s2 == s && f2 < flat))) ++rank;
+  }
+  const bool win = flat >= 0 && rank < k;
+  // read the parent's state before anyone overwrites it
+  int plen = 0, pfin = 0;
+  if (win) {
+    plen = len[b * k + j];
+    pfin = fin[b * k + j];
+    sh_parent[rank] = j;
+  }
+  __syncthreads();
+  // token histories: positions 0..t; every lane reads all k beams of a position, then writes
+  for (int p = lane; p <= t && p < T1; p += 64) {
+    int h[LSQ_MAX_BEAM_];
+#pragma unroll
+    for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
+      if (i < k) h[i] = tokens[(size_t)(b * k + i) * T1 + p];
+#pragma unroll
+    for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
+      if (i < k) {
+        int src = sh_parent[i], val = 0;
+#pragma unroll
+        for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
+          if (jj == src) val = h[jj];
+        if (src != i) tokens[(size_t)(b * k + i) * T1 + p] = val;
+      }
+  }
+  __syncthreads();
+  if (win) {
+    const int row = b * k + rank;
+    int nlen = plen, nfin = pfin;
+    if (!pfin) {
+      nlen = plen + 1;
+      tokens[(size_t)row * T1 + nlen] = tok;
+      nfin = (tok == eos || nlen >= cap[b]) ? 1 : 0;
+    }
+    len[row] = nlen;
+    fin[row] = nfin;
+    score[row] = s;
+    parent[row] = j;
+    if (!nfin) sh_unfinished = 1;
+  }
+  __syncthreads();
+  if (lane == 0 && sh_unfinished) atomicAdd(active, 1);
+}
+
+hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
+                              int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
+                              int32_t* active, int batch, int k, int V, int T, int t, int eos, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
+  beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
+                                          k, V, T + 1, t, eos);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// In-place gather of cache rows by parent.  A thread owns the same 16-byte column of all k rows
+// of one sentence: it loads the rows that some other row needs, then overwrites the rows whose
+// parent is not themselves.  No other thread touches those bytes, so no double buffer is needed,
+// rows that keep their own history cost nothing, and a sentence whose beams did not move is
+// skipped outright.  grid = (chunks of the used prefix, sentences, layers).
+template <int KB>
+__global__ void __launch_bounds__(256) cache_reorder_kernel(uint4* __restrict__ cache,
+                                                            const int32_t* __restrict__ parent, int k,
+                                                            long row_vecs, long used_vecs, long layer_vecs) {
+  const int b = blockIdx.y;
+  int par[KB];
+  unsigned need = 0, moved = 0;
+#pragma unroll
+  for (int i = 0; i < KB; ++i) {
+    par[i] = i < k ? parent[b * k + i] : i;
+    if (par[i] != i) { need |= 1u << par[i]; moved |= 1u << i; }
+  }
+  if (!moved) return;
+  uint4* base = cache + (size_t)blockIdx.z * layer_vecs + (size_t)b * k * row_vecs;
+  for (long v = (long)blockIdx.x * 1024 + threadIdx.x; v < used_vecs && v < (long)(blockIdx.x + 1) * 1024;
+       v += 256) {
+    uint4 val[KB];
+#pragma unroll
+    for (int i = 0; i < KB; ++i)
+      if (need >> i & 1) val[i] = base[i * row_vecs + v];
+#pragma unroll
+    for (int i = 0; i < KB; ++i)
+      if (moved >> i & 1) {
+        uint4 o = val[0];
+#pragma unroll
+        for (int jj = 1; jj < KB; ++jj)
+          if (par[i] == jj) o = val[jj];
+        base[i * row_vecs + v] = o;
+      }
+  }
+}
+
+hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k,
+                                int T, int d, int npos, hipStream_t s) {
+  if (batch <= 0 || layers <= 0 || npos <= 0 || k <= 1) return hipSuccess;
+  size_t esz = dtype == DT_F16 ? 2 : 4;
+  if ((d * esz) % 16 != 0 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
+  long row_vecs = (long)T * d * esz / 16, used = (long)npos * d * esz / 16;
+  long layer_vecs = (long)batch * k * row_vecs;
+  dim3 grid((unsigned)((used + 1023) / 1024), batch, layers), blk(256);
+  if (k <= 4)
+    cache_reorder_kernel<4><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, used, layer_vecs);
+  else
+    cache_reorder_kernel<8><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, used, layer_vecs);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+__global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict__ tokens, int32_t* __restrict__ len,
+                                  int32_t* __restrict__ fin, int32_t* __restrict__ active_counts, int M, int k,
+                                  int T1, int bos, int pad) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < M * T1) tokens[i] = (i % T1 == 0) ? bos : pad;
+  if (i < M) {
+    score[i] = (i % k == 0) ? 0.f : -INFINITY;
+    len[i] = 0;
+    fin[i] = 0;
+  }
+  if (i < T1) active_counts[i] = 0;
+}
+
+hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin, int32_t* active_counts,
+                             int batch, int k, int T, int bos, int pad, hipStream_t s) {
+  int M = batch * k, n = M * (T + 1);
+  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, M, k, T + 1, bos, pad);
+  return hipGetLastError();
+}
+
+// Length-normalised score and best-first order per sentence; one wavefront per sentence.
+__global__ void __launch_bounds__(64) finalize_kernel(const float* __restrict__ score,
+                                                      const int32_t* __restrict__ tokens,
+                                                      const int32_t* __restrict__ len, int32_t* __restrict__ out_ids,
+                                                      int32_t* __restrict__ out_lens, float* __restrict__ out_scores,
+                                                      int k, int T, float alpha, int pad) {
+  __shared__ int order[LSQ_MAX_BEAM_];
+  const int b = blockIdx.x, lane = threadIdx.x;
+  float f = -INFINITY;
+  int n = 0;
+  if (lane < k) {
+    n = len[b * k + lane];
+    float sc = score[b * k + lane];
+    float den = n > 0 ? (alpha == 1.0f ? (float)n : powf((float)n, alpha)) : 1.0f;
+    f = sc / den;
+  }
+  int rank = 0;
+  for (int c = 0; c < k; ++c) {
+    float f2 = __shfl(f, c, kWave);
+    if (f2 > f || (f2 == f && c < lane)) ++rank;
+  }
+  if (lane < k) {
+    order[rank] = lane;
+    out_lens[b * k + rank] = n;
+    out_scores[b * k + rank] = f;
+  }
+  __syncthreads();
+  for (int i = 0; i < k; ++i) {
+    int src = b * k + order[i];
+    int n_i = len[src];
+    for (int p = lane; p < T; p += 64)
+      out_ids[(size_t)(b * k + i) * T + p] = p < n_i ? tokens[(size_t)src * (T + 1) + 1 + p] : pad;
+  }
+}
+
+hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
+                           int32_t* out_lens, float* out_scores, int batch, int k, int T, float alpha, int pad,
+                           hipStream_t s) {
+  finalize_kernel<<<batch, 64, 0, s>>>(score, tokens, len, out_ids, out_lens, out_scores, k, T, alpha, pad);
+  return hipGetLastError();
+}
+
+}  // namespace lsq

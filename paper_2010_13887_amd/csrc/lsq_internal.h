@@ -1,0 +1,119 @@
+// Internal declarations shared by the translation units of liblsq.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lsq {
+
+enum { DT_F32 = 0, DT_F16 = 1 };
+
+typedef _Float16 half_t;
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+constexpr int LSQ_MAX_BEAM_ = 8;   // k*k survivors of one sentence fit one wavefront
+
+// Where a GEMM writes: output column n belongs to segment s = n / seg_n and goes to
+// ptr[s] + m * ld[s] + (n - s * seg_n).  One segment for an ordinary matrix; three for the
+// fused Q | K | V projection whose K and V columns land directly in the caches.
+struct GemmOut {
+  void* ptr[3];
+  long ld[3];
+  int seg_n;
+  int f32_out;   // fp16 GEMM only: write the fp32 accumulators unrounded (vocabulary logits)
+};
+
+inline GemmOut plain_out(void* c, int N) {
+  GemmOut o;
+  o.ptr[0] = c; o.ptr[1] = nullptr; o.ptr[2] = nullptr;
+  o.ld[0] = N; o.ld[1] = 0; o.ld[2] = 0;
+  o.seg_n = N;
+  o.f32_out = 0;
+  return o;
+}
+
+// Every launcher enqueues on `s` and returns hipGetLastError().
+hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out,
+                       int M, int N, int K, bool relu, hipStream_t s);
+
+hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
+                             const int32_t* pos, void* x, int rows, int d, hipStream_t s);
+hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
+                             const int32_t* len, void* x, int rows, int d, int T, int t, hipStream_t s);
+hipError_t launch_add_layernorm(int dtype, void* x, const void* a, const void* g, const void* b,
+                                int rows, int d, float eps, hipStream_t s);
+
+hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
+                                 int rows, int H, int d, int T, int nkeys, hipStream_t s);
+hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
+                                  const int32_t* len, void* out, int batch, int beam, int H, int d,
+                                  hipStream_t s);
+hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent,
+                                    const int32_t* off, const int32_t* len, void* out, int rows, int H,
+                                    int d, hipStream_t s);
+
+hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
+                           int M, int V, int k, int eos, float* out_score, int32_t* out_idx,
+                           hipStream_t s);
+hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
+                              int32_t* tokens, int32_t* len, int32_t* fin, int32_t* parent,
+                              const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
+                              int t, int eos, hipStream_t s);
+hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
+                                int k, int T, int d, int npos, hipStream_t s);
+hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
+                             int32_t* active_counts, int batch, int k, int T, int bos, int pad,
+                             hipStream_t s);
+hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
+                           int32_t* out_lens, float* out_scores, int batch, int k, int T, float alpha,
+                           int pad, hipStream_t s);
+
+bool topk_supported(int V);
+bool head_dim_supported(int dh);
+
+// ---- device helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+template <typename T> struct Vec8;
+template <> struct Vec8<half_t> {
+  __device__ static __forceinline__ void load(const half_t* p, float (&f)[8]) {
+    half8_t h = *reinterpret_cast<const half8_t*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+  }
+  __device__ static __forceinline__ void store(half_t* p, const float (&f)[8]) {
+    half8_t h;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = (half_t)f[i];
+    *reinterpret_cast<half8_t*>(p) = h;
+  }
+};
+template <> struct Vec8<float> {
+  __device__ static __forceinline__ void load(const float* p, float (&f)[8]) {
+    floatx4 a = *reinterpret_cast<const floatx4*>(p);
+    floatx4 b = *reinterpret_cast<const floatx4*>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[i] = a[i]; f[4 + i] = b[i]; }
+  }
+  __device__ static __forceinline__ void store(float* p, const float (&f)[8]) {
+    floatx4 a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = f[i]; b[i] = f[4 + i]; }
+    *reinterpret_cast<floatx4*>(p) = a;
+    *reinterpret_cast<floatx4*>(p + 4) = b;
+  }
+};
+
+}  // namespace lsq

@@ -1,0 +1,611 @@
+// Host side of liblsq.so: the C ABI, blob parsing, the max-shape memory plan (paper sec. 2.3)
+// and the per-call launch sequences.  No device memory is ever allocated here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../../include/lsq.h"
+#include "lsq_internal.h"
+
+using namespace lsq;
+
+static_assert(LSQ_MAX_BEAM == LSQ_MAX_BEAM_, "public and internal beam limits differ");
+
+namespace {
+
+char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIPCHK(expr)                                                                     \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess) return fail(LSQ_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct HParams {
+  int arch, n_enc, n_dec, d, H, F, V, max_pos, act, norm, dtype, pad, bos, eos, cap_extra, sample_topk;
+  float alpha, eps;
+  uint64_t seed, total;
+};
+
+int parse_header(const void* blob, size_t bytes, HParams* hp) {
+  if (!blob) return fail(LSQ_E_ARG, "weights is null");
+  if (bytes < 256) return fail(LSQ_E_BLOB, "blob shorter than its header");
+  const char* p = (const char*)blob;
+  if (memcmp(p, "LSQBLOB1", 8) != 0) return fail(LSQ_E_BLOB, "bad magic");
+  int32_t f[17];
+  memcpy(f, p + 8, sizeof f);
+  if (f[0] != 1) return fail(LSQ_E_BLOB, "unsupported blob version %d", f[0]);
+  hp->arch = f[1]; hp->n_enc = f[2]; hp->n_dec = f[3]; hp->d = f[4]; hp->H = f[5]; hp->F = f[6];
+  hp->V = f[7]; hp->max_pos = f[8]; hp->act = f[9]; hp->norm = f[10]; hp->dtype = f[11];
+  hp->pad = f[12]; hp->bos = f[13]; hp->eos = f[14]; hp->cap_extra = f[15]; hp->sample_topk = f[16];
+  memcpy(&hp->alpha, p + 76, 4);
+  memcpy(&hp->eps, p + 80, 4);
+  memcpy(&hp->seed, p + 88, 8);
+  memcpy(&hp->total, p + 96, 8);
+  if (hp->arch != 0 || hp->norm != 0 || hp->act != 0)
+    return fail(LSQ_E_BLOB, "only post-LN ReLU encoder-decoder models are supported");
+  if (hp->dtype != DT_F32 && hp->dtype != DT_F16) return fail(LSQ_E_BLOB, "unknown dtype %d", hp->dtype);
+  if (hp->n_enc < 1 || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
+      hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0)
+    return fail(LSQ_E_BLOB, "implausible model shape");
+  if (hp->d % 8 != 0 || hp->F % 8 != 0) return fail(LSQ_E_BLOB, "d_model and d_ffn must be multiples of 8");
+  if (!head_dim_supported(hp->d / hp->H)) return fail(LSQ_E_BLOB, "head size %d unsupported (16/32/64/128)", hp->d / hp->H);
+  if (!topk_supported(hp->V)) return fail(LSQ_E_BLOB, "vocabulary %d unsupported (<= 65536)", hp->V);
+  for (int id : {hp->pad, hp->bos, hp->eos})
+    if (id < 0 || id >= hp->V) return fail(LSQ_E_BLOB, "special token id outside the vocabulary");
+  if (hp->cap_extra < 0 || !(hp->eps > 0.f)) return fail(LSQ_E_BLOB, "bad cap_extra / ln_eps");
+  return LSQ_OK;
+}
+
+// One tensor of the blob: `rows` x `cols` as stored ([in, out] for matrices; rows == 1 for vectors).
+struct TensorDesc { int rows, cols; bool transpose; };
+
+void tensor_walk(const HParams& hp, std::vector<TensorDesc>* out) {
+  const int d = hp.d, F = hp.F, V = hp.V;
+  auto mat = [&](int r, int c) { out->push_back({r, c, true}); };
+  auto vec = [&](int n) { out->push_back({1, n, false}); };
+  out->push_back({V, d, false});   // embedding: already [vocab, d] = [N, K] of the logit GEMM
+  for (int i = 0; i < hp.n_enc; ++i) {
+    mat(d, 3 * d); vec(3 * d); mat(d, d); vec(d); vec(d); vec(d);
+    mat(d, F); vec(F); mat(F, d); vec(d); vec(d); vec(d);
+  }
+  for (int i = 0; i < hp.n_dec; ++i) {
+    mat(d, 3 * d); vec(3 * d); mat(d, d); vec(d); vec(d); vec(d);
+    mat(d, d); vec(d); mat(d, 2 * d); vec(2 * d); mat(d, d); vec(d); vec(d); vec(d);
+    mat(d, F); vec(F); mat(F, d); vec(d); vec(d); vec(d);
+  }
+}
+
+struct EncLayer { char *Wqkv, *bqkv, *Wo, *bo, *ln1g, *ln1b, *W1, *b1, *W2, *b2, *ln2g, *ln2b; };
+struct DecLayer {
+  char *Wqkv, *bqkv, *Wo, *bo, *ln1g, *ln1b, *Wq, *bq, *Wkv, *bkv, *Woc, *boc, *ln2g, *ln2b, *W1, *b1, *W2,
+      *b2, *ln3g, *ln3b;
+};
+
+// Byte offsets into the workspace.  Everything is sized for max_batch / beam / max_len once;
+// encoder intermediates and decoder intermediates are never live together and share `scratch`,
+// and inside the decoder the FFN activation and the logits share bytes as well.
+struct Plan {
+  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, src_off, src_len, active,
+      cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
+  // encoder view of scratch
+  size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
+  // decoder view of scratch
+  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits;
+};
+
+Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
+  Plan p;
+  const size_t esz = hp.dtype == DT_F16 ? 2 : 4;
+  const size_t M = (size_t)B * k, R = (size_t)B * T, d = hp.d, F = hp.F, V = hp.V;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  p.weights = take(weight_bytes);
+  p.pe = take((size_t)T * d * 4);
+  p.cache = take((size_t)hp.n_dec * 2 * M * T * d * esz);
+  p.cross = take((size_t)hp.n_dec * R * 2 * d * esz);
+  p.score = take(M * 4);
+  p.tokens = take(M * (T + 1) * 4);
+  p.len = take(M * 4);
+  p.fin = take(M * 4);
+  p.parent = take(M * 4);
+  p.cap = take((size_t)B * 4);
+  p.src_off = take((size_t)(B + 1) * 4);
+  p.src_len = take((size_t)B * 4);
+  p.active = take((size_t)(T + 1) * 4);
+  p.cand_score = take(M * k * 4);
+  p.cand_idx = take(M * k * 4);
+  p.out_ids = take(M * T * 4);
+  p.out_lens = take(M * 4);
+  p.out_scores = take(M * 4);
+  p.scratch = off;
+  // encoder phase
+  size_t e = p.scratch;
+  auto etake = [&](size_t bytes) { size_t o = e; e += up(bytes); return o; };
+  p.e_ids = etake(R * 4); p.e_pos = etake(R * 4); p.e_sent = etake(R * 4);
+  p.e_x = etake(R * d * esz); p.e_qkv = etake(R * 3 * d * esz); p.e_ctx = etake(R * d * esz);
+  p.e_tmp = etake(R * d * esz); p.e_ffn = etake(R * F * esz);
+  // decoder phase
+  size_t q = p.scratch;
+  auto dtake = [&](size_t bytes) { size_t o = q; q += up(bytes); return o; };
+  p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
+  p.d_tmp = dtake(M * d * esz);
+  p.d_ffn = q;
+  p.d_logits = q;
+  q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
+  p.total = std::max(e, q);
+  return p;
+}
+
+size_t device_weight_bytes(const HParams& hp) {
+  std::vector<TensorDesc> ts;
+  tensor_walk(hp, &ts);
+  const size_t esz = hp.dtype == DT_F16 ? 2 : 4;
+  size_t off = 0;
+  for (auto& t : ts) off = up(off) + (size_t)t.rows * t.cols * esz;
+  return up(off);
+}
+
+struct Ctx {
+  int state = 0;   // 0 nothing, 1 workspace set, 2 model loaded, 3 sentences encoded
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  hipStream_t stream = nullptr;
+  HParams hp{};
+  Plan plan{};
+  int max_batch = 0, beam = 0, max_len = 0;
+  int batch = 0, rows_enc = 0, t = 0;
+  bool done = false;
+  char* E = nullptr;
+  std::vector<EncLayer> enc;
+  std::vector<DecLayer> dec;
+  int32_t* pinned = nullptr;   // host staging: ids, positions, sentence map, offsets, lengths, caps, 1 count
+  size_t pinned_ints = 0;
+} g;
+
+template <typename T> T* at(size_t off) { return reinterpret_cast<T*>(g.ws + off); }
+inline size_t esz() { return g.hp.dtype == DT_F16 ? 2 : 4; }
+
+void transpose_copy(const char* src, char* dst, int rows, int cols, size_t es) {
+  // src [rows, cols] -> dst [cols, rows]
+  constexpr int BL = 32;
+  for (int r0 = 0; r0 < rows; r0 += BL)
+    for (int c0 = 0; c0 < cols; c0 += BL) {
+      int r1 = std::min(rows, r0 + BL), c1 = std::min(cols, c0 + BL);
+      if (es == 2) {
+        const uint16_t* s = (const uint16_t*)src;
+        uint16_t* d = (uint16_t*)dst;
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) d[(size_t)c * rows + r] = s[(size_t)r * cols + c];
+      } else {
+        const uint32_t* s = (const uint32_t*)src;
+        uint32_t* d = (uint32_t*)dst;
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) d[(size_t)c * rows + r] = s[(size_t)r * cols + c];
+      }
+    }
+}
+
+int check_limits(int max_batch, int beam, int max_len, const HParams& hp) {
+  if (max_batch < 1 || max_batch > 4096) return fail(LSQ_E_ARG, "max_batch %d outside [1, 4096]", max_batch);
+  if (beam < 1 || beam > LSQ_MAX_BEAM) return fail(LSQ_E_ARG, "beam %d outside [1, %d]", beam, LSQ_MAX_BEAM);
+  if (beam > hp.V) return fail(LSQ_E_ARG, "beam wider than the vocabulary");
+  if (max_len < 1 || max_len > 4096) return fail(LSQ_E_ARG, "max_len %d outside [1, 4096]", max_len);
+  return LSQ_OK;
+}
+
+int enqueue_step() {
+  const HParams& hp = g.hp;
+  const Plan& p = g.plan;
+  hipStream_t s = g.stream;
+  const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, k = g.beam, T = g.max_len, t = g.t;
+  const int B = g.batch, M = B * k;
+  const size_t es = esz();
+  char* x = g.ws + p.d_x; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
+  char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
+  const size_t slab = (size_t)M * T * d * es;       // one layer's K (or V) cache
+  const size_t cross_l = (size_t)g.rows_enc * 2 * d * es;
+  HIPCHK(launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, t, s));
+  for (int l = 0; l < hp.n_dec; ++l) {
+    const DecLayer& L = g.dec[l];
+    char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
+    char* Vc = Kc + slab;
+    GemmOut o;
+    o.ptr[0] = q; o.ptr[1] = Kc + (size_t)t * d * es; o.ptr[2] = Vc + (size_t)t * d * es;
+    o.ld[0] = d; o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
+    o.seg_n = d;
+    o.f32_out = 0;
+    HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
+    HIPCHK(launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, t + 1, s));
+    HIPCHK(launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), M, d, d, false, s));
+    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, M, d, hp.eps, s));
+    HIPCHK(launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
+    HIPCHK(launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+                                  at<int32_t>(p.src_len), ctx, B, k, H, d, s));
+    HIPCHK(launch_gemm(dt, ctx, L.Woc, L.boc, plain_out(tmp, d), M, d, d, false, s));
+    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, M, d, hp.eps, s));
+    HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
+    HIPCHK(launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), M, d, F, false, s));
+    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln3g, L.ln3b, M, d, hp.eps, s));
+  }
+  GemmOut lo = plain_out(logits, V);
+  lo.f32_out = 1;
+  HIPCHK(launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, false, s));
+  HIPCHK(launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos,
+                         at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+  HIPCHK(launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
+                            at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
+                            at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active) + t, B, k, V, T,
+                            t, hp.eos, s));
+  HIPCHK(launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, k, T, d, t + 1, s));
+  g.t = t + 1;
+  return LSQ_OK;
+}
+
+int read_active(int step, int* out) {
+  int32_t* slot = g.pinned + g.pinned_ints - 1;
+  HIPCHK(hipMemcpyAsync(slot, at<int32_t>(g.plan.active) + step, 4, hipMemcpyDeviceToHost, g.stream));
+  HIPCHK(hipStreamSynchronize(g.stream));
+  *out = *slot;
+  return LSQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lsq_last_error(void) { return g_err; }
+
+int lsq_workspace_bytes(const void* weights, size_t weights_bytes, int max_batch, int beam, int max_len,
+                        size_t* out_bytes) {
+  if (!out_bytes) return fail(LSQ_E_ARG, "out_bytes is null");
+  HParams hp;
+  int rc = parse_header(weights, weights_bytes, &hp);
+  if (rc) return rc;
+  rc = check_limits(max_batch, beam, max_len, hp);
+  if (rc) return rc;
+  *out_bytes = make_plan(hp, device_weight_bytes(hp), max_batch, beam, max_len).total;
+  return LSQ_OK;
+}
+
+int lsq_set_workspace(void* dev_ptr, size_t bytes, void* hip_stream) {
+  if (!dev_ptr || bytes == 0) return fail(LSQ_E_ARG, "workspace is null or empty");
+  if (reinterpret_cast<uintptr_t>(dev_ptr) % kAlign) return fail(LSQ_E_ARG, "workspace must be 256-byte aligned");
+  if (g.state >= 2) return fail(LSQ_E_STATE, "a model is loaded; call lsq_free first");
+  g.ws = (char*)dev_ptr;
+  g.ws_bytes = bytes;
+  g.stream = (hipStream_t)hip_stream;
+  g.state = 1;
+  return LSQ_OK;
+}
+
+int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam, int max_len) {
+  if (g.state < 1) return fail(LSQ_E_STATE, "lsq_set_workspace has not been called");
+  if (g.state >= 2) return fail(LSQ_E_STATE, "already initialised; call lsq_free first");
+  HParams hp;
+  int rc = parse_header(weights, weights_bytes, &hp);
+  if (rc) return rc;
+  rc = check_limits(max_batch, beam, max_len, hp);
+  if (rc) return rc;
+  if (hp.total != weights_bytes) return fail(LSQ_E_BLOB, "blob is %zu bytes, header says %llu", weights_bytes,
+                                             (unsigned long long)hp.total);
+  std::vector<TensorDesc> ts;
+  tensor_walk(hp, &ts);
+  const size_t es = hp.dtype == DT_F16 ? 2 : 4;
+  size_t src = 256;
+  for (auto& t : ts) src = up(src) + (size_t)t.rows * t.cols * es;
+  if (src != weights_bytes) return fail(LSQ_E_BLOB, "blob size %zu does not match its shape (%zu)", weights_bytes, src);
+  const size_t wbytes = device_weight_bytes(hp);
+  Plan plan = make_plan(hp, wbytes, max_batch, beam, max_len);
+  if (plan.total > g.ws_bytes)
+    return fail(LSQ_E_NOMEM, "workspace has %zu bytes, %zu needed", g.ws_bytes, plan.total);
+
+  // stage the weights on the host: matrices become [out, in] so every GEMM reads K-contiguous rows
+  char* stage = nullptr;
+  HIPCHK(hipHostMalloc((void**)&stage, wbytes, hipHostMallocDefault));
+  memset(stage, 0, wbytes);
+  std::vector<char*> dev;
+  size_t so = 256, dof = 0;
+  for (auto& t : ts) {
+    so = up(so);
+    dof = up(dof);
+    size_t n = (size_t)t.rows * t.cols * es;
+    if (t.transpose) transpose_copy((const char*)weights + so, stage + dof, t.rows, t.cols, es);
+    else memcpy(stage + dof, (const char*)weights + so, n);
+    dev.push_back(g.ws + plan.weights + dof);
+    so += n;
+    dof += n;
+  }
+  hipError_t e = hipMemcpyAsync(g.ws + plan.weights, stage, wbytes, hipMemcpyHostToDevice, g.stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(g.stream);
+  (void)hipHostFree(stage);
+  if (e != hipSuccess) return fail(LSQ_E_HIP, "weight upload failed: %s", hipGetErrorString(e));
+
+  // sinusoidal position table, evaluated in double precision
+  {
+    const int d = hp.d;
+    float* pe = nullptr;
+    HIPCHK(hipHostMalloc((void**)&pe, (size_t)max_len * d * 4, hipHostMallocDefault));
+    for (int pos = 0; pos < max_len; ++pos)
+      for (int i = 0; i < d; i += 2) {
+        double ang = (double)pos / std::pow(10000.0, (double)i / d);
+        pe[(size_t)pos * d + i] = (float)std::sin(ang);
+        if (i + 1 < d) pe[(size_t)pos * d + i + 1] = (float)std::cos(ang);
+      }
+    e = hipMemcpyAsync(g.ws + plan.pe, pe, (size_t)max_len * d * 4, hipMemcpyHostToDevice, g.stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(g.stream);
+    (void)hipHostFree(pe);
+    if (e != hipSuccess) return fail(LSQ_E_HIP, "position table upload failed: %s", hipGetErrorString(e));
+  }
+
+  g.pinned_ints = (size_t)3 * max_batch * max_len + 3 * (size_t)max_batch + 2;
+  HIPCHK(hipHostMalloc((void**)&g.pinned, g.pinned_ints * 4, hipHostMallocDefault));
+
+  g.hp = hp;
+  g.plan = plan;
+  g.max_batch = max_batch; g.beam = beam; g.max_len = max_len;
+  size_t i = 0;
+  g.E = dev[i++];
+  g.enc.assign(hp.n_enc, EncLayer{});
+  for (auto& L : g.enc) {
+    L.Wqkv = dev[i++]; L.bqkv = dev[i++]; L.Wo = dev[i++]; L.bo = dev[i++]; L.ln1g = dev[i++]; L.ln1b = dev[i++];
+    L.W1 = dev[i++]; L.b1 = dev[i++]; L.W2 = dev[i++]; L.b2 = dev[i++]; L.ln2g = dev[i++]; L.ln2b = dev[i++];
+  }
+  g.dec.assign(hp.n_dec, DecLayer{});
+  for (auto& L : g.dec) {
+    L.Wqkv = dev[i++]; L.bqkv = dev[i++]; L.Wo = dev[i++]; L.bo = dev[i++]; L.ln1g = dev[i++]; L.ln1b = dev[i++];
+    L.Wq = dev[i++]; L.bq = dev[i++]; L.Wkv = dev[i++]; L.bkv = dev[i++]; L.Woc = dev[i++]; L.boc = dev[i++];
+    L.ln2g = dev[i++]; L.ln2b = dev[i++];
+    L.W1 = dev[i++]; L.b1 = dev[i++]; L.W2 = dev[i++]; L.b2 = dev[i++]; L.ln3g = dev[i++]; L.ln3b = dev[i++];
+  }
+  g.state = 2;
+  return LSQ_OK;
+}
+
+int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int src_stride) {
+  if (g.state < 2) return fail(LSQ_E_STATE, "lsq_init has not been called");
+  if (!src_ids || !src_lens) return fail(LSQ_E_ARG, "src_ids / src_lens is null");
+  if (batch < 1 || batch > g.max_batch) return fail(LSQ_E_ARG, "batch %d outside [1, %d]", batch, g.max_batch);
+  if (src_stride < 1 || src_stride > g.max_len)
+    return fail(LSQ_E_ARG, "src_stride %d outside [1, max_len = %d]", src_stride, g.max_len);
+  const HParams& hp = g.hp;
+  long R = 0;
+  for (int b = 0; b < batch; ++b) {
+    int n = src_lens[b];
+    if (n < 1 || n > src_stride) return fail(LSQ_E_ARG, "src_lens[%d] = %d outside [1, %d]", b, n, src_stride);
+    for (int j = 0; j < n; ++j) {
+      int id = src_ids[(size_t)b * src_stride + j];
+      if (id < 0 || id >= hp.V) return fail(LSQ_E_ARG, "src_ids[%d,%d] = %d outside the vocabulary", b, j, id);
+    }
+    R += n;
+  }
+  HIPCHK(hipStreamSynchronize(g.stream));   // the staging buffer may still feed an earlier copy
+  const Plan& p = g.plan;
+  const size_t Rmax = (size_t)g.max_batch * g.max_len;
+  int32_t* h_ids = g.pinned;
+  int32_t* h_pos = h_ids + Rmax;
+  int32_t* h_sent = h_pos + Rmax;
+  int32_t* h_off = h_sent + Rmax;            // batch + 1
+  int32_t* h_len = h_off + g.max_batch + 1;  // batch
+  int32_t* h_cap = h_len + g.max_batch;      // batch
+  int r = 0;
+  for (int b = 0; b < batch; ++b) {
+    h_off[b] = r;
+    h_len[b] = src_lens[b];
+    h_cap[b] = std::min(src_lens[b] + hp.cap_extra, g.max_len);
+    for (int j = 0; j < src_lens[b]; ++j, ++r) {
+      h_ids[r] = src_ids[(size_t)b * src_stride + j];
+      h_pos[r] = j;
+      h_sent[r] = b;
+    }
+  }
+  h_off[batch] = r;
+  hipStream_t s = g.stream;
+  HIPCHK(hipMemcpyAsync(g.ws + p.e_ids, h_ids, (size_t)R * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.e_pos, h_pos, (size_t)R * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.e_sent, h_sent, (size_t)R * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.src_off, h_off, (size_t)(batch + 1) * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.src_len, h_len, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.cap, h_cap, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+
+  const int dt = hp.dtype, d = hp.d, F = hp.F, H = hp.H;
+  const size_t es = esz();
+  char* x = g.ws + p.e_x; char* qkv = g.ws + p.e_qkv; char* ctx = g.ws + p.e_ctx; char* tmp = g.ws + p.e_tmp;
+  char* ffn = g.ws + p.e_ffn;
+  const int32_t* sent = at<int32_t>(p.e_sent);
+  const int32_t* off = at<int32_t>(p.src_off);
+  const int32_t* len = at<int32_t>(p.src_len);
+  HIPCHK(launch_embed_rows(dt, g.E, at<float>(p.pe), at<int32_t>(p.e_ids), at<int32_t>(p.e_pos), x, (int)R, d, s));
+  for (const EncLayer& L : g.enc) {
+    HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, plain_out(qkv, 3 * d), (int)R, 3 * d, d, false, s));
+    HIPCHK(launch_encoder_attention(dt, qkv, sent, off, len, ctx, (int)R, H, d, s));
+    HIPCHK(launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), (int)R, d, d, false, s));
+    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, (int)R, d, hp.eps, s));
+    HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), (int)R, F, d, true, s));
+    HIPCHK(launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), (int)R, d, F, false, s));
+    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, (int)R, d, hp.eps, s));
+  }
+  const size_t cross_l = (size_t)R * 2 * d * es;
+  for (int l = 0; l < hp.n_dec; ++l)
+    HIPCHK(launch_gemm(dt, x, g.dec[l].Wkv, g.dec[l].bkv, plain_out(g.ws + p.cross + l * cross_l, 2 * d), (int)R,
+                       2 * d, d, false, s));
+  HIPCHK(launch_beam_reset(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
+                           at<int32_t>(p.active), batch, g.beam, g.max_len, hp.bos, hp.pad, s));
+  g.batch = batch;
+  g.rows_enc = (int)R;
+  g.t = 0;
+  g.done = false;
+  g.state = 3;
+  return LSQ_OK;
+}
+
+int lsq_decode_step(void) { return lsq_decode_steps(1); }
+
+int lsq_decode_steps(int n) {
+  if (g.state < 3) return fail(LSQ_E_STATE, "lsq_encode has not been called");
+  if (n < 1) return fail(LSQ_E_ARG, "n must be positive");
+  if (g.done || g.t >= g.max_len) return 0;
+  int issued = 0;
+  while (issued < n && g.t < g.max_len) {
+    int rc = enqueue_step();
+    if (rc) return rc;
+    ++issued;
+  }
+  int active = 0;
+  int rc = read_active(g.t - 1, &active);
+  if (rc) return rc;
+  if (active == 0) g.done = true;
+  return active;
+}
+
+int lsq_step_index(void) { return g.state >= 3 ? g.t : 0; }
+
+int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
+  if (g.state < 3) return fail(LSQ_E_STATE, "lsq_encode has not been called");
+  if (!out_ids || !out_lens || !out_scores) return fail(LSQ_E_ARG, "an output pointer is null");
+  const Plan& p = g.plan;
+  const int M = g.batch * g.beam, T = g.max_len;
+  HIPCHK(launch_finalize(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.out_ids),
+                         at<int32_t>(p.out_lens), at<float>(p.out_scores), g.batch, g.beam, T, g.hp.alpha,
+                         g.hp.pad, g.stream));
+  HIPCHK(hipMemcpyAsync(out_ids, g.ws + p.out_ids, (size_t)M * T * 4, hipMemcpyDeviceToHost, g.stream));
+  HIPCHK(hipMemcpyAsync(out_lens, g.ws + p.out_lens, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
+  HIPCHK(hipMemcpyAsync(out_scores, g.ws + p.out_scores, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
+  HIPCHK(hipStreamSynchronize(g.stream));
+  return LSQ_OK;
+}
+
+void lsq_free(void) {
+  if (g.pinned) {
+    if (g.stream || g.state >= 2) (void)hipStreamSynchronize(g.stream);
+    (void)hipHostFree(g.pinned);
+  }
+  g = Ctx{};
+}
+
+int lsq_debug_read(int what, void* host_dst, size_t bytes) {
+  if (g.state < 3) return fail(LSQ_E_STATE, "lsq_encode has not been called");
+  if (!host_dst) return fail(LSQ_E_ARG, "host_dst is null");
+  const Plan& p = g.plan;
+  const HParams& hp = g.hp;
+  const size_t M = (size_t)g.batch * g.beam, T = g.max_len, d = hp.d, R = g.rows_enc;
+  const char* src = nullptr;
+  size_t n = 0;
+  bool is_float_data = false;   // stored in the model dtype, delivered as float
+  switch (what) {
+    case LSQ_DBG_LOGITS: src = g.ws + p.d_logits; n = M * hp.V; break;   // always fp32
+    case LSQ_DBG_SCORE: src = g.ws + p.score; n = M; break;
+    case LSQ_DBG_TOKENS: src = g.ws + p.tokens; n = M * (T + 1); break;
+    case LSQ_DBG_LEN: src = g.ws + p.len; n = M; break;
+    case LSQ_DBG_FINISHED: src = g.ws + p.fin; n = M; break;
+    case LSQ_DBG_PARENT: src = g.ws + p.parent; n = M; break;
+    case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * g.beam; break;
+    case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * g.beam; break;
+    case LSQ_DBG_HIDDEN: src = g.ws + p.d_x; n = M * d; is_float_data = true; break;
+    case LSQ_DBG_MEMORY:
+      if (g.t != 0) return fail(LSQ_E_STATE, "encoder output is overwritten by the first decode step");
+      src = g.ws + p.e_x; n = R * d; is_float_data = true; break;
+    default: {
+      int l = what % 100, kind = what - l;
+      if (l < 0 || l >= hp.n_dec) return fail(LSQ_E_ARG, "unknown debug item %d", what);
+      if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * n * esz(); }
+      else if (kind == LSQ_DBG_CACHE_K) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * n * esz(); }
+      else if (kind == LSQ_DBG_CACHE_V) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * n * esz(); }
+      else return fail(LSQ_E_ARG, "unknown debug item %d", what);
+      is_float_data = true;
+    }
+  }
+  if (bytes != n * 4) return fail(LSQ_E_ARG, "debug item %d has %zu bytes, caller gave %zu", what, n * 4, bytes);
+  if (!is_float_data || hp.dtype == DT_F32) {
+    HIPCHK(hipMemcpyAsync(host_dst, src, n * 4, hipMemcpyDeviceToHost, g.stream));
+    HIPCHK(hipStreamSynchronize(g.stream));
+    return LSQ_OK;
+  }
+  std::vector<_Float16> tmp(n);
+  HIPCHK(hipMemcpyAsync(tmp.data(), src, n * 2, hipMemcpyDeviceToHost, g.stream));
+  HIPCHK(hipStreamSynchronize(g.stream));
+  float* dst = (float*)host_dst;
+  for (size_t i = 0; i < n; ++i) dst[i] = (float)tmp[i];
+  return LSQ_OK;
+}
+
+// ---- single-kernel entry points ---------------------------------------------------------------
+#define KCHK(cond, msg) do { if (!(cond)) return fail(LSQ_E_ARG, msg); } while (0)
+#define KRUN(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail(LSQ_E_HIP, "%s", hipGetErrorString(e_)); return LSQ_OK; } while (0)
+
+int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* C, int M, int N, int K, int flags,
+               void* stream) {
+  KCHK(A && B && C, "null matrix");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(M >= 0 && N >= 0 && K >= 1, "shape");
+  KCHK(dtype == DT_F32 || K % 8 == 0, "K must be a multiple of 8 for float16");
+  GemmOut o = plain_out(C, N);
+  o.f32_out = (dtype == DT_F16 && (flags & LSQ_GEMM_F32_OUT)) ? 1 : 0;
+  KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) != 0, (hipStream_t)stream));
+}
+
+int lsq_k_add_layernorm(int dtype, void* x, const void* a, const void* gamma, const void* beta, int rows, int d,
+                        float eps, void* stream) {
+  KCHK(x && a && gamma && beta, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(rows >= 0 && d >= 1, "shape");
+  KRUN(launch_add_layernorm(dtype, x, a, gamma, beta, rows, d, eps, (hipStream_t)stream));
+}
+
+int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out, int rows, int heads,
+                         int d, int T, int nkeys, void* stream) {
+  KCHK(q && Kc && Vc && out, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(rows >= 0 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "head size must be 16/32/64/128");
+  KCHK(nkeys >= 1 && nkeys <= T, "nkeys outside [1, T]");
+  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, (hipStream_t)stream));
+}
+
+int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off, const int32_t* src_len,
+                          void* out, int batch, int beam, int heads, int d, void* stream) {
+  KCHK(q && kv && src_off && src_len && out, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(batch >= 0 && beam >= 1 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "shape");
+  KRUN(launch_cross_attention(dtype, q, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
+}
+
+int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int32_t* finished, int M, int V, int k,
+                   int eos, float* out_score, int32_t* out_idx, void* stream) {
+  KCHK(logits && score && finished && out_score && out_idx, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(M >= 0 && topk_supported(V) && k >= 1 && k <= LSQ_MAX_BEAM && eos >= 0 && eos < V, "shape");
+  KRUN(launch_row_topk(dtype, logits, score, finished, M, V, k, eos, out_score, out_idx, (hipStream_t)stream));
+}
+
+int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,
+                      int32_t* finished, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
+                      int V, int T, int t, int eos, void* stream) {
+  KCHK(cand_score && cand_idx && score && tokens && len && finished && parent && cap && active, "null pointer");
+  KCHK(batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && V >= k && T >= 1 && t >= 0 && t < T, "shape");
+  KRUN(launch_beam_refine(cand_score, cand_idx, score, tokens, len, finished, parent, cap, active, batch, k, V, T, t,
+                          eos, (hipStream_t)stream));
+}
+
+int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k, int T, int d,
+                        int npos, void* stream) {
+  KCHK(cache && parent, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(layers >= 0 && batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && npos >= 0 && npos <= T && d % 8 == 0, "shape");
+  KRUN(launch_cache_reorder(dtype, cache, parent, layers, batch, k, T, d, npos, (hipStream_t)stream));
+}
+
+}  // extern "C"

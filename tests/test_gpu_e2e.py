@@ -1,0 +1,93 @@
+"""End-to-end parity of the HIP library against the CPU oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import lsq_synth as S
+from oracle import lsq_oracle as O
+from tests.parity import lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lsq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2010_13887_amd as lib
+    lib.load_library()
+    yield lib
+    lib.lsq_free()
+
+
+def _final_check(lsq, eng, blob, w, res):
+    ids, lens, scores = eng.get_beams()
+    (o_ids, o_lens, o_scores) = O.finalize(O.Model(blob), res["state"])
+    for b in np.nonzero(res["comparable_mask"])[0]:
+        assert np.array_equal(lens[b], o_lens[b])
+        assert np.array_equal(ids[b], o_ids[b])
+        np.testing.assert_allclose(scores[b], o_scores[b], rtol=1e-5, atol=2e-4)
+
+
+def test_tiny_fp32_matches_oracle(lsq):
+    w = S.workload("tiny")
+    blob = w.blob()
+    with lsq.Engine(blob, w.batch, w.beam, w.max_len) as eng:
+        res = lockstep(lsq, eng, blob, w, verbose=True)
+        # near-flat distributions: a sentence stops being compared once a margin drops below 1e-3
+        assert res["comparable"] >= 1 and res["compared"] >= 8
+        assert res["steps"] == 8
+        _final_check(lsq, eng, blob, w, res)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_small_vocab_eos_and_caps_fp32(lsq, seed):
+    # vocabulary 12: EOS is drawn often, hypotheses finish at different steps, some hit their cap
+    hp = S.HParams(n_enc=1, n_dec=2, d_model=32, n_heads=2, d_ffn=64, vocab=12, max_pos=32, cap_extra=3,
+                   seed=100 + seed)
+    w = S.custom(hp, [1, 4, 7, 2, 9], beam=3, max_len=11, std=0.6, seed=seed)
+    blob = w.blob(ln_jitter=0.2)
+    with lsq.Engine(blob, 6, w.beam, w.max_len) as eng:     # max_batch above the batch in use
+        res = lockstep(lsq, eng, blob, w)
+        assert res["compared"] > 0
+        _final_check(lsq, eng, blob, w, res)
+
+
+def test_small_fp16_ragged(lsq):
+    hp = S.HParams(n_enc=2, n_dec=2, d_model=128, n_heads=2, d_ffn=264, vocab=1003, max_pos=64, dtype=1,
+                   cap_extra=4)
+    w = S.custom(hp, [3, 17, 9, 1, 12, 6, 11], beam=4, max_len=20, std=0.05)
+    blob = w.blob(ln_jitter=0.1)
+    with lsq.Engine(blob, 7, w.beam, w.max_len) as eng:
+        res = lockstep(lsq, eng, blob, w, verbose=True)
+        assert res["compared"] >= 20, res
+        _final_check(lsq, eng, blob, w, res)
+
+
+def test_reencode_reuses_everything(lsq):
+    w = S.workload("tiny")
+    blob = w.blob()
+    with lsq.Engine(blob, 4, w.beam, w.max_len) as eng:
+        a = eng.translate(w.src_ids, w.src_lens)
+        w2 = S.workload("tiny", batch=4, seed=77)
+        eng.translate(w2.src_ids, w2.src_lens, sync_every=3)
+        c = eng.translate(w.src_ids, w.src_lens, sync_every=100)
+        for x, y in zip(a, c):
+            assert np.array_equal(x, y)          # run-to-run bit identical, whatever ran in between
+
+
+def test_errors_leave_no_device_work(lsq):
+    w = S.workload("tiny")
+    blob = w.blob()
+    with pytest.raises(lsq.LsqError):
+        lsq.lsq_decode_step()
+    with lsq.Engine(blob, 2, w.beam, w.max_len) as eng:
+        with pytest.raises(lsq.LsqError):
+            lsq.lsq_decode_step()                      # before encode
+        bad = w.src_ids.copy(); bad[0, 0] = 5000
+        with pytest.raises(lsq.LsqError):
+            eng.encode(bad, w.src_lens)
+        with pytest.raises(lsq.LsqError):
+            eng.encode(w.src_ids, [0, 8])
+        with pytest.raises(lsq.LsqError):
+            eng.encode(np.zeros((3, 8), np.int32) + 5, [1, 1, 1])   # batch above max_batch
+        eng.translate(w.src_ids, w.src_lens)

@@ -239,8 +239,39 @@ def test_fp16_storage_rounds_and_stays_close_to_wide():
     s32 = O.DecodeState(m32, w.src_lens, w.beam, w.max_len)
     l16 = O.decoder_logits_cached(m16, s16, c16)
     l32 = O.decoder_logits_cached(m32, s32, c32)
-    assert np.array_equal(l16, l16.astype(np.float16).astype(np.float32))
+    # stored tensors are fp16-representable, logits are not rounded
+    assert np.array_equal(s16.Kc[0][:, 0], s16.Kc[0][:, 0].astype(np.float16).astype(np.float32))
+    assert not np.array_equal(l16, l16.astype(np.float16).astype(np.float32))
     rms = np.sqrt((l32 ** 2).mean(-1, keepdims=True))
     err = np.abs(l16 - l32) / (np.abs(l32) + rms)
     assert err.max() < 2e-2
     assert err.max() > 0
+
+
+def test_beam_step_hand_worked_example():
+    """Two steps worked by hand: V = 4 (EOS = 2), beam 2, one sentence.
+    Step 1: p = [.1,.2,.3,.4] from the only live beam -> keep token 3 (log .4) and EOS (log .3).
+    Step 2: live beam offers four candidates at log(.4*.25) = log .1; the finished one offers
+    (log .3, EOS).  Kept: the finished hypothesis first, then token 0 (lowest flat index of the tie)."""
+    hp = S.HParams(n_enc=1, n_dec=1, d_model=8, n_heads=2, d_ffn=8, vocab=4, max_pos=8)
+    m = O.Model(S.make_blob(hp), ctype=np.float64)
+    st = O.DecodeState(m, [3], 2, 5)
+    l1 = np.log(np.array([[.1, .2, .3, .4], [.7, .1, .1, .1]])) + 5.0      # shift must not matter
+    tok, par, sc, mar = O.beam_select(m, st, l1)
+    assert tok.tolist() == [[3, 2]] and par.tolist() == [[0, 0]]
+    np.testing.assert_allclose(sc[0], np.log([.4, .3]), atol=1e-12)
+    np.testing.assert_allclose(mar[0], min(np.log(.4 / .3), np.log(.3 / .2)), atol=1e-12)
+    assert O.beam_advance(m, st, tok, par, sc) == 1
+    assert st.finished.tolist() == [False, True] and st.len.tolist() == [1, 1]
+    l2 = np.log(np.array([[.25, .25, .25, .25], [.97, .01, .01, .01]]))
+    tok, par, sc, mar = O.beam_select(m, st, l2)
+    assert par.tolist() == [[1, 0]] and tok.tolist() == [[2, 0]]
+    np.testing.assert_allclose(sc[0], np.log([.3, .1]), atol=1e-12)
+    assert mar[0] == 0.0                                    # tie with the first dropped candidate
+    assert O.beam_advance(m, st, tok, par, sc) == 1
+    assert st.finished.tolist() == [True, False] and st.len.tolist() == [1, 2]
+    assert st.tokens[0, :2].tolist() == [m.bos, 2] and st.tokens[1, :3].tolist() == [m.bos, 3, 0]
+    (ids, ln, fs), = [O.finalize(m, st)]
+    # final = score / len: log(.3)/1 = -1.204 vs log(.1)/2 = -1.151 -> the longer one ranks first
+    assert ln.tolist() == [[2, 1]] and ids[0, 0, :2].tolist() == [3, 0] and ids[0, 1, :1].tolist() == [2]
+    np.testing.assert_allclose(fs[0], [np.log(.1) / 2, np.log(.3)], atol=1e-12)
