@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Throughput of the beam-search decode hot path on one MI355X.
+
+A "step" is one lsq_decode_step: every decoder layer over the cached keys/values, vocabulary
+logits, log-softmax + beam scores + exact top-k, hypothesis update and K/V-cache reorder, for all
+batch*beam rows.  Default workload: Transformer-big, fp16, batch 128, beam 4, source lengths from
+a truncated log-normal (mean 28, max 128), target cap = source length + 50; synthetic weights
+N(0, 0.02^2) and ids, all resident in HBM before the timed region.
+
+Sequence: one untimed full translation (clocks, caches), then encode, W untimed decode steps
+(t = 0..W-1), then exactly K timed steps (default: all remaining steps of the translation)
+enqueued back to back between two stream synchronisations.  value = target tokens decoded in the
+timed steps / elapsed time (one token per still-unfinished sentence per step).  A second,
+instrumented pass of the same K steps brackets every kernel with HIP events on the library's
+stream to get per-kernel-class durations for the roofline line; the CPU oracle is timed on a
+bounded sample of the same workload.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
+
+
+def class_work(name, hp, B, k, t_mean, s_mean):
+    """Algorithmic work of ONE launch of a kernel class: (flops, bytes).  fp16 storage = 2 bytes,
+    fp32 logits = 4 bytes; t_mean = mean number of cached positions over the timed steps."""
+    M, d, F, V, L = B * k, hp.d_model, hp.d_ffn, hp.vocab, hp.n_dec
+    es = 2 if hp.dtype == 1 else 4
+    gemm = lambda n, kk, out_es=es: (2.0 * M * n * kk, (M * kk + n * kk) * es + M * n * out_es)
+    if name == "gemm_qkv":
+        return gemm(3 * d, d)
+    if name == "gemm_dxd":
+        return gemm(d, d)
+    if name == "gemm_ffn1":
+        return gemm(F, d)
+    if name == "gemm_ffn2":
+        return gemm(d, F)
+    if name == "gemm_vocab":
+        return gemm(V, d, 4)
+    if name == "attn_self":      # K and V of every cached position once, q in, context out
+        return (4.0 * M * t_mean * d, (2 * M * t_mean * d + 2 * M * d) * es)
+    if name == "attn_cross":     # encoder K and V once per sentence (shared by its beams)
+        return (4.0 * M * s_mean * d, (2 * B * s_mean * d + 2 * M * d) * es)
+    if name == "add_layernorm":
+        return (8.0 * M * d, 3 * M * d * es)
+    if name == "embed":
+        return (2.0 * M * d, 2 * M * d * es)
+    if name == "row_topk":       # logits read once
+        return (4.0 * M * V, M * V * 4)
+    if name == "beam_refine":
+        return (0.0, M * k * 8)
+    if name == "cache_reorder":  # whole live cache gathered: read + write, all layers, K and V
+        return (0.0, 2.0 * (2 * L * M * t_mean * d * es))
+    return (0.0, 0.0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed decode steps (0 = to the end of the translation)")
+    ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the timed ones")
+    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle sample")
+    ap.add_argument("--breakdown", default="", help="write the per-kernel-class table to this JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sentences are independent; sharding the batch over "
+              "GPUs needs no collective and is described in DESIGN.md). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import lsq_synth as S
+    import paper_2010_13887_amd as lsq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        return 2
+    lsq.load_library()
+    w = S.workload(args.workload)
+    hp = w.hp
+    blob = w.blob()
+    B, k, T = w.batch, w.beam, w.max_len
+    eng = lsq.Engine(blob, B, k, T)
+
+    # untimed full translation
+    ids, lens, scores = eng.translate(w.src_ids, w.src_lens, sync_every=16)
+    total_steps = lsq.lsq_step_index()
+    best_len = lens[:, 0].astype(np.int64)
+    W = max(0, min(args.warmup, total_steps - 1))
+    K = args.steps if args.steps > 0 else total_steps - W
+    K = max(1, min(K, total_steps - W))
+
+    def run(profile: bool):
+        eng.encode(w.src_ids, w.src_lens)
+        if W:
+            eng.decode_steps(W)
+        lsq.lsq_profile_enable(profile)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.decode_steps(K)                       # K steps enqueued back to back, one wait at the end
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = lsq.lsq_profile_read() if profile else None
+        lsq.lsq_profile_enable(False)
+        return dt, prof
+
+    run(False)                                     # one more warm pass over exactly the timed region
+    dt, _ = run(False)
+    tokens = int((np.minimum(best_len, W + K) - np.minimum(best_len, W)).sum())
+    value = tokens / dt
+    ms_per_step = dt / K * 1e3
+
+    # instrumented pass: per-kernel-class durations over the same K steps
+    dt_prof, prof = run(True)
+    # mean cached positions over the timed steps (step t attends t+1 positions and reorders t+1)
+    t_mean = float(np.mean([t + 1 for t in range(W, W + K)]))
+    s_mean = float(w.src_lens.mean())
+    table = {}
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        fl, by = class_work(name, hp, B, k, t_mean, s_mean)
+        us = ms / n * 1e3
+        table[name] = dict(launches=n, total_ms=ms, avg_us=us, flops_per_launch=fl, bytes_per_launch=by,
+                           tflops=fl / (us * 1e-6) / 1e12 if us > 0 else 0.0,
+                           gbs=by / (us * 1e-6) / 1e9 if us > 0 else 0.0)
+    dom = max(table, key=lambda n: table[n]["total_ms"])
+    d = table[dom]
+    if dom.startswith("gemm"):
+        roof = dict(bound="mfma", kernel=dom, achieved=d["tflops"], peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
+                    frac=d["tflops"] / PEAK_F16_TFLOPS, traffic=None, avg_us=d["avg_us"], launches=d["launches"])
+    else:
+        roof = dict(bound="hbm", kernel=dom, achieved=d["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=d["gbs"] / PEAK_HBM_GBS, traffic=None, avg_us=d["avg_us"], launches=d["launches"])
+    gemm_ms = sum(v["total_ms"] for n, v in table.items() if n.startswith("gemm"))
+    gemm_fl = sum(v["flops_per_launch"] * v["launches"] for n, v in table.items() if n.startswith("gemm"))
+    kernel_ms = sum(v["total_ms"] for v in table.values())
+    extra = dict(kernel_ms_per_step=kernel_ms / K, gemm_share=gemm_ms / kernel_ms,
+                 reorder_share=table.get("cache_reorder", {}).get("total_ms", 0.0) / kernel_ms,
+                 gemm_tflops_aggregate=gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
+                 instrumented_ms_per_step=dt_prof / K * 1e3)
+    if args.breakdown:
+        os.makedirs(os.path.dirname(os.path.abspath(args.breakdown)), exist_ok=True)
+        with open(args.breakdown, "w") as f:
+            json.dump(dict(workload=args.workload, steps=K, warmup=W, ms_per_step=ms_per_step, classes=table,
+                           **extra), f, indent=1)
+    eng.close()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lsq_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        m = O.Model(blob)
+        _, cross = O.encode(m, w.src_ids, w.src_lens)
+        st = O.DecodeState(m, w.src_lens, k, T)
+        n_steps, tok, t0 = 0, 0, time.perf_counter()
+        while True:
+            active_before = int((~st.finished).reshape(B, k).any(axis=1).sum())
+            logits = O.decoder_logits_cached(m, st, cross)
+            sel = O.beam_select(m, st, logits)
+            O.beam_advance(m, st, *sel[:3])
+            n_steps += 1
+            tok += active_before
+            if time.perf_counter() - t0 > args.cpu_seconds or n_steps >= total_steps:
+                break
+        cdt = time.perf_counter() - t0
+        cpu = dict(value=tok / cdt, unit="tokens/s", cores=cores, kind="oracle",
+                   sample=f"first {n_steps} decode steps of the same workload ({cdt:.1f} s, "
+                          f"{cdt / n_steps * 1e3:.0f} ms/step; encoder excluded)")
+
+    out = dict(metric="decoded target tokens/sec at beam 4 (Transformer-big fp16); ms per decode step",
+               value=value, unit="tokens/s", n_gpus=1, steps=K, warmup=W, ms_per_step=ms_per_step,
+               higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="f16" if hp.dtype == 1 else "f32", data="synthetic",
+               config=dict(workload=f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, "
+                                    f"FFN {hp.d_ffn}, vocab {hp.vocab}, batch {B}, beam {k}, "
+                                    f"src len mean {s_mean:.1f} max {int(w.src_lens.max())}, max_len {T}",
+                           global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
+               roofline=roof, cpu_baseline=cpu, **extra)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -101,6 +101,19 @@ const char* lsq_last_error(void);
 int lsq_step_index(void);
 
 /* ------------------------------------------------------------------------- */
+/* Per-kernel timing for benchmarks.  While enabled, each kernel that
+ * lsq_decode_step(s) launches is bracketed by two HIP events on the library's
+ * stream.  lsq_profile_read waits for the stream, then fills ms[c] (summed
+ * elapsed milliseconds) and launches[c] for each of lsq_profile_classes()
+ * kernel classes (names from lsq_profile_class_name) and clears the record.
+ * Enabling costs two event records per launch; leave it off when timing
+ * whole steps.  ms, launches: host arrays of at least lsq_profile_classes(). */
+int lsq_profile_enable(int on);
+int lsq_profile_classes(void);
+const char* lsq_profile_class_name(int c);
+int lsq_profile_read(double* ms, int64_t* launches, int n);
+
+/* ------------------------------------------------------------------------- */
 /* Debug / test hooks: copy library state to host memory.  Floating-point data
  * is always delivered as float32 whatever the model's storage type. `bytes`
  * must equal the size of the item.  M = batch*beam rows, T = max_len.          */

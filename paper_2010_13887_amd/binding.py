@@ -44,6 +44,9 @@ def load_library() -> C.CDLL:
         "lsq_get_beams": [vp, vp, vp],
         "lsq_step_index": [],
         "lsq_debug_read": [i32, vp, sz],
+        "lsq_profile_enable": [i32],
+        "lsq_profile_classes": [],
+        "lsq_profile_read": [vp, vp, i32],
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_add_layernorm": [i32, vp, vp, vp, vp, i32, i32, f32, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
@@ -58,6 +61,8 @@ def load_library() -> C.CDLL:
         fn.restype = C.c_int
     lib.lsq_free.argtypes = []
     lib.lsq_free.restype = None
+    lib.lsq_profile_class_name.argtypes = [i32]
+    lib.lsq_profile_class_name.restype = C.c_char_p
     lib.lsq_last_error.argtypes = []
     lib.lsq_last_error.restype = C.c_char_p
     _LIB = lib
@@ -128,6 +133,20 @@ def lsq_debug_read(what: int, shape, dtype=np.float32) -> np.ndarray:
     out = np.empty(shape, dtype)
     _check(load_library().lsq_debug_read(what, out.ctypes.data, out.nbytes))
     return out
+
+
+def lsq_profile_enable(on: bool) -> None:
+    _check(load_library().lsq_profile_enable(int(on)))
+
+
+def lsq_profile_read() -> dict:
+    """{class name: (summed milliseconds, launches)} since the last read."""
+    lib = load_library()
+    n = lib.lsq_profile_classes()
+    ms = np.zeros(n, np.float64)
+    cnt = np.zeros(n, np.int64)
+    _check(lib.lsq_profile_read(ms.ctypes.data, cnt.ctypes.data, n))
+    return {lib.lsq_profile_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 # ---- single-kernel entry points on torch tensors ----------------------------------------------

@@ -32,6 +32,51 @@ int fail(int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(LSQ_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
+// Optional per-launch timing: when enabled, every kernel launched by lsq_decode_step(s) is
+// bracketed by two events on the library's stream; lsq_profile_read adds the elapsed times up
+// per kernel class.  Events come from a host-side pool that only grows.
+enum ProfClass {
+  PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_COUNT
+};
+const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
+                                          "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
+                                          "beam_refine", "cache_reorder"};
+struct Prof {
+  bool on = false;
+  std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
+  std::vector<int> cls;           // class of pair i
+  size_t used = 0;                // pairs in flight
+} g_prof;
+
+hipError_t prof_mark(hipStream_t s, int c, bool start) {
+  if (!g_prof.on) return hipSuccess;
+  if (start) {
+    if (g_prof.used * 2 >= g_prof.pool.size()) {
+      hipEvent_t a, b;
+      hipError_t e = hipEventCreate(&a);
+      if (e != hipSuccess) return e;
+      e = hipEventCreate(&b);
+      if (e != hipSuccess) return e;
+      g_prof.pool.push_back(a);
+      g_prof.pool.push_back(b);
+      g_prof.cls.push_back(c);
+    }
+    g_prof.cls[g_prof.used] = c;
+    return hipEventRecord(g_prof.pool[g_prof.used * 2], s);
+  }
+  hipError_t e = hipEventRecord(g_prof.pool[g_prof.used * 2 + 1], s);
+  ++g_prof.used;
+  return e;
+}
+
+#define TIMED(cls, expr)                      \
+  do {                                        \
+    HIPCHK(prof_mark(s, cls, true));          \
+    HIPCHK(expr);                             \
+    HIPCHK(prof_mark(s, cls, false));         \
+  } while (0)
+
 constexpr size_t kAlign = 256;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -219,7 +264,7 @@ int enqueue_step() {
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
   const size_t slab = (size_t)M * T * d * es;       // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.rows_enc * 2 * d * es;
-  HIPCHK(launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, t, s));
+  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, t, s));
   for (int l = 0; l < hp.n_dec; ++l) {
     const DecLayer& L = g.dec[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
@@ -229,29 +274,29 @@ int enqueue_step() {
     o.ld[0] = d; o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
     o.seg_n = d;
     o.f32_out = 0;
-    HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
-    HIPCHK(launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, t + 1, s));
-    HIPCHK(launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), M, d, d, false, s));
-    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, M, d, hp.eps, s));
-    HIPCHK(launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
-    HIPCHK(launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+    TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
+    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, t + 1, s));
+    TIMED(PC_GEMM_DD, launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), M, d, d, false, s));
+    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, M, d, hp.eps, s));
+    TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
+    TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                   at<int32_t>(p.src_len), ctx, B, k, H, d, s));
-    HIPCHK(launch_gemm(dt, ctx, L.Woc, L.boc, plain_out(tmp, d), M, d, d, false, s));
-    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, M, d, hp.eps, s));
-    HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
-    HIPCHK(launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), M, d, F, false, s));
-    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln3g, L.ln3b, M, d, hp.eps, s));
+    TIMED(PC_GEMM_DD, launch_gemm(dt, ctx, L.Woc, L.boc, plain_out(tmp, d), M, d, d, false, s));
+    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, M, d, hp.eps, s));
+    TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
+    TIMED(PC_GEMM_FFN2, launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), M, d, F, false, s));
+    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln3g, L.ln3b, M, d, hp.eps, s));
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
-  HIPCHK(launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, false, s));
-  HIPCHK(launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos,
+  TIMED(PC_GEMM_VOCAB, launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, false, s));
+  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
-  HIPCHK(launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
+  TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                             at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active) + t, B, k, V, T,
                             t, hp.eos, s));
-  HIPCHK(launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, k, T, d, t + 1, s));
+  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, k, T, d, t + 1, s));
   g.t = t + 1;
   return LSQ_OK;
 }
@@ -470,6 +515,30 @@ int lsq_decode_steps(int n) {
   if (rc) return rc;
   if (active == 0) g.done = true;
   return active;
+}
+
+int lsq_profile_enable(int on) {
+  if (g_prof.used) return fail(LSQ_E_STATE, "read the pending profile first");
+  g_prof.on = on != 0;
+  return LSQ_OK;
+}
+
+int lsq_profile_classes(void) { return PC_COUNT; }
+
+const char* lsq_profile_class_name(int c) { return (c >= 0 && c < PC_COUNT) ? kProfNames[c] : ""; }
+
+int lsq_profile_read(double* ms, int64_t* launches, int n) {
+  if (!ms || !launches || n < PC_COUNT) return fail(LSQ_E_ARG, "need %d slots", (int)PC_COUNT);
+  for (int i = 0; i < n; ++i) { ms[i] = 0; launches[i] = 0; }
+  if (g.state >= 1) HIPCHK(hipStreamSynchronize(g.stream));
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    float t = 0.f;
+    HIPCHK(hipEventElapsedTime(&t, g_prof.pool[2 * i], g_prof.pool[2 * i + 1]));
+    ms[g_prof.cls[i]] += t;
+    launches[g_prof.cls[i]] += 1;
+  }
+  g_prof.used = 0;
+  return LSQ_OK;
 }
 
 int lsq_step_index(void) { return g.state >= 3 ? g.t : 0; }

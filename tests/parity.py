@@ -19,15 +19,23 @@ def logit_error(got, ref):
 def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
     """Runs the library and the oracle side by side, one decode step at a time.
 
-    Every step: logits against the oracle that rounds where the model stores (tight) and, while
-    both sides have made identical decisions, against the unrounded fp32 oracle (the stated
-    tolerance); then tokens, parents, lengths, finished flags and scores of every sentence that is
-    still comparable.  A sentence stays comparable while, at every step so far, the oracle's
-    smallest gap between competing candidates exceeded MARGIN plus twice the deviation the
-    library's candidate scores can have from the oracle's: (deviation of the hypothesis scores
-    before the step) + 2 * (largest logit difference of the step, which also bounds the
-    difference of the log-normaliser).  Above that bound the two orders cannot differ, so any
-    difference in tokens or parents is an error.  Returns a summary dict."""
+    Every step, for every sentence:
+      * logits against the oracle that rounds where the model stores (tight) and, while both
+        sides have made identical decisions, against the unrounded fp32 oracle (the stated
+        tolerance);
+      * the kept (beam, token) pairs.  Where the oracle's smallest gap between competing
+        candidates exceeds MARGIN plus twice the measured deviation of the library's candidate
+        scores from the oracle's ("strict" decisions) the two orders cannot differ and the pairs
+        must be identical.  Otherwise several selections are correct and the library's is
+        checked for validity instead: every kept pair's oracle score must reach the oracle's
+        k-th best within that band, kept pairs must be in oracle order within the band, and no
+        dropped pair may beat a kept one by more than the band.  The oracle then continues from
+        the library's (valid) selection with its own scores, so that every later step of every
+        sentence is still compared;
+      * token histories, lengths, finished flags (exact) and hypothesis scores (tolerance).
+    The deviation is measured over the 32 best candidates of every live row on either side
+    (candidate = hypothesis score before the step + log-softmax of the row's logits, evaluated
+    here in float64 from each side's own numbers).  Returns a summary dict."""
     m = O.Model(blob)                         # rounds at storage points for fp16 blobs
     mw = O.Model(blob, storage="wide") if (check_wide and m.round16) else None
     B, k, T, V = w.batch, w.beam, w.max_len, m.V
@@ -38,70 +46,117 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
     if mw is not None:
         _, cross_w = O.encode(mw, w.src_ids, w.src_lens)
         st_w = O.DecodeState(mw, w.src_lens, k, T)
-    comparable = np.ones(B, bool)
-    dev = np.zeros(B)                          # |library score - oracle score|, per sentence
     wide_in_sync = mw is not None
-    steps = 0
-    worst_tight = worst_wide = 0.0
-    compared_sentence_steps = 0
-    tol_tight = 2e-3 if m.round16 else TOL_F32
-    score_atol = 5e-3 if m.round16 else 2e-4
+    steps = strict_n = band_n = 0
+    worst_tight = worst_wide = worst_dev = 0.0
+    tol_tight = 1e-2 if m.round16 else TOL_F32
+    score_step_atol = 4e-3 if m.round16 else 2e-5     # hypothesis scores are sums over the steps
     while True:
         ref_logits = O.decoder_logits_cached(m, st, cross)
+        prev_ref = st.score.reshape(-1).copy()
+        prev_gpu = eng.debug(lsq.DBG.SCORE, (M,))
+        old_fin, old_len = st.finished.copy(), st.len.copy()
         active_gpu = eng.decode_step()
         got_logits = eng.debug(lsq.DBG.LOGITS, (M, V))
-        live_rows = np.repeat(comparable, k) & ~st.finished
-        if live_rows.any():
-            e = logit_error(got_logits[live_rows], ref_logits[live_rows])
+        live = ~old_fin
+        if live.any():
+            e = logit_error(got_logits[live], ref_logits[live])
             worst_tight = max(worst_tight, e)
             assert e <= tol_tight, f"step {steps}: logits differ from the storage-rounding oracle by {e}"
         if wide_in_sync:
             wl = O.decoder_logits_cached(mw, st_w, cross_w)
-            rows = live_rows & ~st_w.finished
+            rows = live & ~st_w.finished
             if rows.any():
                 e = logit_error(got_logits[rows], wl[rows])
                 worst_wide = max(worst_wide, e)
                 assert e <= TOL_F16, f"step {steps}: fp16 logits differ from the fp32 oracle by {e}"
         tok, par, sc, margin = O.beam_select(m, st, ref_logits)
-        active_ref = O.beam_advance(m, st, tok, par, sc)
         if wide_in_sync:
             tw, pw, sw, _ = O.beam_select(mw, st_w, wl)
             O.beam_advance(mw, st_w, tw, pw, sw)
             wide_in_sync = bool(np.array_equal(tw, tok) and np.array_equal(pw, par))
-        ldiff = np.zeros(B)
-        for b in range(B):
-            rows = np.arange(b * k, (b + 1) * k)[live_rows[b * k:(b + 1) * k]]
-            if len(rows):
-                ldiff[b] = np.abs(got_logits[rows] - ref_logits[rows]).max()
-        comparable &= margin > MARGIN + 2 * (dev + 2 * ldiff)
         g_tokens = eng.debug(lsq.DBG.TOKENS, (M, T + 1), np.int32)
         g_len = eng.debug(lsq.DBG.LEN, (M,), np.int32)
         g_fin = eng.debug(lsq.DBG.FINISHED, (M,), np.int32)
         g_par = eng.debug(lsq.DBG.PARENT, (M,), np.int32)
         g_score = eng.debug(lsq.DBG.SCORE, (M,))
-        for b in np.nonzero(comparable)[0]:
-            r = slice(b * k, (b + 1) * k)
-            assert np.array_equal(g_par[r], par[b]), f"step {steps} sentence {b}: parents {g_par[r]} vs {par[b]}"
-            assert np.array_equal(g_len[r], st.len[r]), f"step {steps} sentence {b}: lengths"
-            assert np.array_equal(g_fin[r] != 0, st.finished[r]), f"step {steps} sentence {b}: finished flags"
+        logp = O.log_softmax(np.asarray(ref_logits, m.ctype))
+        for b in range(B):
+            base = b * k
+            # measured deviation of candidate scores
+            cdev = 0.0
             for j in range(k):
-                n = st.len[b * k + j]
-                assert np.array_equal(g_tokens[b * k + j, : n + 1], st.tokens[b * k + j, : n + 1]), \
-                    f"step {steps} sentence {b} beam {j}: tokens"
-            fin = np.isfinite(sc[b])
-            assert np.array_equal(np.isfinite(g_score[r]), fin)
-            np.testing.assert_allclose(g_score[r][fin], sc[b][fin], rtol=2e-5, atol=score_atol)
-            dev[b] = np.abs(g_score[r][fin].astype(np.float64) - sc[b][fin]).max() if fin.any() else 0.0
-            compared_sentence_steps += 1
-        if comparable.all():
-            assert active_gpu == active_ref, f"step {steps}: active {active_gpu} vs {active_ref}"
+                r = base + j
+                if not np.isfinite(prev_ref[r]):
+                    assert not np.isfinite(prev_gpu[r])
+                    continue
+                if old_fin[r]:
+                    cdev = max(cdev, abs(float(prev_gpu[r]) - float(prev_ref[r])))
+                    continue
+                c_ref = float(prev_ref[r]) + O.log_softmax(ref_logits[r].astype(np.float64))
+                c_gpu = float(prev_gpu[r]) + O.log_softmax(got_logits[r].astype(np.float64))
+                top = np.union1d(np.argpartition(-c_ref, 32)[:32], np.argpartition(-c_gpu, 32)[:32]) \
+                    if V > 33 else np.arange(V)
+                cdev = max(cdev, float(np.abs(c_gpu[top] - c_ref[top]).max()))
+            worst_dev = max(worst_dev, cdev)
+            band = MARGIN + 2 * cdev
+            # the library's selection for this sentence
+            gp = g_par[base:base + k].astype(np.int64)
+            assert ((gp >= 0) & (gp < k)).all(), f"step {steps} sentence {b}: parent out of range"
+            gt = np.empty(k, np.int64)
+            for i in range(k):
+                pr = base + gp[i]
+                gt[i] = m.eos if old_fin[pr] else g_tokens[base + i, old_len[pr] + 1]
+            if margin[b] > band:
+                strict_n += 1
+                assert np.array_equal(gp, par[b]) and np.array_equal(gt, tok[b]), \
+                    f"step {steps} sentence {b}: kept pairs differ although the margin {margin[b]:.2e} " \
+                    f"exceeds {band:.2e}: parents {gp} vs {par[b]}, tokens {gt} vs {tok[b]}"
+            else:
+                band_n += 1
+                def ref_score(j, v):
+                    r = base + j
+                    return st.score[b, j] if old_fin[r] else st.score[b, j] + logp[r, v]
+                kept = [(int(gp[i]), int(gt[i])) for i in range(k)]
+                assert len(set(kept)) == k, f"step {steps} sentence {b}: a pair was kept twice"
+                ks = np.array([ref_score(j, v) for j, v in kept], np.float64)
+                kth = float(sc[b, k - 1])
+                if np.isfinite(kth):
+                    assert (ks >= kth - band).all(), f"step {steps} sentence {b}: kept pair below the band: {ks} vs {kth}"
+                    assert (np.diff(ks) <= band).all(), f"step {steps} sentence {b}: kept pairs out of order: {ks}"
+                    # best dropped pair by the oracle's order
+                    best_drop = -np.inf
+                    for j in range(k):
+                        r = base + j
+                        if not np.isfinite(prev_ref[r]):
+                            continue
+                        if old_fin[r]:
+                            if (j, m.eos) not in kept:
+                                best_drop = max(best_drop, float(st.score[b, j]))
+                            continue
+                        for v in np.argpartition(-logp[r], min(k, V - 1))[:k + 1]:
+                            if (j, int(v)) not in kept:
+                                best_drop = max(best_drop, float(st.score[b, j] + logp[r, v]))
+                    assert best_drop <= ks.min() + band, \
+                        f"step {steps} sentence {b}: dropped pair {best_drop} beats a kept one {ks.min()}"
+                par[b], tok[b] = gp, gt
+                sc[b] = np.array([ref_score(j, v) for j, v in kept], m.ctype)
+        active_ref = O.beam_advance(m, st, tok, par, sc)
+        assert np.array_equal(g_len, st.len), f"step {steps}: lengths"
+        assert np.array_equal(g_fin != 0, st.finished), f"step {steps}: finished flags"
+        for r in range(M):
+            n = st.len[r]
+            assert np.array_equal(g_tokens[r, : n + 1], st.tokens[r, : n + 1]), f"step {steps} row {r}: tokens"
+        fin = np.isfinite(st.score.reshape(-1))
+        assert np.array_equal(np.isfinite(g_score), fin), f"step {steps}: -inf scores"
+        np.testing.assert_allclose(g_score[fin], st.score.reshape(-1)[fin], rtol=2e-5,
+                                   atol=1e-4 + score_step_atol * (steps + 1))
+        assert active_gpu == active_ref, f"step {steps}: active {active_gpu} vs {active_ref}"
         steps += 1
         if verbose:
-            print(f"step {steps}: active {active_gpu}, comparable {int(comparable.sum())}/{B}, "
-                  f"tight {worst_tight:.2e} wide {worst_wide:.2e}", flush=True)
+            print(f"step {steps}: active {active_gpu}, strict {strict_n} band {band_n}, "
+                  f"tight {worst_tight:.2e} wide {worst_wide:.2e} dev {worst_dev:.2e}", flush=True)
         if active_gpu == 0 or (max_steps is not None and steps >= max_steps):
             break
-        if active_ref == 0 and comparable.all():
-            raise AssertionError("oracle finished but the library did not")
-    return dict(steps=steps, comparable=int(comparable.sum()), batch=B, worst_tight=worst_tight,
-                worst_wide=worst_wide, compared=compared_sentence_steps, state=st, comparable_mask=comparable)
+    return dict(steps=steps, batch=B, worst_tight=worst_tight, worst_wide=worst_wide, worst_dev=worst_dev,
+                strict=strict_n, band=band_n, state=st)

@@ -1,0 +1,265 @@
+"""Kernel-level parity: every HIP kernel against the oracle's function of the same operation on
+seeded tensors, through the C ABI (needs an MI355X).  Sizes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+
+from oracle import lsq_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2010_13887_amd as lib
+    lib.load_library()
+    return lib, torch
+
+
+def _dev(torch, a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def _h(a):       # round to fp16 and widen: the values an fp16 tensor holds
+    return np.asarray(a, np.float32).astype(np.float16).astype(np.float32)
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 192, 64), (33, 1000, 72), (130, 520, 256), (512, 1024, 1024),
+                                   (512, 3072, 1024), (100, 1003, 264), (512, 32000, 1024), (1, 64, 8),
+                                   (700, 136, 4096)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_gemm_fp16(env, M, N, K, relu):
+    lsq, torch = env
+    rng = np.random.default_rng(M * 7 + N)
+    A, B, bias = _h(rng.standard_normal((M, K))), _h(rng.standard_normal((N, K)) * 0.05), _h(rng.standard_normal(N))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + bias
+    if relu:
+        ref = np.maximum(ref, 0)
+    dA, dB, db = _dev(torch, A, torch.float16), _dev(torch, B, torch.float16), _dev(torch, bias, torch.float16)
+    C32 = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    lsq.k_gemm(dA, dB, db, C32, relu)
+    got = C32.cpu().numpy()
+    scale = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).T + np.abs(bias)
+    assert (np.abs(got - ref) <= 2e-6 * scale + 1e-7).all()        # fp32 accumulation of exact products
+    C16 = torch.empty(M, N, dtype=torch.float16, device="cuda")
+    lsq.k_gemm(dA, dB, db, C16, relu)
+    got16 = C16.float().cpu().numpy()
+    np.testing.assert_allclose(got16, ref, rtol=1e-3, atol=2e-6 * scale.max() + 1e-6)
+    # no bias
+    lsq.k_gemm(dA, dB, None, C32, False)
+    assert (np.abs(C32.cpu().numpy() - (ref_nb := A.astype(np.float64) @ B.astype(np.float64).T)) <= 2e-6 * scale + 1e-7).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 192, 64), (33, 1000, 71), (130, 77, 256), (2, 3000, 64)])
+def test_gemm_fp32(env, M, N, K):
+    lsq, torch = env
+    rng = np.random.default_rng(M + N)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    lsq.k_gemm(_dev(torch, A), _dev(torch, B), _dev(torch, bias), C, True)
+    ref = np.maximum(A.astype(np.float64) @ B.astype(np.float64).T + bias, 0)
+    np.testing.assert_allclose(C.cpu().numpy(), ref, rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("rows,d", [(1, 64), (5, 512), (513, 1024), (37, 2048), (3, 4096), (9, 72), (4, 100)])
+@pytest.mark.parametrize("half", [False, True])
+def test_add_layernorm(env, rows, d, half):
+    lsq, torch = env
+    rng = np.random.default_rng(rows + d)
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    x, a = cast(rng.standard_normal((rows, d)) * 2), cast(rng.standard_normal((rows, d)) + 0.3)
+    g, b = cast(1 + 0.3 * rng.standard_normal(d)), cast(0.3 * rng.standard_normal(d))
+    ref = O.layer_norm(x.astype(np.float64) + a, g.astype(np.float64), b.astype(np.float64), 1e-5)
+    td = torch.float16 if half else torch.float32
+    dx = _dev(torch, x, td)
+    lsq.k_add_layernorm(dx, _dev(torch, a, td), _dev(torch, g, td), _dev(torch, b, td), 1e-5)
+    got = dx.float().cpu().numpy()
+    if half:
+        np.testing.assert_allclose(got, ref, rtol=1.1e-3, atol=1e-3)
+        assert np.abs(got - _h(ref)).max() <= 4e-3 and (got != _h(ref)).mean() < 0.02
+    else:
+        np.testing.assert_allclose(got, ref, rtol=2e-5, atol=2e-5)
+
+
+@pytest.mark.parametrize("rows,H,dh,T,nkeys", [(3, 4, 16, 8, 1), (9, 4, 16, 8, 8), (32, 8, 64, 110, 77),
+                                               (5, 2, 128, 40, 33), (7, 3, 32, 50, 50), (130, 16, 64, 178, 41)])
+@pytest.mark.parametrize("half", [False, True])
+def test_self_attention(env, rows, H, dh, T, nkeys, half):
+    lsq, torch = env
+    rng = np.random.default_rng(rows * 3 + nkeys)
+    d = H * dh
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    q = cast(rng.standard_normal((rows, d)))
+    Kc, Vc = cast(rng.standard_normal((rows, T, d))), cast(rng.standard_normal((rows, T, d)))
+    td = torch.float16 if half else torch.float32
+    out = torch.full((rows, d), 7.0, dtype=td, device="cuda")
+    lsq.k_self_attention(_dev(torch, q, td), _dev(torch, Kc, td), _dev(torch, Vc, td), out, H, nkeys)
+    ref = np.stack([O.attention(q[r:r + 1].astype(np.float64), Kc[r, :nkeys].astype(np.float64),
+                                Vc[r, :nkeys].astype(np.float64), H)[0] for r in range(rows)])
+    tol = 1.5e-3 if half else 2e-5
+    np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
+
+
+@pytest.mark.parametrize("lens,beam,H,dh", [([5, 8], 4, 4, 16), ([1, 60, 17, 33], 4, 8, 64), ([9, 2, 31], 3, 2, 32),
+                                            ([4, 4, 128, 7, 1], 8, 16, 64), ([3], 1, 2, 128), ([6, 11], 5, 4, 16)])
+@pytest.mark.parametrize("half", [False, True])
+def test_cross_attention(env, lens, beam, H, dh, half):
+    lsq, torch = env
+    rng = np.random.default_rng(sum(lens) + beam)
+    d, B = H * dh, len(lens)
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    q = cast(rng.standard_normal((B * beam, d)))
+    kv = cast(rng.standard_normal((sum(lens), 2 * d)))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    td = torch.float16 if half else torch.float32
+    out = torch.full((B * beam, d), 7.0, dtype=td, device="cuda")
+    lsq.k_cross_attention(_dev(torch, q, td), _dev(torch, kv, td), _dev(torch, off), _dev(torch, np.array(lens, np.int32)),
+                          out, B, beam, H)
+    ref = np.concatenate([O.attention(q[b * beam:(b + 1) * beam].astype(np.float64),
+                                      kv[off[b]:off[b + 1], :d].astype(np.float64),
+                                      kv[off[b]:off[b + 1], d:].astype(np.float64), H) for b in range(B)])
+    tol = 1.5e-3 if half else 2e-5
+    np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
+
+
+def _oracle_row_topk(logits, score, finished, k, eos):
+    """Per row: the oracle's candidate scores and a full sort."""
+    M, V = logits.shape
+    os_, oi = np.full((M, k), -np.inf, np.float32), np.full((M, k), -1, np.int32)
+    logp = O.log_softmax(logits.astype(np.float32))
+    for r in range(M):
+        if finished[r]:
+            os_[r, 0], oi[r, 0] = score[r], eos
+            continue
+        c = (score[r] + logp[r]).astype(np.float32)
+        best = O.topk_by_full_sort(c, np.arange(V), k)
+        os_[r, :len(best)], oi[r, :len(best)] = c[best], best
+    return os_, oi
+
+
+@pytest.mark.parametrize("M,V,k", [(8, 1000, 4), (5, 12, 3), (33, 32000, 4), (6, 50257, 8), (4, 8192, 1),
+                                   (3, 8200, 5), (2, 65536, 4), (7, 2048, 4), (9, 5, 5)])
+@pytest.mark.parametrize("case", ["random", "ties", "all_equal", "dead_and_finished"])
+def test_row_topk(env, M, V, k, case):
+    lsq, torch = env
+    rng = np.random.default_rng(M + V + k)
+    logits = (rng.standard_normal((M, V)) * 0.7).astype(np.float32)
+    score = -(rng.random(M) * 50).astype(np.float32)
+    fin = np.zeros(M, np.int32)
+    if case == "ties":
+        logits = np.round(logits * 2) / 2            # heavy duplication: order decided by token id
+    elif case == "all_equal":
+        logits[:] = 0.125
+    elif case == "dead_and_finished":
+        score[::2] = -np.inf
+        fin[1::3] = 1
+    eos = 2
+    os_ = torch.zeros(M, k, dtype=torch.float32, device="cuda")
+    oi = torch.zeros(M, k, dtype=torch.int32, device="cuda")
+    lsq.k_row_topk(_dev(torch, logits), _dev(torch, score), _dev(torch, fin), k, eos, os_, oi)
+    got_s, got_i = os_.cpu().numpy(), oi.cpu().numpy()
+    ref_s, ref_i = _oracle_row_topk(logits, score, fin, k, eos)
+    if case == "random":
+        # distinct logits: indices are unique wherever neighbouring candidates differ by more than rounding
+        c = np.sort(-(score[:, None] + O.log_softmax(logits.astype(np.float64))), axis=1)[:, :k + 1]
+        clear = (np.diff(c, axis=1) > 1e-4).all(axis=1) | ~np.isfinite(c).all(axis=1)
+        assert clear.mean() > 0.5
+        assert np.array_equal(got_i[clear], ref_i[clear])
+    else:
+        assert np.array_equal(got_i, ref_i)          # bit-exact indices on identical scores
+    both = np.isfinite(ref_s)
+    assert np.array_equal(np.isfinite(got_s), both)
+    np.testing.assert_allclose(got_s[both], ref_s[both], rtol=1e-5, atol=1e-5)
+
+
+def _state(rng, B, k, V, T, t, eos, finished_frac):
+    M = B * k
+    tokens = rng.integers(4, V, size=(M, T + 1)).astype(np.int32)
+    tokens[:, 0] = 1
+    fin = (rng.random(M) < finished_frac)
+    length = np.where(fin, rng.integers(1, t + 1, size=M) if t >= 1 else 0, t).astype(np.int32)
+    if t == 0:
+        fin[:] = False
+    score = np.sort(-(rng.random((B, k)) * 5).astype(np.float32), axis=1)[:, ::-1].copy()
+    cap = rng.integers(t + 1, T + 1, size=B).astype(np.int32)
+    return tokens, length, fin, score, cap
+
+
+@pytest.mark.parametrize("B,k,V,T,t", [(2, 4, 1000, 8, 0), (5, 3, 12, 11, 4), (128, 4, 32000, 178, 40),
+                                       (3, 8, 50, 9, 8), (4, 1, 100, 6, 2), (6, 5, 37, 12, 7)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_row_topk_then_refine_matches_oracle_step(env, B, k, V, T, t, ties):
+    """retrieve + re-rank on seeded logits and beam state == the oracle's softmax + full sort +
+    bookkeeping, including finished hypotheses, caps, -inf beams and exact ties."""
+    lsq, torch = env
+    rng = np.random.default_rng(B * 31 + V + t)
+    M = B * k
+    import lsq_synth as S
+    hp = S.HParams(n_enc=1, n_dec=1, d_model=8, n_heads=1, d_ffn=8, vocab=V, max_pos=8)
+    m = O.Model(S.make_blob(hp))
+    tokens, length, fin, score, cap = _state(rng, B, k, V, T, t, m.eos, 0.0 if t == 0 else 0.3)
+    if t == 0:
+        score[:, 1:] = -np.inf
+        score[:, 0] = 0
+    logits = (rng.standard_normal((M, V)) * 0.7).astype(np.float32)
+    if ties:
+        logits = np.round(logits * 2) / 2
+        score = np.round(score * 2) / 2                      # equal beam scores too: flat index decides
+    # oracle step
+    st = O.DecodeState(m, np.ones(B, np.int32), k, T)
+    st.tokens, st.len, st.finished, st.score, st.cap, st.t = tokens.copy(), length.copy(), fin.copy(), score.copy(), cap.copy(), t
+    st.Kc, st.Vc = [], []
+    tok, par, sc, margin = O.beam_select(m, st, logits)
+    active_ref = O.beam_advance(m, st, tok, par, sc)
+    # library
+    d_score = _dev(torch, score.reshape(-1))
+    d_tokens, d_len, d_fin = _dev(torch, tokens), _dev(torch, length), _dev(torch, fin.astype(np.int32))
+    cs = torch.zeros(M, k, dtype=torch.float32, device="cuda")
+    ci = torch.zeros(M, k, dtype=torch.int32, device="cuda")
+    parent = torch.zeros(M, dtype=torch.int32, device="cuda")
+    active = torch.zeros(1, dtype=torch.int32, device="cuda")
+    lsq.k_row_topk(_dev(torch, logits), d_score, d_fin, k, m.eos, cs, ci)
+    lsq.k_beam_refine(cs, ci, d_score, d_tokens, d_len, d_fin, parent, _dev(torch, cap), active, B, k, V, T, t, m.eos)
+    ok = (margin > 1e-4) | ties        # with exact ties both sides see identical scores per row
+    g_par = parent.cpu().numpy().reshape(B, k)
+    g_tok, g_len, g_fin = d_tokens.cpu().numpy(), d_len.cpu().numpy(), d_fin.cpu().numpy()
+    g_score = d_score.cpu().numpy().reshape(B, k)
+    assert ok.mean() > 0.5
+    for b in np.nonzero(ok)[0]:
+        r = slice(b * k, (b + 1) * k)
+        assert np.array_equal(g_par[b], par[b])
+        assert np.array_equal(g_len[r], st.len[r]) and np.array_equal(g_fin[r] != 0, st.finished[r])
+        for j in range(k):
+            n = st.len[b * k + j]
+            assert np.array_equal(g_tok[b * k + j, :n + 1], st.tokens[b * k + j, :n + 1])
+        f = np.isfinite(sc[b])
+        assert np.array_equal(np.isfinite(g_score[b]), f)
+        np.testing.assert_allclose(g_score[b][f], sc[b][f], rtol=1e-5, atol=1e-5)
+    if ok.all():
+        assert int(active.item()) == active_ref
+
+
+@pytest.mark.parametrize("layers,B,k,T,d,npos", [(2, 3, 4, 8, 64, 8), (12, 16, 4, 60, 1024, 41), (4, 5, 3, 9, 32, 1),
+                                                 (2, 2, 8, 20, 128, 13), (3, 4, 1, 6, 64, 6), (2, 7, 5, 33, 72 * 8, 20)])
+@pytest.mark.parametrize("half", [False, True])
+def test_cache_reorder(env, layers, B, k, T, d, npos, half):
+    lsq, torch = env
+    rng = np.random.default_rng(layers + B + d)
+    M = B * k
+    cache = rng.standard_normal((layers, M, T, d)).astype(np.float16 if half else np.float32)
+    parent = rng.integers(0, k, size=(B, k)).astype(np.int32)
+    parent[0] = np.arange(k)                               # one sentence whose beams do not move
+    if B > 1:
+        parent[1] = np.roll(np.arange(k), 1)               # a pure permutation (cycle)
+    dc = _dev(torch, cache)
+    lsq.k_cache_reorder(dc, _dev(torch, parent.reshape(-1)), layers, B, k, T, d, npos)
+    rows = (np.arange(B)[:, None] * k + parent).reshape(-1)
+    ref = cache.copy()
+    ref[:, :, :npos] = cache[:, rows, :npos]               # positions beyond npos are untouched
+    assert np.array_equal(dc.cpu().numpy(), ref)
