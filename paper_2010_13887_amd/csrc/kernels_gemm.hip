@@ -62,55 +62,73 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp16 MFMA.  Block tile BM x BN, BK = 64, four wavefronts each owning a WM x WN sub-tile made of
-// 32x32 MFMA blocks.  Global -> registers (next tile) overlaps the MFMAs on the current LDS tile.
-// LDS rows are padded by 8 halves so the 16-byte fragment reads of 32 consecutive rows hit
-// distinct banks.  The MFMA is issued as D = Bfrag x Afrag, i.e. D[n][m]: a lane then owns four
-// consecutive n of one m, which makes the epilogue store an aligned 8-byte vector.
-template <int BM, int BN, int WM, int WN, typename OutT>
+// fp16 MFMA.  Block tile BM x BN x BK, four wavefronts each owning a WM x WN sub-tile made of
+// 32x32 MFMA blocks.
+//
+// Latency hiding: at these sizes (M = batch*beam <= a few hundred rows) a k-iteration's MFMA work
+// is far shorter than a trip to HBM, so the loads of the next D k-tiles are kept in flight in
+// registers (D "stages", statically indexed by unrolling the k-loop D times) while the current
+// tile is multiplied out of LDS.  LDS is double buffered, one barrier per k-iteration: tile kt is
+// written to buffer kt&1 before the barrier and read after it; the buffer it overwrites was last
+// read two iterations ago, which every wavefront has left behind by then.
+// LDS rows are padded by 8 halves so the 16-byte fragment reads of consecutive rows hit distinct
+// banks.  The MFMA is issued as D = Bfrag x Afrag, i.e. D[n][m]: a lane then owns four
+// consecutive n of one m, which makes the epilogue store an aligned 8- or 16-byte vector.
+// Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so the id is remapped
+// to give every XCD a contiguous run of tiles, m fastest: the tiles that share a weight tile then
+// share an L2.
+template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
                                                        const half_t* __restrict__ bias, GemmOut out, int M,
                                                        int N, int K, int relu, int vec_ok) {
-  constexpr int BK = 64, LDK = BK + 8;
+  constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
+  constexpr int VPR = BK / 8;   // 16-byte vectors per tile row
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
-  constexpr int AV = BM * BK / 8 / 256, BV = BN * BK / 8 / 256;   // 16-byte vectors per thread
+  constexpr int AV = BM * VPR / 256, BV = BN * VPR / 256;   // vectors per thread
   static_assert(AV >= 1 && BV >= 1, "tile too small");
-  __shared__ __attribute__((aligned(16))) half_t As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) half_t Bs[BN * LDK];
+  __shared__ __attribute__((aligned(16))) half_t As[2][BM * LDK];
+  __shared__ __attribute__((aligned(16))) half_t Bs[2][BN * LDK];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN, total = mt * nt;
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int m0 = (id % mt) * BM, n0 = (id / mt) * BN;
   const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
 
-  half8_t ra[AV], rb[BV];
-  auto gload = [&](int k0) {
+  // Loads are unconditional (rows clamped to the last valid one, k-tile index clamped by the
+  // caller) so that the k-loop body is straight-line code and the compiler can wait for just the
+  // oldest stage (vmcnt = loads of the younger stages) instead of draining all of them.
+  half8_t ra[D][AV], rb[D][BV];
+  auto gload = [&](half8_t(&a)[AV], half8_t(&b)[BV], int k0) {
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
       int m = min(m0 + row, M - 1);
-      if (k0 + kc < K) ra[i] = *reinterpret_cast<const half8_t*>(A + (size_t)m * K + k0 + kc);
-      else ra[i] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+      int kk = KTAIL ? min(k0 + kc, K - 8) : k0 + kc;
+      a[i] = *reinterpret_cast<const half8_t*>(A + (size_t)m * K + kk);
     }
 #pragma unroll
     for (int i = 0; i < BV; ++i) {
-      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
+      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
       int n = min(n0 + row, N - 1);
-      if (k0 + kc < K) rb[i] = *reinterpret_cast<const half8_t*>(B + (size_t)n * K + k0 + kc);
-      else rb[i] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+      int kk = KTAIL ? min(k0 + kc, K - 8) : k0 + kc;
+      b[i] = *reinterpret_cast<const half8_t*>(B + (size_t)n * K + kk);
     }
   };
-  auto sstore = [&]() {
+  auto sstore = [&](const half8_t(&a)[AV], const half8_t(&b)[BV], int buf, int k0) {
+    const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
-      *reinterpret_cast<half8_t*>(&As[row * LDK + kc]) = ra[i];
+      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      *reinterpret_cast<half8_t*>(&As[buf][row * LDK + kc]) = (KTAIL && k0 + kc >= K) ? zero : a[i];
     }
 #pragma unroll
     for (int i = 0; i < BV; ++i) {
-      int v = tid + i * 256, row = v >> 3, kc = (v & 7) * 8;
-      *reinterpret_cast<half8_t*>(&Bs[row * LDK + kc]) = rb[i];
+      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      *reinterpret_cast<half8_t*>(&Bs[buf][row * LDK + kc]) = (KTAIL && k0 + kc >= K) ? zero : b[i];
     }
   };
 
@@ -122,32 +140,58 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  gload(0);
-  sstore();
-  __syncthreads();
+  // this lane's bias values, fetched now so their latency hides behind the first tile loads
+  float bv[TN][4][4];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int n = min(n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4 + e, N - 1);
+        bv[j][vg][e] = bias ? (float)bias[n] : 0.f;
+      }
+
+  const int nk = (K + BK - 1) / BK;
+  static_assert(D % 2 == 0, "stage s always uses LDS buffer s & 1");
+#pragma unroll
+  for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
   const int fr = lane & 31, fk = (lane >> 5) * 8;
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    const bool more = k0 + BK < K;
-    if (more) gload(k0 + BK);
+  auto compute = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       half8_t af[TM], bf[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const half8_t*>(&As[(wm + i * 32 + fr) * LDK + ks + fk]);
+        af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + ks + fk]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bf[j] = *reinterpret_cast<const half8_t*>(&Bs[(wn + j * 32 + fr) * LDK + ks + fk]);
+        bf[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + ks + fk]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
-    if (more) {
-      sstore();
+  };
+  int it = 0;
+  for (; it + D <= nk; it += D) {
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      const int kt = it + s;
+      sstore(ra[s], rb[s], s & 1, kt * BK);
+      gload(ra[s], rb[s], min(kt + D, nk - 1) * BK);   // beyond the end: a redundant load, never used
       __syncthreads();
+      compute(s & 1);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < D; ++s) {   // the last nk % D tiles are already in registers
+    const int kt = it + s;
+    if (kt < nk) {
+      sstore(ra[s], rb[s], s & 1, kt * BK);
+      __syncthreads();
+      compute(s & 1);
     }
   }
 
@@ -165,8 +209,7 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          v[e] = acc[i][j][vg * 4 + e];
-          if (bias && n + e < N) v[e] += (float)bias[n + e];
+          v[e] = acc[i][j][vg * 4 + e] + bv[j][vg][e];
           if (relu) v[e] = fmaxf(v[e], 0.f);
         }
         if (vec_ok && n + 3 < N) {
@@ -189,14 +232,18 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int D>
 static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
                     int K, int relu, int vec_ok, hipStream_t s) {
-  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), blk(256);
-  if (out.f32_out)
-    gemm_f16_kernel<BM, BN, WM, WN, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
-  else
-    gemm_f16_kernel<BM, BN, WM, WN, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM)), blk(256);
+  const bool tail = (K % BK) != 0;
+  if (out.f32_out) {
+    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  } else {
+    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  }
 }
 
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
@@ -220,11 +267,11 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (M <= 32)
-    run_f16<32, 128, 32, 32>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else if (tiles128 >= 256)
-    run_f16<128, 128, 64, 64>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<128, 128, 32, 64, 64, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else
-    run_f16<64, 64, 32, 32>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   return hipGetLastError();
 }
 
