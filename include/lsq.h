@@ -118,12 +118,12 @@ int lsq_profile_read(double* ms, int64_t* launches, int n);
  * is always delivered as float32 whatever the model's storage type. `bytes`
  * must equal the size of the item.  M = batch*beam rows, T = max_len.          */
 enum {
-  LSQ_DBG_LOGITS = 0,     /* float [M, vocab]  logits of the last step (always fp32)   */
+  LSQ_DBG_LOGITS = 0,     /* float [M, vocab]  logits of the last step (always fp32); rows of sentences past their cap are stale */
   LSQ_DBG_SCORE = 1,      /* float [M]         raw hypothesis scores                   */
   LSQ_DBG_TOKENS = 2,     /* int32 [M, T+1]    token histories, BOS first              */
   LSQ_DBG_LEN = 3,        /* int32 [M]                                                 */
   LSQ_DBG_FINISHED = 4,   /* int32 [M]                                                 */
-  LSQ_DBG_PARENT = 5,     /* int32 [M]         parent beam (0..beam-1) of the last step */
+  LSQ_DBG_PARENT = 5,     /* int32 [M]         parent beam (0..beam-1) chosen in the last step the sentence took part in */
   LSQ_DBG_CAND_SCORE = 6, /* float [M, beam]   per-row top-k scores of the last step   */
   LSQ_DBG_CAND_IDX = 7,   /* int32 [M, beam]   per-row top-k tokens (-1 = none)        */
   LSQ_DBG_HIDDEN = 8,     /* float [M, d]      decoder output of the last step         */

@@ -289,13 +289,13 @@ __global__ void __launch_bounds__(256) cache_reorder_kernel(uint4* __restrict__ 
   }
 }
 
-hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k,
-                                int T, int d, int npos, hipStream_t s) {
+hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
+                                int rows_total, int k, int T, int d, int npos, hipStream_t s) {
   if (batch <= 0 || layers <= 0 || npos <= 0 || k <= 1) return hipSuccess;
   size_t esz = dtype == DT_F16 ? 2 : 4;
   if ((d * esz) % 16 != 0 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
   long row_vecs = (long)T * d * esz / 16, used = (long)npos * d * esz / 16;
-  long layer_vecs = (long)batch * k * row_vecs;
+  long layer_vecs = (long)rows_total * row_vecs;   // a layer holds rows_total rows; the first batch*k are reordered
   dim3 grid((unsigned)((used + 1023) / 1024), batch, layers), blk(256);
   if (k <= 4)
     cache_reorder_kernel<4><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, used, layer_vecs);
@@ -330,9 +330,11 @@ __global__ void __launch_bounds__(64) finalize_kernel(const float* __restrict__ 
                                                       const int32_t* __restrict__ tokens,
                                                       const int32_t* __restrict__ len, int32_t* __restrict__ out_ids,
                                                       int32_t* __restrict__ out_lens, float* __restrict__ out_scores,
-                                                      int k, int T, float alpha, int pad) {
+                                                      const int32_t* __restrict__ sentence_order, int k, int T,
+                                                      float alpha, int pad) {
   __shared__ int order[LSQ_MAX_BEAM_];
   const int b = blockIdx.x, lane = threadIdx.x;
+  const int ob = sentence_order[b];   // where the caller expects this sentence
   float f = -INFINITY;
   int n = 0;
   if (lane < k) {
@@ -348,22 +350,23 @@ __global__ void __launch_bounds__(64) finalize_kernel(const float* __restrict__ 
   }
   if (lane < k) {
     order[rank] = lane;
-    out_lens[b * k + rank] = n;
-    out_scores[b * k + rank] = f;
+    out_lens[ob * k + rank] = n;
+    out_scores[ob * k + rank] = f;
   }
   __syncthreads();
   for (int i = 0; i < k; ++i) {
     int src = b * k + order[i];
     int n_i = len[src];
     for (int p = lane; p < T; p += 64)
-      out_ids[(size_t)(b * k + i) * T + p] = p < n_i ? tokens[(size_t)src * (T + 1) + 1 + p] : pad;
+      out_ids[(size_t)(ob * k + i) * T + p] = p < n_i ? tokens[(size_t)src * (T + 1) + 1 + p] : pad;
   }
 }
 
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
-                           int32_t* out_lens, float* out_scores, int batch, int k, int T, float alpha, int pad,
-                           hipStream_t s) {
-  finalize_kernel<<<batch, 64, 0, s>>>(score, tokens, len, out_ids, out_lens, out_scores, k, T, alpha, pad);
+                           int32_t* out_lens, float* out_scores, const int32_t* sentence_order, int batch, int k,
+                           int T, float alpha, int pad, hipStream_t s) {
+  finalize_kernel<<<batch, 64, 0, s>>>(score, tokens, len, out_ids, out_lens, out_scores, sentence_order, k, T,
+                                       alpha, pad);
   return hipGetLastError();
 }
 

@@ -63,13 +63,13 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
                               int t, int eos, hipStream_t s);
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
-                                int k, int T, int d, int npos, hipStream_t s);
+                                int rows_total, int k, int T, int d, int npos, hipStream_t s);
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
                              int32_t* active_counts, int batch, int k, int T, int bos, int pad,
                              hipStream_t s);
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
-                           int32_t* out_lens, float* out_scores, int batch, int k, int T, float alpha,
-                           int pad, hipStream_t s);
+                           int32_t* out_lens, float* out_scores, const int32_t* sentence_order, int batch,
+                           int k, int T, float alpha, int pad, hipStream_t s);
 
 bool topk_supported(int V);
 bool head_dim_supported(int dh);

@@ -1,5 +1,6 @@
 // Host side of liblsq.so: the C ABI, blob parsing, the max-shape memory plan (paper sec. 2.3)
 // and the per-call launch sequences.  No device memory is ever allocated here.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -145,7 +146,7 @@ struct DecLayer {
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
 struct Plan {
-  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, src_off, src_len, active,
+  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, order, src_off, src_len, active,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
@@ -169,6 +170,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.fin = take(M * 4);
   p.parent = take(M * 4);
   p.cap = take((size_t)B * 4);
+  p.order = take((size_t)B * 4);
   p.src_off = take((size_t)(B + 1) * 4);
   p.src_len = take((size_t)B * 4);
   p.active = take((size_t)(T + 1) * 4);
@@ -215,6 +217,8 @@ struct Ctx {
   int max_batch = 0, beam = 0, max_len = 0;
   int batch = 0, rows_enc = 0, t = 0;
   bool done = false;
+  std::vector<int> order;      // internal (sorted) sentence index -> caller's index
+  std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
   std::vector<EncLayer> enc;
   std::vector<DecLayer> dec;
@@ -258,11 +262,13 @@ int enqueue_step() {
   const Plan& p = g.plan;
   hipStream_t s = g.stream;
   const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, k = g.beam, T = g.max_len, t = g.t;
-  const int B = g.batch, M = B * k;
+  // Sentences are kept sorted by cap (descending), so those that can still be unfinished at step
+  // t are a prefix; the host knows its length without reading anything back.
+  const int B = g.alive_at[t], M = B * k, M_all = g.batch * k;
   const size_t es = esz();
   char* x = g.ws + p.d_x; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
-  const size_t slab = (size_t)M * T * d * es;       // one layer's K (or V) cache
+  const size_t slab = (size_t)M_all * T * d * es;   // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.rows_enc * 2 * d * es;
   TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, t, s));
   for (int l = 0; l < hp.n_dec; ++l) {
@@ -296,7 +302,7 @@ int enqueue_step() {
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                             at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active) + t, B, k, V, T,
                             t, hp.eos, s));
-  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, k, T, d, t + 1, s));
+  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_all, k, T, d, t + 1, s));
   g.t = t + 1;
   return LSQ_OK;
 }
@@ -397,7 +403,7 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
     if (e != hipSuccess) return fail(LSQ_E_HIP, "position table upload failed: %s", hipGetErrorString(e));
   }
 
-  g.pinned_ints = (size_t)3 * max_batch * max_len + 3 * (size_t)max_batch + 2;
+  g.pinned_ints = (size_t)3 * max_batch * max_len + 4 * (size_t)max_batch + 2;
   HIPCHK(hipHostMalloc((void**)&g.pinned, g.pinned_ints * 4, hipHostMallocDefault));
 
   g.hp = hp;
@@ -447,15 +453,29 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
   int32_t* h_off = h_sent + Rmax;            // batch + 1
   int32_t* h_len = h_off + g.max_batch + 1;  // batch
   int32_t* h_cap = h_len + g.max_batch;      // batch
+  int32_t* h_order = h_cap + g.max_batch;    // batch
+  // Internal sentence order: by cap, descending (stable).  A sentence is certainly finished once
+  // it has taken cap steps, so the sentences that can still be unfinished at step t are a prefix
+  // whose length alive_at[t] the host knows in advance; every kernel of step t is launched on
+  // that prefix only.  Results are handed back in the caller's order.
+  g.order.resize(batch);
+  for (int b = 0; b < batch; ++b) g.order[b] = b;
+  auto cap_of = [&](int b) { return std::min(src_lens[b] + hp.cap_extra, g.max_len); };
+  std::stable_sort(g.order.begin(), g.order.end(), [&](int a, int b) { return cap_of(a) > cap_of(b); });
+  g.alive_at.assign(g.max_len + 1, 0);
+  for (int b = 0; b < batch; ++b)
+    for (int t = 0; t < cap_of(b); ++t) g.alive_at[t] += 1;
   int r = 0;
-  for (int b = 0; b < batch; ++b) {
-    h_off[b] = r;
-    h_len[b] = src_lens[b];
-    h_cap[b] = std::min(src_lens[b] + hp.cap_extra, g.max_len);
+  for (int i = 0; i < batch; ++i) {
+    const int b = g.order[i];
+    h_off[i] = r;
+    h_len[i] = src_lens[b];
+    h_cap[i] = cap_of(b);
+    h_order[i] = b;
     for (int j = 0; j < src_lens[b]; ++j, ++r) {
       h_ids[r] = src_ids[(size_t)b * src_stride + j];
       h_pos[r] = j;
-      h_sent[r] = b;
+      h_sent[r] = i;
     }
   }
   h_off[batch] = r;
@@ -466,6 +486,7 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
   HIPCHK(hipMemcpyAsync(g.ws + p.src_off, h_off, (size_t)(batch + 1) * 4, hipMemcpyHostToDevice, s));
   HIPCHK(hipMemcpyAsync(g.ws + p.src_len, h_len, (size_t)batch * 4, hipMemcpyHostToDevice, s));
   HIPCHK(hipMemcpyAsync(g.ws + p.cap, h_cap, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.order, h_order, (size_t)batch * 4, hipMemcpyHostToDevice, s));
 
   const int dt = hp.dtype, d = hp.d, F = hp.F, H = hp.H;
   const size_t es = esz();
@@ -503,9 +524,9 @@ int lsq_decode_step(void) { return lsq_decode_steps(1); }
 int lsq_decode_steps(int n) {
   if (g.state < 3) return fail(LSQ_E_STATE, "lsq_encode has not been called");
   if (n < 1) return fail(LSQ_E_ARG, "n must be positive");
-  if (g.done || g.t >= g.max_len) return 0;
+  if (g.done || g.t >= g.max_len || g.alive_at[g.t] == 0) return 0;
   int issued = 0;
-  while (issued < n && g.t < g.max_len) {
+  while (issued < n && g.t < g.max_len && g.alive_at[g.t] > 0) {
     int rc = enqueue_step();
     if (rc) return rc;
     ++issued;
@@ -549,8 +570,8 @@ int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
   const Plan& p = g.plan;
   const int M = g.batch * g.beam, T = g.max_len;
   HIPCHK(launch_finalize(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.out_ids),
-                         at<int32_t>(p.out_lens), at<float>(p.out_scores), g.batch, g.beam, T, g.hp.alpha,
-                         g.hp.pad, g.stream));
+                         at<int32_t>(p.out_lens), at<float>(p.out_scores), at<int32_t>(p.order), g.batch, g.beam,
+                         T, g.hp.alpha, g.hp.pad, g.stream));
   HIPCHK(hipMemcpyAsync(out_ids, g.ws + p.out_ids, (size_t)M * T * 4, hipMemcpyDeviceToHost, g.stream));
   HIPCHK(hipMemcpyAsync(out_lens, g.ws + p.out_lens, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
   HIPCHK(hipMemcpyAsync(out_scores, g.ws + p.out_scores, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
@@ -575,6 +596,7 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
   const char* src = nullptr;
   size_t n = 0;
   bool is_float_data = false;   // stored in the model dtype, delivered as float
+  bool per_source_row = false;  // leading dimension is packed source rows, not batch*beam rows
   switch (what) {
     case LSQ_DBG_LOGITS: src = g.ws + p.d_logits; n = M * hp.V; break;   // always fp32
     case LSQ_DBG_SCORE: src = g.ws + p.score; n = M; break;
@@ -587,11 +609,11 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     case LSQ_DBG_HIDDEN: src = g.ws + p.d_x; n = M * d; is_float_data = true; break;
     case LSQ_DBG_MEMORY:
       if (g.t != 0) return fail(LSQ_E_STATE, "encoder output is overwritten by the first decode step");
-      src = g.ws + p.e_x; n = R * d; is_float_data = true; break;
+      src = g.ws + p.e_x; n = R * d; is_float_data = true; per_source_row = true; break;
     default: {
       int l = what % 100, kind = what - l;
       if (l < 0 || l >= hp.n_dec) return fail(LSQ_E_ARG, "unknown debug item %d", what);
-      if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * n * esz(); }
+      if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * n * esz(); per_source_row = true; }
       else if (kind == LSQ_DBG_CACHE_K) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * n * esz(); }
       else if (kind == LSQ_DBG_CACHE_V) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * n * esz(); }
       else return fail(LSQ_E_ARG, "unknown debug item %d", what);
@@ -599,16 +621,36 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     }
   }
   if (bytes != n * 4) return fail(LSQ_E_ARG, "debug item %d has %zu bytes, caller gave %zu", what, n * 4, bytes);
+  // download in the internal sentence order, widen, then hand back in the caller's order
+  std::vector<float> raw(n);
   if (!is_float_data || hp.dtype == DT_F32) {
-    HIPCHK(hipMemcpyAsync(host_dst, src, n * 4, hipMemcpyDeviceToHost, g.stream));
+    HIPCHK(hipMemcpyAsync(raw.data(), src, n * 4, hipMemcpyDeviceToHost, g.stream));
     HIPCHK(hipStreamSynchronize(g.stream));
-    return LSQ_OK;
+  } else {
+    std::vector<_Float16> tmp(n);
+    HIPCHK(hipMemcpyAsync(tmp.data(), src, n * 2, hipMemcpyDeviceToHost, g.stream));
+    HIPCHK(hipStreamSynchronize(g.stream));
+    for (size_t i = 0; i < n; ++i) raw[i] = (float)tmp[i];
   }
-  std::vector<_Float16> tmp(n);
-  HIPCHK(hipMemcpyAsync(tmp.data(), src, n * 2, hipMemcpyDeviceToHost, g.stream));
-  HIPCHK(hipStreamSynchronize(g.stream));
   float* dst = (float*)host_dst;
-  for (size_t i = 0; i < n; ++i) dst[i] = (float)tmp[i];
+  if (per_source_row) {
+    // packed encoder rows: sentence i (internal) holds rows off_i .. off_i + len_i
+    const size_t width = n / R;
+    std::vector<size_t> start_internal(g.batch + 1, 0), len_by_caller(g.batch, 0), start_caller(g.batch + 1, 0);
+    for (int i = 0; i < g.batch; ++i) {
+      int32_t li = g.pinned[3 * (size_t)g.max_batch * g.max_len + g.max_batch + 1 + i];   // staged lengths
+      start_internal[i + 1] = start_internal[i] + li;
+      len_by_caller[g.order[i]] = li;
+    }
+    for (int b = 0; b < g.batch; ++b) start_caller[b + 1] = start_caller[b] + len_by_caller[b];
+    for (int i = 0; i < g.batch; ++i)
+      memcpy(dst + start_caller[g.order[i]] * width, raw.data() + start_internal[i] * width,
+             (start_internal[i + 1] - start_internal[i]) * width * 4);
+  } else {
+    const size_t per_sentence = n / g.batch;
+    for (int i = 0; i < g.batch; ++i)
+      memcpy(dst + (size_t)g.order[i] * per_sentence, raw.data() + (size_t)i * per_sentence, per_sentence * 4);
+  }
   return LSQ_OK;
 }
 
@@ -674,7 +716,7 @@ int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layer
   KCHK(cache && parent, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(layers >= 0 && batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && npos >= 0 && npos <= T && d % 8 == 0, "shape");
-  KRUN(launch_cache_reorder(dtype, cache, parent, layers, batch, k, T, d, npos, (hipStream_t)stream));
+  KRUN(launch_cache_reorder(dtype, cache, parent, layers, batch, batch * k, k, T, d, npos, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -83,6 +83,8 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
         logp = O.log_softmax(np.asarray(ref_logits, m.ctype))
         for b in range(B):
             base = b * k
+            if old_fin[base:base + k].all():
+                continue                       # nothing left to decide; the state checks below still apply
             # measured deviation of candidate scores
             cdev = 0.0
             for j in range(k):
