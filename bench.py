@@ -32,8 +32,9 @@ PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 
 
 def class_work(name, hp, B, k, t_mean, s_mean):
-    """Algorithmic work of ONE launch of a kernel class: (flops, bytes).  fp16 storage = 2 bytes,
-    fp32 logits = 4 bytes; t_mean = mean number of cached positions over the timed steps."""
+    """Algorithmic work of ONE launch of a kernel class at a step that works on B sentences
+    (B*k rows) with t_mean cached positions: (flops, bytes).  fp16 storage = 2 bytes, fp32
+    logits = 4 bytes; s_mean = mean source length of those sentences."""
     M, d, F, V, L = B * k, hp.d_model, hp.d_ffn, hp.vocab, hp.n_dec
     es = 2 if hp.dtype == 1 else 4
     gemm = lambda n, kk, out_es=es: (2.0 * M * n * kk, (M * kk + n * kk) * es + M * n * out_es)
@@ -124,18 +125,26 @@ def main() -> int:
 
     # instrumented pass: per-kernel-class durations over the same K steps
     dt_prof, prof = run(True)
-    # mean cached positions over the timed steps (step t attends t+1 positions and reorders t+1)
-    t_mean = float(np.mean([t + 1 for t in range(W, W + K)]))
+    # Work per class summed over the timed steps.  Step t works on the sentences whose cap
+    # (source length + cap_extra, at most max_len) exceeds t, attends t+1 cached positions and
+    # reorders t+1 positions.
+    caps = np.minimum(w.src_lens + hp.cap_extra, T)
     s_mean = float(w.src_lens.mean())
     table = {}
     for name, (ms, n) in prof.items():
         if n == 0:
             continue
-        fl, by = class_work(name, hp, B, k, t_mean, s_mean)
+        fl = by = 0.0
+        per_step = n // K
+        for t in range(W, W + K):
+            alive = caps > t
+            f1, b1 = class_work(name, hp, int(alive.sum()), k, t + 1, float(w.src_lens[alive].mean()) if alive.any() else 0.0)
+            fl += f1 * per_step
+            by += b1 * per_step
         us = ms / n * 1e3
-        table[name] = dict(launches=n, total_ms=ms, avg_us=us, flops_per_launch=fl, bytes_per_launch=by,
-                           tflops=fl / (us * 1e-6) / 1e12 if us > 0 else 0.0,
-                           gbs=by / (us * 1e-6) / 1e9 if us > 0 else 0.0)
+        table[name] = dict(launches=n, total_ms=ms, avg_us=us, flops_per_launch=fl / n, bytes_per_launch=by / n,
+                           tflops=fl / (ms * 1e-3) / 1e12 if ms > 0 else 0.0,
+                           gbs=by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0)
     dom = max(table, key=lambda n: table[n]["total_ms"])
     d = table[dom]
     if dom.startswith("gemm"):

@@ -149,11 +149,16 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes);
 int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* C, int M, int N,
                int K, int flags, void* stream);
 
-/* x[r,:] = LayerNorm(x[r,:] + a[r,:]) * gamma + beta, in place on x, biased
- * variance, one launch and no intermediate (sec. 2.1).  a already holds the
- * sublayer bias. */
-int lsq_k_add_layernorm(int dtype, void* x, const void* a, const void* gamma, const void* beta,
-                        int rows, int d, float eps, void* stream);
+/* One residual sublayer tail: x[M,d] <- LayerNorm(x + in[M,K] . W[d,K]^T + bias) * gamma + beta,
+ * in place on x, biased variance.  The projection's fp32 accumulators are not
+ * rounded before the sum.  Two launches: a GEMM that leaves fp32 partial sums in
+ * `scratch` (split over K when the output has too few tiles to fill the chip) and
+ * one LayerNorm launch with no further intermediate (sec. 2.1).  scratch: device,
+ * 16-byte aligned, lsq_k_gemm_add_layernorm_scratch(dtype, M, d, K) bytes. */
+size_t lsq_k_gemm_add_layernorm_scratch(int dtype, int M, int d, int K);
+int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const void* bias, void* x,
+                             const void* gamma, const void* beta, int M, int d, int K, float eps,
+                             void* scratch, void* stream);
 
 /* Decoder self-attention of one new position per row over its cached keys:
  * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions

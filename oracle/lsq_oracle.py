@@ -16,9 +16,11 @@ operation per line, no blocking or fusion; ``@`` (matmul), ``einsum`` and
 
 Precision.  Arithmetic is IEEE fp32 (``ctype``; fp64 can be asked for).  With
 ``storage='blob'`` and an fp16 blob, every tensor the model *stores* between
-operations (embedding sum, each projection after its bias/activation, attention
-context, LayerNorm output, K/V cache entries) is rounded to fp16 and widened
-again, which is what "fp16 weights and activations, fp32 accumulate" means; the
+operations (embedding sum, the Q/K/V and FFN-hidden projections after their
+bias/activation, attention context, LayerNorm output, K/V cache entries) is
+rounded to fp16 and widened again, which is what "fp16 weights and activations,
+fp32 accumulate" means; a sublayer's output projection is not stored: its fp32
+accumulators go straight into the residual sum that LayerNorm consumes; the
 vocabulary logits, softmax statistics, probabilities, log-probabilities and
 hypothesis scores are never rounded below fp32 (a logit rounded to fp16 moves by
 up to 2e-3 near |x| = 2..4, more than the 1e-3 score margin at which token ids
@@ -209,10 +211,10 @@ def encoder_layer(model, L, x):
     d = model.d
     qkv = model.store(x @ L["Wqkv"] + L["bqkv"])
     ctx = model.store(attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], model.H))
-    a = model.store(ctx @ L["Wo"] + L["bo"])
+    a = ctx @ L["Wo"] + L["bo"]
     x = model.store(layer_norm(x + a, L["ln1_g"], L["ln1_b"], model.eps))
     h = model.store(np.maximum(x @ L["W1"] + L["b1"], 0))
-    f = model.store(h @ L["W2"] + L["b2"])
+    f = h @ L["W2"] + L["b2"]
     return model.store(layer_norm(x + f, L["ln2_g"], L["ln2_b"], model.eps))
 
 
@@ -268,17 +270,17 @@ def decoder_logits_cached(model, st, cross):
         ctx = np.empty((M, d), model.ctype)
         for r in range(M):
             ctx[r] = attention(qkv[r:r + 1, :d], st.Kc[l][r, :t + 1], st.Vc[l][r, :t + 1], model.H)[0]
-        a = model.store(model.store(ctx) @ L["Wo"] + L["bo"])
+        a = model.store(ctx) @ L["Wo"] + L["bo"]
         y = model.store(layer_norm(y + a, L["ln1_g"], L["ln1_b"], model.eps))
         q = model.store(y @ L["Wq_c"] + L["bq_c"])
         ctx = np.empty((M, d), model.ctype)
         for b in range(st.B):
             Ke, Ve = cross[b][l]
             ctx[b * k:(b + 1) * k] = attention(q[b * k:(b + 1) * k], Ke, Ve, model.H)
-        a = model.store(model.store(ctx) @ L["Wo_c"] + L["bo_c"])
+        a = model.store(ctx) @ L["Wo_c"] + L["bo_c"]
         y = model.store(layer_norm(y + a, L["ln2_g"], L["ln2_b"], model.eps))
         h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
-        f = model.store(h @ L["W2"] + L["b2"])
+        f = h @ L["W2"] + L["b2"]
         y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
     return y @ model.E.T
 
@@ -294,15 +296,15 @@ def decoder_logits_full(model, prefix, Ke_Ve_per_layer):
     for l, L in enumerate(model.dec):
         qkv = model.store(y @ L["Wqkv"] + L["bqkv"])
         ctx = model.store(attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], model.H, causal))
-        a = model.store(ctx @ L["Wo"] + L["bo"])
+        a = ctx @ L["Wo"] + L["bo"]
         y = model.store(layer_norm(y + a, L["ln1_g"], L["ln1_b"], model.eps))
         q = model.store(y @ L["Wq_c"] + L["bq_c"])
         Ke, Ve = Ke_Ve_per_layer[l]
         ctx = model.store(attention(q, Ke, Ve, model.H))
-        a = model.store(ctx @ L["Wo_c"] + L["bo_c"])
+        a = ctx @ L["Wo_c"] + L["bo_c"]
         y = model.store(layer_norm(y + a, L["ln2_g"], L["ln2_b"], model.eps))
         h = model.store(np.maximum(y @ L["W1"] + L["b1"], 0))
-        f = model.store(h @ L["W2"] + L["b2"])
+        f = h @ L["W2"] + L["b2"]
         y = model.store(layer_norm(y + f, L["ln3_g"], L["ln3_b"], model.eps))
     return y[-1] @ model.E.T
 

@@ -48,7 +48,7 @@ def load_library() -> C.CDLL:
         "lsq_profile_classes": [],
         "lsq_profile_read": [vp, vp, i32],
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
-        "lsq_k_add_layernorm": [i32, vp, vp, vp, vp, i32, i32, f32, vp],
+        "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_row_topk": [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
@@ -59,6 +59,8 @@ def load_library() -> C.CDLL:
         fn = getattr(lib, name)
         fn.argtypes = args
         fn.restype = C.c_int
+    lib.lsq_k_gemm_add_layernorm_scratch.argtypes = [i32, i32, i32, i32]
+    lib.lsq_k_gemm_add_layernorm_scratch.restype = C.c_size_t
     lib.lsq_free.argtypes = []
     lib.lsq_free.restype = None
     lib.lsq_profile_class_name.argtypes = [i32]
@@ -182,9 +184,17 @@ def k_gemm(A, B, bias, C_out, relu: bool = False) -> None:
     _check(load_library().lsq_k_gemm(_dt(A), _p(A), _p(B), _p(bias), _p(C_out), M, N, K, flags, _stream()))
 
 
-def k_add_layernorm(x, a, gamma, beta, eps: float) -> None:
-    rows, d = x.shape
-    _check(load_library().lsq_k_add_layernorm(_dt(x), _p(x), _p(a), _p(gamma), _p(beta), rows, d, eps, _stream()))
+def k_gemm_add_layernorm(inp, W, bias, x, gamma, beta, eps: float) -> None:
+    """x <- LayerNorm(x + inp . W^T + bias) * gamma + beta, in place on x."""
+    import torch
+    M, K = inp.shape
+    d = W.shape[0]
+    assert W.shape[1] == K and tuple(x.shape) == (M, d)
+    lib = load_library()
+    scratch = torch.empty(max(16, lib.lsq_k_gemm_add_layernorm_scratch(_dt(x), M, d, K)), dtype=torch.uint8,
+                          device=x.device)
+    _check(lib.lsq_k_gemm_add_layernorm(_dt(x), _p(inp), _p(W), _p(bias), _p(x), _p(gamma), _p(beta), M, d, K, eps,
+                                        _p(scratch), _stream()))
 
 
 def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:

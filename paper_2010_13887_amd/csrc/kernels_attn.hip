@@ -10,14 +10,18 @@
 
 namespace lsq {
 
+// Keys j0, j0 + jstep, j0 + 2*jstep, ... (< nkeys) are visited, each lane group taking every
+// KPI-th of them.  On return every lane holds, for its 8 elements of the head row, the merged
+// (running max m, running sum l, un-normalised accumulator acc) of all keys this wavefront saw.
 template <typename T, int DH, int NQ>
-__device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __restrict__ K,
-                                       const T* __restrict__ V, long stride, int nkeys, float scale,
-                                       T* const (&op)[NQ], int lane) {
+__device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T* __restrict__ K,
+                                               const T* __restrict__ V, long stride, int nkeys, float scale,
+                                               int j0, int jstep, int lane, float (&m)[NQ], float (&l)[NQ],
+                                               float (&acc)[NQ][8]) {
   constexpr int LPK = DH / 8;
   constexpr int KPI = 64 / LPK;
   const int g = lane / LPK, c = lane % LPK;
-  float q[NQ][8], acc[NQ][8], m[NQ], l[NQ];
+  float q[NQ][8];
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     Vec8<T>::load(qp[n] + c * 8, q[n]);
@@ -26,7 +30,7 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
   }
-  for (int j = g; j < nkeys; j += KPI) {
+  for (int j = j0 + g * jstep; j < nkeys; j += KPI * jstep) {
     float kv[8], vv[8];
     Vec8<T>::load(K + (long)j * stride + c * 8, kv);
     Vec8<T>::load(V + (long)j * stride + c * 8, vv);
@@ -47,7 +51,7 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
       m[n] = mn;
     }
   }
-  // merge the KPI lane groups
+  // merge the KPI lane groups (butterfly: every group ends with the total)
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
 #pragma unroll
@@ -65,12 +69,24 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
       }
       m[n] = mn;
     }
-    if (g == 0) {
+  }
+}
+
+template <typename T, int DH, int NQ>
+__device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __restrict__ K,
+                                       const T* __restrict__ V, long stride, int nkeys, float scale,
+                                       T* const (&op)[NQ], int lane) {
+  constexpr int LPK = DH / 8;
+  float m[NQ], l[NQ], acc[NQ][8];
+  attend_partial<T, DH, NQ>(qp, K, V, stride, nkeys, scale, 0, 1, lane, m, l, acc);
+  if (lane < LPK) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
       float o8[8];
       float inv = 1.0f / l[n];
 #pragma unroll
       for (int i = 0; i < 8; ++i) o8[i] = acc[n][i] * inv;
-      Vec8<T>::store(op[n] + c * 8, o8);
+      Vec8<T>::store(op[n] + lane * 8, o8);
     }
   }
 }
@@ -90,26 +106,48 @@ __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict
   attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63);
 }
 
-// Cross-attention: NQ beams of one sentence share each key/value load.  kv rows are [K | V].
+// Cross-attention: the NQ beams of one sentence share each key/value load.  kv rows are [K | V].
+// One workgroup of 4 wavefronts per (sentence, head): wavefront w takes keys w, w+4, w+8, ...
+// (source sentences have very different lengths and a workgroup's time is set by its key loop,
+// so the loop is cut four ways); the four partial softmax states are merged through LDS.
 template <typename T, int DH, int NQ>
 __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restrict__ q, const T* __restrict__ kv,
                                                               const int32_t* __restrict__ off,
                                                               const int32_t* __restrict__ len,
                                                               T* __restrict__ out, int batch, int beam,
                                                               int first, int H, int d, float scale) {
-  int w = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (w >= batch * H) return;
-  int b = w / H, h = w % H;
+  constexpr int LPK = DH / 8;
+  __shared__ float sm[4][NQ], sl[4][NQ], sacc[4][NQ][DH];
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const T* qp[NQ];
-  T* op[NQ];
 #pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    size_t r = (size_t)b * beam + first + n;
-    qp[n] = q + r * d + h * DH;
-    op[n] = out + r * d + h * DH;
-  }
+  for (int n = 0; n < NQ; ++n) qp[n] = q + ((size_t)b * beam + first + n) * d + h * DH;
   const T* K = kv + (size_t)off[b] * 2 * d + h * DH;
-  attend<T, DH, NQ>(qp, K, K + d, 2 * d, len[b], scale, op, threadIdx.x & 63);
+  float m[NQ], l[NQ], acc[NQ][8];
+  attend_partial<T, DH, NQ>(qp, K, K + d, 2 * d, len[b], scale, wave, 4, lane, m, l, acc);
+  if (lane < LPK) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      if (lane == 0) { sm[wave][n] = m[n]; sl[wave][n] = l[n]; }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sacc[wave][n][lane * 8 + i] = acc[n][i];
+    }
+  }
+  __syncthreads();
+  // thread (n, e) finishes element e of beam n
+  for (int idx = threadIdx.x; idx < NQ * DH; idx += 256) {
+    const int n = idx / DH, e = idx % DH;
+    float mm = fmaxf(fmaxf(sm[0][n], sm[1][n]), fmaxf(sm[2][n], sm[3][n]));
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float c = (sm[w][n] == -INFINITY) ? 0.f : __expf(sm[w][n] - mm);
+      num += sacc[w][n][e] * c;
+      den += sl[w][n] * c;
+    }
+    out[((size_t)b * beam + first + n) * d + h * DH + e] = (T)(num / den);
+  }
 }
 
 // Encoder self-attention over packed sentences: qkv rows are [Q | K | V]; row i belongs to
@@ -165,7 +203,7 @@ static hipError_t cross_nq(const T* q, const T* kv, const int32_t* off, const in
                            int batch, int beam, int first, int H, int d, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
-  dim3 g((batch * H + 3) / 4), b(256);
+  dim3 g(batch * H), b(256);
   LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ><<<g, b, 0, s>>>(q, kv, off, len, out, batch, beam, first, H, d, scale)));
   return hipGetLastError();
 }

@@ -1,5 +1,5 @@
 // Memory-bound fused kernels between the GEMMs (paper sec. 2.1): token embedding + position,
-// and bias-free residual add + LayerNorm in one launch with no intermediate.
+// and split-K reduction + bias + residual add + LayerNorm in one launch with no intermediate.
 #include "lsq_internal.h"
 
 namespace lsq {
@@ -71,28 +71,41 @@ hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const in
 }
 
 // ---------------------------------------------------------------------------------------------
-// x <- store(LayerNorm(x + a) * g + b): one wavefront per row, the row held in registers
-// (NV vectors of 8 per lane), mean then centred variance (biased), both by wave shuffles.
-template <typename T, int NV>
-__global__ void __launch_bounds__(256) add_layernorm_kernel(T* __restrict__ x, const T* __restrict__ a,
-                                                            const T* __restrict__ g, const T* __restrict__ b,
-                                                            int rows, int d, float eps) {
+// Residual + LayerNorm in one launch with no intermediate (paper sec. 2.1): one wavefront per row,
+// the row held in registers (NV vectors of 8 per lane), mean then centred variance (biased), both
+// by wave shuffles.  The sublayer output arrives as `splits` fp32 partial-sum slabs
+// P[s][rows][d] (the split-K GEMM's output, still without its bias):
+//   x <- store(LN(x + (sum_s P[s] + bias)) * g + b).
+// The slabs are added in index order, so the result is independent of how the GEMM was scheduled.
+template <typename T, int NV, int S>
+__global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restrict__ x, const float* __restrict__ P,
+                                                                     const T* __restrict__ bias,
+                                                                     const T* __restrict__ g, const T* __restrict__ b,
+                                                                     int rows, int d, float eps) {
   int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
   int lane = threadIdx.x & 63;
   T* xr = x + (size_t)r * d;
-  const T* ar = a + (size_t)r * d;
+  const size_t slab = (size_t)rows * d;
   float v[NV][8];
   float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     int c = (j * 64 + lane) * 8;
     if (c < d) {
-      float av[8];
-      Vec8<T>::load(xr + c, v[j]);
-      Vec8<T>::load(ar + c, av);
+      float a[8], t[8], part[S][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { v[j][i] += av[i]; sum += v[j][i]; }
+      for (int s = 0; s < S; ++s) Vec8<float>::load(P + s * slab + (size_t)r * d + c, part[s]);   // all in flight
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = part[0][i];
+#pragma unroll
+      for (int s = 1; s < S; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] += part[s][i];
+      Vec8<T>::load(bias + c, t);
+      Vec8<T>::load(xr + c, v[j]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] += a[i] + t[i]; sum += v[j][i]; }
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[j][i] = 0.f;
@@ -124,55 +137,75 @@ __global__ void __launch_bounds__(256) add_layernorm_kernel(T* __restrict__ x, c
   }
 }
 
-// Any d (not a multiple of 8, or longer than the register variant holds): three passes over memory.
 template <typename T>
-__global__ void __launch_bounds__(256) add_layernorm_generic_kernel(T* __restrict__ x, const T* __restrict__ a,
-                                                                    const T* __restrict__ g,
-                                                                    const T* __restrict__ b, int rows, int d,
-                                                                    float eps) {
+__global__ void __launch_bounds__(256) add_layernorm_partials_generic_kernel(T* __restrict__ x,
+                                                                             const float* __restrict__ P, int splits,
+                                                                             const T* __restrict__ bias,
+                                                                             const T* __restrict__ g,
+                                                                             const T* __restrict__ b, int rows, int d,
+                                                                             float eps) {
   int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
   int lane = threadIdx.x & 63;
   T* xr = x + (size_t)r * d;
-  const T* ar = a + (size_t)r * d;
+  const size_t slab = (size_t)rows * d;
+  auto val = [&](int c) {
+    float a = P[(size_t)r * d + c];
+    for (int s = 1; s < splits; ++s) a += P[s * slab + (size_t)r * d + c];
+    return (float)xr[c] + (a + (float)bias[c]);
+  };
   float sum = 0.f;
-  for (int c = lane; c < d; c += 64) sum += (float)xr[c] + (float)ar[c];
+  for (int c = lane; c < d; c += 64) sum += val(c);
   float mean = wave_sum(sum) / (float)d;
   float sq = 0.f;
-  for (int c = lane; c < d; c += 64) {
-    float t = ((float)xr[c] + (float)ar[c]) - mean;
-    sq += t * t;
-  }
+  for (int c = lane; c < d; c += 64) { float t = val(c) - mean; sq += t * t; }
   float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
   for (int c = lane; c < d; c += 64) {
-    float t = ((float)xr[c] + (float)ar[c]) - mean;
+    float t = val(c) - mean;
     xr[c] = (T)((float)g[c] * (t * rstd) + (float)b[c]);
   }
 }
 
-template <typename T>
-static hipError_t add_layernorm_t(T* x, const T* a, const T* g, const T* b, int rows, int d, float eps,
-                                  hipStream_t s) {
+template <typename T, int S>
+static hipError_t add_layernorm_partials_s(T* x, const float* P, const T* bias, const T* g, const T* b, int rows,
+                                           int d, float eps, hipStream_t s) {
   dim3 grid((rows + 3) / 4), blk(256);
-  if ((d & 7) != 0 || d > 4096)
-    add_layernorm_generic_kernel<T><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
-  else if (d <= 512)
-    add_layernorm_kernel<T, 1><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+  if (d <= 512)
+    add_layernorm_partials_kernel<T, 1, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
   else if (d <= 1024)
-    add_layernorm_kernel<T, 2><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 2, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
   else if (d <= 2048)
-    add_layernorm_kernel<T, 4><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 4, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
   else
-    add_layernorm_kernel<T, 8><<<grid, blk, 0, s>>>(x, a, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 8, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
   return hipGetLastError();
 }
 
-hipError_t launch_add_layernorm(int dtype, void* x, const void* a, const void* g, const void* b, int rows,
-                                int d, float eps, hipStream_t s) {
+template <typename T>
+static hipError_t add_layernorm_partials_t(T* x, const float* P, int splits, const T* bias, const T* g, const T* b,
+                                           int rows, int d, float eps, hipStream_t s) {
+  if ((d & 7) != 0 || d > 4096 || (splits != 1 && splits != 2 && splits != 4 && splits != 8)) {
+    dim3 grid((rows + 3) / 4), blk(256);
+    add_layernorm_partials_generic_kernel<T><<<grid, blk, 0, s>>>(x, P, splits, bias, g, b, rows, d, eps);
+    return hipGetLastError();
+  }
+  switch (splits) {
+    case 1: return add_layernorm_partials_s<T, 1>(x, P, bias, g, b, rows, d, eps, s);
+    case 2: return add_layernorm_partials_s<T, 2>(x, P, bias, g, b, rows, d, eps, s);
+    case 4: return add_layernorm_partials_s<T, 4>(x, P, bias, g, b, rows, d, eps, s);
+    default: return add_layernorm_partials_s<T, 8>(x, P, bias, g, b, rows, d, eps, s);
+  }
+}
+
+hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int splits, const void* bias,
+                                         const void* g, const void* b, int rows, int d, float eps, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  if (splits < 1) return hipErrorInvalidValue;
   if (dtype == DT_F16)
-    return add_layernorm_t<half_t>((half_t*)x, (const half_t*)a, (const half_t*)g, (const half_t*)b, rows, d, eps, s);
-  return add_layernorm_t<float>((float*)x, (const float*)a, (const float*)g, (const float*)b, rows, d, eps, s);
+    return add_layernorm_partials_t<half_t>((half_t*)x, P, splits, (const half_t*)bias, (const half_t*)g,
+                                            (const half_t*)b, rows, d, eps, s);
+  return add_layernorm_partials_t<float>((float*)x, P, splits, (const float*)bias, (const float*)g,
+                                         (const float*)b, rows, d, eps, s);
 }
 
 }  // namespace lsq

@@ -3,6 +3,7 @@
 // fp16: MFMA v_mfma_f32_32x32x16_f16 on LDS-staged tiles.  fp32: a plain LDS-tiled FMA kernel
 // (only the small fp32 configuration uses it).  Bias, ReLU and the output scatter (Q to the
 // activation buffer, K and V straight into the caches) are fused into the epilogue.
+#include <cstdlib>
 #include "lsq_internal.h"
 
 namespace lsq {
@@ -77,7 +78,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so the id is remapped
 // to give every XCD a contiguous run of tiles, m fastest: the tiles that share a weight tile then
 // share an L2.
-template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, typename OutT>
+template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
                                                        const half_t* __restrict__ bias, GemmOut out, int M,
                                                        int N, int K, int relu, int vec_ok) {
@@ -149,51 +150,91 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int n = min(n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4 + e, N - 1);
-        bv[j][vg][e] = bias ? (float)bias[n] : 0.f;
+        bv[j][vg][e] = (!SPLIT && bias) ? (float)bias[n] : 0.f;
       }
 
-  const int nk = (K + BK - 1) / BK;
-  static_assert(D % 2 == 0, "stage s always uses LDS buffer s & 1");
+  // Split-K: gridDim.y workgroups share an output tile; each multiplies an equal share of the
+  // k-tiles and writes its fp32 partial sums (no bias) to its own [M,N] slab; the consumer adds
+  // the slabs in a fixed order, so the result does not depend on scheduling.
+  const int nk_all = (K + BK - 1) / BK;
+  const int nk = SPLIT ? nk_all / (int)gridDim.y : nk_all;
+  if constexpr (SPLIT) {
+    A += (size_t)blockIdx.y * nk * BK;
+    B += (size_t)blockIdx.y * nk * BK;
+  }
+  static_assert(D % 2 == 0, "tile kt always uses LDS buffer kt & 1 = stage & 1");
+  constexpr int KS = BK / 16;                        // MFMA k-steps per tile
+  constexpr bool kSingle = (TM * TN == 1);           // one output block per wave: use two accumulators
+  floatx16 acc2;                                     // so consecutive MFMAs do not wait on each other
+  if constexpr (kSingle)
 #pragma unroll
-  for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
+    for (int e = 0; e < 16; ++e) acc2[e] = 0.f;
   const int fr = lane & 31, fk = (lane >> 5) * 8;
   auto compute = [&](int buf) {
+    if constexpr (kSingle) {
+      half8_t af[KS], bf[KS];
 #pragma unroll
-    for (int ks = 0; ks < BK; ks += 16) {
-      half8_t af[TM], bf[TN];
+      for (int i = 0; i < KS; ++i) {
+        af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + fr) * LDK + i * 16 + fk]);
+        bf[i] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + fr) * LDK + i * 16 + fk]);
+      }
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + ks + fk]);
+      for (int i = 0; i < KS; ++i) {
+        if (i & 1) acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[i], af[i], acc2, 0, 0, 0);
+        else acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[i], af[i], acc[0][0], 0, 0, 0);
+      }
+    } else {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bf[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + ks + fk]);
+      for (int ks = 0; ks < BK; ks += 16) {
+        half8_t af[TM], bf[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
+          af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + ks + fk]);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+          bf[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + ks + fk]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+      }
     }
   };
+  // Register slot s holds tile s (mod D).  Per iteration: the NEXT tile goes from its slot to the
+  // other LDS buffer and the slot is refilled D tiles ahead, then the current tile is multiplied,
+  // then one barrier: it orders this iteration's LDS writes before the next iteration's reads and
+  // this iteration's reads before the writes of the iteration after.
+#pragma unroll
+  for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
+  sstore(ra[0], rb[0], 0, 0);
+  gload(ra[0], rb[0], min(D, nk - 1) * BK);
+  __syncthreads();
   int it = 0;
-  for (; it + D <= nk; it += D) {
+  for (; it + D < nk; it += D) {
 #pragma unroll
     for (int s = 0; s < D; ++s) {
       const int kt = it + s;
-      sstore(ra[s], rb[s], s & 1, kt * BK);
-      gload(ra[s], rb[s], min(kt + D, nk - 1) * BK);   // beyond the end: a redundant load, never used
-      __syncthreads();
+      const int sn = (s + 1) % D;
+      sstore(ra[sn], rb[sn], (s + 1) & 1, (kt + 1) * BK);
+      gload(ra[sn], rb[sn], min(kt + 1 + D, nk - 1) * BK);   // past the end: a redundant load, never used
       compute(s & 1);
+      __syncthreads();
     }
   }
 #pragma unroll
-  for (int s = 0; s < D; ++s) {   // the last nk % D tiles are already in registers
+  for (int s = 0; s < D; ++s) {   // the last 1..D tiles: already in registers or in LDS
     const int kt = it + s;
     if (kt < nk) {
-      sstore(ra[s], rb[s], s & 1, kt * BK);
-      __syncthreads();
+      const int sn = (s + 1) % D;
+      if (kt + 1 < nk) sstore(ra[sn], rb[sn], (s + 1) & 1, (kt + 1) * BK);
       compute(s & 1);
+      __syncthreads();
     }
   }
+  if constexpr (kSingle)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[0][0][e] += acc2[e];
 
   // epilogue: lane owns m = .. + (lane & 31) and, per group vg, n = .. + vg*8 + (lane>>5)*4 + 0..3
 #pragma unroll
@@ -212,7 +253,17 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
           v[e] = acc[i][j][vg * 4 + e] + bv[j][vg][e];
           if (relu) v[e] = fmaxf(v[e], 0.f);
         }
-        if (vec_ok && n + 3 < N) {
+        if constexpr (SPLIT) {
+          float* dst = reinterpret_cast<float*>(out.ptr[0]) + ((size_t)blockIdx.y * M + m) * N + n;
+          if (vec_ok && n + 3 < N) {
+            floatx4 f = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<floatx4*>(dst) = f;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) dst[e] = v[e];
+          }
+        } else if (vec_ok && n + 3 < N) {
           int s = n / out.seg_n;
           OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + (n - s * out.seg_n);
           if constexpr (sizeof(OutT) == 2) {
@@ -238,12 +289,40 @@ static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const 
   dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM)), blk(256);
   const bool tail = (K % BK) != 0;
   if (out.f32_out) {
-    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
-    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
   } else {
-    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
-    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
   }
+}
+
+// How many ways the k-range of an [M,N,K] product is split when its consumer can add partial
+// sums (the residual + LayerNorm kernel).  More slabs put more workgroups (and more wavefronts per
+// CU) on a product whose output has too few tiles to fill 256 CUs.
+int gemm_partial_splits(int dtype, int M, int N, int K) {
+  if (dtype != DT_F16 || K % 64 != 0) return 1;
+  const int nk = K / 64;
+  const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+  int S = 1;
+  while (S < 8 && nk % (S * 2) == 0 && nk / (S * 2) >= 2 && tiles * S * 2 <= 1024) S *= 2;
+  return S;
+}
+
+// P[s][M][N] (fp32) = A[:, k-share s] . B[:, k-share s]^T for s < splits; no bias, no activation.
+hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* P, int M, int N, int K,
+                                int splits, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (K <= 0 || splits < 1) return hipErrorInvalidValue;
+  GemmOut out = plain_out(P, N);
+  out.f32_out = 1;
+  if (dtype == DT_F32 || splits == 1) return launch_gemm(dtype, A, B, nullptr, out, M, N, K, false, s);
+  if (K % (64 * splits) != 0) return hipErrorInvalidValue;
+  const int vec_ok = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(P) & 15) == 0;
+  dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
+  gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, 0, s>>>(
+      (const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
@@ -266,6 +345,11 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  static int force = getenv("LSQ_TILE") ? atoi(getenv("LSQ_TILE")) : 0;   // TEMP experiment switch
+  if (force == 128) { run_f16<128, 128, 32, 64, 64, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
+  if (force == 64) { run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
+  if (force == 12864) { run_f16<128, 64, 64, 64, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
+  if (force == 1281284) { run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
   if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else if (tiles128 >= 256)

@@ -2,8 +2,10 @@
 //
 //  row_topk   -- "retrieve", made exact: one workgroup reads one row of logits ONCE into
 //                registers, computes the full-vocabulary max and sum-of-exponentials, forms
-//                cand = score + ((x - max) - log sum) for every token and keeps the row's k best
-//                by (cand descending, token ascending).  Nothing but k pairs per row is written.
+//                cand = score + ((x - max) - log sum) for every token, picks a rough top-k
+//                threshold from group maxima (the paper's idea, with the lanes as the groups),
+//                collects the tokens at or above it in LDS and ranks those exactly by
+//                (cand descending, token ascending).  Nothing but k pairs per row is written.
 //  beam_refine-- "re-rank": per sentence the k best of the k*k survivors by (cand descending,
 //                beam*V + token ascending), then the hypothesis bookkeeping.
 //  cache_reorder -- gathers K/V cache rows by parent beam, in place.
@@ -99,7 +101,67 @@ __global__ void __launch_bounds__(BLOCK) row_topk_kernel(const T* __restrict__ l
 #pragma unroll
   for (int i = 0; i < NV * 8; ++i) x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
 
-  // k rounds: best candidate that comes strictly after the previous winner in the total order
+  // ---- rough stage: a threshold R with at least k tokens at or above it -----------------------
+  // Every lane's best score is the score of a distinct token.  Each wavefront lists its k largest
+  // lane maxima (shuffles only); R = the k-th largest of all listed values is reached by k distinct
+  // tokens, so every token of the row's top k satisfies score >= R (ties at R included).  Tokens
+  // at or above R go to a short list in LDS -- typically k to a dozen -- which is then ranked
+  // exactly.  Rows where the list overflows (e.g. thousands of equal logits) take the exact
+  // k-round arg-max below instead.
+  constexpr int NW = BLOCK / 64, CAP = 256;
+  __shared__ float wtop[NW * LSQ_MAX_BEAM_];
+  __shared__ float cand_s[CAP];
+  __shared__ int cand_i[CAP];
+  __shared__ int cand_n;
+  const int lane = tid & 63, wave = tid >> 6;
+  float cur = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) cur = fmaxf(cur, x[i]);   // padding slots hold -inf
+  for (int round = 0; round < k; ++round) {
+    const float mx = wave_max(cur);
+    const unsigned long long hit = __ballot(cur == mx);
+    if (lane == 0) wtop[wave * k + round] = mx;
+    if (lane == __ffsll((long long)hit) - 1) cur = -INFINITY;
+  }
+  if (tid == 0) cand_n = 0;
+  __syncthreads();
+  float v0 = lane < NW * k ? wtop[lane] : -INFINITY;
+  float v1 = lane + 64 < NW * k ? wtop[lane + 64] : -INFINITY;
+  float R = -INFINITY;
+  for (int round = 0; round < k; ++round) {
+    R = wave_max(fmaxf(v0, v1));
+    const unsigned long long hit = __ballot(fmaxf(v0, v1) == R);
+    if (lane == __ffsll((long long)hit) - 1) { if (v0 == R) v0 = -INFINITY; else v1 = -INFINITY; }
+  }
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int v = vec ? (j * BLOCK + tid) * 8 + e : (j * 8 + e) * BLOCK + tid;
+      const float sc = x[j * 8 + e];
+      if (v < V && sc >= R) {
+        const int slot = atomicAdd(&cand_n, 1);
+        if (slot < CAP) { cand_s[slot] = sc; cand_i[slot] = v; }
+      }
+    }
+  __syncthreads();
+  const int n = cand_n;
+  if (n <= CAP) {
+    // ---- exact ranking of the short list (first wavefront) -----------------------------------
+    if (wave == 0) {
+      for (int c = lane; c < n; c += 64) {
+        const float sc = cand_s[c];
+        const int v = cand_i[c];
+        int rank = 0;
+        for (int o = 0; o < n; ++o) rank += precedes(cand_s[o], cand_i[o], sc, v) ? 1 : 0;
+        if (rank < k) { os[rank] = sc; oi[rank] = v; }
+      }
+      if (lane >= n && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
+    }
+    return;
+  }
+
+  // ---- exact fallback: k rounds, each the best token strictly after the previous winner ----------
   float ps = INFINITY;
   int pi = -1;
   for (int round = 0; round < k; ++round) {

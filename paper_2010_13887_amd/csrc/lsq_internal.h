@@ -39,12 +39,17 @@ inline GemmOut plain_out(void* c, int N) {
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out,
                        int M, int N, int K, bool relu, hipStream_t s);
 
+int gemm_partial_splits(int dtype, int M, int N, int K);
+hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* P, int M, int N, int K,
+                                int splits, hipStream_t s);
+
 hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
                              const int32_t* pos, void* x, int rows, int d, hipStream_t s);
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
                              const int32_t* len, void* x, int rows, int d, int T, int t, hipStream_t s);
-hipError_t launch_add_layernorm(int dtype, void* x, const void* a, const void* g, const void* b,
-                                int rows, int d, float eps, hipStream_t s);
+hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int splits, const void* bias,
+                                         const void* g, const void* b, int rows, int d, float eps,
+                                         hipStream_t s);
 
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
                                  int rows, int H, int d, int T, int nkeys, hipStream_t s);

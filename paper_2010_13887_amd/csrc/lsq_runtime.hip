@@ -51,7 +51,7 @@ struct Prof {
 } g_prof;
 
 hipError_t prof_mark(hipStream_t s, int c, bool start) {
-  if (!g_prof.on) return hipSuccess;
+  if (!g_prof.on || c < 0) return hipSuccess;
   if (start) {
     if (g_prof.used * 2 >= g_prof.pool.size()) {
       hipEvent_t a, b;
@@ -79,6 +79,7 @@ hipError_t prof_mark(hipStream_t s, int c, bool start) {
   } while (0)
 
 constexpr size_t kAlign = 256;
+constexpr size_t kMaxSplits = 8;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct HParams {
@@ -185,12 +186,12 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   auto etake = [&](size_t bytes) { size_t o = e; e += up(bytes); return o; };
   p.e_ids = etake(R * 4); p.e_pos = etake(R * 4); p.e_sent = etake(R * 4);
   p.e_x = etake(R * d * esz); p.e_qkv = etake(R * 3 * d * esz); p.e_ctx = etake(R * d * esz);
-  p.e_tmp = etake(R * d * esz); p.e_ffn = etake(R * F * esz);
+  p.e_tmp = etake(R * d * 4); p.e_ffn = etake(R * F * esz);   // e_tmp: one fp32 slab (no split-K at encoder sizes)
   // decoder phase
   size_t q = p.scratch;
   auto dtake = [&](size_t bytes) { size_t o = q; q += up(bytes); return o; };
   p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
-  p.d_tmp = dtake(M * d * esz);
+  p.d_tmp = dtake(kMaxSplits * M * d * 4);   // fp32 partial-sum slabs of the split-K GEMMs
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
@@ -257,6 +258,17 @@ int check_limits(int max_batch, int beam, int max_len, const HParams& hp) {
   return LSQ_OK;
 }
 
+// x <- LN(x + in . W^T + bias): the GEMM leaves fp32 partial sums (split over k when the output has
+// too few tiles to fill the chip), the LayerNorm kernel adds them, the bias and the residual.
+int sublayer(int cls, const void* in, const void* W, const void* bias, const void* g_, const void* b_, void* x,
+             float* partials, int M, int d, int K, int max_splits, hipStream_t s) {
+  const HParams& hp = g.hp;
+  int S = std::min(gemm_partial_splits(hp.dtype, M, d, K), max_splits);
+  TIMED(cls, launch_gemm_partials(hp.dtype, in, W, partials, M, d, K, S, s));
+  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(hp.dtype, x, partials, S, bias, g_, b_, M, d, hp.eps, s));
+  return LSQ_OK;
+}
+
 int enqueue_step() {
   const HParams& hp = g.hp;
   const Plan& p = g.plan;
@@ -282,16 +294,13 @@ int enqueue_step() {
     o.f32_out = 0;
     TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, t + 1, s));
-    TIMED(PC_GEMM_DD, launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), M, d, d, false, s));
-    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, M, d, hp.eps, s));
+    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                   at<int32_t>(p.src_len), ctx, B, k, H, d, s));
-    TIMED(PC_GEMM_DD, launch_gemm(dt, ctx, L.Woc, L.boc, plain_out(tmp, d), M, d, d, false, s));
-    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, M, d, hp.eps, s));
+    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
-    TIMED(PC_GEMM_FFN2, launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), M, d, F, false, s));
-    TIMED(PC_LAYERNORM, launch_add_layernorm(dt, x, tmp, L.ln3g, L.ln3b, M, d, hp.eps, s));
+    if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, x, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
@@ -499,11 +508,9 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
   for (const EncLayer& L : g.enc) {
     HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, plain_out(qkv, 3 * d), (int)R, 3 * d, d, false, s));
     HIPCHK(launch_encoder_attention(dt, qkv, sent, off, len, ctx, (int)R, H, d, s));
-    HIPCHK(launch_gemm(dt, ctx, L.Wo, L.bo, plain_out(tmp, d), (int)R, d, d, false, s));
-    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln1g, L.ln1b, (int)R, d, hp.eps, s));
+    if (int rc = sublayer(-1, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, (int)R, d, d, 1, s)) return rc;
     HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), (int)R, F, d, true, s));
-    HIPCHK(launch_gemm(dt, ffn, L.W2, L.b2, plain_out(tmp, d), (int)R, d, F, false, s));
-    HIPCHK(launch_add_layernorm(dt, x, tmp, L.ln2g, L.ln2b, (int)R, d, hp.eps, s));
+    if (int rc = sublayer(-1, ffn, L.W2, L.b2, L.ln2g, L.ln2b, x, (float*)tmp, (int)R, d, F, 1, s)) return rc;
   }
   const size_t cross_l = (size_t)R * 2 * d * es;
   for (int l = 0; l < hp.n_dec; ++l)
@@ -669,12 +676,24 @@ int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* 
   KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) != 0, (hipStream_t)stream));
 }
 
-int lsq_k_add_layernorm(int dtype, void* x, const void* a, const void* gamma, const void* beta, int rows, int d,
-                        float eps, void* stream) {
-  KCHK(x && a && gamma && beta, "null pointer");
+size_t lsq_k_gemm_add_layernorm_scratch(int dtype, int M, int d, int K) {
+  return (size_t)std::max(1, gemm_partial_splits(dtype, M, d, K)) * (size_t)M * d * 4;
+}
+
+int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const void* bias, void* x, const void* gamma,
+                             const void* beta, int M, int d, int K, float eps, void* scratch, void* stream) {
+  KCHK(in && W && bias && x && gamma && beta && scratch, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
-  KCHK(rows >= 0 && d >= 1, "shape");
-  KRUN(launch_add_layernorm(dtype, x, a, gamma, beta, rows, d, eps, (hipStream_t)stream));
+  KCHK(M >= 0 && d >= 1 && K >= 1, "shape");
+  KCHK(dtype == DT_F32 || K % 8 == 0, "K must be a multiple of 8 for float16");
+  KCHK((reinterpret_cast<uintptr_t>(scratch) & 15) == 0, "scratch must be 16-byte aligned");
+  const int S = gemm_partial_splits(dtype, M, d, K);
+  hipError_t e = launch_gemm_partials(dtype, in, W, (float*)scratch, M, d, K, S, (hipStream_t)stream);
+  if (e == hipSuccess)
+    e = launch_add_layernorm_partials(dtype, x, (const float*)scratch, S, bias, gamma, beta, M, d, eps,
+                                      (hipStream_t)stream);
+  if (e != hipSuccess) return fail(LSQ_E_HIP, "%s", hipGetErrorString(e));
+  return LSQ_OK;
 }
 
 int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out, int rows, int heads,

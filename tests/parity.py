@@ -73,8 +73,6 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
         tok, par, sc, margin = O.beam_select(m, st, ref_logits)
         if wide_in_sync:
             tw, pw, sw, _ = O.beam_select(mw, st_w, wl)
-            O.beam_advance(mw, st_w, tw, pw, sw)
-            wide_in_sync = bool(np.array_equal(tw, tok) and np.array_equal(pw, par))
         g_tokens = eng.debug(lsq.DBG.TOKENS, (M, T + 1), np.int32)
         g_len = eng.debug(lsq.DBG.LEN, (M,), np.int32)
         g_fin = eng.debug(lsq.DBG.FINISHED, (M,), np.int32)
@@ -144,6 +142,9 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
                 par[b], tok[b] = gp, gt
                 sc[b] = np.array([ref_score(j, v) for j, v in kept], m.ctype)
         active_ref = O.beam_advance(m, st, tok, par, sc)
+        if wide_in_sync:     # the unrounded oracle is followed only while it decides as the library did
+            O.beam_advance(mw, st_w, tw, pw, sw)
+            wide_in_sync = bool(np.array_equal(tw, tok) and np.array_equal(pw, par))
         assert np.array_equal(g_len, st.len), f"step {steps}: lengths"
         assert np.array_equal(g_fin != 0, st.finished), f"step {steps}: finished flags"
         for r in range(M):

@@ -67,24 +67,29 @@ def test_gemm_fp32(env, M, N, K):
     np.testing.assert_allclose(C.cpu().numpy(), ref, rtol=1e-5, atol=1e-5)
 
 
-@pytest.mark.parametrize("rows,d", [(1, 64), (5, 512), (513, 1024), (37, 2048), (3, 4096), (9, 72), (4, 100)])
+@pytest.mark.parametrize("rows,d,K", [(1, 64, 64), (5, 512, 2048), (513, 1024, 1024), (512, 1024, 4096),
+                                      (37, 2048, 264), (64, 1024, 4096), (9, 72, 40), (4, 100, 16), (3, 4104, 128)])
 @pytest.mark.parametrize("half", [False, True])
-def test_add_layernorm(env, rows, d, half):
+def test_gemm_add_layernorm(env, rows, d, K, half):
+    """x <- LN(x + in . W^T + bias): split-K partial sums, bias, residual and LayerNorm."""
     lsq, torch = env
-    rng = np.random.default_rng(rows + d)
+    rng = np.random.default_rng(rows + d + K)
     cast = _h if half else (lambda a: np.asarray(a, np.float32))
-    x, a = cast(rng.standard_normal((rows, d)) * 2), cast(rng.standard_normal((rows, d)) + 0.3)
+    x, inp = cast(rng.standard_normal((rows, d)) * 2), cast(rng.standard_normal((rows, K)))
+    W, bias = cast(rng.standard_normal((d, K)) * 0.05), cast(rng.standard_normal(d) * 0.3)
     g, b = cast(1 + 0.3 * rng.standard_normal(d)), cast(0.3 * rng.standard_normal(d))
+    a = inp.astype(np.float64) @ W.astype(np.float64).T + bias
     ref = O.layer_norm(x.astype(np.float64) + a, g.astype(np.float64), b.astype(np.float64), 1e-5)
     td = torch.float16 if half else torch.float32
     dx = _dev(torch, x, td)
-    lsq.k_add_layernorm(dx, _dev(torch, a, td), _dev(torch, g, td), _dev(torch, b, td), 1e-5)
+    lsq.k_gemm_add_layernorm(_dev(torch, inp, td), _dev(torch, W, td), _dev(torch, bias, td), dx, _dev(torch, g, td),
+                             _dev(torch, b, td), 1e-5)
     got = dx.float().cpu().numpy()
     if half:
         np.testing.assert_allclose(got, ref, rtol=1.1e-3, atol=1e-3)
         assert np.abs(got - _h(ref)).max() <= 4e-3 and (got != _h(ref)).mean() < 0.02
     else:
-        np.testing.assert_allclose(got, ref, rtol=2e-5, atol=2e-5)
+        np.testing.assert_allclose(got, ref, rtol=3e-5, atol=3e-5)
 
 
 @pytest.mark.parametrize("rows,H,dh,T,nkeys", [(3, 4, 16, 8, 1), (9, 4, 16, 8, 8), (32, 8, 64, 110, 77),
