@@ -3,7 +3,6 @@
 // fp16: MFMA v_mfma_f32_32x32x16_f16 on LDS-staged tiles.  fp32: a plain LDS-tiled FMA kernel
 // (only the small fp32 configuration uses it).  Bias, ReLU and the output scatter (Q to the
 // activation buffer, K and V straight into the caches) are fused into the epilogue.
-#include <cstdlib>
 #include "lsq_internal.h"
 
 namespace lsq {
@@ -12,6 +11,38 @@ template <typename T>
 __device__ __forceinline__ void store_one(const GemmOut& o, int m, int n, float v) {
   int s = n / o.seg_n;
   reinterpret_cast<T*>(o.ptr[s])[(long)m * o.ld[s] + (n - s * o.seg_n)] = (T)v;
+}
+
+// Stores four consecutive outputs (m, n..n+3) of a tile: split-K slab, vector, or element-wise
+// fallback for ragged / unaligned rows.
+template <typename OutT, bool SPLIT>
+__device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const float (&v)[4], int M, int N,
+                                       int vec_ok, int slab) {
+  if constexpr (SPLIT) {
+    float* dst = reinterpret_cast<float*>(out.ptr[0]) + ((size_t)slab * M + m) * N + n;
+    if (vec_ok && n + 3 < N) {
+      floatx4 f = {v[0], v[1], v[2], v[3]};
+      *reinterpret_cast<floatx4*>(dst) = f;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < N) dst[e] = v[e];
+    }
+  } else if (vec_ok && n + 3 < N) {
+    int s = n / out.seg_n;
+    OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + (n - s * out.seg_n);
+    if constexpr (sizeof(OutT) == 2) {
+      half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
+      *reinterpret_cast<half4_t*>(dst) = h;
+    } else {
+      floatx4 f = {v[0], v[1], v[2], v[3]};
+      *reinterpret_cast<floatx4*>(dst) = f;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (n + e < N) store_one<OutT>(out, m, n + e, v[e]);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -253,34 +284,98 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
           v[e] = acc[i][j][vg * 4 + e] + bv[j][vg][e];
           if (relu) v[e] = fmaxf(v[e], 0.f);
         }
-        if constexpr (SPLIT) {
-          float* dst = reinterpret_cast<float*>(out.ptr[0]) + ((size_t)blockIdx.y * M + m) * N + n;
-          if (vec_ok && n + 3 < N) {
-            floatx4 f = {v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<floatx4*>(dst) = f;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (n + e < N) dst[e] = v[e];
-          }
-        } else if (vec_ok && n + 3 < N) {
-          int s = n / out.seg_n;
-          OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + (n - s * out.seg_n);
-          if constexpr (sizeof(OutT) == 2) {
-            half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
-            *reinterpret_cast<half4_t*>(dst) = h;
-          } else {
-            floatx4 f = {v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<floatx4*>(dst) = f;
-          }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < N) store_one<OutT>(out, m, n + e, v[e]);
-        }
+        store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y);
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Skinny fp16 GEMM for M <= 32*TM rows (few hypotheses alive, or small batches): the product is
+// a stream of weights, so the job is to keep many weight bytes in flight from many CUs.
+// A workgroup owns 32 output columns and all rows; its four wavefronts take every fourth 16-wide
+// k-step, load their MFMA fragments straight from global memory (16 bytes per lane, no LDS and no
+// barrier in the loop, U k-steps in flight per wavefront), and their four partial tiles are added
+// through LDS at the end.  gridDim.y > 1 additionally splits K across workgroups (SPLIT, fp32
+// slabs for the LayerNorm consumer).
+template <int TM, bool SPLIT, typename OutT>
+__global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
+                                                              const half_t* __restrict__ B,
+                                                              const half_t* __restrict__ bias, GemmOut out, int M,
+                                                              int N, int K, int relu, int vec_ok) {
+  constexpr int U = 4;
+  __shared__ float red[4][TM][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * 32;
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int ksteps_all = K / 16;                      // K % 16 == 0 is checked by the launcher
+  const int ksteps = SPLIT ? ksteps_all / (int)gridDim.y : ksteps_all;
+  const int ks0 = SPLIT ? (int)blockIdx.y * ksteps : 0;
+  const half_t* bp = B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  const half_t* ap[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) ap[i] = A + (size_t)min(i * 32 + fr, M - 1) * K + fk;
+  floatx16 acc[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  int ks = ks0 + wave;
+  const int ks_end = ks0 + ksteps;
+  for (; ks + 4 * (U - 1) < ks_end; ks += 4 * U) {
+    half8_t bf[U], af[U][TM];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)(ks + 4 * u) * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[u][i] = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)(ks + 4 * u) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af[u][i], acc[i], 0, 0, 0);
+  }
+  for (; ks < ks_end; ks += 4) {
+    half8_t bf = *reinterpret_cast<const half8_t*>(bp + (size_t)ks * 16);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      half8_t af = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)ks * 16);
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, af, acc[i], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) red[wave][i][e][lane] = acc[i][e];
+  __syncthreads();
+  // thread (vg = wave, lane) finishes the four outputs m = i*32 + (lane & 31), n = n0 + vg*8 + (lane>>5)*4 + 0..3
+  const int vg = wave;
+  const int n = n0 + vg * 8 + (lane >> 5) * 4;
+  if (n >= N) return;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = i * 32 + (lane & 31);
+    if (m >= M) continue;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = vg * 4 + e;
+      v[e] = (red[0][i][r][lane] + red[1][i][r][lane]) + (red[2][i][r][lane] + red[3][i][r][lane]);
+      if (!SPLIT && bias) v[e] += (float)bias[min(n + e, N - 1)];
+      if (relu) v[e] = fmaxf(v[e], 0.f);
+    }
+    store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y);
+  }
+}
+
+template <int TM>
+static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
+                       int K, int relu, int vec_ok, hipStream_t s) {
+  dim3 grid((N + 31) / 32), blk(256);
+  if (out.f32_out)
+    gemm_f16_skinny_kernel<TM, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  else
+    gemm_f16_skinny_kernel<TM, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int D>
@@ -303,7 +398,7 @@ static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const 
 int gemm_partial_splits(int dtype, int M, int N, int K) {
   if (dtype != DT_F16 || K % 64 != 0) return 1;
   const int nk = K / 64;
-  const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+  const long tiles = M <= 128 ? (N + 31) / 32 : (long)((M + 63) / 64) * ((N + 63) / 64);
   int S = 1;
   while (S < 8 && nk % (S * 2) == 0 && nk / (S * 2) >= 2 && tiles * S * 2 <= 1024) S *= 2;
   return S;
@@ -319,6 +414,16 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   if (dtype == DT_F32 || splits == 1) return launch_gemm(dtype, A, B, nullptr, out, M, N, K, false, s);
   if (K % (64 * splits) != 0) return hipErrorInvalidValue;
   const int vec_ok = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(P) & 15) == 0;
+  if (M <= 128) {
+    dim3 grid((N + 31) / 32, splits), blk(256);
+    const half_t* a = (const half_t*)A;
+    const half_t* b = (const half_t*)B;
+    if (M <= 32) gemm_f16_skinny_kernel<1, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    else if (M <= 64) gemm_f16_skinny_kernel<2, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    else if (M <= 96) gemm_f16_skinny_kernel<3, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    else gemm_f16_skinny_kernel<4, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    return hipGetLastError();
+  }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
   gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, 0, s>>>(
       (const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok);
@@ -345,12 +450,12 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  static int force = getenv("LSQ_TILE") ? atoi(getenv("LSQ_TILE")) : 0;   // TEMP experiment switch
-  if (force == 128) { run_f16<128, 128, 32, 64, 64, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
-  if (force == 64) { run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
-  if (force == 12864) { run_f16<128, 64, 64, 64, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
-  if (force == 1281284) { run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, relu, vec_ok, s); return hipGetLastError(); }
-  if (M <= 32)
+  if (M <= 128 && K % 16 == 0) {
+    if (M <= 32) run_skinny<1>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    else if (M <= 64) run_skinny<2>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    else if (M <= 96) run_skinny<3>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    else run_skinny<4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+  } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else if (tiles128 >= 256)
     run_f16<128, 128, 32, 64, 64, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
