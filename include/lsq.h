@@ -97,6 +97,12 @@ void lsq_free(void);
 
 const char* lsq_last_error(void);
 
+/* Decode steps are replayed from hipGraphs captured on first use, one per number
+ * of sentences still alive, when the stream given to lsq_set_workspace is not
+ * the default stream (stream capture needs a capturable stream).  on = 0 issues
+ * the same kernels one by one instead; results are identical.  Default: on. */
+int lsq_set_graphs(int on);
+
 /* Number of decode steps taken since the last lsq_encode. */
 int lsq_step_index(void);
 

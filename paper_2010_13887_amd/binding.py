@@ -43,6 +43,7 @@ def load_library() -> C.CDLL:
         "lsq_decode_steps": [i32],
         "lsq_get_beams": [vp, vp, vp],
         "lsq_step_index": [],
+        "lsq_set_graphs": [i32],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -113,6 +114,10 @@ def lsq_decode_step() -> int:
 
 def lsq_decode_steps(n: int) -> int:
     return _check(load_library().lsq_decode_steps(n))
+
+
+def lsq_set_graphs(on: bool) -> None:
+    _check(load_library().lsq_set_graphs(int(on)))
 
 
 def lsq_step_index() -> int:
@@ -241,7 +246,10 @@ class Engine:
         nbytes = lsq_workspace_bytes(blob, max_batch, beam, max_len)
         torch.cuda.set_device(device)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        self.stream = torch.cuda.current_stream().cuda_stream
+        # a stream of its own (default priority): the default stream cannot be captured into graphs
+        self.torch_stream = torch.cuda.Stream(device=device)
+        self.stream = self.torch_stream.cuda_stream
+        torch.cuda.current_stream().synchronize()
         lsq_set_workspace(self.workspace.data_ptr(), nbytes, self.stream)
         try:
             lsq_init(blob, max_batch, beam, max_len)

@@ -95,10 +95,11 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
 template <typename T, int DH>
 __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict__ q, const T* __restrict__ Kc,
                                                              const T* __restrict__ Vc, T* __restrict__ out,
-                                                             int rows, int H, int d, int T_, int nkeys,
-                                                             float scale) {
+                                                             int rows, int H, int d, int T_, int nkeys_base,
+                                                             const int32_t* __restrict__ tp, float scale) {
   int w = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= rows * H) return;
+  const int nkeys = nkeys_base + (tp ? *tp : 0);
   int r = w / H, h = w % H;
   const T* qp[1] = {q + (size_t)r * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
@@ -182,20 +183,20 @@ bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh 
 
 template <typename T>
 static hipError_t self_t(const T* q, const T* Kc, const T* Vc, T* out, int rows, int H, int d, int T_,
-                         int nkeys, hipStream_t s) {
+                         int nkeys, const int32_t* tp, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
   dim3 g((rows * H + 3) / 4), b(256);
-  LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, scale)));
+  LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
   return hipGetLastError();
 }
 
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
-                                 int rows, int H, int d, int T, int nkeys, hipStream_t s) {
+                                 int rows, int H, int d, int T, int nkeys, const int32_t* tp, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (dtype == DT_F16)
-    return self_t<half_t>((const half_t*)q, (const half_t*)Kc, (const half_t*)Vc, (half_t*)out, rows, H, d, T, nkeys, s);
-  return self_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, rows, H, d, T, nkeys, s);
+    return self_t<half_t>((const half_t*)q, (const half_t*)Kc, (const half_t*)Vc, (half_t*)out, rows, H, d, T, nkeys, tp, s);
+  return self_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, rows, H, d, T, nkeys, tp, s);
 }
 
 template <typename T, int NQ>

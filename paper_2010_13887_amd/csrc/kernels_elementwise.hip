@@ -39,9 +39,11 @@ template <typename T>
 __global__ void __launch_bounds__(256) embed_last_kernel(const T* __restrict__ E, const float* __restrict__ pe,
                                                          const int32_t* __restrict__ tokens,
                                                          const int32_t* __restrict__ len, T* __restrict__ x,
-                                                         int rows, int d, int T1, int t, float scale) {
+                                                         int rows, int d, int T1, const int32_t* __restrict__ tp,
+                                                         float scale) {
   int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
+  const int t = *tp;   // decode-step counter, kept on the device
   int id = tokens[(size_t)r * T1 + len[r]];
   embed_row<T>(E + (size_t)id * d, pe + (size_t)t * d, x + (size_t)r * d, d, scale, threadIdx.x & 63, 64);
 }
@@ -59,14 +61,15 @@ hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const in
 }
 
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
-                             const int32_t* len, void* x, int rows, int d, int T, int t, hipStream_t s) {
+                             const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp,
+                             hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   float scale = sqrtf((float)d);
   dim3 g((rows + 3) / 4), b(256);
   if (dtype == DT_F16)
-    embed_last_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, tokens, len, (half_t*)x, rows, d, T + 1, t, scale);
+    embed_last_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, tokens, len, (half_t*)x, rows, d, T + 1, tp, scale);
   else
-    embed_last_kernel<float><<<g, b, 0, s>>>((const float*)E, pe, tokens, len, (float*)x, rows, d, T + 1, t, scale);
+    embed_last_kernel<float><<<g, b, 0, s>>>((const float*)E, pe, tokens, len, (float*)x, rows, d, T + 1, tp, scale);
   return hipGetLastError();
 }
 
@@ -87,7 +90,7 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
   int lane = threadIdx.x & 63;
   T* xr = x + (size_t)r * d;
   const size_t slab = (size_t)rows * d;
-  float v[NV][8];
+  float v[NV][8], gv[NV][8], bv[NV][8];
   float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
@@ -96,14 +99,16 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
       float a[8], t[8], part[S][8];
 #pragma unroll
       for (int s = 0; s < S; ++s) Vec8<float>::load(P + s * slab + (size_t)r * d + c, part[s]);   // all in flight
+      Vec8<T>::load(bias + c, t);
+      Vec8<T>::load(xr + c, v[j]);
+      Vec8<T>::load(g + c, gv[j]);      // gain and shift too: one round trip to memory in all
+      Vec8<T>::load(b + c, bv[j]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) a[i] = part[0][i];
 #pragma unroll
       for (int s = 1; s < S; ++s)
 #pragma unroll
         for (int i = 0; i < 8; ++i) a[i] += part[s][i];
-      Vec8<T>::load(bias + c, t);
-      Vec8<T>::load(xr + c, v[j]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) { v[j][i] += a[i] + t[i]; sum += v[j][i]; }
     } else {
@@ -127,11 +132,9 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
   for (int j = 0; j < NV; ++j) {
     int c = (j * 64 + lane) * 8;
     if (c < d) {
-      float gv[8], bv[8], o[8];
-      Vec8<T>::load(g + c, gv);
-      Vec8<T>::load(b + c, bv);
+      float o[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = gv[i] * (v[j][i] * rstd) + bv[i];
+      for (int i = 0; i < 8; ++i) o[i] = gv[j][i] * (v[j][i] * rstd) + bv[j][i];
       Vec8<T>::store(xr + c, o);
     }
   }

@@ -8,16 +8,16 @@
 namespace lsq {
 
 template <typename T>
-__device__ __forceinline__ void store_one(const GemmOut& o, int m, int n, float v) {
+__device__ __forceinline__ void store_one(const GemmOut& o, int m, int n, float v, long tp) {
   int s = n / o.seg_n;
-  reinterpret_cast<T*>(o.ptr[s])[(long)m * o.ld[s] + (n - s * o.seg_n)] = (T)v;
+  reinterpret_cast<T*>(o.ptr[s])[(long)m * o.ld[s] + tp * o.tmul[s] + (n - s * o.seg_n)] = (T)v;
 }
 
 // Stores four consecutive outputs (m, n..n+3) of a tile: split-K slab, vector, or element-wise
 // fallback for ragged / unaligned rows.
 template <typename OutT, bool SPLIT>
 __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const float (&v)[4], int M, int N,
-                                       int vec_ok, int slab) {
+                                       int vec_ok, int slab, long tp) {
   if constexpr (SPLIT) {
     float* dst = reinterpret_cast<float*>(out.ptr[0]) + ((size_t)slab * M + m) * N + n;
     if (vec_ok && n + 3 < N) {
@@ -30,7 +30,7 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
     }
   } else if (vec_ok && n + 3 < N) {
     int s = n / out.seg_n;
-    OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + (n - s * out.seg_n);
+    OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + tp * out.tmul[s] + (n - s * out.seg_n);
     if constexpr (sizeof(OutT) == 2) {
       half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
       *reinterpret_cast<half4_t*>(dst) = h;
@@ -41,7 +41,7 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-      if (n + e < N) store_one<OutT>(out, m, n + e, v[e]);
+      if (n + e < N) store_one<OutT>(out, m, n + e, v[e], tp);
   }
 }
 
@@ -53,6 +53,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tid = threadIdx.x;
+  const long tp = out.tpos ? *out.tpos : 0;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   const int tx = tid & 15, ty = tid >> 4;
   float acc[4][4] = {};
@@ -88,7 +89,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
       if (n >= N) continue;
       float v = acc[i][j] + (bias ? bias[n] : 0.f);
       if (relu) v = fmaxf(v, 0.f);
-      store_one<float>(out, m, n, v);
+      store_one<float>(out, m, n, v, tp);
     }
   }
 }
@@ -124,6 +125,7 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
   __shared__ __attribute__((aligned(16))) half_t Bs[2][BN * LDK];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long tp = out.tpos ? *out.tpos : 0;
   const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN, total = mt * nt;
   int id = blockIdx.x;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
@@ -284,7 +286,7 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
           v[e] = acc[i][j][vg * 4 + e] + bv[j][vg][e];
           if (relu) v[e] = fmaxf(v[e], 0.f);
         }
-        store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y);
+        store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
       }
     }
   }
@@ -303,9 +305,10 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
                                                               const half_t* __restrict__ B,
                                                               const half_t* __restrict__ bias, GemmOut out, int M,
                                                               int N, int K, int relu, int vec_ok) {
-  constexpr int U = 4;
+  constexpr int U = 16 / TM;   // k-steps in flight per wavefront: one round trip covers 256 / TM of K
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long tp = out.tpos ? *out.tpos : 0;
   const int n0 = blockIdx.x * 32;
   const int fr = lane & 31, fk = (lane >> 5) * 8;
   const int ksteps_all = K / 16;                      // K % 16 == 0 is checked by the launcher
@@ -364,9 +367,11 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
       if (!SPLIT && bias) v[e] += (float)bias[min(n + e, N - 1)];
       if (relu) v[e] = fmaxf(v[e], 0.f);
     }
-    store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y);
+    store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
   }
 }
+
+constexpr int kSkinnyRows = 64;   // above this the LDS-tiled kernel is faster
 
 template <int TM>
 static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
@@ -398,7 +403,7 @@ static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const 
 int gemm_partial_splits(int dtype, int M, int N, int K) {
   if (dtype != DT_F16 || K % 64 != 0) return 1;
   const int nk = K / 64;
-  const long tiles = M <= 128 ? (N + 31) / 32 : (long)((M + 63) / 64) * ((N + 63) / 64);
+  const long tiles = M <= kSkinnyRows ? (N + 31) / 32 : (long)((M + 63) / 64) * ((N + 63) / 64);
   int S = 1;
   while (S < 8 && nk % (S * 2) == 0 && nk / (S * 2) >= 2 && tiles * S * 2 <= 1024) S *= 2;
   return S;
@@ -414,14 +419,12 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   if (dtype == DT_F32 || splits == 1) return launch_gemm(dtype, A, B, nullptr, out, M, N, K, false, s);
   if (K % (64 * splits) != 0) return hipErrorInvalidValue;
   const int vec_ok = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(P) & 15) == 0;
-  if (M <= 128) {
+  if (M <= kSkinnyRows) {
     dim3 grid((N + 31) / 32, splits), blk(256);
     const half_t* a = (const half_t*)A;
     const half_t* b = (const half_t*)B;
     if (M <= 32) gemm_f16_skinny_kernel<1, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
-    else if (M <= 64) gemm_f16_skinny_kernel<2, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
-    else if (M <= 96) gemm_f16_skinny_kernel<3, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
-    else gemm_f16_skinny_kernel<4, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    else gemm_f16_skinny_kernel<2, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
     return hipGetLastError();
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
@@ -445,16 +448,14 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   if (nseg > 3) return hipErrorInvalidValue;
   int vec_ok = (out.seg_n % 4 == 0);
   for (int i = 0; i < nseg; ++i)
-    if (out.ld[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & (out.f32_out ? 15 : 7)) != 0) vec_ok = 0;
+    if (out.ld[i] % 4 != 0 || out.tmul[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & (out.f32_out ? 15 : 7)) != 0) vec_ok = 0;
   const half_t* a = (const half_t*)A;
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (M <= 128 && K % 16 == 0) {
+  if (M <= kSkinnyRows && K % 16 == 0) {
     if (M <= 32) run_skinny<1>(a, b, bi, out, M, N, K, relu, vec_ok, s);
-    else if (M <= 64) run_skinny<2>(a, b, bi, out, M, N, K, relu, vec_ok, s);
-    else if (M <= 96) run_skinny<3>(a, b, bi, out, M, N, K, relu, vec_ok, s);
-    else run_skinny<4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    else run_skinny<2>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else if (tiles128 >= 256)

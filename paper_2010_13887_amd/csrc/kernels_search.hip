@@ -236,11 +236,12 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
                                                          int32_t* __restrict__ len, int32_t* __restrict__ fin,
                                                          int32_t* __restrict__ parent,
                                                          const int32_t* __restrict__ cap,
-                                                         int32_t* __restrict__ active, int k, int V, int T1, int t,
-                                                         int eos) {
+                                                         int32_t* __restrict__ active, int k, int V, int T1,
+                                                         int t_base, int32_t* __restrict__ step_state, int eos) {
   __shared__ int sh_parent[LSQ_MAX_BEAM_];
   __shared__ int sh_unfinished;
   const int b = blockIdx.x, lane = threadIdx.x;
+  const int t = t_base + (step_state ? step_state[0] : 0);
   const int kk = k * k;
   if (lane == 0) sh_unfinished = 0;
   float s = -INFINITY;
@@ -300,16 +301,28 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     if (!nfin) sh_unfinished = 1;
   }
   __syncthreads();
-  if (lane == 0 && sh_unfinished) atomicAdd(active, 1);
+  if (lane == 0) {
+    if (sh_unfinished) atomicAdd(step_state ? active + t : active, 1);   // per-step counters, or the caller's one
+    if (step_state) {
+      // the last sentence to get here advances the step counter; every workgroup read it at its
+      // start, and kernels launched later see the new value
+      __threadfence();
+      if (atomicAdd(&step_state[1], 1) == (int)gridDim.x - 1) {
+        step_state[1] = 0;
+        step_state[0] = t + 1 - t_base;
+      }
+    }
+  }
 }
 
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
                               int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
-                              int32_t* active, int batch, int k, int V, int T, int t, int eos, hipStream_t s) {
+                              int32_t* active, int batch, int k, int V, int T, int t_base, int32_t* step_state,
+                              int eos, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
   beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
-                                          k, V, T + 1, t, eos);
+                                          k, V, T + 1, t_base, step_state, eos);
   return hipGetLastError();
 }
 
@@ -322,8 +335,11 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
 template <int KB>
 __global__ void __launch_bounds__(256) cache_reorder_kernel(uint4* __restrict__ cache,
                                                             const int32_t* __restrict__ parent, int k,
-                                                            long row_vecs, long used_vecs, long layer_vecs) {
+                                                            long row_vecs, long pos_vecs, int npos_base,
+                                                            const int32_t* __restrict__ tp, long layer_vecs) {
   const int b = blockIdx.y;
+  const long used_vecs = (long)(npos_base + (tp ? *tp : 0)) * pos_vecs;
+  if ((long)blockIdx.x * 1024 >= used_vecs) return;
   int par[KB];
   unsigned need = 0, moved = 0;
 #pragma unroll
@@ -352,25 +368,28 @@ __global__ void __launch_bounds__(256) cache_reorder_kernel(uint4* __restrict__ 
 }
 
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
-                                int rows_total, int k, int T, int d, int npos, hipStream_t s) {
-  if (batch <= 0 || layers <= 0 || npos <= 0 || k <= 1) return hipSuccess;
+                                int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,
+                                int npos_max, hipStream_t s) {
+  if (batch <= 0 || layers <= 0 || npos_max <= 0 || k <= 1) return hipSuccess;
   size_t esz = dtype == DT_F16 ? 2 : 4;
   if ((d * esz) % 16 != 0 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
-  long row_vecs = (long)T * d * esz / 16, used = (long)npos * d * esz / 16;
+  long pos_vecs = (long)d * esz / 16;
+  long row_vecs = (long)T * pos_vecs, used = (long)npos_max * pos_vecs;
   long layer_vecs = (long)rows_total * row_vecs;   // a layer holds rows_total rows; the first batch*k are reordered
   dim3 grid((unsigned)((used + 1023) / 1024), batch, layers), blk(256);
   if (k <= 4)
-    cache_reorder_kernel<4><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, used, layer_vecs);
+    cache_reorder_kernel<4><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, pos_vecs, npos_base, tp, layer_vecs);
   else
-    cache_reorder_kernel<8><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, used, layer_vecs);
+    cache_reorder_kernel<8><<<grid, blk, 0, s>>>((uint4*)cache, parent, k, row_vecs, pos_vecs, npos_base, tp, layer_vecs);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
 __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict__ tokens, int32_t* __restrict__ len,
-                                  int32_t* __restrict__ fin, int32_t* __restrict__ active_counts, int M, int k,
-                                  int T1, int bos, int pad) {
+                                  int32_t* __restrict__ fin, int32_t* __restrict__ active_counts,
+                                  int32_t* __restrict__ step_state, int M, int k, int T1, int bos, int pad) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < 2) step_state[i] = 0;
   if (i < M * T1) tokens[i] = (i % T1 == 0) ? bos : pad;
   if (i < M) {
     score[i] = (i % k == 0) ? 0.f : -INFINITY;
@@ -381,9 +400,10 @@ __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict
 }
 
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin, int32_t* active_counts,
-                             int batch, int k, int T, int bos, int pad, hipStream_t s) {
+                             int32_t* step_state, int batch, int k, int T, int bos, int pad, hipStream_t s) {
   int M = batch * k, n = M * (T + 1);
-  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, M, k, T + 1, bos, pad);
+  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, step_state, M, k, T + 1,
+                                                    bos, pad);
   return hipGetLastError();
 }
 

@@ -24,6 +24,10 @@ struct GemmOut {
   long ld[3];
   int seg_n;
   int f32_out;   // fp16 GEMM only: write the fp32 accumulators unrounded (vocabulary logits)
+  // Optional step-dependent offset: segment s is shifted by (*tpos) * tmul[s] elements, with *tpos
+  // read on the device (the decode-step counter), so the same launch serves every step.
+  const int32_t* tpos;
+  long tmul[3];
 };
 
 inline GemmOut plain_out(void* c, int N) {
@@ -32,6 +36,8 @@ inline GemmOut plain_out(void* c, int N) {
   o.ld[0] = N; o.ld[1] = 0; o.ld[2] = 0;
   o.seg_n = N;
   o.f32_out = 0;
+  o.tpos = nullptr;
+  o.tmul[0] = o.tmul[1] = o.tmul[2] = 0;
   return o;
 }
 
@@ -46,13 +52,16 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
 hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
                              const int32_t* pos, void* x, int rows, int d, hipStream_t s);
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
-                             const int32_t* len, void* x, int rows, int d, int T, int t, hipStream_t s);
+                             const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp,
+                             hipStream_t s);
 hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int splits, const void* bias,
                                          const void* g, const void* b, int rows, int d, float eps,
                                          hipStream_t s);
 
+// nkeys = nkeys_base + (tp ? *tp : 0), with *tp read on the device
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
-                                 int rows, int H, int d, int T, int nkeys, hipStream_t s);
+                                 int rows, int H, int d, int T, int nkeys_base, const int32_t* tp,
+                                 hipStream_t s);
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
                                   const int32_t* len, void* out, int batch, int beam, int H, int d,
                                   hipStream_t s);
@@ -63,15 +72,20 @@ hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* r
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
                            int M, int V, int k, int eos, float* out_score, int32_t* out_idx,
                            hipStream_t s);
+// step = t_base + (step_state ? step_state[0] : 0).  `active` points at the counter array indexed
+// by step.  With step_state != null the last workgroup to finish advances step_state[0]
+// (step_state[1] is its arrival counter and must be zero at launch).
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
                               int32_t* tokens, int32_t* len, int32_t* fin, int32_t* parent,
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
-                              int t, int eos, hipStream_t s);
+                              int t_base, int32_t* step_state, int eos, hipStream_t s);
+// npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
-                                int rows_total, int k, int T, int d, int npos, hipStream_t s);
+                                int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,
+                                int npos_max, hipStream_t s);
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
-                             int32_t* active_counts, int batch, int k, int T, int bos, int pad,
-                             hipStream_t s);
+                             int32_t* active_counts, int32_t* step_state, int batch, int k, int T, int bos,
+                             int pad, hipStream_t s);
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
                            int32_t* out_lens, float* out_scores, const int32_t* sentence_order, int batch,
                            int k, int T, float alpha, int pad, hipStream_t s);

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <vector>
 
 #include "../../include/lsq.h"
@@ -79,7 +80,7 @@ hipError_t prof_mark(hipStream_t s, int c, bool start) {
   } while (0)
 
 constexpr size_t kAlign = 256;
-constexpr size_t kMaxSplits = 8;
+constexpr size_t kMaxSplits = 4;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct HParams {
@@ -147,7 +148,7 @@ struct DecLayer {
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
 struct Plan {
-  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, order, src_off, src_len, active,
+  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, order, src_off, src_len, active, step_state,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
@@ -175,6 +176,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.src_off = take((size_t)(B + 1) * 4);
   p.src_len = take((size_t)B * 4);
   p.active = take((size_t)(T + 1) * 4);
+  p.step_state = take(2 * 4);   // [0] decode-step counter, [1] arrival counter of the refine kernel
   p.cand_score = take(M * k * 4);
   p.cand_idx = take(M * k * 4);
   p.out_ids = take(M * T * 4);
@@ -219,6 +221,8 @@ struct Ctx {
   int batch = 0, rows_enc = 0, t = 0;
   bool done = false;
   std::vector<int> order;      // internal (sorted) sentence index -> caller's index
+  bool use_graphs = true;
+  std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
   std::vector<EncLayer> enc;
@@ -269,31 +273,35 @@ int sublayer(int cls, const void* in, const void* W, const void* bias, const voi
   return LSQ_OK;
 }
 
-int enqueue_step() {
+// All launches of one decode step for the first B sentences (B*k rows).  Nothing here depends on
+// the step index: kernels read it from the device-side counter (step_state[0]), the cache and
+// cross-K/V strides are those of the maximum shapes, and the cache-reorder grid covers max_len
+// positions.  The same sequence therefore serves every step with B sentences alive, which is what
+// lets it be captured once into a hipGraph and replayed.
+int launch_step(int B) {
   const HParams& hp = g.hp;
   const Plan& p = g.plan;
   hipStream_t s = g.stream;
-  const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, k = g.beam, T = g.max_len, t = g.t;
-  // Sentences are kept sorted by cap (descending), so those that can still be unfinished at step
-  // t are a prefix; the host knows its length without reading anything back.
-  const int B = g.alive_at[t], M = B * k, M_all = g.batch * k;
+  const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, k = g.beam, T = g.max_len;
+  const int M = B * k, M_max = g.max_batch * k;
   const size_t es = esz();
   char* x = g.ws + p.d_x; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
-  const size_t slab = (size_t)M_all * T * d * es;   // one layer's K (or V) cache
-  const size_t cross_l = (size_t)g.rows_enc * 2 * d * es;
-  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, t, s));
+  int32_t* step = at<int32_t>(p.step_state);
+  const size_t slab = (size_t)M_max * T * d * es;   // one layer's K (or V) cache
+  const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
+  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, s));
   for (int l = 0; l < hp.n_dec; ++l) {
     const DecLayer& L = g.dec[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
     char* Vc = Kc + slab;
-    GemmOut o;
-    o.ptr[0] = q; o.ptr[1] = Kc + (size_t)t * d * es; o.ptr[2] = Vc + (size_t)t * d * es;
-    o.ld[0] = d; o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
-    o.seg_n = d;
-    o.f32_out = 0;
+    GemmOut o = plain_out(q, d);        // Q | K | V: Q to the activation buffer, K and V to cache position t
+    o.ptr[1] = Kc; o.ptr[2] = Vc;
+    o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
+    o.tpos = step;
+    o.tmul[1] = d; o.tmul[2] = d;
     TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
-    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, t + 1, s));
+    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, s));
     if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
@@ -307,12 +315,44 @@ int enqueue_step() {
   TIMED(PC_GEMM_VOCAB, launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, false, s));
   TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+  // refine advances the device-side step counter when its last workgroup finishes, so the
+  // reorder that follows reads t + 1 = the number of cache positions to gather
   TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
-                            at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active) + t, B, k, V, T,
-                            t, hp.eos, s));
-  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_all, k, T, d, t + 1, s));
-  g.t = t + 1;
+                            at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T, 0,
+                            step, hp.eos, s));
+  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
+                                         0, step, T, s));
+  return LSQ_OK;
+}
+
+// One decode step: replay the captured graph for this number of live sentences, capturing it on
+// first use.  Graphs need a capturable (non-default) stream and are bypassed while per-kernel
+// timing is on.
+int enqueue_step() {
+  const int B = g.alive_at[g.t];
+  if (!g.use_graphs || g.stream == nullptr || g_prof.on) {
+    int rc = launch_step(B);
+    if (rc) return rc;
+    g.t += 1;
+    return LSQ_OK;
+  }
+  auto it = g.graphs.find(B);
+  if (it == g.graphs.end()) {
+    hipGraph_t graph = nullptr;
+    HIPCHK(hipStreamBeginCapture(g.stream, hipStreamCaptureModeThreadLocal));
+    int rc = launch_step(B);
+    hipError_t e = hipStreamEndCapture(g.stream, &graph);
+    if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess) return fail(LSQ_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return fail(LSQ_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    it = g.graphs.emplace(B, exec).first;
+  }
+  HIPCHK(hipGraphLaunch(it->second, g.stream));
+  g.t += 1;
   return LSQ_OK;
 }
 
@@ -512,12 +552,13 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), (int)R, F, d, true, s));
     if (int rc = sublayer(-1, ffn, L.W2, L.b2, L.ln2g, L.ln2b, x, (float*)tmp, (int)R, d, F, 1, s)) return rc;
   }
-  const size_t cross_l = (size_t)R * 2 * d * es;
+  const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;   // layer stride of the maximum shape
   for (int l = 0; l < hp.n_dec; ++l)
     HIPCHK(launch_gemm(dt, x, g.dec[l].Wkv, g.dec[l].bkv, plain_out(g.ws + p.cross + l * cross_l, 2 * d), (int)R,
                        2 * d, d, false, s));
   HIPCHK(launch_beam_reset(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
-                           at<int32_t>(p.active), batch, g.beam, g.max_len, hp.bos, hp.pad, s));
+                           at<int32_t>(p.active), at<int32_t>(p.step_state), batch, g.beam, g.max_len, hp.bos,
+                           hp.pad, s));
   g.batch = batch;
   g.rows_enc = (int)R;
   g.t = 0;
@@ -569,6 +610,11 @@ int lsq_profile_read(double* ms, int64_t* launches, int n) {
   return LSQ_OK;
 }
 
+int lsq_set_graphs(int on) {
+  g.use_graphs = on != 0;
+  return LSQ_OK;
+}
+
 int lsq_step_index(void) { return g.state >= 3 ? g.t : 0; }
 
 int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
@@ -587,6 +633,11 @@ int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
 }
 
 void lsq_free(void) {
+  if (!g.graphs.empty()) {
+    (void)hipStreamSynchronize(g.stream);
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+  }
   if (g.pinned) {
     if (g.stream || g.state >= 2) (void)hipStreamSynchronize(g.stream);
     (void)hipHostFree(g.pinned);
@@ -620,9 +671,9 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     default: {
       int l = what % 100, kind = what - l;
       if (l < 0 || l >= hp.n_dec) return fail(LSQ_E_ARG, "unknown debug item %d", what);
-      if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * n * esz(); per_source_row = true; }
-      else if (kind == LSQ_DBG_CACHE_K) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * n * esz(); }
-      else if (kind == LSQ_DBG_CACHE_V) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * n * esz(); }
+      if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * g.max_batch * g.max_len * 2 * d * esz(); per_source_row = true; }
+      else if (kind == LSQ_DBG_CACHE_K) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * g.max_batch * g.beam * T * d * esz(); }
+      else if (kind == LSQ_DBG_CACHE_V) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * g.max_batch * g.beam * T * d * esz(); }
       else return fail(LSQ_E_ARG, "unknown debug item %d", what);
       is_float_data = true;
     }
@@ -702,7 +753,7 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(rows >= 0 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "head size must be 16/32/64/128");
   KCHK(nkeys >= 1 && nkeys <= T, "nkeys outside [1, T]");
-  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, (hipStream_t)stream));
+  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, nullptr, (hipStream_t)stream));
 }
 
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off, const int32_t* src_len,
@@ -727,7 +778,7 @@ int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* s
   KCHK(cand_score && cand_idx && score && tokens && len && finished && parent && cap && active, "null pointer");
   KCHK(batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && V >= k && T >= 1 && t >= 0 && t < T, "shape");
   KRUN(launch_beam_refine(cand_score, cand_idx, score, tokens, len, finished, parent, cap, active, batch, k, V, T, t,
-                          eos, (hipStream_t)stream));
+                          nullptr, eos, (hipStream_t)stream));
 }
 
 int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k, int T, int d,
@@ -735,7 +786,7 @@ int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layer
   KCHK(cache && parent, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(layers >= 0 && batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && npos >= 0 && npos <= T && d % 8 == 0, "shape");
-  KRUN(launch_cache_reorder(dtype, cache, parent, layers, batch, batch * k, k, T, d, npos, (hipStream_t)stream));
+  KRUN(launch_cache_reorder(dtype, cache, parent, layers, batch, batch * k, k, T, d, npos, nullptr, npos, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -94,3 +94,25 @@ def test_errors_leave_no_device_work(lsq):
         with pytest.raises(lsq.LsqError):
             eng.encode(np.zeros((3, 8), np.int32) + 5, [1, 1, 1])   # batch above max_batch
         eng.translate(w.src_ids, w.src_lens)
+
+
+def test_graph_replay_matches_eager_launches(lsq):
+    """Decode steps replayed from captured hipGraphs (several replays per graph, with eager work and
+    synchronisations in between) give bit-identical beams to the same kernels launched one by one."""
+    hp = S.HParams(n_enc=1, n_dec=2, d_model=128, n_heads=2, d_ffn=256, vocab=504, max_pos=64, dtype=1, cap_extra=6)
+    w = S.custom(hp, [3, 17, 9, 1, 12, 6, 11, 2], beam=4, max_len=24, std=0.05)
+    blob = w.blob(ln_jitter=0.1)
+    with lsq.Engine(blob, 8, w.beam, w.max_len) as eng:
+        lsq.lsq_set_graphs(False)
+        eager = eng.translate(w.src_ids, w.src_lens)
+        lsq.lsq_set_graphs(True)
+        eng.encode(w.src_ids, w.src_lens)
+        steps = 0
+        while eng.decode_step() > 0:                      # one replay per call, a read-back between replays
+            eng.debug(lsq.DBG.SCORE, (w.batch * w.beam,))
+            steps += 1
+        graphed = eng.get_beams()
+        again = eng.translate(w.src_ids, w.src_lens, sync_every=5)   # graphs already captured: pure replays
+        assert steps >= 10
+        for a, b, c in zip(eager, graphed, again):
+            assert np.array_equal(a, b) and np.array_equal(a, c)
