@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Kernel-level roofline table: every kernel of the decode step, alone, through the C ABI's
+single-kernel entry points, at the headline workload's shapes (Transformer-big, M = 512 rows,
+t = 40 cached positions) and at stress shapes whose working set exceeds the last-level cache.
+
+Each case is launched `--iters` times back to back on torch's current stream between two
+torch.cuda.Event records (the entry points launch on that stream); the table gives the average
+time, the algorithmic bytes / FLOP of one launch and the fraction of the MI355X peak (HBM 8 TB/s,
+dense fp16 MFMA 2.5 PFLOP/s).  Back-to-back launches overlap the launch latency of one with the
+execution of the previous, so small cases read lower here than inside the decode step.
+A "copy" case (torch's device-to-device copy of a known size) calibrates rocprofv3's FETCH_SIZE /
+WRITE_SIZE counters when this script is run under `rocprofv3 --pmc`.
+Prints one JSON object per case, then a summary table on stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM = 8000.0      # GB/s
+PEAK_MFMA = 2500.0     # TFLOP/s, dense fp16
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=50)
+    ap.add_argument("--only", default="", help="comma-separated case-name prefixes")
+    ap.add_argument("--no-stress", action="store_true")
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+    import paper_2010_13887_amd as lsq
+
+    if not torch.cuda.is_available():
+        print("bench_kernels.py: no GPU visible", file=sys.stderr)
+        return 2
+    lsq.load_library()
+    dev = "cuda"
+    h = torch.float16
+    g = torch.Generator(device=dev).manual_seed(4321)
+
+    def rnd(*shape, dtype=h, scale=1.0):
+        return (torch.randn(*shape, device=dev, dtype=torch.float32, generator=g) * scale).to(dtype)
+
+    cases = []   # (name, bound, flops, bytes, callable)
+
+    def gemm_case(name, M, N, K, out_f32=False, relu=False):
+        A, B, bias = rnd(M, K), rnd(N, K, scale=0.02), rnd(N, scale=0.02)
+        C = torch.empty(M, N, device=dev, dtype=torch.float32 if out_f32 else h)
+        by = (M * K + N * K) * 2 + M * N * (4 if out_f32 else 2)
+        cases.append((name, "mfma", 2.0 * M * N * K, by, lambda: lsq.k_gemm(A, B, bias, C, relu)))
+
+    def sublayer_case(name, M, d, K):
+        inp, W, bias = rnd(M, K), rnd(d, K, scale=0.02), rnd(d, scale=0.02)
+        x, gm, bt = rnd(M, d), rnd(d) * 0 + 1, rnd(d) * 0
+        by = (M * K + d * K) * 2 + 2 * M * d * 2
+        cases.append((name, "mfma", 2.0 * M * d * K, by, lambda: lsq.k_gemm_add_layernorm(inp, W, bias, x, gm, bt, 1e-5)))
+
+    def self_attn_case(name, M, H, d, T, nkeys):
+        q, Kc, Vc = rnd(M, d), rnd(M, T, d), rnd(M, T, d)
+        out = torch.empty(M, d, device=dev, dtype=h)
+        by = (2 * M * nkeys * d + 2 * M * d) * 2
+        cases.append((name, "hbm", 4.0 * M * nkeys * d, by, lambda: lsq.k_self_attention(q, Kc, Vc, out, H, nkeys)))
+
+    def cross_attn_case(name, B, k, H, d, lens):
+        lens = np.asarray(lens, np.int32)
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+        q, kv = rnd(B * k, d), rnd(int(lens.sum()), 2 * d)
+        ln = torch.from_numpy(lens).to(dev)
+        out = torch.empty(B * k, d, device=dev, dtype=h)
+        by = (2 * int(lens.sum()) * d + 2 * B * k * d) * 2
+        cases.append((name, "hbm", 4.0 * k * int(lens.sum()) * d, by,
+                      lambda: lsq.k_cross_attention(q, kv, off, ln, out, B, k, H)))
+
+    def topk_case(name, M, V, k):
+        logits = rnd(M, V, dtype=torch.float32, scale=0.64)
+        score = -torch.rand(M, device=dev, generator=g) * 40
+        fin = torch.zeros(M, device=dev, dtype=torch.int32)
+        os_ = torch.empty(M, k, device=dev, dtype=torch.float32)
+        oi = torch.empty(M, k, device=dev, dtype=torch.int32)
+        cases.append((name, "hbm", 4.0 * M * V, M * V * 4, lambda: lsq.k_row_topk(logits, score, fin, k, 2, os_, oi)))
+
+    def reorder_case(name, layers, B, k, T, d, npos):
+        cache = rnd(layers, B * k, T, d)
+        # every sentence: beams 1..k-1 take beam 0's history (k-1 rows move, 1 row is read)
+        par = torch.zeros(B * k, device=dev, dtype=torch.int32)
+        by = layers * B * npos * d * 2 * (1 + (k - 1))
+        cases.append((name, "hbm", 0.0, by, lambda: lsq.k_cache_reorder(cache, par, layers, B, k, T, d, npos)))
+
+    def copy_case(name, nbytes):
+        a = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+        b = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+        a.fill_(1)
+        cases.append((name, "hbm", 0.0, 2 * nbytes, lambda: b.copy_(a)))
+
+    M, d, F, V, H, L, T = 512, 1024, 4096, 32000, 16, 6, 175
+    gemm_case("gemm_qkv M512 N3072 K1024", M, 3 * d, d)
+    gemm_case("gemm_dxd M512 N1024 K1024", M, d, d)
+    gemm_case("gemm_ffn1 M512 N4096 K1024", M, F, d, relu=True)
+    sublayer_case("sublayer_out M512 d1024 K1024 (split-K gemm + add_layernorm)", M, d, d)
+    sublayer_case("sublayer_ffn2 M512 d1024 K4096 (split-K gemm + add_layernorm)", M, d, F)
+    gemm_case("gemm_vocab M512 N32000 K1024 f32out", M, V, d, out_f32=True)
+    self_attn_case("attn_self M512 t41", M, H, d, T, 41)
+    rs = np.random.default_rng(4321)
+    cross_attn_case("attn_cross B128 k4 meanlen29", 128, 4, H, d, np.clip(np.rint(rs.lognormal(3.15, 0.6, 128)), 1, 128))
+    topk_case("row_topk M512 V32000 k4", M, V, 4)
+    reorder_case("cache_reorder L12 B128 k4 t41 (3 of 4 rows move)", 2 * L, 128, 4, T, d, 41)
+    if not args.no_stress:
+        gemm_case("stress gemm M4096 N4096 K4096", 4096, 4096, 4096)
+        gemm_case("stress gemm_vocab M4096 N32000 K1024 f32out", 4096, V, d, out_f32=True)
+        sublayer_case("stress sublayer M16384 d1024 K1024", 16384, d, d)
+        self_attn_case("stress attn_self M2048 t175 (full cache, 2.9 GB)", 2048, H, d, T, T)
+        topk_case("stress row_topk M16384 V32000 k4 (2.1 GB)", 16384, V, 4)
+        reorder_case("stress cache_reorder L12 B512 k4 t175 (3 of 4 rows move)", 2 * L, 512, 4, T, d, T)
+    copy_case("copy 1 GiB -> 1 GiB (torch)", 1 << 30)
+
+    only = [p for p in args.only.split(",") if p]
+    rows = []
+    for name, bound, fl, by, fn in cases:
+        if only and not any(name.startswith(p) for p in only):
+            continue
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / args.iters * 1e3
+        rec = dict(case=name, bound=bound, avg_us=us, flops=fl, bytes=by,
+                   tflops=fl / us / 1e6, gbs=by / us / 1e3)
+        rec["frac"] = rec["tflops"] / PEAK_MFMA if bound == "mfma" else rec["gbs"] / PEAK_HBM
+        rows.append(rec)
+        print(json.dumps(rec), flush=True)
+    print(f"{'case':72s} {'us':>9s} {'TFLOP/s':>9s} {'GB/s':>9s} {'bound':>5s} {'frac':>6s}", file=sys.stderr)
+    for r in rows:
+        print(f"{r['case']:72s} {r['avg_us']:9.1f} {r['tflops']:9.1f} {r['gbs']:9.1f} {r['bound']:>5s} {r['frac']:6.3f}",
+              file=sys.stderr)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

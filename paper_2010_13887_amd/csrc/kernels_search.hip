@@ -18,39 +18,17 @@ __device__ __forceinline__ bool precedes(float s1, int i1, float s2, int i2) {
   return s1 > s2 || (s1 == s2 && i1 < i2);
 }
 
-template <int BLOCK>
-__device__ __forceinline__ float block_max(float v, float* red) {
-  v = wave_max(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = red[0];
-#pragma unroll
-  for (int w = 1; w < BLOCK / 64; ++w) r = fmaxf(r, red[w]);
-  return r;
-}
-template <int BLOCK>
-__device__ __forceinline__ float block_sum(float v, float* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = red[0];
-#pragma unroll
-  for (int w = 1; w < BLOCK / 64; ++w) r += red[w];
-  return r;
-}
-
 // One workgroup of BLOCK threads per row; each thread holds NV*8 tokens in registers.
 // Token held in slot (j, e) of thread tid:  vectorised rows (V % 8 == 0): (j*BLOCK + tid)*8 + e;
 // otherwise (j*8 + e)*BLOCK + tid.
+// Register budget: two workgroups must fit a CU, so that one loads its row while the other reduces.
 template <typename T, int BLOCK, int NV>
-__global__ void __launch_bounds__(BLOCK) row_topk_kernel(const T* __restrict__ logits,
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(BLOCK == 512 ? 4 : 1)))
+row_topk_kernel(const T* __restrict__ logits,
                                                          const float* __restrict__ score,
                                                          const int32_t* __restrict__ fin, int V, int k, int eos,
                                                          float* __restrict__ out_score,
                                                          int32_t* __restrict__ out_idx) {
-  __shared__ float red[BLOCK / 64];
   __shared__ float reds[BLOCK / 64];
   __shared__ int redi[BLOCK / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -92,46 +70,76 @@ __global__ void __launch_bounds__(BLOCK) row_topk_kernel(const T* __restrict__ l
 #pragma unroll
     for (int e = 0; e < 8; ++e) mx = fmaxf(mx, x[j * 8 + e]);
   }
-  const float m = block_max<BLOCK>(mx, red);
-  float z = 0.f;
-#pragma unroll
-  for (int i = 0; i < NV * 8; ++i) z += expf(x[i] - m);   // padding slots: exp(-inf) = 0
-  const float logz = logf(block_sum<BLOCK>(z, red));
-  // candidate scores, rounded exactly as (score + ((x - m) - logz)) with no fused operation
-#pragma unroll
-  for (int i = 0; i < NV * 8; ++i) x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
-
-  // ---- rough stage: a threshold R with at least k tokens at or above it -----------------------
-  // Every lane's best score is the score of a distinct token.  Each wavefront lists its k largest
-  // lane maxima (shuffles only); R = the k-th largest of all listed values is reached by k distinct
-  // tokens, so every token of the row's top k satisfies score >= R (ties at R included).  Tokens
-  // at or above R go to a short list in LDS -- typically k to a dozen -- which is then ranked
-  // exactly.  Rows where the list overflows (e.g. thousands of equal logits) take the exact
-  // k-round arg-max below instead.
+  // One reduction for both softmax statistics: every thread owns (local max, local sum of
+  // exp(x - local max)); pairs merge as (max, z1*exp(m1-max) + z2*exp(m2-max)).
   constexpr int NW = BLOCK / 64, CAP = 256;
-  __shared__ float wtop[NW * LSQ_MAX_BEAM_];
+  __shared__ float red_m[NW], red_z[NW], wave_best[NW < LSQ_MAX_BEAM_ ? NW * LSQ_MAX_BEAM_ : NW];
   __shared__ float cand_s[CAP];
   __shared__ int cand_i[CAP];
   __shared__ int cand_n;
   const int lane = tid & 63, wave = tid >> 6;
-  float cur = -INFINITY;
+  float z = 0.f;
+  if (mx != -INFINITY) {
 #pragma unroll
-  for (int i = 0; i < NV * 8; ++i) cur = fmaxf(cur, x[i]);   // padding slots hold -inf
-  for (int round = 0; round < k; ++round) {
-    const float mx = wave_max(cur);
-    const unsigned long long hit = __ballot(cur == mx);
-    if (lane == 0) wtop[wave * k + round] = mx;
-    if (lane == __ffsll((long long)hit) - 1) cur = -INFINITY;
+    for (int i = 0; i < NV * 8; ++i) z += __expf(x[i] - mx);   // padding slots: exp(-inf) = 0
   }
+  float wm = mx, wz = z;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(wm, o, kWave), z2 = __shfl_xor(wz, o, kWave);
+    const float mn = fmaxf(wm, m2);
+    if (mn != -INFINITY) wz = wz * __expf(wm - mn) + z2 * __expf(m2 - mn);
+    wm = mn;
+  }
+  if (lane == 0) { red_m[wave] = wm; red_z[wave] = wz; }
   if (tid == 0) cand_n = 0;
   __syncthreads();
-  float v0 = lane < NW * k ? wtop[lane] : -INFINITY;
-  float v1 = lane + 64 < NW * k ? wtop[lane + 64] : -INFINITY;
-  float R = -INFINITY;
-  for (int round = 0; round < k; ++round) {
-    R = wave_max(fmaxf(v0, v1));
-    const unsigned long long hit = __ballot(fmaxf(v0, v1) == R);
-    if (lane == __ffsll((long long)hit) - 1) { if (v0 == R) v0 = -INFINITY; else v1 = -INFINITY; }
+  float m = red_m[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, red_m[w]);
+  float zt = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) zt += red_z[w] * __expf(red_m[w] - m);   // a wave of padding has z = 0
+  const float logz = logf(zt);
+  // candidate scores, rounded exactly as (score + ((x - m) - logz)) with no fused operation
+  float best = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) {
+    x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
+    best = fmaxf(best, x[i]);     // padding slots stay -inf
+  }
+
+  // ---- rough stage (the paper's retrieve, sec. 2.2): split the row into k groups, take each
+  // group's maximum, R = the smallest of them.  Each group maximum is the score of a distinct
+  // token, so k tokens reach R and every token of the row's top k satisfies score >= R (ties at R
+  // included).  Groups here: the wavefronts taken modulo k (blocks of at least 8 wavefronts) or the
+  // lanes taken modulo k (small blocks).  The tokens at or above R -- a dozen or so on average --
+  // go to a short list in LDS which is then ranked exactly.  Rows where the list
+  // overflows (e.g. thousands of equal logits) take the exact k-round arg-max below instead.
+  float R;
+  if (NW >= LSQ_MAX_BEAM_) {
+    const float wb = wave_max(best);
+    if (lane == 0) wave_best[wave] = wb;
+    __syncthreads();
+    R = INFINITY;
+    for (int grp = 0; grp < k; ++grp) {
+      float gm = -INFINITY;
+      for (int w = grp; w < NW; w += k) gm = fmaxf(gm, wave_best[w]);
+      R = fminf(R, gm);
+    }
+  } else {
+    // few wavefronts: groups are lanes modulo k within each wavefront, merged across wavefronts
+    R = INFINITY;
+    for (int grp = 0; grp < k; ++grp) {
+      const float gm = wave_max((lane % k) == grp ? best : -INFINITY);
+      if (lane == 0) wave_best[wave * LSQ_MAX_BEAM_ + grp] = gm;
+    }
+    __syncthreads();
+    for (int grp = 0; grp < k; ++grp) {
+      float gm = -INFINITY;
+      for (int w = 0; w < NW; ++w) gm = fmaxf(gm, wave_best[w * LSQ_MAX_BEAM_ + grp]);
+      R = fminf(R, gm);
+    }
   }
 #pragma unroll
   for (int j = 0; j < NV; ++j)
@@ -212,8 +220,8 @@ static hipError_t row_topk_t(const T* logits, const float* score, const int32_t*
     row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
   else if (V <= 8192)
     row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
-  else if (V <= 32768)
-    row_topk_kernel<T, 1024, 4><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+  else if (V <= 32768)   // 512 threads x 64 tokens: two workgroups fit a CU, one loads while the other reduces
+    row_topk_kernel<T, 512, 8><<<M, 512, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
   else if (V <= 65536)
     row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
   else
