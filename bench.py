@@ -30,6 +30,22 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 
+# HBM bytes per launch at the full-batch shape of the big128 workload (M = 512 rows, t = 40), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench_kernels.py scaled by the same counters'
+# readings for a 1 GiB copy (x2.0 for reads, x1.0 for writes): profiles/kernel_traffic_big128.txt.
+# Split-K classes are given for the 4 slabs used inside the decode step.
+MEASURED_TRAFFIC_BIG128 = {
+    "gemm_qkv": 14.9e6 + 3.1e6,
+    "gemm_dxd": (2 * (10.6e6 + 8.4e6) + (10.7e6 + 1.0e6)) / 3,   # two split-K products and one plain per layer
+    "gemm_ffn1": 17.0e6 + 4.2e6,
+    "gemm_ffn2": 42.0e6 + 8.4e6,
+    "gemm_vocab": 86.6e6 + 68.3e6,
+    "attn_self": 87.1e6 + 1.0e6,
+    "attn_cross": 16.2e6 + 1.0e6,
+    "row_topk": 65.9e6 + 8.4e6,
+    "cache_reorder": 129.2e6 + 386.9e6,     # 3 of 4 rows of every sentence moved
+}
+
 
 def class_work(name, hp, B, k, t_mean, s_mean):
     """Algorithmic work of ONE launch of a kernel class at a step that works on B sentences
@@ -147,12 +163,13 @@ def main() -> int:
                            gbs=by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0)
     dom = max(table, key=lambda n: table[n]["total_ms"])
     d = table[dom]
+    traffic = MEASURED_TRAFFIC_BIG128.get(dom) if args.workload == "big128" else None
     if dom.startswith("gemm"):
         roof = dict(bound="mfma", kernel=dom, achieved=d["tflops"], peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
-                    frac=d["tflops"] / PEAK_F16_TFLOPS, traffic=None, avg_us=d["avg_us"], launches=d["launches"])
+                    frac=d["tflops"] / PEAK_F16_TFLOPS, traffic=traffic, avg_us=d["avg_us"], launches=d["launches"])
     else:
         roof = dict(bound="hbm", kernel=dom, achieved=d["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=d["gbs"] / PEAK_HBM_GBS, traffic=None, avg_us=d["avg_us"], launches=d["launches"])
+                    frac=d["gbs"] / PEAK_HBM_GBS, traffic=traffic, avg_us=d["avg_us"], launches=d["launches"])
     gemm_ms = sum(v["total_ms"] for n, v in table.items() if n.startswith("gemm"))
     gemm_fl = sum(v["flops_per_launch"] * v["launches"] for n, v in table.items() if n.startswith("gemm"))
     kernel_ms = sum(v["total_ms"] for v in table.values())
