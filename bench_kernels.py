@@ -77,7 +77,7 @@ def main() -> int:
         out = torch.empty(B * k, d, device=dev, dtype=h)
         by = (2 * int(lens.sum()) * d + 2 * B * k * d) * 2
         cases.append((name, "hbm", 4.0 * k * int(lens.sum()) * d, by,
-                      lambda: lsq.k_cross_attention(q, kv, off, ln, out, B, k, H)))
+                      lambda: lsq.k_cross_attention(q, kv, off, ln, out, B, k, H, int(lens.max()))))
 
     def topk_case(name, M, V, k):
         logits = rnd(M, V, dtype=torch.float32, scale=0.64)

@@ -174,10 +174,11 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
 
 /* Cross-attention: the `beam` rows of sentence b attend over that sentence's
  * src_len[b] encoder positions, kv packed as [sum(src_len), 2d] = [K | V] with
- * sentence b starting at row src_off[b] (both int32, device). */
+ * sentence b starting at row src_off[b] (both int32, device).  max_src_len: a
+ * host-side upper bound of src_len[] (sizes an LDS buffer; at most 3840). */
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off,
                           const int32_t* src_len, void* out, int batch, int beam, int heads, int d,
-                          void* stream);
+                          int max_src_len, void* stream);
 
 /* Retrieve stage of the hierarchical search (sec. 2.2) made exact: per row r of
  * logits [M,V], cand = score[r] + log_softmax(logits[r,:]) and the k best

@@ -51,7 +51,7 @@ def load_library() -> C.CDLL:
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
-        "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_row_topk": [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
         "lsq_k_beam_refine": [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
         "lsq_k_cache_reorder": [i32, vp, vp, i32, i32, i32, i32, i32, i32, vp],
@@ -209,10 +209,10 @@ def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:
                                                _stream()))
 
 
-def k_cross_attention(q, kv, src_off, src_len, out, batch: int, beam: int, heads: int) -> None:
+def k_cross_attention(q, kv, src_off, src_len, out, batch: int, beam: int, heads: int, max_src_len: int) -> None:
     d = q.shape[1]
     _check(load_library().lsq_k_cross_attention(_dt(q), _p(q), _p(kv), _p(src_off), _p(src_len), _p(out), batch,
-                                                beam, heads, d, _stream()))
+                                                beam, heads, d, max_src_len, _stream()))
 
 
 def k_row_topk(logits, score, finished, k: int, eos: int, out_score, out_idx) -> None:

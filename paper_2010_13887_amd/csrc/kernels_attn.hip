@@ -107,47 +107,107 @@ __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict
   attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63);
 }
 
-// Cross-attention: the NQ beams of one sentence share each key/value load.  kv rows are [K | V].
-// One workgroup of 4 wavefronts per (sentence, head): wavefront w takes keys w, w+4, w+8, ...
-// (source sentences have very different lengths and a workgroup's time is set by its key loop,
-// so the loop is cut four ways); the four partial softmax states are merged through LDS.
+// Cross-attention: the NQ beams of one sentence share every key/value load.  kv rows are [K | V].
+// One workgroup of 256 threads per (sentence, head).  Source sentences are short (tens of keys),
+// so the work is organised to keep the fixed cost per workgroup small rather than to stream:
+//   1. scores: thread (key slot, 8-element chunk) dots its K chunk with the NQ query chunks; the
+//      chunks of a key are summed by shuffles; scaled scores go to LDS [NQ][keys];
+//   2. softmax: one wavefront per query takes max and sum over the keys and leaves exp(s - max) in
+//      LDS (masked keys are simply not there);
+//   3. values: 8 lanes per (query, 8-element chunk) split the keys, each summing p[key] * V chunk
+//      with 16-byte loads; the 8 partial sums are added by shuffles and divided by the sum.
+// smax = the longest source sentence of the batch bounds the LDS score buffer (NQ * smax floats).
 template <typename T, int DH, int NQ>
 __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restrict__ q, const T* __restrict__ kv,
                                                               const int32_t* __restrict__ off,
                                                               const int32_t* __restrict__ len,
                                                               T* __restrict__ out, int batch, int beam,
-                                                              int first, int H, int d, float scale) {
-  constexpr int LPK = DH / 8;
-  __shared__ float sm[4][NQ], sl[4][NQ], sacc[4][NQ][DH];
+                                                              int first, int H, int d, int smax, float scale) {
+  constexpr int LPK = DH / 8;       // lanes per key in phase 1
+  constexpr int KP = 256 / LPK;     // keys per pass
+  extern __shared__ float sc[];     // [NQ][smax] scores, then exp(score - max)
+  __shared__ float inv[NQ];
   const int b = blockIdx.x / H, h = blockIdx.x % H;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const T* qp[NQ];
-#pragma unroll
-  for (int n = 0; n < NQ; ++n) qp[n] = q + ((size_t)b * beam + first + n) * d + h * DH;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_keys = len[b];
   const T* K = kv + (size_t)off[b] * 2 * d + h * DH;
-  float m[NQ], l[NQ], acc[NQ][8];
-  attend_partial<T, DH, NQ>(qp, K, K + d, 2 * d, len[b], scale, wave, 4, lane, m, l, acc);
-  if (lane < LPK) {
+  const T* V = K + d;
+  const long stride = 2 * d;
+  {
+    const int c = tid % LPK;
+    float qv[NQ][8];
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      if (lane == 0) { sm[wave][n] = m[n]; sl[wave][n] = l[n]; }
+    for (int n = 0; n < NQ; ++n) Vec8<T>::load(q + ((size_t)b * beam + first + n) * d + h * DH + c * 8, qv[n]);
+    // four key rows are requested before any is used: a sentence of up to 4*KP keys costs one
+    // round trip to memory here, not four
+    for (int j0 = tid / LPK; j0 < n_keys; j0 += 4 * KP) {
+      float kk[4][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sacc[wave][n][lane * 8 + i] = acc[n][i];
+      for (int u = 0; u < 4; ++u) {
+        const int j = min(j0 + u * KP, n_keys - 1);
+        Vec8<T>::load(K + (long)j * stride + c * 8, kk[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = j0 + u * KP;
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) {
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) s += qv[n][i] * kk[u][i];
+#pragma unroll
+          for (int o = 1; o < LPK; o <<= 1) s += __shfl_xor(s, o, kWave);
+          if (c == 0 && j < n_keys) sc[n * smax + j] = s * scale;
+        }
+      }
     }
   }
   __syncthreads();
-  // thread (n, e) finishes element e of beam n
-  for (int idx = threadIdx.x; idx < NQ * DH; idx += 256) {
-    const int n = idx / DH, e = idx % DH;
-    float mm = fmaxf(fmaxf(sm[0][n], sm[1][n]), fmaxf(sm[2][n], sm[3][n]));
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      float c = (sm[w][n] == -INFINITY) ? 0.f : __expf(sm[w][n] - mm);
-      num += sacc[w][n][e] * c;
-      den += sl[w][n] * c;
+  for (int n = wave; n < NQ; n += 4) {
+    float mx = -INFINITY;
+    for (int j = lane; j < n_keys; j += 64) mx = fmaxf(mx, sc[n * smax + j]);
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int j = lane; j < n_keys; j += 64) {
+      const float p = __expf(sc[n * smax + j] - mx);
+      sc[n * smax + j] = p;
+      sum += p;
     }
-    out[((size_t)b * beam + first + n) * d + h * DH + e] = (T)(num / den);
+    sum = wave_sum(sum);
+    if (lane == 0) inv[n] = 1.0f / sum;
+  }
+  __syncthreads();
+  // unit (query n, 8-element chunk c) is served by 8 adjacent lanes, lane ks taking keys ks, ks+8, ...
+  {
+    const int ks = tid & 7;
+    for (int unit = tid >> 3; unit < NQ * LPK; unit += 32) {
+      const int n = unit / LPK, c = unit % LPK;
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int j0 = ks; j0 < n_keys; j0 += 32) {   // four value rows in flight per lane
+        float vv[4][8], pp[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int j = j0 + 8 * u;
+          const int jc = min(j, n_keys - 1);
+          Vec8<T>::load(V + (long)jc * stride + c * 8, vv[u]);
+          pp[u] = j < n_keys ? sc[n * smax + jc] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[i] += pp[u] * vv[u][i];
+      }
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += __shfl_xor(acc[i], o, kWave);
+      if (ks == 0) {
+        const float r = inv[n];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= r;
+        Vec8<T>::store(out + ((size_t)b * beam + first + n) * d + h * DH + c * 8, acc);
+      }
+    }
   }
 }
 
@@ -201,37 +261,40 @@ hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const
 
 template <typename T, int NQ>
 static hipError_t cross_nq(const T* q, const T* kv, const int32_t* off, const int32_t* len, T* out,
-                           int batch, int beam, int first, int H, int d, hipStream_t s) {
+                           int batch, int beam, int first, int H, int d, int smax, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
   dim3 g(batch * H), b(256);
-  LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ><<<g, b, 0, s>>>(q, kv, off, len, out, batch, beam, first, H, d, scale)));
+  const size_t lds = (size_t)NQ * smax * sizeof(float);
+  if (lds > 60 * 1024) return hipErrorInvalidValue;   // source sentences longer than ~3800 tokens: not supported
+  LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ><<<g, b, lds, s>>>(q, kv, off, len, out, batch, beam, first, H, d, smax, scale)));
   return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t cross_t(const T* q, const T* kv, const int32_t* off, const int32_t* len, T* out, int batch,
-                          int beam, int H, int d, hipStream_t s) {
+                          int beam, int H, int d, int smax, hipStream_t s) {
   // beams are handled in groups of 4, 2 or 1 queries per wavefront
   int first = 0;
   while (first < beam) {
     int left = beam - first;
     hipError_t e;
-    if (left >= 4) { e = cross_nq<T, 4>(q, kv, off, len, out, batch, beam, first, H, d, s); first += 4; }
-    else if (left >= 2) { e = cross_nq<T, 2>(q, kv, off, len, out, batch, beam, first, H, d, s); first += 2; }
-    else { e = cross_nq<T, 1>(q, kv, off, len, out, batch, beam, first, H, d, s); first += 1; }
+    if (left >= 4) { e = cross_nq<T, 4>(q, kv, off, len, out, batch, beam, first, H, d, smax, s); first += 4; }
+    else if (left >= 2) { e = cross_nq<T, 2>(q, kv, off, len, out, batch, beam, first, H, d, smax, s); first += 2; }
+    else { e = cross_nq<T, 1>(q, kv, off, len, out, batch, beam, first, H, d, smax, s); first += 1; }
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
-                                  const int32_t* len, void* out, int batch, int beam, int H, int d,
+                                  const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
                                   hipStream_t s) {
   if (batch <= 0) return hipSuccess;
+  if (smax < 1) return hipErrorInvalidValue;
   if (dtype == DT_F16)
-    return cross_t<half_t>((const half_t*)q, (const half_t*)kv, off, len, (half_t*)out, batch, beam, H, d, s);
-  return cross_t<float>((const float*)q, (const float*)kv, off, len, (float*)out, batch, beam, H, d, s);
+    return cross_t<half_t>((const half_t*)q, (const half_t*)kv, off, len, (half_t*)out, batch, beam, H, d, smax, s);
+  return cross_t<float>((const float*)q, (const float*)kv, off, len, (float*)out, batch, beam, H, d, smax, s);
 }
 
 template <typename T>

@@ -121,8 +121,10 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
   constexpr int AV = BM * VPR / 256, BV = BN * VPR / 256;   // vectors per thread
   static_assert(AV >= 1 && BV >= 1, "tile too small");
-  __shared__ __attribute__((aligned(16))) half_t As[2][BM * LDK];
-  __shared__ __attribute__((aligned(16))) half_t Bs[2][BN * LDK];
+  // LDS comes from the launch (dynamic), so that tiles above the 64 KB static limit can be used
+  extern __shared__ __attribute__((aligned(16))) half_t lds_tiles[];
+  half_t(*As)[BM * LDK] = reinterpret_cast<half_t(*)[BM * LDK]>(lds_tiles);
+  half_t(*Bs)[BN * LDK] = reinterpret_cast<half_t(*)[BN * LDK]>(lds_tiles + 2 * BM * LDK);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long tp = out.tpos ? *out.tpos : 0;
@@ -217,20 +219,30 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
         else acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[i], af[i], acc[0][0], 0, 0, 0);
       }
     } else {
+      // fragments of k-step i+1 are fetched from LDS while the MFMAs of k-step i run
+      half8_t af[2][TM], bf[2][TN];
 #pragma unroll
-      for (int ks = 0; ks < BK; ks += 16) {
-        half8_t af[TM], bf[TN];
+      for (int i = 0; i < TM; ++i)
+        af[0][i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + fk]);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + ks + fk]);
+      for (int j = 0; j < TN; ++j)
+        bf[0][j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + fk]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          bf[j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + ks + fk]);
+      for (int s = 0; s < KS; ++s) {
+        const int cur = s & 1, nxt = cur ^ 1;
+        if (s + 1 < KS) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            af[nxt][i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + (s + 1) * 16 + fk]);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            bf[nxt][j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + (s + 1) * 16 + fk]);
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
       }
     }
   };
@@ -383,17 +395,35 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, con
     gemm_f16_skinny_kernel<TM, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
 }
 
+template <int BM, int BN, int BK>
+constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * (BK + 8) * sizeof(half_t); }
+
+// Launch with the tile's LDS size; sizes above the default 64 KB limit are opted into once per kernel.
+template <typename Kern>
+static void launch_tiles(Kern kern, size_t lds, dim3 grid, hipStream_t s, const half_t* A, const half_t* B,
+                         const half_t* bias, const GemmOut& out, int M, int N, int K, int relu, int vec_ok) {
+  if (lds > 64 * 1024) {
+    static bool raised = false;   // one flag per instantiation of this template, i.e. per kernel
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+  }
+  kern<<<grid, dim3(256), lds, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int D>
 static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
                     int K, int relu, int vec_ok, hipStream_t s) {
-  dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM)), blk(256);
+  dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM));
+  constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
   const bool tail = (K % BK) != 0;
   if (out.f32_out) {
-    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
-    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
   } else {
-    if (tail) gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
-    else gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
   }
 }
 
@@ -428,7 +458,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
     return hipGetLastError();
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
-  gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, 0, s>>>(
+  gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, gemm_lds_bytes<64, 64, 64>(), s>>>(
       (const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok);
   return hipGetLastError();
 }
@@ -459,7 +489,7 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   else if (tiles128 >= 256)
-    run_f16<128, 128, 32, 64, 64, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, relu, vec_ok, s);   // 72 KB of LDS, two workgroups per CU
   else
     run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
   return hipGetLastError();

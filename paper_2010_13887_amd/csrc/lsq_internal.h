@@ -62,8 +62,9 @@ hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
                                  int rows, int H, int d, int T, int nkeys_base, const int32_t* tp,
                                  hipStream_t s);
+// smax: an upper bound of len[] known to the host (sizes the LDS score buffer)
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
-                                  const int32_t* len, void* out, int batch, int beam, int H, int d,
+                                  const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
                                   hipStream_t s);
 hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent,
                                     const int32_t* off, const int32_t* len, void* out, int rows, int H,

@@ -305,7 +305,7 @@ int launch_step(int B) {
     if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
-                                  at<int32_t>(p.src_len), ctx, B, k, H, d, s));
+                                  at<int32_t>(p.src_len), ctx, B, k, H, d, g.max_len, s));
     if (int rc = sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
     if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, x, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
@@ -757,11 +757,12 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
 }
 
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off, const int32_t* src_len,
-                          void* out, int batch, int beam, int heads, int d, void* stream) {
+                          void* out, int batch, int beam, int heads, int d, int max_src_len, void* stream) {
   KCHK(q && kv && src_off && src_len && out, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(batch >= 0 && beam >= 1 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "shape");
-  KRUN(launch_cross_attention(dtype, q, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
+  KCHK(max_src_len >= 1 && (size_t)std::min(beam, 4) * max_src_len * 4 <= 60 * 1024, "max_src_len");
+  KRUN(launch_cross_attention(dtype, q, kv, src_off, src_len, out, batch, beam, heads, d, max_src_len, (hipStream_t)stream));
 }
 
 int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int32_t* finished, int M, int V, int k,

@@ -125,7 +125,7 @@ def test_cross_attention(env, lens, beam, H, dh, half):
     td = torch.float16 if half else torch.float32
     out = torch.full((B * beam, d), 7.0, dtype=td, device="cuda")
     lsq.k_cross_attention(_dev(torch, q, td), _dev(torch, kv, td), _dev(torch, off), _dev(torch, np.array(lens, np.int32)),
-                          out, B, beam, H)
+                          out, B, beam, H, max(lens))
     ref = np.concatenate([O.attention(q[b * beam:(b + 1) * beam].astype(np.float64),
                                       kv[off[b]:off[b + 1], :d].astype(np.float64),
                                       kv[off[b]:off[b + 1], d:].astype(np.float64), H) for b in range(B)])
