@@ -30,25 +30,38 @@ __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
   }
-  for (int j = j0 + g * jstep; j < nkeys; j += KPI * jstep) {
-    float kv[8], vv[8];
-    Vec8<T>::load(K + (long)j * stride + c * 8, kv);
-    Vec8<T>::load(V + (long)j * stride + c * 8, vv);
+  // U keys per lane group are requested (K and V rows) before any is used, so a cache of n
+  // positions costs n / (KPI * U) round trips to memory instead of n / KPI.
+  constexpr int U = 4;
+  const int step = KPI * jstep;
+  for (int jb = j0 + g * jstep; jb < nkeys; jb += U * step) {
+    float kv[U][8], vv[U][8];
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      float s = 0.f;
+    for (int u = 0; u < U; ++u) {
+      const int j = min(jb + u * step, nkeys - 1);   // past the end: a repeated row, not used
+      Vec8<T>::load(K + (long)j * stride + c * 8, kv[u]);
+      Vec8<T>::load(V + (long)j * stride + c * 8, vv[u]);
+    }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) s += q[n][i] * kv[i];
+    for (int u = 0; u < U; ++u) {
+      if (jb + u * step < nkeys) {
 #pragma unroll
-      for (int o = 1; o < LPK; o <<= 1) s += __shfl_xor(s, o, kWave);
-      s *= scale;
-      float mn = fmaxf(m[n], s);
-      float corr = __expf(m[n] - mn);   // m = -inf on the first key: exp(-inf) = 0
-      float p = __expf(s - mn);
-      l[n] = l[n] * corr + p;
+        for (int n = 0; n < NQ; ++n) {
+          float s = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc[n][i] = acc[n][i] * corr + p * vv[i];
-      m[n] = mn;
+          for (int i = 0; i < 8; ++i) s += q[n][i] * kv[u][i];
+#pragma unroll
+          for (int o = 1; o < LPK; o <<= 1) s += __shfl_xor(s, o, kWave);
+          s *= scale;
+          float mn = fmaxf(m[n], s);
+          float corr = __expf(m[n] - mn);   // m = -inf on the first key: exp(-inf) = 0
+          float p = __expf(s - mn);
+          l[n] = l[n] * corr + p;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[n][i] = acc[n][i] * corr + p * vv[u][i];
+          m[n] = mn;
+        }
+      }
     }
   }
   // merge the KPI lane groups (butterfly: every group ends with the total)
