@@ -19,6 +19,16 @@
  * Call order:
  *   lsq_workspace_bytes -> lsq_set_workspace -> lsq_init ->
  *   ( lsq_encode -> lsq_decode_step* -> lsq_get_beams )* -> lsq_free
+ *
+ * Two model kinds are accepted (blob header): the encoder-decoder Transformer
+ * decoded with beam search, and a decoder-only model (pre-LN, tanh-GELU,
+ * learned positions; the paper's GPT column and sampling decoding, Table 1 and
+ * sec. 3.4) decoded with top-k sampling at beam 1.  For the latter lsq_encode
+ * takes the prompts (all of one length P), fills the cache from their first
+ * P-1 tokens, and each lsq_decode_step samples one token per row from a Philox
+ * stream keyed by the blob's seed (counter = step, row) until cap_extra tokens
+ * have been produced; lsq_get_beams returns those tokens and the sum of their
+ * log-probabilities under the k-way softmax.
  */
 #ifndef LSQ_H
 #define LSQ_H
@@ -130,7 +140,7 @@ enum {
   LSQ_DBG_LEN = 3,        /* int32 [M]                                                 */
   LSQ_DBG_FINISHED = 4,   /* int32 [M]                                                 */
   LSQ_DBG_PARENT = 5,     /* int32 [M]         parent beam (0..beam-1) chosen in the last step the sentence took part in */
-  LSQ_DBG_CAND_SCORE = 6, /* float [M, beam]   per-row top-k scores of the last step   */
+  LSQ_DBG_CAND_SCORE = 6, /* float [M, beam]   per-row top-k scores of the last step ([M, sample_topk] logits for a sampling model) */
   LSQ_DBG_CAND_IDX = 7,   /* int32 [M, beam]   per-row top-k tokens (-1 = none)        */
   LSQ_DBG_HIDDEN = 8,     /* float [M, d]      decoder output of the last step         */
   LSQ_DBG_MEMORY = 9,     /* float [sum(src_lens), d] encoder output, sentences packed */
@@ -152,6 +162,7 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes);
  * unrounded, as the vocabulary-logit GEMM does.  K % 8 == 0 for float16. */
 #define LSQ_GEMM_RELU 1
 #define LSQ_GEMM_F32_OUT 2
+#define LSQ_GEMM_GELU 4    /* tanh-GELU instead of ReLU */
 int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* C, int M, int N,
                int K, int flags, void* stream);
 

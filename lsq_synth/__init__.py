@@ -36,6 +36,13 @@ Tensor order for arch 0 (encoder-decoder)::
                        ln2_g[d] ln2_b[d]
                        W1[d,F] b1[F] W2[F,d] b2[d] ln3_g[d] ln3_b[d]
 
+Tensor order for arch 1 (decoder-only, pre-LN, learned positions)::
+
+    E[vocab, d]  P[max_pos, d]
+    per layer: ln1_g[d] ln1_b[d] Wqkv[d,3d] bqkv[3d] Wo[d,d] bo[d]
+               ln2_g[d] ln2_b[d] W1[d,F] b1[F] W2[F,d] b2[d]
+    lnf_g[d] lnf_b[d]
+
 Columns of Wqkv are [Q | K | V]; columns of Wkv_c are [K | V]; head h owns
 columns h*dh .. (h+1)*dh of each part.
 """
@@ -81,8 +88,17 @@ def tensor_list(hp: HParams):
     """(name, shape) of every tensor in file order."""
     d, F, V = hp.d_model, hp.d_ffn, hp.vocab
     out = [("E", (V, d))]
+    if hp.arch == 1:
+        out.append(("P", (hp.max_pos, d)))
+        for i in range(hp.n_dec):
+            p = f"dec{i}."
+            out += [(p + "ln1_g", (d,)), (p + "ln1_b", (d,)), (p + "Wqkv", (d, 3 * d)), (p + "bqkv", (3 * d,)),
+                    (p + "Wo", (d, d)), (p + "bo", (d,)), (p + "ln2_g", (d,)), (p + "ln2_b", (d,)),
+                    (p + "W1", (d, F)), (p + "b1", (F,)), (p + "W2", (F, d)), (p + "b2", (d,))]
+        out += [("lnf_g", (d,)), ("lnf_b", (d,))]
+        return out
     if hp.arch != 0:
-        raise NotImplementedError("only the encoder-decoder layout is generated")
+        raise NotImplementedError("unknown architecture")
     for i in range(hp.n_enc):
         p = f"enc{i}."
         out += [(p + "Wqkv", (d, 3 * d)), (p + "bqkv", (3 * d,)), (p + "Wo", (d, d)), (p + "bo", (d,)),
@@ -188,6 +204,7 @@ BIG = dict(n_enc=6, n_dec=6, d_model=1024, n_heads=16, d_ffn=4096, vocab=32000, 
 def workload(name: str, *, batch: int | None = None, seed: int = INPUT_SEED) -> Workload:
     """The named synthetic workloads (stand-ins for the paper's WMT14 En-De buckets).
 
+    gpt2s : decoder-only GPT-2-small shape, fp16, top-8 sampling (see below).
     tiny : 1+1 layers, d 64, 4 heads, FFN 256, vocab 1000, fp32; batch 2, lengths 5 and 8,
            beam 4, max target length 8.
     base : Transformer-base shape, fp16; batch 8, lengths U{10..60}, beam 4, cap = len + 50.
@@ -213,6 +230,14 @@ def workload(name: str, *, batch: int | None = None, seed: int = INPUT_SEED) -> 
         lens = _lognormal_lens(rng, b)
         return Workload(name, hp, b, 4, int(lens.max()) + hp.cap_extra, lens,
                         _ids(rng, lens, hp.vocab, hp.pad_id))
+    if name == "gpt2s":
+        # decoder-only, GPT-2-small shape: 12 layers, d 768, 12 heads, FFN 3072, tanh-GELU, pre-LN,
+        # vocab 50257, learned positions; batch 32 prompts of 64 random ids, 128 sampled tokens (top-8)
+        hp = HParams(arch=1, n_enc=0, n_dec=12, d_model=768, n_heads=12, d_ffn=3072, vocab=50257, dtype=1,
+                     max_pos=256, act=1, norm=1, sample_topk=8, cap_extra=128)
+        b = batch or 32
+        lens = np.full(b, 64, np.int32)
+        return Workload(name, hp, b, 1, 64 + 128, lens, _ids(rng, lens, hp.vocab, hp.pad_id))
     raise KeyError(name)
 
 

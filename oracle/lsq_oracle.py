@@ -74,7 +74,7 @@ class Model:
          self.sample_topk) = struct.unpack_from("<17i", blob, 8)
         self.alpha, self.eps = struct.unpack_from("<2f", blob, 76)
         self.seed, total = struct.unpack_from("<2Q", blob, 88)
-        if ver != 1 or total != len(blob) or self.arch != 0 or self.norm != 0 or self.act != 0:
+        if ver != 1 or total != len(blob) or (self.arch, self.norm, self.act) not in ((0, 0, 0), (1, 1, 1)):
             raise ValueError("unsupported blob")
         if self.d % self.H:
             raise ValueError("d_model not divisible by heads")
@@ -96,7 +96,20 @@ class Model:
             return a
 
         self.E = take(V, d)
-        self.enc = []
+        self.enc, self.dec = [], []
+        if self.arch == 1:      # decoder-only: learned positions, pre-LN blocks, final LayerNorm
+            self.P = take(self.max_pos, d)
+            for _ in range(self.n_dec):
+                L = {}
+                L["ln1_g"], L["ln1_b"] = take(d), take(d)
+                L["Wqkv"], L["bqkv"], L["Wo"], L["bo"] = take(d, 3 * d), take(3 * d), take(d, d), take(d)
+                L["ln2_g"], L["ln2_b"] = take(d), take(d)
+                L["W1"], L["b1"], L["W2"], L["b2"] = take(d, F), take(F), take(F, d), take(d)
+                self.dec.append(L)
+            self.lnf_g, self.lnf_b = take(d), take(d)
+            if pos != len(blob):
+                raise ValueError("blob size does not match its header")
+            return
         for _ in range(self.n_enc):
             L = {}
             L["Wqkv"], L["bqkv"], L["Wo"], L["bo"] = take(d, 3 * d), take(3 * d), take(d, d), take(d)
@@ -104,7 +117,6 @@ class Model:
             L["W1"], L["b1"], L["W2"], L["b2"] = take(d, F), take(F), take(F, d), take(d)
             L["ln2_g"], L["ln2_b"] = take(d), take(d)
             self.enc.append(L)
-        self.dec = []
         for _ in range(self.n_dec):
             L = {}
             L["Wqkv"], L["bqkv"], L["Wo"], L["bo"] = take(d, 3 * d), take(3 * d), take(d, d), take(d)
@@ -412,3 +424,142 @@ def translate(model, src_ids, src_lens, beam, max_len, max_steps=None, trace=Non
         if active == 0 or (max_steps is not None and steps >= max_steps):
             break
     return finalize(model, st), st
+
+
+# ----------------------------------------------------------------------------
+# decoder-only model with top-k sampling (the paper's GPT column of Table 1 and
+# the sampling decoding of sec. 3.4; the paper gives no definitions, so: pre-LN
+# blocks x += Attn(LN1 x), x += MLP(LN2 x), final LN, tanh-GELU, learned
+# positions, tied output embedding; sampling: the k largest logits in the order
+# (logit descending, token ascending), p = softmax over those k,
+# u = (philox4x32_10(key = seed, counter = (step, row, 0, 0))[0] >> 8) * 2^-24,
+# token = the first j whose cumulative p exceeds u * sum(p))
+# ----------------------------------------------------------------------------
+def gelu_tanh(x):
+    c = x.dtype.type(np.sqrt(2.0 / np.pi))
+    return x.dtype.type(0.5) * x * (x.dtype.type(1) + np.tanh(c * (x + x.dtype.type(0.044715) * x * x * x)))
+
+
+def philox4x32_10(counter, key):
+    """Philox-4x32 with 10 rounds (Salmon et al., SC'11): counter = 4 and key = 2 uint32 words."""
+    M0, M1, W0, W1 = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85
+    c = [int(v) & 0xFFFFFFFF for v in counter]
+    k = [int(v) & 0xFFFFFFFF for v in key]
+    for _ in range(10):
+        p0, p1 = M0 * c[0], M1 * c[2]
+        c = [((p1 >> 32) ^ c[1] ^ k[0]) & 0xFFFFFFFF, p1 & 0xFFFFFFFF,
+             ((p0 >> 32) ^ c[3] ^ k[1]) & 0xFFFFFFFF, p0 & 0xFFFFFFFF]
+        k = [(k[0] + W0) & 0xFFFFFFFF, (k[1] + W1) & 0xFFFFFFFF]
+    return c
+
+
+def sample_uniform(seed, step, row):
+    """The uniform number in [0, 1) that decides the token of (step, row)."""
+    word = philox4x32_10((step, row, 0, 0), (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))[0]
+    return np.float32((word >> 8) * 2.0 ** -24)
+
+
+def sample_topk(logits, k, u):
+    """One draw: returns (token, log-probability under the k-way softmax, gap).  gap says how far the
+    decision is from changing: the smallest of the logit gap between the k-th and (k+1)-th token (the
+    candidate set), the logit gaps between the chosen candidate and its neighbours in the ranking (a
+    swap of two ranks exchanges their probability segments) and the distance of the draw from the
+    nearest cumulative-probability boundary."""
+    V = logits.shape[0]
+    order = np.lexsort((np.arange(V), -logits))[:k + 1]
+    top = order[:k]
+    l = logits[top].astype(np.float32)
+    e = np.exp(l - l[0])
+    cum = np.cumsum(e, dtype=np.float32)
+    target = np.float32(u) * cum[-1]
+    j = int(np.searchsorted(cum, target, side="right"))
+    j = min(j, k - 1)
+    edge = float(np.min(np.abs(cum.astype(np.float64) - float(target))) / float(cum[-1]))
+    gap = float(logits[order[k - 1]] - logits[order[k]]) if len(order) > k else np.inf
+    if j > 0:
+        gap = min(gap, float(l[j - 1] - l[j]))
+    if j < k - 1:
+        gap = min(gap, float(l[j] - l[j + 1]))
+    return int(top[j]), float(np.log(e[j] / cum[-1])), min(gap, edge)
+
+
+def gpt_forward_full(model, ids):
+    """Logits after the last token of ``ids`` for ONE sequence, every position recomputed with a
+    causal mask and no cache."""
+    n, d = len(ids), model.d
+    x = model.store(model.E[np.asarray(ids)] + model.P[:n])
+    causal = np.tril(np.ones((n, n), bool))
+    for L in model.dec:
+        y = model.store(layer_norm(x, L["ln1_g"], L["ln1_b"], model.eps))
+        qkv = model.store(y @ L["Wqkv"] + L["bqkv"])
+        ctx = model.store(attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], model.H, causal))
+        x = model.store(x + (ctx @ L["Wo"] + L["bo"]))
+        y = model.store(layer_norm(x, L["ln2_g"], L["ln2_b"], model.eps))
+        h = model.store(gelu_tanh(y @ L["W1"] + L["b1"]))
+        x = model.store(x + (h @ L["W2"] + L["b2"]))
+    y = model.store(layer_norm(x[-1], model.lnf_g, model.lnf_b, model.eps))
+    return y @ model.E.T
+
+
+class GptState:
+    def __init__(self, model, prompts, max_len):
+        prompts = np.asarray(prompts, np.int32)
+        self.B, self.P = prompts.shape
+        self.T = max_len
+        self.tokens = np.full((self.B, max_len + 1), model.pad, np.int32)
+        self.tokens[:, :self.P] = prompts
+        self.pos = self.P - 1            # position of the token fed to the next step
+        self.t = 0
+        self.logp = np.zeros(self.B, model.ctype)
+        self.Kc = [np.zeros((self.B, max_len, model.d), model.ctype) for _ in model.dec]
+        self.Vc = [np.zeros((self.B, max_len, model.d), model.ctype) for _ in model.dec]
+
+
+def gpt_rows(model, st, ids, positions, write_cache=True):
+    """Runs the blocks for one position per sequence (ids [B], common position), K/V cached."""
+    d, p = model.d, positions
+    x = model.store(model.E[ids] + model.P[p])
+    for l, L in enumerate(model.dec):
+        y = model.store(layer_norm(x, L["ln1_g"], L["ln1_b"], model.eps))
+        qkv = model.store(y @ L["Wqkv"] + L["bqkv"])
+        st.Kc[l][:, p] = qkv[:, d:2 * d]
+        st.Vc[l][:, p] = qkv[:, 2 * d:]
+        ctx = np.empty_like(x)
+        for r in range(x.shape[0]):
+            ctx[r] = attention(qkv[r:r + 1, :d], st.Kc[l][r, :p + 1], st.Vc[l][r, :p + 1], model.H)[0]
+        x = model.store(x + (model.store(ctx) @ L["Wo"] + L["bo"]))
+        y = model.store(layer_norm(x, L["ln2_g"], L["ln2_b"], model.eps))
+        h = model.store(gelu_tanh(y @ L["W1"] + L["b1"]))
+        x = model.store(x + (h @ L["W2"] + L["b2"]))
+    return x
+
+
+def gpt_prefill(model, st):
+    """Feeds the prompt except its last token, filling the cache for positions 0 .. P-2."""
+    for p in range(st.P - 1):
+        gpt_rows(model, st, st.tokens[:, p], p)
+
+
+def gpt_step_logits(model, st):
+    x = gpt_rows(model, st, st.tokens[:, st.pos], st.pos)
+    y = model.store(layer_norm(x, model.lnf_g, model.lnf_b, model.eps))
+    return y @ model.E.T
+
+
+def gpt_advance(model, st, tokens, logps):
+    st.pos += 1
+    st.tokens[:, st.pos] = tokens
+    st.logp = (st.logp + np.asarray(logps, model.ctype)).astype(model.ctype)
+    st.t += 1
+
+
+def generate(model, prompts, n_new, max_len, trace=None):
+    st = GptState(model, prompts, max_len)
+    gpt_prefill(model, st)
+    for _ in range(n_new):
+        logits = gpt_step_logits(model, st)
+        picks = [sample_topk(logits[r], model.sample_topk, sample_uniform(model.seed, st.t, r)) for r in range(st.B)]
+        if trace is not None:
+            trace.append(dict(logits=logits, picks=picks))
+        gpt_advance(model, st, [p[0] for p in picks], [p[1] for p in picks])
+    return st.tokens[:, st.P:st.P + n_new].copy(), st.logp.copy(), st

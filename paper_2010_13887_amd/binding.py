@@ -178,13 +178,15 @@ def _p(t) -> int:
     return t.data_ptr()
 
 
-def k_gemm(A, B, bias, C_out, relu: bool = False) -> None:
-    """C_out = act(A . B^T + bias); a float32 C_out with float16 inputs keeps the accumulators unrounded."""
+def k_gemm(A, B, bias, C_out, relu: bool = False, gelu: bool = False) -> None:
+    """C_out = act(A . B^T + bias), act = ReLU, tanh-GELU or none; a float32 C_out with float16 inputs
+    keeps the accumulators unrounded."""
     import torch
     M, K = A.shape
     N = B.shape[0]
     assert B.shape[1] == K and tuple(C_out.shape) == (M, N)
-    flags = int(relu) | (2 if (A.dtype == torch.float16 and C_out.dtype == torch.float32) else 0)
+    assert not (relu and gelu)
+    flags = int(relu) | (4 if gelu else 0) | (2 if (A.dtype == torch.float16 and C_out.dtype == torch.float32) else 0)
     assert flags & 2 or C_out.dtype == A.dtype
     _check(load_library().lsq_k_gemm(_dt(A), _p(A), _p(B), _p(bias), _p(C_out), M, N, K, flags, _stream()))
 

@@ -232,15 +232,17 @@ __global__ void __launch_bounds__(256) encoder_attention_kernel(const T* __restr
                                                                 const int32_t* __restrict__ off,
                                                                 const int32_t* __restrict__ len,
                                                                 T* __restrict__ out, int rows, int H, int d,
-                                                                float scale) {
+                                                                int causal, float scale) {
   int w = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= rows * H) return;
   int r = w / H, h = w % H;
   int b = row_sent[r];
+  // causal (decoder-only prefill): row r sits at position r - off[b] and sees keys up to itself
+  const int nk = causal ? r - off[b] + 1 : len[b];
   const T* qp[1] = {qkv + (size_t)r * 3 * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
   const T* K = qkv + (size_t)off[b] * 3 * d + d + h * DH;
-  attend<T, DH, 1>(qp, K, K + d, 3 * d, len[b], scale, op, threadIdx.x & 63);
+  attend<T, DH, 1>(qp, K, K + d, 3 * d, nk, scale, op, threadIdx.x & 63);
 }
 
 bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh == 128; }
@@ -312,20 +314,21 @@ hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, cons
 
 template <typename T>
 static hipError_t enc_t(const T* qkv, const int32_t* row_sent, const int32_t* off, const int32_t* len, T* out,
-                        int rows, int H, int d, hipStream_t s) {
+                        int rows, int H, int d, int causal, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
   dim3 g((rows * H + 3) / 4), b(256);
-  LSQ_DISPATCH_DH(dh, (encoder_attention_kernel<T, DH><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, scale)));
+  LSQ_DISPATCH_DH(dh, (encoder_attention_kernel<T, DH><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, causal, scale)));
   return hipGetLastError();
 }
 
 hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent, const int32_t* off,
-                                    const int32_t* len, void* out, int rows, int H, int d, hipStream_t s) {
+                                    const int32_t* len, void* out, int rows, int H, int d, int causal,
+                                    hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (dtype == DT_F16)
-    return enc_t<half_t>((const half_t*)qkv, row_sent, off, len, (half_t*)out, rows, H, d, s);
-  return enc_t<float>((const float*)qkv, row_sent, off, len, (float*)out, rows, H, d, s);
+    return enc_t<half_t>((const half_t*)qkv, row_sent, off, len, (half_t*)out, rows, H, d, causal, s);
+  return enc_t<float>((const float*)qkv, row_sent, off, len, (float*)out, rows, H, d, causal, s);
 }
 
 }  // namespace lsq

@@ -49,9 +49,8 @@ __global__ void __launch_bounds__(256) embed_last_kernel(const T* __restrict__ E
 }
 
 hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
-                             const int32_t* pos, void* x, int rows, int d, hipStream_t s) {
+                             const int32_t* pos, void* x, int rows, int d, float scale, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  float scale = sqrtf((float)d);
   dim3 g((rows + 3) / 4), b(256);
   if (dtype == DT_F16)
     embed_rows_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, ids, pos, (half_t*)x, rows, d, scale);
@@ -61,10 +60,9 @@ hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const in
 }
 
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
-                             const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp,
+                             const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp, float scale,
                              hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  float scale = sqrtf((float)d);
   dim3 g((rows + 3) / 4), b(256);
   if (dtype == DT_F16)
     embed_last_kernel<half_t><<<g, b, 0, s>>>((const half_t*)E, pe, tokens, len, (half_t*)x, rows, d, T + 1, tp, scale);
@@ -80,8 +78,12 @@ hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const in
 // P[s][rows][d] (the split-K GEMM's output, still without its bias):
 //   x <- store(LN(x + (sum_s P[s] + bias)) * g + b).
 // The slabs are added in index order, so the result is independent of how the GEMM was scheduled.
-template <typename T, int NV, int S>
-__global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restrict__ x, const float* __restrict__ P,
+// PRE (pre-LN blocks): the residual stream itself is updated, x <- store(x + sum_s P[s] + bias), and
+// the normalised copy y <- store(LN(x) * g + b) goes to a second buffer for the next sublayer's GEMM;
+// S = 0 means "no sublayer output to add", i.e. y <- LN(x).
+template <typename T, int NV, int S, bool PRE>
+__global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restrict__ x, T* __restrict__ y,
+                                                                     const float* __restrict__ P,
                                                                      const T* __restrict__ bias,
                                                                      const T* __restrict__ g, const T* __restrict__ b,
                                                                      int rows, int d, float eps) {
@@ -96,21 +98,30 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
   for (int j = 0; j < NV; ++j) {
     int c = (j * 64 + lane) * 8;
     if (c < d) {
-      float a[8], t[8], part[S][8];
+      float a[8], t[8], part[S > 0 ? S : 1][8];
 #pragma unroll
       for (int s = 0; s < S; ++s) Vec8<float>::load(P + s * slab + (size_t)r * d + c, part[s]);   // all in flight
-      Vec8<T>::load(bias + c, t);
+      if (S > 0) Vec8<T>::load(bias + c, t);
       Vec8<T>::load(xr + c, v[j]);
       Vec8<T>::load(g + c, gv[j]);      // gain and shift too: one round trip to memory in all
       Vec8<T>::load(b + c, bv[j]);
+      if (S > 0) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) a[i] = part[0][i];
+        for (int i = 0; i < 8; ++i) a[i] = part[0][i];
 #pragma unroll
-      for (int s = 1; s < S; ++s)
+        for (int s = 1; s < S; ++s)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] += part[s][i];
+          for (int i = 0; i < 8; ++i) a[i] += part[s][i];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { v[j][i] += a[i] + t[i]; sum += v[j][i]; }
+        for (int i = 0; i < 8; ++i) v[j][i] += a[i] + t[i];
+        if (PRE) {   // the residual stream is stored here; LayerNorm sees the stored values
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[j][i] = (float)(T)v[j][i];
+          Vec8<T>::store(xr + c, v[j]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += v[j][i];
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[j][i] = 0.f;
@@ -135,7 +146,7 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
       float o[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[i] = gv[j][i] * (v[j][i] * rstd) + bv[j][i];
-      Vec8<T>::store(xr + c, o);
+      Vec8<T>::store((PRE ? y + (size_t)r * d : xr) + c, o);
     }
   }
 }
@@ -169,46 +180,88 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_generic_kernel(T* 
   }
 }
 
-template <typename T, int S>
-static hipError_t add_layernorm_partials_s(T* x, const float* P, const T* bias, const T* g, const T* b, int rows,
-                                           int d, float eps, hipStream_t s) {
+template <typename T, int S, bool PRE>
+static hipError_t add_layernorm_partials_s(T* x, T* y, const float* P, const T* bias, const T* g, const T* b,
+                                           int rows, int d, float eps, hipStream_t s) {
   dim3 grid((rows + 3) / 4), blk(256);
   if (d <= 512)
-    add_layernorm_partials_kernel<T, 1, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 1, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
   else if (d <= 1024)
-    add_layernorm_partials_kernel<T, 2, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 2, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
   else if (d <= 2048)
-    add_layernorm_partials_kernel<T, 4, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 4, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
   else
-    add_layernorm_partials_kernel<T, 8, S><<<grid, blk, 0, s>>>(x, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 8, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
   return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t add_layernorm_partials_t(T* x, const float* P, int splits, const T* bias, const T* g, const T* b,
-                                           int rows, int d, float eps, hipStream_t s) {
-  if ((d & 7) != 0 || d > 4096 || (splits != 1 && splits != 2 && splits != 4 && splits != 8)) {
+static hipError_t add_layernorm_partials_t(T* x, T* y, const float* P, int splits, const T* bias, const T* g,
+                                           const T* b, int rows, int d, float eps, hipStream_t s) {
+  const bool pre = y != nullptr;
+  if ((d & 7) != 0 || d > 4096 || (splits != 0 && splits != 1 && splits != 2 && splits != 4 && splits != 8) ||
+      (splits == 0 && !pre)) {
+    if (pre) return hipErrorInvalidValue;   // pre-LN models need d % 8 == 0, d <= 4096, 0/1/2/4/8 slabs
     dim3 grid((rows + 3) / 4), blk(256);
     add_layernorm_partials_generic_kernel<T><<<grid, blk, 0, s>>>(x, P, splits, bias, g, b, rows, d, eps);
     return hipGetLastError();
   }
+  if (pre) {
+    switch (splits) {
+      case 0: return add_layernorm_partials_s<T, 0, true>(x, y, P, bias, g, b, rows, d, eps, s);
+      case 1: return add_layernorm_partials_s<T, 1, true>(x, y, P, bias, g, b, rows, d, eps, s);
+      case 2: return add_layernorm_partials_s<T, 2, true>(x, y, P, bias, g, b, rows, d, eps, s);
+      case 4: return add_layernorm_partials_s<T, 4, true>(x, y, P, bias, g, b, rows, d, eps, s);
+      default: return add_layernorm_partials_s<T, 8, true>(x, y, P, bias, g, b, rows, d, eps, s);
+    }
+  }
   switch (splits) {
-    case 1: return add_layernorm_partials_s<T, 1>(x, P, bias, g, b, rows, d, eps, s);
-    case 2: return add_layernorm_partials_s<T, 2>(x, P, bias, g, b, rows, d, eps, s);
-    case 4: return add_layernorm_partials_s<T, 4>(x, P, bias, g, b, rows, d, eps, s);
-    default: return add_layernorm_partials_s<T, 8>(x, P, bias, g, b, rows, d, eps, s);
+    case 1: return add_layernorm_partials_s<T, 1, false>(x, y, P, bias, g, b, rows, d, eps, s);
+    case 2: return add_layernorm_partials_s<T, 2, false>(x, y, P, bias, g, b, rows, d, eps, s);
+    case 4: return add_layernorm_partials_s<T, 4, false>(x, y, P, bias, g, b, rows, d, eps, s);
+    default: return add_layernorm_partials_s<T, 8, false>(x, y, P, bias, g, b, rows, d, eps, s);
   }
 }
 
-hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int splits, const void* bias,
+// y == nullptr: post-LN (x <- LN(x + sublayer)); y != nullptr: pre-LN (x <- x + sublayer, y <- LN(x)).
+hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const float* P, int splits, const void* bias,
                                          const void* g, const void* b, int rows, int d, float eps, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (splits < 1) return hipErrorInvalidValue;
+  if (splits < 0) return hipErrorInvalidValue;
   if (dtype == DT_F16)
-    return add_layernorm_partials_t<half_t>((half_t*)x, P, splits, (const half_t*)bias, (const half_t*)g,
-                                            (const half_t*)b, rows, d, eps, s);
-  return add_layernorm_partials_t<float>((float*)x, P, splits, (const float*)bias, (const float*)g,
+    return add_layernorm_partials_t<half_t>((half_t*)x, (half_t*)y, P, splits, (const half_t*)bias,
+                                            (const half_t*)g, (const half_t*)b, rows, d, eps, s);
+  return add_layernorm_partials_t<float>((float*)x, (float*)y, P, splits, (const float*)bias, (const float*)g,
                                          (const float*)b, rows, d, eps, s);
+}
+
+// Prefill of a decoder-only model: copies the K and V thirds of packed [rows, 3d] projections into
+// the cache rows [sentence][position] (cache row stride = T * d elements).
+template <typename T>
+__global__ void __launch_bounds__(256) scatter_kv_kernel(const T* __restrict__ qkv, const int32_t* __restrict__ sent,
+                                                         const int32_t* __restrict__ pos, T* __restrict__ Kc,
+                                                         T* __restrict__ Vc, int rows, int d, int T_) {
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const size_t dst = ((size_t)sent[r] * T_ + pos[r]) * d;
+  for (int c = (threadIdx.x & 63) * 8; c < d; c += 64 * 8) {
+    float t[8];
+    Vec8<T>::load(qkv + (size_t)r * 3 * d + d + c, t);
+    Vec8<T>::store(Kc + dst + c, t);
+    Vec8<T>::load(qkv + (size_t)r * 3 * d + 2 * d + c, t);
+    Vec8<T>::store(Vc + dst + c, t);
+  }
+}
+
+hipError_t launch_scatter_kv(int dtype, const void* qkv, const int32_t* sent, const int32_t* pos, void* Kc, void* Vc,
+                             int rows, int d, int T, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((rows + 3) / 4), blk(256);
+  if (dtype == DT_F16)
+    scatter_kv_kernel<half_t><<<grid, blk, 0, s>>>((const half_t*)qkv, sent, pos, (half_t*)Kc, (half_t*)Vc, rows, d, T);
+  else
+    scatter_kv_kernel<float><<<grid, blk, 0, s>>>((const float*)qkv, sent, pos, (float*)Kc, (float*)Vc, rows, d, T);
+  return hipGetLastError();
 }
 
 }  // namespace lsq

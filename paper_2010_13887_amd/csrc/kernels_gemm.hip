@@ -13,6 +13,13 @@ __device__ __forceinline__ void store_one(const GemmOut& o, int m, int n, float 
   reinterpret_cast<T*>(o.ptr[s])[(long)m * o.ld[s] + tp * o.tmul[s] + (n - s * o.seg_n)] = (T)v;
 }
 
+// Epilogue activation: 0 none, 1 ReLU, 2 tanh-GELU 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).
+__device__ __forceinline__ float activate(float v, int act) {
+  if (act == 1) return fmaxf(v, 0.f);
+  if (act == 2) return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+  return v;
+}
+
 // Stores four consecutive outputs (m, n..n+3) of a tile: split-K slab, vector, or element-wise
 // fallback for ragged / unaligned rows.
 template <typename OutT, bool SPLIT>
@@ -49,7 +56,7 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
 // fp32: 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread.
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                        const float* __restrict__ bias, GemmOut out, int M,
-                                                       int N, int K, int relu) {
+                                                       int N, int K, int act) {
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tid = threadIdx.x;
@@ -88,7 +95,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
       int n = n0 + tx * 4 + j;
       if (n >= N) continue;
       float v = acc[i][j] + (bias ? bias[n] : 0.f);
-      if (relu) v = fmaxf(v, 0.f);
+      v = activate(v, act);
       store_one<float>(out, m, n, v, tp);
     }
   }
@@ -113,7 +120,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
                                                        const half_t* __restrict__ bias, GemmOut out, int M,
-                                                       int N, int K, int relu, int vec_ok) {
+                                                       int N, int K, int act, int vec_ok) {
   constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
@@ -295,8 +302,7 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          v[e] = acc[i][j][vg * 4 + e] + bv[j][vg][e];
-          if (relu) v[e] = fmaxf(v[e], 0.f);
+          v[e] = activate(acc[i][j][vg * 4 + e] + bv[j][vg][e], act);
         }
         store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
       }
@@ -316,7 +322,7 @@ template <int TM, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
                                                               const half_t* __restrict__ B,
                                                               const half_t* __restrict__ bias, GemmOut out, int M,
-                                                              int N, int K, int relu, int vec_ok) {
+                                                              int N, int K, int act, int vec_ok) {
   constexpr int U = 16 / TM;   // k-steps in flight per wavefront: one round trip covers 256 / TM of K
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -377,7 +383,7 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
       const int r = vg * 4 + e;
       v[e] = (red[0][i][r][lane] + red[1][i][r][lane]) + (red[2][i][r][lane] + red[3][i][r][lane]);
       if (!SPLIT && bias) v[e] += (float)bias[min(n + e, N - 1)];
-      if (relu) v[e] = fmaxf(v[e], 0.f);
+      v[e] = activate(v[e], act);
     }
     store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
   }
@@ -387,12 +393,12 @@ constexpr int kSkinnyRows = 64;   // above this the LDS-tiled kernel is faster
 
 template <int TM>
 static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
-                       int K, int relu, int vec_ok, hipStream_t s) {
+                       int K, int act, int vec_ok, hipStream_t s) {
   dim3 grid((N + 31) / 32), blk(256);
   if (out.f32_out)
-    gemm_f16_skinny_kernel<TM, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    gemm_f16_skinny_kernel<TM, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
   else
-    gemm_f16_skinny_kernel<TM, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+    gemm_f16_skinny_kernel<TM, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
 }
 
 template <int BM, int BN, int BK>
@@ -401,7 +407,7 @@ constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * (BK + 8) * si
 // Launch with the tile's LDS size; sizes above the default 64 KB limit are opted into once per kernel.
 template <typename Kern>
 static void launch_tiles(Kern kern, size_t lds, dim3 grid, hipStream_t s, const half_t* A, const half_t* B,
-                         const half_t* bias, const GemmOut& out, int M, int N, int K, int relu, int vec_ok) {
+                         const half_t* bias, const GemmOut& out, int M, int N, int K, int act, int vec_ok) {
   if (lds > 64 * 1024) {
     static bool raised = false;   // one flag per instantiation of this template, i.e. per kernel
     if (!raised) {
@@ -409,21 +415,21 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, hipStream_t s, const 
       raised = true;
     }
   }
-  kern<<<grid, dim3(256), lds, s>>>(A, B, bias, out, M, N, K, relu, vec_ok);
+  kern<<<grid, dim3(256), lds, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int D>
 static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
-                    int K, int relu, int vec_ok, hipStream_t s) {
+                    int K, int act, int vec_ok, hipStream_t s) {
   dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM));
   constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
   const bool tail = (K % BK) != 0;
   if (out.f32_out) {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
   } else {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, relu, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
   }
 }
 
@@ -464,13 +470,13 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
 }
 
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
-                       int N, int K, bool relu, hipStream_t s) {
+                       int N, int K, int act /* activation: 0 none, 1 ReLU, 2 tanh-GELU */, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K <= 0) return hipErrorInvalidValue;
   if (dtype == DT_F32) {
     dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);
     gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, (const float*)bias, out, M, N, K,
-                                         relu ? 1 : 0);
+                                         act);
     return hipGetLastError();
   }
   if (K % 8 != 0) return hipErrorInvalidValue;
@@ -484,14 +490,14 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (M <= kSkinnyRows && K % 16 == 0) {
-    if (M <= 32) run_skinny<1>(a, b, bi, out, M, N, K, relu, vec_ok, s);
-    else run_skinny<2>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    if (M <= 32) run_skinny<1>(a, b, bi, out, M, N, K, act, vec_ok, s);
+    else run_skinny<2>(a, b, bi, out, M, N, K, act, vec_ok, s);
   } else if (M <= 32)
-    run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if (tiles128 >= 256)
-    run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, relu, vec_ok, s);   // 72 KB of LDS, two workgroups per CU
+    run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);   // 72 KB of LDS, two workgroups per CU
   else
-    run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, relu, vec_ok, s);
+    run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   return hipGetLastError();
 }
 

@@ -27,15 +27,15 @@ __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(BLOC
 row_topk_kernel(const T* __restrict__ logits,
                                                          const float* __restrict__ score,
                                                          const int32_t* __restrict__ fin, int V, int k, int eos,
-                                                         float* __restrict__ out_score,
+                                                         int raw, float* __restrict__ out_score,
                                                          int32_t* __restrict__ out_idx) {
   __shared__ float reds[BLOCK / 64];
   __shared__ int redi[BLOCK / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
-  const float bs = score[r];
+  const float bs = raw ? 0.f : score[r];
   float* os = out_score + (size_t)r * k;
   int32_t* oi = out_idx + (size_t)r * k;
-  if (fin[r]) {   // a finished hypothesis offers itself once
+  if (!raw && fin[r]) {   // a finished hypothesis offers itself once
     if (tid < k) { os[tid] = tid == 0 ? bs : -INFINITY; oi[tid] = tid == 0 ? eos : -1; }
     return;
   }
@@ -79,7 +79,7 @@ row_topk_kernel(const T* __restrict__ logits,
   __shared__ int cand_n;
   const int lane = tid & 63, wave = tid >> 6;
   float z = 0.f;
-  if (mx != -INFINITY) {
+  if (!raw && mx != -INFINITY) {
 #pragma unroll
     for (int i = 0; i < NV * 8; ++i) z += __expf(x[i] - mx);   // padding slots: exp(-inf) = 0
   }
@@ -101,11 +101,12 @@ row_topk_kernel(const T* __restrict__ logits,
 #pragma unroll
   for (int w = 0; w < NW; ++w) zt += red_z[w] * __expf(red_m[w] - m);   // a wave of padding has z = 0
   const float logz = logf(zt);
-  // candidate scores, rounded exactly as (score + ((x - m) - logz)) with no fused operation
+  // candidate scores, rounded exactly as (score + ((x - m) - logz)) with no fused operation;
+  // raw mode (sampling) ranks the logits themselves
   float best = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NV * 8; ++i) {
-    x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
+    if (!raw) x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
     best = fmaxf(best, x[i]);     // padding slots stay -inf
   }
 
@@ -215,25 +216,25 @@ bool topk_supported(int V) { return V >= 1 && V <= 65536; }
 
 template <typename T>
 static hipError_t row_topk_t(const T* logits, const float* score, const int32_t* fin, int M, int V, int k,
-                             int eos, float* os, int32_t* oi, hipStream_t s) {
+                             int eos, int raw, float* os, int32_t* oi, hipStream_t s) {
   if (V <= 2048)
-    row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+    row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
   else if (V <= 8192)
-    row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+    row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
   else if (V <= 32768)   // 512 threads x 64 tokens: two workgroups fit a CU, one loads while the other reduces
-    row_topk_kernel<T, 512, 8><<<M, 512, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+    row_topk_kernel<T, 512, 8><<<M, 512, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
   else if (V <= 65536)
-    row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, os, oi);
+    row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin, int M,
-                           int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s) {
+                           int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, out_score, out_idx, s);
-  return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, out_score, out_idx, s);
+  if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
+  return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -397,7 +398,7 @@ __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict
                                   int32_t* __restrict__ fin, int32_t* __restrict__ active_counts,
                                   int32_t* __restrict__ step_state, int M, int k, int T1, int bos, int pad) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < 2) step_state[i] = 0;
+  if (i < 3) step_state[i] = 0;   // [0] position counter, [1] arrival counter, [2] position of step 0
   if (i < M * T1) tokens[i] = (i % T1 == 0) ? bos : pad;
   if (i < M) {
     score[i] = (i % k == 0) ? 0.f : -INFINITY;
@@ -421,14 +422,14 @@ __global__ void __launch_bounds__(64) finalize_kernel(const float* __restrict__ 
                                                       const int32_t* __restrict__ len, int32_t* __restrict__ out_ids,
                                                       int32_t* __restrict__ out_lens, float* __restrict__ out_scores,
                                                       const int32_t* __restrict__ sentence_order, int k, int T,
-                                                      float alpha, int pad) {
+                                                      float alpha, int pad, int first) {
   __shared__ int order[LSQ_MAX_BEAM_];
   const int b = blockIdx.x, lane = threadIdx.x;
   const int ob = sentence_order[b];   // where the caller expects this sentence
   float f = -INFINITY;
   int n = 0;
   if (lane < k) {
-    n = len[b * k + lane];
+    n = len[b * k + lane] - (first - 1);   // len = index of the last token in the history
     float sc = score[b * k + lane];
     float den = n > 0 ? (alpha == 1.0f ? (float)n : powf((float)n, alpha)) : 1.0f;
     f = sc / den;
@@ -446,17 +447,84 @@ __global__ void __launch_bounds__(64) finalize_kernel(const float* __restrict__ 
   __syncthreads();
   for (int i = 0; i < k; ++i) {
     int src = b * k + order[i];
-    int n_i = len[src];
+    int n_i = len[src] - (first - 1);
     for (int p = lane; p < T; p += 64)
-      out_ids[(size_t)(ob * k + i) * T + p] = p < n_i ? tokens[(size_t)src * (T + 1) + 1 + p] : pad;
+      out_ids[(size_t)(ob * k + i) * T + p] = p < n_i ? tokens[(size_t)src * (T + 1) + first + p] : pad;
   }
 }
 
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
                            int32_t* out_lens, float* out_scores, const int32_t* sentence_order, int batch, int k,
-                           int T, float alpha, int pad, hipStream_t s) {
+                           int T, float alpha, int pad, int first, hipStream_t s) {
   finalize_kernel<<<batch, 64, 0, s>>>(score, tokens, len, out_ids, out_lens, out_scores, sentence_order, k, T,
-                                       alpha, pad);
+                                       alpha, pad, first);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-k sampling (the paper's sampling decoding, sec. 3.4): one thread per row.  The row's k largest
+// logits arrive ranked (logit descending, token ascending); p = softmax over those k;
+// u = (philox4x32_10(key = seed, counter = (step, row, 0, 0))[0] >> 8) * 2^-24; the token is the
+// first j whose cumulative p exceeds u * sum(p).  Appends it to the history, adds log p to the
+// row's score, and the last thread to finish advances the position counter.
+__device__ __forceinline__ unsigned philox4x32_10_first(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
+                                                        unsigned k0, unsigned k1) {
+  const unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const unsigned hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const unsigned hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    c0 = hi1 ^ c1 ^ k0; c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+    k0 += W0; k1 += W1;
+  }
+  return c0;
+}
+
+__global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ cand_logit,
+                                                    const int32_t* __restrict__ cand_idx,
+                                                    int32_t* __restrict__ tokens, int32_t* __restrict__ len,
+                                                    float* __restrict__ logp, int32_t* __restrict__ active,
+                                                    int32_t* __restrict__ step_state, int rows, int k, int T1,
+                                                    unsigned seed_lo, unsigned seed_hi, int n_new) {
+  const int r = blockIdx.x * 64 + threadIdx.x;
+  const int pos = step_state[0], t = pos - step_state[2];   // position of the token just fed; step index
+  if (r < rows) {
+    float e[LSQ_MAX_BEAM_], cum[LSQ_MAX_BEAM_];
+    const float l0 = cand_logit[(size_t)r * k];
+    float run = 0.f;
+    for (int j = 0; j < k; ++j) {
+      e[j] = expf(cand_logit[(size_t)r * k + j] - l0);
+      run += e[j];
+      cum[j] = run;
+    }
+    const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)r, 0u, 0u, seed_lo, seed_hi);
+    const float u = (float)(word >> 8) * 5.9604644775390625e-08f;   // 2^-24
+    const float target = __fmul_rn(u, run);
+    int j = 0;
+    while (j < k - 1 && !(cum[j] > target)) ++j;
+    tokens[(size_t)r * T1 + pos + 1] = cand_idx[(size_t)r * k + j];
+    len[r] = pos + 1;
+    logp[r] += logf(e[j] / run);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    if (atomicAdd(&step_state[1], 1) == (int)gridDim.x - 1) {
+      step_state[1] = 0;
+      active[t] = (t + 1 < n_new) ? rows : 0;
+      step_state[0] = pos + 1;
+    }
+  }
+}
+
+hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
+                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, int T,
+                         unsigned long long seed, int n_new, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
+  sample_kernel<<<(rows + 63) / 64, 64, 0, s>>>(cand_logit, cand_idx, tokens, len, logp, active, step_state, rows, k,
+                                                T + 1, (unsigned)(seed & 0xFFFFFFFFull), (unsigned)(seed >> 32), n_new);
   return hipGetLastError();
 }
 

@@ -42,21 +42,25 @@ inline GemmOut plain_out(void* c, int N) {
 }
 
 // Every launcher enqueues on `s` and returns hipGetLastError().
+// act: 0 none, 1 ReLU, 2 tanh-GELU
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out,
-                       int M, int N, int K, bool relu, hipStream_t s);
+                       int M, int N, int K, int act, hipStream_t s);
 
 int gemm_partial_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* P, int M, int N, int K,
                                 int splits, hipStream_t s);
 
+// x = E[id] * scale + pe[position]
 hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const int32_t* ids,
-                             const int32_t* pos, void* x, int rows, int d, hipStream_t s);
+                             const int32_t* pos, void* x, int rows, int d, float scale, hipStream_t s);
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
                              const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp,
-                             hipStream_t s);
-hipError_t launch_add_layernorm_partials(int dtype, void* x, const float* P, int splits, const void* bias,
-                                         const void* g, const void* b, int rows, int d, float eps,
-                                         hipStream_t s);
+                             float scale, hipStream_t s);
+hipError_t launch_scatter_kv(int dtype, const void* qkv, const int32_t* sent, const int32_t* pos, void* Kc,
+                             void* Vc, int rows, int d, int T, hipStream_t s);
+hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const float* P, int splits,
+                                         const void* bias, const void* g, const void* b, int rows, int d,
+                                         float eps, hipStream_t s);
 
 // nkeys = nkeys_base + (tp ? *tp : 0), with *tp read on the device
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
@@ -68,11 +72,15 @@ hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, cons
                                   hipStream_t s);
 hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent,
                                     const int32_t* off, const int32_t* len, void* out, int rows, int H,
-                                    int d, hipStream_t s);
+                                    int d, int causal, hipStream_t s);
 
+// raw != 0: rank the logits themselves (score and fin are ignored, may be null)
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
-                           int M, int V, int k, int eos, float* out_score, int32_t* out_idx,
+                           int M, int V, int k, int eos, int raw, float* out_score, int32_t* out_idx,
                            hipStream_t s);
+hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
+                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, int T,
+                         unsigned long long seed, int n_new, hipStream_t s);
 // step = t_base + (step_state ? step_state[0] : 0).  `active` points at the counter array indexed
 // by step.  With step_state != null the last workgroup to finish advances step_state[0]
 // (step_state[1] is its arrival counter and must be zero at launch).
@@ -87,9 +95,11 @@ hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, i
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
                              int32_t* active_counts, int32_t* step_state, int batch, int k, int T, int bos,
                              int pad, hipStream_t s);
+// first: index in the token history of the first token to hand out (1 after BOS; prompt length for
+// the decoder-only model)
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,
                            int32_t* out_lens, float* out_scores, const int32_t* sentence_order, int batch,
-                           int k, int T, float alpha, int pad, hipStream_t s);
+                           int k, int T, float alpha, int pad, int first, hipStream_t s);
 
 bool topk_supported(int V);
 bool head_dim_supported(int dh);

@@ -104,10 +104,15 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
   memcpy(&hp->eps, p + 80, 4);
   memcpy(&hp->seed, p + 88, 8);
   memcpy(&hp->total, p + 96, 8);
-  if (hp->arch != 0 || hp->norm != 0 || hp->act != 0)
-    return fail(LSQ_E_BLOB, "only post-LN ReLU encoder-decoder models are supported");
+  const bool encdec = hp->arch == 0 && hp->norm == 0 && hp->act == 0;
+  const bool deconly = hp->arch == 1 && hp->norm == 1 && hp->act == 1;
+  if (!encdec && !deconly)
+    return fail(LSQ_E_BLOB, "supported: post-LN ReLU encoder-decoder (arch 0) or pre-LN tanh-GELU decoder-only (arch 1)");
   if (hp->dtype != DT_F32 && hp->dtype != DT_F16) return fail(LSQ_E_BLOB, "unknown dtype %d", hp->dtype);
-  if (hp->n_enc < 1 || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
+  if (deconly && (hp->n_enc != 0 || hp->sample_topk < 1 || hp->sample_topk > LSQ_MAX_BEAM || hp->max_pos < 1 ||
+                  hp->d > 4096))
+    return fail(LSQ_E_BLOB, "decoder-only blob: n_enc must be 0, sample_topk in [1, %d], max_pos >= 1, d <= 4096", LSQ_MAX_BEAM);
+  if ((encdec && hp->n_enc < 1) || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
       hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0)
     return fail(LSQ_E_BLOB, "implausible model shape");
   if (hp->d % 8 != 0 || hp->F % 8 != 0) return fail(LSQ_E_BLOB, "d_model and d_ffn must be multiples of 8");
@@ -127,6 +132,15 @@ void tensor_walk(const HParams& hp, std::vector<TensorDesc>* out) {
   auto mat = [&](int r, int c) { out->push_back({r, c, true}); };
   auto vec = [&](int n) { out->push_back({1, n, false}); };
   out->push_back({V, d, false});   // embedding: already [vocab, d] = [N, K] of the logit GEMM
+  if (hp.arch == 1) {
+    out->push_back({hp.max_pos, d, false});   // learned positions
+    for (int i = 0; i < hp.n_dec; ++i) {
+      vec(d); vec(d); mat(d, 3 * d); vec(3 * d); mat(d, d); vec(d);
+      vec(d); vec(d); mat(d, F); vec(F); mat(F, d); vec(d);
+    }
+    vec(d); vec(d);
+    return;
+  }
   for (int i = 0; i < hp.n_enc; ++i) {
     mat(d, 3 * d); vec(3 * d); mat(d, d); vec(d); vec(d); vec(d);
     mat(d, F); vec(F); mat(F, d); vec(d); vec(d); vec(d);
@@ -138,6 +152,7 @@ void tensor_walk(const HParams& hp, std::vector<TensorDesc>* out) {
   }
 }
 
+struct GptLayer { char *ln1g, *ln1b, *Wqkv, *bqkv, *Wo, *bo, *ln2g, *ln2b, *W1, *b1, *W2, *b2; };
 struct EncLayer { char *Wqkv, *bqkv, *Wo, *bo, *ln1g, *ln1b, *W1, *b1, *W2, *b2, *ln2g, *ln2b; };
 struct DecLayer {
   char *Wqkv, *bqkv, *Wo, *bo, *ln1g, *ln1b, *Wq, *bq, *Wkv, *bkv, *Woc, *boc, *ln2g, *ln2b, *W1, *b1, *W2,
@@ -153,7 +168,7 @@ struct Plan {
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
-  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits;
+  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits, d_y, e_y;
 };
 
 Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
@@ -176,9 +191,10 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.src_off = take((size_t)(B + 1) * 4);
   p.src_len = take((size_t)B * 4);
   p.active = take((size_t)(T + 1) * 4);
-  p.step_state = take(2 * 4);   // [0] decode-step counter, [1] arrival counter of the refine kernel
-  p.cand_score = take(M * k * 4);
-  p.cand_idx = take(M * k * 4);
+  p.step_state = take(4 * 4);   // [0] position counter, [1] arrival counter, [2] position of step 0
+  const size_t kk = std::max(k, hp.arch == 1 ? hp.sample_topk : 0);   // survivors per row
+  p.cand_score = take(M * kk * 4);
+  p.cand_idx = take(M * kk * 4);
   p.out_ids = take(M * T * 4);
   p.out_lens = take(M * 4);
   p.out_scores = take(M * 4);
@@ -188,12 +204,14 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   auto etake = [&](size_t bytes) { size_t o = e; e += up(bytes); return o; };
   p.e_ids = etake(R * 4); p.e_pos = etake(R * 4); p.e_sent = etake(R * 4);
   p.e_x = etake(R * d * esz); p.e_qkv = etake(R * 3 * d * esz); p.e_ctx = etake(R * d * esz);
-  p.e_tmp = etake(R * d * 4); p.e_ffn = etake(R * F * esz);   // e_tmp: one fp32 slab (no split-K at encoder sizes)
+  p.e_tmp = etake(R * d * 4); p.e_ffn = etake(R * F * esz);
+  p.e_y = etake(R * d * esz);     // pre-LN models: normalised copy of the residual stream   // e_tmp: one fp32 slab (no split-K at encoder sizes)
   // decoder phase
   size_t q = p.scratch;
   auto dtake = [&](size_t bytes) { size_t o = q; q += up(bytes); return o; };
   p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
   p.d_tmp = dtake(kMaxSplits * M * d * 4);   // fp32 partial-sum slabs of the split-K GEMMs
+  p.d_y = dtake(M * d * esz);
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
@@ -225,6 +243,9 @@ struct Ctx {
   std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
+  std::vector<GptLayer> gpt;
+  char *lnfg = nullptr, *lnfb = nullptr;
+  int prompt_len = 0;
   std::vector<EncLayer> enc;
   std::vector<DecLayer> dec;
   int32_t* pinned = nullptr;   // host staging: ids, positions, sentence map, offsets, lengths, caps, 1 count
@@ -259,17 +280,21 @@ int check_limits(int max_batch, int beam, int max_len, const HParams& hp) {
   if (beam < 1 || beam > LSQ_MAX_BEAM) return fail(LSQ_E_ARG, "beam %d outside [1, %d]", beam, LSQ_MAX_BEAM);
   if (beam > hp.V) return fail(LSQ_E_ARG, "beam wider than the vocabulary");
   if (max_len < 1 || max_len > 4096) return fail(LSQ_E_ARG, "max_len %d outside [1, 4096]", max_len);
+  if (hp.arch == 1 && beam != 1) return fail(LSQ_E_ARG, "a decoder-only (sampling) model runs with beam 1");
+  if (hp.arch == 1 && max_len > hp.max_pos) return fail(LSQ_E_ARG, "max_len %d exceeds the model's %d positions", max_len, hp.max_pos);
   return LSQ_OK;
 }
 
 // x <- LN(x + in . W^T + bias): the GEMM leaves fp32 partial sums (split over k when the output has
 // too few tiles to fill the chip), the LayerNorm kernel adds them, the bias and the residual.
+// Post-LN (y == nullptr): x <- LN(x + in.W^T + bias).  Pre-LN (y given): x <- x + in.W^T + bias and
+// y <- LN(x) with the NEXT sublayer's gain and shift.
 int sublayer(int cls, const void* in, const void* W, const void* bias, const void* g_, const void* b_, void* x,
-             float* partials, int M, int d, int K, int max_splits, hipStream_t s) {
+             void* y, float* partials, int M, int d, int K, int max_splits, hipStream_t s) {
   const HParams& hp = g.hp;
   int S = std::min(gemm_partial_splits(hp.dtype, M, d, K), max_splits);
   TIMED(cls, launch_gemm_partials(hp.dtype, in, W, partials, M, d, K, S, s));
-  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(hp.dtype, x, partials, S, bias, g_, b_, M, d, hp.eps, s));
+  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(hp.dtype, x, y, partials, S, bias, g_, b_, M, d, hp.eps, s));
   return LSQ_OK;
 }
 
@@ -290,7 +315,7 @@ int launch_step(int B) {
   int32_t* step = at<int32_t>(p.step_state);
   const size_t slab = (size_t)M_max * T * d * es;   // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
-  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, s));
+  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
   for (int l = 0; l < hp.n_dec; ++l) {
     const DecLayer& L = g.dec[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
@@ -300,20 +325,20 @@ int launch_step(int B) {
     o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
     o.tpos = step;
     o.tmul[1] = d; o.tmul[2] = d;
-    TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, false, s));
+    TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, s));
-    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
-    TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, false, s));
+    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, nullptr, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
+    TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, 0, s));
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                   at<int32_t>(p.src_len), ctx, B, k, H, d, g.max_len, s));
-    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, x, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
-    TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, true, s));
-    if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, x, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
+    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, x, nullptr, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
+    TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, 1, s));
+    if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, x, nullptr, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
-  TIMED(PC_GEMM_VOCAB, launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, false, s));
-  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos,
+  TIMED(PC_GEMM_VOCAB, launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, 0, s));
+  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
   // refine advances the device-side step counter when its last workgroup finishes, so the
   // reorder that follows reads t + 1 = the number of cache positions to gather
@@ -326,13 +351,56 @@ int launch_step(int B) {
   return LSQ_OK;
 }
 
+// Decoder-only model: one sampled token for every row.  Same conventions as launch_step.
+int launch_step_gpt(int B) {
+  const HParams& hp = g.hp;
+  const Plan& p = g.plan;
+  hipStream_t s = g.stream;
+  const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, T = g.max_len, ks = hp.sample_topk;
+  const int M = B, M_max = g.max_batch;
+  const size_t es = esz();
+  char* x = g.ws + p.d_x; char* y = g.ws + p.d_y; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx;
+  char* tmp = g.ws + p.d_tmp; char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
+  int32_t* step = at<int32_t>(p.step_state);
+  const size_t slab = (size_t)M_max * T * d * es;
+  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, 1.0f, s));
+  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, y, nullptr, 0, nullptr, g.gpt[0].ln1g, g.gpt[0].ln1b, M, d, hp.eps, s));
+  for (int l = 0; l < hp.n_dec; ++l) {
+    const GptLayer& L = g.gpt[l];
+    char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
+    char* Vc = Kc + slab;
+    GemmOut o = plain_out(q, d);
+    o.ptr[1] = Kc; o.ptr[2] = Vc;
+    o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
+    o.tpos = step;
+    o.tmul[1] = d; o.tmul[2] = d;
+    TIMED(PC_GEMM_QKV, launch_gemm(dt, y, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
+    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, s));
+    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln2g, L.ln2b, x, y, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
+    TIMED(PC_GEMM_FFN1, launch_gemm(dt, y, L.W1, L.b1, plain_out(ffn, F), M, F, d, 2, s));
+    const bool last = l + 1 == hp.n_dec;
+    if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, last ? g.lnfg : g.gpt[l + 1].ln1g, last ? g.lnfb : g.gpt[l + 1].ln1b,
+                          x, y, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
+  }
+  GemmOut lo = plain_out(logits, V);
+  lo.f32_out = 1;
+  TIMED(PC_GEMM_VOCAB, launch_gemm(dt, y, g.E, nullptr, lo, M, V, d, 0, s));
+  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, ks, hp.eos, 1, at<float>(p.cand_score),
+                                     at<int32_t>(p.cand_idx), s));
+  TIMED(PC_REFINE, launch_sample(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<int32_t>(p.tokens),
+                                 at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, ks, T,
+                                 (unsigned long long)hp.seed, hp.cap_extra, s));
+  return LSQ_OK;
+}
+
 // One decode step: replay the captured graph for this number of live sentences, capturing it on
 // first use.  Graphs need a capturable (non-default) stream and are bypassed while per-kernel
 // timing is on.
 int enqueue_step() {
   const int B = g.alive_at[g.t];
+  auto launch = [&](int n) { return g.hp.arch == 1 ? launch_step_gpt(n) : launch_step(n); };
   if (!g.use_graphs || g.stream == nullptr || g_prof.on) {
-    int rc = launch_step(B);
+    int rc = launch(B);
     if (rc) return rc;
     g.t += 1;
     return LSQ_OK;
@@ -341,7 +409,7 @@ int enqueue_step() {
   if (it == g.graphs.end()) {
     hipGraph_t graph = nullptr;
     HIPCHK(hipStreamBeginCapture(g.stream, hipStreamCaptureModeThreadLocal));
-    int rc = launch_step(B);
+    int rc = launch(B);
     hipError_t e = hipStreamEndCapture(g.stream, &graph);
     if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
     if (e != hipSuccess) return fail(LSQ_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
@@ -361,6 +429,92 @@ int read_active(int step, int* out) {
   HIPCHK(hipMemcpyAsync(slot, at<int32_t>(g.plan.active) + step, 4, hipMemcpyDeviceToHost, g.stream));
   HIPCHK(hipStreamSynchronize(g.stream));
   *out = *slot;
+  return LSQ_OK;
+}
+
+// Decoder-only model: "encode" takes the prompts (all of one length P), runs the blocks over their
+// first P-1 tokens to fill the K/V cache (causal attention inside the prompt), and leaves the last
+// prompt token as the input of decode step 0, so that every sampled token comes from a decode step.
+int encode_gpt(const int32_t* ids, const int32_t* lens, int batch, int stride) {
+  const HParams& hp = g.hp;
+  const Plan& p = g.plan;
+  const int P = lens[0], T = g.max_len, n_new = hp.cap_extra;
+  for (int b = 0; b < batch; ++b)
+    if (lens[b] != P) return fail(LSQ_E_ARG, "decoder-only models need prompts of one length (got %d and %d)", P, lens[b]);
+  if (P + n_new > T + 1) return fail(LSQ_E_ARG, "prompt %d + %d new tokens do not fit max_len %d", P, n_new, T);
+  hipStream_t s = g.stream;
+  const int R = batch * (P - 1);
+  const size_t Rmax = (size_t)g.max_batch * g.max_len;
+  int32_t* h_ids = g.pinned;
+  int32_t* h_pos = h_ids + Rmax;
+  int32_t* h_sent = h_pos + Rmax;
+  int32_t* h_off = h_sent + Rmax;
+  int32_t* h_len = h_off + g.max_batch + 1;
+  int32_t* h_order = h_len + 2 * g.max_batch;
+  int32_t* h_tok = h_order + g.max_batch + 2;                  // [batch, T+1] token histories
+  int32_t* h_row = h_tok + (size_t)g.max_batch * (T + 1);      // [batch] index of the last token
+  int32_t* h_step = h_row + g.max_batch;                       // step_state
+  g.order.resize(batch);
+  for (int b = 0; b < batch; ++b) {
+    g.order[b] = b;
+    h_order[b] = b;
+    h_off[b] = b * (P - 1);
+    h_len[b] = P - 1;
+    h_row[b] = P - 1;
+    for (int j = 0; j <= T; ++j) h_tok[(size_t)b * (T + 1) + j] = j < P ? ids[(size_t)b * stride + j] : hp.pad;
+    for (int j = 0; j + 1 < P; ++j) {
+      h_ids[b * (P - 1) + j] = ids[(size_t)b * stride + j];
+      h_pos[b * (P - 1) + j] = j;
+      h_sent[b * (P - 1) + j] = b;
+    }
+  }
+  h_off[batch] = R;
+  h_step[0] = P - 1; h_step[1] = 0; h_step[2] = P - 1; h_step[3] = 0;
+  g.alive_at.assign(g.max_len + 1, 0);
+  for (int t = 0; t < n_new && t <= g.max_len; ++t) g.alive_at[t] = batch;
+  if (R > 0) {
+    HIPCHK(hipMemcpyAsync(g.ws + p.e_ids, h_ids, (size_t)R * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(g.ws + p.e_pos, h_pos, (size_t)R * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(g.ws + p.e_sent, h_sent, (size_t)R * 4, hipMemcpyHostToDevice, s));
+  }
+  HIPCHK(hipMemcpyAsync(g.ws + p.src_off, h_off, (size_t)(batch + 1) * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.src_len, h_len, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.order, h_order, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.tokens, h_tok, (size_t)batch * (T + 1) * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.len, h_row, (size_t)batch * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemcpyAsync(g.ws + p.step_state, h_step, 16, hipMemcpyHostToDevice, s));
+  HIPCHK(hipMemsetAsync(g.ws + p.score, 0, (size_t)batch * 4, s));
+  HIPCHK(hipMemsetAsync(g.ws + p.active, 0, (size_t)(T + 1) * 4, s));
+
+  const int dt = hp.dtype, d = hp.d, F = hp.F, H = hp.H;
+  const size_t es = esz();
+  char* x = g.ws + p.e_x; char* y = g.ws + p.e_y; char* qkv = g.ws + p.e_qkv; char* ctx = g.ws + p.e_ctx;
+  char* tmp = g.ws + p.e_tmp; char* ffn = g.ws + p.e_ffn;
+  const int32_t* sent = at<int32_t>(p.e_sent);
+  const int32_t* pos = at<int32_t>(p.e_pos);
+  const size_t slab = (size_t)g.max_batch * T * d * es;
+  if (R > 0) {
+    HIPCHK(launch_embed_rows(dt, g.E, at<float>(p.pe), at<int32_t>(p.e_ids), pos, x, R, d, 1.0f, s));
+    HIPCHK(launch_add_layernorm_partials(dt, x, y, nullptr, 0, nullptr, g.gpt[0].ln1g, g.gpt[0].ln1b, R, d, hp.eps, s));
+    for (int l = 0; l < hp.n_dec; ++l) {
+      const GptLayer& L = g.gpt[l];
+      char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
+      HIPCHK(launch_gemm(dt, y, L.Wqkv, L.bqkv, plain_out(qkv, 3 * d), R, 3 * d, d, 0, s));
+      HIPCHK(launch_scatter_kv(dt, qkv, sent, pos, Kc, Kc + slab, R, d, T, s));
+      HIPCHK(launch_encoder_attention(dt, qkv, sent, at<int32_t>(p.src_off), at<int32_t>(p.src_len), ctx, R, H, d, 1, s));
+      if (int rc = sublayer(-1, ctx, L.Wo, L.bo, L.ln2g, L.ln2b, x, y, (float*)tmp, R, d, d, 1, s)) return rc;
+      HIPCHK(launch_gemm(dt, y, L.W1, L.b1, plain_out(ffn, F), R, F, d, 2, s));
+      const bool last = l + 1 == hp.n_dec;
+      if (int rc = sublayer(-1, ffn, L.W2, L.b2, last ? g.lnfg : g.gpt[l + 1].ln1g, last ? g.lnfb : g.gpt[l + 1].ln1b,
+                            x, y, (float*)tmp, R, d, F, 1, s)) return rc;
+    }
+  }
+  g.batch = batch;
+  g.rows_enc = R;
+  g.prompt_len = P;
+  g.t = 0;
+  g.done = false;
+  g.state = 3;
   return LSQ_OK;
 }
 
@@ -435,12 +589,17 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
   (void)hipHostFree(stage);
   if (e != hipSuccess) return fail(LSQ_E_HIP, "weight upload failed: %s", hipGetErrorString(e));
 
-  // sinusoidal position table, evaluated in double precision
+  // position table in fp32: sinusoidal, evaluated in double precision, or the model's learned one
   {
     const int d = hp.d;
     float* pe = nullptr;
     HIPCHK(hipHostMalloc((void**)&pe, (size_t)max_len * d * 4, hipHostMallocDefault));
-    for (int pos = 0; pos < max_len; ++pos)
+    if (hp.arch == 1) {
+      const char* P = (const char*)weights + up(256 + (size_t)hp.V * d * es);   // second tensor of the blob
+      for (size_t i = 0; i < (size_t)max_len * d; ++i)
+        pe[i] = es == 2 ? (float)((const _Float16*)P)[i] : ((const float*)P)[i];
+    }
+    for (int pos = 0; pos < max_len && hp.arch == 0; ++pos)
       for (int i = 0; i < d; i += 2) {
         double ang = (double)pos / std::pow(10000.0, (double)i / d);
         pe[(size_t)pos * d + i] = (float)std::sin(ang);
@@ -452,7 +611,7 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
     if (e != hipSuccess) return fail(LSQ_E_HIP, "position table upload failed: %s", hipGetErrorString(e));
   }
 
-  g.pinned_ints = (size_t)3 * max_batch * max_len + 4 * (size_t)max_batch + 2;
+  g.pinned_ints = (size_t)3 * max_batch * max_len + 4 * (size_t)max_batch + 2 + (size_t)max_batch * (max_len + 2) + 8;
   HIPCHK(hipHostMalloc((void**)&g.pinned, g.pinned_ints * 4, hipHostMallocDefault));
 
   g.hp = hp;
@@ -460,6 +619,17 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
   g.max_batch = max_batch; g.beam = beam; g.max_len = max_len;
   size_t i = 0;
   g.E = dev[i++];
+  if (hp.arch == 1) {
+    ++i;   // learned positions: used through the fp32 table
+    g.gpt.assign(hp.n_dec, GptLayer{});
+    for (auto& L : g.gpt) {
+      L.ln1g = dev[i++]; L.ln1b = dev[i++]; L.Wqkv = dev[i++]; L.bqkv = dev[i++]; L.Wo = dev[i++]; L.bo = dev[i++];
+      L.ln2g = dev[i++]; L.ln2b = dev[i++]; L.W1 = dev[i++]; L.b1 = dev[i++]; L.W2 = dev[i++]; L.b2 = dev[i++];
+    }
+    g.lnfg = dev[i++]; g.lnfb = dev[i++];
+    g.state = 2;
+    return LSQ_OK;
+  }
   g.enc.assign(hp.n_enc, EncLayer{});
   for (auto& L : g.enc) {
     L.Wqkv = dev[i++]; L.bqkv = dev[i++]; L.Wo = dev[i++]; L.bo = dev[i++]; L.ln1g = dev[i++]; L.ln1b = dev[i++];
@@ -494,6 +664,7 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     R += n;
   }
   HIPCHK(hipStreamSynchronize(g.stream));   // the staging buffer may still feed an earlier copy
+  if (hp.arch == 1) return encode_gpt(src_ids, src_lens, batch, src_stride);
   const Plan& p = g.plan;
   const size_t Rmax = (size_t)g.max_batch * g.max_len;
   int32_t* h_ids = g.pinned;
@@ -544,18 +715,18 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
   const int32_t* sent = at<int32_t>(p.e_sent);
   const int32_t* off = at<int32_t>(p.src_off);
   const int32_t* len = at<int32_t>(p.src_len);
-  HIPCHK(launch_embed_rows(dt, g.E, at<float>(p.pe), at<int32_t>(p.e_ids), at<int32_t>(p.e_pos), x, (int)R, d, s));
+  HIPCHK(launch_embed_rows(dt, g.E, at<float>(p.pe), at<int32_t>(p.e_ids), at<int32_t>(p.e_pos), x, (int)R, d, sqrtf((float)d), s));
   for (const EncLayer& L : g.enc) {
-    HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, plain_out(qkv, 3 * d), (int)R, 3 * d, d, false, s));
-    HIPCHK(launch_encoder_attention(dt, qkv, sent, off, len, ctx, (int)R, H, d, s));
-    if (int rc = sublayer(-1, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, (float*)tmp, (int)R, d, d, 1, s)) return rc;
-    HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), (int)R, F, d, true, s));
-    if (int rc = sublayer(-1, ffn, L.W2, L.b2, L.ln2g, L.ln2b, x, (float*)tmp, (int)R, d, F, 1, s)) return rc;
+    HIPCHK(launch_gemm(dt, x, L.Wqkv, L.bqkv, plain_out(qkv, 3 * d), (int)R, 3 * d, d, 0, s));
+    HIPCHK(launch_encoder_attention(dt, qkv, sent, off, len, ctx, (int)R, H, d, 0, s));
+    if (int rc = sublayer(-1, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, nullptr, (float*)tmp, (int)R, d, d, 1, s)) return rc;
+    HIPCHK(launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), (int)R, F, d, 1, s));
+    if (int rc = sublayer(-1, ffn, L.W2, L.b2, L.ln2g, L.ln2b, x, nullptr, (float*)tmp, (int)R, d, F, 1, s)) return rc;
   }
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;   // layer stride of the maximum shape
   for (int l = 0; l < hp.n_dec; ++l)
     HIPCHK(launch_gemm(dt, x, g.dec[l].Wkv, g.dec[l].bkv, plain_out(g.ws + p.cross + l * cross_l, 2 * d), (int)R,
-                       2 * d, d, false, s));
+                       2 * d, d, 0, s));
   HIPCHK(launch_beam_reset(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                            at<int32_t>(p.active), at<int32_t>(p.step_state), batch, g.beam, g.max_len, hp.bos,
                            hp.pad, s));
@@ -624,7 +795,8 @@ int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
   const int M = g.batch * g.beam, T = g.max_len;
   HIPCHK(launch_finalize(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.out_ids),
                          at<int32_t>(p.out_lens), at<float>(p.out_scores), at<int32_t>(p.order), g.batch, g.beam,
-                         T, g.hp.alpha, g.hp.pad, g.stream));
+                         T, g.hp.arch == 1 ? 0.0f : g.hp.alpha, g.hp.pad, g.hp.arch == 1 ? g.prompt_len : 1,
+                         g.stream));
   HIPCHK(hipMemcpyAsync(out_ids, g.ws + p.out_ids, (size_t)M * T * 4, hipMemcpyDeviceToHost, g.stream));
   HIPCHK(hipMemcpyAsync(out_lens, g.ws + p.out_lens, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
   HIPCHK(hipMemcpyAsync(out_scores, g.ws + p.out_scores, (size_t)M * 4, hipMemcpyDeviceToHost, g.stream));
@@ -662,8 +834,8 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     case LSQ_DBG_LEN: src = g.ws + p.len; n = M; break;
     case LSQ_DBG_FINISHED: src = g.ws + p.fin; n = M; break;
     case LSQ_DBG_PARENT: src = g.ws + p.parent; n = M; break;
-    case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * g.beam; break;
-    case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * g.beam; break;
+    case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
+    case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
     case LSQ_DBG_HIDDEN: src = g.ws + p.d_x; n = M * d; is_float_data = true; break;
     case LSQ_DBG_MEMORY:
       if (g.t != 0) return fail(LSQ_E_STATE, "encoder output is overwritten by the first decode step");
@@ -724,7 +896,7 @@ int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* 
   KCHK(dtype == DT_F32 || K % 8 == 0, "K must be a multiple of 8 for float16");
   GemmOut o = plain_out(C, N);
   o.f32_out = (dtype == DT_F16 && (flags & LSQ_GEMM_F32_OUT)) ? 1 : 0;
-  KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) != 0, (hipStream_t)stream));
+  KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) ? 1 : ((flags & LSQ_GEMM_GELU) ? 2 : 0), (hipStream_t)stream));
 }
 
 size_t lsq_k_gemm_add_layernorm_scratch(int dtype, int M, int d, int K) {
@@ -741,7 +913,7 @@ int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const voi
   const int S = gemm_partial_splits(dtype, M, d, K);
   hipError_t e = launch_gemm_partials(dtype, in, W, (float*)scratch, M, d, K, S, (hipStream_t)stream);
   if (e == hipSuccess)
-    e = launch_add_layernorm_partials(dtype, x, (const float*)scratch, S, bias, gamma, beta, M, d, eps,
+    e = launch_add_layernorm_partials(dtype, x, nullptr, (const float*)scratch, S, bias, gamma, beta, M, d, eps,
                                       (hipStream_t)stream);
   if (e != hipSuccess) return fail(LSQ_E_HIP, "%s", hipGetErrorString(e));
   return LSQ_OK;
@@ -770,7 +942,7 @@ int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int3
   KCHK(logits && score && finished && out_score && out_idx, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(M >= 0 && topk_supported(V) && k >= 1 && k <= LSQ_MAX_BEAM && eos >= 0 && eos < V, "shape");
-  KRUN(launch_row_topk(dtype, logits, score, finished, M, V, k, eos, out_score, out_idx, (hipStream_t)stream));
+  KRUN(launch_row_topk(dtype, logits, score, finished, M, V, k, eos, 0, out_score, out_idx, (hipStream_t)stream));
 }
 
 int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,

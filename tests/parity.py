@@ -163,3 +163,67 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
             break
     return dict(steps=steps, batch=B, worst_tight=worst_tight, worst_wide=worst_wide, worst_dev=worst_dev,
                 strict=strict_n, band=band_n, state=st)
+
+
+def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
+    """Decoder-only model with top-k sampling, library and oracle side by side.
+
+    Every step: logits against the oracle (same tolerances as lockstep), then the sampled token of
+    every row.  The uniform numbers are identical on both sides (same Philox counter), so the
+    tokens must be identical wherever the decision is clear: the k-th and (k+1)-th logit differ,
+    and the draw is away from every cumulative-probability boundary, by more than the measured
+    logit deviation allows.  Elsewhere the library's token must be one of the oracle's k
+    candidates, and the oracle continues from it.  Returns a summary dict."""
+    m = O.Model(blob)
+    B, T, V, k = w.batch, w.max_len, m.V, m.sample_topk
+    n_new = m.cap_extra if n_steps is None else n_steps
+    eng.encode(w.src_ids, w.src_lens)
+    P = int(w.src_lens[0])
+    st = O.GptState(m, w.src_ids[:, :P], T)
+    O.gpt_prefill(m, st)
+    tol = 1e-2 if m.round16 else TOL_F32
+    worst = 0.0
+    strict = loose = 0
+    for step in range(n_new):
+        ref = O.gpt_step_logits(m, st)
+        active = eng.decode_step()
+        got = eng.debug(lsq.DBG.LOGITS, (B, V))
+        e = logit_error(got, ref)
+        worst = max(worst, e)
+        assert e <= tol, f"step {step}: logits differ from the oracle by {e}"
+        g_tok = eng.debug(lsq.DBG.TOKENS, (B, T + 1), np.int32)[:, st.pos + 1]
+        g_ci = eng.debug(lsq.DBG.CAND_IDX, (B, k), np.int32)
+        g_cl = eng.debug(lsq.DBG.CAND_SCORE, (B, k))
+        toks, lps = [], []
+        for r in range(B):
+            u = O.sample_uniform(m.seed, st.t, r)
+            # selection alone, on the library's own logits: its k candidates are exactly the k largest
+            # (logit descending, token ascending), and its token is the oracle's draw from them
+            mine = np.lexsort((np.arange(V), -got[r]))[:k]
+            assert np.array_equal(g_ci[r], mine) and np.array_equal(g_cl[r], got[r][mine]), f"step {step} row {r}: candidates"
+            tok_own, _, gap_own = O.sample_topk(got[r], k, u)
+            assert g_tok[r] == tok_own or gap_own < 1e-5, f"step {step} row {r}: token {g_tok[r]}, expected {tok_own}"
+            tok, lp, gap = O.sample_topk(ref[r], k, u)
+            dev = float(np.abs(got[r] - ref[r]).max())
+            if gap > 4 * dev + 1e-5:
+                strict += 1
+                assert g_tok[r] == tok, f"step {step} row {r}: sampled {g_tok[r]}, oracle {tok} (gap {gap:.2e})"
+            else:
+                loose += 1
+                order = np.lexsort((np.arange(V), -ref[r]))[:k + 1]
+                assert g_tok[r] in order, f"step {step} row {r}: sampled token is not among the oracle's candidates"
+                if g_tok[r] != tok:
+                    top = order[:k]
+                    l = ref[r][top].astype(np.float32)
+                    pe = np.exp(l - l[0])
+                    j = int(np.nonzero(top == g_tok[r])[0][0]) if g_tok[r] in top else k - 1
+                    tok, lp = int(g_tok[r]), float(np.log(pe[j] / pe.sum()))
+            toks.append(tok)
+            lps.append(lp)
+        O.gpt_advance(m, st, toks, lps)
+        g_logp = eng.debug(lsq.DBG.SCORE, (B,))
+        np.testing.assert_allclose(g_logp, st.logp, rtol=2e-5, atol=1e-4 + (4e-3 if m.round16 else 2e-5) * (step + 1))
+        assert active == (B if step + 1 < m.cap_extra else 0), f"step {step}: active {active}"
+        if verbose:
+            print(f"step {step + 1}: strict {strict} loose {loose} worst logit error {worst:.2e}", flush=True)
+    return dict(steps=n_new, strict=strict, loose=loose, worst=worst, state=st)

@@ -67,6 +67,21 @@ def test_gemm_fp32(env, M, N, K):
     np.testing.assert_allclose(C.cpu().numpy(), ref, rtol=1e-5, atol=1e-5)
 
 
+@pytest.mark.parametrize("M,N,K", [(5, 264, 128), (32, 3072, 768), (200, 520, 72), (600, 3072, 768)])
+@pytest.mark.parametrize("half", [False, True])
+def test_gemm_gelu(env, M, N, K, half):
+    """tanh-GELU epilogue (decoder-only model's feed-forward) against the oracle's gelu_tanh in float64."""
+    lsq, torch = env
+    rng = np.random.default_rng(M + N + K)
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    A, B, bias = cast(rng.standard_normal((M, K))), cast(rng.standard_normal((N, K)) * 0.1), cast(rng.standard_normal(N))
+    ref = O.gelu_tanh(A.astype(np.float64) @ B.astype(np.float64).T + bias)
+    td = torch.float16 if half else torch.float32
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    lsq.k_gemm(_dev(torch, A, td), _dev(torch, B, td), _dev(torch, bias, td), C, gelu=True)
+    np.testing.assert_allclose(C.cpu().numpy(), ref, rtol=2e-5, atol=2e-5)
+
+
 @pytest.mark.parametrize("rows,d,K", [(1, 64, 64), (5, 512, 2048), (513, 1024, 1024), (512, 1024, 4096),
                                       (37, 2048, 264), (64, 1024, 4096), (9, 72, 40), (4, 100, 16), (3, 4104, 128)])
 @pytest.mark.parametrize("half", [False, True])
