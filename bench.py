@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Throughput of the beam-search decode hot path on one MI355X.
+"""Throughput of the auto-regressive decode hot path on one MI355X.
 
 A "step" is one lsq_decode_step: every decoder layer over the cached keys/values, vocabulary
 logits, log-softmax + beam scores + exact top-k, hypothesis update and K/V-cache reorder, for all
@@ -14,6 +14,10 @@ timed steps / elapsed time (one token per still-unfinished sentence per step).  
 instrumented pass of the same K steps brackets every kernel with HIP events on the library's
 stream to get per-kernel-class durations for the roofline line; the CPU oracle is timed on a
 bounded sample of the same workload.  Prints ONE JSON line.
+
+--workload gpt2s times the decoder-only model instead (GPT-2-small shape, batch 32, prompt 64,
+top-8 sampling, 128 generated tokens): a step is one lsq_decode_step of that model (12 pre-LN
+blocks over the cache, logits, top-k, Philox draw); value = sampled tokens / elapsed time.
 """
 from __future__ import annotations
 
@@ -75,7 +79,7 @@ def class_work(name, hp, B, k, t_mean, s_mean):
     if name == "row_topk":       # logits read once
         return (4.0 * M * V, M * V * 4)
     if name == "beam_refine":
-        return (0.0, M * k * 8)
+        return (0.0, M * max(k, hp.sample_topk) * 8)
     if name == "cache_reorder":  # whole live cache gathered: read + write, all layers, K and V
         return (0.0, 2.0 * (2 * L * M * t_mean * d * es))
     return (0.0, 0.0)
@@ -86,7 +90,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed decode steps (0 = to the end of the translation)")
     ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the timed ones")
-    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128"])
+    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle sample")
     ap.add_argument("--breakdown", default="", help="write the per-kernel-class table to this JSON file")
@@ -144,7 +148,10 @@ def main() -> int:
     # Work per class summed over the timed steps.  Step t works on the sentences whose cap
     # (source length + cap_extra, at most max_len) exceeds t, attends t+1 cached positions and
     # reorders t+1 positions.
-    caps = np.minimum(w.src_lens + hp.cap_extra, T)
+    gpt = hp.arch == 1
+    # decoder-only: every row generates cap_extra tokens; step t attends the prompt and t earlier tokens
+    caps = np.full(B, hp.cap_extra) if gpt else np.minimum(w.src_lens + hp.cap_extra, T)
+    t_base = int(w.src_lens[0]) - 1 if gpt else 0
     s_mean = float(w.src_lens.mean())
     table = {}
     for name, (ms, n) in prof.items():
@@ -154,7 +161,7 @@ def main() -> int:
         per_step = n // K
         for t in range(W, W + K):
             alive = caps > t
-            f1, b1 = class_work(name, hp, int(alive.sum()), k, t + 1, float(w.src_lens[alive].mean()) if alive.any() else 0.0)
+            f1, b1 = class_work(name, hp, int(alive.sum()), k, t_base + t + 1, float(w.src_lens[alive].mean()) if alive.any() else 0.0)
             fl += f1 * per_step
             by += b1 * per_step
         us = ms / n * 1e3
@@ -164,7 +171,10 @@ def main() -> int:
     dom = max(table, key=lambda n: table[n]["total_ms"])
     d = table[dom]
     traffic = MEASURED_TRAFFIC_BIG128.get(dom) if args.workload == "big128" else None
-    if dom.startswith("gemm"):
+    # a product whose FLOP per byte is below peak FLOP/s / peak B/s (small M: the weights are
+    # streamed for few rows) is bounded by the memory roof, not by the matrix cores
+    intensity = d["flops_per_launch"] / max(d["bytes_per_launch"], 1.0)
+    if dom.startswith("gemm") and intensity >= PEAK_F16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         roof = dict(bound="mfma", kernel=dom, achieved=d["tflops"], peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
                     frac=d["tflops"] / PEAK_F16_TFLOPS, traffic=traffic, avg_us=d["avg_us"], launches=d["launches"])
     else:
@@ -193,10 +203,23 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count() or 1
         m = O.Model(blob)
-        _, cross = O.encode(m, w.src_ids, w.src_lens)
-        st = O.DecodeState(m, w.src_lens, k, T)
+        if gpt:
+            P = int(w.src_lens[0])
+            st = O.GptState(m, w.src_ids[:, :P], T)
+            O.gpt_prefill(m, st)
+        else:
+            _, cross = O.encode(m, w.src_ids, w.src_lens)
+            st = O.DecodeState(m, w.src_lens, k, T)
         n_steps, tok, t0 = 0, 0, time.perf_counter()
-        while True:
+        while gpt:
+            logits = O.gpt_step_logits(m, st)
+            picks = [O.sample_topk(logits[r], m.sample_topk, O.sample_uniform(m.seed, st.t, r)) for r in range(B)]
+            O.gpt_advance(m, st, [q[0] for q in picks], [q[1] for q in picks])
+            n_steps += 1
+            tok += B
+            if time.perf_counter() - t0 > args.cpu_seconds or n_steps >= total_steps:
+                break
+        while not gpt:
             active_before = int((~st.finished).reshape(B, k).any(axis=1).sum())
             logits = O.decoder_logits_cached(m, st, cross)
             sel = O.beam_select(m, st, logits)
@@ -208,16 +231,22 @@ def main() -> int:
         cdt = time.perf_counter() - t0
         cpu = dict(value=tok / cdt, unit="tokens/s", cores=cores, kind="oracle",
                    sample=f"first {n_steps} decode steps of the same workload ({cdt:.1f} s, "
-                          f"{cdt / n_steps * 1e3:.0f} ms/step; encoder excluded)")
+                          f"{cdt / n_steps * 1e3:.0f} ms/step; {'prompt prefill' if gpt else 'encoder'} excluded)")
 
-    out = dict(metric="decoded target tokens/sec at beam 4 (Transformer-big fp16); ms per decode step",
+    if gpt:
+        metric = f"sampled tokens/sec, top-{hp.sample_topk} sampling (decoder-only, GPT-2-small shape); ms per decode step"
+        desc = (f"{args.workload}: decoder-only d_model {hp.d_model}, {hp.n_dec} layers, FFN {hp.d_ffn}, vocab {hp.vocab}, "
+                f"batch {B}, prompt {int(w.src_lens[0])}, {hp.cap_extra} new tokens, top-{hp.sample_topk} sampling")
+    else:
+        metric = "decoded target tokens/sec at beam 4 (Transformer-big fp16); ms per decode step"
+        desc = (f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, "
+                f"FFN {hp.d_ffn}, vocab {hp.vocab}, batch {B}, beam {k}, "
+                f"src len mean {s_mean:.1f} max {int(w.src_lens.max())}, max_len {T}")
+    out = dict(metric=metric,
                value=value, unit="tokens/s", n_gpus=1, steps=K, warmup=W, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f16" if hp.dtype == 1 else "f32", data="synthetic",
-               config=dict(workload=f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, "
-                                    f"FFN {hp.d_ffn}, vocab {hp.vocab}, batch {B}, beam {k}, "
-                                    f"src len mean {s_mean:.1f} max {int(w.src_lens.max())}, max_len {T}",
-                           global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
+               config=dict(workload=desc, global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
                roofline=roof, cpu_baseline=cpu, **extra)
     print(json.dumps(out))
     return 0
