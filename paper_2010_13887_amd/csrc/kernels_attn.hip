@@ -120,6 +120,50 @@ __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict
   attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63);
 }
 
+// The same for few rows (rows * heads too small to fill the chip with one wavefront each): one
+// workgroup per (row, head), its four wavefronts take every fourth cached position and their
+// partial (max, sum, accumulator) are merged through LDS, so a cache of n positions costs
+// n / 128 round trips to memory per wavefront instead of n / 32.
+template <typename T, int DH>
+__global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __restrict__ q,
+                                                                   const T* __restrict__ Kc,
+                                                                   const T* __restrict__ Vc, T* __restrict__ out,
+                                                                   int rows, int H, int d, int T_, int nkeys_base,
+                                                                   const int32_t* __restrict__ tp, float scale) {
+  constexpr int LPK = DH / 8;
+  __shared__ float part[4][LPK][10];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nkeys = nkeys_base + (tp ? *tp : 0);
+  const int r = blockIdx.x / H, h = blockIdx.x % H;
+  const T* qp[1] = {q + (size_t)r * d + h * DH};
+  const size_t base = (size_t)r * T_ * d + h * DH;
+  float m[1], l[1], acc[1][8];
+  attend_partial<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, wave, 4, lane, m, l, acc);
+  if (lane < LPK) {
+    part[wave][lane][0] = m[0];
+    part[wave][lane][1] = l[0];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[wave][lane][2 + i] = acc[0][i];
+  }
+  __syncthreads();
+  if (wave == 0 && lane < LPK) {
+    float mx = fmaxf(fmaxf(part[0][lane][0], part[1][lane][0]), fmaxf(part[2][lane][0], part[3][lane][0]));
+    float sum = 0.f, o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = part[w][lane][0];
+      const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mx);   // a wavefront that saw no key
+      sum += part[w][lane][1] * c;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o8[i] += part[w][lane][2 + i] * c;
+    }
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o8[i] *= inv;
+    Vec8<T>::store(out + (size_t)r * d + h * DH + lane * 8, o8);
+  }
+}
+
 // Cross-attention: the NQ beams of one sentence share every key/value load.  kv rows are [K | V].
 // One workgroup of 256 threads per (sentence, head).  Source sentences are short (tens of keys),
 // so the work is organised to keep the fixed cost per workgroup small rather than to stream:
@@ -256,13 +300,22 @@ bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh 
     default: return hipErrorInvalidValue;         \
   }
 
+// up to this many (row, head) pairs a workgroup, not a wavefront, takes each pair
+constexpr int kSplitAttentionUnits = 2048;
+
 template <typename T>
 static hipError_t self_t(const T* q, const T* Kc, const T* Vc, T* out, int rows, int H, int d, int T_,
                          int nkeys, const int32_t* tp, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
-  dim3 g((rows * H + 3) / 4), b(256);
-  LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
+  dim3 b(256);
+  if (rows * H <= kSplitAttentionUnits) {
+    dim3 g(rows * H);
+    LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
+  } else {
+    dim3 g((rows * H + 3) / 4);
+    LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
+  }
   return hipGetLastError();
 }
 

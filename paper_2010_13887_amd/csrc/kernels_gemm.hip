@@ -315,15 +315,15 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
 // a stream of weights, so the job is to keep many weight bytes in flight from many CUs.
 // A workgroup owns 32 output columns and all rows; its four wavefronts take every fourth 16-wide
 // k-step, load their MFMA fragments straight from global memory (16 bytes per lane, no LDS and no
-// barrier in the loop, U k-steps in flight per wavefront), and their four partial tiles are added
-// through LDS at the end.  gridDim.y > 1 additionally splits K across workgroups (SPLIT, fp32
+// barrier in the loop, U k-steps in flight per wavefront: the launcher picks U so that a
+// wavefront's share of K is covered in as few passes, with as few padded loads, as possible),
+// and their four partial tiles are added through LDS at the end.  gridDim.y > 1 additionally splits K across workgroups (SPLIT, fp32
 // slabs for the LayerNorm consumer).
-template <int TM, bool SPLIT, typename OutT>
+template <int TM, int U, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
                                                               const half_t* __restrict__ B,
                                                               const half_t* __restrict__ bias, GemmOut out, int M,
                                                               int N, int K, int act, int vec_ok) {
-  constexpr int U = 16 / TM;   // k-steps in flight per wavefront: one round trip covers 256 / TM of K
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long tp = out.tpos ? *out.tpos : 0;
@@ -341,27 +341,27 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-  int ks = ks0 + wave;
   const int ks_end = ks0 + ksteps;
-  for (; ks + 4 * (U - 1) < ks_end; ks += 4 * U) {
+  // Every pass requests U k-steps before using any.  A k-step past the end of this wavefront's
+  // share re-reads the last valid one (no branch around the loads, so all U stay in flight) and
+  // its weight fragment is replaced by zeros.
+  for (int ks = ks0 + wave; ks < ks_end; ks += 4 * U) {
     half8_t bf[U], af[U][TM];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)(ks + 4 * u) * 16);
+      const int kc = min(ks + 4 * u, ks_end - 1);
+      bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)kc * 16);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[u][i] = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)(ks + 4 * u) * 16);
+      for (int i = 0; i < TM; ++i) af[u][i] = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)kc * 16);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+      if (ks + 4 * u >= ks_end) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bf[u][e] = (half_t)0.f;
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af[u][i], acc[i], 0, 0, 0);
-  }
-  for (; ks < ks_end; ks += 4) {
-    half8_t bf = *reinterpret_cast<const half8_t*>(bp + (size_t)ks * 16);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      half8_t af = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)ks * 16);
-      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, af, acc[i], 0, 0, 0);
     }
   }
 #pragma unroll
@@ -391,14 +391,45 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
 
 constexpr int kSkinnyRows = 64;   // above this the LDS-tiled kernel is faster
 
-template <int TM>
+// k-steps requested per pass for a wavefront that owns `per_wave` of them: at most `cap`
+// (registers), and among the sizes built, the one that pads the last pass least.
+static int skinny_unroll(int per_wave, int cap) {
+  static const int sizes[] = {16, 12, 8, 6, 4, 2};
+  int best = 2, best_cost = 1 << 30;
+  for (int u : sizes) {
+    if (u > cap) continue;
+    const int passes = (per_wave + u - 1) / u;
+    const int cost = passes * 64 + (passes * u - per_wave);   // passes first, then padding
+    if (cost < best_cost) { best = u; best_cost = cost; }
+  }
+  return best;
+}
+
+template <bool SPLIT, typename OutT>
 static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
-                       int K, int act, int vec_ok, hipStream_t s) {
-  dim3 grid((N + 31) / 32), blk(256);
-  if (out.f32_out)
-    gemm_f16_skinny_kernel<TM, false, float><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
-  else
-    gemm_f16_skinny_kernel<TM, false, half_t><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
+                       int K, int act, int vec_ok, int splits, hipStream_t s) {
+  dim3 grid((N + 31) / 32, splits), blk(256);
+  const int per_wave = (K / 16 / splits + 3) / 4;
+#define LSQ_SKINNY(TM_, U_) \
+  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok)
+  if (M <= 32) {
+    switch (skinny_unroll(per_wave, 16)) {
+      case 16: LSQ_SKINNY(1, 16); break;
+      case 12: LSQ_SKINNY(1, 12); break;
+      case 8: LSQ_SKINNY(1, 8); break;
+      case 6: LSQ_SKINNY(1, 6); break;
+      case 4: LSQ_SKINNY(1, 4); break;
+      default: LSQ_SKINNY(1, 2); break;
+    }
+  } else {
+    switch (skinny_unroll(per_wave, 8)) {
+      case 8: LSQ_SKINNY(2, 8); break;
+      case 6: LSQ_SKINNY(2, 6); break;
+      case 4: LSQ_SKINNY(2, 4); break;
+      default: LSQ_SKINNY(2, 2); break;
+    }
+  }
+#undef LSQ_SKINNY
 }
 
 template <int BM, int BN, int BK>
@@ -456,11 +487,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   if (K % (64 * splits) != 0) return hipErrorInvalidValue;
   const int vec_ok = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(P) & 15) == 0;
   if (M <= kSkinnyRows) {
-    dim3 grid((N + 31) / 32, splits), blk(256);
-    const half_t* a = (const half_t*)A;
-    const half_t* b = (const half_t*)B;
-    if (M <= 32) gemm_f16_skinny_kernel<1, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
-    else gemm_f16_skinny_kernel<2, true, float><<<grid, blk, 0, s>>>(a, b, nullptr, out, M, N, K, 0, vec_ok);
+    run_skinny<true, float>((const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok, splits, s);
     return hipGetLastError();
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
@@ -490,8 +517,8 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (M <= kSkinnyRows && K % 16 == 0) {
-    if (M <= 32) run_skinny<1>(a, b, bi, out, M, N, K, act, vec_ok, s);
-    else run_skinny<2>(a, b, bi, out, M, N, K, act, vec_ok, s);
+    if (out.f32_out) run_skinny<false, float>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
+    else run_skinny<false, half_t>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if (tiles128 >= 256)
