@@ -113,6 +113,17 @@ const char* lsq_last_error(void);
  * the same kernels one by one instead; results are identical.  Default: on. */
 int lsq_set_graphs(int on);
 
+/* Cache refreshing (sec. 3.2): after every beam-search step hypothesis r continues
+ * the history of hypothesis parent[r], so its cached keys/values must follow.
+ * LSQ_REFRESH_MOVE copies cache rows (what the paper does; lsq_k_cache_reorder).
+ * LSQ_REFRESH_TABLE (default) never moves a key or value: a table slab[r, j] names,
+ * for every position j of r's history, which of its sentence's beam rows wrote it;
+ * the re-rank kernel gathers that small table by parent and self-attention reads
+ * through it.  Takes effect at the next lsq_encode; results are bit-identical.
+ * Models decoded at beam 1 have nothing to refresh. */
+enum { LSQ_REFRESH_MOVE = 0, LSQ_REFRESH_TABLE = 1 };
+int lsq_set_cache_refresh(int mode);
+
 /* Number of decode steps taken since the last lsq_encode. */
 int lsq_step_index(void);
 
@@ -207,6 +218,22 @@ int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* s
                       int32_t* tokens, int32_t* len, int32_t* finished, int32_t* parent,
                       const int32_t* cap, int32_t* active, int batch, int k, int V, int T, int t,
                       int eos, void* stream);
+
+/* The same with the slab table of LSQ_REFRESH_TABLE: slab int32 [M, T+1] (device),
+ * slab[r, j] in 0..k-1 for j <= t on entry.  On return slab[r, 0..t] =
+ * old slab[b*k + parent[r], 0..t] and slab[r, t+1] = r mod k (row r itself will
+ * write position t+1). */
+int lsq_k_beam_refine_table(const float* cand_score, const int32_t* cand_idx, float* score,
+                            int32_t* tokens, int32_t* len, int32_t* finished, int32_t* parent,
+                            const int32_t* cap, int32_t* active, int32_t* slab, int batch, int k, int V,
+                            int T, int t, int eos, void* stream);
+
+/* Self-attention through the slab table: as lsq_k_self_attention, but position j
+ * of row r is read from cache row (r - r mod beam) + slab[r*(T+1) + j].
+ * rows must be a multiple of beam. */
+int lsq_k_self_attention_table(int dtype, const void* q, const void* Kc, const void* Vc,
+                               const int32_t* slab, void* out, int rows, int beam, int heads, int d,
+                               int T, int nkeys, void* stream);
 
 /* Cache refreshing (sec. 3.2): cache[l, b*k+i, 0:npos, :] <- cache[l, b*k+parent[b*k+i], 0:npos, :]
  * for all layers, in place.  cache [layers, M, T, d]. */

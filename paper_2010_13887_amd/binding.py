@@ -44,6 +44,7 @@ def load_library() -> C.CDLL:
         "lsq_get_beams": [vp, vp, vp],
         "lsq_step_index": [],
         "lsq_set_graphs": [i32],
+        "lsq_set_cache_refresh": [i32],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -51,9 +52,11 @@ def load_library() -> C.CDLL:
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "lsq_k_self_attention_table": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
         "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_row_topk": [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
         "lsq_k_beam_refine": [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
+        "lsq_k_beam_refine_table": [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
         "lsq_k_cache_reorder": [i32, vp, vp, i32, i32, i32, i32, i32, i32, vp],
     }
     for name, args in sig.items():
@@ -118,6 +121,15 @@ def lsq_decode_steps(n: int) -> int:
 
 def lsq_set_graphs(on: bool) -> None:
     _check(load_library().lsq_set_graphs(int(on)))
+
+
+REFRESH_MOVE, REFRESH_TABLE = 0, 1
+
+
+def lsq_set_cache_refresh(mode: int) -> None:
+    """How the K/V cache follows the beams from the next encode on: REFRESH_MOVE copies cache rows,
+    REFRESH_TABLE (default) keeps a table of which row holds which position."""
+    _check(load_library().lsq_set_cache_refresh(int(mode)))
 
 
 def lsq_step_index() -> int:
@@ -211,6 +223,15 @@ def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:
                                                _stream()))
 
 
+def k_self_attention_table(q, Kc, Vc, slab, out, beam: int, heads: int, nkeys: int) -> None:
+    """Self-attention where position j of row r is read from cache row (r - r % beam) + slab[r, j]."""
+    rows, d = q.shape
+    T = Kc.shape[1]
+    assert tuple(slab.shape) == (rows, T + 1)
+    _check(load_library().lsq_k_self_attention_table(_dt(q), _p(q), _p(Kc), _p(Vc), _p(slab), _p(out), rows, beam,
+                                                     heads, d, T, nkeys, _stream()))
+
+
 def k_cross_attention(q, kv, src_off, src_len, out, batch: int, beam: int, heads: int, max_src_len: int) -> None:
     d = q.shape[1]
     _check(load_library().lsq_k_cross_attention(_dt(q), _p(q), _p(kv), _p(src_off), _p(src_len), _p(out), batch,
@@ -224,10 +245,17 @@ def k_row_topk(logits, score, finished, k: int, eos: int, out_score, out_idx) ->
 
 
 def k_beam_refine(cand_score, cand_idx, score, tokens, length, finished, parent, cap, active, batch: int, k: int,
-                  V: int, T: int, t: int, eos: int) -> None:
-    _check(load_library().lsq_k_beam_refine(_p(cand_score), _p(cand_idx), _p(score), _p(tokens), _p(length),
-                                            _p(finished), _p(parent), _p(cap), _p(active), batch, k, V, T, t, eos,
-                                            _stream()))
+                  V: int, T: int, t: int, eos: int, slab=None) -> None:
+    """slab: optional int32 [batch*k, T+1] table gathered by parent along with the token histories."""
+    lib = load_library()
+    if slab is None:
+        _check(lib.lsq_k_beam_refine(_p(cand_score), _p(cand_idx), _p(score), _p(tokens), _p(length), _p(finished),
+                                     _p(parent), _p(cap), _p(active), batch, k, V, T, t, eos, _stream()))
+    else:
+        assert tuple(slab.shape) == (batch * k, T + 1)
+        _check(lib.lsq_k_beam_refine_table(_p(cand_score), _p(cand_idx), _p(score), _p(tokens), _p(length),
+                                           _p(finished), _p(parent), _p(cap), _p(active), _p(slab), batch, k, V, T,
+                                           t, eos, _stream()))
 
 
 def k_cache_reorder(cache, parent, layers: int, batch: int, k: int, T: int, d: int, npos: int) -> None:

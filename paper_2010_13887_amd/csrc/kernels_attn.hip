@@ -13,11 +13,15 @@ namespace lsq {
 // Keys j0, j0 + jstep, j0 + 2*jstep, ... (< nkeys) are visited, each lane group taking every
 // KPI-th of them.  On return every lane holds, for its 8 elements of the head row, the merged
 // (running max m, running sum l, un-normalised accumulator acc) of all keys this wavefront saw.
+// slot != nullptr: position j is not in this row's own slab but in slab slot[j] of its sentence
+// (K + slot[j] * slot_stride); the slot numbers of the next pass are requested together with the
+// rows of the current one, so the extra indirection is off the critical path after the first pass.
 template <typename T, int DH, int NQ>
 __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T* __restrict__ K,
                                                const T* __restrict__ V, long stride, int nkeys, float scale,
                                                int j0, int jstep, int lane, float (&m)[NQ], float (&l)[NQ],
-                                               float (&acc)[NQ][8]) {
+                                               float (&acc)[NQ][8], const int32_t* __restrict__ slot = nullptr,
+                                               long slot_stride = 0) {
   constexpr int LPK = DH / 8;
   constexpr int KPI = 64 / LPK;
   const int g = lane / LPK, c = lane % LPK;
@@ -34,13 +38,21 @@ __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T
   // positions costs n / (KPI * U) round trips to memory instead of n / KPI.
   constexpr int U = 4;
   const int step = KPI * jstep;
+  int sl[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) sl[u] = slot ? slot[min(j0 + g * jstep + u * step, nkeys - 1)] : 0;
   for (int jb = j0 + g * jstep; jb < nkeys; jb += U * step) {
     float kv[U][8], vv[U][8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = min(jb + u * step, nkeys - 1);   // past the end: a repeated row, not used
-      Vec8<T>::load(K + (long)j * stride + c * 8, kv[u]);
-      Vec8<T>::load(V + (long)j * stride + c * 8, vv[u]);
+      const long at = (long)sl[u] * slot_stride + (long)j * stride + c * 8;
+      Vec8<T>::load(K + at, kv[u]);
+      Vec8<T>::load(V + at, vv[u]);
+    }
+    if (slot) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) sl[u] = slot[min(jb + (U + u) * step, nkeys - 1)];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -88,10 +100,11 @@ __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T
 template <typename T, int DH, int NQ>
 __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __restrict__ K,
                                        const T* __restrict__ V, long stride, int nkeys, float scale,
-                                       T* const (&op)[NQ], int lane) {
+                                       T* const (&op)[NQ], int lane, const int32_t* __restrict__ slot = nullptr,
+                                       long slot_stride = 0) {
   constexpr int LPK = DH / 8;
   float m[NQ], l[NQ], acc[NQ][8];
-  attend_partial<T, DH, NQ>(qp, K, V, stride, nkeys, scale, 0, 1, lane, m, l, acc);
+  attend_partial<T, DH, NQ>(qp, K, V, stride, nkeys, scale, 0, 1, lane, m, l, acc, slot, slot_stride);
   if (lane < LPK) {
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
@@ -105,19 +118,25 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
 }
 
 // Decoder self-attention: row r, head h over cache positions 0..nkeys-1 of Kc/Vc [rows, T, d].
+// anc == nullptr: the history of row r is slab r.  Otherwise (cache refreshing without moving the
+// cache, paper sec. 3.2 turned around): position j of row r's history lives in slab
+// (r / beam) * beam + anc[r * anc_ld + j], the slab of the hypothesis that wrote it.
 template <typename T, int DH>
 __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict__ q, const T* __restrict__ Kc,
                                                              const T* __restrict__ Vc, T* __restrict__ out,
                                                              int rows, int H, int d, int T_, int nkeys_base,
-                                                             const int32_t* __restrict__ tp, float scale) {
+                                                             const int32_t* __restrict__ tp, float scale,
+                                                             const int32_t* __restrict__ anc, int beam, int anc_ld) {
   int w = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= rows * H) return;
   const int nkeys = nkeys_base + (tp ? *tp : 0);
   int r = w / H, h = w % H;
   const T* qp[1] = {q + (size_t)r * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
-  size_t base = (size_t)r * T_ * d + h * DH;
-  attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63);
+  const int home = anc ? r - r % beam : r;
+  size_t base = (size_t)home * T_ * d + h * DH;
+  attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63,
+                   anc ? anc + (size_t)r * anc_ld : nullptr, (long)T_ * d);
 }
 
 // The same for few rows (rows * heads too small to fill the chip with one wavefront each): one
@@ -129,16 +148,20 @@ __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __re
                                                                    const T* __restrict__ Kc,
                                                                    const T* __restrict__ Vc, T* __restrict__ out,
                                                                    int rows, int H, int d, int T_, int nkeys_base,
-                                                                   const int32_t* __restrict__ tp, float scale) {
+                                                                   const int32_t* __restrict__ tp, float scale,
+                                                                   const int32_t* __restrict__ anc, int beam,
+                                                                   int anc_ld) {
   constexpr int LPK = DH / 8;
   __shared__ float part[4][LPK][10];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nkeys = nkeys_base + (tp ? *tp : 0);
   const int r = blockIdx.x / H, h = blockIdx.x % H;
   const T* qp[1] = {q + (size_t)r * d + h * DH};
-  const size_t base = (size_t)r * T_ * d + h * DH;
+  const int home = anc ? r - r % beam : r;
+  const size_t base = (size_t)home * T_ * d + h * DH;
   float m[1], l[1], acc[1][8];
-  attend_partial<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, wave, 4, lane, m, l, acc);
+  attend_partial<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, wave, 4, lane, m, l, acc,
+                           anc ? anc + (size_t)r * anc_ld : nullptr, (long)T_ * d);
   if (lane < LPK) {
     part[wave][lane][0] = m[0];
     part[wave][lane][1] = l[0];
@@ -305,26 +328,28 @@ constexpr int kSplitAttentionUnits = 2048;
 
 template <typename T>
 static hipError_t self_t(const T* q, const T* Kc, const T* Vc, T* out, int rows, int H, int d, int T_,
-                         int nkeys, const int32_t* tp, hipStream_t s) {
+                         int nkeys, const int32_t* tp, const int32_t* anc, int beam, int anc_ld, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
   dim3 b(256);
   if (rows * H <= kSplitAttentionUnits) {
     dim3 g(rows * H);
-    LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
+    LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale, anc, beam, anc_ld)));
   } else {
     dim3 g((rows * H + 3) / 4);
-    LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale)));
+    LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale, anc, beam, anc_ld)));
   }
   return hipGetLastError();
 }
 
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
-                                 int rows, int H, int d, int T, int nkeys, const int32_t* tp, hipStream_t s) {
+                                 int rows, int H, int d, int T, int nkeys, const int32_t* tp, const int32_t* anc,
+                                 int beam, int anc_ld, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  if (anc && (beam < 1 || rows % beam != 0)) return hipErrorInvalidValue;
   if (dtype == DT_F16)
-    return self_t<half_t>((const half_t*)q, (const half_t*)Kc, (const half_t*)Vc, (half_t*)out, rows, H, d, T, nkeys, tp, s);
-  return self_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, rows, H, d, T, nkeys, tp, s);
+    return self_t<half_t>((const half_t*)q, (const half_t*)Kc, (const half_t*)Vc, (half_t*)out, rows, H, d, T, nkeys, tp, anc, beam, anc_ld, s);
+  return self_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, rows, H, d, T, nkeys, tp, anc, beam, anc_ld, s);
 }
 
 template <typename T, int NQ>

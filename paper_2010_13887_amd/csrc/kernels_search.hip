@@ -246,7 +246,8 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
                                                          int32_t* __restrict__ parent,
                                                          const int32_t* __restrict__ cap,
                                                          int32_t* __restrict__ active, int k, int V, int T1,
-                                                         int t_base, int32_t* __restrict__ step_state, int eos) {
+                                                         int t_base, int32_t* __restrict__ step_state, int eos,
+                                                         int32_t* __restrict__ anc) {
   __shared__ int sh_parent[LSQ_MAX_BEAM_];
   __shared__ int sh_unfinished;
   const int b = blockIdx.x, lane = threadIdx.x;
@@ -293,7 +294,24 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
           if (jj == src) val = h[jj];
         if (src != i) tokens[(size_t)(b * k + i) * T1 + p] = val;
       }
+    // the same gather for the table that says which slab holds position p of each history
+    // (cache refreshing without moving the cache); position t+1 will be written by the row itself
+    if (anc) {
+#pragma unroll
+      for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
+        if (i < k) h[i] = anc[(size_t)(b * k + i) * T1 + p];
+#pragma unroll
+      for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
+        if (i < k) {
+          int src = sh_parent[i], val = 0;
+#pragma unroll
+          for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
+            if (jj == src) val = h[jj];
+          if (src != i) anc[(size_t)(b * k + i) * T1 + p] = val;
+        }
+    }
   }
+  if (anc && lane < k && t + 1 < T1) anc[(size_t)(b * k + lane) * T1 + t + 1] = lane;
   __syncthreads();
   if (win) {
     const int row = b * k + rank;
@@ -327,11 +345,11 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
                               int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
                               int32_t* active, int batch, int k, int V, int T, int t_base, int32_t* step_state,
-                              int eos, hipStream_t s) {
+                              int eos, int32_t* anc, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
   beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
-                                          k, V, T + 1, t_base, step_state, eos);
+                                          k, V, T + 1, t_base, step_state, eos, anc);
   return hipGetLastError();
 }
 
@@ -396,7 +414,8 @@ hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, i
 // ---------------------------------------------------------------------------------------------
 __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict__ tokens, int32_t* __restrict__ len,
                                   int32_t* __restrict__ fin, int32_t* __restrict__ active_counts,
-                                  int32_t* __restrict__ step_state, int M, int k, int T1, int bos, int pad) {
+                                  int32_t* __restrict__ step_state, int32_t* __restrict__ anc, int M, int k,
+                                  int T1, int bos, int pad) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 3) step_state[i] = 0;   // [0] position counter, [1] arrival counter, [2] position of step 0
   if (i < M * T1) tokens[i] = (i % T1 == 0) ? bos : pad;
@@ -404,15 +423,17 @@ __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict
     score[i] = (i % k == 0) ? 0.f : -INFINITY;
     len[i] = 0;
     fin[i] = 0;
+    if (anc) anc[(size_t)i * T1] = i % k;   // position 0 is written by the row itself
   }
   if (i < T1) active_counts[i] = 0;
 }
 
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin, int32_t* active_counts,
-                             int32_t* step_state, int batch, int k, int T, int bos, int pad, hipStream_t s) {
+                             int32_t* step_state, int32_t* anc, int batch, int k, int T, int bos, int pad,
+                             hipStream_t s) {
   int M = batch * k, n = M * (T + 1);
-  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, step_state, M, k, T + 1,
-                                                    bos, pad);
+  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, step_state, anc, M, k,
+                                                    T + 1, bos, pad);
   return hipGetLastError();
 }
 

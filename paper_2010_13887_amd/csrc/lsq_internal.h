@@ -62,10 +62,11 @@ hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const floa
                                          const void* bias, const void* g, const void* b, int rows, int d,
                                          float eps, hipStream_t s);
 
-// nkeys = nkeys_base + (tp ? *tp : 0), with *tp read on the device
+// nkeys = nkeys_base + (tp ? *tp : 0), with *tp read on the device.  anc != null: position j of row
+// r's history is in slab (r / beam) * beam + anc[r * anc_ld + j] instead of slab r.
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
                                  int rows, int H, int d, int T, int nkeys_base, const int32_t* tp,
-                                 hipStream_t s);
+                                 const int32_t* anc, int beam, int anc_ld, hipStream_t s);
 // smax: an upper bound of len[] known to the host (sizes the LDS score buffer)
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
                                   const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
@@ -83,18 +84,20 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
                          unsigned long long seed, int n_new, hipStream_t s);
 // step = t_base + (step_state ? step_state[0] : 0).  `active` points at the counter array indexed
 // by step.  With step_state != null the last workgroup to finish advances step_state[0]
-// (step_state[1] is its arrival counter and must be zero at launch).
+// (step_state[1] is its arrival counter and must be zero at launch).  anc != null: the slab table
+// [batch*k, T+1] is gathered by parent like the token histories, and entry t+1 of every row is set
+// to the row's own beam index.
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
                               int32_t* tokens, int32_t* len, int32_t* fin, int32_t* parent,
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
-                              int t_base, int32_t* step_state, int eos, hipStream_t s);
+                              int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s);
 // npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
                                 int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,
                                 int npos_max, hipStream_t s);
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
-                             int32_t* active_counts, int32_t* step_state, int batch, int k, int T, int bos,
-                             int pad, hipStream_t s);
+                             int32_t* active_counts, int32_t* step_state, int32_t* anc, int batch, int k,
+                             int T, int bos, int pad, hipStream_t s);
 // first: index in the token history of the first token to hand out (1 after BOS; prompt length for
 // the decoder-only model)
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,

@@ -163,7 +163,7 @@ struct DecLayer {
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
 struct Plan {
-  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, cap, order, src_off, src_len, active, step_state,
+  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, anc, cap, order, src_off, src_len, active, step_state,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
@@ -186,6 +186,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.len = take(M * 4);
   p.fin = take(M * 4);
   p.parent = take(M * 4);
+  p.anc = take(M * (T + 1) * 4);   // which slab of its sentence holds position j of row r's history
   p.cap = take((size_t)B * 4);
   p.order = take((size_t)B * 4);
   p.src_off = take((size_t)(B + 1) * 4);
@@ -240,6 +241,8 @@ struct Ctx {
   bool done = false;
   std::vector<int> order;      // internal (sorted) sentence index -> caller's index
   bool use_graphs = true;
+  int refresh_mode = 1;   // how the next lsq_encode keeps the cache in step with the beams: 0 move rows, 1 slab table
+  bool anc_on = false;    // this translation uses the slab table
   std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
@@ -313,6 +316,7 @@ int launch_step(int B) {
   char* x = g.ws + p.d_x; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
   int32_t* step = at<int32_t>(p.step_state);
+  int32_t* anc = g.anc_on ? at<int32_t>(p.anc) : nullptr;
   const size_t slab = (size_t)M_max * T * d * es;   // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
   TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
@@ -326,7 +330,7 @@ int launch_step(int B) {
     o.tpos = step;
     o.tmul[1] = d; o.tmul[2] = d;
     TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
-    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, s));
+    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, anc, k, T + 1, s));
     if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, nullptr, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, 0, s));
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
@@ -345,9 +349,10 @@ int launch_step(int B) {
   TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                             at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T, 0,
-                            step, hp.eos, s));
-  TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
-                                         0, step, T, s));
+                            step, hp.eos, anc, s));
+  if (!anc)
+    TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
+                                           0, step, T, s));
   return LSQ_OK;
 }
 
@@ -375,7 +380,7 @@ int launch_step_gpt(int B) {
     o.tpos = step;
     o.tmul[1] = d; o.tmul[2] = d;
     TIMED(PC_GEMM_QKV, launch_gemm(dt, y, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
-    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, s));
+    TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, nullptr, 1, 0, s));
     if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln2g, L.ln2b, x, y, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_FFN1, launch_gemm(dt, y, L.W1, L.b1, plain_out(ffn, F), M, F, d, 2, s));
     const bool last = l + 1 == hp.n_dec;
@@ -664,6 +669,12 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     R += n;
   }
   HIPCHK(hipStreamSynchronize(g.stream));   // the staging buffer may still feed an earlier copy
+  const bool anc_on = hp.arch == 0 && g.beam > 1 && g.refresh_mode == 1;
+  if (anc_on != g.anc_on) {   // captured steps hold the other mode's kernels and arguments
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+    g.anc_on = anc_on;
+  }
   if (hp.arch == 1) return encode_gpt(src_ids, src_lens, batch, src_stride);
   const Plan& p = g.plan;
   const size_t Rmax = (size_t)g.max_batch * g.max_len;
@@ -728,7 +739,8 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     HIPCHK(launch_gemm(dt, x, g.dec[l].Wkv, g.dec[l].bkv, plain_out(g.ws + p.cross + l * cross_l, 2 * d), (int)R,
                        2 * d, d, 0, s));
   HIPCHK(launch_beam_reset(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
-                           at<int32_t>(p.active), at<int32_t>(p.step_state), batch, g.beam, g.max_len, hp.bos,
+                           at<int32_t>(p.active), at<int32_t>(p.step_state), g.anc_on ? at<int32_t>(p.anc) : nullptr, batch,
+                           g.beam, g.max_len, hp.bos,
                            hp.pad, s));
   g.batch = batch;
   g.rows_enc = (int)R;
@@ -786,6 +798,12 @@ int lsq_set_graphs(int on) {
   return LSQ_OK;
 }
 
+int lsq_set_cache_refresh(int mode) {
+  if (mode != LSQ_REFRESH_MOVE && mode != LSQ_REFRESH_TABLE) return fail(LSQ_E_ARG, "unknown cache refresh mode %d", mode);
+  g.refresh_mode = mode;
+  return LSQ_OK;
+}
+
 int lsq_step_index(void) { return g.state >= 3 ? g.t : 0; }
 
 int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
@@ -827,6 +845,7 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
   size_t n = 0;
   bool is_float_data = false;   // stored in the model dtype, delivered as float
   bool per_source_row = false;  // leading dimension is packed source rows, not batch*beam rows
+  bool cache_item = false;
   switch (what) {
     case LSQ_DBG_LOGITS: src = g.ws + p.d_logits; n = M * hp.V; break;   // always fp32
     case LSQ_DBG_SCORE: src = g.ws + p.score; n = M; break;
@@ -844,8 +863,8 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
       int l = what % 100, kind = what - l;
       if (l < 0 || l >= hp.n_dec) return fail(LSQ_E_ARG, "unknown debug item %d", what);
       if (kind == LSQ_DBG_CROSS_KV) { n = R * 2 * d; src = g.ws + p.cross + (size_t)l * g.max_batch * g.max_len * 2 * d * esz(); per_source_row = true; }
-      else if (kind == LSQ_DBG_CACHE_K) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * g.max_batch * g.beam * T * d * esz(); }
-      else if (kind == LSQ_DBG_CACHE_V) { n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * g.max_batch * g.beam * T * d * esz(); }
+      else if (kind == LSQ_DBG_CACHE_K) { cache_item = true; n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l) * g.max_batch * g.beam * T * d * esz(); }
+      else if (kind == LSQ_DBG_CACHE_V) { cache_item = true; n = M * T * d; src = g.ws + p.cache + (size_t)(2 * l + 1) * g.max_batch * g.beam * T * d * esz(); }
       else return fail(LSQ_E_ARG, "unknown debug item %d", what);
       is_float_data = true;
     }
@@ -861,6 +880,20 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     HIPCHK(hipMemcpyAsync(tmp.data(), src, n * 2, hipMemcpyDeviceToHost, g.stream));
     HIPCHK(hipStreamSynchronize(g.stream));
     for (size_t i = 0; i < n; ++i) raw[i] = (float)tmp[i];
+  }
+  if (cache_item && g.anc_on) {
+    // hand the cache back as if rows had been moved: position j of row r comes from the slab the table names
+    std::vector<int32_t> anc((size_t)M * (T + 1));
+    HIPCHK(hipMemcpyAsync(anc.data(), g.ws + p.anc, anc.size() * 4, hipMemcpyDeviceToHost, g.stream));
+    HIPCHK(hipStreamSynchronize(g.stream));
+    std::vector<float> moved(n);
+    const size_t written = std::min((size_t)g.t, T);   // positions 0..t-1 hold keys/values; the rest is stale either way
+    for (size_t r = 0; r < M; ++r)
+      for (size_t j = 0; j < T; ++j) {
+        const size_t from = j < written ? r - r % g.beam + (size_t)anc[r * (T + 1) + j] : r;
+        memcpy(&moved[(r * T + j) * d], &raw[(from * T + j) * d], d * 4);
+      }
+    raw.swap(moved);
   }
   float* dst = (float*)host_dst;
   if (per_source_row) {
@@ -925,7 +958,7 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
   KCHK(rows >= 0 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "head size must be 16/32/64/128");
   KCHK(nkeys >= 1 && nkeys <= T, "nkeys outside [1, T]");
-  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, nullptr, (hipStream_t)stream));
+  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, nullptr, nullptr, 1, 0, (hipStream_t)stream));
 }
 
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off, const int32_t* src_len,
@@ -945,13 +978,31 @@ int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int3
   KRUN(launch_row_topk(dtype, logits, score, finished, M, V, k, eos, 0, out_score, out_idx, (hipStream_t)stream));
 }
 
-int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,
-                      int32_t* finished, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
-                      int V, int T, int t, int eos, void* stream) {
+int lsq_k_beam_refine_table(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
+                            int32_t* len, int32_t* finished, int32_t* parent, const int32_t* cap, int32_t* active,
+                            int32_t* slab, int batch, int k, int V, int T, int t, int eos, void* stream) {
   KCHK(cand_score && cand_idx && score && tokens && len && finished && parent && cap && active, "null pointer");
   KCHK(batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && V >= k && T >= 1 && t >= 0 && t < T, "shape");
   KRUN(launch_beam_refine(cand_score, cand_idx, score, tokens, len, finished, parent, cap, active, batch, k, V, T, t,
-                          nullptr, eos, (hipStream_t)stream));
+                          nullptr, eos, slab, (hipStream_t)stream));
+}
+
+int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,
+                      int32_t* finished, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
+                      int V, int T, int t, int eos, void* stream) {
+  return lsq_k_beam_refine_table(cand_score, cand_idx, score, tokens, len, finished, parent, cap, active, nullptr,
+                                 batch, k, V, T, t, eos, stream);
+}
+
+int lsq_k_self_attention_table(int dtype, const void* q, const void* Kc, const void* Vc, const int32_t* slab,
+                               void* out, int rows, int beam, int heads, int d, int T, int nkeys, void* stream) {
+  KCHK(q && Kc && Vc && slab && out, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(rows >= 0 && beam >= 1 && beam <= LSQ_MAX_BEAM && rows % beam == 0, "rows must be a multiple of beam");
+  KCHK(heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "head size must be 16/32/64/128");
+  KCHK(T >= 1 && nkeys >= 1 && nkeys <= T, "nkeys outside [1, T]");
+  KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, nullptr, slab, beam, T + 1,
+                             (hipStream_t)stream));
 }
 
 int lsq_k_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch, int k, int T, int d,

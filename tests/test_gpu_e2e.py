@@ -116,3 +116,33 @@ def test_graph_replay_matches_eager_launches(lsq):
         assert steps >= 10
         for a, b, c in zip(eager, graphed, again):
             assert np.array_equal(a, b) and np.array_equal(a, c)
+
+
+def test_cache_refresh_modes_agree_and_cache_matches_oracle(lsq):
+    """Moving cache rows by parent and reading through the slab table are the same computation:
+    bit-identical beams, and after some steps the cache handed back (row r = history of hypothesis r)
+    holds the oracle's keys and values in both modes."""
+    hp = S.HParams(n_enc=1, n_dec=2, d_model=128, n_heads=2, d_ffn=256, vocab=504, max_pos=64, dtype=0, cap_extra=8)
+    w = S.custom(hp, [3, 17, 9, 1, 12, 6], beam=4, max_len=26, std=0.3)
+    blob = w.blob(ln_jitter=0.1)
+    m = O.Model(blob)
+    B, k, T, d = w.batch, w.beam, w.max_len, hp.d_model
+    results = []
+    try:
+        for mode in (lsq.REFRESH_MOVE, lsq.REFRESH_TABLE):
+            lsq.lsq_set_cache_refresh(mode)
+            with lsq.Engine(blob, B, k, T) as eng:
+                res = lockstep(lsq, eng, blob, w, max_steps=7)
+                st = res["state"]                            # oracle state after 7 steps, resynced to the library
+                moved = (eng.debug(lsq.DBG.PARENT, (B * k,), np.int32).reshape(B, k) != np.arange(k)).any()
+                for l in range(hp.n_dec):
+                    for item, ref in ((lsq.DBG.CACHE_K, st.Kc[l]), (lsq.DBG.CACHE_V, st.Vc[l])):
+                        got = eng.debug(item + l, (B * k, T, d))
+                        alive = np.repeat(st.cap > 7, k) & ~st.finished.reshape(-1)   # rows both sides still extend
+                        np.testing.assert_allclose(got[alive, :7], np.asarray(ref)[alive, :7], rtol=1e-4, atol=1e-4)
+                results.append(eng.translate(w.src_ids, w.src_lens, sync_every=3) + (moved,))
+    finally:
+        lsq.lsq_set_cache_refresh(lsq.REFRESH_TABLE)
+    assert results[0][3] or results[1][3]                    # beams really changed parents
+    for a, b in zip(results[0][:3], results[1][:3]):
+        assert np.array_equal(a, b)

@@ -108,7 +108,8 @@ def test_gemm_add_layernorm(env, rows, d, K, half):
 
 
 @pytest.mark.parametrize("rows,H,dh,T,nkeys", [(3, 4, 16, 8, 1), (9, 4, 16, 8, 8), (32, 8, 64, 110, 77),
-                                               (5, 2, 128, 40, 33), (7, 3, 32, 50, 50), (130, 16, 64, 178, 41)])
+                                               (5, 2, 128, 40, 33), (7, 3, 32, 50, 50), (130, 16, 64, 178, 41),
+                                               (300, 8, 64, 60, 60), (2, 2, 16, 200, 199)])
 @pytest.mark.parametrize("half", [False, True])
 def test_self_attention(env, rows, H, dh, T, nkeys, half):
     lsq, torch = env
@@ -122,6 +123,30 @@ def test_self_attention(env, rows, H, dh, T, nkeys, half):
     lsq.k_self_attention(_dev(torch, q, td), _dev(torch, Kc, td), _dev(torch, Vc, td), out, H, nkeys)
     ref = np.stack([O.attention(q[r:r + 1].astype(np.float64), Kc[r, :nkeys].astype(np.float64),
                                 Vc[r, :nkeys].astype(np.float64), H)[0] for r in range(rows)])
+    tol = 1.5e-3 if half else 2e-5
+    np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
+
+
+@pytest.mark.parametrize("B,k,H,dh,T,nkeys", [(2, 4, 4, 16, 8, 1), (3, 4, 8, 64, 110, 77), (5, 3, 2, 32, 50, 50),
+                                              (75, 4, 8, 64, 60, 41), (2, 8, 2, 128, 40, 33), (4, 1, 4, 16, 9, 9)])
+@pytest.mark.parametrize("half", [False, True])
+def test_self_attention_through_slab_table(env, B, k, H, dh, T, nkeys, half):
+    """Position j of row r is read from cache row (r - r % k) + slab[r, j]: equals attention over the
+    gathered history."""
+    lsq, torch = env
+    rng = np.random.default_rng(B * 7 + k + nkeys)
+    rows, d = B * k, H * dh
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    q = cast(rng.standard_normal((rows, d)))
+    Kc, Vc = cast(rng.standard_normal((rows, T, d))), cast(rng.standard_normal((rows, T, d)))
+    slab = rng.integers(0, k, size=(rows, T + 1)).astype(np.int32)
+    slab[:, nkeys:] = 1 << 20                              # entries past the history must never be read
+    td = torch.float16 if half else torch.float32
+    out = torch.full((rows, d), 7.0, dtype=td, device="cuda")
+    lsq.k_self_attention_table(_dev(torch, q, td), _dev(torch, Kc, td), _dev(torch, Vc, td), _dev(torch, slab), out, k, H, nkeys)
+    j = np.arange(nkeys)
+    ref = np.stack([O.attention(q[r:r + 1].astype(np.float64), Kc[r - r % k + slab[r, :nkeys], j].astype(np.float64),
+                                Vc[r - r % k + slab[r, :nkeys], j].astype(np.float64), H)[0] for r in range(rows)])
     tol = 1.5e-3 if half else 2e-5
     np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
 
@@ -245,9 +270,19 @@ def test_row_topk_then_refine_matches_oracle_step(env, B, k, V, T, t, ties):
     parent = torch.zeros(M, dtype=torch.int32, device="cuda")
     active = torch.zeros(1, dtype=torch.int32, device="cuda")
     lsq.k_row_topk(_dev(torch, logits), d_score, d_fin, k, m.eos, cs, ci)
-    lsq.k_beam_refine(cs, ci, d_score, d_tokens, d_len, d_fin, parent, _dev(torch, cap), active, B, k, V, T, t, m.eos)
+    slab0 = rng.integers(0, k, size=(M, T + 1)).astype(np.int32)
+    slab0[:, t + 1:] = -7                                   # not yet meaningful
+    d_slab = _dev(torch, slab0)
+    lsq.k_beam_refine(cs, ci, d_score, d_tokens, d_len, d_fin, parent, _dev(torch, cap), active, B, k, V, T, t, m.eos,
+                      slab=d_slab)
     ok = (margin > 1e-4) | ties        # with exact ties both sides see identical scores per row
     g_par = parent.cpu().numpy().reshape(B, k)
+    # the slab table follows the library's own parents exactly: history gathered, next position = own row
+    g_slab = d_slab.cpu().numpy()
+    src_row = (np.arange(M) // k) * k + g_par.reshape(-1)
+    assert np.array_equal(g_slab[:, :t + 1], slab0[src_row, :t + 1])
+    assert np.array_equal(g_slab[:, t + 1], np.arange(M) % k)
+    assert (g_slab[:, t + 2:] == -7).all()
     g_tok, g_len, g_fin = d_tokens.cpu().numpy(), d_len.cpu().numpy(), d_fin.cpu().numpy()
     g_score = d_score.cpu().numpy().reshape(B, k)
     assert ok.mean() > 0.5
