@@ -69,6 +69,25 @@ def main() -> int:
         by = (2 * M * nkeys * d + 2 * M * d) * 2
         cases.append((name, "hbm", 4.0 * M * nkeys * d, by, lambda: lsq.k_self_attention(q, Kc, Vc, out, H, nkeys)))
 
+    def self_attn_table_case(name, B, k, H, d, T, nkeys):
+        # slab table of a simulated beam search: every step each row continues a random row of its
+        # sentence (its own with probability 1/2), so older positions converge on few ancestors
+        M = B * k
+        rs_ = np.random.default_rng(99)
+        slab = np.zeros((M, T + 1), np.int32)
+        slab[:, 0] = np.arange(M) % k
+        for t in range(1, nkeys):
+            par = np.where(rs_.random(M) < 0.5, np.arange(M) % k, rs_.integers(0, k, M))
+            slab[:, :t] = slab[(np.arange(M) // k) * k + par, :t]
+            slab[:, t] = np.arange(M) % k
+        q, Kc, Vc = rnd(M, d), rnd(M, T, d), rnd(M, T, d)
+        out = torch.empty(M, d, device=dev, dtype=h)
+        dslab = torch.from_numpy(slab).to(dev)
+        distinct = sum(len(set(zip(slab[b * k:(b + 1) * k, j].tolist(), [j] * k))) for b in range(B) for j in range(nkeys))
+        by = (2 * distinct * d + 2 * M * d) * 2          # distinct (row, position) pairs actually referenced
+        cases.append((name + f" ({distinct / (M * nkeys):.2f} of the rows distinct)", "hbm", 4.0 * M * nkeys * d, by,
+                      lambda: lsq.k_self_attention_table(q, Kc, Vc, dslab, out, k, H, nkeys)))
+
     def cross_attn_case(name, B, k, H, d, lens):
         lens = np.asarray(lens, np.int32)
         off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
@@ -108,6 +127,7 @@ def main() -> int:
     sublayer_case("sublayer_ffn2 M512 d1024 K4096 (split-K gemm + add_layernorm)", M, d, F)
     gemm_case("gemm_vocab M512 N32000 K1024 f32out", M, V, d, out_f32=True)
     self_attn_case("attn_self M512 t41", M, H, d, T, 41)
+    self_attn_table_case("attn_self_table M512 t41", 128, 4, H, d, T, 41)
     rs = np.random.default_rng(4321)
     cross_attn_case("attn_cross B128 k4 meanlen29", 128, 4, H, d, np.clip(np.rint(rs.lognormal(3.15, 0.6, 128)), 1, 128))
     topk_case("row_topk M512 V32000 k4", M, V, 4)
@@ -117,6 +137,7 @@ def main() -> int:
         gemm_case("stress gemm_vocab M4096 N32000 K1024 f32out", 4096, V, d, out_f32=True)
         sublayer_case("stress sublayer M16384 d1024 K1024", 16384, d, d)
         self_attn_case("stress attn_self M2048 t175 (full cache, 2.9 GB)", 2048, H, d, T, T)
+        self_attn_table_case("stress attn_self_table M2048 t175", 512, 4, H, d, T, T)
         topk_case("stress row_topk M16384 V32000 k4 (2.1 GB)", 16384, V, 4)
         reorder_case("stress cache_reorder L12 B512 k4 t175 (3 of 4 rows move)", 2 * L, 512, 4, T, d, T)
     copy_case("copy 1 GiB -> 1 GiB (torch)", 1 << 30)

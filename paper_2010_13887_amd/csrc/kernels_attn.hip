@@ -131,6 +131,13 @@ __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict
   if (w >= rows * H) return;
   const int nkeys = nkeys_base + (tp ? *tp : 0);
   int r = w / H, h = w % H;
+  if (anc) {
+    // the beams of a sentence mostly read the same slabs (shared ancestors): put them, for one
+    // head, into neighbouring wavefronts of one workgroup so that those rows are fetched once
+    const int bm = w % beam, rest = w / beam;
+    h = rest % H;
+    r = (rest / H) * beam + bm;
+  }
   const T* qp[1] = {q + (size_t)r * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
   const int home = anc ? r - r % beam : r;
