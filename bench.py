@@ -143,6 +143,20 @@ def main() -> int:
     value = tokens / dt
     ms_per_step = dt / K * 1e3
 
+    # whole translation, end to end: encode (host ids in, encoder, cross K/V) + every decode step +
+    # get_beams (results back on the host); tokens = length of the best hypothesis of every sentence
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.encode(w.src_ids, w.src_lens)
+    torch.cuda.synchronize()
+    t_enc = time.perf_counter() - t0
+    while eng.decode_steps(64) > 0:
+        pass
+    eng.get_beams()
+    t_all = time.perf_counter() - t0
+    end_to_end = dict(tokens_per_s=float(best_len.sum()) / t_all, total_ms=t_all * 1e3, encode_ms=t_enc * 1e3,
+                      steps=total_steps)
+
     # instrumented pass: per-kernel-class durations over the same K steps
     dt_prof, prof = run(True)
     # Work per class summed over the timed steps.  Step t works on the sentences whose cap
@@ -247,7 +261,7 @@ def main() -> int:
                higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f16" if hp.dtype == 1 else "f32", data="synthetic",
                config=dict(workload=desc, global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
-               roofline=roof, cpu_baseline=cpu, **extra)
+               roofline=roof, cpu_baseline=cpu, end_to_end=end_to_end, **extra)
     print(json.dumps(out))
     return 0
 
