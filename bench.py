@@ -44,10 +44,10 @@ MEASURED_TRAFFIC_BIG128 = {
     "gemm_ffn1": 17.0e6 + 4.2e6,
     "gemm_ffn2": 42.0e6 + 8.4e6,
     "gemm_vocab": 86.6e6 + 68.3e6,
-    "attn_self": 87.1e6 + 1.0e6,
+    "attn_self": 29.9e6 + 1.0e6,            # through the slab table: 0.32 of the (row, position) pairs distinct
     "attn_cross": 16.2e6 + 1.0e6,
     "row_topk": 65.9e6 + 8.4e6,
-    "cache_reorder": 129.2e6 + 386.9e6,     # 3 of 4 rows of every sentence moved
+    "cache_reorder": 129.2e6 + 386.9e6,     # LSQ_REFRESH_MOVE only: 3 of 4 rows of every sentence moved
 }
 
 
