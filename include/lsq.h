@@ -124,6 +124,13 @@ int lsq_set_graphs(int on);
 enum { LSQ_REFRESH_MOVE = 0, LSQ_REFRESH_TABLE = 1 };
 int lsq_set_cache_refresh(int mode);
 
+/* With at most 8 rows alive (the end of a batch, single sentences) a float16
+ * encoder-decoder model folds every sublayer's "partial sums + bias + residual,
+ * LayerNorm" into the product that consumes the normalised rows (sec. 2.1 taken
+ * one step further: 18 fewer launches per step).  on = 0 keeps the stand-alone
+ * LayerNorm kernel at every size; results are bit-identical.  Default: on. */
+int lsq_set_layernorm_fusion(int on);
+
 /* Number of decode steps taken since the last lsq_encode. */
 int lsq_step_index(void);
 
@@ -187,6 +194,14 @@ size_t lsq_k_gemm_add_layernorm_scratch(int dtype, int M, int d, int K);
 int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const void* bias, void* x,
                              const void* gamma, const void* beta, int M, int d, int K, float eps,
                              void* scratch, void* stream);
+
+/* C = act(LN(x_old + sum_s P[s] + ln_bias) . W^T + bias) for 1..8 rows, float16:
+ * the LayerNorm of lsq_k_gemm_add_layernorm done by the product that consumes it.
+ * P float [splits <= 4, M, K]; x_old, x_new [M,K] (different buffers; x_new
+ * receives the normalised rows); W [N,K]; K a multiple of 16, at most 1024. */
+int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_bias, const void* gamma,
+                         const void* beta, const void* x_old, void* x_new, float eps, const void* W,
+                         const void* bias, void* C, int M, int N, int K, int flags, void* stream);
 
 /* Decoder self-attention of one new position per row over its cached keys:
  * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions

@@ -45,6 +45,8 @@ def load_library() -> C.CDLL:
         "lsq_step_index": [],
         "lsq_set_graphs": [i32],
         "lsq_set_cache_refresh": [i32],
+        "lsq_set_layernorm_fusion": [i32],
+        "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -121,6 +123,11 @@ def lsq_decode_steps(n: int) -> int:
 
 def lsq_set_graphs(on: bool) -> None:
     _check(load_library().lsq_set_graphs(int(on)))
+
+
+def lsq_set_layernorm_fusion(on: bool) -> None:
+    """LayerNorm inside the consuming product when at most 8 rows are alive (default on)."""
+    _check(load_library().lsq_set_layernorm_fusion(int(on)))
 
 
 REFRESH_MOVE, REFRESH_TABLE = 0, 1
@@ -214,6 +221,16 @@ def k_gemm_add_layernorm(inp, W, bias, x, gamma, beta, eps: float) -> None:
                           device=x.device)
     _check(lib.lsq_k_gemm_add_layernorm(_dt(x), _p(inp), _p(W), _p(bias), _p(x), _p(gamma), _p(beta), M, d, K, eps,
                                         _p(scratch), _stream()))
+
+
+def k_layernorm_gemm(P, ln_bias, gamma, beta, x_old, x_new, eps: float, W, bias, C_out, relu: bool = False) -> None:
+    """C_out = act(LN(x_old + sum of the slabs P + ln_bias) . W^T + bias); x_new receives the normalised rows."""
+    import torch
+    splits, M, K = P.shape
+    N = W.shape[0]
+    flags = int(relu) | (2 if C_out.dtype == torch.float32 else 0)
+    _check(load_library().lsq_k_layernorm_gemm(_dt(x_old), _p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old),
+                                               _p(x_new), eps, _p(W), _p(bias), _p(C_out), M, N, K, flags, _stream()))
 
 
 def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:

@@ -93,12 +93,11 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
   T* xr = x + (size_t)r * d;
   const size_t slab = (size_t)rows * d;
   float v[NV][8], gv[NV][8], bv[NV][8];
-  float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     int c = (j * 64 + lane) * 8;
     if (c < d) {
-      float a[8], t[8], part[S > 0 ? S : 1][8];
+      float t[8], part[S > 0 ? S : 1][8];
 #pragma unroll
       for (int s = 0; s < S; ++s) Vec8<float>::load(P + s * slab + (size_t)r * d + c, part[s]);   // all in flight
       if (S > 0) Vec8<T>::load(bias + c, t);
@@ -106,48 +105,24 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
       Vec8<T>::load(g + c, gv[j]);      // gain and shift too: one round trip to memory in all
       Vec8<T>::load(b + c, bv[j]);
       if (S > 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] = part[0][i];
-#pragma unroll
-        for (int s = 1; s < S; ++s)
-#pragma unroll
-          for (int i = 0; i < 8; ++i) a[i] += part[s][i];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[j][i] += a[i] + t[i];
+        add_partials<(S > 0 ? S : 1)>(v[j], part, S, t);
         if (PRE) {   // the residual stream is stored here; LayerNorm sees the stored values
 #pragma unroll
           for (int i = 0; i < 8; ++i) v[j][i] = (float)(T)v[j][i];
           Vec8<T>::store(xr + c, v[j]);
         }
       }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) sum += v[j][i];
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[j][i] = 0.f;
+      for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
     }
   }
-  float mean = wave_sum(sum) / (float)d;
-  float sq = 0.f;
+  float o[NV][8];
+  layernorm_row<NV>(v, gv, bv, d, eps, lane, o);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     int c = (j * 64 + lane) * 8;
-    if (c < d) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { v[j][i] -= mean; sq += v[j][i] * v[j][i]; }
-    }
-  }
-  float var = wave_sum(sq) / (float)d;
-  float rstd = 1.0f / sqrtf(var + eps);
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    int c = (j * 64 + lane) * 8;
-    if (c < d) {
-      float o[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = gv[j][i] * (v[j][i] * rstd) + bv[j][i];
-      Vec8<T>::store((PRE ? y + (size_t)r * d : xr) + c, o);
-    }
+    if (c < d) Vec8<T>::store((PRE ? y + (size_t)r * d : xr) + c, o[j]);
   }
 }
 

@@ -432,6 +432,141 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, con
 #undef LSQ_SKINNY
 }
 
+// ---------------------------------------------------------------------------------------------
+// Skinny product whose input rows are made on the spot: A = LayerNorm(residual + split-K partial
+// sums of the previous product + its bias), for the very few rows left near the end of a batch
+// (M <= kLnFusedRows), where the step is nothing but launch latencies and a separate LayerNorm
+// kernel costs as much as a product.  Every workgroup requests its weight fragments first, then
+// its four wavefronts normalise the M rows (the same arithmetic, in the same order, as the
+// stand-alone kernel) into LDS while those fragments travel, and the multiply reads A from LDS.
+// Workgroup 0 also writes the normalised rows to x_new -- a different buffer from x_old, which the
+// other workgroups are still reading -- for the next residual connection.
+template <int U, typename OutT>
+__global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(LnInput ln, const half_t* __restrict__ B,
+                                                                 const half_t* __restrict__ bias, GemmOut out,
+                                                                 int M, int N, int K, int act, int vec_ok) {
+  constexpr int NV = 2;   // K <= 1024: a lane owns at most two 8-element pieces of a row
+  extern __shared__ __attribute__((aligned(16))) half_t a_rows[];   // [M][K + 8]
+  __shared__ float red[4][16][64];
+  const int LDA = K + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long tp = out.tpos ? *out.tpos : 0;
+  const int n0 = blockIdx.x * 32;
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int ksteps = K / 16;
+  const half_t* bp = B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  half8_t bf[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(wave + 4 * u, ksteps - 1) * 16);
+
+  const size_t slab = (size_t)M * K;
+  for (int r = wave; r < M; r += 4) {
+    float v[NV][8], gv[NV][8], bv[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * 8;
+      if (c < K) {
+        float t[8], part[4][8];
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp)
+          if (sp < ln.splits) Vec8<float>::load(ln.P + sp * slab + (size_t)r * K + c, part[sp]);
+        Vec8<half_t>::load(ln.bias + c, t);
+        Vec8<half_t>::load(ln.x_old + (size_t)r * K + c, v[j]);
+        Vec8<half_t>::load(ln.g + c, gv[j]);
+        Vec8<half_t>::load(ln.b + c, bv[j]);
+        add_partials<4>(v[j], part, ln.splits, t);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
+      }
+    }
+    float o[NV][8];
+    layernorm_row<NV>(v, gv, bv, K, ln.eps, lane, o);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int c = (j * 64 + lane) * 8;
+      if (c < K) {
+        Vec8<half_t>::store(&a_rows[r * LDA + c], o[j]);
+        if (blockIdx.x == 0) Vec8<half_t>::store(ln.x_new + (size_t)r * K + c, o[j]);
+      }
+    }
+  }
+  __syncthreads();
+
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  const half_t* ar = a_rows + min(fr, M - 1) * LDA + fk;
+  for (int ks = wave; ks < ksteps; ks += 4 * U) {
+    if (ks != wave) {   // K beyond one pass: later fragments are fetched here
+#pragma unroll
+      for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(ks + 4 * u, ksteps - 1) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const half8_t af = *reinterpret_cast<const half8_t*>(ar + min(ks + 4 * u, ksteps - 1) * 16);
+      if (ks + 4 * u >= ksteps) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bf[u][e] = (half_t)0.f;
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af, acc, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
+  __syncthreads();
+  const int vg = wave;
+  const int n = n0 + vg * 8 + (lane >> 5) * 4;
+  const int m = lane & 31;
+  if (n >= N || m >= M) return;
+  float v4[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int r = vg * 4 + e;
+    v4[e] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+    if (bias) v4[e] += (float)bias[min(n + e, N - 1)];
+    v4[e] = activate(v4[e], act);
+  }
+  store4<OutT, false>(out, m, n, v4, M, N, vec_ok, 0, tp);
+}
+
+constexpr int kLnFusedRows = 8;
+
+bool gemm_ln_supported(int dtype, int M, int K) {
+  return dtype == DT_F16 && M >= 1 && M <= kLnFusedRows && K >= 16 && K <= 1024 && K % 16 == 0;
+}
+
+hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, const GemmOut& out, int M, int N,
+                          int K, int act, hipStream_t s) {
+  if (N <= 0) return hipSuccess;
+  if (!gemm_ln_supported(DT_F16, M, K) || ln.splits < 1 || ln.splits > 4 || ln.x_old == ln.x_new) return hipErrorInvalidValue;
+  int nseg = (N + out.seg_n - 1) / out.seg_n;
+  if (nseg > 3) return hipErrorInvalidValue;
+  int vec_ok = (out.seg_n % 4 == 0);
+  for (int i = 0; i < nseg; ++i)
+    if (out.ld[i] % 4 != 0 || out.tmul[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & (out.f32_out ? 15 : 7)) != 0) vec_ok = 0;
+  dim3 grid((N + 31) / 32), blk(256);
+  const size_t lds = (size_t)M * (K + 8) * sizeof(half_t);
+  const int per_wave = (K / 16 + 3) / 4;
+  const half_t* b = (const half_t*)B;
+  const half_t* bi = (const half_t*)bias;
+#define LSQ_SKINNY_LN(U_)                                                                                          \
+  do {                                                                                                             \
+    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(ln, b, bi, out, M, N, K, act, vec_ok); \
+    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(ln, b, bi, out, M, N, K, act, vec_ok);      \
+  } while (0)
+  switch (skinny_unroll(per_wave, 16)) {
+    case 16: LSQ_SKINNY_LN(16); break;
+    case 12: LSQ_SKINNY_LN(12); break;
+    case 8: LSQ_SKINNY_LN(8); break;
+    case 6: LSQ_SKINNY_LN(6); break;
+    case 4: LSQ_SKINNY_LN(4); break;
+    default: LSQ_SKINNY_LN(2); break;
+  }
+#undef LSQ_SKINNY_LN
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int BK>
 constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * (BK + 8) * sizeof(half_t); }
 

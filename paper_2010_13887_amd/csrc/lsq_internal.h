@@ -47,6 +47,23 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
                        int M, int N, int K, int act, hipStream_t s);
 
 int gemm_partial_splits(int dtype, int M, int N, int K);
+
+// A product that makes its own input: A = LayerNorm(x_old + sum of `splits` fp32 slabs P[s][M][K] + bias) * g + b,
+// rounded to float16; the rows are also written to x_new (not the same buffer as x_old).  For the few-row end
+// of a batch only: see gemm_ln_supported.
+struct LnInput {
+  const float* P;
+  int splits;
+  const half_t* bias;
+  const half_t* g;
+  const half_t* b;
+  const half_t* x_old;
+  half_t* x_new;
+  float eps;
+};
+bool gemm_ln_supported(int dtype, int M, int K);
+hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, const GemmOut& out, int M, int N,
+                          int K, int act, hipStream_t s);
 hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* P, int M, int N, int K,
                                 int splits, hipStream_t s);
 
@@ -148,5 +165,59 @@ template <> struct Vec8<float> {
     *reinterpret_cast<floatx4*>(p + 4) = b;
   }
 };
+
+// LayerNorm of one row held by one wavefront: lane l owns elements (j*64 + l)*8 .. +7 of the row for
+// j < NV (those at or beyond d are absent).  v comes in as the row, leaves centred; o = g * (v * rstd) + b.
+// Shared by the stand-alone kernel and the product kernel that normalises its own input, so that
+// both round identically.
+template <int NV>
+__device__ __forceinline__ void layernorm_row(float (&v)[NV][8], const float (&gv)[NV][8], const float (&bv)[NV][8],
+                                              int d, float eps, int lane, float (&o)[NV][8]) {
+  // every operation is spelled out (no contraction left to the compiler), so the two kernels that
+  // inline this give the same bits
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if ((j * 64 + lane) * 8 < d) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum = __fadd_rn(sum, v[j][i]);
+    }
+  const float mean = __fdiv_rn(wave_sum(sum), (float)d);
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if ((j * 64 + lane) * 8 < d) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] = __fsub_rn(v[j][i], mean); sq = __fmaf_rn(v[j][i], v[j][i], sq); }
+    }
+  const float var = __fdiv_rn(wave_sum(sq), (float)d);
+  const float rstd = __fdiv_rn(1.0f, __fsqrt_rn(__fadd_rn(var, eps)));
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      o[j][i] = __fmaf_rn(gv[j][i], __fmul_rn(v[j][i], rstd), bv[j][i]);
+      // keep the float32 result as it is: without this the compiler may merge the multiply-add with
+      // the caller's conversion to float16 into one mixed-precision instruction that rounds once
+      // instead of twice, in one kernel and not in the other
+      asm volatile("" : "+v"(o[j][i]));
+    }
+}
+
+// v <- v + ((p[0] + p[1] + ... + p[S-1]) + t), slabs added in index order, nothing contracted
+template <int SMAX>
+__device__ __forceinline__ void add_partials(float (&v)[8], const float (&part)[SMAX][8], int S, const float (&t)[8]) {
+  float a[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = part[0][i];
+#pragma unroll
+  for (int sp = 1; sp < SMAX; ++sp)
+    if (sp < S) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = __fadd_rn(a[i], part[sp][i]);
+    }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = __fadd_rn(v[i], __fadd_rn(a[i], t[i]));
+}
 
 }  // namespace lsq

@@ -168,7 +168,7 @@ struct Plan {
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
-  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits, d_y, e_y;
+  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits, d_y, e_y, d_x2;
 };
 
 Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
@@ -213,6 +213,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
   p.d_tmp = dtake(kMaxSplits * M * d * 4);   // fp32 partial-sum slabs of the split-K GEMMs
   p.d_y = dtake(M * d * esz);
+  p.d_x2 = dtake(M * d * esz);   // second hidden-state buffer for products that normalise their own input
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
@@ -243,6 +244,8 @@ struct Ctx {
   bool use_graphs = true;
   int refresh_mode = 1;   // how the next lsq_encode keeps the cache in step with the beams: 0 move rows, 1 slab table
   bool anc_on = false;    // this translation uses the slab table
+  bool fuse_ln = true;    // few rows alive: LayerNorm inside the product that consumes it
+  bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
   std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
@@ -320,6 +323,33 @@ int launch_step(int B) {
   const size_t slab = (size_t)M_max * T * d * es;   // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
   TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
+  // With very few rows alive a sublayer's "add the partial sums, the bias and the residual, then
+  // LayerNorm" is not a kernel of its own: the product that consumes the normalised rows does it
+  // on its way in, reading the residual from one hidden-state buffer and leaving the new rows in
+  // the other.  `pending` carries what that product needs.
+  const bool fuse = g.fuse_ln && gemm_ln_supported(dt, M, d);
+  char* x_alt = g.ws + p.d_x2;
+  struct { bool on; int S; const void* bias; const void* gain; const void* shift; } pending = {false, 0, nullptr, nullptr, nullptr};
+  auto close_sublayer = [&](int cls, const void* in, const void* W, const void* bias, const void* gain, const void* shift,
+                            int K) -> int {
+    if (!fuse) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, (float*)tmp, M, d, K, kMaxSplits, s);
+    const int S = std::min(gemm_partial_splits(dt, M, d, K), (int)kMaxSplits);
+    TIMED(cls, launch_gemm_partials(dt, in, W, (float*)tmp, M, d, K, S, s));
+    pending = {true, S, bias, gain, shift};
+    return LSQ_OK;
+  };
+  auto product = [&](int cls, const void* W, const void* bias, const GemmOut& o, int N, int act) -> int {
+    if (!pending.on) {
+      TIMED(cls, launch_gemm(dt, x, W, bias, o, M, N, d, act, s));
+      return LSQ_OK;
+    }
+    LnInput ln = {(const float*)tmp, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
+                  (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
+    TIMED(cls, launch_gemm_ln(ln, W, bias, o, M, N, d, act, s));
+    std::swap(x, x_alt);
+    pending.on = false;
+    return LSQ_OK;
+  };
   for (int l = 0; l < hp.n_dec; ++l) {
     const DecLayer& L = g.dec[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
@@ -329,19 +359,19 @@ int launch_step(int B) {
     o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
     o.tpos = step;
     o.tmul[1] = d; o.tmul[2] = d;
-    TIMED(PC_GEMM_QKV, launch_gemm(dt, x, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
+    if (int rc = product(PC_GEMM_QKV, L.Wqkv, L.bqkv, o, 3 * d, 0)) return rc;
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, anc, k, T + 1, s));
-    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, x, nullptr, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
-    TIMED(PC_GEMM_DD, launch_gemm(dt, x, L.Wq, L.bq, plain_out(q, d), M, d, d, 0, s));
+    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d)) return rc;
+    if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                   at<int32_t>(p.src_len), ctx, B, k, H, d, g.max_len, s));
-    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, x, nullptr, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
-    TIMED(PC_GEMM_FFN1, launch_gemm(dt, x, L.W1, L.b1, plain_out(ffn, F), M, F, d, 1, s));
-    if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, x, nullptr, (float*)tmp, M, d, F, kMaxSplits, s)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d)) return rc;
+    if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F)) return rc;
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
-  TIMED(PC_GEMM_VOCAB, launch_gemm(dt, x, g.E, nullptr, lo, M, V, d, 0, s));
+  if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
   // refine advances the device-side step counter when its last workgroup finishes, so the
@@ -404,6 +434,8 @@ int launch_step_gpt(int B) {
 int enqueue_step() {
   const int B = g.alive_at[g.t];
   auto launch = [&](int n) { return g.hp.arch == 1 ? launch_step_gpt(n) : launch_step(n); };
+  g.hidden_in_alt = g.hp.arch == 0 && g.fuse_ln && gemm_ln_supported(g.hp.dtype, B * g.beam, g.hp.d) &&
+                    ((3 * g.hp.n_dec) & 1) != 0;
   if (!g.use_graphs || g.stream == nullptr || g_prof.on) {
     int rc = launch(B);
     if (rc) return rc;
@@ -798,6 +830,16 @@ int lsq_set_graphs(int on) {
   return LSQ_OK;
 }
 
+int lsq_set_layernorm_fusion(int on) {
+  if ((on != 0) != g.fuse_ln) {   // captured steps hold the other variant's launches
+    if (g.stream) (void)hipStreamSynchronize(g.stream);
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+  }
+  g.fuse_ln = on != 0;
+  return LSQ_OK;
+}
+
 int lsq_set_cache_refresh(int mode) {
   if (mode != LSQ_REFRESH_MOVE && mode != LSQ_REFRESH_TABLE) return fail(LSQ_E_ARG, "unknown cache refresh mode %d", mode);
   g.refresh_mode = mode;
@@ -855,7 +897,7 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     case LSQ_DBG_PARENT: src = g.ws + p.parent; n = M; break;
     case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
     case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
-    case LSQ_DBG_HIDDEN: src = g.ws + p.d_x; n = M * d; is_float_data = true; break;
+    case LSQ_DBG_HIDDEN: src = g.ws + (g.hidden_in_alt ? p.d_x2 : p.d_x); n = M * d; is_float_data = true; break;
     case LSQ_DBG_MEMORY:
       if (g.t != 0) return fail(LSQ_E_STATE, "encoder output is overwritten by the first decode step");
       src = g.ws + p.e_x; n = R * d; is_float_data = true; per_source_row = true; break;
@@ -950,6 +992,21 @@ int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const voi
                                       (hipStream_t)stream);
   if (e != hipSuccess) return fail(LSQ_E_HIP, "%s", hipGetErrorString(e));
   return LSQ_OK;
+}
+
+int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_bias, const void* gamma, const void* beta,
+                         const void* x_old, void* x_new, float eps, const void* W, const void* bias, void* C, int M,
+                         int N, int K, int flags, void* stream) {
+  KCHK(P && ln_bias && gamma && beta && x_old && x_new && W && C, "null pointer");
+  KCHK(x_old != x_new, "x_new must not be x_old");
+  KCHK(gemm_ln_supported(dtype, M, K), "float16, 1..8 rows, K a multiple of 16 up to 1024");
+  KCHK(splits >= 1 && splits <= 4 && N >= 0, "shape");
+  GemmOut o = plain_out(C, N);
+  o.f32_out = (flags & LSQ_GEMM_F32_OUT) ? 1 : 0;
+  LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
+                (half_t*)x_new, eps};
+  KRUN(launch_gemm_ln(ln, W, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) ? 1 : ((flags & LSQ_GEMM_GELU) ? 2 : 0),
+                      (hipStream_t)stream));
 }
 
 int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out, int rows, int heads,

@@ -146,3 +146,29 @@ def test_cache_refresh_modes_agree_and_cache_matches_oracle(lsq):
     assert results[0][3] or results[1][3]                    # beams really changed parents
     for a, b in zip(results[0][:3], results[1][:3]):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("n_dec", [1, 2])
+def test_layernorm_fusion_is_bit_identical(lsq, n_dec):
+    """At most 8 rows alive: LayerNorm inside the consuming product (default) against the stand-alone
+    LayerNorm kernel; lock-step with the oracle runs on the fused path."""
+    hp = S.HParams(n_enc=1, n_dec=n_dec, d_model=128, n_heads=2, d_ffn=256, vocab=504, max_pos=64, dtype=1, cap_extra=9)
+    w = S.custom(hp, [3, 17], beam=4, max_len=29, std=0.05)           # 8 rows from the first step on
+    w3 = S.custom(hp, [3, 17, 1, 9, 20], beam=4, max_len=29, std=0.05)  # 20 rows, then 8 and 4 near the end
+    blob = w.blob(ln_jitter=0.1)
+    out = {}
+    try:
+        for on in (False, True):
+            lsq.lsq_set_layernorm_fusion(on)
+            with lsq.Engine(blob, 5, 4, 29) as eng:
+                out[on] = eng.translate(w.src_ids, w.src_lens, sync_every=2) + eng.translate(w3.src_ids, w3.src_lens, sync_every=3)
+                if on:
+                    res = lockstep(lsq, eng, blob, w)
+                    assert res["steps"] >= 10
+                    _final_check(lsq, eng, blob, w, res)
+                    hidden = eng.debug(lsq.DBG.HIDDEN, (w.batch * w.beam, hp.d_model))
+                    assert np.isfinite(hidden).all() and np.abs(hidden).max() > 0.1
+    finally:
+        lsq.lsq_set_layernorm_fusion(True)
+    for a, b in zip(out[False], out[True]):
+        assert np.array_equal(a, b)

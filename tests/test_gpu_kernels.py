@@ -107,6 +107,36 @@ def test_gemm_add_layernorm(env, rows, d, K, half):
         np.testing.assert_allclose(got, ref, rtol=3e-5, atol=3e-5)
 
 
+@pytest.mark.parametrize("rows,d,N,splits", [(1, 64, 96, 1), (4, 1024, 3072, 4), (8, 1024, 1000, 4), (5, 512, 2048, 2),
+                                             (7, 768, 50, 3), (8, 1024, 32000, 4), (3, 48, 40, 1)])
+@pytest.mark.parametrize("f32_out", [False, True])
+def test_layernorm_inside_product(env, rows, d, N, splits, f32_out):
+    """Product that normalises its own input: x_new is bit-identical to the stand-alone LayerNorm
+    kernel's rows, and C equals the plain product of those rows."""
+    lsq, torch = env
+    rng = np.random.default_rng(rows + d + N)
+    x = _h(rng.standard_normal((rows, d)) * 2)
+    P = (rng.standard_normal((splits, rows, d)) * 0.5).astype(np.float32)
+    lb, g, b = _h(rng.standard_normal(d) * 0.3), _h(1 + 0.3 * rng.standard_normal(d)), _h(0.3 * rng.standard_normal(d))
+    W, bias = _h(rng.standard_normal((N, d)) * 0.05), _h(rng.standard_normal(N))
+    h = torch.float16
+    dx, dP = _dev(torch, x, h), _dev(torch, P)
+    dlb, dg, db, dW, dbias = (_dev(torch, a, h) for a in (lb, g, b, W, bias))
+    x_new = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    C = torch.full((rows, N), 7.0, dtype=torch.float32 if f32_out else h, device="cuda")
+    lsq.k_layernorm_gemm(dP, dlb, dg, db, dx, x_new, 1e-5, dW, dbias, C, relu=True)
+    assert torch.equal(dx, _dev(torch, x, h))                       # the residual input is left alone
+    # the same rows from the oracle (float64), and the product of the rows the kernel actually made
+    a = P.astype(np.float64).sum(0) + lb
+    ref_rows = O.layer_norm(x.astype(np.float64) + a, g.astype(np.float64), b.astype(np.float64), 1e-5)
+    got_rows = x_new.float().cpu().numpy()
+    np.testing.assert_allclose(got_rows, ref_rows, rtol=1.1e-3, atol=1e-3)
+    assert np.abs(got_rows - _h(ref_rows)).max() <= 4e-3 and (got_rows != _h(ref_rows)).mean() < 0.02
+    C2 = torch.empty_like(C)
+    lsq.k_gemm(x_new, dW, dbias, C2, relu=True)
+    assert torch.equal(C, C2)                                        # same fragments, same order of accumulation
+
+
 @pytest.mark.parametrize("rows,H,dh,T,nkeys", [(3, 4, 16, 8, 1), (9, 4, 16, 8, 8), (32, 8, 64, 110, 77),
                                                (5, 2, 128, 40, 33), (7, 3, 32, 50, 50), (130, 16, 64, 178, 41),
                                                (300, 8, 64, 60, 60), (2, 2, 16, 200, 199)])
