@@ -82,8 +82,9 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
 
 /* One auto-regressive step for every hypothesis of every sentence: decoder
  * layers over the cached keys/values, vocabulary logits, log-softmax plus
- * hypothesis score, the k best (beam, token) pairs per sentence, K/V-cache
- * reorder by parent beam (sec. 2.2 and the "cache refreshing" of sec. 3.2).
+ * hypothesis score, the k best (beam, token) pairs per sentence, and the
+ * K/V cache made to follow the parent beams (sec. 2.2 and the "cache
+ * refreshing" of sec. 3.2; see lsq_set_cache_refresh).
  * Returns the number of sentences that still have an unfinished hypothesis
  * (0 = done); waits for the step to finish to read that count back.
  * A step after every sentence finished, or after max_len steps, changes

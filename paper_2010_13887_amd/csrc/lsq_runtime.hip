@@ -306,9 +306,9 @@ int sublayer(int cls, const void* in, const void* W, const void* bias, const voi
 
 // All launches of one decode step for the first B sentences (B*k rows).  Nothing here depends on
 // the step index: kernels read it from the device-side counter (step_state[0]), the cache and
-// cross-K/V strides are those of the maximum shapes, and the cache-reorder grid covers max_len
-// positions.  The same sequence therefore serves every step with B sentences alive, which is what
-// lets it be captured once into a hipGraph and replayed.
+// cross-K/V strides are those of the maximum shapes, and grids that depend on the number of cached
+// positions cover max_len of them.  The same sequence therefore serves every step with B sentences
+// alive, which is what lets it be captured once into a hipGraph and replayed.
 int launch_step(int B) {
   const HParams& hp = g.hp;
   const Plan& p = g.plan;
@@ -374,8 +374,9 @@ int launch_step(int B) {
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
-  // refine advances the device-side step counter when its last workgroup finishes, so the
-  // reorder that follows reads t + 1 = the number of cache positions to gather
+  // refine gathers the token histories (and the slab table, when the cache is refreshed through
+  // it) by parent and advances the device-side step counter when its last workgroup finishes, so a
+  // reorder kernel that follows reads t + 1 = the number of cache positions to move
   TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                             at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T, 0,

@@ -172,3 +172,24 @@ def test_layernorm_fusion_is_bit_identical(lsq, n_dec):
         lsq.lsq_set_layernorm_fusion(True)
     for a, b in zip(out[False], out[True]):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("beam,lens,vocab,cap_extra,max_len,dtype", [
+    (1, [1], 37, 3, 6, 0),            # one sentence of one token, greedy
+    (8, [4, 2, 7], 64, 2, 9, 0),      # the widest beam
+    (4, [5, 3], 5, 0, 5, 0),          # vocabulary barely above the beam; cap = source length, = max_len for one
+    (3, [2, 6, 6, 1], 301, 4, 7, 1),  # caps cut off by max_len, float16, beam that does not divide 64
+    (2, [9], 1000, 1, 12, 1),         # single sentence, float16: the few-row kernels from the first step on
+])
+def test_edge_shapes_match_oracle(lsq, beam, lens, vocab, cap_extra, max_len, dtype):
+    hp = S.HParams(n_enc=1, n_dec=2, d_model=64, n_heads=4, d_ffn=96, vocab=vocab, max_pos=16, dtype=dtype,
+                   cap_extra=cap_extra)
+    w = S.custom(hp, lens, beam=beam, max_len=max_len, std=0.08 if dtype else 0.3)
+    blob = w.blob(ln_jitter=0.1)
+    with lsq.Engine(blob, len(lens), beam, max_len) as eng:
+        res = lockstep(lsq, eng, blob, w)
+        assert res["steps"] == min(max(lens) + cap_extra, max_len)
+        _final_check(lsq, eng, blob, w, res)
+        ids, out_lens, scores = eng.get_beams()
+        assert ((out_lens >= 0) & (out_lens <= max_len)).all()
+        assert ((ids >= 0) & (ids < vocab)).all()
