@@ -157,6 +157,25 @@ def main() -> int:
     end_to_end = dict(tokens_per_s=float(best_len.sum()) / t_all, total_ms=t_all * 1e3, encode_ms=t_enc * 1e3,
                       steps=total_steps)
 
+    # the curve over t: the same translation in chunks of 8 steps with a wait after each chunk
+    # (the waits make these figures slightly higher than the back-to-back ones above)
+    eng.encode(w.src_ids, w.src_lens)
+    torch.cuda.synchronize()
+    curve, t_at = [], 0
+    while True:
+        t0 = time.perf_counter()
+        a = eng.decode_steps(8)
+        n_done = lsq.lsq_step_index() - t_at
+        dt8 = time.perf_counter() - t0
+        if n_done > 0:
+            curve.append(dict(t=t_at, ms_per_step=dt8 / n_done * 1e3))
+        t_at += n_done
+        if a == 0 or n_done == 0:
+            break
+    per_step = sorted(c["ms_per_step"] for c in curve)
+    step_curve = dict(p50_ms=per_step[len(per_step) // 2], min_ms=per_step[0], max_ms=per_step[-1],
+                      chunks=[[c["t"], round(c["ms_per_step"], 4)] for c in curve])
+
     # instrumented pass: per-kernel-class durations over the same K steps
     dt_prof, prof = run(True)
     # Work per class summed over the timed steps.  Step t works on the sentences whose cap
@@ -261,7 +280,7 @@ def main() -> int:
                higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f16" if hp.dtype == 1 else "f32", data="synthetic",
                config=dict(workload=desc, global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
-               roofline=roof, cpu_baseline=cpu, end_to_end=end_to_end, **extra)
+               roofline=roof, cpu_baseline=cpu, end_to_end=end_to_end, step_curve=step_curve, **extra)
     print(json.dumps(out))
     return 0
 
