@@ -98,6 +98,19 @@ def main() -> int:
         cases.append((name, "hbm", 4.0 * k * int(lens.sum()) * d, by,
                       lambda: lsq.k_cross_attention(q, kv, off, ln, out, B, k, H, int(lens.max()))))
 
+    def enc_attn_case(name, H, d, lens):
+        lens = np.asarray(lens, np.int32)
+        R = int(lens.sum())
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        qkv = rnd(R, 3 * d)
+        out = torch.empty(R, d, device=dev, dtype=h)
+        row_seq = torch.from_numpy(np.repeat(np.arange(len(lens)), lens).astype(np.int32)).to(dev)
+        doff, dlen = torch.from_numpy(off[:-1].copy()).to(dev), torch.from_numpy(lens).to(dev)
+        pairs = float((lens.astype(np.int64) ** 2).sum())            # (query, key) pairs
+        by = (3 * R * d + R * d) * 2                                  # every Q, K, V row once, context out
+        cases.append((name + f" ({R} rows)", "hbm", 4.0 * pairs * d, by,
+                      lambda: lsq.k_encoder_attention(qkv, row_seq, doff, dlen, out, H)))
+
     def topk_case(name, M, V, k):
         logits = rnd(M, V, dtype=torch.float32, scale=0.64)
         score = -torch.rand(M, device=dev, generator=g) * 40
@@ -131,6 +144,11 @@ def main() -> int:
     rs = np.random.default_rng(4321)
     cross_attn_case("attn_cross B128 k4 meanlen29", 128, 4, H, d, np.clip(np.rint(rs.lognormal(3.15, 0.6, 128)), 1, 128))
     topk_case("row_topk M512 V32000 k4", M, V, 4)
+    enc_lens = np.clip(np.rint(np.random.default_rng(4321).lognormal(3.15, 0.6, 128)), 1, 128)
+    enc_attn_case("enc_attn B128 meanlen29", H, d, enc_lens)
+    gemm_case("enc gemm_qkv M3660 N3072 K1024", 3660, 3 * d, d)
+    gemm_case("enc gemm_ffn1 M3660 N4096 K1024", 3660, F, d, relu=True)
+    sublayer_case("enc sublayer_ffn2 M3660 d1024 K4096", 3660, d, F)
     reorder_case("cache_reorder L12 B128 k4 t41 (3 of 4 rows move)", 2 * L, 128, 4, T, d, 41)
     if not args.no_stress:
         gemm_case("stress gemm M4096 N4096 K4096", 4096, 4096, 4096)

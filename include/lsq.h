@@ -218,6 +218,15 @@ int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_
                           const int32_t* src_len, void* out, int batch, int beam, int heads, int d,
                           int max_src_len, void* stream);
 
+/* Self-attention inside packed sequences (encoder layers; with causal != 0 the
+ * prompt prefill of a decoder-only model): qkv [rows, 3d] = [Q | K | V], row i
+ * belongs to sequence row_seq[i], whose rows are seq_off[b] .. seq_off[b] +
+ * seq_len[b] - 1 (all int32, device).  Row i attends every row of its sequence,
+ * or with causal only those up to itself.  out [rows, d]. */
+int lsq_k_encoder_attention(int dtype, const void* qkv, const int32_t* row_seq, const int32_t* seq_off,
+                            const int32_t* seq_len, void* out, int rows, int heads, int d, int causal,
+                            void* stream);
+
 /* Retrieve stage of the hierarchical search (sec. 2.2) made exact: per row r of
  * logits [M,V], cand = score[r] + log_softmax(logits[r,:]) and the k best
  * (cand descending, token ascending) are written to out_score/out_idx [M,k].

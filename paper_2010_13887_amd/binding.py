@@ -54,6 +54,7 @@ def load_library() -> C.CDLL:
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "lsq_k_encoder_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_self_attention_table": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
         "lsq_k_cross_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_row_topk": [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
@@ -247,6 +248,13 @@ def k_self_attention_table(q, Kc, Vc, slab, out, beam: int, heads: int, nkeys: i
     assert tuple(slab.shape) == (rows, T + 1)
     _check(load_library().lsq_k_self_attention_table(_dt(q), _p(q), _p(Kc), _p(Vc), _p(slab), _p(out), rows, beam,
                                                      heads, d, T, nkeys, _stream()))
+
+
+def k_encoder_attention(qkv, row_seq, seq_off, seq_len, out, heads: int, causal: bool = False) -> None:
+    """Self-attention inside packed sequences; qkv [rows, 3d] = [Q | K | V]."""
+    rows, d3 = qkv.shape
+    _check(load_library().lsq_k_encoder_attention(_dt(qkv), _p(qkv), _p(row_seq), _p(seq_off), _p(seq_len), _p(out),
+                                                  rows, heads, d3 // 3, int(causal), _stream()))
 
 
 def k_cross_attention(q, kv, src_off, src_len, out, batch: int, beam: int, heads: int, max_src_len: int) -> None:

@@ -1019,6 +1019,15 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
   KRUN(launch_self_attention(dtype, q, Kc, Vc, out, rows, heads, d, T, nkeys, nullptr, nullptr, 1, 0, (hipStream_t)stream));
 }
 
+int lsq_k_encoder_attention(int dtype, const void* qkv, const int32_t* row_seq, const int32_t* seq_off,
+                            const int32_t* seq_len, void* out, int rows, int heads, int d, int causal, void* stream) {
+  KCHK(qkv && row_seq && seq_off && seq_len && out, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(rows >= 0 && heads >= 1 && d % heads == 0 && head_dim_supported(d / heads), "head size must be 16/32/64/128");
+  KRUN(launch_encoder_attention(dtype, qkv, row_seq, seq_off, seq_len, out, rows, heads, d, causal ? 1 : 0,
+                                (hipStream_t)stream));
+}
+
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off, const int32_t* src_len,
                           void* out, int batch, int beam, int heads, int d, int max_src_len, void* stream) {
   KCHK(q && kv && src_off && src_len && out, "null pointer");

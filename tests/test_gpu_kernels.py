@@ -181,6 +181,32 @@ def test_self_attention_through_slab_table(env, B, k, H, dh, T, nkeys, half):
     np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
 
 
+@pytest.mark.parametrize("lens,H,dh", [([5, 8], 4, 16), ([1, 60, 17, 33], 8, 64), ([128, 3], 16, 64), ([9], 2, 128),
+                                       ([40] * 7, 3, 32)])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("half", [False, True])
+def test_encoder_attention(env, lens, H, dh, causal, half):
+    """Packed sequences: every row attends its own sequence (all of it, or up to itself)."""
+    lsq, torch = env
+    rng = np.random.default_rng(sum(lens) + H)
+    d, R = H * dh, sum(lens)
+    cast = _h if half else (lambda a: np.asarray(a, np.float32))
+    qkv = cast(rng.standard_normal((R, 3 * d)))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    row_seq = np.repeat(np.arange(len(lens)), lens).astype(np.int32)
+    td = torch.float16 if half else torch.float32
+    out = torch.full((R, d), 7.0, dtype=td, device="cuda")
+    lsq.k_encoder_attention(_dev(torch, qkv, td), _dev(torch, row_seq), _dev(torch, off[:-1].copy()),
+                            _dev(torch, np.array(lens, np.int32)), out, H, causal)
+    ref = np.empty((R, d))
+    for b, n in enumerate(lens):
+        blk = qkv[off[b]:off[b] + n].astype(np.float64)
+        mask = np.tril(np.ones((n, n), bool)) if causal else None
+        ref[off[b]:off[b] + n] = O.attention(blk[:, :d], blk[:, d:2 * d], blk[:, 2 * d:], H, mask)
+    tol = 1.5e-3 if half else 2e-5
+    np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
+
+
 @pytest.mark.parametrize("lens,beam,H,dh", [([5, 8], 4, 4, 16), ([1, 60, 17, 33], 4, 8, 64), ([9, 2, 31], 3, 2, 32),
                                             ([4, 4, 128, 7, 1], 8, 16, 64), ([3], 1, 2, 128), ([6, 11], 5, 4, 16)])
 @pytest.mark.parametrize("half", [False, True])
