@@ -183,17 +183,29 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // this lane's bias values, fetched now so their latency hides behind the first tile loads
+  // this lane's bias values: requested behind the first tiles (whose arrival the loop waits for
+  // first), four consecutive columns per 8-byte load where the row allows it
   float bv[TN][4][4];
+  auto load_bias = [&]() {
+    const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 7) == 0;
 #pragma unroll
-  for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int vg = 0; vg < 4; ++vg)
+      for (int vg = 0; vg < 4; ++vg) {
+        const int n4 = n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4;
+        if (SPLIT || !bias) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int n = min(n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4 + e, N - 1);
-        bv[j][vg][e] = (!SPLIT && bias) ? (float)bias[n] : 0.f;
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = 0.f;
+        } else if (bias_vec && n4 + 3 < N) {
+          const half4_t b4 = *reinterpret_cast<const half4_t*>(bias + n4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = (float)b4[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = (float)bias[min(n4 + e, N - 1)];
+        }
       }
+  };
 
   // Split-K: gridDim.y workgroups share an output tile; each multiplies an equal share of the
   // k-tiles and writes its fp32 partial sums (no bias) to its own [M,N] slab; the consumer adds
@@ -259,6 +271,7 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
   // this iteration's reads before the writes of the iteration after.
 #pragma unroll
   for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
+  load_bias();
   sstore(ra[0], rb[0], 0, 0);
   gload(ra[0], rb[0], min(D, nk - 1) * BK);
   __syncthreads();
