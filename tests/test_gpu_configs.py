@@ -54,3 +54,19 @@ def test_config_matches_oracle_then_finishes(lsq, name, steps):
         # the same translation again, chunked differently: bit-identical
         ids2, lens2, scores2 = eng.translate(w.src_ids, w.src_lens, sync_every=7)
         assert np.array_equal(ids, ids2) and np.array_equal(lens, lens2) and np.array_equal(scores, scores2)
+
+
+def test_big_shape_few_sentences_whole_translation(lsq):
+    """Transformer-big weights, three sentences, every step to the end in lock-step with the oracle:
+    the few-row regime at the real layer sizes (skinny products, LayerNorm inside the consuming
+    product once one or two sentences are left, split self-attention, long slab-table histories)."""
+    big = S.workload("big")
+    w = S.custom(big.hp, [12, 30, 5], beam=4, max_len=30 + big.hp.cap_extra)
+    blob = w.blob()
+    with lsq.Engine(blob, w.batch, w.beam, w.max_len) as eng:
+        res = lockstep(lsq, eng, blob, w, check_wide=False, verbose=True)
+        assert res["steps"] == 30 + big.hp.cap_extra
+        assert res["strict"] >= 0.5 * (12 + 30 + 5 + 3 * big.hp.cap_extra), res
+        assert res["worst_tight"] <= 1e-2
+        ids, lens, scores = eng.get_beams()
+        _properties(w, ids, lens, scores, w.hp)
