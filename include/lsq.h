@@ -28,7 +28,10 @@
  * P-1 tokens, and each lsq_decode_step samples one token per row from a Philox
  * stream keyed by the blob's seed (counter = step, row) until cap_extra tokens
  * have been produced; lsq_get_beams returns those tokens and the sum of their
- * log-probabilities under the k-way softmax.
+ * log-probabilities.  The draw is from the k <= LSQ_MAX_SAMPLE_TOPK largest
+ * logits under their k-way softmax, cut -- when the blob sets a nucleus mass
+ * p < 1 -- to the shortest ranked prefix whose probability reaches p (top-k
+ * and top-p sampling, sec. 3.4).
  */
 #ifndef LSQ_H
 #define LSQ_H
@@ -50,6 +53,7 @@ typedef enum {
 } lsq_status;
 
 #define LSQ_MAX_BEAM 8
+#define LSQ_MAX_SAMPLE_TOPK 32 /* widest per-row retrieve: candidates a sampling model draws from */
 
 /* Bytes of device workspace that lsq_init will need for this model blob and
  * these maxima (sec. 2.3: every dynamic shape is bounded when the service
@@ -229,7 +233,8 @@ int lsq_k_encoder_attention(int dtype, const void* qkv, const int32_t* row_seq, 
 
 /* Retrieve stage of the hierarchical search (sec. 2.2) made exact: per row r of
  * logits [M,V], cand = score[r] + log_softmax(logits[r,:]) and the k best
- * (cand descending, token ascending) are written to out_score/out_idx [M,k].
+ * (cand descending, token ascending) are written to out_score/out_idx [M,k],
+ * 1 <= k <= LSQ_MAX_SAMPLE_TOPK.
  * A finished row yields the single candidate (score[r], eos) and k-1 empty
  * slots (idx -1).  score float32, finished int32. */
 int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int32_t* finished,

@@ -22,7 +22,7 @@ Header fields (byte offset: type name)::
      48: i32 norm (0 post-LN, 1 pre-LN)
      52: i32 dtype              56: i32 pad_id   60: i32 bos_id   64: i32 eos_id
      68: i32 cap_extra          72: i32 sample_topk
-     76: f32 length_penalty     80: f32 ln_eps   84: u32 reserved
+     76: f32 length_penalty     80: f32 ln_eps   84: f32 sample_topp (0 = off)
      88: u64 seed               96: u64 total_bytes
     104..255: zero
 
@@ -79,6 +79,7 @@ class HParams:
     eos_id: int = 2
     cap_extra: int = 50
     sample_topk: int = 0
+    sample_topp: float = 1.0   # nucleus mass kept inside the top-k candidates; 1.0 = off
     length_penalty: float = 1.0
     ln_eps: float = 1e-5
     seed: int = WEIGHT_SEED
@@ -118,9 +119,9 @@ def tensor_list(hp: HParams):
 
 def _pack_header(hp: HParams, total: int) -> bytes:
     h = MAGIC + struct.pack(
-        "<17i2fIQQ", 1, hp.arch, hp.n_enc, hp.n_dec, hp.d_model, hp.n_heads, hp.d_ffn, hp.vocab,
+        "<17i3fQQ", 1, hp.arch, hp.n_enc, hp.n_dec, hp.d_model, hp.n_heads, hp.d_ffn, hp.vocab,
         hp.max_pos, hp.act, hp.norm, hp.dtype, hp.pad_id, hp.bos_id, hp.eos_id, hp.cap_extra,
-        hp.sample_topk, hp.length_penalty, hp.ln_eps, 0, hp.seed, total)
+        hp.sample_topk, hp.length_penalty, hp.ln_eps, hp.sample_topp if hp.sample_topp < 1.0 else 0.0, hp.seed, total)
     return h + b"\0" * (HEADER_BYTES - len(h))
 
 

@@ -72,7 +72,8 @@ class Model:
         (ver, self.arch, self.n_enc, self.n_dec, self.d, self.H, self.F, self.V, self.max_pos,
          self.act, self.norm, self.dtype, self.pad, self.bos, self.eos, self.cap_extra,
          self.sample_topk) = struct.unpack_from("<17i", blob, 8)
-        self.alpha, self.eps = struct.unpack_from("<2f", blob, 76)
+        self.alpha, self.eps, topp = struct.unpack_from("<3f", blob, 76)
+        self.sample_topp = float(topp) if 0.0 < topp < 1.0 else 1.0      # 0 in the header: no nucleus cut
         self.seed, total = struct.unpack_from("<2Q", blob, 88)
         if ver != 1 or total != len(blob) or (self.arch, self.norm, self.act) not in ((0, 0, 0), (1, 1, 1)):
             raise ValueError("unsupported blob")
@@ -459,28 +460,40 @@ def sample_uniform(seed, step, row):
     return np.float32((word >> 8) * 2.0 ** -24)
 
 
-def sample_topk(logits, k, u):
-    """One draw: returns (token, log-probability under the k-way softmax, gap).  gap says how far the
-    decision is from changing: the smallest of the logit gap between the k-th and (k+1)-th token (the
-    candidate set), the logit gaps between the chosen candidate and its neighbours in the ranking (a
-    swap of two ranks exchanges their probability segments) and the distance of the draw from the
-    nearest cumulative-probability boundary."""
+def sample_topk(logits, k, u, p=1.0):
+    """One draw (sampling decoding, sec. 3.4): the k largest logits, ranked (logit descending, token
+    ascending), get the k-way softmax; with p < 1 only the shortest prefix of that ranking whose
+    probability mass reaches p stays (nucleus inside the top k); the token is the first of the
+    survivors whose cumulative weight exceeds u times the survivors' total.
+    Returns (token, log-probability among the survivors, gap).  gap says how far the decision is
+    from changing: the smallest of the logit gap between the k-th and (k+1)-th token (the candidate
+    set), the logit gaps between the chosen candidate and its neighbours in the ranking (a swap of
+    two ranks exchanges their probability segments), the distance of the draw from the nearest
+    cumulative-probability boundary, and the distance of the nucleus mass from p at its cut."""
     V = logits.shape[0]
     order = np.lexsort((np.arange(V), -logits))[:k + 1]
     top = order[:k]
     l = logits[top].astype(np.float32)
     e = np.exp(l - l[0])
     cum = np.cumsum(e, dtype=np.float32)
-    target = np.float32(u) * cum[-1]
-    j = int(np.searchsorted(cum, target, side="right"))
-    j = min(j, k - 1)
-    edge = float(np.min(np.abs(cum.astype(np.float64) - float(target))) / float(cum[-1]))
+    n = k
+    cut_gap = np.inf
+    if p < 1.0:
+        thresh = np.float32(p) * cum[-1]
+        n = min(int(np.searchsorted(cum, thresh, side="left")) + 1, k)     # first prefix with cum >= thresh
+        cut_gap = abs(float(cum[n - 1]) / float(cum[-1]) - p)
+        if n > 1:
+            cut_gap = min(cut_gap, abs(float(cum[n - 2]) / float(cum[-1]) - p))
+    target = np.float32(u) * cum[n - 1]
+    j = int(np.searchsorted(cum[:n], target, side="right"))
+    j = min(j, n - 1)
+    edge = float(np.min(np.abs(cum[:n].astype(np.float64) - float(target))) / float(cum[n - 1]))
     gap = float(logits[order[k - 1]] - logits[order[k]]) if len(order) > k else np.inf
     if j > 0:
         gap = min(gap, float(l[j - 1] - l[j]))
     if j < k - 1:
         gap = min(gap, float(l[j] - l[j + 1]))
-    return int(top[j]), float(np.log(e[j] / cum[-1])), min(gap, edge)
+    return int(top[j]), float(np.log(e[j] / cum[n - 1])), min(gap, edge, cut_gap)
 
 
 def gpt_forward_full(model, ids):
@@ -558,7 +571,8 @@ def generate(model, prompts, n_new, max_len, trace=None):
     gpt_prefill(model, st)
     for _ in range(n_new):
         logits = gpt_step_logits(model, st)
-        picks = [sample_topk(logits[r], model.sample_topk, sample_uniform(model.seed, st.t, r)) for r in range(st.B)]
+        picks = [sample_topk(logits[r], model.sample_topk, sample_uniform(model.seed, st.t, r), model.sample_topp)
+                 for r in range(st.B)]
         if trace is not None:
             trace.append(dict(logits=logits, picks=picks))
         gpt_advance(model, st, [p[0] for p in picks], [p[1] for p in picks])

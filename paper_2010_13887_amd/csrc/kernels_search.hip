@@ -73,7 +73,7 @@ row_topk_kernel(const T* __restrict__ logits,
   // One reduction for both softmax statistics: every thread owns (local max, local sum of
   // exp(x - local max)); pairs merge as (max, z1*exp(m1-max) + z2*exp(m2-max)).
   constexpr int NW = BLOCK / 64, CAP = 256;
-  __shared__ float red_m[NW], red_z[NW], wave_best[NW < LSQ_MAX_BEAM_ ? NW * LSQ_MAX_BEAM_ : NW];
+  __shared__ float red_m[NW], red_z[NW], wave_best[NW * LSQ_MAX_TOPK_];
   __shared__ float cand_s[CAP];
   __shared__ int cand_i[CAP];
   __shared__ int cand_n;
@@ -113,12 +113,12 @@ row_topk_kernel(const T* __restrict__ logits,
   // ---- rough stage (the paper's retrieve, sec. 2.2): split the row into k groups, take each
   // group's maximum, R = the smallest of them.  Each group maximum is the score of a distinct
   // token, so k tokens reach R and every token of the row's top k satisfies score >= R (ties at R
-  // included).  Groups here: the wavefronts taken modulo k (blocks of at least 8 wavefronts) or the
-  // lanes taken modulo k (small blocks).  The tokens at or above R -- a dozen or so on average --
+  // included).  Groups here: the wavefronts taken modulo k (blocks of at least k wavefronts) or the
+  // lanes taken modulo k (fewer wavefronts than k).  The tokens at or above R -- a dozen or so on average --
   // go to a short list in LDS which is then ranked exactly.  Rows where the list
   // overflows (e.g. thousands of equal logits) take the exact k-round arg-max below instead.
   float R;
-  if (NW >= LSQ_MAX_BEAM_) {
+  if (NW >= k) {
     const float wb = wave_max(best);
     if (lane == 0) wave_best[wave] = wb;
     __syncthreads();
@@ -129,16 +129,16 @@ row_topk_kernel(const T* __restrict__ logits,
       R = fminf(R, gm);
     }
   } else {
-    // few wavefronts: groups are lanes modulo k within each wavefront, merged across wavefronts
+    // fewer wavefronts than groups: groups are lanes modulo k within each wavefront, merged across wavefronts
     R = INFINITY;
     for (int grp = 0; grp < k; ++grp) {
       const float gm = wave_max((lane % k) == grp ? best : -INFINITY);
-      if (lane == 0) wave_best[wave * LSQ_MAX_BEAM_ + grp] = gm;
+      if (lane == 0) wave_best[wave * LSQ_MAX_TOPK_ + grp] = gm;
     }
     __syncthreads();
     for (int grp = 0; grp < k; ++grp) {
       float gm = -INFINITY;
-      for (int w = 0; w < NW; ++w) gm = fmaxf(gm, wave_best[w * LSQ_MAX_BEAM_ + grp]);
+      for (int w = 0; w < NW; ++w) gm = fmaxf(gm, wave_best[w * LSQ_MAX_TOPK_ + grp]);
       R = fminf(R, gm);
     }
   }
@@ -233,6 +233,7 @@ static hipError_t row_topk_t(const T* logits, const float* score, const int32_t*
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin, int M,
                            int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s) {
   if (M <= 0) return hipSuccess;
+  if (k < 1 || k > LSQ_MAX_TOPK_) return hipErrorInvalidValue;
   if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
   return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
 }
@@ -484,9 +485,10 @@ hipError_t launch_finalize(const float* score, const int32_t* tokens, const int3
 
 // ---------------------------------------------------------------------------------------------
 // Top-k sampling (the paper's sampling decoding, sec. 3.4): one thread per row.  The row's k largest
-// logits arrive ranked (logit descending, token ascending); p = softmax over those k;
+// logits arrive ranked (logit descending, token ascending); p = softmax over those k, cut to the
+// shortest prefix whose mass reaches topp when topp < 1;
 // u = (philox4x32_10(key = seed, counter = (step, row, 0, 0))[0] >> 8) * 2^-24; the token is the
-// first j whose cumulative p exceeds u * sum(p).  Appends it to the history, adds log p to the
+// first j whose cumulative p exceeds u * (sum of the kept p).  Appends it to the history, adds log p to the
 // row's score, and the last thread to finish advances the position counter.
 __device__ __forceinline__ unsigned philox4x32_10_first(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
                                                         unsigned k0, unsigned k1) {
@@ -506,12 +508,12 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
                                                     const int32_t* __restrict__ cand_idx,
                                                     int32_t* __restrict__ tokens, int32_t* __restrict__ len,
                                                     float* __restrict__ logp, int32_t* __restrict__ active,
-                                                    int32_t* __restrict__ step_state, int rows, int k, int T1,
-                                                    unsigned seed_lo, unsigned seed_hi, int n_new) {
+                                                    int32_t* __restrict__ step_state, int rows, int k, float topp,
+                                                    int T1, unsigned seed_lo, unsigned seed_hi, int n_new) {
   const int r = blockIdx.x * 64 + threadIdx.x;
   const int pos = step_state[0], t = pos - step_state[2];   // position of the token just fed; step index
   if (r < rows) {
-    float e[LSQ_MAX_BEAM_], cum[LSQ_MAX_BEAM_];
+    float e[LSQ_MAX_TOPK_], cum[LSQ_MAX_TOPK_];
     const float l0 = cand_logit[(size_t)r * k];
     float run = 0.f;
     for (int j = 0; j < k; ++j) {
@@ -519,14 +521,22 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
       run += e[j];
       cum[j] = run;
     }
+    // nucleus inside the candidates: the shortest ranked prefix whose mass reaches topp of the total
+    int n = k;
+    if (topp < 1.0f) {
+      const float thresh = __fmul_rn(topp, run);
+      n = 1;
+      while (n < k && !(cum[n - 1] >= thresh)) ++n;
+    }
+    const float total = cum[n - 1];
     const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)r, 0u, 0u, seed_lo, seed_hi);
     const float u = (float)(word >> 8) * 5.9604644775390625e-08f;   // 2^-24
-    const float target = __fmul_rn(u, run);
+    const float target = __fmul_rn(u, total);
     int j = 0;
-    while (j < k - 1 && !(cum[j] > target)) ++j;
+    while (j < n - 1 && !(cum[j] > target)) ++j;
     tokens[(size_t)r * T1 + pos + 1] = cand_idx[(size_t)r * k + j];
     len[r] = pos + 1;
-    logp[r] += logf(e[j] / run);
+    logp[r] += logf(e[j] / total);
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -540,12 +550,13 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
 }
 
 hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
-                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, int T,
+                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, float topp, int T,
                          unsigned long long seed, int n_new, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
+  if (k < 1 || k > LSQ_MAX_TOPK_ || !(topp > 0.f)) return hipErrorInvalidValue;
   sample_kernel<<<(rows + 63) / 64, 64, 0, s>>>(cand_logit, cand_idx, tokens, len, logp, active, step_state, rows, k,
-                                                T + 1, (unsigned)(seed & 0xFFFFFFFFull), (unsigned)(seed >> 32), n_new);
+                                                topp, T + 1, (unsigned)(seed & 0xFFFFFFFFull), (unsigned)(seed >> 32),
+                                                n_new);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kWave = 64;
 constexpr int LSQ_MAX_BEAM_ = 8;   // k*k survivors of one sentence fit one wavefront
+constexpr int LSQ_MAX_TOPK_ = 32;  // per-row retrieve width (sampling draws from up to this many candidates)
 
 // Where a GEMM writes: output column n belongs to segment s = n / seg_n and goes to
 // ptr[s] + m * ld[s] + (n - s * seg_n).  One segment for an ordinary matrix; three for the
@@ -96,8 +97,9 @@ hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* r
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
                            int M, int V, int k, int eos, int raw, float* out_score, int32_t* out_idx,
                            hipStream_t s);
+// topp < 1: only the shortest prefix of the ranked candidates whose k-way softmax mass reaches topp is drawn from
 hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
-                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, int T,
+                         float* logp, int32_t* active, int32_t* step_state, int rows, int k, float topp, int T,
                          unsigned long long seed, int n_new, hipStream_t s);
 // step = t_base + (step_state ? step_state[0] : 0).  `active` points at the counter array indexed
 // by step.  With step_state != null the last workgroup to finish advances step_state[0]

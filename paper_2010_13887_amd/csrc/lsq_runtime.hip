@@ -15,6 +15,7 @@
 using namespace lsq;
 
 static_assert(LSQ_MAX_BEAM == LSQ_MAX_BEAM_, "public and internal beam limits differ");
+static_assert(LSQ_MAX_SAMPLE_TOPK == LSQ_MAX_TOPK_, "public and internal retrieve widths differ");
 
 namespace {
 
@@ -85,7 +86,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct HParams {
   int arch, n_enc, n_dec, d, H, F, V, max_pos, act, norm, dtype, pad, bos, eos, cap_extra, sample_topk;
-  float alpha, eps;
+  float alpha, eps, topp;
   uint64_t seed, total;
 };
 
@@ -102,6 +103,8 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
   hp->pad = f[12]; hp->bos = f[13]; hp->eos = f[14]; hp->cap_extra = f[15]; hp->sample_topk = f[16];
   memcpy(&hp->alpha, p + 76, 4);
   memcpy(&hp->eps, p + 80, 4);
+  memcpy(&hp->topp, p + 84, 4);
+  if (!(hp->topp > 0.f && hp->topp < 1.f)) hp->topp = 1.f;   // 0 in the header: no nucleus cut
   memcpy(&hp->seed, p + 88, 8);
   memcpy(&hp->total, p + 96, 8);
   const bool encdec = hp->arch == 0 && hp->norm == 0 && hp->act == 0;
@@ -109,9 +112,9 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
   if (!encdec && !deconly)
     return fail(LSQ_E_BLOB, "supported: post-LN ReLU encoder-decoder (arch 0) or pre-LN tanh-GELU decoder-only (arch 1)");
   if (hp->dtype != DT_F32 && hp->dtype != DT_F16) return fail(LSQ_E_BLOB, "unknown dtype %d", hp->dtype);
-  if (deconly && (hp->n_enc != 0 || hp->sample_topk < 1 || hp->sample_topk > LSQ_MAX_BEAM || hp->max_pos < 1 ||
+  if (deconly && (hp->n_enc != 0 || hp->sample_topk < 1 || hp->sample_topk > LSQ_MAX_SAMPLE_TOPK || hp->max_pos < 1 ||
                   hp->d > 4096))
-    return fail(LSQ_E_BLOB, "decoder-only blob: n_enc must be 0, sample_topk in [1, %d], max_pos >= 1, d <= 4096", LSQ_MAX_BEAM);
+    return fail(LSQ_E_BLOB, "decoder-only blob: n_enc must be 0, sample_topk in [1, %d], max_pos >= 1, d <= 4096", LSQ_MAX_SAMPLE_TOPK);
   if ((encdec && hp->n_enc < 1) || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
       hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0)
     return fail(LSQ_E_BLOB, "implausible model shape");
@@ -424,7 +427,7 @@ int launch_step_gpt(int B) {
   TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, ks, hp.eos, 1, at<float>(p.cand_score),
                                      at<int32_t>(p.cand_idx), s));
   TIMED(PC_REFINE, launch_sample(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<int32_t>(p.tokens),
-                                 at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, ks, T,
+                                 at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, ks, hp.topp, T,
                                  (unsigned long long)hp.seed, hp.cap_extra, s));
   return LSQ_OK;
 }
@@ -1041,7 +1044,7 @@ int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int3
                    int eos, float* out_score, int32_t* out_idx, void* stream) {
   KCHK(logits && score && finished && out_score && out_idx, "null pointer");
   KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
-  KCHK(M >= 0 && topk_supported(V) && k >= 1 && k <= LSQ_MAX_BEAM && eos >= 0 && eos < V, "shape");
+  KCHK(M >= 0 && topk_supported(V) && k >= 1 && k <= LSQ_MAX_SAMPLE_TOPK && eos >= 0 && eos < V, "shape");
   KRUN(launch_row_topk(dtype, logits, score, finished, M, V, k, eos, 0, out_score, out_idx, (hipStream_t)stream));
 }
 

@@ -175,7 +175,7 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
     logit deviation allows.  Elsewhere the library's token must be one of the oracle's k
     candidates, and the oracle continues from it.  Returns a summary dict."""
     m = O.Model(blob)
-    B, T, V, k = w.batch, w.max_len, m.V, m.sample_topk
+    B, T, V, k, topp = w.batch, w.max_len, m.V, m.sample_topk, m.sample_topp
     n_new = m.cap_extra if n_steps is None else n_steps
     eng.encode(w.src_ids, w.src_lens)
     P = int(w.src_lens[0])
@@ -201,9 +201,9 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
             # (logit descending, token ascending), and its token is the oracle's draw from them
             mine = np.lexsort((np.arange(V), -got[r]))[:k]
             assert np.array_equal(g_ci[r], mine) and np.array_equal(g_cl[r], got[r][mine]), f"step {step} row {r}: candidates"
-            tok_own, _, gap_own = O.sample_topk(got[r], k, u)
+            tok_own, _, gap_own = O.sample_topk(got[r], k, u, topp)
             assert g_tok[r] == tok_own or gap_own < 1e-5, f"step {step} row {r}: token {g_tok[r]}, expected {tok_own}"
-            tok, lp, gap = O.sample_topk(ref[r], k, u)
+            tok, lp, gap = O.sample_topk(ref[r], k, u, topp)
             dev = float(np.abs(got[r] - ref[r]).max())
             if gap > 4 * dev + 1e-5:
                 strict += 1
@@ -213,11 +213,15 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
                 order = np.lexsort((np.arange(V), -ref[r]))[:k + 1]
                 assert g_tok[r] in order, f"step {step} row {r}: sampled token is not among the oracle's candidates"
                 if g_tok[r] != tok:
+                    # the library's token under the oracle's logits: its weight over the mass of the
+                    # oracle's survivors (stretched to include it if it sits just past the oracle's cut)
                     top = order[:k]
                     l = ref[r][top].astype(np.float32)
                     pe = np.exp(l - l[0])
+                    cum = np.cumsum(pe, dtype=np.float32)
+                    n = k if topp >= 1.0 else min(int(np.searchsorted(cum, np.float32(topp) * cum[-1], side="left")) + 1, k)
                     j = int(np.nonzero(top == g_tok[r])[0][0]) if g_tok[r] in top else k - 1
-                    tok, lp = int(g_tok[r]), float(np.log(pe[j] / pe.sum()))
+                    tok, lp = int(g_tok[r]), float(np.log(pe[j] / cum[max(n, j + 1) - 1]))
             toks.append(tok)
             lps.append(lp)
         O.gpt_advance(m, st, toks, lps)

@@ -40,6 +40,25 @@ def test_small_gpt_matches_oracle(lsq, dtype):
         assert eng.decode_step() == 0                       # nothing left to generate
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("k,topp", [(32, 0.75), (16, 1.0), (32, 0.2), (3, 0.9)])
+def test_topk_topp_sampling_matches_oracle(lsq, dtype, k, topp):
+    """Wide candidate sets and a nucleus cut inside them (the paper's sampling runs use top-k 32, top-p 0.75)."""
+    hp = S.HParams(arch=1, n_enc=0, n_dec=2, d_model=128, n_heads=2, d_ffn=264, vocab=1003, max_pos=64, act=1, norm=1,
+                   dtype=dtype, sample_topk=k, sample_topp=topp, cap_extra=8, seed=40 + k)
+    w = S.custom(hp, [5] * 6, beam=1, max_len=5 + 8, std=0.3 if dtype == 0 else 0.08, seed=3)
+    blob = w.blob(ln_jitter=0.1)
+    with lsq.Engine(blob, 6, 1, w.max_len) as eng:
+        res = lockstep_gpt(lsq, eng, blob, w)
+        # float16 with 32 candidates: the 32nd and 33rd logits are rarely further apart than the fp16 band, so most
+        # draws are checked on the library's own logits (exactly) rather than against the oracle's
+        assert res["strict"] >= (0.1 if dtype else 0.8) * res["steps"] * w.batch, res
+        ids, lens, scores = eng.get_beams()
+        st = res["state"]
+        assert np.array_equal(ids[:, 0, :8], st.tokens[:, 5:13])
+        np.testing.assert_allclose(scores[:, 0], st.logp, rtol=2e-5, atol=5e-2 if dtype else 1e-3)
+
+
 def test_prompt_of_one_token_and_errors(lsq):
     hp = S.HParams(arch=1, n_enc=0, n_dec=2, d_model=64, n_heads=4, d_ffn=128, vocab=300, max_pos=32, act=1, norm=1,
                    sample_topk=8, cap_extra=4, seed=5)

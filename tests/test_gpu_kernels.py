@@ -245,7 +245,8 @@ def _oracle_row_topk(logits, score, finished, k, eos):
 
 
 @pytest.mark.parametrize("M,V,k", [(8, 1000, 4), (5, 12, 3), (33, 32000, 4), (6, 50257, 8), (4, 8192, 1),
-                                   (3, 8200, 5), (2, 65536, 4), (7, 2048, 4), (9, 5, 5)])
+                                   (3, 8200, 5), (2, 65536, 4), (7, 2048, 4), (9, 5, 5), (5, 1000, 32), (4, 32000, 16),
+                                   (3, 50257, 32), (6, 40, 32), (2, 20, 32), (3, 50257, 16)])
 @pytest.mark.parametrize("case", ["random", "ties", "all_equal", "dead_and_finished"])
 def test_row_topk(env, M, V, k, case):
     lsq, torch = env

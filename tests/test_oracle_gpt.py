@@ -91,3 +91,50 @@ def test_sampling_rule():
         counts[O.sample_topk(logits, k, O.sample_uniform(5, i, 3))[0]] += 1
     assert counts[[v for v in range(50) if v not in top]].sum() == 0
     assert np.abs(counts[top] / 4000 - p).max() < 0.03
+
+
+def test_nucleus_inside_topk():
+    """top-p on top of top-k: hand-made probabilities 0.5, 0.25, 0.125, 0.0625, ... among the k candidates."""
+    # logits = log2-spaced: softmax over the 5 kept ones is (16, 8, 4, 2, 1) / 31
+    logits = np.full(12, -50.0, np.float32)
+    kept = [7, 2, 9, 4, 11]
+    for r, v in enumerate(kept):
+        logits[v] = np.float32(np.log(2.0) * (4 - r))
+    w = np.array([16, 8, 4, 2, 1], np.float64) / 31
+    # p = 0.75: 16/31 = 0.516 < 0.75 <= 24/31 = 0.774 -> the first two survive, renormalised to 2/3 and 1/3
+    seen = {}
+    for u in np.linspace(0.0005, 0.9995, 400):
+        tok, lp, gap = O.sample_topk(logits, 5, np.float32(u), 0.75)
+        seen.setdefault(tok, []).append((u, lp))
+    assert set(seen) == {7, 2}
+    assert max(u for u, _ in seen[7]) < 2 / 3 < min(u for u, _ in seen[2])
+    assert abs(seen[7][0][1] - np.log(2 / 3)) < 1e-6 and abs(seen[2][0][1] - np.log(1 / 3)) < 1e-6
+    # p below the first probability: greedy; p = 1: plain top-k; p just above a prefix mass keeps one more
+    assert all(O.sample_topk(logits, 5, np.float32(u), 0.3)[0] == 7 for u in (0.0, 0.5, 0.999))
+    for u in (0.01, 0.6, 0.8, 0.93, 0.99):
+        assert O.sample_topk(logits, 5, np.float32(u), 1.0)[:2] == O.sample_topk(logits, 5, np.float32(u))[:2]
+    assert O.sample_topk(logits, 5, np.float32(0.999), float(w[:3].sum()) + 1e-4)[0] == 4     # four survive
+    assert O.sample_topk(logits, 5, np.float32(0.999), float(w[:3].sum()) - 1e-4)[0] == 9     # three survive
+    # the cut is reported as a near-decision when p sits on a prefix mass
+    assert O.sample_topk(logits, 5, np.float32(0.1), float(w[:2].sum()) + 1e-7)[2] < 1e-5
+    # k larger than 8 (the paper's sampling runs use 32): survivors and frequencies
+    rng = np.random.default_rng(4)
+    lg = (rng.standard_normal(500) * 2).astype(np.float32)
+    order = sorted(range(500), key=lambda v: (-lg[v], v))[:32]
+    pr = np.exp(lg[order].astype(np.float64)); pr /= pr.sum()
+    n = int(np.searchsorted(np.cumsum(pr), 0.9)) + 1
+    counts = np.zeros(500)
+    for i in range(6000):
+        counts[O.sample_topk(lg, 32, O.sample_uniform(9, i, 1), 0.9)[0]] += 1
+    assert counts[[v for v in range(500) if v not in order[:n]]].sum() == 0
+    assert np.abs(counts[order[:n]] / 6000 - pr[:n] / pr[:n].sum()).max() < 0.03
+
+
+def test_blob_header_carries_nucleus_mass():
+    import lsq_synth as S
+    hp = S.HParams(arch=1, n_enc=0, n_dec=1, d_model=16, n_heads=1, d_ffn=16, vocab=20, max_pos=8, act=1, norm=1,
+                   sample_topk=32, sample_topp=0.75)
+    m = O.Model(S.make_blob(hp))
+    assert m.sample_topk == 32 and abs(m.sample_topp - 0.75) < 1e-7
+    assert O.Model(S.make_blob(S.HParams(arch=1, n_enc=0, n_dec=1, d_model=16, n_heads=1, d_ffn=16, vocab=20, max_pos=8,
+                                         act=1, norm=1, sample_topk=4))).sample_topp == 1.0
