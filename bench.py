@@ -90,7 +90,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed decode steps (0 = to the end of the translation)")
     ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the timed ones")
-    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s"])
+    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s", "gpt2s_k32p75"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle sample")
     ap.add_argument("--breakdown", default="", help="write the per-kernel-class table to this JSON file")
@@ -246,7 +246,7 @@ def main() -> int:
         n_steps, tok, t0 = 0, 0, time.perf_counter()
         while gpt:
             logits = O.gpt_step_logits(m, st)
-            picks = [O.sample_topk(logits[r], m.sample_topk, O.sample_uniform(m.seed, st.t, r)) for r in range(B)]
+            picks = [O.sample_topk(logits[r], m.sample_topk, O.sample_uniform(m.seed, st.t, r), m.sample_topp) for r in range(B)]
             O.gpt_advance(m, st, [q[0] for q in picks], [q[1] for q in picks])
             n_steps += 1
             tok += B
@@ -267,9 +267,10 @@ def main() -> int:
                           f"{cdt / n_steps * 1e3:.0f} ms/step; {'prompt prefill' if gpt else 'encoder'} excluded)")
 
     if gpt:
-        metric = f"sampled tokens/sec, top-{hp.sample_topk} sampling (decoder-only, GPT-2-small shape); ms per decode step"
+        nucleus = f", top-p {hp.sample_topp:g}" if hp.sample_topp < 1 else ""
+        metric = f"sampled tokens/sec, top-{hp.sample_topk}{nucleus} sampling (decoder-only, GPT-2-small shape); ms per decode step"
         desc = (f"{args.workload}: decoder-only d_model {hp.d_model}, {hp.n_dec} layers, FFN {hp.d_ffn}, vocab {hp.vocab}, "
-                f"batch {B}, prompt {int(w.src_lens[0])}, {hp.cap_extra} new tokens, top-{hp.sample_topk} sampling")
+                f"batch {B}, prompt {int(w.src_lens[0])}, {hp.cap_extra} new tokens, top-{hp.sample_topk}{nucleus} sampling")
     else:
         metric = "decoded target tokens/sec at beam 4 (Transformer-big fp16); ms per decode step"
         desc = (f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, "

@@ -206,6 +206,7 @@ def workload(name: str, *, batch: int | None = None, seed: int = INPUT_SEED) -> 
     """The named synthetic workloads (stand-ins for the paper's WMT14 En-De buckets).
 
     gpt2s : decoder-only GPT-2-small shape, fp16, top-8 sampling (see below).
+    gpt2s_k32p75 : the same with the paper's sampling setting, top-k 32 and top-p 0.75.
     tiny : 1+1 layers, d 64, 4 heads, FFN 256, vocab 1000, fp32; batch 2, lengths 5 and 8,
            beam 4, max target length 8.
     base : Transformer-base shape, fp16; batch 8, lengths U{10..60}, beam 4, cap = len + 50.
@@ -231,11 +232,12 @@ def workload(name: str, *, batch: int | None = None, seed: int = INPUT_SEED) -> 
         lens = _lognormal_lens(rng, b)
         return Workload(name, hp, b, 4, int(lens.max()) + hp.cap_extra, lens,
                         _ids(rng, lens, hp.vocab, hp.pad_id))
-    if name == "gpt2s":
+    if name in ("gpt2s", "gpt2s_k32p75"):
         # decoder-only, GPT-2-small shape: 12 layers, d 768, 12 heads, FFN 3072, tanh-GELU, pre-LN,
         # vocab 50257, learned positions; batch 32 prompts of 64 random ids, 128 sampled tokens (top-8)
         hp = HParams(arch=1, n_enc=0, n_dec=12, d_model=768, n_heads=12, d_ffn=3072, vocab=50257, dtype=1,
-                     max_pos=256, act=1, norm=1, sample_topk=8, cap_extra=128)
+                     max_pos=256, act=1, norm=1, cap_extra=128,
+                     **(dict(sample_topk=8) if name == "gpt2s" else dict(sample_topk=32, sample_topp=0.75)))
         b = batch or 32
         lens = np.full(b, 64, np.int32)
         return Workload(name, hp, b, 1, 64 + 128, lens, _ids(rng, lens, hp.vocab, hp.pad_id))

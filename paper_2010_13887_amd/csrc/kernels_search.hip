@@ -72,7 +72,7 @@ row_topk_kernel(const T* __restrict__ logits,
   }
   // One reduction for both softmax statistics: every thread owns (local max, local sum of
   // exp(x - local max)); pairs merge as (max, z1*exp(m1-max) + z2*exp(m2-max)).
-  constexpr int NW = BLOCK / 64, CAP = 256;
+  constexpr int NW = BLOCK / 64, CAP = 1024;   // a few k * H_k candidates are expected; k = 32 needs the room
   __shared__ float red_m[NW], red_z[NW], wave_best[NW * LSQ_MAX_TOPK_];
   __shared__ float cand_s[CAP];
   __shared__ int cand_i[CAP];
@@ -156,16 +156,17 @@ row_topk_kernel(const T* __restrict__ logits,
   __syncthreads();
   const int n = cand_n;
   if (n <= CAP) {
-    // ---- exact ranking of the short list (first wavefront) -----------------------------------
-    if (wave == 0) {
-      for (int c = lane; c < n; c += 64) {
+    // ---- exact ranking of the short list: a dozen entries for a beam (first wavefront), up to a
+    // few hundred for wide sampling (all wavefronts) ----------------------------------------------
+    if (wave == 0 || n > 64) {
+      for (int c = (n > 64 ? tid : lane); c < n; c += (n > 64 ? BLOCK : 64)) {
         const float sc = cand_s[c];
         const int v = cand_i[c];
         int rank = 0;
         for (int o = 0; o < n; ++o) rank += precedes(cand_s[o], cand_i[o], sc, v) ? 1 : 0;
         if (rank < k) { os[rank] = sc; oi[rank] = v; }
       }
-      if (lane >= n && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
+      if (wave == 0 && lane >= n && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
     }
     return;
   }

@@ -201,7 +201,7 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
             # (logit descending, token ascending), and its token is the oracle's draw from them
             mine = np.lexsort((np.arange(V), -got[r]))[:k]
             assert np.array_equal(g_ci[r], mine) and np.array_equal(g_cl[r], got[r][mine]), f"step {step} row {r}: candidates"
-            tok_own, _, gap_own = O.sample_topk(got[r], k, u, topp)
+            tok_own, lp_own, gap_own = O.sample_topk(got[r], k, u, topp)
             assert g_tok[r] == tok_own or gap_own < 1e-5, f"step {step} row {r}: token {g_tok[r]}, expected {tok_own}"
             tok, lp, gap = O.sample_topk(ref[r], k, u, topp)
             dev = float(np.abs(got[r] - ref[r]).max())
@@ -212,16 +212,10 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
                 loose += 1
                 order = np.lexsort((np.arange(V), -ref[r]))[:k + 1]
                 assert g_tok[r] in order, f"step {step} row {r}: sampled token is not among the oracle's candidates"
-                if g_tok[r] != tok:
-                    # the library's token under the oracle's logits: its weight over the mass of the
-                    # oracle's survivors (stretched to include it if it sits just past the oracle's cut)
-                    top = order[:k]
-                    l = ref[r][top].astype(np.float32)
-                    pe = np.exp(l - l[0])
-                    cum = np.cumsum(pe, dtype=np.float32)
-                    n = k if topp >= 1.0 else min(int(np.searchsorted(cum, np.float32(topp) * cum[-1], side="left")) + 1, k)
-                    j = int(np.nonzero(top == g_tok[r])[0][0]) if g_tok[r] in top else k - 1
-                    tok, lp = int(g_tok[r]), float(np.log(pe[j] / cum[max(n, j + 1) - 1]))
+                # a near-decision (rank swap, draw at an edge, nucleus cut at its threshold): the oracle
+                # follows the library, taking the oracle's own rule applied to the library's logits for
+                # the token and for its log-probability (the survivors' mass depends on where the cut fell)
+                tok, lp = int(g_tok[r]), lp_own
             toks.append(tok)
             lps.append(lp)
         O.gpt_advance(m, st, toks, lps)
