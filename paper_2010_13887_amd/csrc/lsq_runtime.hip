@@ -116,7 +116,8 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
                   hp->d > 4096))
     return fail(LSQ_E_BLOB, "decoder-only blob: n_enc must be 0, sample_topk in [1, %d], max_pos >= 1, d <= 4096", LSQ_MAX_SAMPLE_TOPK);
   if ((encdec && hp->n_enc < 1) || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
-      hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0)
+      hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0 || hp->d > 16384 || hp->F > 262144 || hp->max_pos < 0 ||
+      hp->max_pos > (1 << 20) || hp->cap_extra > (1 << 20))
     return fail(LSQ_E_BLOB, "implausible model shape");
   if (hp->d % 8 != 0 || hp->F % 8 != 0) return fail(LSQ_E_BLOB, "d_model and d_ffn must be multiples of 8");
   if (!head_dim_supported(hp->d / hp->H)) return fail(LSQ_E_BLOB, "head size %d unsupported (16/32/64/128)", hp->d / hp->H);
@@ -222,6 +223,16 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
   p.total = std::max(e, q);
   return p;
+}
+
+// Size of the serialized model these hyper-parameters describe: header, then tensors at 256-byte boundaries.
+size_t blob_bytes(const HParams& hp) {
+  std::vector<TensorDesc> ts;
+  tensor_walk(hp, &ts);
+  const size_t es = hp.dtype == DT_F16 ? 2 : 4;
+  size_t n = 256;
+  for (auto& t : ts) n = up(n) + (size_t)t.rows * t.cols * es;
+  return n;
 }
 
 size_t device_weight_bytes(const HParams& hp) {
@@ -573,6 +584,8 @@ int lsq_workspace_bytes(const void* weights, size_t weights_bytes, int max_batch
   if (rc) return rc;
   rc = check_limits(max_batch, beam, max_len, hp);
   if (rc) return rc;
+  if (blob_bytes(hp) != hp.total)
+    return fail(LSQ_E_BLOB, "header says %llu bytes, its shapes add up to %zu", (unsigned long long)hp.total, blob_bytes(hp));
   *out_bytes = make_plan(hp, device_weight_bytes(hp), max_batch, beam, max_len).total;
   return LSQ_OK;
 }
@@ -601,9 +614,8 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
   std::vector<TensorDesc> ts;
   tensor_walk(hp, &ts);
   const size_t es = hp.dtype == DT_F16 ? 2 : 4;
-  size_t src = 256;
-  for (auto& t : ts) src = up(src) + (size_t)t.rows * t.cols * es;
-  if (src != weights_bytes) return fail(LSQ_E_BLOB, "blob size %zu does not match its shape (%zu)", weights_bytes, src);
+  if (blob_bytes(hp) != weights_bytes)
+    return fail(LSQ_E_BLOB, "blob size %zu does not match its shape (%zu)", weights_bytes, blob_bytes(hp));
   const size_t wbytes = device_weight_bytes(hp);
   Plan plan = make_plan(hp, wbytes, max_batch, beam, max_len);
   if (plan.total > g.ws_bytes)

@@ -67,3 +67,38 @@ def test_blob_writer_and_oracle_reader_agree():
     assert m.dec[0]["Wkv_c"][3, 5] == (3 * 32 + 5) / 64.0
     assert len(S.tensor_list(hp)) == 1 + 12 * 2 + 20
     assert m.enc[1]["ln2_g"].tolist() == [1.0] * 16 and m.enc[1]["ln2_b"].tolist() == [0.0] * 16
+
+
+def test_corrupt_headers_are_refused_not_trusted(lib):
+    """Random damage to the 256-byte header: lsq_workspace_bytes (host only) either refuses the blob or
+    reports a plan no smaller than the blob itself; it never crashes or overflows into nonsense."""
+    import numpy as np
+    rng = np.random.default_rng(7)
+    n = ctypes.c_size_t()
+    for base in (S.workload("tiny").blob(),
+                 S.make_blob(S.HParams(arch=1, n_enc=0, n_dec=1, d_model=16, n_heads=1, d_ffn=16, vocab=20, max_pos=8, act=1,
+                                       norm=1, sample_topk=4, sample_topp=0.5))):
+        assert lib.lsq_workspace_bytes(base, len(base), 2, 1, 8, ctypes.byref(n)) == 0 and n.value > len(base)
+        ok = refused = 0
+        for trial in range(400):
+            hdr = bytearray(base[:256])
+            for _ in range(int(rng.integers(1, 4))):
+                off = int(rng.integers(8, 104))
+                kind = int(rng.integers(0, 3))
+                if kind == 0:
+                    hdr[off] = int(rng.integers(0, 256))
+                elif kind == 1:
+                    hdr[off - off % 4: off - off % 4 + 4] = int(rng.integers(-2**31, 2**31)).to_bytes(4, "little", signed=True)
+                else:
+                    hdr[off - off % 4: off - off % 4 + 4] = int(rng.choice([0, -1, 1, 2**31 - 1, 65536, 65537])).to_bytes(
+                        4, "little", signed=True)
+            blob = bytes(hdr) + base[256:]
+            rc = lib.lsq_workspace_bytes(blob, len(blob), 2, 1, 8, ctypes.byref(n))
+            assert rc in (0, -1, -3), rc
+            if rc == 0:
+                ok += 1
+                assert len(base) <= n.value < (1 << 40)       # accepted only if the shapes still add up to the stated size
+            else:
+                refused += 1
+                assert len(lib.lsq_last_error()) > 0
+        assert refused > 100                                  # most damage is caught by a range or size check
