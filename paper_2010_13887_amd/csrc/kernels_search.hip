@@ -73,6 +73,7 @@ row_topk_kernel(const T* __restrict__ logits,
   // One reduction for both softmax statistics: every thread owns (local max, local sum of
   // exp(x - local max)); pairs merge as (max, z1*exp(m1-max) + z2*exp(m2-max)).
   constexpr int NW = BLOCK / 64, CAP = 1024;   // a few k * H_k candidates are expected; k = 32 needs the room
+  const int cap = k > LSQ_MAX_BEAM_ ? CAP : 256;   // a beam's list is short: beyond 256 the k-round search is quicker
   __shared__ float red_m[NW], red_z[NW], wave_best[NW * LSQ_MAX_TOPK_];
   __shared__ float cand_s[CAP];
   __shared__ int cand_i[CAP];
@@ -118,7 +119,10 @@ row_topk_kernel(const T* __restrict__ logits,
   // go to a short list in LDS which is then ranked exactly.  Rows where the list
   // overflows (e.g. thousands of equal logits) take the exact k-round arg-max below instead.
   float R;
-  if (NW >= k) {
+  // wavefront groups need every wavefront to hold tokens: with the vectorised layout wavefront w
+  // starts at token 512 w, so short rows leave the last wavefronts empty (their maximum would be
+  // -inf and every token would pass the threshold)
+  if (NW >= k && (long)(NW - 1) * 512 < V) {
     const float wb = wave_max(best);
     if (lane == 0) wave_best[wave] = wb;
     __syncthreads();
@@ -129,18 +133,34 @@ row_topk_kernel(const T* __restrict__ logits,
       R = fminf(R, gm);
     }
   } else {
-    // fewer wavefronts than groups: groups are lanes modulo k within each wavefront, merged across wavefronts
-    R = INFINITY;
-    for (int grp = 0; grp < k; ++grp) {
-      const float gm = wave_max((lane % k) == grp ? best : -INFINITY);
-      if (lane == 0) wave_best[wave * LSQ_MAX_TOPK_ + grp] = gm;
+    // fewer wavefronts than groups (or empty ones): groups are the lanes modulo k of every
+    // wavefront.  Group maxima inside a wavefront: a butterfly over the lanes that share lane % k
+    // when k is a power of two, else one wavefront reduction per group; then thread g < k merges
+    // group g across the wavefronts and the first wavefront takes the minimum.
+    __shared__ float r_sh;
+    if ((k & (k - 1)) == 0) {
+      float gm = best;
+      for (int o = k; o < 64; o <<= 1) gm = fmaxf(gm, __shfl_xor(gm, o, kWave));
+      if (lane < k) wave_best[wave * LSQ_MAX_TOPK_ + lane] = gm;
+    } else {
+      for (int grp = 0; grp < k; ++grp) {
+        const float gm = wave_max((lane % k) == grp ? best : -INFINITY);
+        if (lane == 0) wave_best[wave * LSQ_MAX_TOPK_ + grp] = gm;
+      }
     }
     __syncthreads();
-    for (int grp = 0; grp < k; ++grp) {
-      float gm = -INFINITY;
-      for (int w = 0; w < NW; ++w) gm = fmaxf(gm, wave_best[w * LSQ_MAX_TOPK_ + grp]);
-      R = fminf(R, gm);
+    if (wave == 0) {
+      float gm = INFINITY;
+      if (lane < k) {
+        gm = -INFINITY;
+        for (int w = 0; w < NW; ++w) gm = fmaxf(gm, wave_best[w * LSQ_MAX_TOPK_ + lane]);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) gm = fminf(gm, __shfl_xor(gm, o, kWave));
+      if (lane == 0) r_sh = gm;
     }
+    __syncthreads();
+    R = r_sh;
   }
 #pragma unroll
   for (int j = 0; j < NV; ++j)
@@ -150,12 +170,12 @@ row_topk_kernel(const T* __restrict__ logits,
       const float sc = x[j * 8 + e];
       if (v < V && sc >= R) {
         const int slot = atomicAdd(&cand_n, 1);
-        if (slot < CAP) { cand_s[slot] = sc; cand_i[slot] = v; }
+        if (slot < cap) { cand_s[slot] = sc; cand_i[slot] = v; }
       }
     }
   __syncthreads();
   const int n = cand_n;
-  if (n <= CAP) {
+  if (n <= cap) {
     // ---- exact ranking of the short list: a dozen entries for a beam (first wavefront), up to a
     // few hundred for wide sampling (all wavefronts) ----------------------------------------------
     if (wave == 0 || n > 64) {
