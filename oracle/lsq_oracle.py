@@ -253,9 +253,10 @@ def encode(model, src_ids, src_lens):
 # decoder, one position for every hypothesis row, K/V cached
 # ----------------------------------------------------------------------------
 class DecodeState:
-    def __init__(self, model, src_lens, beam, max_len):
+    def __init__(self, model, src_lens, beam, max_len, groups=1):
         B = len(src_lens)
-        self.B, self.k, self.T = B, beam, max_len
+        assert groups >= 1 and beam % groups == 0
+        self.B, self.k, self.T, self.groups = B, beam, max_len, groups
         M = B * beam
         self.t = 0
         self.tokens = np.full((M, max_len + 1), model.pad, np.int32)
@@ -263,7 +264,7 @@ class DecodeState:
         self.len = np.zeros(M, np.int32)
         self.finished = np.zeros(M, bool)
         self.score = np.full((B, beam), -np.inf, model.ctype)
-        self.score[:, 0] = 0
+        self.score[:, ::beam // groups] = 0          # one live hypothesis per group (one group: per sentence)
         self.cap = np.minimum(np.asarray(src_lens, np.int64) + model.cap_extra, max_len).astype(np.int32)
         self.Kc = [np.zeros((M, max_len, model.d), model.ctype) for _ in model.dec]
         self.Vc = [np.zeros((M, max_len, model.d), model.ctype) for _ in model.dec]
@@ -362,6 +363,63 @@ def beam_select(model, st, logits):
     return token, parent, score, margin
 
 
+def group_select(model, st, logp, b, g, strength, counts):
+    """Diverse beam search (Vijayakumar et al. 2016, Hamming diversity; named in sec. 3.4's list of
+    search methods): group g of sentence b picks its k' = k / groups best (beam, token) pairs among
+    its own hypotheses, ranked by score + log p(token) - strength * counts[token], where
+    counts[token] says how many hypotheses of the groups before g chose that token at this step.
+    A finished hypothesis offers itself once, unpenalised.  Ties: flat index (beam within the
+    sentence) * V + token, ascending.  Returns tokens, parents (beam index within the sentence),
+    the hypotheses' new scores (log-probability sums, without the penalty), the ranking values and
+    the smallest gap between consecutive ranking values among the kept and the first dropped."""
+    k, V = st.k, model.V
+    kg = k // st.groups
+    cs, cp, cf = [], [], []
+    for j in range(g * kg, (g + 1) * kg):
+        r = b * k + j
+        if st.finished[r]:
+            plain = np.array([st.score[b, j]], model.ctype)
+            cs.append(plain); cp.append(plain)
+            cf.append(np.array([j * V + model.eos], np.int64))
+        else:
+            plain = (st.score[b, j] + logp[r]).astype(model.ctype)
+            pen = (np.asarray(strength, model.ctype) * counts.astype(model.ctype)).astype(model.ctype)
+            cs.append((plain - pen).astype(model.ctype)); cp.append(plain)
+            cf.append(j * V + np.arange(V, dtype=np.int64))
+    cs, cp, cf = np.concatenate(cs), np.concatenate(cp), np.concatenate(cf)
+    order = np.lexsort((cf, -cs))
+    best = order[:kg]
+    top = cs[order[:kg + 1]].astype(np.float64)
+    fin = np.isfinite(top)
+    gaps = [top[i] - top[i + 1] for i in range(len(top) - 1) if fin[i] and fin[i + 1]]
+    return (cf[best] % V).astype(np.int32), (cf[best] // V).astype(np.int32), cp[best], cs[best], \
+        (min(gaps) if gaps else np.inf)
+
+
+def beam_select_diverse(model, st, logits, strength):
+    """One pruning step of diverse beam search for every sentence: the groups choose in order, each
+    seeing the tokens the earlier groups of its sentence took at this step.  Same returns as
+    beam_select (margin = the smallest over the groups)."""
+    B, k, V, G = st.B, st.k, model.V, st.groups
+    kg = k // G
+    logp = log_softmax(np.asarray(logits, model.ctype))
+    token = np.zeros((B, k), np.int32)
+    parent = np.zeros((B, k), np.int32)
+    score = np.zeros((B, k), model.ctype)
+    margin = np.full(B, np.inf)
+    for b in range(B):
+        counts = np.zeros(V, np.int64)
+        for g in range(G):
+            tok, par, sc, _, m = group_select(model, st, logp, b, g, strength, counts)
+            sl = slice(g * kg, (g + 1) * kg)
+            token[b, sl], parent[b, sl], score[b, sl] = tok, par, sc
+            margin[b] = min(margin[b], m)
+            for i in range(kg):
+                if not st.finished[b * k + par[i]] and np.isfinite(sc[i]):
+                    counts[tok[i]] += 1
+    return token, parent, score, margin
+
+
 def beam_advance(model, st, token, parent, score):
     """Adopt the selected candidates: gather histories and caches from the
     parents ("cache refreshing", sec. 3.2), append tokens, update flags."""
@@ -408,15 +466,19 @@ def finalize(model, st):
     return ids, lens, scores
 
 
-def translate(model, src_ids, src_lens, beam, max_len, max_steps=None, trace=None):
+def translate(model, src_ids, src_lens, beam, max_len, max_steps=None, trace=None, groups=1, strength=0.0):
     """Whole path: encode, then decode steps until every sentence is finished
-    (or ``max_steps``).  ``trace``, if a list, receives one dict per step."""
+    (or ``max_steps``).  ``trace``, if a list, receives one dict per step.
+    groups > 1: diverse beam search with that many groups and that diversity strength."""
     memory, cross = encode(model, src_ids, src_lens)
-    st = DecodeState(model, src_lens, beam, max_len)
+    st = DecodeState(model, src_lens, beam, max_len, groups)
     steps = 0
     while True:
         logits = decoder_logits_cached(model, st, cross)
-        token, parent, score, margin = beam_select(model, st, logits)
+        if groups > 1:
+            token, parent, score, margin = beam_select_diverse(model, st, logits, strength)
+        else:
+            token, parent, score, margin = beam_select(model, st, logits)
         active = beam_advance(model, st, token, parent, score)
         steps += 1
         if trace is not None:
