@@ -136,6 +136,17 @@ int lsq_set_cache_refresh(int mode);
  * LayerNorm kernel at every size; results are bit-identical.  Default: on. */
 int lsq_set_layernorm_fusion(int on);
 
+/* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
+ * al. 2016, Hamming diversity).  The beam is split into `groups` groups of
+ * beam / groups hypotheses; at every step the groups of a sentence choose in
+ * order, and a candidate token is ranked by score + log p - strength * (number
+ * of hypotheses of the earlier groups that took that token at this step).
+ * Hypothesis scores stay plain log-probability sums; finished hypotheses are
+ * neither penalised nor counted.  groups = 1 (default) is ordinary beam search.
+ * groups must divide the beam of lsq_init; takes effect at the next lsq_encode
+ * (which fails with LSQ_E_ARG otherwise).  Encoder-decoder models only. */
+int lsq_set_diversity(int groups, float strength);
+
 /* Number of decode steps taken since the last lsq_encode. */
 int lsq_step_index(void);
 

@@ -45,6 +45,7 @@ def load_library() -> C.CDLL:
         "lsq_step_index": [],
         "lsq_set_graphs": [i32],
         "lsq_set_cache_refresh": [i32],
+        "lsq_set_diversity": [i32, f32],
         "lsq_set_layernorm_fusion": [i32],
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_debug_read": [i32, vp, sz],
@@ -129,6 +130,11 @@ def lsq_set_graphs(on: bool) -> None:
 def lsq_set_layernorm_fusion(on: bool) -> None:
     """LayerNorm inside the consuming product when at most 8 rows are alive (default on)."""
     _check(load_library().lsq_set_layernorm_fusion(int(on)))
+
+
+def lsq_set_diversity(groups: int = 1, strength: float = 0.0) -> None:
+    """Diverse beam search from the next encode on: `groups` groups per sentence, Hamming penalty `strength`."""
+    _check(load_library().lsq_set_diversity(int(groups), float(strength)))
 
 
 REFRESH_MOVE, REFRESH_TABLE = 0, 1

@@ -28,19 +28,28 @@ row_topk_kernel(const T* __restrict__ logits,
                                                          const float* __restrict__ score,
                                                          const int32_t* __restrict__ fin, int V, int k, int eos,
                                                          int raw, float* __restrict__ out_score,
-                                                         int32_t* __restrict__ out_idx) {
+                                                         int32_t* __restrict__ out_idx, SearchGroups gr) {
   __shared__ float reds[BLOCK / 64];
   __shared__ int redi[BLOCK / 64];
-  const int r = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int sent = blockIdx.x / gr.kg;                                   // one group of every sentence per launch
+  const int r = sent * gr.k_all + gr.goff + blockIdx.x % gr.kg;
   const float bs = raw ? 0.f : score[r];
   float* os = out_score + (size_t)r * k;
   int32_t* oi = out_idx + (size_t)r * k;
+  float* op = gr.out_plain ? gr.out_plain + (size_t)r * k : nullptr;     // unpenalised values of the kept
   if (!raw && fin[r]) {   // a finished hypothesis offers itself once
-    if (tid < k) { os[tid] = tid == 0 ? bs : -INFINITY; oi[tid] = tid == 0 ? eos : -1; }
+    if (tid < k) {
+      os[tid] = tid == 0 ? bs : -INFINITY; oi[tid] = tid == 0 ? eos : -1;
+      if (op) op[tid] = os[tid];
+    }
     return;
   }
   if (bs == -INFINITY) {   // every candidate is -inf: the order is by token alone
-    if (tid < k) { os[tid] = -INFINITY; oi[tid] = tid < V ? tid : -1; }
+    if (tid < k) {
+      os[tid] = -INFINITY; oi[tid] = tid < V ? tid : -1;
+      if (op) op[tid] = -INFINITY;
+    }
     return;
   }
   const T* row = logits + (size_t)r * V;
@@ -108,8 +117,33 @@ row_topk_kernel(const T* __restrict__ logits,
 #pragma unroll
   for (int i = 0; i < NV * 8; ++i) {
     if (!raw) x[i] = __fadd_rn(bs, __fsub_rn(__fsub_rn(x[i], m), logz));
-    best = fmaxf(best, x[i]);     // padding slots stay -inf
   }
+  // diverse beam search: every time an earlier group of this sentence took token v at this step,
+  // v's ranking value drops by `strength` (all occurrences counted first, one subtraction)
+  auto plain_of = [&](int v) { return __fadd_rn(bs, __fsub_rn(__fsub_rn((float)row[v], m), logz)); };
+  if (gr.pen_tok) {
+    const int np = gr.pen_n[sent];
+    for (int p = 0; p < np; ++p) {
+      const int tk = gr.pen_tok[(size_t)sent * gr.pen_ld + p];
+      int cnt = 0;
+      bool first = true;
+      for (int q = 0; q < np; ++q) {
+        const bool same = gr.pen_tok[(size_t)sent * gr.pen_ld + q] == tk;
+        cnt += same ? 1 : 0;
+        if (same && q < p) first = false;
+      }
+      const int owner = vec ? (tk >> 3) % BLOCK : tk % BLOCK;
+      if (first && owner == tid && tk < V) {
+        const int slot = vec ? ((tk >> 3) / BLOCK) * 8 + (tk & 7) : tk / BLOCK;
+        const float pen = __fmul_rn(gr.strength, (float)cnt);
+#pragma unroll
+        for (int i = 0; i < NV * 8; ++i)
+          if (i == slot) x[i] = __fsub_rn(x[i], pen);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) best = fmaxf(best, x[i]);     // padding slots stay -inf
 
   // ---- rough stage (the paper's retrieve, sec. 2.2): split the row into k groups, take each
   // group's maximum, R = the smallest of them.  Each group maximum is the score of a distinct
@@ -184,9 +218,15 @@ row_topk_kernel(const T* __restrict__ logits,
         const int v = cand_i[c];
         int rank = 0;
         for (int o = 0; o < n; ++o) rank += precedes(cand_s[o], cand_i[o], sc, v) ? 1 : 0;
-        if (rank < k) { os[rank] = sc; oi[rank] = v; }
+        if (rank < k) {
+          os[rank] = sc; oi[rank] = v;
+          if (op) op[rank] = plain_of(v);
+        }
       }
-      if (wave == 0 && lane >= n && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
+      if (wave == 0 && lane >= n && lane < k) {   // vocabulary smaller than k
+        os[lane] = -INFINITY; oi[lane] = -1;
+        if (op) op[lane] = -INFINITY;
+      }
     }
     return;
   }
@@ -224,9 +264,9 @@ row_topk_kernel(const T* __restrict__ logits,
       if (i2 != 0x7fffffff && (ci == 0x7fffffff || precedes(s2, i2, cs, ci))) { cs = s2; ci = i2; }
     }
     if (ci == 0x7fffffff) {   // fewer than k tokens in the vocabulary
-      if (tid == 0) { os[round] = -INFINITY; oi[round] = -1; }
+      if (tid == 0) { os[round] = -INFINITY; oi[round] = -1; if (op) op[round] = -INFINITY; }
     } else {
-      if (tid == 0) { os[round] = cs; oi[round] = ci; }
+      if (tid == 0) { os[round] = cs; oi[round] = ci; if (op) op[round] = plain_of(ci); }
       ps = cs;
       pi = ci;
     }
@@ -237,30 +277,33 @@ bool topk_supported(int V) { return V >= 1 && V <= 65536; }
 
 template <typename T>
 static hipError_t row_topk_t(const T* logits, const float* score, const int32_t* fin, int M, int V, int k,
-                             int eos, int raw, float* os, int32_t* oi, hipStream_t s) {
+                             int eos, int raw, float* os, int32_t* oi, hipStream_t s, const SearchGroups& gr) {
   if (V <= 2048)
-    row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
+    row_topk_kernel<T, 256, 1><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi, gr);
   else if (V <= 8192)
-    row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
+    row_topk_kernel<T, 256, 4><<<M, 256, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi, gr);
   else if (V <= 32768)   // 512 threads x 64 tokens: two workgroups fit a CU, one loads while the other reduces
-    row_topk_kernel<T, 512, 8><<<M, 512, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
+    row_topk_kernel<T, 512, 8><<<M, 512, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi, gr);
   else if (V <= 65536)
-    row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi);
+    row_topk_kernel<T, 1024, 8><<<M, 1024, 0, s>>>(logits, score, fin, V, k, eos, raw, os, oi, gr);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin, int M,
-                           int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s) {
+                           int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s,
+                           const SearchGroups& gr) {
   if (M <= 0) return hipSuccess;
-  if (k < 1 || k > LSQ_MAX_TOPK_) return hipErrorInvalidValue;
-  if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
-  return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s);
+  if (k < 1 || k > LSQ_MAX_TOPK_ || gr.kg < 1 || M % gr.kg != 0) return hipErrorInvalidValue;
+  if (dtype == DT_F16) return row_topk_t<half_t>((const half_t*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s, gr);
+  return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s, gr);
 }
 
 // ---------------------------------------------------------------------------------------------
-// One wavefront per sentence.  Lane c < k*k owns survivor (beam c / k, slot c % k).
+// One wavefront per sentence (per group of a sentence under diverse beam search: k is then the
+// group width, the group's rows start at beam slot goff of the sentence's k_all).  Lane c < k*k owns
+// survivor (beam c / k of the group, slot c % k).
 __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict__ cand_score,
                                                          const int32_t* __restrict__ cand_idx,
                                                          float* __restrict__ score, int32_t* __restrict__ tokens,
@@ -269,35 +312,38 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
                                                          const int32_t* __restrict__ cap,
                                                          int32_t* __restrict__ active, int k, int V, int T1,
                                                          int t_base, int32_t* __restrict__ step_state, int eos,
-                                                         int32_t* __restrict__ anc) {
+                                                         int32_t* __restrict__ anc, SearchGroups gr) {
   __shared__ int sh_parent[LSQ_MAX_BEAM_];
-  __shared__ int sh_unfinished;
+  __shared__ int sh_unfinished, sh_taken;
   const int b = blockIdx.x, lane = threadIdx.x;
   const int t = t_base + (step_state ? step_state[0] : 0);
   const int kk = k * k;
-  if (lane == 0) sh_unfinished = 0;
-  float s = -INFINITY;
+  const int k_all = gr.k_all > 1 ? gr.k_all : k;           // rows of a sentence (k_all == 1: no groups)
+  const int base = b * k_all + gr.goff;                    // first row of this group
+  if (lane == 0) { sh_unfinished = 0; sh_taken = 0; }
+  float s = -INFINITY, plain = -INFINITY;
   long flat = -1;
   int tok = -1, j = 0;
   if (lane < kk) {
     j = lane / k;
-    s = cand_score[(size_t)b * kk + lane];
-    tok = cand_idx[(size_t)b * kk + lane];
-    if (tok >= 0) flat = (long)j * V + tok;
+    s = cand_score[(size_t)base * k + lane];
+    plain = gr.out_plain ? gr.out_plain[(size_t)base * k + lane] : s;
+    tok = cand_idx[(size_t)base * k + lane];
+    if (tok >= 0) flat = (long)(gr.goff + j) * V + tok;
   }
   int rank = 0;
   for (int c = 0; c < kk; ++c) {
     float s2 = __shfl(s, c, kWave);
     int t2 = __shfl(tok, c, kWave);
-    long f2 = t2 >= 0 ? (long)(c / k) * V + t2 : -1;
+    long f2 = t2 >= 0 ? (long)(gr.goff + c / k) * V + t2 : -1;
     if (f2 >= 0 && (s2 > s || (s2 == s && f2 < flat))) ++rank;
   }
   const bool win = flat >= 0 && rank < k;
   // read the parent's state before anyone overwrites it
   int plen = 0, pfin = 0;
   if (win) {
-    plen = len[b * k + j];
-    pfin = fin[b * k + j];
+    plen = len[base + j];
+    pfin = fin[base + j];
     sh_parent[rank] = j;
   }
   __syncthreads();
@@ -306,7 +352,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     int h[LSQ_MAX_BEAM_];
 #pragma unroll
     for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
-      if (i < k) h[i] = tokens[(size_t)(b * k + i) * T1 + p];
+      if (i < k) h[i] = tokens[(size_t)(base + i) * T1 + p];
 #pragma unroll
     for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
       if (i < k) {
@@ -314,14 +360,14 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
 #pragma unroll
         for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
           if (jj == src) val = h[jj];
-        if (src != i) tokens[(size_t)(b * k + i) * T1 + p] = val;
+        if (src != i) tokens[(size_t)(base + i) * T1 + p] = val;
       }
     // the same gather for the table that says which slab holds position p of each history
     // (cache refreshing without moving the cache); position t+1 will be written by the row itself
     if (anc) {
 #pragma unroll
       for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
-        if (i < k) h[i] = anc[(size_t)(b * k + i) * T1 + p];
+        if (i < k) h[i] = anc[(size_t)(base + i) * T1 + p];
 #pragma unroll
       for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
         if (i < k) {
@@ -329,29 +375,41 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
 #pragma unroll
           for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
             if (jj == src) val = h[jj];
-          if (src != i) anc[(size_t)(b * k + i) * T1 + p] = val;
+          if (src != i) anc[(size_t)(base + i) * T1 + p] = val;
         }
     }
   }
-  if (anc && lane < k && t + 1 < T1) anc[(size_t)(b * k + lane) * T1 + t + 1] = lane;
+  if (anc && lane < k && t + 1 < T1) anc[(size_t)(base + lane) * T1 + t + 1] = gr.goff + lane;
   __syncthreads();
   if (win) {
-    const int row = b * k + rank;
+    const int row = base + rank;
     int nlen = plen, nfin = pfin;
     if (!pfin) {
       nlen = plen + 1;
       tokens[(size_t)row * T1 + nlen] = tok;
       nfin = (tok == eos || nlen >= cap[b]) ? 1 : 0;
+      // a live hypothesis that took a token: later groups of this sentence are steered away from it
+      if (gr.pen_tok && !gr.last && plain != -INFINITY) {
+        const int at = atomicAdd(&sh_taken, 1);
+        gr.pen_tok[(size_t)b * gr.pen_ld + gr.pen_n[b] + at] = tok;
+      }
     }
     len[row] = nlen;
     fin[row] = nfin;
-    score[row] = s;
-    parent[row] = j;
+    score[row] = plain;
+    parent[row] = gr.goff + j;
     if (!nfin) sh_unfinished = 1;
   }
   __syncthreads();
+  if (gr.pen_n && lane == 0) gr.pen_n[b] = gr.last ? 0 : gr.pen_n[b] + sh_taken;
+  if (!gr.last) return;
+  // the sentence is still active if any hypothesis of any group is unfinished (the other groups'
+  // rows were settled by earlier launches of this step)
+  int others = 0;
+  if (lane < k_all && (lane < gr.goff || lane >= gr.goff + k)) others = fin[b * k_all + lane] ? 0 : 1;
+  others = __any(others) ? 1 : 0;
   if (lane == 0) {
-    if (sh_unfinished) atomicAdd(step_state ? active + t : active, 1);   // per-step counters, or the caller's one
+    if (sh_unfinished || others) atomicAdd(step_state ? active + t : active, 1);   // per-step counters, or the caller's one
     if (step_state) {
       // the last sentence to get here advances the step counter; every workgroup read it at its
       // start, and kernels launched later see the new value
@@ -367,11 +425,13 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
                               int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
                               int32_t* active, int batch, int k, int V, int T, int t_base, int32_t* step_state,
-                              int eos, int32_t* anc, hipStream_t s) {
+                              int eos, int32_t* anc, hipStream_t s, const SearchGroups& gr) {
   if (batch <= 0) return hipSuccess;
   if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
+  if (gr.k_all > 1 && (gr.kg != k || gr.k_all % k != 0 || gr.k_all > LSQ_MAX_BEAM_ || gr.goff % k != 0 || gr.goff + k > gr.k_all))
+    return hipErrorInvalidValue;
   beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
-                                          k, V, T + 1, t_base, step_state, eos, anc);
+                                          k, V, T + 1, t_base, step_state, eos, anc, gr);
   return hipGetLastError();
 }
 
@@ -436,13 +496,14 @@ hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, i
 // ---------------------------------------------------------------------------------------------
 __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict__ tokens, int32_t* __restrict__ len,
                                   int32_t* __restrict__ fin, int32_t* __restrict__ active_counts,
-                                  int32_t* __restrict__ step_state, int32_t* __restrict__ anc, int M, int k,
-                                  int T1, int bos, int pad) {
+                                  int32_t* __restrict__ step_state, int32_t* __restrict__ anc,
+                                  int32_t* __restrict__ pen_n, int M, int k, int kg, int T1, int bos, int pad) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 3) step_state[i] = 0;   // [0] position counter, [1] arrival counter, [2] position of step 0
   if (i < M * T1) tokens[i] = (i % T1 == 0) ? bos : pad;
   if (i < M) {
-    score[i] = (i % k == 0) ? 0.f : -INFINITY;
+    score[i] = (i % kg == 0) ? 0.f : -INFINITY;   // one live hypothesis per search group
+    if (pen_n && i % k == 0) pen_n[i / k] = 0;
     len[i] = 0;
     fin[i] = 0;
     if (anc) anc[(size_t)i * T1] = i % k;   // position 0 is written by the row itself
@@ -451,11 +512,12 @@ __global__ void beam_reset_kernel(float* __restrict__ score, int32_t* __restrict
 }
 
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin, int32_t* active_counts,
-                             int32_t* step_state, int32_t* anc, int batch, int k, int T, int bos, int pad,
-                             hipStream_t s) {
+                             int32_t* step_state, int32_t* anc, int32_t* pen_n, int batch, int k, int kg, int T,
+                             int bos, int pad, hipStream_t s) {
   int M = batch * k, n = M * (T + 1);
-  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, step_state, anc, M, k,
-                                                    T + 1, bos, pad);
+  if (kg < 1 || k % kg != 0) return hipErrorInvalidValue;
+  beam_reset_kernel<<<(n + 255) / 256, 256, 0, s>>>(score, tokens, len, fin, active_counts, step_state, anc, pen_n, M,
+                                                    k, kg, T + 1, bos, pad);
   return hipGetLastError();
 }
 

@@ -93,10 +93,28 @@ hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* r
                                     const int32_t* off, const int32_t* len, void* out, int rows, int H,
                                     int d, int causal, hipStream_t s);
 
-// raw != 0: rank the logits themselves (score and fin are ignored, may be null)
+// Diverse beam search: the search kernels work on one group of every sentence at a time.  A sentence's
+// k_all rows are split into groups of kg; this launch takes group goff / kg (rows goff .. goff+kg-1 of
+// each sentence).  pen_tok [sentences, pen_ld] / pen_n [sentences]: tokens taken at this step by the
+// groups before it; every occurrence of a token lowers its ranking value by `strength`.
+// out_plain [M, k]: the unpenalised values of the kept candidates (what the hypothesis score becomes).
+struct SearchGroups {
+  int kg, k_all, goff;
+  int32_t* pen_tok;
+  int32_t* pen_n;
+  int pen_ld;
+  float strength;
+  float* out_plain;
+  int last;   // the last group of the step: counts active sentences, advances the step, clears pen_n
+};
+// no groups: every row is its own unit for the retrieve kernel, a sentence's k rows one unit for the re-rank kernel
+inline SearchGroups one_group() { return SearchGroups{1, 1, 0, nullptr, nullptr, 0, 0.f, nullptr, 1}; }
+
+// raw != 0: rank the logits themselves (score and fin are ignored, may be null).  M counts the rows
+// this launch works on (sentences * groups.kg).
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
                            int M, int V, int k, int eos, int raw, float* out_score, int32_t* out_idx,
-                           hipStream_t s);
+                           hipStream_t s, const SearchGroups& groups = one_group());
 // topp < 1: only the shortest prefix of the ranked candidates whose k-way softmax mass reaches topp is drawn from
 hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
                          float* logp, int32_t* active, int32_t* step_state, int rows, int k, float topp, int T,
@@ -106,17 +124,20 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
 // (step_state[1] is its arrival counter and must be zero at launch).  anc != null: the slab table
 // [batch*k, T+1] is gathered by parent like the token histories, and entry t+1 of every row is set
 // to the row's own beam index.
+// groups given (kg < k_all): k is the group width kg, candidates are [rows, kg]; see SearchGroups.
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
                               int32_t* tokens, int32_t* len, int32_t* fin, int32_t* parent,
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
-                              int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s);
+                              int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
+                              const SearchGroups& groups = one_group());
 // npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
                                 int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,
                                 int npos_max, hipStream_t s);
+// kg: width of a search group (k without diverse beam search): the first hypothesis of every group starts alive
 hipError_t launch_beam_reset(float* score, int32_t* tokens, int32_t* len, int32_t* fin,
-                             int32_t* active_counts, int32_t* step_state, int32_t* anc, int batch, int k,
-                             int T, int bos, int pad, hipStream_t s);
+                             int32_t* active_counts, int32_t* step_state, int32_t* anc, int32_t* pen_n, int batch,
+                             int k, int kg, int T, int bos, int pad, hipStream_t s);
 // first: index in the token history of the first token to hand out (1 after BOS; prompt length for
 // the decoder-only model)
 hipError_t launch_finalize(const float* score, const int32_t* tokens, const int32_t* len, int32_t* out_ids,

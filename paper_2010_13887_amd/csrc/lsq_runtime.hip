@@ -167,7 +167,7 @@ struct DecLayer {
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
 struct Plan {
-  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, anc, cap, order, src_off, src_len, active, step_state,
+  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, anc, pen_tok, pen_n, cand_plain, cap, order, src_off, src_len, active, step_state,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
@@ -191,6 +191,9 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.fin = take(M * 4);
   p.parent = take(M * 4);
   p.anc = take(M * (T + 1) * 4);   // which slab of its sentence holds position j of row r's history
+  p.pen_tok = take(M * 4);         // diverse beam search: tokens taken at this step by the earlier groups of a sentence
+  p.pen_n = take((size_t)B * 4);
+  p.cand_plain = take(M * k * 4);  // ... and the kept candidates' values without the diversity penalty
   p.cap = take((size_t)B * 4);
   p.order = take((size_t)B * 4);
   p.src_off = take((size_t)(B + 1) * 4);
@@ -259,6 +262,8 @@ struct Ctx {
   int refresh_mode = 1;   // how the next lsq_encode keeps the cache in step with the beams: 0 move rows, 1 slab table
   bool anc_on = false;    // this translation uses the slab table
   bool fuse_ln = true;    // few rows alive: LayerNorm inside the product that consumes it
+  int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
+  float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
   std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
@@ -386,6 +391,25 @@ int launch_step(int B) {
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
+  if (g.groups > 1) {
+    // diverse beam search: the groups of a sentence choose one after the other, each steered away
+    // from the tokens the earlier ones took at this step
+    const int kg = k / g.groups;
+    for (int gi = 0; gi < g.groups; ++gi) {
+      SearchGroups gr{kg, k, gi * kg, at<int32_t>(p.pen_tok), at<int32_t>(p.pen_n), k, g.strength,
+                      at<float>(p.cand_plain), gi + 1 == g.groups ? 1 : 0};
+      TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), B * kg, V, kg, hp.eos,
+                                         0, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s, gr));
+      TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
+                                          at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
+                                          at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, kg, V,
+                                          T, 0, step, hp.eos, anc, s, gr));
+    }
+    if (!anc)
+      TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
+                                             0, step, T, s));
+    return LSQ_OK;
+  }
   TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
                          at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
   // refine gathers the token histories (and the slab table, when the cache is refreshed through
@@ -717,7 +741,15 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     R += n;
   }
   HIPCHK(hipStreamSynchronize(g.stream));   // the staging buffer may still feed an earlier copy
+  const int groups = hp.arch == 0 ? g.groups_next : 1;
+  if (g.beam % groups != 0) return fail(LSQ_E_ARG, "beam %d is not a multiple of %d groups", g.beam, groups);
   const bool anc_on = hp.arch == 0 && g.beam > 1 && g.refresh_mode == 1;
+  if (groups != g.groups || (groups > 1 && g.strength_next != g.strength)) {
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+  }
+  g.groups = groups;
+  g.strength = g.strength_next;
   if (anc_on != g.anc_on) {   // captured steps hold the other mode's kernels and arguments
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
@@ -787,8 +819,8 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
     HIPCHK(launch_gemm(dt, x, g.dec[l].Wkv, g.dec[l].bkv, plain_out(g.ws + p.cross + l * cross_l, 2 * d), (int)R,
                        2 * d, d, 0, s));
   HIPCHK(launch_beam_reset(at<float>(p.score), at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
-                           at<int32_t>(p.active), at<int32_t>(p.step_state), g.anc_on ? at<int32_t>(p.anc) : nullptr, batch,
-                           g.beam, g.max_len, hp.bos,
+                           at<int32_t>(p.active), at<int32_t>(p.step_state), g.anc_on ? at<int32_t>(p.anc) : nullptr,
+                           at<int32_t>(p.pen_n), batch, g.beam, g.beam / g.groups, g.max_len, hp.bos,
                            hp.pad, s));
   g.batch = batch;
   g.rows_enc = (int)R;
@@ -853,6 +885,14 @@ int lsq_set_layernorm_fusion(int on) {
     g.graphs.clear();
   }
   g.fuse_ln = on != 0;
+  return LSQ_OK;
+}
+
+int lsq_set_diversity(int groups, float strength) {
+  if (groups < 1 || groups > LSQ_MAX_BEAM) return fail(LSQ_E_ARG, "groups %d outside [1, %d]", groups, LSQ_MAX_BEAM);
+  if (!(strength >= 0.f)) return fail(LSQ_E_ARG, "diversity strength must be >= 0");
+  g.groups_next = groups;
+  g.strength_next = strength;
   return LSQ_OK;
 }
 

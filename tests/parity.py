@@ -225,3 +225,113 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
         if verbose:
             print(f"step {step + 1}: strict {strict} loose {loose} worst logit error {worst:.2e}", flush=True)
     return dict(steps=n_new, strict=strict, loose=loose, worst=worst, state=st)
+
+
+def lockstep_diverse(lsq, eng, blob, w, groups, strength, max_steps=None):
+    """Diverse beam search, library and oracle side by side.  Per step: logits, then group by group
+    (in the order the groups choose) the kept (beam, token) pairs of every sentence.  The oracle's
+    selection for a group is computed with the token counts of the earlier groups as the LIBRARY
+    chose them (already checked), so one near-tie does not derail the later groups.  Where the
+    oracle's smallest gap between ranking values exceeds MARGIN plus twice the measured deviation of
+    the library's candidate scores the pairs must be identical; otherwise every kept pair's ranking
+    value must reach the oracle's last kept one within that band, in order within the band, and the
+    oracle continues from the library's selection.  Histories, lengths, flags exact; scores within
+    tolerance."""
+    lsq.lsq_set_diversity(groups, strength)
+    m = O.Model(blob)
+    B, k, T, V = w.batch, w.beam, w.max_len, m.V
+    kg, M = k // groups, B * k
+    try:
+        eng.encode(w.src_ids, w.src_lens)
+    finally:
+        lsq.lsq_set_diversity(1, 0.0)                 # the setting was taken by encode; later encodes are plain again
+    _, cross = O.encode(m, w.src_ids, w.src_lens)
+    st = O.DecodeState(m, w.src_lens, k, T, groups)
+    tol = 1e-2 if m.round16 else TOL_F32
+    step_atol = 4e-3 if m.round16 else 2e-5
+    steps = strict = band_n = 0
+    while True:
+        ref_logits = O.decoder_logits_cached(m, st, cross)
+        prev_ref = st.score.reshape(-1).copy()
+        prev_gpu = eng.debug(lsq.DBG.SCORE, (M,))
+        old_fin, old_len = st.finished.copy(), st.len.copy()
+        active_gpu = eng.decode_step()
+        got_logits = eng.debug(lsq.DBG.LOGITS, (M, V))
+        live = ~old_fin
+        if live.any():
+            e = logit_error(got_logits[live], ref_logits[live])
+            assert e <= tol, f"step {steps}: logits differ from the oracle by {e}"
+        g_tokens = eng.debug(lsq.DBG.TOKENS, (M, T + 1), np.int32)
+        g_len = eng.debug(lsq.DBG.LEN, (M,), np.int32)
+        g_fin = eng.debug(lsq.DBG.FINISHED, (M,), np.int32)
+        g_par = eng.debug(lsq.DBG.PARENT, (M,), np.int32)
+        g_score = eng.debug(lsq.DBG.SCORE, (M,))
+        logp = O.log_softmax(np.asarray(ref_logits, m.ctype))
+        tok = np.zeros((B, k), np.int32); par = np.zeros((B, k), np.int32); sc = np.zeros((B, k), m.ctype)
+        for b in range(B):
+            base = b * k
+            if old_fin[base:base + k].all():
+                tok[b], par[b], sc[b] = m.eos, np.arange(k), st.score[b]
+                continue
+            cdev = 0.0
+            for j in range(k):
+                r = base + j
+                if not np.isfinite(prev_ref[r]) or old_fin[r]:
+                    continue
+                c_ref = float(prev_ref[r]) + O.log_softmax(ref_logits[r].astype(np.float64))
+                c_gpu = float(prev_gpu[r]) + O.log_softmax(got_logits[r].astype(np.float64))
+                top = np.argpartition(-c_ref, min(32, V - 1))[:32] if V > 33 else np.arange(V)
+                cdev = max(cdev, float(np.abs(c_gpu[top] - c_ref[top]).max()))
+            band = MARGIN + 2 * cdev
+            counts = np.zeros(V, np.int64)
+            for g in range(groups):
+                rows = slice(base + g * kg, base + (g + 1) * kg)
+                t_o, p_o, s_o, sel_o, margin = O.group_select(m, st, logp, b, g, strength, counts)
+                gp = g_par[rows].astype(np.int64)
+                assert ((gp >= g * kg) & (gp < (g + 1) * kg)).all(), f"step {steps} sentence {b} group {g}: parent outside the group"
+                gt = np.array([m.eos if old_fin[base + gp[i]] else g_tokens[base + g * kg + i, old_len[base + gp[i]] + 1]
+                               for i in range(kg)], np.int64)
+
+                def rank_value(j, v):
+                    r = base + j
+                    if old_fin[r]:
+                        return float(st.score[b, j])
+                    return float(st.score[b, j] + logp[r, v]) - float(strength) * float(counts[v])
+
+                def plain_value(j, v):
+                    r = base + j
+                    return st.score[b, j] if old_fin[r] else m.ctype(st.score[b, j] + logp[r, v])
+                if margin > band:
+                    strict += 1
+                    assert np.array_equal(gp, p_o) and np.array_equal(gt, t_o), \
+                        f"step {steps} sentence {b} group {g}: kept pairs differ although the margin {margin:.2e} exceeds " \
+                        f"{band:.2e}: parents {gp} vs {p_o}, tokens {gt} vs {t_o}"
+                else:
+                    band_n += 1
+                    kept = [(int(gp[i]), int(gt[i])) for i in range(kg)]
+                    assert len(set(kept)) == kg, f"step {steps} sentence {b} group {g}: a pair was kept twice"
+                    ks = np.array([rank_value(j, v) for j, v in kept])
+                    kth = float(sel_o[kg - 1])
+                    if np.isfinite(kth):
+                        assert (ks >= kth - band).all(), f"step {steps} sentence {b} group {g}: kept pair below the band"
+                        assert (np.diff(ks) <= band).all(), f"step {steps} sentence {b} group {g}: kept pairs out of order"
+                    t_o, p_o = gt.astype(np.int32), gp.astype(np.int32)
+                    s_o = np.array([plain_value(j, v) for j, v in kept], m.ctype)
+                tok[b, g * kg:(g + 1) * kg], par[b, g * kg:(g + 1) * kg], sc[b, g * kg:(g + 1) * kg] = t_o, p_o, s_o
+                for i in range(kg):
+                    if not old_fin[base + p_o[i]] and np.isfinite(s_o[i]):
+                        counts[t_o[i]] += 1
+        active_ref = O.beam_advance(m, st, tok, par, sc)
+        assert np.array_equal(g_len, st.len), f"step {steps}: lengths"
+        assert np.array_equal(g_fin != 0, st.finished), f"step {steps}: finished flags"
+        for r in range(M):
+            n = st.len[r]
+            assert np.array_equal(g_tokens[r, : n + 1], st.tokens[r, : n + 1]), f"step {steps} row {r}: tokens"
+        fin = np.isfinite(st.score.reshape(-1))
+        assert np.array_equal(np.isfinite(g_score), fin), f"step {steps}: -inf scores"
+        np.testing.assert_allclose(g_score[fin], st.score.reshape(-1)[fin], rtol=2e-5, atol=1e-4 + step_atol * (steps + 1))
+        assert active_gpu == active_ref, f"step {steps}: active {active_gpu} vs {active_ref}"
+        steps += 1
+        if active_gpu == 0 or (max_steps is not None and steps >= max_steps):
+            break
+    return dict(steps=steps, strict=strict, band=band_n, state=st)
