@@ -53,7 +53,9 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp32: 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread.
+// fp32, plain vector arithmetic: 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread.  Only
+// for shapes the matrix-core kernel further down does not take (K not a multiple of 8, operands
+// not 16-byte aligned).
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                        const float* __restrict__ bias, GemmOut out, int M,
                                                        int N, int K, int act) {
@@ -446,6 +448,76 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, con
 }
 
 // ---------------------------------------------------------------------------------------------
+// fp32 models: the same streaming scheme on the fp32 matrix cores (v_mfma_f32_32x32x2_f32).  A
+// workgroup owns 32 output columns and a block of 32*TM rows (blockIdx.z), its four wavefronts take
+// every fourth 8-wide k-step; a lane loads four consecutive k of its row (16 bytes), lanes 0-31 the
+// first half of the step and lanes 32-63 the second, so MFMA i of a step multiplies k = 8s+i and
+// 8s+4+i -- any pairing of k does, as long as both operands use the same one.  U steps in flight.
+template <int TM, int U>
+__global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                              const float* __restrict__ bias, GemmOut out, int M,
+                                                              int N, int K, int act, int vec_ok) {
+  __shared__ float red[4][TM][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long tp = out.tpos ? *out.tpos : 0;
+  const int n0 = blockIdx.x * 32, mb = blockIdx.z * 32 * TM;
+  const int fr = lane & 31, fk = (lane >> 5) * 4;
+  const int ksteps = K / 8;                      // K % 8 == 0 is checked by the launcher
+  const float* bp = B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  const float* ap[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) ap[i] = A + (size_t)min(mb + i * 32 + fr, M - 1) * K + fk;
+  floatx16 acc[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  for (int ks = wave; ks < ksteps; ks += 4 * U) {
+    floatx4 bf[U], af[U][TM];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(ks + 4 * u, ksteps - 1);
+      bf[u] = *reinterpret_cast<const floatx4*>(bp + (size_t)kc * 8);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[u][i] = *reinterpret_cast<const floatx4*>(ap[i] + (size_t)kc * 8);
+    }
+    // all U steps are requested before the first multiply: without this fence the instruction
+    // scheduler sinks each load next to its use and waits for it there, one at a time
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (ks + 4 * u >= ksteps) bf[u] = floatx4{0.f, 0.f, 0.f, 0.f};   // a step past the end: multiplies by zero
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[u][q], af[u][i][q], acc[i], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) red[wave][i][e][lane] = acc[i][e];
+  __syncthreads();
+  const int vg = wave;
+  const int n = n0 + vg * 8 + (lane >> 5) * 4;
+  if (n >= N) return;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = mb + i * 32 + (lane & 31);
+    if (m >= M) continue;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = vg * 4 + e;
+      v[e] = (red[0][i][r][lane] + red[1][i][r][lane]) + (red[2][i][r][lane] + red[3][i][r][lane]);
+      if (bias) v[e] += bias[min(n + e, N - 1)];
+      v[e] = activate(v[e], act);
+    }
+    store4<float, false>(out, m, n, v, M, N, vec_ok, 0, tp);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Skinny product whose input rows are made on the spot: A = LayerNorm(residual + split-K partial
 // sums of the previous product + its bias), for the very few rows left near the end of a batch
 // (M <= kLnFusedRows), where the step is nothing but launch latencies and a separate LayerNorm
@@ -649,7 +721,27 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K <= 0) return hipErrorInvalidValue;
   if (dtype == DT_F32) {
-    dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);
+    if (K % 8 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0) {
+      int nseg = (N + out.seg_n - 1) / out.seg_n;
+      if (nseg > 3) return hipErrorInvalidValue;
+      int vec_ok = (out.seg_n % 4 == 0);
+      for (int i = 0; i < nseg; ++i)
+        if (out.ld[i] % 4 != 0 || out.tmul[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & 15) != 0) vec_ok = 0;
+      const float* a = (const float*)A;
+      const float* b = (const float*)B;
+      const float* bi = (const float*)bias;
+      const int per_wave = (K / 8 + 3) / 4;
+      if (M <= 32) {
+        dim3 grid((N + 31) / 32, 1, 1), blk(256);
+        if (per_wave <= 8) gemm_f32_stream_kernel<1, 8><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
+        else gemm_f32_stream_kernel<1, 16><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
+      } else {
+        dim3 grid((N + 31) / 32, 1, (M + 63) / 64), blk(256);
+        gemm_f32_stream_kernel<2, 8><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
+      }
+      return hipGetLastError();
+    }
+    dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);   // odd K or unaligned operands: the plain tile kernel
     gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, (const float*)bias, out, M, N, K,
                                          act);
     return hipGetLastError();

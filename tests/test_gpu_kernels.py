@@ -54,17 +54,27 @@ def test_gemm_fp16(env, M, N, K, relu):
     assert (np.abs(C32.cpu().numpy() - (ref_nb := A.astype(np.float64) @ B.astype(np.float64).T)) <= 2e-6 * scale + 1e-7).all()
 
 
-@pytest.mark.parametrize("M,N,K", [(8, 192, 64), (33, 1000, 71), (130, 77, 256), (2, 3000, 64)])
-def test_gemm_fp32(env, M, N, K):
+@pytest.mark.parametrize("M,N,K", [(8, 192, 64), (33, 1000, 71), (130, 77, 256), (2, 3000, 64), (33, 1000, 72),
+                                   (512, 1024, 1024), (100, 1003, 264), (1, 64, 8), (700, 136, 4096), (64, 50, 40),
+                                   (65, 32000, 512)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_gemm_fp32(env, M, N, K, relu):
+    """fp32 models: streamed through the fp32 matrix cores when K is a multiple of 8, the plain tile
+    kernel otherwise; fp32 accumulation in both."""
     lsq, torch = env
     rng = np.random.default_rng(M + N)
     A = rng.standard_normal((M, K)).astype(np.float32)
     B = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
     bias = rng.standard_normal(N).astype(np.float32)
-    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
-    lsq.k_gemm(_dev(torch, A), _dev(torch, B), _dev(torch, bias), C, True)
-    ref = np.maximum(A.astype(np.float64) @ B.astype(np.float64).T + bias, 0)
-    np.testing.assert_allclose(C.cpu().numpy(), ref, rtol=1e-5, atol=1e-5)
+    C = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    lsq.k_gemm(_dev(torch, A), _dev(torch, B), _dev(torch, bias), C, relu)
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + bias
+    if relu:
+        ref = np.maximum(ref, 0)
+    scale = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).T + np.abs(bias)
+    assert (np.abs(C.cpu().numpy() - ref) <= 3e-6 * scale + 1e-6).all()
+    lsq.k_gemm(_dev(torch, A), _dev(torch, B), None, C, False)                       # no bias
+    assert (np.abs(C.cpu().numpy() - A.astype(np.float64) @ B.astype(np.float64).T) <= 3e-6 * scale + 1e-6).all()
 
 
 @pytest.mark.parametrize("M,N,K", [(5, 264, 128), (32, 3072, 768), (200, 520, 72), (600, 3072, 768)])
