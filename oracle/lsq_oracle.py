@@ -639,3 +639,47 @@ def generate(model, prompts, n_new, max_len, trace=None):
             trace.append(dict(logits=logits, picks=picks))
         gpt_advance(model, st, [p[0] for p in picks], [p[1] for p in picks])
     return st.tokens[:, st.P:st.P + n_new].copy(), st.logp.copy(), st
+
+
+# ----------------------------------------------------------------------------
+# sampling decoding for an encoder-decoder model (sec. 3.4: the paper's text-generation runs use a
+# Transformer with top-k 32 / top-p 0.75): one hypothesis per sentence; at every step each
+# unfinished sentence draws its next token with sample_topk from its own logits, the uniform number
+# being that of (step, index of the sentence in the batch); the hypothesis score adds the log of
+# the drawn token's probability among the kept candidates; EOS or the length cap finishes a
+# sentence, which then stays as it is.  The final score is the same length-normalised one as
+# after beam search.
+# ----------------------------------------------------------------------------
+def sample_select(model, st, logits):
+    """The draw of step st.t for every sentence: (token [B,1], parent [B,1] = 0, score [B,1], gaps [B])."""
+    assert st.k == 1
+    token = np.full((st.B, 1), model.eos, np.int32)
+    parent = np.zeros((st.B, 1), np.int32)
+    score = st.score.copy()
+    gaps = np.full(st.B, np.inf)
+    for b in range(st.B):
+        if st.finished[b]:
+            continue
+        tok, lp, gaps[b] = sample_topk(logits[b], model.sample_topk, sample_uniform(model.seed, st.t, b), model.sample_topp)
+        token[b, 0] = tok
+        score[b, 0] = model.ctype(st.score[b, 0] + model.ctype(lp))
+    return token, parent, score, gaps
+
+
+def translate_sample(model, src_ids, src_lens, max_len, max_steps=None, trace=None):
+    """Whole path with sampling instead of beam search; same returns as translate (beam = 1)."""
+    assert model.sample_topk >= 1
+    memory, cross = encode(model, src_ids, src_lens)
+    st = DecodeState(model, src_lens, 1, max_len)
+    steps = 0
+    while True:
+        logits = decoder_logits_cached(model, st, cross)
+        token, parent, score, gaps = sample_select(model, st, logits)
+        active = beam_advance(model, st, token, parent, score)
+        steps += 1
+        if trace is not None:
+            trace.append(dict(logits=logits, token=token, score=score, gaps=gaps, active=active,
+                              finished=st.finished.copy(), len=st.len.copy()))
+        if active == 0 or (max_steps is not None and steps >= max_steps):
+            break
+    return finalize(model, st), st
