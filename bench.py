@@ -90,7 +90,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed decode steps (0 = to the end of the translation)")
     ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the timed ones")
-    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s", "gpt2s_k32p75"])
+    ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s", "gpt2s_k32p75", "base_k32p75"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle sample")
     ap.add_argument("--breakdown", default="", help="write the per-kernel-class table to this JSON file")
@@ -255,7 +255,7 @@ def main() -> int:
         while not gpt:
             active_before = int((~st.finished).reshape(B, k).any(axis=1).sum())
             logits = O.decoder_logits_cached(m, st, cross)
-            sel = O.beam_select(m, st, logits)
+            sel = O.sample_select(m, st, logits) if hp.sample_topk > 0 else O.beam_select(m, st, logits)
             O.beam_advance(m, st, *sel[:3])
             n_steps += 1
             tok += active_before
@@ -271,6 +271,12 @@ def main() -> int:
         metric = f"sampled tokens/sec, top-{hp.sample_topk}{nucleus} sampling (decoder-only, GPT-2-small shape); ms per decode step"
         desc = (f"{args.workload}: decoder-only d_model {hp.d_model}, {hp.n_dec} layers, FFN {hp.d_ffn}, vocab {hp.vocab}, "
                 f"batch {B}, prompt {int(w.src_lens[0])}, {hp.cap_extra} new tokens, top-{hp.sample_topk}{nucleus} sampling")
+    elif hp.sample_topk > 0:
+        nucleus = f", top-p {hp.sample_topp:g}" if hp.sample_topp < 1 else ""
+        metric = f"sampled target tokens/sec, top-{hp.sample_topk}{nucleus} sampling (encoder-decoder Transformer); ms per decode step"
+        desc = (f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, FFN {hp.d_ffn}, vocab {hp.vocab}, "
+                f"batch {B}, one sampled hypothesis per sentence (top-{hp.sample_topk}{nucleus}), "
+                f"src len mean {s_mean:.1f} max {int(w.src_lens.max())}, max_len {T}")
     else:
         metric = "decoded target tokens/sec at beam 4 (Transformer-big fp16); ms per decode step"
         desc = (f"{args.workload}: d_model {hp.d_model}, {hp.n_enc}+{hp.n_dec} layers, "

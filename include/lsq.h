@@ -32,6 +32,13 @@
  * logits under their k-way softmax, cut -- when the blob sets a nucleus mass
  * p < 1 -- to the shortest ranked prefix whose probability reaches p (top-k
  * and top-p sampling, sec. 3.4).
+ * An encoder-decoder blob whose header sets sample_topk >= 1 is decoded with the
+ * same sampling instead of beam search (sec. 3.4: the paper's text-generation
+ * runs sample from a Transformer): beam must be 1, every sentence carries one
+ * hypothesis, an unfinished sentence draws one token per step (counter = step,
+ * index of the sentence in the caller's batch), its score adds the log of the
+ * token's probability among the kept candidates, and EOS or the length cap
+ * finishes it as under beam search.
  */
 #ifndef LSQ_H
 #define LSQ_H

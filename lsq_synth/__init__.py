@@ -226,6 +226,14 @@ def workload(name: str, *, batch: int | None = None, seed: int = INPUT_SEED) -> 
         lens = rng.integers(10, 61, size=b).astype(np.int32)
         return Workload(name, hp, b, 4, int(lens.max()) + hp.cap_extra, lens,
                         _ids(rng, lens, hp.vocab, hp.pad_id))
+    if name == "base_k32p75":
+        # the paper's text-generation runs (sec. 3.4): randomly initialised Transformer-base, random
+        # inputs, sampling decoding with top-k 32 / top-p 0.75; batch 32, one hypothesis per sentence
+        hp = HParams(**BASE, sample_topk=32, sample_topp=0.75)
+        b = batch or 32
+        lens = rng.integers(10, 61, size=b).astype(np.int32)
+        return Workload(name, hp, b, 1, int(lens.max()) + hp.cap_extra, lens,
+                        _ids(rng, lens, hp.vocab, hp.pad_id))
     if name == "big128":
         hp = HParams(**BIG)
         b = batch or 128

@@ -587,15 +587,22 @@ __device__ __forceinline__ unsigned philox4x32_10_first(unsigned c0, unsigned c1
   return c0;
 }
 
+// Encoder-decoder models (fin given): a finished sentence draws nothing and keeps its state; EOS or
+// the sentence's cap finishes one; the uniform number is that of the sentence's place in the
+// caller's batch (order[r]); active[t] counts the sentences still unfinished after the step.
+// Decoder-only models (fin == nullptr): every row draws at every step, n_new tokens in all.
 __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ cand_logit,
                                                     const int32_t* __restrict__ cand_idx,
                                                     int32_t* __restrict__ tokens, int32_t* __restrict__ len,
                                                     float* __restrict__ logp, int32_t* __restrict__ active,
                                                     int32_t* __restrict__ step_state, int rows, int k, float topp,
-                                                    int T1, unsigned seed_lo, unsigned seed_hi, int n_new) {
+                                                    int T1, unsigned seed_lo, unsigned seed_hi, int n_new,
+                                                    int32_t* __restrict__ fin, const int32_t* __restrict__ cap,
+                                                    const int32_t* __restrict__ order, int eos) {
   const int r = blockIdx.x * 64 + threadIdx.x;
   const int pos = step_state[0], t = pos - step_state[2];   // position of the token just fed; step index
-  if (r < rows) {
+  bool unfinished = false;
+  if (r < rows && !(fin && fin[r])) {
     float e[LSQ_MAX_TOPK_], cum[LSQ_MAX_TOPK_];
     const float l0 = cand_logit[(size_t)r * k];
     float run = 0.f;
@@ -612,21 +619,27 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
       while (n < k && !(cum[n - 1] >= thresh)) ++n;
     }
     const float total = cum[n - 1];
-    const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)r, 0u, 0u, seed_lo, seed_hi);
+    const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)(order ? order[r] : r), 0u, 0u, seed_lo, seed_hi);
     const float u = (float)(word >> 8) * 5.9604644775390625e-08f;   // 2^-24
     const float target = __fmul_rn(u, total);
     int j = 0;
     while (j < n - 1 && !(cum[j] > target)) ++j;
-    tokens[(size_t)r * T1 + pos + 1] = cand_idx[(size_t)r * k + j];
+    const int tok = cand_idx[(size_t)r * k + j];
+    tokens[(size_t)r * T1 + pos + 1] = tok;
     len[r] = pos + 1;
     logp[r] += logf(e[j] / total);
+    if (fin) {
+      unfinished = !(tok == eos || pos + 1 >= cap[r]);
+      fin[r] = unfinished ? 0 : 1;
+    }
   }
-  __syncthreads();
+  const int alive = __popcll(__ballot(unfinished));
   if (threadIdx.x == 0) {
+    if (fin && alive) atomicAdd(active + t, alive);
     __threadfence();
     if (atomicAdd(&step_state[1], 1) == (int)gridDim.x - 1) {
       step_state[1] = 0;
-      active[t] = (t + 1 < n_new) ? rows : 0;
+      if (!fin) active[t] = (t + 1 < n_new) ? rows : 0;
       step_state[0] = pos + 1;
     }
   }
@@ -634,12 +647,13 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
 
 hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
                          float* logp, int32_t* active, int32_t* step_state, int rows, int k, float topp, int T,
-                         unsigned long long seed, int n_new, hipStream_t s) {
+                         unsigned long long seed, int n_new, hipStream_t s, int32_t* fin, const int32_t* cap,
+                         const int32_t* order, int eos) {
   if (rows <= 0) return hipSuccess;
-  if (k < 1 || k > LSQ_MAX_TOPK_ || !(topp > 0.f)) return hipErrorInvalidValue;
+  if (k < 1 || k > LSQ_MAX_TOPK_ || !(topp > 0.f) || (fin && !cap)) return hipErrorInvalidValue;
   sample_kernel<<<(rows + 63) / 64, 64, 0, s>>>(cand_logit, cand_idx, tokens, len, logp, active, step_state, rows, k,
                                                 topp, T + 1, (unsigned)(seed & 0xFFFFFFFFull), (unsigned)(seed >> 32),
-                                                n_new);
+                                                n_new, fin, cap, order, eos);
   return hipGetLastError();
 }
 

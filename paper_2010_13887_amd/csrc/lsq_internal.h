@@ -115,10 +115,14 @@ inline SearchGroups one_group() { return SearchGroups{1, 1, 0, nullptr, nullptr,
 hipError_t launch_row_topk(int dtype, const void* logits, const float* score, const int32_t* fin,
                            int M, int V, int k, int eos, int raw, float* out_score, int32_t* out_idx,
                            hipStream_t s, const SearchGroups& groups = one_group());
-// topp < 1: only the shortest prefix of the ranked candidates whose k-way softmax mass reaches topp is drawn from
+// topp < 1: only the shortest prefix of the ranked candidates whose k-way softmax mass reaches topp is drawn from.
+// fin != null (encoder-decoder models; cap [rows] then required): finished rows draw nothing, EOS or the cap
+// finishes a row, the uniform number is that of row order[r] (r if order is null) and active[step] counts the
+// rows left unfinished; fin == null: every row draws, active[step] = rows until n_new tokens are out.
 hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32_t* tokens, int32_t* len,
                          float* logp, int32_t* active, int32_t* step_state, int rows, int k, float topp, int T,
-                         unsigned long long seed, int n_new, hipStream_t s);
+                         unsigned long long seed, int n_new, hipStream_t s, int32_t* fin = nullptr,
+                         const int32_t* cap = nullptr, const int32_t* order = nullptr, int eos = -1);
 // step = t_base + (step_state ? step_state[0] : 0).  `active` points at the counter array indexed
 // by step.  With step_state != null the last workgroup to finish advances step_state[0]
 // (step_state[1] is its arrival counter and must be zero at launch).  anc != null: the slab table

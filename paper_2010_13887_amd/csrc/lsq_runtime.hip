@@ -115,6 +115,8 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
   if (deconly && (hp->n_enc != 0 || hp->sample_topk < 1 || hp->sample_topk > LSQ_MAX_SAMPLE_TOPK || hp->max_pos < 1 ||
                   hp->d > 4096))
     return fail(LSQ_E_BLOB, "decoder-only blob: n_enc must be 0, sample_topk in [1, %d], max_pos >= 1, d <= 4096", LSQ_MAX_SAMPLE_TOPK);
+  if (encdec && (hp->sample_topk < 0 || hp->sample_topk > LSQ_MAX_SAMPLE_TOPK))
+    return fail(LSQ_E_BLOB, "sample_topk outside [0, %d] (0: beam search)", LSQ_MAX_SAMPLE_TOPK);
   if ((encdec && hp->n_enc < 1) || hp->n_dec < 1 || hp->n_enc > 64 || hp->n_dec > 64 || hp->d < 8 || hp->H < 1 ||
       hp->F < 8 || hp->V < 4 || hp->d % hp->H != 0 || hp->d > 16384 || hp->F > 262144 || hp->max_pos < 0 ||
       hp->max_pos > (1 << 20) || hp->cap_extra > (1 << 20))
@@ -200,7 +202,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.src_len = take((size_t)B * 4);
   p.active = take((size_t)(T + 1) * 4);
   p.step_state = take(4 * 4);   // [0] position counter, [1] arrival counter, [2] position of step 0
-  const size_t kk = std::max(k, hp.arch == 1 ? hp.sample_topk : 0);   // survivors per row
+  const size_t kk = std::max(k, hp.sample_topk);   // survivors per row
   p.cand_score = take(M * kk * 4);
   p.cand_idx = take(M * kk * 4);
   p.out_ids = take(M * T * 4);
@@ -305,7 +307,7 @@ int check_limits(int max_batch, int beam, int max_len, const HParams& hp) {
   if (beam < 1 || beam > LSQ_MAX_BEAM) return fail(LSQ_E_ARG, "beam %d outside [1, %d]", beam, LSQ_MAX_BEAM);
   if (beam > hp.V) return fail(LSQ_E_ARG, "beam wider than the vocabulary");
   if (max_len < 1 || max_len > 4096) return fail(LSQ_E_ARG, "max_len %d outside [1, 4096]", max_len);
-  if (hp.arch == 1 && beam != 1) return fail(LSQ_E_ARG, "a decoder-only (sampling) model runs with beam 1");
+  if (hp.sample_topk > 0 && beam != 1) return fail(LSQ_E_ARG, "a sampling model (sample_topk > 0) runs with beam 1");
   if (hp.arch == 1 && max_len > hp.max_pos) return fail(LSQ_E_ARG, "max_len %d exceeds the model's %d positions", max_len, hp.max_pos);
   return LSQ_OK;
 }
@@ -391,6 +393,16 @@ int launch_step(int B) {
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
+  if (hp.sample_topk > 0) {
+    // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
+    TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, hp.sample_topk, hp.eos, 1,
+                                       at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+    TIMED(PC_REFINE, launch_sample(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<int32_t>(p.tokens),
+                                   at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M,
+                                   hp.sample_topk, hp.topp, T, (unsigned long long)hp.seed, 0, s, at<int32_t>(p.fin),
+                                   at<int32_t>(p.cap), at<int32_t>(p.order), hp.eos));
+    return LSQ_OK;
+  }
   if (g.groups > 1) {
     // diverse beam search: the groups of a sentence choose one after the other, each steered away
     // from the tokens the earlier ones took at this step
@@ -951,8 +963,8 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes) {
     case LSQ_DBG_LEN: src = g.ws + p.len; n = M; break;
     case LSQ_DBG_FINISHED: src = g.ws + p.fin; n = M; break;
     case LSQ_DBG_PARENT: src = g.ws + p.parent; n = M; break;
-    case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
-    case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * (hp.arch == 1 ? hp.sample_topk : g.beam); break;
+    case LSQ_DBG_CAND_SCORE: src = g.ws + p.cand_score; n = M * (hp.sample_topk > 0 ? hp.sample_topk : g.beam); break;
+    case LSQ_DBG_CAND_IDX: src = g.ws + p.cand_idx; n = M * (hp.sample_topk > 0 ? hp.sample_topk : g.beam); break;
     case LSQ_DBG_HIDDEN: src = g.ws + (g.hidden_in_alt ? p.d_x2 : p.d_x); n = M * d; is_float_data = true; break;
     case LSQ_DBG_MEMORY:
       if (g.t != 0) return fail(LSQ_E_STATE, "encoder output is overwritten by the first decode step");

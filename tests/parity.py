@@ -227,6 +227,74 @@ def lockstep_gpt(lsq, eng, blob, w, n_steps=None, verbose=False):
     return dict(steps=n_new, strict=strict, loose=loose, worst=worst, state=st)
 
 
+def lockstep_sample(lsq, eng, blob, w, max_steps=None):
+    """Encoder-decoder model with sampling decoding, library and oracle side by side: as
+    lockstep_gpt for the draws (candidates and token exact on the library's own logits; against the
+    oracle's logits identical wherever the decision is clear, else among its candidates and the
+    oracle follows), plus the bookkeeping of translation: a finished sentence draws nothing, EOS or
+    the cap finishes one, lengths and flags exact, the count of unfinished sentences.
+    For float32 models the oracle runs in float64: with the large test weights numpy's float32
+    forward pass is itself up to 1e-4 away from the float64 one, ten times further than the library."""
+    m = O.Model(blob)
+    if not m.round16:
+        m = O.Model(blob, ctype=np.float64)
+    B, T, V, k, topp = w.batch, w.max_len, m.V, m.sample_topk, m.sample_topp
+    eng.encode(w.src_ids, w.src_lens)
+    _, cross = O.encode(m, w.src_ids, w.src_lens)
+    st = O.DecodeState(m, w.src_lens, 1, T)
+    tol = 1e-2 if m.round16 else TOL_F32
+    worst = 0.0
+    steps = strict = loose = 0
+    while True:
+        ref = O.decoder_logits_cached(m, st, cross)
+        old_fin = st.finished.copy()
+        active = eng.decode_step()
+        got = eng.debug(lsq.DBG.LOGITS, (B, V))
+        live = ~old_fin
+        if live.any():
+            e = logit_error(got[live], ref[live])
+            worst = max(worst, e)
+            assert e <= tol, f"step {steps}: logits differ from the oracle by {e}"
+        g_tokens = eng.debug(lsq.DBG.TOKENS, (B, T + 1), np.int32)
+        g_ci = eng.debug(lsq.DBG.CAND_IDX, (B, k), np.int32)
+        g_cl = eng.debug(lsq.DBG.CAND_SCORE, (B, k))
+        token = np.full((B, 1), m.eos, np.int32)
+        score = st.score.copy()
+        for b in range(B):
+            if old_fin[b]:
+                continue
+            u = O.sample_uniform(m.seed, st.t, b)
+            g_tok = int(g_tokens[b, st.len[b] + 1])
+            mine = np.lexsort((np.arange(V), -got[b]))[:k]
+            assert np.array_equal(g_ci[b], mine) and np.array_equal(g_cl[b], got[b][mine]), f"step {steps} sentence {b}: candidates"
+            tok_own, lp_own, gap_own = O.sample_topk(got[b], k, u, topp)
+            assert g_tok == tok_own or gap_own < 1e-5, f"step {steps} sentence {b}: token {g_tok}, expected {tok_own}"
+            tok, lp, gap = O.sample_topk(ref[b], k, u, topp)
+            dev = float(np.abs(got[b] - ref[b]).max())
+            if gap > 4 * dev + 1e-5:
+                strict += 1
+                assert g_tok == tok, f"step {steps} sentence {b}: sampled {g_tok}, oracle {tok} (gap {gap:.2e})"
+            else:
+                loose += 1
+                assert g_tok in np.lexsort((np.arange(V), -ref[b]))[:k + 1], f"step {steps} sentence {b}: not a candidate"
+                tok, lp = g_tok, lp_own
+            token[b, 0] = tok
+            score[b, 0] = m.ctype(st.score[b, 0] + m.ctype(lp))
+        active_ref = O.beam_advance(m, st, token, np.zeros((B, 1), np.int32), score)
+        steps += 1
+        assert active == active_ref, f"step {steps}: active {active}, oracle {active_ref}"
+        g_tokens = eng.debug(lsq.DBG.TOKENS, (B, T + 1), np.int32)
+        assert np.array_equal(eng.debug(lsq.DBG.LEN, (B,), np.int32), st.len), f"step {steps}: lengths"
+        assert np.array_equal(eng.debug(lsq.DBG.FINISHED, (B,), np.int32) != 0, st.finished), f"step {steps}: finished flags"
+        for b in range(B):
+            assert np.array_equal(g_tokens[b, :st.len[b] + 1], st.tokens[b, :st.len[b] + 1]), f"step {steps}: history of sentence {b}"
+        np.testing.assert_allclose(eng.debug(lsq.DBG.SCORE, (B,)), st.score[:, 0], rtol=2e-5,
+                                   atol=1e-4 + (4e-3 if m.round16 else 2e-5) * steps)
+        if active_ref == 0 or (max_steps is not None and steps >= max_steps):
+            break
+    return dict(steps=steps, strict=strict, loose=loose, worst=worst, state=st)
+
+
 def lockstep_diverse(lsq, eng, blob, w, groups, strength, max_steps=None):
     """Diverse beam search, library and oracle side by side.  Per step: logits, then group by group
     (in the order the groups choose) the kept (beam, token) pairs of every sentence.  The oracle's
