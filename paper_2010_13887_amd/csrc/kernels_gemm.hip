@@ -120,15 +120,16 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // to give every XCD a contiguous run of tiles, m fastest: the tiles that share a weight tile then
 // share an L2.
 template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT>
-__global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
+__global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
                                                        const half_t* __restrict__ bias, GemmOut out, int M,
                                                        int N, int K, int act, int vec_ok) {
   constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int VPR = BK / 8;   // 16-byte vectors per tile row
-  static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
-  constexpr int AV = BM * VPR / 256, BV = BN * VPR / 256;   // vectors per thread
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);   // threads: one wavefront per wave tile
+  static_assert(NT == 256 || NT == 512, "four or eight wavefronts");
+  constexpr int AV = BM * VPR / NT, BV = BN * VPR / NT;   // vectors per thread
   static_assert(AV >= 1 && BV >= 1, "tile too small");
   // LDS comes from the launch (dynamic), so that tiles above the 64 KB static limit can be used
   extern __shared__ __attribute__((aligned(16))) half_t lds_tiles[];
@@ -150,14 +151,14 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
   auto gload = [&](half8_t(&a)[AV], half8_t(&b)[BV], int k0) {
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
       int m = min(m0 + row, M - 1);
       int kk = KTAIL ? min(k0 + kc, K - 8) : k0 + kc;
       a[i] = *reinterpret_cast<const half8_t*>(A + (size_t)m * K + kk);
     }
 #pragma unroll
     for (int i = 0; i < BV; ++i) {
-      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
       int n = min(n0 + row, N - 1);
       int kk = KTAIL ? min(k0 + kc, K - 8) : k0 + kc;
       b[i] = *reinterpret_cast<const half8_t*>(B + (size_t)n * K + kk);
@@ -167,12 +168,12 @@ __global__ void __launch_bounds__(256) gemm_f16_kernel(const half_t* __restrict_
     const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
       *reinterpret_cast<half8_t*>(&As[buf][row * LDK + kc]) = (KTAIL && k0 + kc >= K) ? zero : a[i];
     }
 #pragma unroll
     for (int i = 0; i < BV; ++i) {
-      int v = tid + i * 256, row = v / VPR, kc = (v % VPR) * 8;
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
       *reinterpret_cast<half8_t*>(&Bs[buf][row * LDK + kc]) = (KTAIL && k0 + kc >= K) ? zero : b[i];
     }
   };
@@ -657,7 +658,7 @@ constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * (BK + 8) * si
 
 // Launch with the tile's LDS size; sizes above the default 64 KB limit are opted into once per kernel.
 template <typename Kern>
-static void launch_tiles(Kern kern, size_t lds, dim3 grid, hipStream_t s, const half_t* A, const half_t* B,
+static void launch_tiles(Kern kern, size_t lds, dim3 grid, int threads, hipStream_t s, const half_t* A, const half_t* B,
                          const half_t* bias, const GemmOut& out, int M, int N, int K, int act, int vec_ok) {
   if (lds > 64 * 1024) {
     static bool raised = false;   // one flag per instantiation of this template, i.e. per kernel
@@ -666,7 +667,7 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, hipStream_t s, const 
       raised = true;
     }
   }
-  kern<<<grid, dim3(256), lds, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
+  kern<<<grid, dim3(threads), lds, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int D>
@@ -674,25 +675,34 @@ static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const 
                     int K, int act, int vec_ok, hipStream_t s) {
   dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM));
   constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
   const bool tail = (K % BK) != 0;
   if (out.f32_out) {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
   } else {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, s, A, B, bias, out, M, N, K, act, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
   }
 }
 
 // How many ways the k-range of an [M,N,K] product is split when its consumer can add partial
 // sums (the residual + LayerNorm kernel).  More slabs put more workgroups (and more wavefronts per
-// CU) on a product whose output has too few tiles to fill 256 CUs.
+// CU) on a product whose output has too few tiles to fill 256 CUs, but every slab is M*N floats
+// written and read again, and a workgroup's fixed cost is only worth paying for four k-tiles or
+// more.  Tiled kernel: the most slabs that keep the launch within one workgroup per CU (measured
+// at d = 512 and 1024, K = d and 4d, 65..512 rows: beyond 256 workgroups every step up is slower).
+// Skinny kernel (32 columns per workgroup): up to 512 workgroups.
 int gemm_partial_splits(int dtype, int M, int N, int K) {
   if (dtype != DT_F16 || K % 64 != 0) return 1;
   const int nk = K / 64;
-  const long tiles = M <= kSkinnyRows ? (N + 31) / 32 : (long)((M + 63) / 64) * ((N + 63) / 64);
+  const bool skinny = M <= kSkinnyRows;
+  const long tiles = skinny ? (N + 31) / 32 : (long)((M + 63) / 64) * ((N + 63) / 64);
+  const long most = skinny ? 512 : 256;
+  const int least = skinny ? 2 : 4;   // k-tiles per workgroup
   int S = 1;
-  while (S < 8 && nk % (S * 2) == 0 && nk / (S * 2) >= 2 && tiles * S * 2 <= 1024) S *= 2;
+  const int cap = skinny ? 4 : 8;
+  while (S < cap && nk % (S * 2) == 0 && nk / (S * 2) >= least && tiles * S * 2 <= most) S *= 2;
   return S;
 }
 
@@ -763,6 +773,10 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if (tiles128 >= 256)
     run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);   // 72 KB of LDS, two workgroups per CU
+  else if ((long)((M + 63) / 64) * ((N + 63) / 64) > 256)
+    // more 64x64 tiles than CUs: eight wavefronts on a 64x128 tile move fewer operand bytes per FLOP
+    // into the CU and keep its LDS pipe as busy as two four-wave workgroups would
+    run_f16<64, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else
     run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   return hipGetLastError();

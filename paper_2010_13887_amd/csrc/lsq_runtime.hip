@@ -81,7 +81,8 @@ hipError_t prof_mark(hipStream_t s, int c, bool start) {
   } while (0)
 
 constexpr size_t kAlign = 256;
-constexpr size_t kMaxSplits = 4;
+constexpr size_t kMaxSplits = 8;        // fp32 partial-sum slabs a split-K product may leave
+constexpr int kMaxSplitsFusedLn = 4;    // ... when the consuming product adds them itself
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct HParams {
@@ -354,7 +355,7 @@ int launch_step(int B) {
   auto close_sublayer = [&](int cls, const void* in, const void* W, const void* bias, const void* gain, const void* shift,
                             int K) -> int {
     if (!fuse) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, (float*)tmp, M, d, K, kMaxSplits, s);
-    const int S = std::min(gemm_partial_splits(dt, M, d, K), (int)kMaxSplits);
+    const int S = std::min(gemm_partial_splits(dt, M, d, K), kMaxSplitsFusedLn);
     TIMED(cls, launch_gemm_partials(dt, in, W, (float*)tmp, M, d, K, S, s));
     pending = {true, S, bias, gain, shift};
     return LSQ_OK;
