@@ -701,7 +701,7 @@ int gemm_partial_splits(int dtype, int M, int N, int K) {
   const long most = skinny ? 512 : 256;
   const int least = skinny ? 2 : 4;   // k-tiles per workgroup
   int S = 1;
-  const int cap = skinny ? 4 : 8;
+  const int cap = 8;
   while (S < cap && nk % (S * 2) == 0 && nk / (S * 2) >= least && tiles * S * 2 <= most) S *= 2;
   return S;
 }
