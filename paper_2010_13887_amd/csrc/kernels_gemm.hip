@@ -771,8 +771,11 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     else run_skinny<false, half_t>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
-  else if (tiles128 >= 256)
-    run_f16<128, 128, 64, 64, 64, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);   // 72 KB of LDS, two workgroups per CU
+  else if (tiles128 >= 200)
+    // 128x128 tiles (72 KB of LDS, two workgroups per CU), eight wavefronts of 64x32 each: measured
+    // ahead of four wavefronts of 64x64 on every shape that has this many tiles (vocabulary
+    // product from 65 rows up, encoder products), behind the smaller tiles below that
+    run_f16<128, 128, 64, 64, 32, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if ((long)((M + 63) / 64) * ((N + 63) / 64) > 256)
     // more 64x64 tiles than CUs: eight wavefronts on a 64x128 tile move fewer operand bytes per FLOP
     // into the CU and keep its LDS pipe as busy as two four-wave workgroups would
