@@ -119,15 +119,18 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so the id is remapped
 // to give every XCD a contiguous run of tiles, m fastest: the tiles that share a weight tile then
 // share an L2.
-template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT>
-__global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
+template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT, int KG = 1>
+__global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
                                                        const half_t* __restrict__ bias, GemmOut out, int M,
                                                        int N, int K, int act, int vec_ok) {
   constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int VPR = BK / 8;   // 16-byte vectors per tile row
-  constexpr int NT = 64 * (BM / WM) * (BN / WN);   // threads: one wavefront per wave tile
+  // KG = 2: two wavefronts per wave tile, each multiplying one half of every k-tile (all of them load
+  // the tile); their accumulators are added through LDS at the end
+  constexpr int NT = 64 * (BM / WM) * (BN / WN) * KG;   // threads
+  static_assert(KG == 1 || (KG == 2 && WM == 32 && WN == 32 && BK % 32 == 0), "k-groups: 32x32 wave tiles only");
   static_assert(NT == 256 || NT == 512, "four or eight wavefronts");
   constexpr int AV = BM * VPR / NT, BV = BN * VPR / NT;   // vectors per thread
   static_assert(AV >= 1 && BV >= 1, "tile too small");
@@ -136,7 +139,9 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(co
   half_t(*As)[BM * LDK] = reinterpret_cast<half_t(*)[BM * LDK]>(lds_tiles);
   half_t(*Bs)[BN * LDK] = reinterpret_cast<half_t(*)[BN * LDK]>(lds_tiles + 2 * BM * LDK);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  constexpr int TILE_WAVES = (BM / WM) * (BN / WN);
+  const int wave = (tid >> 6) % TILE_WAVES, kgrp = (tid >> 6) / TILE_WAVES;   // wave tile, k-group
   const long tp = out.tpos ? *out.tpos : 0;
   const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN, total = mt * nt;
   int id = blockIdx.x;
@@ -220,7 +225,8 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(co
     B += (size_t)blockIdx.y * nk * BK;
   }
   static_assert(D % 2 == 0, "tile kt always uses LDS buffer kt & 1 = stage & 1");
-  constexpr int KS = BK / 16;                        // MFMA k-steps per tile
+  constexpr int KS = BK / 16 / KG;                   // MFMA k-steps per tile and k-group
+  const int kg0 = kgrp * (BK / KG);                  // this k-group's first column of a tile
   constexpr bool kSingle = (TM * TN == 1);           // one output block per wave: use two accumulators
   floatx16 acc2;                                     // so consecutive MFMAs do not wait on each other
   if constexpr (kSingle)
@@ -232,8 +238,8 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(co
       half8_t af[KS], bf[KS];
 #pragma unroll
       for (int i = 0; i < KS; ++i) {
-        af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + fr) * LDK + i * 16 + fk]);
-        bf[i] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + fr) * LDK + i * 16 + fk]);
+        af[i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + fr) * LDK + kg0 + i * 16 + fk]);
+        bf[i] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + fr) * LDK + kg0 + i * 16 + fk]);
       }
 #pragma unroll
       for (int i = 0; i < KS; ++i) {
@@ -303,6 +309,18 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_kernel(co
   if constexpr (kSingle)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[0][0][e] += acc2[e];
+  if constexpr (KG == 2) {
+    // the last loop iteration ended with a barrier: the tile buffers are free
+    float* red = reinterpret_cast<float*>(lds_tiles);   // [TILE_WAVES][16][64]
+    if (kgrp == 1) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red[(wave * 16 + e) * 64 + lane] = acc[0][0][e];
+    }
+    __syncthreads();
+    if (kgrp == 1) return;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[0][0][e] += red[(wave * 16 + e) * 64 + lane];
+  }
 
   // epilogue: lane owns m = .. + (lane & 31) and, per group vg, n = .. + vg*8 + (lane>>5)*4 + 0..3
 #pragma unroll
@@ -670,19 +688,19 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, int threads, hipStrea
   kern<<<grid, dim3(threads), lds, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int D>
+template <int BM, int BN, int BK, int WM, int WN, int D, int KG = 1>
 static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
                     int K, int act, int vec_ok, hipStream_t s) {
   dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM));
   constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
-  constexpr int NT = 64 * (BM / WM) * (BN / WN);
+  constexpr int NT = 64 * (BM / WM) * (BN / WN) * KG;
   const bool tail = (K % BK) != 0;
   if (out.f32_out) {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, float, KG>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, float, KG>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
   } else {
-    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
-    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    if (tail) launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, true, false, half_t, KG>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
+    else launch_tiles(gemm_f16_kernel<BM, BN, BK, WM, WN, D, false, false, half_t, KG>, lds, grid, NT, s, A, B, bias, out, M, N, K, act, vec_ok);
   }
 }
 
@@ -781,7 +799,9 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     // into the CU and keep its LDS pipe as busy as two four-wave workgroups would
     run_f16<64, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else
-    run_f16<64, 64, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
+    // at most one 64x64 tile per CU: a second set of four wavefronts multiplies the other half of
+    // every k-tile (0.5-0.7 us off a 1024-deep product)
+    run_f16<64, 64, 64, 32, 32, 4, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);
   return hipGetLastError();
 }
 
