@@ -235,7 +235,9 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
 /* Cross-attention: the `beam` rows of sentence b attend over that sentence's
  * src_len[b] encoder positions, kv packed as [sum(src_len), 2d] = [K | V] with
  * sentence b starting at row src_off[b] (both int32, device).  max_src_len: a
- * host-side upper bound of src_len[] (sizes an LDS buffer; at most 3840). */
+ * the longest of src_len[] as the host knows it (or an upper bound), at least
+ * 1; it only picks the launch geometry: one wavefront per (sentence, head), or
+ * four when few sentences are left and the longest one has many keys. */
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off,
                           const int32_t* src_len, void* out, int batch, int beam, int heads, int d,
                           int max_src_len, void* stream);

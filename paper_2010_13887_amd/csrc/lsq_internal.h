@@ -85,7 +85,9 @@ hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const floa
 hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
                                  int rows, int H, int d, int T, int nkeys_base, const int32_t* tp,
                                  const int32_t* anc, int beam, int anc_ld, hipStream_t s);
-// smax: an upper bound of len[] known to the host (sizes the LDS score buffer)
+// smax: the longest of len[] as known to the host, or an upper bound of it; it only picks the launch geometry:
+// cross_attention_splits(batch * H, smax) says whether a (sentence, head) gets four wavefronts instead of one
+bool cross_attention_splits(int units, int smax);
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
                                   const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
                                   hipStream_t s);
@@ -165,6 +167,13 @@ __device__ __forceinline__ float wave_max(float v) {
 
 template <typename T> struct Vec8;
 template <> struct Vec8<half_t> {
+  // the 16 bytes as they are in memory, for data that waits in registers before it is used
+  using raw_t = half8_t;
+  __device__ static __forceinline__ raw_t load_raw(const half_t* p) { return *reinterpret_cast<const half8_t*>(p); }
+  __device__ static __forceinline__ void unpack(const raw_t& h, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+  }
   __device__ static __forceinline__ void load(const half_t* p, float (&f)[8]) {
     half8_t h = *reinterpret_cast<const half8_t*>(p);
 #pragma unroll
@@ -178,6 +187,14 @@ template <> struct Vec8<half_t> {
   }
 };
 template <> struct Vec8<float> {
+  struct raw_t { floatx4 a, b; };
+  __device__ static __forceinline__ raw_t load_raw(const float* p) {
+    return {*reinterpret_cast<const floatx4*>(p), *reinterpret_cast<const floatx4*>(p + 4)};
+  }
+  __device__ static __forceinline__ void unpack(const raw_t& r, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[i] = r.a[i]; f[4 + i] = r.b[i]; }
+  }
   __device__ static __forceinline__ void load(const float* p, float (&f)[8]) {
     floatx4 a = *reinterpret_cast<const floatx4*>(p);
     floatx4 b = *reinterpret_cast<const floatx4*>(p + 4);

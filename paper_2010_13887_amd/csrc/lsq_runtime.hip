@@ -259,6 +259,7 @@ struct Ctx {
   Plan plan{};
   int max_batch = 0, beam = 0, max_len = 0;
   int batch = 0, rows_enc = 0, t = 0;
+  int src_longest = 1;         // longest source sentence of this translation
   bool done = false;
   std::vector<int> order;      // internal (sorted) sentence index -> caller's index
   bool use_graphs = true;
@@ -268,7 +269,7 @@ struct Ctx {
   int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
-  std::map<int, hipGraphExec_t> graphs;   // live sentences -> captured decode step
+  std::map<int, hipGraphExec_t> graphs;   // (live sentences, cross-attention geometry) -> captured decode step
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
   std::vector<GptLayer> gpt;
@@ -386,7 +387,7 @@ int launch_step(int B) {
     if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d)) return rc;
     if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
     TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
-                                  at<int32_t>(p.src_len), ctx, B, k, H, d, g.max_len, s));
+                                  at<int32_t>(p.src_len), ctx, B, k, H, d, g.src_longest, s));
     if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d)) return rc;
     if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
     if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F)) return rc;
@@ -494,7 +495,10 @@ int enqueue_step() {
     g.t += 1;
     return LSQ_OK;
   }
-  auto it = g.graphs.find(B);
+  // the captured launches depend on the number of live sentences and, through the geometry of
+  // cross-attention, on the longest source sentence
+  const int key = B * 2 + (g.hp.arch == 0 && cross_attention_splits(B * g.hp.H, g.src_longest) ? 1 : 0);
+  auto it = g.graphs.find(key);
   if (it == g.graphs.end()) {
     hipGraph_t graph = nullptr;
     HIPCHK(hipStreamBeginCapture(g.stream, hipStreamCaptureModeThreadLocal));
@@ -506,7 +510,7 @@ int enqueue_step() {
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
     if (e != hipSuccess) return fail(LSQ_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
-    it = g.graphs.emplace(B, exec).first;
+    it = g.graphs.emplace(key, exec).first;
   }
   HIPCHK(hipGraphLaunch(it->second, g.stream));
   g.t += 1;
@@ -837,6 +841,7 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
                            hp.pad, s));
   g.batch = batch;
   g.rows_enc = (int)R;
+  g.src_longest = *std::max_element(src_lens, src_lens + batch);
   g.t = 0;
   g.done = false;
   g.state = 3;

@@ -218,7 +218,9 @@ def test_encoder_attention(env, lens, H, dh, causal, half):
 
 
 @pytest.mark.parametrize("lens,beam,H,dh", [([5, 8], 4, 4, 16), ([1, 60, 17, 33], 4, 8, 64), ([9, 2, 31], 3, 2, 32),
-                                            ([4, 4, 128, 7, 1], 8, 16, 64), ([3], 1, 2, 128), ([6, 11], 5, 4, 16)])
+                                            ([4, 4, 128, 7, 1], 8, 16, 64), ([3], 1, 2, 128), ([6, 11], 5, 4, 16),
+                                            ([300, 2, 257], 4, 2, 64), ([256, 40], 2, 4, 32), ([33, 64, 65], 4, 2, 128),
+                                            ([700], 3, 2, 16)])
 @pytest.mark.parametrize("half", [False, True])
 def test_cross_attention(env, lens, beam, H, dh, half):
     lsq, torch = env
