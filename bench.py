@@ -97,7 +97,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (sentences are independent; sharding the batch over "
-              "GPUs needs no collective and is described in DESIGN.md). Use --gpus 1.", file=sys.stderr)
+              "GPUs needs no collective). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
