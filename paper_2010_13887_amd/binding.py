@@ -32,6 +32,10 @@ def load_library() -> C.CDLL:
     if not os.path.exists(path):
         raise LsqError(f"{path} is missing: build it with `python -m paper_2010_13887_amd.build` "
                        "(or __graft_entry__.build()); there is no fallback path")
+    # PyTorch ships its own HIP runtime; whichever copy is loaded first serves the whole process, and
+    # the workspace tensor and this library must talk to the same one (loaded the other way round,
+    # the library's first runtime call reports that there is no device)
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, sz, i32, f32 = C.c_void_p, C.c_size_t, C.c_int, C.c_float
     sig = {
