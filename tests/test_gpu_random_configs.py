@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import lsq_synth as S
-from tests.parity import lockstep, lockstep_diverse, lockstep_sample
+from tests.parity import lockstep, lockstep_diverse, lockstep_gpt, lockstep_sample
 
 pytestmark = pytest.mark.gpu
 
@@ -70,3 +70,38 @@ def test_random_configuration_matches_oracle(lsq, seed):
         ids, lens, _ = eng.get_beams()
         assert ((lens >= 0) & (lens <= caps[:, None])).all()
         assert ((ids >= 0) & (ids < w.hp.vocab)).all()
+
+
+def draw_decoder_only(seed):
+    rng = np.random.default_rng(5000 + seed)
+    dh = int(rng.choice([16, 32, 64, 128]))
+    H = int(rng.choice([1, 2, 3, 4, 6]))
+    if dh * H > 768:
+        H = 768 // dh
+    d = dh * H
+    F = int(rng.choice([24, 64, 136, 264, 520]))
+    V = int(rng.choice([37, 64, 301, 1003, 2048, 9001]))
+    dtype = int(rng.integers(0, 2))
+    n_dec = int(rng.integers(1, 5))
+    batch = int(rng.integers(1, 12))
+    P = int(rng.integers(1, 20))
+    n_new = int(rng.integers(1, 12))
+    k = int(min(V, rng.choice([1, 2, 5, 8, 16, 32])))
+    topp = float(rng.choice([1.0, 0.9, 0.5]))
+    hp = S.HParams(arch=1, n_enc=0, n_dec=n_dec, d_model=d, n_heads=H, d_ffn=F, vocab=V, max_pos=64, act=1, norm=1,
+                   dtype=dtype, sample_topk=k, sample_topp=topp, cap_extra=n_new, seed=seed)
+    std = min(0.08, 0.9 / d ** 0.5) if dtype else min(0.3, 3.4 / d ** 0.5)
+    w = S.custom(hp, [P] * batch, beam=1, max_len=P + n_new + int(rng.integers(0, 3)), std=std, seed=seed)
+    return w, int(rng.integers(0, 3))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_decoder_only_configuration_matches_oracle(lsq, seed):
+    w, spare = draw_decoder_only(seed)
+    blob = w.blob(ln_jitter=0.1)
+    with lsq.Engine(blob, w.batch + spare, 1, w.max_len) as eng:
+        res = lockstep_gpt(lsq, eng, blob, w)
+        assert res["steps"] == w.hp.cap_extra
+        ids, lens, _ = eng.get_beams()
+        assert (lens[:, 0] == w.hp.cap_extra).all()
+        assert np.array_equal(ids[:, 0, :w.hp.cap_extra], res["state"].tokens[:, int(w.src_lens[0]):int(w.src_lens[0]) + w.hp.cap_extra])
