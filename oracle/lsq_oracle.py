@@ -14,7 +14,9 @@ sec. 3.1) and textbook beam search with a full sort.  Plain numpy, one
 operation per line, no blocking or fusion; ``@`` (matmul), ``einsum`` and
 ``lexsort`` are the library primitives used as steps.
 
-Precision.  Arithmetic is IEEE fp32 (``ctype``; fp64 can be asked for).  With
+Precision.  The arithmetic type is ``ctype``: the pins and the parity runs of fp32
+models use fp64; parity runs of fp16 models use fp32 between the storage points
+(the type of the accumulators the rounding to fp16 is applied to).  With
 ``storage='blob'`` and an fp16 blob, every tensor the model *stores* between
 operations (embedding sum, the Q/K/V and FFN-hidden projections after their
 bias/activation, attention context, LayerNorm output, K/V cache entries) is
