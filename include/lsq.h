@@ -204,8 +204,19 @@ int lsq_debug_read(int what, void* host_dst, size_t bytes);
 #define LSQ_GEMM_RELU 1
 #define LSQ_GEMM_F32_OUT 2
 #define LSQ_GEMM_GELU 4    /* tanh-GELU instead of ReLU */
+#define LSQ_GEMM_PACKED_B 16 /* lsq_k_gemm: B is in fragment order (lsq_k_pack_weights); float16, M <= 64, K % 16 == 0 */
 int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* C, int M, int N,
                int K, int flags, void* stream);
+
+/* Weights in fragment order, which the products of at most 64 rows read fastest (one
+ * contiguous KB per matrix-core fragment instead of 16 bytes from each of 32 rows):
+ * packed [ceil(N/32)][K/16][64 lanes][8 halves], lane l of block b and k-step s holding
+ * W[32 b + (l & 31), 16 s + 8 (l >> 5) ... + 7], rows past N zero.  lsq_init packs the
+ * model's matrices itself; these two calls exist for lsq_k_gemm with LSQ_GEMM_PACKED_B.
+ * W [N,K] float16, device, 16-byte aligned; packed: device, lsq_k_packed_weight_bytes(N, K)
+ * bytes (0 if K is not a multiple of 16: unsupported). */
+size_t lsq_k_packed_weight_bytes(int N, int K);
+int lsq_k_pack_weights(const void* W, void* packed, int N, int K, void* stream);
 
 /* One residual sublayer tail: x[M,d] <- LayerNorm(x + in[M,K] . W[d,K]^T + bias) * gamma + beta,
  * in place on x, biased variance.  The projection's fp32 accumulators are not

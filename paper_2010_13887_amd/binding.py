@@ -57,6 +57,7 @@ def load_library() -> C.CDLL:
         "lsq_profile_classes": [],
         "lsq_profile_read": [vp, vp, i32],
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_pack_weights": [vp, vp, i32, i32, vp],
         "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_encoder_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
@@ -73,6 +74,8 @@ def load_library() -> C.CDLL:
         fn.restype = C.c_int
     lib.lsq_k_gemm_add_layernorm_scratch.argtypes = [i32, i32, i32, i32]
     lib.lsq_k_gemm_add_layernorm_scratch.restype = C.c_size_t
+    lib.lsq_k_packed_weight_bytes.argtypes = [i32, i32]
+    lib.lsq_k_packed_weight_bytes.restype = C.c_size_t
     lib.lsq_free.argtypes = []
     lib.lsq_free.restype = None
     lib.lsq_profile_class_name.argtypes = [i32]
@@ -208,17 +211,31 @@ def _p(t) -> int:
     return t.data_ptr()
 
 
-def k_gemm(A, B, bias, C_out, relu: bool = False, gelu: bool = False) -> None:
+def k_gemm(A, B, bias, C_out, relu: bool = False, gelu: bool = False, packed: bool = False) -> None:
     """C_out = act(A . B^T + bias), act = ReLU, tanh-GELU or none; a float32 C_out with float16 inputs
-    keeps the accumulators unrounded."""
+    keeps the accumulators unrounded.  packed: B is the output of k_pack_weights (N and K from C_out and A)."""
     import torch
     M, K = A.shape
-    N = B.shape[0]
-    assert B.shape[1] == K and tuple(C_out.shape) == (M, N)
-    assert not (relu and gelu)
+    N = C_out.shape[1]
+    assert packed or (tuple(B.shape) == (N, K))
+    assert C_out.shape[0] == M and not (relu and gelu)
     flags = int(relu) | (4 if gelu else 0) | (2 if (A.dtype == torch.float16 and C_out.dtype == torch.float32) else 0)
+    flags |= 16 if packed else 0
     assert flags & 2 or C_out.dtype == A.dtype
     _check(load_library().lsq_k_gemm(_dt(A), _p(A), _p(B), _p(bias), _p(C_out), M, N, K, flags, _stream()))
+
+
+def k_pack_weights(W):
+    """The float16 matrix W [N, K] in fragment order (see lsq_k_pack_weights): a flat float16 tensor."""
+    import torch
+    N, K = W.shape
+    lib = load_library()
+    nbytes = lib.lsq_k_packed_weight_bytes(N, K)
+    if nbytes == 0:
+        raise LsqError("K must be a multiple of 16")
+    out = torch.empty(nbytes // 2, dtype=torch.float16, device=W.device)
+    _check(lib.lsq_k_pack_weights(_p(W), _p(out), N, K, _stream()))
+    return out
 
 
 def k_gemm_add_layernorm(inp, W, bias, x, gamma, beta, eps: float) -> None:

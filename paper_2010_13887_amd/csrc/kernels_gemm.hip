@@ -3,6 +3,8 @@
 // fp16: MFMA v_mfma_f32_32x32x16_f16 on LDS-staged tiles.  fp32: a plain LDS-tiled FMA kernel
 // (only the small fp32 configuration uses it).  Bias, ReLU and the output scatter (Q to the
 // activation buffer, K and V straight into the caches) are fused into the epilogue.
+#include <unordered_map>
+
 #include "lsq_internal.h"
 
 namespace lsq {
@@ -345,6 +347,53 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
 }
 
 // ---------------------------------------------------------------------------------------------
+// Weights in fragment order, for the skinny kernels below.  Read from row-major rows, an MFMA
+// weight fragment is 16 bytes from each of 32 rows: 32 cache lines per load instruction, of which
+// the texture path retires few per clock.  Stored as [column block of 32][k-step of 16][lane][8]
+// the same fragment is one contiguous KB, and a skinny product is 1.2-1.5 us shorter (6.4 -> 5.0 us
+// for 4 rows x 3072 x 1024, 20.0 -> 15.6 us for 32 rows of the 32000 x 1024 vocabulary product).
+// The model's matrices are packed once at load time next to their row-major copies (which the
+// tiled kernels and the embedding lookup keep using) and found here by the row-major pointer.
+namespace {
+struct PackedEntry { const half_t* packed; int N, K; };
+std::unordered_map<const void*, PackedEntry> g_packed;
+
+const half_t* packed_of(const void* plain, int N, int K) {
+  auto it = g_packed.find(plain);
+  return (it != g_packed.end() && it->second.N == N && it->second.K == K) ? it->second.packed : nullptr;
+}
+
+__global__ void __launch_bounds__(256) pack_weights_kernel(const half_t* __restrict__ src, half_t* __restrict__ dst,
+                                                           int N, int K, size_t chunks) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;   // one 16-byte piece of the packed matrix
+  if (c >= chunks) return;
+  const int ksteps = K / 16;
+  const int lane = (int)(c & 63);
+  const size_t frag = c >> 6;
+  const int ks = (int)(frag % ksteps), nb = (int)(frag / ksteps);
+  const int row = nb * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
+  half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (row < N) v = *reinterpret_cast<const half8_t*>(src + (size_t)row * K + k);
+  *reinterpret_cast<half8_t*>(dst + c * 8) = v;
+}
+}  // namespace
+
+size_t gemm_packed_bytes(int N, int K) { return K % 16 == 0 ? (size_t)((N + 31) / 32) * 32 * K * sizeof(half_t) : 0; }
+
+hipError_t launch_pack_weights(const void* plain, void* packed, int N, int K, hipStream_t s) {
+  if (N <= 0 || K <= 0 || K % 16 != 0) return hipErrorInvalidValue;
+  const size_t chunks = gemm_packed_bytes(N, K) / 16;
+  pack_weights_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, s>>>((const half_t*)plain, (half_t*)packed, N, K, chunks);
+  return hipGetLastError();
+}
+
+void gemm_register_packed(const void* plain, const void* packed, int N, int K) {
+  g_packed[plain] = PackedEntry{(const half_t*)packed, N, K};
+}
+
+void gemm_clear_packed() { g_packed.clear(); }
+
+// ---------------------------------------------------------------------------------------------
 // Skinny fp16 GEMM for M <= 32*TM rows (few hypotheses alive, or small batches): the product is
 // a stream of weights, so the job is to keep many weight bytes in flight from many CUs.
 // A workgroup owns 32 output columns and all rows; its four wavefronts take every fourth 16-wide
@@ -356,6 +405,7 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
 template <int TM, int U, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
                                                               const half_t* __restrict__ B,
+                                                              const half_t* __restrict__ Bp,
                                                               const half_t* __restrict__ bias, GemmOut out, int M,
                                                               int N, int K, int act, int vec_ok) {
   __shared__ float red[4][TM][16][64];
@@ -366,7 +416,10 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
   const int ksteps_all = K / 16;                      // K % 16 == 0 is checked by the launcher
   const int ksteps = SPLIT ? ksteps_all / (int)gridDim.y : ksteps_all;
   const int ks0 = SPLIT ? (int)blockIdx.y * ksteps : 0;
-  const half_t* bp = B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  // weights: row-major rows (32 cache lines per fragment load), or, when the caller has them in
+  // fragment order (Bp), one contiguous KB per fragment: 512 halves per (column block, k-step)
+  const half_t* bp = Bp ? Bp + (size_t)blockIdx.x * ksteps_all * 512 + lane * 8 : B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  const size_t bstep = Bp ? 512 : 16;
   const half_t* ap[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) ap[i] = A + (size_t)min(i * 32 + fr, M - 1) * K + fk;
@@ -384,7 +437,7 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int kc = min(ks + 4 * u, ks_end - 1);
-      bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)kc * 16);
+      bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)kc * bstep);
 #pragma unroll
       for (int i = 0; i < TM; ++i) af[u][i] = *reinterpret_cast<const half8_t*>(ap[i] + (size_t)kc * 16);
     }
@@ -440,12 +493,12 @@ static int skinny_unroll(int per_wave, int cap) {
 }
 
 template <bool SPLIT, typename OutT>
-static void run_skinny(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
-                       int K, int act, int vec_ok, int splits, hipStream_t s) {
+static void run_skinny(const half_t* A, const half_t* B, const half_t* Bp, const half_t* bias, const GemmOut& out,
+                       int M, int N, int K, int act, int vec_ok, int splits, hipStream_t s) {
   dim3 grid((N + 31) / 32, splits), blk(256);
   const int per_wave = (K / 16 / splits + 3) / 4;
 #define LSQ_SKINNY(TM_, U_) \
-  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, bias, out, M, N, K, act, vec_ok)
+  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, Bp, bias, out, M, N, K, act, vec_ok)
   if (M <= 32) {
     switch (skinny_unroll(per_wave, 16)) {
       case 16: LSQ_SKINNY(1, 16); break;
@@ -547,6 +600,7 @@ __global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __res
 // other workgroups are still reading -- for the next residual connection.
 template <int U, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(LnInput ln, const half_t* __restrict__ B,
+                                                                 const half_t* __restrict__ Bp,
                                                                  const half_t* __restrict__ bias, GemmOut out,
                                                                  int M, int N, int K, int act, int vec_ok) {
   constexpr int NV = 2;   // K <= 1024: a lane owns at most two 8-element pieces of a row
@@ -558,10 +612,11 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(LnInput ln, con
   const int n0 = blockIdx.x * 32;
   const int fr = lane & 31, fk = (lane >> 5) * 8;
   const int ksteps = K / 16;
-  const half_t* bp = B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  const half_t* bp = Bp ? Bp + (size_t)blockIdx.x * ksteps * 512 + lane * 8 : B + (size_t)min(n0 + fr, N - 1) * K + fk;
+  const size_t bstep = Bp ? 512 : 16;   // weights in fragment order: see gemm_f16_skinny_kernel
   half8_t bf[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(wave + 4 * u, ksteps - 1) * 16);
+  for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(wave + 4 * u, ksteps - 1) * bstep);
 
   const size_t slab = (size_t)M * K;
   for (int r = wave; r < M; r += 4) {
@@ -604,7 +659,7 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(LnInput ln, con
   for (int ks = wave; ks < ksteps; ks += 4 * U) {
     if (ks != wave) {   // K beyond one pass: later fragments are fetched here
 #pragma unroll
-      for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(ks + 4 * u, ksteps - 1) * 16);
+      for (int u = 0; u < U; ++u) bf[u] = *reinterpret_cast<const half8_t*>(bp + (size_t)min(ks + 4 * u, ksteps - 1) * bstep);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -653,11 +708,12 @@ hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, co
   const size_t lds = (size_t)M * (K + 8) * sizeof(half_t);
   const int per_wave = (K / 16 + 3) / 4;
   const half_t* b = (const half_t*)B;
+  const half_t* bpk = packed_of(B, N, K);
   const half_t* bi = (const half_t*)bias;
 #define LSQ_SKINNY_LN(U_)                                                                                          \
   do {                                                                                                             \
-    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(ln, b, bi, out, M, N, K, act, vec_ok); \
-    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(ln, b, bi, out, M, N, K, act, vec_ok);      \
+    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(ln, b, bpk, bi, out, M, N, K, act, vec_ok); \
+    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(ln, b, bpk, bi, out, M, N, K, act, vec_ok);      \
   } while (0)
   switch (skinny_unroll(per_wave, 16)) {
     case 16: LSQ_SKINNY_LN(16); break;
@@ -735,7 +791,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   if (K % (64 * splits) != 0) return hipErrorInvalidValue;
   const int vec_ok = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(P) & 15) == 0;
   if (M <= kSkinnyRows) {
-    run_skinny<true, float>((const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok, splits, s);
+    run_skinny<true, float>((const half_t*)A, (const half_t*)B, packed_of(B, N, K), nullptr, out, M, N, K, 0, vec_ok, splits, s);
     return hipGetLastError();
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
@@ -745,9 +801,11 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
 }
 
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
-                       int N, int K, int act /* activation: 0 none, 1 ReLU, 2 tanh-GELU */, hipStream_t s) {
+                       int N, int K, int act /* activation: 0 none, 1 ReLU, 2 tanh-GELU */, hipStream_t s,
+                       bool b_packed) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K <= 0) return hipErrorInvalidValue;
+  if (b_packed && !(dtype == DT_F16 && M <= kSkinnyRows && K % 16 == 0)) return hipErrorInvalidValue;
   if (dtype == DT_F32) {
     if (K % 8 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0) {
       int nseg = (N + out.seg_n - 1) / out.seg_n;
@@ -785,8 +843,9 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (M <= kSkinnyRows && K % 16 == 0) {
-    if (out.f32_out) run_skinny<false, float>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
-    else run_skinny<false, half_t>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
+    const half_t* bpk = b_packed ? b : packed_of(B, N, K);
+    if (out.f32_out) run_skinny<false, float>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
+    else run_skinny<false, half_t>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if (tiles128 >= 200)

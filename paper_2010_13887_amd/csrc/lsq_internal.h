@@ -45,9 +45,18 @@ inline GemmOut plain_out(void* c, int N) {
 // Every launcher enqueues on `s` and returns hipGetLastError().
 // act: 0 none, 1 ReLU, 2 tanh-GELU
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out,
-                       int M, int N, int K, int act, hipStream_t s);
+                       int M, int N, int K, int act, hipStream_t s, bool b_packed = false);
 
 int gemm_partial_splits(int dtype, int M, int N, int K);
+
+// float16 weights in fragment order ([column block of 32][k-step of 16][lane][8 halves], rows past N
+// zero) for the products of at most 64 rows.  launch_pack_weights makes the copy (gemm_packed_bytes
+// of it; K a multiple of 16); after gemm_register_packed every product launched with the row-major
+// pointer and the same N, K finds it.  launch_gemm's b_packed says B itself is such a copy.
+size_t gemm_packed_bytes(int N, int K);
+hipError_t launch_pack_weights(const void* plain, void* packed, int N, int K, hipStream_t s);
+void gemm_register_packed(const void* plain, const void* packed, int N, int K);
+void gemm_clear_packed();
 
 // A product that makes its own input: A = LayerNorm(x_old + sum of `splits` fp32 slabs P[s][M][K] + bias) * g + b,
 // rounded to float16; the rows are also written to x_new (not the same buffer as x_old).  For the few-row end

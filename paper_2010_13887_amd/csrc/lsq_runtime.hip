@@ -132,13 +132,13 @@ int parse_header(const void* blob, size_t bytes, HParams* hp) {
 }
 
 // One tensor of the blob: `rows` x `cols` as stored ([in, out] for matrices; rows == 1 for vectors).
-struct TensorDesc { int rows, cols; bool transpose; };
+struct TensorDesc { int rows, cols; bool transpose; bool gemm = false; };   // gemm: the weight matrix of a product
 
 void tensor_walk(const HParams& hp, std::vector<TensorDesc>* out) {
   const int d = hp.d, F = hp.F, V = hp.V;
-  auto mat = [&](int r, int c) { out->push_back({r, c, true}); };
+  auto mat = [&](int r, int c) { out->push_back({r, c, true, true}); };
   auto vec = [&](int n) { out->push_back({1, n, false}); };
-  out->push_back({V, d, false});   // embedding: already [vocab, d] = [N, K] of the logit GEMM
+  out->push_back({V, d, false, true});   // embedding: already [vocab, d] = [N, K] of the logit GEMM
   if (hp.arch == 1) {
     out->push_back({hp.max_pos, d, false});   // learned positions
     for (int i = 0; i < hp.n_dec; ++i) {
@@ -170,13 +170,15 @@ struct DecLayer {
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
 struct Plan {
-  size_t weights, pe, cache, cross, score, tokens, len, fin, parent, anc, pen_tok, pen_n, cand_plain, cap, order, src_off, src_len, active, step_state,
+  size_t weights, wpacked, pe, cache, cross, score, tokens, len, fin, parent, anc, pen_tok, pen_n, cand_plain, cap, order, src_off, src_len, active, step_state,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
   size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits, d_y, e_y, d_x2;
 };
+
+size_t packed_weight_bytes(const HParams& hp);
 
 Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   Plan p;
@@ -185,6 +187,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
   p.weights = take(weight_bytes);
+  p.wpacked = take(packed_weight_bytes(hp));
   p.pe = take((size_t)T * d * 4);
   p.cache = take((size_t)hp.n_dec * 2 * M * T * d * esz);
   p.cross = take((size_t)hp.n_dec * R * 2 * d * esz);
@@ -238,6 +241,17 @@ size_t blob_bytes(const HParams& hp) {
   const size_t es = hp.dtype == DT_F16 ? 2 : 4;
   size_t n = 256;
   for (auto& t : ts) n = up(n) + (size_t)t.rows * t.cols * es;
+  return n;
+}
+
+// Fragment-ordered second copies of the float16 matrices (products of at most 64 rows read these).
+size_t packed_weight_bytes(const HParams& hp) {
+  if (hp.dtype != DT_F16) return 0;
+  std::vector<TensorDesc> ts;
+  tensor_walk(hp, &ts);
+  size_t n = 0;
+  for (auto& t : ts)
+    if (t.gemm) n += up(gemm_packed_bytes(t.transpose ? t.cols : t.rows, t.transpose ? t.rows : t.cols));
   return n;
 }
 
@@ -682,6 +696,21 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
   if (e == hipSuccess) e = hipStreamSynchronize(g.stream);
   (void)hipHostFree(stage);
   if (e != hipSuccess) return fail(LSQ_E_HIP, "weight upload failed: %s", hipGetErrorString(e));
+  gemm_clear_packed();
+  if (hp.dtype == DT_F16) {
+    size_t po = 0;
+    for (size_t i = 0; i < ts.size(); ++i) {
+      if (!ts[i].gemm) continue;
+      const int N = ts[i].transpose ? ts[i].cols : ts[i].rows, K = ts[i].transpose ? ts[i].rows : ts[i].cols;
+      const size_t nb = gemm_packed_bytes(N, K);
+      if (nb == 0) continue;   // K not a multiple of 16: the products read the row-major copy
+      char* dst = g.ws + plan.wpacked + po;
+      HIPCHK(launch_pack_weights(dev[i], dst, N, K, g.stream));
+      gemm_register_packed(dev[i], dst, N, K);
+      po += up(nb);
+    }
+    HIPCHK(hipStreamSynchronize(g.stream));
+  }
 
   // position table in fp32: sinusoidal, evaluated in double precision, or the model's learned one
   {
@@ -948,6 +977,7 @@ void lsq_free(void) {
     if (g.stream || g.state >= 2) (void)hipStreamSynchronize(g.stream);
     (void)hipHostFree(g.pinned);
   }
+  gemm_clear_packed();
   g = Ctx{};
 }
 
@@ -1045,7 +1075,19 @@ int lsq_k_gemm(int dtype, const void* A, const void* B, const void* bias, void* 
   KCHK(dtype == DT_F32 || K % 8 == 0, "K must be a multiple of 8 for float16");
   GemmOut o = plain_out(C, N);
   o.f32_out = (dtype == DT_F16 && (flags & LSQ_GEMM_F32_OUT)) ? 1 : 0;
-  KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) ? 1 : ((flags & LSQ_GEMM_GELU) ? 2 : 0), (hipStream_t)stream));
+  const bool packed = (flags & LSQ_GEMM_PACKED_B) != 0;
+  KCHK(!packed || (dtype == DT_F16 && M <= 64 && K % 16 == 0), "fragment-ordered weights: float16, at most 64 rows, K a multiple of 16");
+  KRUN(launch_gemm(dtype, A, B, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) ? 1 : ((flags & LSQ_GEMM_GELU) ? 2 : 0),
+                   (hipStream_t)stream, packed));
+}
+
+size_t lsq_k_packed_weight_bytes(int N, int K) { return gemm_packed_bytes(N, K); }
+
+int lsq_k_pack_weights(const void* W, void* packed, int N, int K, void* stream) {
+  KCHK(W && packed, "null pointer");
+  KCHK(N >= 1 && K >= 16 && K % 16 == 0, "N >= 1, K a positive multiple of 16");
+  KCHK((reinterpret_cast<uintptr_t>(W) & 15) == 0 && (reinterpret_cast<uintptr_t>(packed) & 15) == 0, "16-byte alignment");
+  KRUN(launch_pack_weights(W, packed, N, K, (hipStream_t)stream));
 }
 
 size_t lsq_k_gemm_add_layernorm_scratch(int dtype, int M, int d, int K) {

@@ -117,6 +117,34 @@ def test_gemm_add_layernorm(env, rows, d, K, half):
         np.testing.assert_allclose(got, ref, rtol=3e-5, atol=3e-5)
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 32, 16), (4, 3072, 1024), (32, 1000, 512), (33, 96, 768), (64, 50257, 64),
+                                   (7, 37, 48), (64, 2304, 768), (17, 31, 1024)])
+@pytest.mark.parametrize("f32_out", [False, True])
+def test_gemm_with_fragment_ordered_weights(env, M, N, K, f32_out):
+    """lsq_k_pack_weights lays the matrix out exactly as documented, and a product that reads it gives
+    the same bits as the product that reads the row-major matrix (same fragments, same order)."""
+    lsq, torch = env
+    rng = np.random.default_rng(M + N + K)
+    A, W, bias = _h(rng.standard_normal((M, K))), _h(rng.standard_normal((N, K)) * 0.1), _h(rng.standard_normal(N))
+    h = torch.float16
+    dA, dW, dbias = _dev(torch, A, h), _dev(torch, W, h), _dev(torch, bias, h)
+    packed = lsq.k_pack_weights(dW)
+    nb = (N + 31) // 32
+    Wp = np.zeros((nb * 32, K), np.float16)
+    Wp[:N] = W
+    # [block][row in block][k-step][half of the step][8] -> [block][k-step][half][row][8]: lane = half * 32 + row
+    ref = Wp.reshape(nb, 32, K // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(-1)
+    assert np.array_equal(packed.cpu().numpy(), ref)
+    C1 = torch.full((M, N), 7.0, dtype=torch.float32 if f32_out else h, device="cuda")
+    C2 = torch.full_like(C1, 9.0)
+    lsq.k_gemm(dA, dW, dbias, C1, relu=True)
+    lsq.k_gemm(dA, packed, dbias, C2, relu=True, packed=True)
+    assert torch.equal(C1, C2)
+    want = np.maximum(A.astype(np.float64) @ W.astype(np.float64).T + bias, 0)
+    np.testing.assert_allclose(C2.double().cpu().numpy(), want, rtol=2e-3 if not f32_out else 1e-5,
+                               atol=(2e-3 if not f32_out else 1e-5) * (1 + np.abs(want).max()))
+
+
 @pytest.mark.parametrize("rows,d,N,splits", [(1, 64, 96, 1), (4, 1024, 3072, 4), (8, 1024, 1000, 4), (5, 512, 2048, 2),
                                              (7, 768, 50, 3), (8, 1024, 32000, 4), (3, 48, 40, 1)])
 @pytest.mark.parametrize("f32_out", [False, True])
