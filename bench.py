@@ -39,11 +39,11 @@ PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 # readings for a 1 GiB copy (x2.0 for reads, x1.0 for writes): profiles/kernel_traffic_big128.txt.
 # Split-K classes are given for the 2 slabs used at this shape.
 MEASURED_TRAFFIC_BIG128 = {
-    "gemm_qkv": 15.0e6 + 3.1e6,
+    "gemm_qkv": 14.9e6 + 3.1e6,
     "gemm_dxd": (2 * (10.7e6 + 4.2e6) + (10.7e6 + 1.0e6)) / 3,   # two split-K products and one plain per layer
     "gemm_ffn1": 17.0e6 + 4.2e6,
     "gemm_ffn2": 42.1e6 + 4.2e6,
-    "gemm_vocab": 89.6e6 + 75.8e6,
+    "gemm_vocab": 89.5e6 + 73.2e6,
     "attn_self": 29.9e6 + 1.0e6,            # through the slab table: 0.32 of the (row, position) pairs distinct
     "attn_cross": 16.2e6 + 1.0e6,
     "row_topk": 66.0e6 + 21.0e6,
