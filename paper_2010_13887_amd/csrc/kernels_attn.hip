@@ -62,9 +62,7 @@ __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T
           float s = 0.f;
 #pragma unroll
           for (int i = 0; i < 8; ++i) s += q[n][i] * kv[u][i];
-#pragma unroll
-          for (int o = 1; o < LPK; o <<= 1) s += __shfl_xor(s, o, kWave);
-          s *= scale;
+          s = group_sum<LPK>(s) * scale;   // the lanes of a group are active together
           float mn = fmaxf(m[n], s);
           float corr = __expf(m[n] - mn);   // m = -inf on the first key: exp(-inf) = 0
           float p = __expf(s - mn);
@@ -79,21 +77,21 @@ __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T
   // merge the KPI lane groups (butterfly: every group ends with the total)
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
-#pragma unroll
-    for (int o = LPK; o < 64; o <<= 1) {
-      float m2 = __shfl_xor(m[n], o, kWave);
-      float l2 = __shfl_xor(l[n], o, kWave);
+    for_lane_bits<LPK>([&](auto bit) {
+      constexpr int O = decltype(bit)::value;
+      float m2 = lane_xor<O>(m[n]);
+      float l2 = lane_xor<O>(l[n]);
       float mn = fmaxf(m[n], m2);
       float c1 = (m[n] == -INFINITY) ? 0.f : __expf(m[n] - mn);
       float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
       l[n] = l[n] * c1 + l2 * c2;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        float a2 = __shfl_xor(acc[n][i], o, kWave);
+        float a2 = lane_xor<O>(acc[n][i]);
         acc[n][i] = acc[n][i] * c1 + a2 * c2;
       }
       m[n] = mn;
-    }
+    });
   }
 }
 
@@ -254,13 +252,11 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
         Vec8<T>::unpack(kk[u], kf);
 #pragma unroll
         for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
-#pragma unroll
-        for (int o = 1; o < LPK; o <<= 1) sdot += __shfl_xor(sdot, o, kWave);
+        sdot = group_sum<LPK>(sdot);
         sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * scale : -INFINITY;
         mx = fmaxf(mx, sc[u]);
       }
-#pragma unroll
-      for (int o = LPK; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));   // over the key slots
+      for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });   // over the key slots
       // mx is finite: key j0 exists
       const float corr = __expf(m[n] - mx);   // 0 the first time (m = -inf)
       m[n] = mx;
@@ -280,12 +276,12 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
   }
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
+    for_lane_bits<LPK>([&](auto bit) {
+      constexpr int O = decltype(bit)::value;
+      l[n] = add_lane_xor<O>(l[n]);
 #pragma unroll
-    for (int o = LPK; o < 64; o <<= 1) {
-      l[n] += __shfl_xor(l[n], o, kWave);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[n][i] += __shfl_xor(acc[n][i], o, kWave);
-    }
+      for (int i = 0; i < 8; ++i) acc[n][i] = add_lane_xor<O>(acc[n][i]);
+    });
     if (slot == 0) {
       if constexpr (SPLIT) {
 #pragma unroll

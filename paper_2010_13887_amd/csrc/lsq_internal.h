@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of liblsq.so.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace lsq {
@@ -163,15 +164,101 @@ bool topk_supported(int V);
 bool head_dim_supported(int dh);
 
 // ---- device helpers -------------------------------------------------------------------------
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+// Cross-lane moves inside the vector ALU.  __shfl_xor is an LDS-crossbar instruction (ds_bpermute:
+// an address register, the LDS queue and its latency for every step of a reduction); operand
+// swizzles (quad permutes, mirrors and rotations inside a row of 16 lanes) are a modifier of the
+// add or max itself, and gfx950 swaps rows of 16 and halves of 32 lanes between two registers in
+// one instruction.  All of them want every lane they read to be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside every 8 lanes
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside every 16 lanes
+constexpr int kDppRor8 = 0x128;        // rotate every 16 lanes by 8: lane i <-> i ^ 8
+
+// O = 16 or 32: {a, b} = the values of this lane and of lane (lane ^ O), the lower lane's in one and
+// the upper lane's in the other, in both lanes alike (swap(x, x) does exactly this).
+template <int O>
+__device__ __forceinline__ void lane_pair(float v, float& a, float& b) {
+  static_assert(O == 16 || O == 32, "rows of 16 or halves of 32 lanes");
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  unsigned ra, rb;
+  if constexpr (O == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    ra = r[0]; rb = r[1];
+  } else {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    ra = r[0]; rb = r[1];
+  }
+  a = __builtin_bit_cast(float, ra);
+  b = __builtin_bit_cast(float, rb);
+}
+
+// The value that lane (lane ^ O) holds.
+template <int O>
+__device__ __forceinline__ float lane_xor(float v) {
+  static_assert(O == 1 || O == 2 || O == 4 || O == 8 || O == 16 || O == 32, "one bit of the lane number");
+  if constexpr (O == 1) return dpp_move<kDppXor1>(v);
+  else if constexpr (O == 2) return dpp_move<kDppXor2>(v);
+  else if constexpr (O == 8) return dpp_move<kDppRor8>(v);
+  else if constexpr (O == 16 || O == 32) {
+    float a, b;
+    lane_pair<O>(v, a, b);   // whichever is not this lane's own value is the other's (or equal to it)
+    return __builtin_bit_cast(unsigned, a) == __builtin_bit_cast(unsigned, v) ? b : a;
+  } else {
+    return __shfl_xor(v, O, kWave);
+  }
+}
+
+// v + (value of lane ^ O) and max(v, value of lane ^ O)
+template <int O>
+__device__ __forceinline__ float add_lane_xor(float v) {
+  if constexpr (O == 16 || O == 32) { float a, b; lane_pair<O>(v, a, b); return a + b; }
+  else return v + lane_xor<O>(v);
+}
+template <int O>
+__device__ __forceinline__ float max_lane_xor(float v) {
+  if constexpr (O == 16 || O == 32) { float a, b; lane_pair<O>(v, a, b); return fmaxf(a, b); }
+  else return fmaxf(v, lane_xor<O>(v));
+}
+
+// Sum / maximum over every aligned group of W lanes (W a power of two), left in all of its lanes.
+// Once the quads hold equal values a mirror is as good as an exchange.
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(W >= 1 && W <= 64 && (W & (W - 1)) == 0, "power of two");
+  if constexpr (W >= 2) v += dpp_move<kDppXor1>(v);
+  if constexpr (W >= 4) v += dpp_move<kDppXor2>(v);
+  if constexpr (W >= 8) v += dpp_move<kDppHalfMirror>(v);
+  if constexpr (W >= 16) v += dpp_move<kDppMirror>(v);
+  if constexpr (W >= 32) v = add_lane_xor<16>(v);
+  if constexpr (W >= 64) v = add_lane_xor<32>(v);
   return v;
 }
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+template <int W>
+__device__ __forceinline__ float group_max(float v) {
+  static_assert(W >= 1 && W <= 64 && (W & (W - 1)) == 0, "power of two");
+  if constexpr (W >= 2) v = fmaxf(v, dpp_move<kDppXor1>(v));
+  if constexpr (W >= 4) v = fmaxf(v, dpp_move<kDppXor2>(v));
+  if constexpr (W >= 8) v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+  if constexpr (W >= 16) v = fmaxf(v, dpp_move<kDppMirror>(v));
+  if constexpr (W >= 32) v = max_lane_xor<16>(v);
+  if constexpr (W >= 64) v = max_lane_xor<32>(v);
   return v;
+}
+__device__ __forceinline__ float wave_sum(float v) { return group_sum<64>(v); }
+__device__ __forceinline__ float wave_max(float v) { return group_max<64>(v); }
+
+// f(integral constant O) for O = LO, 2 LO, ... < 64: the steps of a butterfly over lane groups
+template <int LO, typename F>
+__device__ __forceinline__ void for_lane_bits(F&& f) {
+  if constexpr (LO < 64) {
+    f(std::integral_constant<int, LO>{});
+    for_lane_bits<LO * 2>(f);
+  }
 }
 
 template <typename T> struct Vec8;
