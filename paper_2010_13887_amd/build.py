@@ -13,7 +13,10 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["lsq_runtime.hip", "kernels_elementwise.hip", "kernels_attn.hip", "kernels_gemm.hip",
            "kernels_search.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first kernel arguments arrive in scalar registers with the wavefront instead of being
+         # fetched by its first instructions: one dependent trip to memory less in every kernel
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _hipcc() -> str:

@@ -12,97 +12,160 @@ namespace lsq {
 
 // Keys j0, j0 + jstep, j0 + 2*jstep, ... (< nkeys) are visited, each lane group taking every
 // KPI-th of them.  On return every lane holds, for its 8 elements of the head row, the merged
-// (running max m, running sum l, un-normalised accumulator acc) of all keys this wavefront saw.
-// slot != nullptr: position j is not in this row's own slab but in slab slot[j] of its sentence
-// (K + slot[j] * slot_stride); the slot numbers of the next pass are requested together with the
-// rows of the current one, so the extra indirection is off the critical path after the first pass.
-template <typename T, int DH, int NQ>
+// (running max m, in units of log 2: the sums are of 2^(score - m); running sum l; un-normalised
+// accumulator acc) of all keys this wavefront saw.
+// TABLE: position j is not in this row's own slab but in slab slot[j] of its sentence
+// (K + slot[j] * slot_stride, slot numbers 0..slot_max).
+//
+// Trips to memory are what this costs at decoding sizes, so as few as possible depend on each
+// other.  nkeys usually comes from a counter in memory: nothing that forms an address uses it
+// before the first keys and values have been requested.  That first request is speculative: it
+// reads positions up to jcap (the last one that exists in memory, nkeys - 1 <= jcap) and slot
+// numbers forced into 0..slot_max, so whatever the table and the cache hold beyond nkeys the
+// addresses stay inside them; what was read from beyond nkeys is discarded by selection (not by a
+// zero weight: it may be anything) once nkeys has arrived.  After that each trip's rows, and the
+// slot numbers of the trip after it, are requested before the current trip is worked on.
+template <typename T, int DH, int NQ, bool TABLE = false>
 __device__ __forceinline__ void attend_partial(const T* const (&qp)[NQ], const T* __restrict__ K,
-                                               const T* __restrict__ V, long stride, int nkeys, float scale,
-                                               int j0, int jstep, int lane, float (&m)[NQ], float (&l)[NQ],
-                                               float (&acc)[NQ][8], const int32_t* __restrict__ slot = nullptr,
-                                               long slot_stride = 0) {
+                                               const T* __restrict__ V, int stride, int nkeys, int jcap,
+                                               float scale, int j0, int jstep, int lane, float (&m)[NQ],
+                                               float (&l)[NQ], float (&acc)[NQ][8],
+                                               const int32_t* __restrict__ slot = nullptr, int slot_stride = 0,
+                                               int slot_max = 0) {
+  using raw_t = typename Vec8<T>::raw_t;
   constexpr int LPK = DH / 8;
   constexpr int KPI = 64 / LPK;
+  constexpr int U = 4;   // keys per lane group and trip
   const int g = lane / LPK, c = lane % LPK;
+  const int step = KPI * jstep;
+  const int jfirst = j0 + g * jstep;
+  int sl[U];
+  raw_t kn[U], vn[U];   // the trip that is on its way
+  auto request_slots = [&](int jb, int last) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) sl[u] = TABLE ? slot[min(jb + u * step, last)] : 0;   // as stored: forced into range when used
+  };
+  auto request = [&](int jb, int last) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // K, V and the strides are the same in every lane (the caller's part of the address sits in
+      // scalar registers); a lane's own part fits 32 bits: an element offset inside one sentence's slabs
+      // (in bytes, so that the instruction takes it as it is next to the scalar base)
+      const unsigned at = ((TABLE ? min(max(sl[u], 0), slot_max) * slot_stride : 0) + min(jb + u * step, last) * stride + c * 8) *
+                          (unsigned)sizeof(T);
+      kn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(reinterpret_cast<const char*>(K) + at));
+      vn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(reinterpret_cast<const char*>(V) + at));
+    }
+  };
+  jcap = max(jcap, 0);   // position 0 exists whenever the kernel runs
+  request_slots(jfirst, jcap);
+  raw_t qr[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) qr[n] = Vec8<T>::load_raw(qp[n] + c * 8);
+  request(jfirst, jcap);
+  request_slots(jfirst + U * step, jcap);
+  // scores are kept in units of log 2 (multiplied by scale * log2 e), so every exponential below is
+  // the bare hardware instruction
+  const float qscale = scale * 1.44269504088896340736f;
   float q[NQ][8];
 #pragma unroll
+  for (int n = 0; n < NQ; ++n) Vec8<T>::unpack(qr[n], q[n]);
+  float kv[U][8], vv[U][8];
+  auto scores = [&](int jb, int n, float (&sc)[U]) {   // of query n against the U keys in kv; -inf beyond nkeys
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += q[n][i] * kv[u][i];
+      s = group_sum<LPK>(s) * qscale;   // the lanes of a group are active together
+      sc[u] = (jb + u * step < nkeys) ? s : -INFINITY;
+      mx = fmaxf(mx, sc[u]);
+    }
+    return mx;
+  };
+#pragma unroll
   for (int n = 0; n < NQ; ++n) {
-    Vec8<T>::load(qp[n] + c * 8, q[n]);
     m[n] = -INFINITY;
     l[n] = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
   }
-  // U keys per lane group are requested (K and V rows) before any is used, so a cache of n
-  // positions costs n / (KPI * U) round trips to memory instead of n / KPI.
-  constexpr int U = 4;
-  const int step = KPI * jstep;
-  int sl[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) sl[u] = slot ? slot[min(j0 + g * jstep + u * step, nkeys - 1)] : 0;
-  for (int jb = j0 + g * jstep; jb < nkeys; jb += U * step) {
-    float kv[U][8], vv[U][8];
+  // The loop body runs at least once, whether or not this lane group has a key at all (a test of
+  // nkeys in front of it would draw the requests above down behind the test): in the first trip
+  // nkeys only selects.  The U scores of a trip share one update of the running maximum (one
+  // rescaling of the sums per U keys, not per key).
+  int jb = jfirst;
+  bool speculative = true;
+  do {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int j = min(jb + u * step, nkeys - 1);   // past the end: a repeated row, not used
-      const long at = (long)sl[u] * slot_stride + (long)j * stride + c * 8;
-      Vec8<T>::load(K + at, kv[u]);
-      Vec8<T>::load(V + at, vv[u]);
+      Vec8<T>::unpack(kn[u], kv[u]);
+      Vec8<T>::unpack(vn[u], vv[u]);
     }
-    if (slot) {
+    if (speculative) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) sl[u] = slot[min(jb + (U + u) * step, nkeys - 1)];
-    }
+      for (int u = 0; u < U; ++u)
+        if (jb + u * step >= nkeys) {   // read from beyond the end: may be anything, and 0 * anything is not 0
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (jb + u * step < nkeys) {
-#pragma unroll
-        for (int n = 0; n < NQ; ++n) {
-          float s = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) s += q[n][i] * kv[u][i];
-          s = group_sum<LPK>(s) * scale;   // the lanes of a group are active together
-          float mn = fmaxf(m[n], s);
-          float corr = __expf(m[n] - mn);   // m = -inf on the first key: exp(-inf) = 0
-          float p = __expf(s - mn);
-          l[n] = l[n] * corr + p;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc[n][i] = acc[n][i] * corr + p * vv[u][i];
-          m[n] = mn;
+          for (int i = 0; i < 8; ++i) vv[u][i] = 0.f;
         }
+    }
+    // from here on no position beyond nkeys - 1 is read: a lane past the end repeats the last row, weighted 0
+    const int jn = jb + U * step;
+    if (jn < nkeys) {   // requested before this trip's arithmetic
+      request(jn, nkeys - 1);
+      request_slots(jn + U * step, nkeys - 1);
+    }
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      float sc[U];
+      const float mn = fmaxf(m[n], scores(jb, n, sc));   // -inf: no key for this group so far
+      const float corr = m[n] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[n] - mn);
+      m[n] = mn;
+      l[n] *= corr;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[n][i] *= corr;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = sc[u] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sc[u] - mn);
+        l[n] += p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[n][i] += p * vv[u][i];
       }
     }
-  }
-  // merge the KPI lane groups (butterfly: every group ends with the total)
+    jb = jn;
+    speculative = false;
+  } while (jb < nkeys);
+  // merge the KPI lane groups: every group rescales its sums to the maximum over all groups once,
+  // then the sums are added (every group ends with the totals)
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
+    float mx = m[n];
+    for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });
+    const float c1 = (m[n] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[n] - mx);   // a group that saw no key
+    m[n] = mx;
+    l[n] *= c1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[n][i] *= c1;
     for_lane_bits<LPK>([&](auto bit) {
       constexpr int O = decltype(bit)::value;
-      float m2 = lane_xor<O>(m[n]);
-      float l2 = lane_xor<O>(l[n]);
-      float mn = fmaxf(m[n], m2);
-      float c1 = (m[n] == -INFINITY) ? 0.f : __expf(m[n] - mn);
-      float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
-      l[n] = l[n] * c1 + l2 * c2;
+      l[n] = add_lane_xor<O>(l[n]);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float a2 = lane_xor<O>(acc[n][i]);
-        acc[n][i] = acc[n][i] * c1 + a2 * c2;
-      }
-      m[n] = mn;
+      for (int i = 0; i < 8; ++i) acc[n][i] = add_lane_xor<O>(acc[n][i]);
     });
   }
 }
 
-template <typename T, int DH, int NQ>
+template <typename T, int DH, int NQ, bool TABLE = false>
 __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __restrict__ K,
-                                       const T* __restrict__ V, long stride, int nkeys, float scale,
-                                       T* const (&op)[NQ], int lane, const int32_t* __restrict__ slot = nullptr,
-                                       long slot_stride = 0) {
+                                       const T* __restrict__ V, int stride, int nkeys, int jcap, float scale,
+                                       T* const (&op)[NQ], int lane,
+                                       const int32_t* __restrict__ slot = nullptr, int slot_stride = 0,
+                                       int slot_max = 0) {
   constexpr int LPK = DH / 8;
   float m[NQ], l[NQ], acc[NQ][8];
-  attend_partial<T, DH, NQ>(qp, K, V, stride, nkeys, scale, 0, 1, lane, m, l, acc, slot, slot_stride);
+  attend_partial<T, DH, NQ, TABLE>(qp, K, V, stride, nkeys, jcap, scale, 0, 1, lane, m, l, acc, slot, slot_stride, slot_max);
   if (lane < LPK) {
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
@@ -119,17 +182,25 @@ __device__ __forceinline__ void attend(const T* const (&qp)[NQ], const T* __rest
 // anc == nullptr: the history of row r is slab r.  Otherwise (cache refreshing without moving the
 // cache, paper sec. 3.2 turned around): position j of row r's history lives in slab
 // (r / beam) * beam + anc[r * anc_ld + j], the slab of the hypothesis that wrote it.
-template <typename T, int DH>
+// Argument order (here and in the kernels below): what the first addresses are formed from comes
+// first, so that it is among the arguments that arrive in registers with the wavefront; the step
+// counter and the output pointer, needed later, may take a trip of their own.
+template <typename T, int DH, bool TABLE>
 __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict__ q, const T* __restrict__ Kc,
-                                                             const T* __restrict__ Vc, T* __restrict__ out,
-                                                             int rows, int H, int d, int T_, int nkeys_base,
-                                                             const int32_t* __restrict__ tp, float scale,
-                                                             const int32_t* __restrict__ anc, int beam, int anc_ld) {
-  int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+                                                             const T* __restrict__ Vc,
+                                                             const int32_t* __restrict__ anc,
+                                                             const int32_t* __restrict__ tp, int H_beam, int d,
+                                                             int T_, int rows, int nkeys_base, T* __restrict__ out) {
+  const int H = H_beam & 0xffff, beam = H_beam >> 16;
+  constexpr float scale = DH == 16 ? 0.25f : DH == 32 ? 0.17677669529663688f : DH == 64 ? 0.125f : 0.08838834764831845f;
+  const int anc_ld = T_ + 1;
+  // the wavefront's number is the same in all of its lanes: said so, the row, the head and the
+  // bases below are computed once, in scalar registers
+  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
   if (w >= rows * H) return;
   const int nkeys = nkeys_base + (tp ? *tp : 0);
   int r = w / H, h = w % H;
-  if (anc) {
+  if constexpr (TABLE) {
     // the beams of a sentence mostly read the same slabs (shared ancestors): put them, for one
     // head, into neighbouring wavefronts of one workgroup so that those rows are fetched once
     const int bm = w % beam, rest = w / beam;
@@ -138,35 +209,38 @@ __global__ void __launch_bounds__(256) self_attention_kernel(const T* __restrict
   }
   const T* qp[1] = {q + (size_t)r * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
-  const int home = anc ? r - r % beam : r;
+  const int home = TABLE ? r - r % beam : r;
   size_t base = (size_t)home * T_ * d + h * DH;
-  attend<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, op, threadIdx.x & 63,
-                   anc ? anc + (size_t)r * anc_ld : nullptr, (long)T_ * d);
+  attend<T, DH, 1, TABLE>(qp, Kc + base, Vc + base, d, nkeys, T_ - 1, scale, op, threadIdx.x & 63,
+                          anc + (size_t)r * anc_ld, T_ * d, beam - 1);
 }
 
 // The same for few rows (rows * heads too small to fill the chip with one wavefront each): one
 // workgroup per (row, head), its four wavefronts take every fourth cached position and their
 // partial (max, sum, accumulator) are merged through LDS, so a cache of n positions costs
 // n / 128 round trips to memory per wavefront instead of n / 32.
-template <typename T, int DH>
+template <typename T, int DH, bool TABLE>
 __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __restrict__ q,
                                                                    const T* __restrict__ Kc,
-                                                                   const T* __restrict__ Vc, T* __restrict__ out,
-                                                                   int rows, int H, int d, int T_, int nkeys_base,
-                                                                   const int32_t* __restrict__ tp, float scale,
-                                                                   const int32_t* __restrict__ anc, int beam,
-                                                                   int anc_ld) {
+                                                                   const T* __restrict__ Vc,
+                                                                   const int32_t* __restrict__ anc,
+                                                                   const int32_t* __restrict__ tp, int H_beam,
+                                                                   int d, int T_, int rows, int nkeys_base,
+                                                                   T* __restrict__ out) {
+  const int H = H_beam & 0xffff, beam = H_beam >> 16;
+  constexpr float scale = DH == 16 ? 0.25f : DH == 32 ? 0.17677669529663688f : DH == 64 ? 0.125f : 0.08838834764831845f;
+  const int anc_ld = T_ + 1;
   constexpr int LPK = DH / 8;
   __shared__ float part[4][LPK][10];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nkeys = nkeys_base + (tp ? *tp : 0);
   const int r = blockIdx.x / H, h = blockIdx.x % H;
   const T* qp[1] = {q + (size_t)r * d + h * DH};
-  const int home = anc ? r - r % beam : r;
+  const int home = TABLE ? r - r % beam : r;
   const size_t base = (size_t)home * T_ * d + h * DH;
   float m[1], l[1], acc[1][8];
-  attend_partial<T, DH, 1>(qp, Kc + base, Vc + base, d, nkeys, scale, wave, 4, lane, m, l, acc,
-                           anc ? anc + (size_t)r * anc_ld : nullptr, (long)T_ * d);
+  attend_partial<T, DH, 1, TABLE>(qp, Kc + base, Vc + base, d, nkeys, T_ - 1, scale, wave, 4, lane, m, l, acc,
+                                  anc + (size_t)r * anc_ld, T_ * d, beam - 1);
   if (lane < LPK) {
     part[wave][lane][0] = m[0];
     part[wave][lane][1] = l[0];
@@ -180,7 +254,7 @@ __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __re
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float mw = part[w][lane][0];
-      const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mx);   // a wavefront that saw no key
+      const float c = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);   // a wavefront that saw no key; m is in units of log 2
       sum += part[w][lane][1] * c;
 #pragma unroll
       for (int i = 0; i < 8; ++i) o8[i] += part[w][lane][2 + i] * c;
@@ -206,9 +280,9 @@ __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __re
 template <typename T, int DH, int NQ, bool SPLIT>
 __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restrict__ q, const T* __restrict__ kv,
                                                               const int32_t* __restrict__ off,
-                                                              const int32_t* __restrict__ len,
-                                                              T* __restrict__ out, int batch, int beam,
-                                                              int first, int H, int d, float scale) {
+                                                              const int32_t* __restrict__ len, int batch, int beam,
+                                                              int first, int H, int d, T* __restrict__ out) {
+  constexpr float scale = DH == 16 ? 0.25f : DH == 32 ? 0.17677669529663688f : DH == 64 ? 0.125f : 0.08838834764831845f;
   using raw_t = typename Vec8<T>::raw_t;
   constexpr int LPK = DH / 8;        // lanes per key
   constexpr int KPW = 64 / LPK;      // keys per pass
@@ -219,14 +293,37 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
   const int w = SPLIT ? blockIdx.x : blockIdx.x * 4 + wave;
   if (w >= batch * H) return;
   const int b = w / H, h = w % H;
-  const int n_keys = len[b];
   const int c = lane % LPK, slot = lane / LPK;
-  const T* K = kv + (size_t)off[b] * 2 * d + h * DH + c * 8;
+  // Trips to memory before the first score: {length, first row, queries} together, then the keys
+  // and values of the first G passes.  Left to itself the compiler fetches the row offset only
+  // once the length has arrived (it is used in the loop, which the length may skip) and waits for
+  // the queries (to convert them) before the loop requests any key; so the queries are kept as
+  // they come from memory until the first keys are on their way, and length and offset are
+  // awaited at one point.
+  raw_t qr[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) qr[n] = Vec8<T>::load_raw(q + ((size_t)b * beam + first + n) * d + h * DH + c * 8);
+  int n_keys = len[b], row0 = off[b];
+  asm volatile("" : "+v"(n_keys), "+v"(row0));
+  const T* K = kv + (size_t)row0 * 2 * d + h * DH + c * 8;
   const T* V = K + d;
   const long stride = 2 * d;
+  const float qscale = scale * 1.44269504088896340736f;   // scores in units of log 2, as in attend_partial
+  raw_t kn[G], vn[G];   // the trip that is on its way
+  auto request = [&](int j0) {
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const int j = min(j0 + u * KPW + slot, n_keys - 1);
+      kn[u] = Vec8<T>::load_raw(K + (long)j * stride);
+      vn[u] = Vec8<T>::load_raw(V + (long)j * stride);
+    }
+  };
+  const int jfirst = SPLIT ? wave * G * KPW : 0;
+  if (jfirst < n_keys) request(jfirst);
+  asm volatile("" ::: "memory");   // keeps the requests above what follows
   float qv[NQ][8];
 #pragma unroll
-  for (int n = 0; n < NQ; ++n) Vec8<T>::load(q + ((size_t)b * beam + first + n) * d + h * DH + c * 8, qv[n]);
+  for (int n = 0; n < NQ; ++n) Vec8<T>::unpack(qr[n], qv[n]);
   float m[NQ], l[NQ], acc[NQ][8];
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
@@ -235,14 +332,12 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
   }
-  for (int j0 = SPLIT ? wave * G * KPW : 0; j0 < n_keys; j0 += NW * G * KPW) {
+  for (int j0 = jfirst; j0 < n_keys; j0 += NW * G * KPW) {
     raw_t kk[G], vv[G];
 #pragma unroll
-    for (int u = 0; u < G; ++u) {
-      const int j = min(j0 + u * KPW + slot, n_keys - 1);
-      kk[u] = Vec8<T>::load_raw(K + (long)j * stride);
-      vv[u] = Vec8<T>::load_raw(V + (long)j * stride);
-    }
+    for (int u = 0; u < G; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
+    if (j0 + NW * G * KPW < n_keys) request(j0 + NW * G * KPW);   // travels while this trip is worked on
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
       float sc[G], mx = m[n];
@@ -253,12 +348,12 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
 #pragma unroll
         for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
         sdot = group_sum<LPK>(sdot);
-        sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * scale : -INFINITY;
+        sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * qscale : -INFINITY;
         mx = fmaxf(mx, sc[u]);
       }
       for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });   // over the key slots
       // mx is finite: key j0 exists
-      const float corr = __expf(m[n] - mx);   // 0 the first time (m = -inf)
+      const float corr = __builtin_amdgcn_exp2f(m[n] - mx);   // 0 the first time (m = -inf)
       m[n] = mx;
       l[n] *= corr;
 #pragma unroll
@@ -267,7 +362,7 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
       for (int u = 0; u < G; ++u) {
         float vf[8];
         Vec8<T>::unpack(vv[u], vf);
-        const float pj = __expf(sc[u] - mx);   // masked keys: exp(-inf) = 0
+        const float pj = __builtin_amdgcn_exp2f(sc[u] - mx);   // masked keys: 2^-inf = 0
         l[n] += pj;
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[n][i] += pj * vf[i];
@@ -304,11 +399,11 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
       for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, part[w2][n][DH]);
       float sum = 0.f;
 #pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __expf(part[w2][n][DH] - mx);
+      for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
       for (int x = lane; x < DH; x += 64) {
         float v = 0.f;
 #pragma unroll
-        for (int w2 = 0; w2 < 4; ++w2) v += part[w2][n][x] * __expf(part[w2][n][DH] - mx);
+        for (int w2 = 0; w2 < 4; ++w2) v += part[w2][n][x] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
         out[((size_t)b * beam + first + n) * d + h * DH + x] = (T)(v / sum);
       }
     }
@@ -324,7 +419,7 @@ __global__ void __launch_bounds__(256) encoder_attention_kernel(const T* __restr
                                                                 const int32_t* __restrict__ len,
                                                                 T* __restrict__ out, int rows, int H, int d,
                                                                 int causal, float scale) {
-  int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));   // one value per wavefront
   if (w >= rows * H) return;
   int r = w / H, h = w % H;
   int b = row_sent[r];
@@ -333,7 +428,7 @@ __global__ void __launch_bounds__(256) encoder_attention_kernel(const T* __restr
   const T* qp[1] = {qkv + (size_t)r * 3 * d + h * DH};
   T* op[1] = {out + (size_t)r * d + h * DH};
   const T* K = qkv + (size_t)off[b] * 3 * d + d + h * DH;
-  attend<T, DH, 1>(qp, K, K + d, 3 * d, nk, scale, op, threadIdx.x & 63);
+  attend<T, DH, 1>(qp, K, K + d, 3 * d, nk, nk - 1, scale, op, threadIdx.x & 63);
 }
 
 bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh == 128; }
@@ -354,14 +449,17 @@ template <typename T>
 static hipError_t self_t(const T* q, const T* Kc, const T* Vc, T* out, int rows, int H, int d, int T_,
                          int nkeys, const int32_t* tp, const int32_t* anc, int beam, int anc_ld, hipStream_t s) {
   int dh = d / H;
-  float scale = 1.0f / sqrtf((float)dh);
+  if (H > 0xffff || beam < 0 || beam > 0x7fff) return hipErrorInvalidValue;
+  const int H_beam = H | beam << 16;   // two small numbers in one argument word
   dim3 b(256);
   if (rows * H <= kSplitAttentionUnits) {
     dim3 g(rows * H);
-    LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale, anc, beam, anc_ld)));
+    if (anc) { LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH, true><<<g, b, 0, s>>>(q, Kc, Vc, anc, tp, H_beam, d, T_, rows, nkeys, out))); }
+    else { LSQ_DISPATCH_DH(dh, (self_attention_split_kernel<T, DH, false><<<g, b, 0, s>>>(q, Kc, Vc, anc, tp, H_beam, d, T_, rows, nkeys, out))); }
   } else {
     dim3 g((rows * H + 3) / 4);
-    LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH><<<g, b, 0, s>>>(q, Kc, Vc, out, rows, H, d, T_, nkeys, tp, scale, anc, beam, anc_ld)));
+    if (anc) { LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH, true><<<g, b, 0, s>>>(q, Kc, Vc, anc, tp, H_beam, d, T_, rows, nkeys, out))); }
+    else { LSQ_DISPATCH_DH(dh, (self_attention_kernel<T, DH, false><<<g, b, 0, s>>>(q, Kc, Vc, anc, tp, H_beam, d, T_, rows, nkeys, out))); }
   }
   return hipGetLastError();
 }
@@ -370,7 +468,8 @@ hipError_t launch_self_attention(int dtype, const void* q, const void* Kc, const
                                  int rows, int H, int d, int T, int nkeys, const int32_t* tp, const int32_t* anc,
                                  int beam, int anc_ld, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (anc && (beam < 1 || rows % beam != 0)) return hipErrorInvalidValue;
+  if (anc && (beam < 1 || rows % beam != 0 || anc_ld != T + 1)) return hipErrorInvalidValue;   // table rows hold T + 1 entries
+  if ((long)(anc ? beam : 1) * T * d * 4 > 0xffffffffL) return hipErrorInvalidValue;   // a lane's byte offset inside a sentence's slabs is 32 bits wide
   if (dtype == DT_F16)
     return self_t<half_t>((const half_t*)q, (const half_t*)Kc, (const half_t*)Vc, (half_t*)out, rows, H, d, T, nkeys, tp, anc, beam, anc_ld, s);
   return self_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, rows, H, d, T, nkeys, tp, anc, beam, anc_ld, s);
@@ -386,14 +485,13 @@ template <typename T, int NQ>
 static hipError_t cross_nq(const T* q, const T* kv, const int32_t* off, const int32_t* len, T* out,
                            int batch, int beam, int first, int H, int d, int smax, hipStream_t s) {
   int dh = d / H;
-  float scale = 1.0f / sqrtf((float)dh);
   if (cross_attention_splits(batch * H, smax)) {
     dim3 g(batch * H), b(256);
-    LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ, true><<<g, b, 0, s>>>(q, kv, off, len, out, batch, beam, first, H, d, scale)));
+    LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ, true><<<g, b, 0, s>>>(q, kv, off, len, batch, beam, first, H, d, out)));
     return hipGetLastError();
   }
   dim3 g((batch * H + 3) / 4), b(256);
-  LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ, false><<<g, b, 0, s>>>(q, kv, off, len, out, batch, beam, first, H, d, scale)));
+  LSQ_DISPATCH_DH(dh, (cross_attention_kernel<T, DH, NQ, false><<<g, b, 0, s>>>(q, kv, off, len, batch, beam, first, H, d, out)));
   return hipGetLastError();
 }
 
@@ -437,6 +535,7 @@ hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* r
                                     const int32_t* len, void* out, int rows, int H, int d, int causal,
                                     hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  if ((long)rows * 3 * d * 4 > 0xffffffffL) return hipErrorInvalidValue;   // a lane's byte offset inside a sentence is 32 bits wide
   if (dtype == DT_F16)
     return enc_t<half_t>((const half_t*)qkv, row_sent, off, len, (half_t*)out, rows, H, d, causal, s);
   return enc_t<float>((const float*)qkv, row_sent, off, len, (float*)out, rows, H, d, causal, s);

@@ -59,8 +59,8 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
 // for shapes the matrix-core kernel further down does not take (K not a multiple of 8, operands
 // not 16-byte aligned).
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                       const float* __restrict__ bias, GemmOut out, int M,
-                                                       int N, int K, int act) {
+                                                       int M, int N, int K, const float* __restrict__ bias,
+                                                       int act, GemmOut out) {
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tid = threadIdx.x;
@@ -118,13 +118,16 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // LDS rows are padded by 8 halves so the 16-byte fragment reads of consecutive rows hit distinct
 // banks.  The MFMA is issued as D = Bfrag x Afrag, i.e. D[n][m]: a lane then owns four
 // consecutive n of one m, which makes the epilogue store an aligned 8- or 16-byte vector.
+// Parameter order (all product kernels): the operands and the shape come first, so that they are
+// among the arguments that arrive in scalar registers with the wavefront and the first tile can be
+// requested at once; the output description, needed only by the epilogue, is fetched meanwhile.
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so the id is remapped
 // to give every XCD a contiguous run of tiles, m fastest: the tiles that share a weight tile then
 // share an L2.
 template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT, int KG = 1>
 __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
-                                                       const half_t* __restrict__ bias, GemmOut out, int M,
-                                                       int N, int K, int act, int vec_ok) {
+                                                       int M, int N, int K, const half_t* __restrict__ bias,
+                                                       int act, int vec_ok, GemmOut out) {
   constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
@@ -405,9 +408,9 @@ void gemm_clear_packed() { g_packed.clear(); }
 template <int TM, int U, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
                                                               const half_t* __restrict__ B,
-                                                              const half_t* __restrict__ Bp,
-                                                              const half_t* __restrict__ bias, GemmOut out, int M,
-                                                              int N, int K, int act, int vec_ok) {
+                                                              const half_t* __restrict__ Bp, int M, int N,
+                                                              int K, const half_t* __restrict__ bias, int act,
+                                                              int vec_ok, GemmOut out) {
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long tp = out.tpos ? *out.tpos : 0;
@@ -498,7 +501,7 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* Bp, const
   dim3 grid((N + 31) / 32, splits), blk(256);
   const int per_wave = (K / 16 / splits + 3) / 4;
 #define LSQ_SKINNY(TM_, U_) \
-  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, Bp, bias, out, M, N, K, act, vec_ok)
+  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, Bp, M, N, K, bias, act, vec_ok, out)
   if (M <= 32) {
     switch (skinny_unroll(per_wave, 16)) {
       case 16: LSQ_SKINNY(1, 16); break;
@@ -527,8 +530,8 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* Bp, const
 // 8s+4+i -- any pairing of k does, as long as both operands use the same one.  U steps in flight.
 template <int TM, int U>
 __global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                              const float* __restrict__ bias, GemmOut out, int M,
-                                                              int N, int K, int act, int vec_ok) {
+                                                              int M, int N, int K, const float* __restrict__ bias,
+                                                              int act, int vec_ok, GemmOut out) {
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long tp = out.tpos ? *out.tpos : 0;
@@ -599,10 +602,10 @@ __global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __res
 // Workgroup 0 also writes the normalised rows to x_new -- a different buffer from x_old, which the
 // other workgroups are still reading -- for the next residual connection.
 template <int U, typename OutT>
-__global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(LnInput ln, const half_t* __restrict__ B,
-                                                                 const half_t* __restrict__ Bp,
-                                                                 const half_t* __restrict__ bias, GemmOut out,
-                                                                 int M, int N, int K, int act, int vec_ok) {
+__global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(const half_t* __restrict__ Bp,
+                                                                 const half_t* __restrict__ B, int M, int N, int K,
+                                                                 LnInput ln, const half_t* __restrict__ bias,
+                                                                 int act, int vec_ok, GemmOut out) {
   constexpr int NV = 2;   // K <= 1024: a lane owns at most two 8-element pieces of a row
   extern __shared__ __attribute__((aligned(16))) half_t a_rows[];   // [M][K + 8]
   __shared__ float red[4][16][64];
@@ -712,8 +715,8 @@ hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, co
   const half_t* bi = (const half_t*)bias;
 #define LSQ_SKINNY_LN(U_)                                                                                          \
   do {                                                                                                             \
-    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(ln, b, bpk, bi, out, M, N, K, act, vec_ok); \
-    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(ln, b, bpk, bi, out, M, N, K, act, vec_ok);      \
+    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(bpk, b, M, N, K, ln, bi, act, vec_ok, out); \
+    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(bpk, b, M, N, K, ln, bi, act, vec_ok, out);      \
   } while (0)
   switch (skinny_unroll(per_wave, 16)) {
     case 16: LSQ_SKINNY_LN(16); break;
@@ -741,7 +744,7 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, int threads, hipStrea
       raised = true;
     }
   }
-  kern<<<grid, dim3(threads), lds, s>>>(A, B, bias, out, M, N, K, act, vec_ok);
+  kern<<<grid, dim3(threads), lds, s>>>(A, B, M, N, K, bias, act, vec_ok, out);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int D, int KG = 1>
@@ -796,7 +799,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
   gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, gemm_lds_bytes<64, 64, 64>(), s>>>(
-      (const half_t*)A, (const half_t*)B, nullptr, out, M, N, K, 0, vec_ok);
+      (const half_t*)A, (const half_t*)B, M, N, K, nullptr, 0, vec_ok, out);
   return hipGetLastError();
 }
 
@@ -819,17 +822,16 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
       const int per_wave = (K / 8 + 3) / 4;
       if (M <= 32) {
         dim3 grid((N + 31) / 32, 1, 1), blk(256);
-        if (per_wave <= 8) gemm_f32_stream_kernel<1, 8><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
-        else gemm_f32_stream_kernel<1, 16><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
+        if (per_wave <= 8) gemm_f32_stream_kernel<1, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
+        else gemm_f32_stream_kernel<1, 16><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
       } else {
         dim3 grid((N + 31) / 32, 1, (M + 63) / 64), blk(256);
-        gemm_f32_stream_kernel<2, 8><<<grid, blk, 0, s>>>(a, b, bi, out, M, N, K, act, vec_ok);
+        gemm_f32_stream_kernel<2, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
       }
       return hipGetLastError();
     }
     dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);   // odd K or unaligned operands: the plain tile kernel
-    gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, (const float*)bias, out, M, N, K,
-                                         act);
+    gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, M, N, K, (const float*)bias, act, out);
     return hipGetLastError();
   }
   if (K % 8 != 0) return hipErrorInvalidValue;

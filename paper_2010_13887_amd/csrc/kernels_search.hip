@@ -321,63 +321,63 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   const int k_all = gr.k_all > 1 ? gr.k_all : k;           // rows of a sentence (k_all == 1: no groups)
   const int base = b * k_all + gr.goff;                    // first row of this group
   if (lane == 0) { sh_unfinished = 0; sh_taken = 0; }
+  // Everything the kernel reads is requested here, before any of it is used (one trip to memory
+  // instead of one per phase): the candidates, the state of the beam a candidate continues (lane
+  // c continues beam c / k whatever its rank turns out to be), the sentence's length cap and this
+  // lane's first position of the k token histories and slab tables.
   float s = -INFINITY, plain = -INFINITY;
   long flat = -1;
-  int tok = -1, j = 0;
+  int tok = -1, j = 0, plen = 0, pfin = 0;
   if (lane < kk) {
     j = lane / k;
     s = cand_score[(size_t)base * k + lane];
     plain = gr.out_plain ? gr.out_plain[(size_t)base * k + lane] : s;
     tok = cand_idx[(size_t)base * k + lane];
-    if (tok >= 0) flat = (long)(gr.goff + j) * V + tok;
-  }
-  int rank = 0;
-  for (int c = 0; c < kk; ++c) {
-    float s2 = __shfl(s, c, kWave);
-    int t2 = __shfl(tok, c, kWave);
-    long f2 = t2 >= 0 ? (long)(gr.goff + c / k) * V + t2 : -1;
-    if (f2 >= 0 && (s2 > s || (s2 == s && f2 < flat))) ++rank;
-  }
-  const bool win = flat >= 0 && rank < k;
-  // read the parent's state before anyone overwrites it
-  int plen = 0, pfin = 0;
-  if (win) {
     plen = len[base + j];
     pfin = fin[base + j];
-    sh_parent[rank] = j;
   }
-  __syncthreads();
-  // token histories: positions 0..t; every lane reads all k beams of a position, then writes
-  for (int p = lane; p <= t && p < T1; p += 64) {
-    int h[LSQ_MAX_BEAM_];
-#pragma unroll
-    for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
-      if (i < k) h[i] = tokens[(size_t)(base + i) * T1 + p];
+  const int cap_b = cap[b];
+  int p = lane;
+  int h[LSQ_MAX_BEAM_], ha[LSQ_MAX_BEAM_];
+  auto fetch = [&]() {
 #pragma unroll
     for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
       if (i < k) {
-        int src = sh_parent[i], val = 0;
+        h[i] = tokens[(size_t)(base + i) * T1 + p];
+        ha[i] = anc ? anc[(size_t)(base + i) * T1 + p] : 0;
+      }
+  };
+  if (p <= t && p < T1) fetch();
+  if (tok >= 0) flat = (long)(gr.goff + j) * V + tok;
+  // rank among the k*k candidates: lane c's pair is read straight from its registers
+  int rank = 0;
+  for (int c = 0; c < kk; ++c) {
+    const float s2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), c));
+    const int t2 = __builtin_amdgcn_readlane(tok, c);
+    const long f2 = t2 >= 0 ? (long)(gr.goff + c / k) * V + t2 : -1;
+    if (f2 >= 0 && (s2 > s || (s2 == s && f2 < flat))) ++rank;
+  }
+  const bool win = flat >= 0 && rank < k;
+  if (win) sh_parent[rank] = j;
+  __syncthreads();
+  // token histories, positions 0..t, and the table that says which slab holds position p of each
+  // history (cache refreshing without moving the cache; position t+1 is written by the row
+  // itself): every lane has all k beams of a position, then writes those that change
+  for (; p <= t && p < T1;) {
+#pragma unroll
+    for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
+      if (i < k) {
+        int src = sh_parent[i], val = 0, vala = 0;
 #pragma unroll
         for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
-          if (jj == src) val = h[jj];
-        if (src != i) tokens[(size_t)(base + i) * T1 + p] = val;
-      }
-    // the same gather for the table that says which slab holds position p of each history
-    // (cache refreshing without moving the cache); position t+1 will be written by the row itself
-    if (anc) {
-#pragma unroll
-      for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
-        if (i < k) h[i] = anc[(size_t)(base + i) * T1 + p];
-#pragma unroll
-      for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
-        if (i < k) {
-          int src = sh_parent[i], val = 0;
-#pragma unroll
-          for (int jj = 0; jj < LSQ_MAX_BEAM_; ++jj)
-            if (jj == src) val = h[jj];
-          if (src != i) anc[(size_t)(base + i) * T1 + p] = val;
+          if (jj == src) { val = h[jj]; vala = ha[jj]; }
+        if (src != i) {
+          tokens[(size_t)(base + i) * T1 + p] = val;
+          if (anc) anc[(size_t)(base + i) * T1 + p] = vala;
         }
-    }
+      }
+    p += 64;
+    if (p <= t && p < T1) fetch();
   }
   if (anc && lane < k && t + 1 < T1) anc[(size_t)(base + lane) * T1 + t + 1] = gr.goff + lane;
   __syncthreads();
@@ -387,7 +387,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     if (!pfin) {
       nlen = plen + 1;
       tokens[(size_t)row * T1 + nlen] = tok;
-      nfin = (tok == eos || nlen >= cap[b]) ? 1 : 0;
+      nfin = (tok == eos || nlen >= cap_b) ? 1 : 0;
       // a live hypothesis that took a token: later groups of this sentence are steered away from it
       if (gr.pen_tok && !gr.last && plain != -INFINITY) {
         const int at = atomicAdd(&sh_taken, 1);
@@ -411,9 +411,8 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   if (lane == 0) {
     if (sh_unfinished || others) atomicAdd(step_state ? active + t : active, 1);   // per-step counters, or the caller's one
     if (step_state) {
-      // the last sentence to get here advances the step counter; every workgroup read it at its
-      // start, and kernels launched later see the new value
-      __threadfence();
+      // the last sentence to get here advances the step counter: every workgroup read it at its
+      // start, before its own increment, and the only other readers are kernels launched later
       if (atomicAdd(&step_state[1], 1) == (int)gridDim.x - 1) {
         step_state[1] = 0;
         step_state[0] = t + 1 - t_base;
