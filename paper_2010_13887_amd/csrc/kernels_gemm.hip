@@ -59,12 +59,12 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
 // for shapes the matrix-core kernel further down does not take (K not a multiple of 8, operands
 // not 16-byte aligned).
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                       int M, int N, int K, const float* __restrict__ bias,
-                                                       int act, GemmOut out) {
+                                                       int M, int N, int K, const int32_t* __restrict__ tpos,
+                                                       const float* __restrict__ bias, int act, GemmOut out) {
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tid = threadIdx.x;
-  const long tp = out.tpos ? *out.tpos : 0;
+  const long tp = tpos ? *tpos : 0;   // the counter's address is among the first arguments: requested at once, awaited by the epilogue
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   const int tx = tid & 15, ty = tid >> 4;
   float acc[4][4] = {};
@@ -126,8 +126,10 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // share an L2.
 template <int BM, int BN, int BK, int WM, int WN, int D, bool KTAIL, bool SPLIT, typename OutT, int KG = 1>
 __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
-                                                       int M, int N, int K, const half_t* __restrict__ bias,
-                                                       int act, int vec_ok, GemmOut out) {
+                                                       int M, int N, int K, int splits,
+                                                       const int32_t* __restrict__ tpos,
+                                                       const half_t* __restrict__ bias, int act, int vec_ok,
+                                                       GemmOut out) {
   constexpr int LDK = BK + 8;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int WAVES_N = BN / WN;
@@ -147,7 +149,7 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
   const int tid = threadIdx.x, lane = tid & 63;
   constexpr int TILE_WAVES = (BM / WM) * (BN / WN);
   const int wave = (tid >> 6) % TILE_WAVES, kgrp = (tid >> 6) / TILE_WAVES;   // wave tile, k-group
-  const long tp = out.tpos ? *out.tpos : 0;
+  const long tp = tpos ? *tpos : 0;   // the counter's address is among the first arguments: requested at once, awaited by the epilogue
   const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN, total = mt * nt;
   int id = blockIdx.x;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
@@ -224,7 +226,7 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
   // k-tiles and writes its fp32 partial sums (no bias) to its own [M,N] slab; the consumer adds
   // the slabs in a fixed order, so the result does not depend on scheduling.
   const int nk_all = (K + BK - 1) / BK;
-  const int nk = SPLIT ? nk_all / (int)gridDim.y : nk_all;
+  const int nk = SPLIT ? nk_all / splits : nk_all;   // splits = gridDim.y, as an argument: no trip for it
   if constexpr (SPLIT) {
     A += (size_t)blockIdx.y * nk * BK;
     B += (size_t)blockIdx.y * nk * BK;
@@ -409,15 +411,16 @@ template <int TM, int U, bool SPLIT, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __restrict__ A,
                                                               const half_t* __restrict__ B,
                                                               const half_t* __restrict__ Bp, int M, int N,
-                                                              int K, const half_t* __restrict__ bias, int act,
+                                                              int K, int splits, const int32_t* __restrict__ tpos,
+                                                              const half_t* __restrict__ bias, int act,
                                                               int vec_ok, GemmOut out) {
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long tp = out.tpos ? *out.tpos : 0;
+  const long tp = tpos ? *tpos : 0;   // the counter's address is among the first arguments: requested at once, awaited by the epilogue
   const int n0 = blockIdx.x * 32;
   const int fr = lane & 31, fk = (lane >> 5) * 8;
   const int ksteps_all = K / 16;                      // K % 16 == 0 is checked by the launcher
-  const int ksteps = SPLIT ? ksteps_all / (int)gridDim.y : ksteps_all;
+  const int ksteps = SPLIT ? ksteps_all / splits : ksteps_all;   // splits = gridDim.y
   const int ks0 = SPLIT ? (int)blockIdx.y * ksteps : 0;
   // weights: row-major rows (32 cache lines per fragment load), or, when the caller has them in
   // fragment order (Bp), one contiguous KB per fragment: 512 halves per (column block, k-step)
@@ -501,7 +504,7 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* Bp, const
   dim3 grid((N + 31) / 32, splits), blk(256);
   const int per_wave = (K / 16 / splits + 3) / 4;
 #define LSQ_SKINNY(TM_, U_) \
-  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, Bp, M, N, K, bias, act, vec_ok, out)
+  gemm_f16_skinny_kernel<TM_, U_, SPLIT, OutT><<<grid, blk, 0, s>>>(A, B, Bp, M, N, K, splits, out.tpos, bias, act, vec_ok, out)
   if (M <= 32) {
     switch (skinny_unroll(per_wave, 16)) {
       case 16: LSQ_SKINNY(1, 16); break;
@@ -530,11 +533,12 @@ static void run_skinny(const half_t* A, const half_t* B, const half_t* Bp, const
 // 8s+4+i -- any pairing of k does, as long as both operands use the same one.  U steps in flight.
 template <int TM, int U>
 __global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                              int M, int N, int K, const float* __restrict__ bias,
-                                                              int act, int vec_ok, GemmOut out) {
+                                                              int M, int N, int K, const int32_t* __restrict__ tpos,
+                                                              const float* __restrict__ bias, int act, int vec_ok,
+                                                              GemmOut out) {
   __shared__ float red[4][TM][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long tp = out.tpos ? *out.tpos : 0;
+  const long tp = tpos ? *tpos : 0;   // the counter's address is among the first arguments: requested at once, awaited by the epilogue
   const int n0 = blockIdx.x * 32, mb = blockIdx.z * 32 * TM;
   const int fr = lane & 31, fk = (lane >> 5) * 4;
   const int ksteps = K / 8;                      // K % 8 == 0 is checked by the launcher
@@ -604,14 +608,15 @@ __global__ void __launch_bounds__(256) gemm_f32_stream_kernel(const float* __res
 template <int U, typename OutT>
 __global__ void __launch_bounds__(256) gemm_f16_skinny_ln_kernel(const half_t* __restrict__ Bp,
                                                                  const half_t* __restrict__ B, int M, int N, int K,
-                                                                 LnInput ln, const half_t* __restrict__ bias,
-                                                                 int act, int vec_ok, GemmOut out) {
+                                                                 const int32_t* __restrict__ tpos, LnInput ln,
+                                                                 const half_t* __restrict__ bias, int act,
+                                                                 int vec_ok, GemmOut out) {
   constexpr int NV = 2;   // K <= 1024: a lane owns at most two 8-element pieces of a row
   extern __shared__ __attribute__((aligned(16))) half_t a_rows[];   // [M][K + 8]
   __shared__ float red[4][16][64];
   const int LDA = K + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long tp = out.tpos ? *out.tpos : 0;
+  const long tp = tpos ? *tpos : 0;   // the counter's address is among the first arguments: requested at once, awaited by the epilogue
   const int n0 = blockIdx.x * 32;
   const int fr = lane & 31, fk = (lane >> 5) * 8;
   const int ksteps = K / 16;
@@ -715,8 +720,8 @@ hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, co
   const half_t* bi = (const half_t*)bias;
 #define LSQ_SKINNY_LN(U_)                                                                                          \
   do {                                                                                                             \
-    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(bpk, b, M, N, K, ln, bi, act, vec_ok, out); \
-    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(bpk, b, M, N, K, ln, bi, act, vec_ok, out);      \
+    if (out.f32_out) gemm_f16_skinny_ln_kernel<U_, float><<<grid, blk, lds, s>>>(bpk, b, M, N, K, out.tpos, ln, bi, act, vec_ok, out); \
+    else gemm_f16_skinny_ln_kernel<U_, half_t><<<grid, blk, lds, s>>>(bpk, b, M, N, K, out.tpos, ln, bi, act, vec_ok, out);      \
   } while (0)
   switch (skinny_unroll(per_wave, 16)) {
     case 16: LSQ_SKINNY_LN(16); break;
@@ -744,7 +749,7 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, int threads, hipStrea
       raised = true;
     }
   }
-  kern<<<grid, dim3(threads), lds, s>>>(A, B, M, N, K, bias, act, vec_ok, out);
+  kern<<<grid, dim3(threads), lds, s>>>(A, B, M, N, K, (int)grid.y, out.tpos, bias, act, vec_ok, out);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int D, int KG = 1>
@@ -799,7 +804,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   }
   dim3 grid(((N + 63) / 64) * ((M + 63) / 64), splits), blk(256);
   gemm_f16_kernel<64, 64, 64, 32, 32, 4, false, true, float><<<grid, blk, gemm_lds_bytes<64, 64, 64>(), s>>>(
-      (const half_t*)A, (const half_t*)B, M, N, K, nullptr, 0, vec_ok, out);
+      (const half_t*)A, (const half_t*)B, M, N, K, splits, out.tpos, nullptr, 0, vec_ok, out);
   return hipGetLastError();
 }
 
@@ -822,16 +827,16 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
       const int per_wave = (K / 8 + 3) / 4;
       if (M <= 32) {
         dim3 grid((N + 31) / 32, 1, 1), blk(256);
-        if (per_wave <= 8) gemm_f32_stream_kernel<1, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
-        else gemm_f32_stream_kernel<1, 16><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
+        if (per_wave <= 8) gemm_f32_stream_kernel<1, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, out.tpos, bi, act, vec_ok, out);
+        else gemm_f32_stream_kernel<1, 16><<<grid, blk, 0, s>>>(a, b, M, N, K, out.tpos, bi, act, vec_ok, out);
       } else {
         dim3 grid((N + 31) / 32, 1, (M + 63) / 64), blk(256);
-        gemm_f32_stream_kernel<2, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, bi, act, vec_ok, out);
+        gemm_f32_stream_kernel<2, 8><<<grid, blk, 0, s>>>(a, b, M, N, K, out.tpos, bi, act, vec_ok, out);
       }
       return hipGetLastError();
     }
     dim3 grid((N + 63) / 64, (M + 63) / 64), blk(256);   // odd K or unaligned operands: the plain tile kernel
-    gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, M, N, K, (const float*)bias, act, out);
+    gemm_f32_kernel<<<grid, blk, 0, s>>>((const float*)A, (const float*)B, M, N, K, out.tpos, (const float*)bias, act, out);
     return hipGetLastError();
   }
   if (K % 8 != 0) return hipErrorInvalidValue;
