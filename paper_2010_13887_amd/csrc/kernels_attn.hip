@@ -290,7 +290,9 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
   constexpr int NW = SPLIT ? 4 : 1;  // wavefronts that share a (sentence, head)
   __shared__ float part[SPLIT ? 4 : 1][NQ][DH + 2];   // SPLIT: per wavefront and query the sums, then max and sum
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int w = SPLIT ? blockIdx.x : blockIdx.x * 4 + wave;
+  // one (sentence, head) per wavefront: its number, and with it the sentence's length, first row
+  // and the bases below, live in scalar registers
+  const int w = SPLIT ? blockIdx.x : __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave);
   if (w >= batch * H) return;
   const int b = w / H, h = w % H;
   const int c = lane % LPK, slot = lane / LPK;
@@ -304,18 +306,18 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
 #pragma unroll
   for (int n = 0; n < NQ; ++n) qr[n] = Vec8<T>::load_raw(q + ((size_t)b * beam + first + n) * d + h * DH + c * 8);
   int n_keys = len[b], row0 = off[b];
-  asm volatile("" : "+v"(n_keys), "+v"(row0));
-  const T* K = kv + (size_t)row0 * 2 * d + h * DH + c * 8;
-  const T* V = K + d;
-  const long stride = 2 * d;
+  asm volatile("" : "+s"(n_keys), "+s"(row0));
+  const char* K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  const char* V = K + d * sizeof(T);
+  const unsigned stride = 2 * d * sizeof(T), lane_at = c * 8 * sizeof(T);   // a lane's part of the address: 32-bit byte offsets
   const float qscale = scale * 1.44269504088896340736f;   // scores in units of log 2, as in attend_partial
   raw_t kn[G], vn[G];   // the trip that is on its way
   auto request = [&](int j0) {
 #pragma unroll
     for (int u = 0; u < G; ++u) {
-      const int j = min(j0 + u * KPW + slot, n_keys - 1);
-      kn[u] = Vec8<T>::load_raw(K + (long)j * stride);
-      vn[u] = Vec8<T>::load_raw(V + (long)j * stride);
+      const unsigned at = (unsigned)min(j0 + u * KPW + slot, n_keys - 1) * stride + lane_at;
+      kn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(K + at));
+      vn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(V + at));
     }
   };
   const int jfirst = SPLIT ? wave * G * KPW : 0;
