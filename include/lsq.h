@@ -239,7 +239,9 @@ int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_b
 
 /* Decoder self-attention of one new position per row over its cached keys:
  * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions
- * 0..nkeys-1 of Kc/Vc [rows, T, d]. */
+ * 0..nkeys-1 of Kc/Vc [rows, T, d].  Positions nkeys..T-1 of a row may be read
+ * too (requested before the length is known, then discarded whatever they
+ * hold), never anything outside [rows, T, d].  T*d*4 must fit 32 bits. */
 int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out,
                          int rows, int heads, int d, int T, int nkeys, void* stream);
 
@@ -248,7 +250,8 @@ int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* V
  * sentence b starting at row src_off[b] (both int32, device).  max_src_len: a
  * the longest of src_len[] as the host knows it (or an upper bound), at least
  * 1; it only picks the launch geometry: one wavefront per (sentence, head), or
- * four when few sentences are left and the longest one has many keys. */
+ * four when few sentences are left and the longest one has many keys.  One
+ * sentence's keys and values must span less than 4 GiB. */
 int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_t* src_off,
                           const int32_t* src_len, void* out, int batch, int beam, int heads, int d,
                           int max_src_len, void* stream);
@@ -257,7 +260,8 @@ int lsq_k_cross_attention(int dtype, const void* q, const void* kv, const int32_
  * prompt prefill of a decoder-only model): qkv [rows, 3d] = [Q | K | V], row i
  * belongs to sequence row_seq[i], whose rows are seq_off[b] .. seq_off[b] +
  * seq_len[b] - 1 (all int32, device).  Row i attends every row of its sequence,
- * or with causal only those up to itself.  out [rows, d]. */
+ * or with causal only those up to itself.  out [rows, d].  rows*3*d*4 must
+ * fit 32 bits. */
 int lsq_k_encoder_attention(int dtype, const void* qkv, const int32_t* row_seq, const int32_t* seq_off,
                             const int32_t* seq_len, void* out, int rows, int heads, int d, int causal,
                             void* stream);
@@ -291,7 +295,9 @@ int lsq_k_beam_refine_table(const float* cand_score, const int32_t* cand_idx, fl
 
 /* Self-attention through the slab table: as lsq_k_self_attention, but position j
  * of row r is read from cache row (r - r mod beam) + slab[r*(T+1) + j].
- * rows must be a multiple of beam. */
+ * rows must be a multiple of beam; beam*T*d*4 must fit 32 bits.  Table entries
+ * at j >= nkeys may hold anything (a value read from there is forced into
+ * 0..beam-1 before it forms an address, and what it fetches is discarded). */
 int lsq_k_self_attention_table(int dtype, const void* q, const void* Kc, const void* Vc,
                                const int32_t* slab, void* out, int rows, int beam, int heads, int d,
                                int T, int nkeys, void* stream);

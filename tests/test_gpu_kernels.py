@@ -186,6 +186,8 @@ def test_self_attention(env, rows, H, dh, T, nkeys, half):
     cast = _h if half else (lambda a: np.asarray(a, np.float32))
     q = cast(rng.standard_normal((rows, d)))
     Kc, Vc = cast(rng.standard_normal((rows, T, d))), cast(rng.standard_normal((rows, T, d)))
+    Kc[:, nkeys:] = np.nan                                 # positions past the history may be read, and must not matter
+    Vc[:, nkeys:] = np.inf
     td = torch.float16 if half else torch.float32
     out = torch.full((rows, d), 7.0, dtype=td, device="cuda")
     lsq.k_self_attention(_dev(torch, q, td), _dev(torch, Kc, td), _dev(torch, Vc, td), out, H, nkeys)
@@ -208,7 +210,9 @@ def test_self_attention_through_slab_table(env, B, k, H, dh, T, nkeys, half):
     q = cast(rng.standard_normal((rows, d)))
     Kc, Vc = cast(rng.standard_normal((rows, T, d))), cast(rng.standard_normal((rows, T, d)))
     slab = rng.integers(0, k, size=(rows, T + 1)).astype(np.int32)
-    slab[:, nkeys:] = 1 << 20                              # entries past the history must never be read
+    slab[:, nkeys:] = rng.choice([1 << 20, -5, k, -(1 << 30)], size=(rows, T + 1 - nkeys))   # entries past the history
+    Kc[:, nkeys:] = np.nan                                 # and cache positions past it may be read (the first request
+    Vc[:, nkeys:] = np.nan                                 # does not wait for the length), and must not matter
     td = torch.float16 if half else torch.float32
     out = torch.full((rows, d), 7.0, dtype=td, device="cuda")
     lsq.k_self_attention_table(_dev(torch, q, td), _dev(torch, Kc, td), _dev(torch, Vc, td), _dev(torch, slab), out, k, H, nkeys)
