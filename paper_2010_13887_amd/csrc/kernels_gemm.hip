@@ -864,6 +864,12 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     // more 64x64 tiles than CUs: eight wavefronts on a 64x128 tile move fewer operand bytes per FLOP
     // into the CU and keep its LDS pipe as busy as two four-wave workgroups would
     run_f16<64, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
+  else if ((long)((M + 63) / 64) * ((N + 63) / 64) <= 128)
+    // 64x64 tiles would leave half of the CUs or more without one: 32x64 tiles reach twice as many, and
+    // each workgroup takes in 12 instead of 16 KB per k-tile (two wave tiles, two k-groups each);
+    // measured on whole steps: 0.480 -> 0.460 ms at 128 rows of the big model, 0.491 -> 0.486 on big128
+    // (32x32 tiles with four k-groups were no better)
+    run_f16<32, 64, 64, 32, 32, 4, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else
     // at most one 64x64 tile per CU: a second set of four wavefronts multiplies the other half of
     // every k-tile (0.5-0.7 us off a 1024-deep product)
