@@ -177,7 +177,8 @@ def test_layernorm_inside_product(env, rows, d, N, splits, f32_out):
 
 @pytest.mark.parametrize("rows,H,dh,T,nkeys", [(3, 4, 16, 8, 1), (9, 4, 16, 8, 8), (32, 8, 64, 110, 77),
                                                (5, 2, 128, 40, 33), (7, 3, 32, 50, 50), (130, 16, 64, 178, 41),
-                                               (300, 8, 64, 60, 60), (2, 2, 16, 200, 199)])
+                                               (300, 8, 64, 60, 60), (2, 2, 16, 200, 199), (5, 2, 16, 1, 1),
+                                               (600, 4, 32, 3, 2)])
 @pytest.mark.parametrize("half", [False, True])
 def test_self_attention(env, rows, H, dh, T, nkeys, half):
     lsq, torch = env
@@ -198,7 +199,8 @@ def test_self_attention(env, rows, H, dh, T, nkeys, half):
 
 
 @pytest.mark.parametrize("B,k,H,dh,T,nkeys", [(2, 4, 4, 16, 8, 1), (3, 4, 8, 64, 110, 77), (5, 3, 2, 32, 50, 50),
-                                              (75, 4, 8, 64, 60, 41), (2, 8, 2, 128, 40, 33), (4, 1, 4, 16, 9, 9)])
+                                              (75, 4, 8, 64, 60, 41), (2, 8, 2, 128, 40, 33), (4, 1, 4, 16, 9, 9),
+                                              (3, 4, 2, 16, 1, 1), (140, 4, 4, 32, 2, 1)])
 @pytest.mark.parametrize("half", [False, True])
 def test_self_attention_through_slab_table(env, B, k, H, dh, T, nkeys, half):
     """Position j of row r is read from cache row (r - r % k) + slab[r, j]: equals attention over the
