@@ -5,7 +5,7 @@
 // Lane layout: a head row of DH elements is split over LPK = DH/8 lanes (8 elements each), so a
 // wavefront covers KPI = 64/LPK keys per iteration.  Each lane group runs its own online softmax
 // (running max, running sum, running value accumulator) over the keys it sees; the groups are
-// merged by shuffles at the end.  Masking is by key count: keys beyond it are never read.
+// merged across lanes at the end.  Masking is by key count: what lies beyond it never reaches a sum.
 #include "lsq_internal.h"
 
 namespace lsq {
@@ -272,8 +272,8 @@ __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __re
 // slot, 8-element chunk): DH/8 lanes share a key, 64/(DH/8) keys per pass.  A lane requests the key
 // and the value chunks of its keys of G passes at once (32 keys at head size 64: one round trip
 // for the usual sentence), dots the key chunks with the NQ query chunks (summed over the chunk
-// lanes by shuffles) and updates a running maximum, a running sum and an unnormalised weighted
-// value sum per query (the usual streaming softmax); the key slots add theirs up by shuffles at
+// lanes) and updates a running maximum, a running sum and an unnormalised weighted
+// value sum per query (the usual streaming softmax); the key slots add theirs up across lanes at
 // the end.  Measured against a workgroup per (sentence, head) with the scores in LDS (two barriers,
 // values fetched after the softmax): 7.9 instead of 13.3 us for 128 sentences of 28 keys, 17.8
 // instead of 26.7 us at 128 keys; more passes in flight per wavefront were slower, not faster.

@@ -74,7 +74,7 @@ hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const in
 // ---------------------------------------------------------------------------------------------
 // Residual + LayerNorm in one launch with no intermediate (paper sec. 2.1): one wavefront per row,
 // the row held in registers (NV vectors of 8 per lane), mean then centred variance (biased), both
-// by wave shuffles.  The sublayer output arrives as `splits` fp32 partial-sum slabs
+// by reductions over the wavefront.  The sublayer output arrives as `splits` fp32 partial-sum slabs
 // P[s][rows][d] (the split-K GEMM's output, still without its bias):
 //   x <- store(LN(x + (sum_s P[s] + bias)) * g + b).
 // The slabs are added in index order, so the result is independent of how the GEMM was scheduled.
