@@ -237,6 +237,22 @@ int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_b
                          const void* beta, const void* x_old, void* x_new, float eps, const void* W,
                          const void* bias, void* C, int M, int N, int K, int flags, void* stream);
 
+/* Cross-attention that normalises its rows and makes its queries itself (the
+ * last one or two sentences of a batch, where fewer launches matter most;
+ * paper sec. 2.1 taken one step further): for every sentence b and head h,
+ *   rows  = LN(x_old + sum_s P[s] + ln_bias)            (as lsq_k_layernorm_gemm; written to x_new)
+ *   q     = rows . Wq[h*64:(h+1)*64, :]^T + bq[h*64:..]   (rounded to float16)
+ *   out   = lsq_k_cross_attention(q, kv, ...)
+ * float16 only; batch*beam <= 8 rows, beam <= 4, heads of 64, d = 64*heads <=
+ * 1024.  Wq_packed: the fragment-ordered copy of Wq [d, d] made by
+ * lsq_k_pack_weights; P float [splits <= 4, batch*beam, d]; x_old and x_new
+ * different buffers; everything else as in lsq_k_cross_attention. */
+int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_bias, const void* gamma,
+                                    const void* beta, const void* x_old, void* x_new, float eps,
+                                    const void* Wq_packed, const void* bq, const void* kv,
+                                    const int32_t* src_off, const int32_t* src_len, void* out, int batch,
+                                    int beam, int heads, int d, void* stream);
+
 /* Decoder self-attention of one new position per row over its cached keys:
  * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions
  * 0..nkeys-1 of Kc/Vc [rows, T, d].  Positions nkeys..T-1 of a row may be read

@@ -52,6 +52,8 @@ def load_library() -> C.CDLL:
         "lsq_set_diversity": [i32, f32],
         "lsq_set_layernorm_fusion": [i32],
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_layernorm_cross_attention": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, i32, i32,
+                                            i32, vp],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -259,6 +261,17 @@ def k_layernorm_gemm(P, ln_bias, gamma, beta, x_old, x_new, eps: float, W, bias,
     flags = int(relu) | (2 if C_out.dtype == torch.float32 else 0)
     _check(load_library().lsq_k_layernorm_gemm(_dt(x_old), _p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old),
                                                _p(x_new), eps, _p(W), _p(bias), _p(C_out), M, N, K, flags, _stream()))
+
+
+def k_layernorm_cross_attention(P, ln_bias, gamma, beta, x_old, x_new, eps: float, Wq_packed, bq, kv, src_off, src_len,
+                                out, batch: int, beam: int, heads: int) -> None:
+    """out = cross-attention of q = LN(x_old + sum of the slabs P + ln_bias) . Wq^T + bq; x_new receives the normalised
+    rows.  Wq_packed: k_pack_weights(Wq)."""
+    splits, M, d = P.shape
+    assert M == batch * beam
+    _check(load_library().lsq_k_layernorm_cross_attention(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old),
+                                                          _p(x_new), eps, _p(Wq_packed), _p(bq), _p(kv), _p(src_off),
+                                                          _p(src_len), _p(out), batch, beam, heads, d, _stream()))
 
 
 def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:

@@ -412,6 +412,239 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
   }
 }
 
+// Cross-attention that makes its own queries, for the last one or two sentences of a batch, where
+// a step is a chain of launches that each cost their latency: the query product of those few rows
+// (32 workgroups that each re-do the LayerNorm and stream 64 KB of Wq) and the attention kernel
+// become one.  One workgroup per (sentence, head):
+//   1. requests its 64 x d slice of Wq (fragment order), the sentence's length and first row, then
+//      its first keys and values: everything the kernel reads from memory is on its way before
+//      anything is computed;
+//   2. wavefront w normalises row w of the sentence's NQ rows (the arithmetic of
+//      gemm_f16_skinny_ln_kernel, so the rows are the same bits) into LDS, head 0 also to x_new;
+//   3. q = rows . slice^T: eight wavefronts, four per 32-column half, each taking every fourth
+//      16-wide k-step of its half; partial tiles are added through LDS (in the order of the skinny
+//      kernels: the queries are the same bits), bias added, rounded to float16 as the stored q of
+//      the separate kernels is;
+//   4. the first four wavefronts attend as cross_attention_kernel's four-wavefront variant does.
+template <int NQ>
+__global__ void __launch_bounds__(512) cross_attention_ln_kernel(const half_t* __restrict__ Wp,
+                                                                 const half_t* __restrict__ kv,
+                                                                 const int32_t* __restrict__ off,
+                                                                 const int32_t* __restrict__ len, int beam, int H,
+                                                                 int d, int M, LnInput ln,
+                                                                 const half_t* __restrict__ bq,
+                                                                 half_t* __restrict__ out) {
+  constexpr int DH = 64, LPK = 8, KPW = 8, G = 4, NV = 2, UMAX = 16;
+  constexpr float scale = 0.125f;
+  using raw_t = half8_t;
+  __shared__ __attribute__((aligned(16))) half_t a_rows[NQ][1024 + 8];
+  __shared__ float red[8][16][64];
+  __shared__ float q_s[NQ][DH];
+  __shared__ float part[4][NQ][DH + 2];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int ksteps = d / 16, per_wave = ksteps / 4;   // d is a multiple of 64
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int cb = wave >> 2, kw = wave & 3;            // product: column half and k-share of this wavefront
+  // 1. requests: this wavefront's share of the slice (16 fragments: all 128 KB of the slice are on
+  // their way at once, 16 KB per wavefront), then length and first row, then the first keys
+  const half_t* wp = Wp + ((size_t)(h * 2 + cb) * ksteps) * 512 + lane * 8;
+  half8_t bf[UMAX];
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u) bf[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(kw + 4 * u, ksteps - 1) * 512);
+  int n_keys = len[b], row0 = off[b];
+  asm volatile("" : "+s"(n_keys), "+s"(row0));
+  const int c = lane % LPK, slot = lane / LPK;
+  const char* K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  const char* V = K + d * sizeof(half_t);
+  const unsigned stride = 2 * d * sizeof(half_t), lane_at = c * 8 * sizeof(half_t);
+  raw_t kn[G], vn[G];
+  auto request = [&](int j0) {
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const unsigned at = (unsigned)min(j0 + u * KPW + slot, n_keys - 1) * stride + lane_at;
+      kn[u] = *reinterpret_cast<const raw_t*>(K + at);
+      vn[u] = *reinterpret_cast<const raw_t*>(V + at);
+    }
+  };
+  // the first four wavefronts attend (step 4); the others have no keys
+  const int jfirst = wave < 4 ? wave * G * KPW : 0x7fffffff;
+  if (jfirst < n_keys) request(jfirst);
+  // 2. LayerNorm of row (b * beam + wave)
+  if (wave < NQ) {
+    const int r = b * beam + wave;
+    const size_t slab = (size_t)M * d;
+    float v[NV][8], gv[NV][8], bv[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int cc = (j * 64 + lane) * 8;
+      if (cc < d) {
+        float t[8], prt[4][8];
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp)
+          if (sp < ln.splits) Vec8<float>::load(ln.P + sp * slab + (size_t)r * d + cc, prt[sp]);
+        Vec8<half_t>::load(ln.bias + cc, t);
+        Vec8<half_t>::load(ln.x_old + (size_t)r * d + cc, v[j]);
+        Vec8<half_t>::load(ln.g + cc, gv[j]);
+        Vec8<half_t>::load(ln.b + cc, bv[j]);
+        add_partials<4>(v[j], prt, ln.splits, t);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
+      }
+    }
+    float o[NV][8];
+    layernorm_row<NV>(v, gv, bv, d, ln.eps, lane, o);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int cc = (j * 64 + lane) * 8;
+      if (cc < d) {
+        Vec8<half_t>::store(&a_rows[wave][cc], o[j]);
+        if (h == 0) Vec8<half_t>::store(ln.x_new + (size_t)r * d + cc, o[j]);
+      }
+    }
+  }
+  __syncthreads();
+  // 3. the head's 64 query columns of the NQ rows (rows past NQ repeat the last one; never stored):
+  // wavefront (cb, kw) multiplies every fourth k-step of column half cb
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  const half_t* ar = &a_rows[min(fr, NQ - 1)][fk];
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u)
+    if (u < per_wave) {
+      const half8_t af = *reinterpret_cast<const half8_t*>(ar + (kw + 4 * u) * 16);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af, acc, 0, 0, 0);
+    }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
+  __syncthreads();
+  {
+    // accumulator element vg*4 + e of lane (m, half) is column vg*8 + half*4 + e of row m (the
+    // layout of the skinny kernels' epilogue); wavefront (cb, vg) finishes those of its half
+    const int vg = kw, m = lane & 31;
+    if (m < NQ) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int rr = vg * 4 + e, n = cb * 32 + vg * 8 + (lane >> 5) * 4 + e;
+        float x = (red[cb * 4 + 0][rr][lane] + red[cb * 4 + 1][rr][lane]) + (red[cb * 4 + 2][rr][lane] + red[cb * 4 + 3][rr][lane]);
+        x += (float)bq[h * DH + n];
+        q_s[m][n] = (float)(half_t)x;
+      }
+    }
+  }
+  __syncthreads();
+  // 4. attention, four wavefronts sharing the keys
+  const float qscale = scale * 1.44269504088896340736f;
+  float qv[NQ][8];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qv[n][i] = q_s[n][c * 8 + i];
+  float mx_[NQ], l_[NQ], acc_[NQ][8];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    mx_[n] = -INFINITY;
+    l_[n] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc_[n][i] = 0.f;
+  }
+  for (int j0 = jfirst; j0 < n_keys; j0 += 4 * G * KPW) {
+    raw_t kk[G], vv[G];
+#pragma unroll
+    for (int u = 0; u < G; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
+    if (j0 + 4 * G * KPW < n_keys) request(j0 + 4 * G * KPW);
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      float sc[G], mx = mx_[n];
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        float kf[8], sdot = 0.f;
+        Vec8<half_t>::unpack(kk[u], kf);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
+        sdot = group_sum<LPK>(sdot);
+        sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * qscale : -INFINITY;
+        mx = fmaxf(mx, sc[u]);
+      }
+      for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });
+      const float corr = __builtin_amdgcn_exp2f(mx_[n] - mx);
+      mx_[n] = mx;
+      l_[n] *= corr;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc_[n][i] *= corr;
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        float vf[8];
+        Vec8<half_t>::unpack(vv[u], vf);
+        const float pj = __builtin_amdgcn_exp2f(sc[u] - mx);
+        l_[n] += pj;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc_[n][i] += pj * vf[i];
+      }
+    }
+  }
+  if (wave < 4) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      for_lane_bits<LPK>([&](auto bit) {
+        constexpr int O = decltype(bit)::value;
+        l_[n] = add_lane_xor<O>(l_[n]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc_[n][i] = add_lane_xor<O>(acc_[n][i]);
+      });
+      if (slot == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[wave][n][c * 8 + i] = acc_[n][i];
+        if (c == 0) { part[wave][n][DH] = mx_[n]; part[wave][n][DH + 1] = l_[n]; }
+      }
+    }
+  }
+  __syncthreads();
+  for (int n = wave; n < NQ; n += 4) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, part[w2][n][DH]);
+    float sum = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
+    for (int x = lane; x < DH; x += 64) {
+      float vsum = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) vsum += part[w2][n][x] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
+      out[((size_t)b * beam + n) * d + h * DH + x] = (half_t)(vsum / sum);
+    }
+  }
+}
+
+bool cross_attention_ln_supported(int dtype, int rows, int beam, int H, int d) {
+  return dtype == DT_F16 && rows >= 1 && rows <= 8 && beam >= 1 && beam <= 4 && rows % beam == 0 && H >= 1 &&
+         d == H * 64 && d <= 1024 && d % 64 == 0;
+}
+
+hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, const void* bq, const void* kv,
+                                     const int32_t* off, const int32_t* len, void* out, int batch, int beam,
+                                     int H, int d, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  if (!cross_attention_ln_supported(DT_F16, batch * beam, beam, H, d) || !Wq_packed || !bq || ln.splits < 1 ||
+      ln.splits > 4 || ln.x_old == ln.x_new)
+    return hipErrorInvalidValue;
+  dim3 g(batch * H), b(512);
+  const int M = batch * beam;
+#define LSQ_CROSS_LN(NQ_)                                                                                    \
+  cross_attention_ln_kernel<NQ_><<<g, b, 0, s>>>((const half_t*)Wq_packed, (const half_t*)kv, off, len, beam, H, d, M, ln, \
+                                                  (const half_t*)bq, (half_t*)out)
+  switch (beam) {
+    case 1: LSQ_CROSS_LN(1); break;
+    case 2: LSQ_CROSS_LN(2); break;
+    case 3: LSQ_CROSS_LN(3); break;
+    default: LSQ_CROSS_LN(4); break;
+  }
+#undef LSQ_CROSS_LN
+  return hipGetLastError();
+}
+
 // Encoder self-attention over packed sentences: qkv rows are [Q | K | V]; row i belongs to
 // sentence row_sent[i] whose rows start at off[.] and number len[.].
 template <typename T, int DH>

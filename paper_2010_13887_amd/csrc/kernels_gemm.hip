@@ -396,6 +396,8 @@ void gemm_register_packed(const void* plain, const void* packed, int N, int K) {
   g_packed[plain] = PackedEntry{(const half_t*)packed, N, K};
 }
 
+const void* gemm_packed_weights(const void* plain, int N, int K) { return packed_of(plain, N, K); }
+
 void gemm_clear_packed() { g_packed.clear(); }
 
 // ---------------------------------------------------------------------------------------------

@@ -58,6 +58,8 @@ size_t gemm_packed_bytes(int N, int K);
 hipError_t launch_pack_weights(const void* plain, void* packed, int N, int K, hipStream_t s);
 void gemm_register_packed(const void* plain, const void* packed, int N, int K);
 void gemm_clear_packed();
+// the registered fragment-ordered copy of a row-major matrix, or nullptr
+const void* gemm_packed_weights(const void* plain, int N, int K);
 
 // A product that makes its own input: A = LayerNorm(x_old + sum of `splits` fp32 slabs P[s][M][K] + bias) * g + b,
 // rounded to float16; the rows are also written to x_new (not the same buffer as x_old).  For the few-row end
@@ -101,6 +103,15 @@ bool cross_attention_splits(int units, int smax);
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
                                   const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
                                   hipStream_t s);
+// The tail of a batch (at most 8 rows alive, beams of 4 at most, head size 64, float16): the
+// cross-attention kernel makes its own queries, q = LayerNorm(x_old + partial sums + bias) . Wq^T
+// + bq for the head it serves, from the fragment-ordered copy of Wq (gemm_packed_weights), instead
+// of a product kernel of 32 workgroups followed by an attention kernel.  The workgroups of head 0
+// write the normalised rows to ln.x_new.
+bool cross_attention_ln_supported(int dtype, int rows, int beam, int H, int d);
+hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, const void* bq, const void* kv,
+                                     const int32_t* off, const int32_t* len, void* out, int batch, int beam,
+                                     int H, int d, hipStream_t s);
 hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent,
                                     const int32_t* off, const int32_t* len, void* out, int rows, int H,
                                     int d, int causal, hipStream_t s);

@@ -399,9 +399,20 @@ int launch_step(int B) {
     if (int rc = product(PC_GEMM_QKV, L.Wqkv, L.bqkv, o, 3 * d, 0)) return rc;
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, anc, k, T + 1, s));
     if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d)) return rc;
-    if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
-    TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
-                                  at<int32_t>(p.src_len), ctx, B, k, H, d, g.src_longest, s));
+    const void* wq_packed = pending.on && cross_attention_ln_supported(dt, M, k, H, d) ? gemm_packed_weights(L.Wq, d, d) : nullptr;
+    if (wq_packed) {
+      // the last sentences of a batch: the attention kernel normalises its rows and makes its queries itself
+      LnInput ln = {(const float*)tmp, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
+                    (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
+      TIMED(PC_ATTN_CROSS, launch_cross_attention_ln(ln, wq_packed, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+                                                     at<int32_t>(p.src_len), ctx, B, k, H, d, s));
+      std::swap(x, x_alt);
+      pending.on = false;
+    } else {
+      if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
+      TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+                                                  at<int32_t>(p.src_len), ctx, B, k, H, d, g.src_longest, s));
+    }
     if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d)) return rc;
     if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
     if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F)) return rc;
@@ -1123,6 +1134,20 @@ int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_b
                 (half_t*)x_new, eps};
   KRUN(launch_gemm_ln(ln, W, bias, o, M, N, K, (flags & LSQ_GEMM_RELU) ? 1 : ((flags & LSQ_GEMM_GELU) ? 2 : 0),
                       (hipStream_t)stream));
+}
+
+int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_bias, const void* gamma,
+                                    const void* beta, const void* x_old, void* x_new, float eps, const void* Wq_packed,
+                                    const void* bq, const void* kv, const int32_t* src_off, const int32_t* src_len,
+                                    void* out, int batch, int beam, int heads, int d, void* stream) {
+  KCHK(P && ln_bias && gamma && beta && x_old && x_new && Wq_packed && bq && kv && src_off && src_len && out, "null pointer");
+  KCHK(x_old != x_new, "x_new must not be x_old");
+  KCHK(batch >= 0 && splits >= 1 && splits <= 4, "shape");
+  KCHK(batch == 0 || cross_attention_ln_supported(DT_F16, batch * beam, beam, heads, d),
+       "float16, at most 8 rows, beam 1..4, heads of 64, d a multiple of 64 up to 1024");
+  LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
+                (half_t*)x_new, eps};
+  KRUN(launch_cross_attention_ln(ln, Wq_packed, bq, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
 }
 
 int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out, int rows, int heads,

@@ -275,6 +275,51 @@ def test_cross_attention(env, lens, beam, H, dh, half):
     np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=tol, atol=tol)
 
 
+@pytest.mark.parametrize("lens,beam,H,splits", [([5], 4, 16, 4), ([130, 7], 4, 16, 2), ([33, 60], 3, 8, 1), ([1, 2, 90, 49], 2, 4, 4),
+                                               ([257], 1, 1, 3), ([40, 40, 41, 200, 9, 64, 64, 3], 1, 16, 4)])
+def test_cross_attention_that_makes_its_queries(env, lens, beam, H, splits):
+    """LayerNorm + query product + attention in one kernel: the normalised rows are bit-identical to those of
+    the product kernel that normalises its input, the queries are the same bits too, so the output equals
+    attention over those queries (up to the order in which the keys are summed), and the oracle's."""
+    lsq, torch = env
+    rng = np.random.default_rng(sum(lens) * 7 + beam + H)
+    d, B = H * 64, len(lens)
+    rows = B * beam
+    x = _h(rng.standard_normal((rows, d)) * 2)
+    P = (rng.standard_normal((splits, rows, d)) * 0.5).astype(np.float32)
+    lb, g, b = _h(rng.standard_normal(d) * 0.3), _h(1 + 0.3 * rng.standard_normal(d)), _h(0.3 * rng.standard_normal(d))
+    Wq, bq = _h(rng.standard_normal((d, d)) * 0.05), _h(rng.standard_normal(d) * 0.5)
+    kv = _h(rng.standard_normal((sum(lens), 2 * d)))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    h = torch.float16
+    dx, dP, dkv = _dev(torch, x, h), _dev(torch, P), _dev(torch, kv, h)
+    dlb, dg, db, dW, dbq = (_dev(torch, a, h) for a in (lb, g, b, Wq, bq))
+    doff, dlen = _dev(torch, off), _dev(torch, np.array(lens, np.int32))
+    packed = lsq.k_pack_weights(dW)
+    x_new = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    out = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    lsq.k_layernorm_cross_attention(dP, dlb, dg, db, dx, x_new, 1e-5, packed, dbq, dkv, doff, dlen, out, B, beam, H)
+    assert torch.equal(dx, _dev(torch, x, h))                       # the residual input is left alone
+    # the separate kernels: product that normalises its input, then attention
+    x_new2 = torch.full_like(x_new, 9.0)
+    q2 = torch.empty((rows, d), dtype=h, device="cuda")
+    lsq.k_layernorm_gemm(dP, dlb, dg, db, dx, x_new2, 1e-5, dW, dbq, q2)
+    assert torch.equal(x_new, x_new2)
+    out2 = torch.empty_like(out)
+    lsq.k_cross_attention(q2, dkv, doff, dlen, out2, B, beam, H, max(lens))
+    np.testing.assert_allclose(out.float().cpu().numpy(), out2.float().cpu().numpy(), rtol=2e-3, atol=2e-3)
+    # the oracle, from the queries the kernels made (their rounding to float16 is part of the path)
+    qf = q2.float().cpu().numpy()
+    ref = np.concatenate([O.attention(qf[i * beam:(i + 1) * beam].astype(np.float64),
+                                      kv[off[i]:off[i + 1], :d].astype(np.float64),
+                                      kv[off[i]:off[i + 1], d:].astype(np.float64), H) for i in range(B)])
+    np.testing.assert_allclose(out.float().cpu().numpy(), ref, rtol=1.5e-3, atol=1.5e-3)
+    # and the queries themselves against the oracle's rows
+    a = P.astype(np.float64).sum(0) + lb
+    rows_ref = O.layer_norm(x.astype(np.float64) + a, g.astype(np.float64), b.astype(np.float64), 1e-5)
+    np.testing.assert_allclose(qf, _h(rows_ref) @ Wq.astype(np.float64).T + bq, rtol=4e-3, atol=4e-3 * (1 + np.abs(qf).max()))
+
+
 def _oracle_row_topk(logits, score, finished, k, eos):
     """Per row: the oracle's candidate scores and a full sort."""
     M, V = logits.shape
