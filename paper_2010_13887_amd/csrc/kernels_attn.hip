@@ -266,6 +266,125 @@ __global__ void __launch_bounds__(256) self_attention_split_kernel(const T* __re
   }
 }
 
+// The key stream of cross-attention, shared by the two kernels below.  A wavefront's lanes are
+// (key slot, 8-element chunk): DH/8 lanes share a key, KPW = 64/(DH/8) keys per pass, G passes per
+// trip to memory.  K and V are the sentence's first key and value row of this head (the same in
+// every lane: scalar registers), a lane adds 32-bit byte offsets.
+template <typename T, int DH, int NQ>
+struct CrossKeys {
+  static constexpr int LPK = DH / 8, KPW = 64 / LPK, G = 4;
+  using raw_t = typename Vec8<T>::raw_t;
+  const char* K;
+  const char* V;
+  unsigned stride, lane_at;
+  int n_keys, slot;
+  raw_t kn[G], vn[G];   // the trip that is on its way
+
+  __device__ __forceinline__ void request(int j0) {
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const unsigned at = (unsigned)min(j0 + u * KPW + slot, n_keys - 1) * stride + lane_at;
+      kn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(K + at));
+      vn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(V + at));
+    }
+  }
+
+  // Trips j0 = jfirst, jfirst + jstep, ... < n_keys; the first one has been requested by the
+  // caller (if jfirst < n_keys), each later one is requested before the one before it is worked
+  // on.  Streaming softmax per query in units of log 2 (qscale = scale * log2 e): running maximum
+  // m, sum l of 2^(score - m), weighted value sum acc; on return the key slots have been added up.
+  __device__ __forceinline__ void run(const float (&qv)[NQ][8], float qscale, int jfirst, int jstep, float (&m)[NQ],
+                                      float (&l)[NQ], float (&acc)[NQ][8]) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      m[n] = -INFINITY;
+      l[n] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
+    }
+    for (int j0 = jfirst; j0 < n_keys; j0 += jstep) {
+      raw_t kk[G], vv[G];
+#pragma unroll
+      for (int u = 0; u < G; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
+      if (j0 + jstep < n_keys) request(j0 + jstep);   // travels while this trip is worked on
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        float sc[G], mx = m[n];
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          float kf[8], sdot = 0.f;
+          Vec8<T>::unpack(kk[u], kf);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
+          sdot = group_sum<LPK>(sdot);
+          sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * qscale : -INFINITY;
+          mx = fmaxf(mx, sc[u]);
+        }
+        for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });   // over the key slots
+        // mx is finite: key j0 exists
+        const float corr = __builtin_amdgcn_exp2f(m[n] - mx);   // 0 the first time (m = -inf)
+        m[n] = mx;
+        l[n] *= corr;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[n][i] *= corr;
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          float vf[8];
+          Vec8<T>::unpack(vv[u], vf);
+          const float pj = __builtin_amdgcn_exp2f(sc[u] - mx);   // masked keys: 2^-inf = 0
+          l[n] += pj;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[n][i] += pj * vf[i];
+        }
+      }
+    }
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+      for_lane_bits<LPK>([&](auto bit) {
+        constexpr int O = decltype(bit)::value;
+        l[n] = add_lane_xor<O>(l[n]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[n][i] = add_lane_xor<O>(acc[n][i]);
+      });
+  }
+};
+
+// Four wavefronts shared a (sentence, head): each leaves its sums, maximum and total in LDS
+// (`deposit`, wavefronts 0..3), and after the workgroup's barrier wavefront n finishes query n
+// (`finish`): a wavefront that had no keys left m = -inf, l = 0.  out_row0: row of query 0.
+template <int DH, int NQ>
+__device__ __forceinline__ void cross_deposit(float (&part)[4][NQ][DH + 2], int wave, int lane, const float (&m)[NQ],
+                                              const float (&l)[NQ], const float (&acc)[NQ][8]) {
+  constexpr int LPK = DH / 8;
+  const int c = lane % LPK;
+  if (lane / LPK != 0) return;
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[wave][n][c * 8 + i] = acc[n][i];
+    if (c == 0) { part[wave][n][DH] = m[n]; part[wave][n][DH + 1] = l[n]; }
+  }
+}
+template <typename T, int DH, int NQ>
+__device__ __forceinline__ void cross_finish(const float (&part)[4][NQ][DH + 2], int wave, int lane, T* __restrict__ out_row0,
+                                             int d) {
+  for (int n = wave; n < NQ; n += 4) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, part[w2][n][DH]);
+    float sum = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
+    for (int x = lane; x < DH; x += 64) {
+      float v = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) v += part[w2][n][x] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
+      out_row0[(size_t)n * d + x] = (T)(v / sum);
+    }
+  }
+}
+
 // Cross-attention: the NQ beams of one sentence share every key/value load.  kv rows are [K | V].
 // One wavefront per (sentence, head): no LDS, no barrier.  Source sentences are short (tens of
 // keys), so the work is organised to keep the fixed cost small rather than to stream.  Lane = (key
@@ -307,107 +426,33 @@ __global__ void __launch_bounds__(256) cross_attention_kernel(const T* __restric
   for (int n = 0; n < NQ; ++n) qr[n] = Vec8<T>::load_raw(q + ((size_t)b * beam + first + n) * d + h * DH + c * 8);
   int n_keys = len[b], row0 = off[b];
   asm volatile("" : "+s"(n_keys), "+s"(row0));
-  const char* K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
-  const char* V = K + d * sizeof(T);
-  const unsigned stride = 2 * d * sizeof(T), lane_at = c * 8 * sizeof(T);   // a lane's part of the address: 32-bit byte offsets
-  const float qscale = scale * 1.44269504088896340736f;   // scores in units of log 2, as in attend_partial
-  raw_t kn[G], vn[G];   // the trip that is on its way
-  auto request = [&](int j0) {
-#pragma unroll
-    for (int u = 0; u < G; ++u) {
-      const unsigned at = (unsigned)min(j0 + u * KPW + slot, n_keys - 1) * stride + lane_at;
-      kn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(K + at));
-      vn[u] = Vec8<T>::load_raw(reinterpret_cast<const T*>(V + at));
-    }
-  };
+  CrossKeys<T, DH, NQ> keys;
+  keys.K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  keys.V = keys.K + d * sizeof(T);
+  keys.stride = 2 * d * sizeof(T);
+  keys.lane_at = c * 8 * sizeof(T);
+  keys.n_keys = n_keys;
+  keys.slot = slot;
   const int jfirst = SPLIT ? wave * G * KPW : 0;
-  if (jfirst < n_keys) request(jfirst);
+  if (jfirst < n_keys) keys.request(jfirst);
   asm volatile("" ::: "memory");   // keeps the requests above what follows
   float qv[NQ][8];
 #pragma unroll
   for (int n = 0; n < NQ; ++n) Vec8<T>::unpack(qr[n], qv[n]);
   float m[NQ], l[NQ], acc[NQ][8];
-#pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    m[n] = -INFINITY;
-    l[n] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[n][i] = 0.f;
-  }
-  for (int j0 = jfirst; j0 < n_keys; j0 += NW * G * KPW) {
-    raw_t kk[G], vv[G];
-#pragma unroll
-    for (int u = 0; u < G; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
-    if (j0 + NW * G * KPW < n_keys) request(j0 + NW * G * KPW);   // travels while this trip is worked on
-    asm volatile("" ::: "memory");
+  keys.run(qv, scale * 1.44269504088896340736f, jfirst, NW * G * KPW, m, l, acc);
+  T* out_row0 = out + ((size_t)b * beam + first) * d + h * DH;
+  if constexpr (SPLIT) {
+    cross_deposit<DH, NQ>(part, wave, lane, m, l, acc);
+    __syncthreads();   // every wavefront of the workgroup gets here: none left early
+    cross_finish<T, DH, NQ>(part, wave, lane, out_row0, d);
+  } else if (slot == 0) {
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
-      float sc[G], mx = m[n];
+      const float r = 1.0f / l[n];
 #pragma unroll
-      for (int u = 0; u < G; ++u) {
-        float kf[8], sdot = 0.f;
-        Vec8<T>::unpack(kk[u], kf);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
-        sdot = group_sum<LPK>(sdot);
-        sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * qscale : -INFINITY;
-        mx = fmaxf(mx, sc[u]);
-      }
-      for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });   // over the key slots
-      // mx is finite: key j0 exists
-      const float corr = __builtin_amdgcn_exp2f(m[n] - mx);   // 0 the first time (m = -inf)
-      m[n] = mx;
-      l[n] *= corr;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[n][i] *= corr;
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        float vf[8];
-        Vec8<T>::unpack(vv[u], vf);
-        const float pj = __builtin_amdgcn_exp2f(sc[u] - mx);   // masked keys: 2^-inf = 0
-        l[n] += pj;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[n][i] += pj * vf[i];
-      }
-    }
-  }
-#pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    for_lane_bits<LPK>([&](auto bit) {
-      constexpr int O = decltype(bit)::value;
-      l[n] = add_lane_xor<O>(l[n]);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[n][i] = add_lane_xor<O>(acc[n][i]);
-    });
-    if (slot == 0) {
-      if constexpr (SPLIT) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) part[wave][n][c * 8 + i] = acc[n][i];
-        if (c == 0) { part[wave][n][DH] = m[n]; part[wave][n][DH + 1] = l[n]; }
-      } else {
-        const float r = 1.0f / l[n];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[n][i] *= r;
-        Vec8<T>::store(out + ((size_t)b * beam + first + n) * d + h * DH + c * 8, acc[n]);
-      }
-    }
-  }
-  if constexpr (SPLIT) {
-    __syncthreads();   // every wavefront of the workgroup gets here: none left early
-    // wavefront n (and n + 4, ...) finishes query n; a wavefront that had no keys left m = -inf, l = 0
-    for (int n = wave; n < NQ; n += 4) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, part[w2][n][DH]);
-      float sum = 0.f;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
-      for (int x = lane; x < DH; x += 64) {
-        float v = 0.f;
-#pragma unroll
-        for (int w2 = 0; w2 < 4; ++w2) v += part[w2][n][x] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
-        out[((size_t)b * beam + first + n) * d + h * DH + x] = (T)(v / sum);
-      }
+      for (int i = 0; i < 8; ++i) acc[n][i] *= r;
+      Vec8<T>::store(out_row0 + (size_t)n * d + c * 8, acc[n]);
     }
   }
 }
@@ -436,7 +481,6 @@ __global__ void __launch_bounds__(512) cross_attention_ln_kernel(const half_t* _
                                                                  half_t* __restrict__ out) {
   constexpr int DH = 64, LPK = 8, KPW = 8, G = 4, NV = 2, UMAX = 16;
   constexpr float scale = 0.125f;
-  using raw_t = half8_t;
   __shared__ __attribute__((aligned(16))) half_t a_rows[NQ][1024 + 8];
   __shared__ float red[8][16][64];
   __shared__ float q_s[NQ][DH];
@@ -455,21 +499,16 @@ __global__ void __launch_bounds__(512) cross_attention_ln_kernel(const half_t* _
   int n_keys = len[b], row0 = off[b];
   asm volatile("" : "+s"(n_keys), "+s"(row0));
   const int c = lane % LPK, slot = lane / LPK;
-  const char* K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
-  const char* V = K + d * sizeof(half_t);
-  const unsigned stride = 2 * d * sizeof(half_t), lane_at = c * 8 * sizeof(half_t);
-  raw_t kn[G], vn[G];
-  auto request = [&](int j0) {
-#pragma unroll
-    for (int u = 0; u < G; ++u) {
-      const unsigned at = (unsigned)min(j0 + u * KPW + slot, n_keys - 1) * stride + lane_at;
-      kn[u] = *reinterpret_cast<const raw_t*>(K + at);
-      vn[u] = *reinterpret_cast<const raw_t*>(V + at);
-    }
-  };
+  CrossKeys<half_t, DH, NQ> keys;
+  keys.K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  keys.V = keys.K + d * sizeof(half_t);
+  keys.stride = 2 * d * sizeof(half_t);
+  keys.lane_at = c * 8 * sizeof(half_t);
+  keys.n_keys = n_keys;
+  keys.slot = slot;
   // the first four wavefronts attend (step 4); the others have no keys
   const int jfirst = wave < 4 ? wave * G * KPW : 0x7fffffff;
-  if (jfirst < n_keys) request(jfirst);
+  if (jfirst < n_keys) keys.request(jfirst);
   // 2. LayerNorm of row (b * beam + wave)
   if (wave < NQ) {
     const int r = b * beam + wave;
@@ -536,86 +575,16 @@ __global__ void __launch_bounds__(512) cross_attention_ln_kernel(const half_t* _
   }
   __syncthreads();
   // 4. attention, four wavefronts sharing the keys
-  const float qscale = scale * 1.44269504088896340736f;
   float qv[NQ][8];
 #pragma unroll
   for (int n = 0; n < NQ; ++n)
 #pragma unroll
     for (int i = 0; i < 8; ++i) qv[n][i] = q_s[n][c * 8 + i];
   float mx_[NQ], l_[NQ], acc_[NQ][8];
-#pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    mx_[n] = -INFINITY;
-    l_[n] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc_[n][i] = 0.f;
-  }
-  for (int j0 = jfirst; j0 < n_keys; j0 += 4 * G * KPW) {
-    raw_t kk[G], vv[G];
-#pragma unroll
-    for (int u = 0; u < G; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
-    if (j0 + 4 * G * KPW < n_keys) request(j0 + 4 * G * KPW);
-#pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      float sc[G], mx = mx_[n];
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        float kf[8], sdot = 0.f;
-        Vec8<half_t>::unpack(kk[u], kf);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) sdot += qv[n][i] * kf[i];
-        sdot = group_sum<LPK>(sdot);
-        sc[u] = (j0 + u * KPW + slot < n_keys) ? sdot * qscale : -INFINITY;
-        mx = fmaxf(mx, sc[u]);
-      }
-      for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });
-      const float corr = __builtin_amdgcn_exp2f(mx_[n] - mx);
-      mx_[n] = mx;
-      l_[n] *= corr;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc_[n][i] *= corr;
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        float vf[8];
-        Vec8<half_t>::unpack(vv[u], vf);
-        const float pj = __builtin_amdgcn_exp2f(sc[u] - mx);
-        l_[n] += pj;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc_[n][i] += pj * vf[i];
-      }
-    }
-  }
-  if (wave < 4) {
-#pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      for_lane_bits<LPK>([&](auto bit) {
-        constexpr int O = decltype(bit)::value;
-        l_[n] = add_lane_xor<O>(l_[n]);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc_[n][i] = add_lane_xor<O>(acc_[n][i]);
-      });
-      if (slot == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) part[wave][n][c * 8 + i] = acc_[n][i];
-        if (c == 0) { part[wave][n][DH] = mx_[n]; part[wave][n][DH + 1] = l_[n]; }
-      }
-    }
-  }
+  keys.run(qv, scale * 1.44269504088896340736f, jfirst, 4 * G * KPW, mx_, l_, acc_);
+  if (wave < 4) cross_deposit<DH, NQ>(part, wave, lane, mx_, l_, acc_);
   __syncthreads();
-  for (int n = wave; n < NQ; n += 4) {
-    float mx = -INFINITY;
-#pragma unroll
-    for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, part[w2][n][DH]);
-    float sum = 0.f;
-#pragma unroll
-    for (int w2 = 0; w2 < 4; ++w2) sum += part[w2][n][DH + 1] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
-    for (int x = lane; x < DH; x += 64) {
-      float vsum = 0.f;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) vsum += part[w2][n][x] * __builtin_amdgcn_exp2f(part[w2][n][DH] - mx);
-      out[((size_t)b * beam + n) * d + h * DH + x] = (half_t)(vsum / sum);
-    }
-  }
+  cross_finish<half_t, DH, NQ>(part, wave, lane, out + (size_t)b * beam * d + h * DH, d);
 }
 
 bool cross_attention_ln_supported(int dtype, int rows, int beam, int H, int d) {
