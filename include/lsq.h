@@ -139,8 +139,12 @@ int lsq_set_cache_refresh(int mode);
 /* With at most 8 rows alive (the end of a batch, single sentences) a float16
  * encoder-decoder model folds every sublayer's "partial sums + bias + residual,
  * LayerNorm" into the product that consumes the normalised rows (sec. 2.1 taken
- * one step further: 18 fewer launches per step).  on = 0 keeps the stand-alone
- * LayerNorm kernel at every size; results are bit-identical.  Default: on. */
+ * one step further: 18 fewer launches per step), and with at most 64 rows (beams
+ * of at most 4, heads of 64) the cross-attention kernel normalises its rows and
+ * makes its queries itself (12 fewer).  on = 0 keeps the stand-alone LayerNorm
+ * kernel at every size.  With at most 8 rows the results are bit-identical
+ * either way; above, sums are taken in another order (fewer split-K slabs, keys
+ * shared by four wavefronts) and differ in the last bits.  Default: on. */
 int lsq_set_layernorm_fusion(int on);
 
 /* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
@@ -237,13 +241,13 @@ int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_b
                          const void* beta, const void* x_old, void* x_new, float eps, const void* W,
                          const void* bias, void* C, int M, int N, int K, int flags, void* stream);
 
-/* Cross-attention that normalises its rows and makes its queries itself (the
- * last one or two sentences of a batch, where fewer launches matter most;
+/* Cross-attention that normalises its rows and makes its queries itself (few
+ * rows alive, where fewer launches matter most;
  * paper sec. 2.1 taken one step further): for every sentence b and head h,
  *   rows  = LN(x_old + sum_s P[s] + ln_bias)            (as lsq_k_layernorm_gemm; written to x_new)
  *   q     = rows . Wq[h*64:(h+1)*64, :]^T + bq[h*64:..]   (rounded to float16)
  *   out   = lsq_k_cross_attention(q, kv, ...)
- * float16 only; batch*beam <= 8 rows, beam <= 4, heads of 64, d = 64*heads <=
+ * float16 only; batch*beam <= 64 rows, beam <= 4, heads of 64, d = 64*heads <=
  * 1024.  Wq_packed: the fragment-ordered copy of Wq [d, d] made by
  * lsq_k_pack_weights; P float [splits <= 4, batch*beam, d]; x_old and x_new
  * different buffers; everything else as in lsq_k_cross_attention. */

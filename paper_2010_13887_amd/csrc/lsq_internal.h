@@ -103,7 +103,7 @@ bool cross_attention_splits(int units, int smax);
 hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, const int32_t* off,
                                   const int32_t* len, void* out, int batch, int beam, int H, int d, int smax,
                                   hipStream_t s);
-// The tail of a batch (at most 8 rows alive, beams of 4 at most, head size 64, float16): the
+// Few rows alive (at most 64, beams of 4 at most, head size 64, float16): the
 // cross-attention kernel makes its own queries, q = LayerNorm(x_old + partial sums + bias) . Wq^T
 // + bq for the head it serves, from the fragment-ordered copy of Wq (gemm_packed_weights), instead
 // of a product kernel of 32 workgroups followed by an attention kernel.  The workgroups of head 0

@@ -368,8 +368,8 @@ int launch_step(int B) {
   char* x_alt = g.ws + p.d_x2;
   struct { bool on; int S; const void* bias; const void* gain; const void* shift; } pending = {false, 0, nullptr, nullptr, nullptr};
   auto close_sublayer = [&](int cls, const void* in, const void* W, const void* bias, const void* gain, const void* shift,
-                            int K) -> int {
-    if (!fuse) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, (float*)tmp, M, d, K, kMaxSplits, s);
+                            int K, bool defer) -> int {
+    if (!defer) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, (float*)tmp, M, d, K, kMaxSplits, s);
     const int S = std::min(gemm_partial_splits(dt, M, d, K), kMaxSplitsFusedLn);
     TIMED(cls, launch_gemm_partials(dt, in, W, (float*)tmp, M, d, K, S, s));
     pending = {true, S, bias, gain, shift};
@@ -398,10 +398,12 @@ int launch_step(int B) {
     o.tmul[1] = d; o.tmul[2] = d;
     if (int rc = product(PC_GEMM_QKV, L.Wqkv, L.bqkv, o, 3 * d, 0)) return rc;
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, anc, k, T + 1, s));
-    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d)) return rc;
-    const void* wq_packed = pending.on && cross_attention_ln_supported(dt, M, k, H, d) ? gemm_packed_weights(L.Wq, d, d) : nullptr;
+    // the cross-attention kernel can normalise its own rows with more sentences alive than the products can
+    const void* wq_for_ln = g.fuse_ln && cross_attention_ln_supported(dt, M, k, H, d) ? gemm_packed_weights(L.Wq, d, d) : nullptr;
+    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d, fuse || wq_for_ln != nullptr)) return rc;
+    const void* wq_packed = pending.on ? wq_for_ln : nullptr;
     if (wq_packed) {
-      // the last sentences of a batch: the attention kernel normalises its rows and makes its queries itself
+      // few rows: the attention kernel normalises its rows and makes its queries itself
       LnInput ln = {(const float*)tmp, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
                     (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
       TIMED(PC_ATTN_CROSS, launch_cross_attention_ln(ln, wq_packed, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
@@ -413,9 +415,9 @@ int launch_step(int B) {
       TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                   at<int32_t>(p.src_len), ctx, B, k, H, d, g.src_longest, s));
     }
-    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d, fuse)) return rc;
     if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
-    if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F, fuse)) return rc;
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
@@ -1144,7 +1146,7 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
   KCHK(x_old != x_new, "x_new must not be x_old");
   KCHK(batch >= 0 && splits >= 1 && splits <= 4, "shape");
   KCHK(batch == 0 || cross_attention_ln_supported(DT_F16, batch * beam, beam, heads, d),
-       "float16, at most 8 rows, beam 1..4, heads of 64, d a multiple of 64 up to 1024");
+       "float16, at most 64 rows, beam 1..4, heads of 64, d a multiple of 64 up to 1024");
   LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
                 (half_t*)x_new, eps};
   KRUN(launch_cross_attention_ln(ln, Wq_packed, bq, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
