@@ -139,7 +139,11 @@ def lockstep(lsq, eng, blob, w, max_steps=None, check_wide=True, verbose=False):
         for b in range(B):
             base = b * k
             if old_fin[base:base + k].all():
-                continue                       # nothing left to decide; the state checks below still apply
+                # nothing left to decide, and the library no longer touches the sentence: the hypotheses stay
+                # where they are.  (Selecting again would re-sort them by the oracle's scores, which undoes
+                # the library's order wherever an earlier step took it over within the band.)
+                par[b], tok[b], sc[b] = np.arange(k), m.eos, st.score[b]
+                continue                       # the state checks below still apply
             # measured deviation of candidate scores
             cdev = 0.0
             for j in range(k):

@@ -52,7 +52,9 @@ def draw(seed):
                 groups=int(rng.choice(groups)) if groups else 1, strength=float(rng.choice([0.0, 0.5, 2.0])))
 
 
-@pytest.mark.parametrize("seed", range(48))
+# 597: beams of 8 over 37 tokens; a sentence finishes in an order that the comparison took over from the library
+# within its band, and must then be left alone by both sides while the other sentences go on
+@pytest.mark.parametrize("seed", list(range(48)) + [597])
 def test_random_configuration_matches_oracle(lsq, seed):
     c = draw(seed)
     w = c["w"]
