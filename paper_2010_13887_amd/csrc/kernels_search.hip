@@ -325,29 +325,30 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   // instead of one per phase): the candidates, the state of the beam a candidate continues (lane
   // c continues beam c / k whatever its rank turns out to be), the sentence's length cap and this
   // lane's first position of the k token histories and slab tables.
-  float s = -INFINITY, plain = -INFINITY;
-  long flat = -1;
-  int tok = -1, j = 0, plen = 0, pfin = 0;
-  if (lane < kk) {
-    j = lane / k;
-    s = cand_score[(size_t)base * k + lane];
-    plain = gr.out_plain ? gr.out_plain[(size_t)base * k + lane] : s;
-    tok = cand_idx[(size_t)base * k + lane];
-    plen = len[base + j];
-    pfin = fin[base + j];
-  }
+  // No request sits behind a test of something that is itself read from memory: lanes past the
+  // k*k candidates repeat the last one and positions past the step repeat the last position of the
+  // histories (both discarded below), so every load can leave before the step counter has arrived.
+  const int cl = min(lane, kk - 1);
+  const int j = cl / k;
+  float s = cand_score[(size_t)base * k + cl];
+  float plain = gr.out_plain ? gr.out_plain[(size_t)base * k + cl] : s;
+  int tok = cand_idx[(size_t)base * k + cl];
+  const int plen = len[base + j], pfin = fin[base + j];
   const int cap_b = cap[b];
   int p = lane;
   int h[LSQ_MAX_BEAM_], ha[LSQ_MAX_BEAM_];
   auto fetch = [&]() {
+    const int pc = min(p, T1 - 1);
 #pragma unroll
     for (int i = 0; i < LSQ_MAX_BEAM_; ++i)
       if (i < k) {
-        h[i] = tokens[(size_t)(base + i) * T1 + p];
-        ha[i] = anc ? anc[(size_t)(base + i) * T1 + p] : 0;
+        h[i] = tokens[(size_t)(base + i) * T1 + pc];
+        ha[i] = anc ? anc[(size_t)(base + i) * T1 + pc] : 0;
       }
   };
-  if (p <= t && p < T1) fetch();
+  fetch();
+  if (lane >= kk) { s = -INFINITY; plain = -INFINITY; tok = -1; }
+  long flat = -1;
   if (tok >= 0) flat = (long)(gr.goff + j) * V + tok;
   // rank among the k*k candidates: lane c's pair is read straight from its registers
   int rank = 0;
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
         }
       }
     p += 64;
-    if (p <= t && p < T1) fetch();
+    if (p <= t && p < T1) fetch();   // a history longer than 64 positions: one more trip per 64
   }
   if (anc && lane < k && t + 1 < T1) anc[(size_t)(base + lane) * T1 + t + 1] = gr.goff + lane;
   __syncthreads();
