@@ -233,6 +233,22 @@ int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const voi
                              const void* gamma, const void* beta, int M, int d, int K, float eps,
                              void* scratch, void* stream);
 
+/* lsq_k_gemm_add_layernorm for callers that cannot allocate device memory or bring a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * two launches, with the fp32 partial sums in a buffer built into the library (one copy per GPU,
+ * held until the process ends) of lsq_k_gemm_add_layernorm_static_limit() = 16 MiB.  Allocates
+ * nothing and frees nothing; results are those of lsq_k_gemm_add_layernorm bit for bit.  A shape
+ * whose lsq_k_gemm_add_layernorm_scratch() exceeds the limit is refused with LSQ_E_ARG before any
+ * device work (M * d * 4 bytes per slab, up to 8 slabs: e.g. 512 rows of 1024 always fit).  Every
+ * call on a GPU uses that GPU's one buffer: calls that overlap on one GPU (two streams, two
+ * threads) race; calls on one stream are ordered and need nothing cleared in between (every slab
+ * element that is read was written by the same call).  The device current at the call is the
+ * one whose buffer is used and must be the device of the operands and the stream. */
+size_t lsq_k_gemm_add_layernorm_static_limit(void);
+int lsq_k_gemm_add_layernorm_static(int dtype, const void* in, const void* W, const void* bias, void* x,
+                                    const void* gamma, const void* beta, int M, int d, int K, float eps,
+                                    void* stream);
+
 /* C = act(LN(x_old + sum_s P[s] + ln_bias) . W^T + bias) for 1..8 rows, float16:
  * the LayerNorm of lsq_k_gemm_add_layernorm done by the product that consumes it.
  * P float [splits <= 4, M, K]; x_old, x_new [M,K] (different buffers; x_new

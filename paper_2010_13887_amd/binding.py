@@ -61,6 +61,7 @@ def load_library() -> C.CDLL:
         "lsq_k_gemm": [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_pack_weights": [vp, vp, i32, i32, vp],
         "lsq_k_gemm_add_layernorm": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp],
+        "lsq_k_gemm_add_layernorm_static": [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp],
         "lsq_k_self_attention": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "lsq_k_encoder_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_self_attention_table": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp],
@@ -76,6 +77,8 @@ def load_library() -> C.CDLL:
         fn.restype = C.c_int
     lib.lsq_k_gemm_add_layernorm_scratch.argtypes = [i32, i32, i32, i32]
     lib.lsq_k_gemm_add_layernorm_scratch.restype = C.c_size_t
+    lib.lsq_k_gemm_add_layernorm_static_limit.argtypes = []
+    lib.lsq_k_gemm_add_layernorm_static_limit.restype = C.c_size_t
     lib.lsq_k_packed_weight_bytes.argtypes = [i32, i32]
     lib.lsq_k_packed_weight_bytes.restype = C.c_size_t
     lib.lsq_free.argtypes = []
@@ -251,6 +254,19 @@ def k_gemm_add_layernorm(inp, W, bias, x, gamma, beta, eps: float) -> None:
                           device=x.device)
     _check(lib.lsq_k_gemm_add_layernorm(_dt(x), _p(inp), _p(W), _p(bias), _p(x), _p(gamma), _p(beta), M, d, K, eps,
                                         _p(scratch), _stream()))
+
+
+def k_gemm_add_layernorm_static(inp, W, bias, x, gamma, beta, eps: float) -> None:
+    """k_gemm_add_layernorm with the partial sums in the library's built-in buffer: nothing is allocated."""
+    M, K = inp.shape
+    d = W.shape[0]
+    assert W.shape[1] == K and tuple(x.shape) == (M, d)
+    _check(load_library().lsq_k_gemm_add_layernorm_static(_dt(x), _p(inp), _p(W), _p(bias), _p(x), _p(gamma), _p(beta),
+                                                          M, d, K, eps, _stream()))
+
+
+def k_gemm_add_layernorm_static_limit() -> int:
+    return load_library().lsq_k_gemm_add_layernorm_static_limit()
 
 
 def k_layernorm_gemm(P, ln_bias, gamma, beta, x_old, x_new, eps: float, W, bias, C_out, relu: bool = False) -> None:

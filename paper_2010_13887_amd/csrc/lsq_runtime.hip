@@ -1131,6 +1131,47 @@ int lsq_k_gemm_add_layernorm(int dtype, const void* in, const void* W, const voi
   return LSQ_OK;
 }
 
+// ---- the same sublayer tail for callers that cannot allocate ------------------------------------
+// The split-K slabs live in a file-scope device array instead of caller memory.  In host code the
+// array's name is only a stand-in for the symbol: its device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and kept; kernels, and anything else that touches
+// the memory from the host, get that address.
+}  // extern "C"
+
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;   // 8 slabs of 512 x 1024 floats
+constexpr int kMaxDevices = 64;
+void* g_static_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+static __device__ __align__(256) unsigned char lsq_static_scratch[kStaticScratchBytes];
+
+extern "C" {
+
+size_t lsq_k_gemm_add_layernorm_static_limit(void) { return kStaticScratchBytes; }
+
+int lsq_k_gemm_add_layernorm_static(int dtype, const void* in, const void* W, const void* bias, void* x,
+                                    const void* gamma, const void* beta, int M, int d, int K, float eps,
+                                    void* stream) {
+  KCHK(in && W && bias && x && gamma && beta, "null pointer");
+  KCHK(dtype == DT_F32 || dtype == DT_F16, "dtype");
+  KCHK(M >= 0 && d >= 1 && K >= 1, "shape");
+  KCHK(dtype == DT_F32 || K % 8 == 0, "K must be a multiple of 8 for float16");
+  const size_t need = lsq_k_gemm_add_layernorm_scratch(dtype, M, d, K);
+  if (need > kStaticScratchBytes)
+    return fail(LSQ_E_ARG, "this shape needs %zu bytes of partial sums, the built-in buffer holds %zu", need,
+                kStaticScratchBytes);
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(LSQ_E_ARG, "device %d outside [0, %d)", dev, kMaxDevices);
+  if (!g_static_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(lsq_static_scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 15) != 0) return fail(LSQ_E_HIP, "built-in scratch buffer has no usable address");
+    g_static_scratch_ptr[dev] = p;
+  }
+  return lsq_k_gemm_add_layernorm(dtype, in, W, bias, x, gamma, beta, M, d, K, eps, g_static_scratch_ptr[dev], stream);
+}
+
 int lsq_k_layernorm_gemm(int dtype, const float* P, int splits, const void* ln_bias, const void* gamma, const void* beta,
                          const void* x_old, void* x_new, float eps, const void* W, const void* bias, void* C, int M,
                          int N, int K, int flags, void* stream) {
