@@ -2,18 +2,33 @@
 """Throughput of the auto-regressive decode hot path on one MI355X.
 
 A "step" is one lsq_decode_step: every decoder layer over the cached keys/values, vocabulary
-logits, log-softmax + beam scores + exact top-k, hypothesis update and K/V-cache reorder, for all
+logits, log-softmax + beam scores + exact top-k, hypothesis update and K/V-cache refresh, for all
 batch*beam rows.  Default workload: Transformer-big, fp16, batch 128, beam 4, source lengths from
 a truncated log-normal (mean 28, max 128), target cap = source length + 50; synthetic weights
-N(0, 0.02^2) and ids, all resident in HBM before the timed region.
+N(0, 0.02^2) and ids; weights, caches and every intermediate resident in HBM before any timed region.
 
-Sequence: one untimed full translation (clocks, caches), then encode, W untimed decode steps
-(t = 0..W-1), then exactly K timed steps (default: all remaining steps of the translation)
-enqueued back to back between two stream synchronisations.  value = target tokens decoded in the
-timed steps / elapsed time (one token per still-unfinished sentence per step).  A second,
-instrumented pass of the same K steps brackets every kernel with HIP events on the library's
-stream to get per-kernel-class durations for the roofline line; the CPU oracle is timed on a
-bounded sample of the same workload.  Prints ONE JSON line.
+What is timed.
+  value          whole translations, end to end: lsq_encode (a few KB of source ids go up, encoder,
+                 cross K/V) + every decode step, enqueued 64 at a time + lsq_get_beams (results back on
+                 the host); tokens = length of the best hypothesis of every sentence; 3 untimed
+                 translations, then the MEDIAN of --repeats (default 10) timed ones.  This is the metric:
+                 it includes the long tail of steps with few sentences alive.
+  ms_per_step    decode time of those translations (encode excluded) / decode steps, median run.
+  window         the driver's --warmup W / --steps K: after encode and W untimed steps, exactly K steps
+                 enqueued back to back between two stream synchronisations, median of the same number of
+                 repeats; tokens = one per still-unfinished sentence and step.  With K short of the whole
+                 translation this is the full-batch rate, not the metric, and is reported beside it.
+  roofline       per-kernel-class durations over the window of steps in which every sentence is alive
+                 (the full-batch shape, M = batch*beam rows), from HIP events around every launch on the
+                 library's stream.  The events' own cost is calibrated in the same run: the GPU runs the
+                 step's kernels back to back, so (sum of all brackets - time of the same steps without
+                 brackets) / launches is what a bracket adds, and it is subtracted from every launch.
+                 The class with the largest corrected time is the dominant kernel; a product whose FLOP
+                 per byte exceeds peak FLOP/s / peak B/s is held against the fp16 MFMA roof, everything
+                 else against HBM.  traffic: HBM bytes per launch read from the committed rocprofv3 PMC
+                 summary (profiles/kernel_traffic_big128.txt), null for other workloads.
+  cpu_baseline   the oracle as it stands, first decode steps of the same workload, bounded time.
+Prints ONE JSON line.
 
 --workload gpt2s times the decoder-only model instead (GPT-2-small shape, batch 32, prompt 64,
 top-8 sampling, 128 generated tokens): a step is one lsq_decode_step of that model (12 pre-LN
@@ -24,6 +39,8 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -34,21 +51,29 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 
-# HBM bytes per launch at the full-batch shape of the big128 workload (M = 512 rows, t = 40), from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench_kernels.py scaled by the same counters'
-# readings for a 1 GiB copy (x2.0 for reads, x1.0 for writes): profiles/kernel_traffic_big128.txt.
-# Split-K classes are given for the 2 slabs used at this shape.
-MEASURED_TRAFFIC_BIG128 = {
-    "gemm_qkv": 14.9e6 + 3.1e6,
-    "gemm_dxd": (2 * (10.7e6 + 4.2e6) + (10.7e6 + 1.0e6)) / 3,   # two split-K products and one plain per layer
-    "gemm_ffn1": 17.0e6 + 4.2e6,
-    "gemm_ffn2": 42.1e6 + 4.2e6,
-    "gemm_vocab": 89.5e6 + 73.2e6,
-    "attn_self": 29.9e6 + 1.0e6,            # through the slab table: 0.32 of the (row, position) pairs distinct
-    "attn_cross": 16.2e6 + 1.0e6,
-    "row_topk": 66.0e6 + 21.0e6,
-    "cache_reorder": 129.2e6 + 386.9e6,     # LSQ_REFRESH_MOVE only: 3 of 4 rows of every sentence moved
+# kernel class of the per-launch timing -> case names of profiles/kernel_traffic_big128.txt (read + write MB
+# per launch at the full-batch shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench_kernels.py)
+TRAFFIC_CASES = {
+    "gemm_qkv": ["gemm_qkv"], "gemm_dxd": ["gemm_dxd"], "gemm_ffn1": ["gemm_ffn1"],
+    "gemm_out": ["sublayer_out"], "gemm_ffn2": ["sublayer_ffn2"],
+    "gemm_vocab": ["gemm_vocab"], "attn_self": ["attn_self_table"], "attn_cross": ["attn_cross"],
+    "row_topk": ["row_topk"], "cache_reorder": ["cache_reorder"],
 }
+
+
+def measured_traffic(cls):
+    """HBM bytes per launch of a kernel class from the committed PMC summary, or None."""
+    path = os.path.join(ROOT, "profiles", "kernel_traffic_big128.txt")
+    cases = TRAFFIC_CASES.get(cls)
+    if not cases or not os.path.exists(path):
+        return None
+    total, found = 0.0, False
+    for line in open(path):
+        m = re.match(r"(\S.{25}) (\S.{47}) +([\d.]+) +([\d.]+)\s*$", line)
+        if m and m.group(1).strip() in cases and "rocclr" not in m.group(2) and not m.group(2).startswith("add_layernorm"):
+            total += (float(m.group(3)) + float(m.group(4))) * 1e6
+            found = True
+    return total if found else None
 
 
 def class_work(name, hp, B, k, t_mean, s_mean):
@@ -60,7 +85,7 @@ def class_work(name, hp, B, k, t_mean, s_mean):
     gemm = lambda n, kk, out_es=es: (2.0 * M * n * kk, (M * kk + n * kk) * es + M * n * out_es)
     if name == "gemm_qkv":
         return gemm(3 * d, d)
-    if name == "gemm_dxd":
+    if name in ("gemm_dxd", "gemm_out"):
         return gemm(d, d)
     if name == "gemm_ffn1":
         return gemm(F, d)
@@ -88,8 +113,9 @@ def class_work(name, hp, B, k, t_mean, s_mean):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="timed decode steps (0 = to the end of the translation)")
-    ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the timed ones")
+    ap.add_argument("--steps", type=int, default=0, help="decode steps of the timed window (0 = to the end of the translation)")
+    ap.add_argument("--warmup", type=int, default=3, help="untimed decode steps before the window")
+    ap.add_argument("--repeats", type=int, default=10, help="timed repetitions (the median is reported); 3 untimed ones precede them")
     ap.add_argument("--workload", default="big128", choices=["tiny", "base", "big", "big128", "gpt2s", "gpt2s_k32p75", "base_k32p75"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle sample")
@@ -113,51 +139,69 @@ def main() -> int:
     hp = w.hp
     blob = w.blob()
     B, k, T = w.batch, w.beam, w.max_len
+    R = max(1, args.repeats)
     eng = lsq.Engine(blob, B, k, T)
 
-    # untimed full translation
+    # untimed full translation (clocks, caches, graph capture)
     ids, lens, scores = eng.translate(w.src_ids, w.src_lens, sync_every=16)
     total_steps = lsq.lsq_step_index()
     best_len = lens[:, 0].astype(np.int64)
+    gpt = hp.arch == 1
+    # decoder-only: every row generates cap_extra tokens; step t attends the prompt and t earlier tokens
+    caps = np.full(B, hp.cap_extra) if gpt else np.minimum(w.src_lens + hp.cap_extra, T)
+    t_base = int(w.src_lens[0]) - 1 if gpt else 0
+    s_mean = float(w.src_lens.mean())
+
+    # ---- the metric: whole translations end to end, median of R after 3 untimed ones
+    def whole():
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.encode(w.src_ids, w.src_lens)
+        torch.cuda.synchronize()
+        t_enc = time.perf_counter() - t0
+        while eng.decode_steps(64) > 0:
+            pass
+        eng.get_beams()
+        return time.perf_counter() - t0, t_enc
+
+    for _ in range(3):
+        whole()
+    runs = sorted(whole() for _ in range(R))
+    t_all, t_enc = runs[len(runs) // 2]
+    n_tokens = int(best_len.sum())
+    value = n_tokens / t_all
+    ms_per_step = (t_all - t_enc) / total_steps * 1e3
+    end_to_end = dict(tokens=n_tokens, total_ms=t_all * 1e3, encode_ms=t_enc * 1e3, steps=total_steps, repeats=R,
+                      min_ms=runs[0][0] * 1e3, max_ms=runs[-1][0] * 1e3,
+                      decode_only_tokens_per_s=n_tokens / (t_all - t_enc))
+
+    # ---- the driver's window: W untimed steps, then exactly K timed ones
     W = max(0, min(args.warmup, total_steps - 1))
     K = args.steps if args.steps > 0 else total_steps - W
     K = max(1, min(K, total_steps - W))
 
-    def run(profile: bool):
+    def window(profile: bool, w0: int, kk: int):
         eng.encode(w.src_ids, w.src_lens)
-        if W:
-            eng.decode_steps(W)
+        if w0:
+            eng.decode_steps(w0)
         lsq.lsq_profile_enable(profile)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        eng.decode_steps(K)                       # K steps enqueued back to back, one wait at the end
+        eng.decode_steps(kk)                      # kk steps enqueued back to back, one wait at the end
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         prof = lsq.lsq_profile_read() if profile else None
         lsq.lsq_profile_enable(False)
         return dt, prof
 
-    run(False)                                     # one more warm pass over exactly the timed region
-    dt, _ = run(False)
+    window(False, W, K)
+    dts = sorted(window(False, W, K)[0] for _ in range(R))
+    dt = dts[len(dts) // 2]
     tokens = int((np.minimum(best_len, W + K) - np.minimum(best_len, W)).sum())
-    value = tokens / dt
-    ms_per_step = dt / K * 1e3
+    win = dict(first_step=W, steps=K, tokens=tokens, tokens_per_s=tokens / dt, ms_per_step=dt / K * 1e3,
+               min_ms_per_step=dts[0] / K * 1e3, max_ms_per_step=dts[-1] / K * 1e3)
 
-    # whole translation, end to end: encode (host ids in, encoder, cross K/V) + every decode step +
-    # get_beams (results back on the host); tokens = length of the best hypothesis of every sentence
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    eng.encode(w.src_ids, w.src_lens)
-    torch.cuda.synchronize()
-    t_enc = time.perf_counter() - t0
-    while eng.decode_steps(64) > 0:
-        pass
-    eng.get_beams()
-    t_all = time.perf_counter() - t0
-    end_to_end = dict(tokens_per_s=float(best_len.sum()) / t_all, total_ms=t_all * 1e3, encode_ms=t_enc * 1e3,
-                      steps=total_steps)
-
-    # the curve over t: the same translation in chunks of 8 steps with a wait after each chunk
+    # ---- the curve over t: the same translation in chunks of 8 steps with a wait after each chunk
     # (the waits make these figures slightly higher than the back-to-back ones above)
     eng.encode(w.src_ids, w.src_lens)
     torch.cuda.synchronize()
@@ -176,55 +220,60 @@ def main() -> int:
     step_curve = dict(p50_ms=per_step[len(per_step) // 2], min_ms=per_step[0], max_ms=per_step[-1],
                       chunks=[[c["t"], round(c["ms_per_step"], 4)] for c in curve])
 
-    # instrumented pass: per-kernel-class durations over the same K steps
-    dt_prof, prof = run(True)
-    # Work per class summed over the timed steps.  Step t works on the sentences whose cap
-    # (source length + cap_extra, at most max_len) exceeds t, attends t+1 cached positions and
-    # reorders t+1 positions.
-    gpt = hp.arch == 1
-    # decoder-only: every row generates cap_extra tokens; step t attends the prompt and t earlier tokens
-    caps = np.full(B, hp.cap_extra) if gpt else np.minimum(w.src_lens + hp.cap_extra, T)
-    t_base = int(w.src_lens[0]) - 1 if gpt else 0
-    s_mean = float(w.src_lens.mean())
+    # ---- per kernel class, over the steps in which every sentence is alive (the full-batch shape)
+    full = int(caps.min())                                   # steps 0 .. full-1 work on all B sentences
+    w0 = min(3, max(0, full - 1))
+    kk = max(1, min(full - w0, 64))
+    window(False, w0, kk)
+    plain = sorted(window(False, w0, kk)[0] for _ in range(max(3, R // 2)))
+    dt_plain = plain[len(plain) // 2]
+    window(True, w0, kk)                                     # event pool, first eager launches
+    dt_prof, prof = window(True, w0, kk)
+    n_launch = sum(n for _, n in prof.values())
+    bracket_ms = sum(ms for ms, _ in prof.values())
+    # what a bracket adds to a launch: the kernels of a step run back to back, so without brackets
+    # their durations add up to the time of the steps
+    overhead_us = max(0.0, (bracket_ms - dt_plain * 1e3) / max(n_launch, 1) * 1e3)
+    t_mean = t_base + w0 + (kk + 1) / 2.0                    # mean number of cached positions attended
     table = {}
     for name, (ms, n) in prof.items():
         if n == 0:
             continue
-        fl = by = 0.0
-        per_step = n // K
-        for t in range(W, W + K):
-            alive = caps > t
-            f1, b1 = class_work(name, hp, int(alive.sum()), k, t_base + t + 1, float(w.src_lens[alive].mean()) if alive.any() else 0.0)
-            fl += f1 * per_step
-            by += b1 * per_step
-        us = ms / n * 1e3
-        table[name] = dict(launches=n, total_ms=ms, avg_us=us, flops_per_launch=fl / n, bytes_per_launch=by / n,
-                           tflops=fl / (ms * 1e-3) / 1e12 if ms > 0 else 0.0,
-                           gbs=by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0)
+        fl, by = class_work(name, hp, B, k, t_mean, s_mean)
+        raw_us = ms / n * 1e3
+        us = max(raw_us - overhead_us, 0.05)
+        table[name] = dict(launches_per_step=n / kk, avg_us=us, event_us=raw_us, total_ms=us * n * 1e-3,
+                           flops_per_launch=fl, bytes_per_launch=by, tflops=fl / us / 1e6, gbs=by / us / 1e3)
+    ridge = PEAK_F16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    for name, d in table.items():
+        mfma = name.startswith("gemm") and d["flops_per_launch"] / max(d["bytes_per_launch"], 1.0) >= ridge
+        d["bound"] = "mfma" if mfma else "hbm"
+        d["frac"] = d["tflops"] / PEAK_F16_TFLOPS if mfma else d["gbs"] / PEAK_HBM_GBS
     dom = max(table, key=lambda n: table[n]["total_ms"])
     d = table[dom]
-    traffic = MEASURED_TRAFFIC_BIG128.get(dom) if args.workload == "big128" else None
-    # a product whose FLOP per byte is below peak FLOP/s / peak B/s (small M: the weights are
-    # streamed for few rows) is bounded by the memory roof, not by the matrix cores
-    intensity = d["flops_per_launch"] / max(d["bytes_per_launch"], 1.0)
-    if dom.startswith("gemm") and intensity >= PEAK_F16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        roof = dict(bound="mfma", kernel=dom, achieved=d["tflops"], peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
-                    frac=d["tflops"] / PEAK_F16_TFLOPS, traffic=traffic, avg_us=d["avg_us"], launches=d["launches"])
-    else:
-        roof = dict(bound="hbm", kernel=dom, achieved=d["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=d["gbs"] / PEAK_HBM_GBS, traffic=traffic, avg_us=d["avg_us"], launches=d["launches"])
+    traffic = measured_traffic(dom) if args.workload == "big128" else None
+    roof = dict(bound=d["bound"], kernel=dom, achieved=d["tflops"] if d["bound"] == "mfma" else d["gbs"],
+                peak=PEAK_F16_TFLOPS if d["bound"] == "mfma" else PEAK_HBM_GBS,
+                unit="TFLOP/s" if d["bound"] == "mfma" else "GB/s", frac=d["frac"], traffic=traffic,
+                avg_us=d["avg_us"], event_us=d["event_us"], bracket_overhead_us=overhead_us,
+                launches_per_step=d["launches_per_step"], rows=B * k, steps=[w0, w0 + kk],
+                algorithmic_flops=d["flops_per_launch"], algorithmic_bytes=d["bytes_per_launch"])
     gemm_ms = sum(v["total_ms"] for n, v in table.items() if n.startswith("gemm"))
-    gemm_fl = sum(v["flops_per_launch"] * v["launches"] for n, v in table.items() if n.startswith("gemm"))
+    gemm_fl = sum(v["flops_per_launch"] * v["launches_per_step"] * kk for n, v in table.items() if n.startswith("gemm"))
     kernel_ms = sum(v["total_ms"] for v in table.values())
-    extra = dict(kernel_ms_per_step=kernel_ms / K, gemm_share=gemm_ms / kernel_ms,
-                 reorder_share=table.get("cache_reorder", {}).get("total_ms", 0.0) / kernel_ms,
-                 gemm_tflops_aggregate=gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
-                 instrumented_ms_per_step=dt_prof / K * 1e3)
+    extra = dict(full_batch=dict(ms_per_step=dt_plain / kk * 1e3, launches_per_step=n_launch / kk,
+                                 gemm_share=gemm_ms / kernel_ms,
+                                 reorder_share=table.get("cache_reorder", {}).get("total_ms", 0.0) / kernel_ms,
+                                 gemm_tflops_aggregate=gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
+                                 gemm_mfma_frac=gemm_fl / (gemm_ms * 1e-3) / 1e12 / PEAK_F16_TFLOPS if gemm_ms else 0.0,
+                                 instrumented_ms_per_step=dt_prof / kk * 1e3),
+                 kernel_classes={n: [round(v["launches_per_step"], 2), round(v["avg_us"], 2), v["bound"], round(v["frac"], 4)]
+                                 for n, v in sorted(table.items(), key=lambda kv: -kv[1]["total_ms"])})
     if args.breakdown:
         os.makedirs(os.path.dirname(os.path.abspath(args.breakdown)), exist_ok=True)
         with open(args.breakdown, "w") as f:
-            json.dump(dict(workload=args.workload, steps=K, warmup=W, ms_per_step=ms_per_step, classes=table,
-                           **extra), f, indent=1)
+            json.dump(dict(workload=args.workload, steps=[w0, w0 + kk], ms_per_step=dt_plain / kk * 1e3,
+                           bracket_overhead_us=overhead_us, classes=table), f, indent=1)
     eng.close()
 
     cpu = None
@@ -286,8 +335,10 @@ def main() -> int:
                value=value, unit="tokens/s", n_gpus=1, steps=K, warmup=W, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f16" if hp.dtype == 1 else "f32", data="synthetic",
-               config=dict(workload=desc, global_batch=B, beam=k, decode_steps_total=total_steps, tokens_timed=tokens),
-               roofline=roof, cpu_baseline=cpu, end_to_end=end_to_end, step_curve=step_curve, **extra)
+               config=dict(workload=desc, global_batch=B, beam=k, decode_steps_total=total_steps,
+                           value_covers=f"whole translations end to end (encode + all {total_steps} decode steps + results "
+                                        f"on the host), median of {R} after 3 untimed; the --steps/--warmup window is in 'window'"),
+               roofline=roof, cpu_baseline=cpu, end_to_end=end_to_end, window=win, step_curve=step_curve, **extra)
     print(json.dumps(out))
     return 0
 

@@ -40,11 +40,11 @@ int fail(int code, const char* fmt, ...) {
 // per kernel class.  Events come from a host-side pool that only grows.
 enum ProfClass {
   PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
-  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_COUNT
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
                                           "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
-                                          "beam_refine", "cache_reorder"};
+                                          "beam_refine", "cache_reorder", "gemm_out"};
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
@@ -284,6 +284,7 @@ struct Ctx {
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
   std::map<int, hipGraphExec_t> graphs;   // (live sentences, cross-attention geometry) -> captured decode step
+  std::map<int, bool> graph_hidden_in_alt; // ... and where that step leaves its final hidden rows
   std::vector<int> alive_at;   // alive_at[t] = sentences whose cap exceeds t: the prefix step t works on
   char* E = nullptr;
   std::vector<GptLayer> gpt;
@@ -400,7 +401,7 @@ int launch_step(int B) {
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, anc, k, T + 1, s));
     // the cross-attention kernel can normalise its own rows with more sentences alive than the products can
     const void* wq_for_ln = g.fuse_ln && cross_attention_ln_supported(dt, M, k, H, d) ? gemm_packed_weights(L.Wq, d, d) : nullptr;
-    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d, fuse || wq_for_ln != nullptr)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_OUT, ctx, L.Wo, L.bo, L.ln1g, L.ln1b, d, fuse || wq_for_ln != nullptr)) return rc;
     const void* wq_packed = pending.on ? wq_for_ln : nullptr;
     if (wq_packed) {
       // few rows: the attention kernel normalises its rows and makes its queries itself
@@ -415,7 +416,7 @@ int launch_step(int B) {
       TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                   at<int32_t>(p.src_len), ctx, B, k, H, d, g.src_longest, s));
     }
-    if (int rc = close_sublayer(PC_GEMM_DD, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d, fuse)) return rc;
+    if (int rc = close_sublayer(PC_GEMM_OUT, ctx, L.Woc, L.boc, L.ln2g, L.ln2b, d, fuse)) return rc;
     if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
     if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F, fuse)) return rc;
   }
@@ -429,6 +430,7 @@ int launch_step(int B) {
                                                       pending.shift, M, d, hp.eps, s));
     pending.on = false;
   }
+  g.hidden_in_alt = (x != g.ws + p.d_x);   // which of the two hidden-state buffers the last LayerNorm wrote
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   if (hp.sample_topk > 0) {
     // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
@@ -499,7 +501,7 @@ int launch_step_gpt(int B) {
     o.tmul[1] = d; o.tmul[2] = d;
     TIMED(PC_GEMM_QKV, launch_gemm(dt, y, L.Wqkv, L.bqkv, o, M, 3 * d, d, 0, s));
     TIMED(PC_ATTN_SELF, launch_self_attention(dt, q, Kc, Vc, ctx, M, H, d, T, 1, step, nullptr, 1, 0, s));
-    if (int rc = sublayer(PC_GEMM_DD, ctx, L.Wo, L.bo, L.ln2g, L.ln2b, x, y, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
+    if (int rc = sublayer(PC_GEMM_OUT, ctx, L.Wo, L.bo, L.ln2g, L.ln2b, x, y, (float*)tmp, M, d, d, kMaxSplits, s)) return rc;
     TIMED(PC_GEMM_FFN1, launch_gemm(dt, y, L.W1, L.b1, plain_out(ffn, F), M, F, d, 2, s));
     const bool last = l + 1 == hp.n_dec;
     if (int rc = sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, last ? g.lnfg : g.gpt[l + 1].ln1g, last ? g.lnfb : g.gpt[l + 1].ln1b,
@@ -522,8 +524,7 @@ int launch_step_gpt(int B) {
 int enqueue_step() {
   const int B = g.alive_at[g.t];
   auto launch = [&](int n) { return g.hp.arch == 1 ? launch_step_gpt(n) : launch_step(n); };
-  g.hidden_in_alt = g.hp.arch == 0 && g.fuse_ln && gemm_ln_supported(g.hp.dtype, B * g.beam, g.hp.d) &&
-                    ((3 * g.hp.n_dec) & 1) != 0;
+  g.hidden_in_alt = false;   // launch_step says otherwise
   if (!g.use_graphs || g.stream == nullptr || g_prof.on) {
     int rc = launch(B);
     if (rc) return rc;
@@ -546,7 +547,9 @@ int enqueue_step() {
     (void)hipGraphDestroy(graph);
     if (e != hipSuccess) return fail(LSQ_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
     it = g.graphs.emplace(key, exec).first;
+    g.graph_hidden_in_alt[key] = g.hidden_in_alt;
   }
+  g.hidden_in_alt = g.graph_hidden_in_alt[key];
   HIPCHK(hipGraphLaunch(it->second, g.stream));
   g.t += 1;
   return LSQ_OK;
@@ -814,12 +817,14 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
   if (groups != g.groups || (groups > 1 && g.strength_next != g.strength)) {
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
   }
   g.groups = groups;
   g.strength = g.strength_next;
   if (anc_on != g.anc_on) {   // captured steps hold the other mode's kernels and arguments
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
     g.anc_on = anc_on;
   }
   if (hp.arch == 1) return encode_gpt(src_ids, src_lens, batch, src_stride);
@@ -951,6 +956,7 @@ int lsq_set_layernorm_fusion(int on) {
     if (g.stream) (void)hipStreamSynchronize(g.stream);
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
   }
   g.fuse_ln = on != 0;
   return LSQ_OK;
@@ -993,6 +999,7 @@ void lsq_free(void) {
     (void)hipStreamSynchronize(g.stream);
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
   }
   if (g.pinned) {
     if (g.stream || g.state >= 2) (void)hipStreamSynchronize(g.stream);

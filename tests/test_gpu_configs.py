@@ -35,25 +35,63 @@ def _properties(w, ids, lens, scores, hp):
     assert np.isfinite(scores).all() and (scores < 0).all()
 
 
-@pytest.mark.parametrize("name,steps", [("base", 40), ("big", 12), ("big128", 6)])
-def test_config_matches_oracle_then_finishes(lsq, name, steps):
+def _final_step_index(w, lens, stepped, chunk):
+    """Steps the library has taken once it reports "nothing active": the step at which the last hypothesis
+    finished is the longest final length (a finished hypothesis can only be displaced by one that finishes
+    later), steps are issued in chunks of `chunk` after the first `stepped`, never beyond the longest cap."""
+    last = int(lens.max())
+    longest_cap = int(np.minimum(w.src_lens + w.hp.cap_extra, w.max_len).max())
+    if last <= stepped:
+        return stepped
+    return min(longest_cap, stepped + -(-(last - stepped) // chunk) * chunk)
+
+
+# (workload, lock-step steps, arithmetic of the judge oracle, kernel-mirroring oracle beside it, pinned share of
+# strict decisions = a little under the measured 0.944 / 0.934 / 0.917).  The full-batch runs of the big model use a float32 judge
+# (numpy float32 is 1e-6 from float64 here, the tolerances are 1e-3 and up); everything smaller uses float64.
+@pytest.mark.parametrize("name,steps,ctype,mirror,min_strict", [("base", 40, np.float64, True, 0.92),
+                                                                ("big", 40, np.float32, False, 0.91),
+                                                                ("big128", 48, np.float32, False, 0.90)])
+def test_config_matches_oracle_then_finishes(lsq, name, steps, ctype, mirror, min_strict):
     w = S.workload(name)
     blob = w.blob()
     print(f"{name}: batch {w.batch} max_len {w.max_len}", flush=True)
     with lsq.Engine(blob, w.batch, w.beam, w.max_len) as eng:
-        res = lockstep(lsq, eng, blob, w, max_steps=steps, verbose=True)
+        res = lockstep(lsq, eng, blob, w, max_steps=steps, judge_ctype=ctype, mirror=mirror, verbose=True)
+        print({k: v for k, v in res.items() if k not in ("state", "judge", "bound")}, flush=True)
         assert res["steps"] == steps
-        assert res["strict"] >= 0.5 * steps * w.batch, res     # most decisions are outside the near-tie band
-        assert res["worst_wide"] <= 2e-2 and res["worst_tight"] <= 1e-2
+        assert res["strict_share"] >= min_strict, res["strict_share"]
+        assert res["worst_logit"] <= 2e-2 and res["worst_mirror"] <= 1e-2
         # run to the end without per-step synchronisation, as bench.py does
         while eng.decode_steps(32) > 0:
             pass
-        assert lsq.lsq_step_index() == int((w.src_lens + w.hp.cap_extra).max()) or lsq.lsq_step_index() <= w.max_len
         ids, lens, scores = eng.get_beams()
+        assert lsq.lsq_step_index() == _final_step_index(w, lens, steps, 32)
         _properties(w, ids, lens, scores, w.hp)
         # the same translation again, chunked differently: bit-identical
         ids2, lens2, scores2 = eng.translate(w.src_ids, w.src_lens, sync_every=7)
         assert np.array_equal(ids, ids2) and np.array_equal(lens, lens2) and np.array_equal(scores, scores2)
+
+
+def test_headline_sentences_every_step_to_the_end(lsq):
+    """The headline workload (Transformer-big, batch 128, beam 4) runs whole on the GPU, all 175 steps, while
+    the float64 judge follows eleven of its sentences -- the three with the longest caps (alive to the very
+    end: the one-or-two-sentence tail), and eight spread over the rest of the cap order -- through every one
+    of their steps.  Sentences do not interact, so each of them is compared exactly as in a full lock-step
+    run: 512 rows with 20 to 60 cached positions, the live prefix shrinking from 127 sentences to 3, every
+    graph switch, the few-row kernels of the tail."""
+    w = S.workload("big128")
+    blob = w.blob()
+    order = np.argsort(-(w.src_lens + w.hp.cap_extra), kind="stable")
+    pick = sorted(set(order[:3].tolist() + order[8::16].tolist()))
+    assert len(pick) == 11
+    with lsq.Engine(blob, w.batch, w.beam, w.max_len) as eng:
+        res = lockstep(lsq, eng, blob, w, sentences=pick, mirror=False, verbose=True)
+        print({k: v for k, v in res.items() if k not in ("state", "judge", "bound")}, flush=True)
+        assert res["steps"] == int((w.src_lens[pick] + w.hp.cap_extra).max()) == w.max_len
+        assert res["strict_share"] >= 0.84, res["strict_share"]        # measured 0.866
+        assert res["worst_logit"] <= 2e-2
+        assert eng.decode_steps(8) == 0 and lsq.lsq_step_index() == w.max_len
 
 
 def test_big_shape_few_sentences_whole_translation(lsq):
@@ -64,9 +102,10 @@ def test_big_shape_few_sentences_whole_translation(lsq):
     w = S.custom(big.hp, [12, 30, 5], beam=4, max_len=30 + big.hp.cap_extra)
     blob = w.blob()
     with lsq.Engine(blob, w.batch, w.beam, w.max_len) as eng:
-        res = lockstep(lsq, eng, blob, w, check_wide=False, verbose=True)
+        res = lockstep(lsq, eng, blob, w, verbose=True)
+        print({k: v for k, v in res.items() if k not in ("state", "judge", "bound")}, flush=True)
         assert res["steps"] == 30 + big.hp.cap_extra
-        assert res["strict"] >= 0.5 * (12 + 30 + 5 + 3 * big.hp.cap_extra), res
-        assert res["worst_tight"] <= 1e-2
+        assert res["strict_share"] >= 0.86, res["strict_share"]        # measured 0.888
+        assert res["worst_logit"] <= 2e-2 and res["worst_mirror"] <= 1e-2
         ids, lens, scores = eng.get_beams()
         _properties(w, ids, lens, scores, w.hp)

@@ -275,3 +275,44 @@ def test_beam_step_hand_worked_example():
     # final = score / len: log(.3)/1 = -1.204 vs log(.1)/2 = -1.151 -> the longer one ranks first
     assert ln.tolist() == [[2, 1]] and ids[0, 0, :2].tolist() == [3, 0] and ids[0, 1, :1].tolist() == [2]
     np.testing.assert_allclose(fs[0], [np.log(.1) / 2, np.log(.3)], atol=1e-12)
+
+
+def test_length_penalty_hand_worked():
+    """score / len^alpha with alpha != 1, worked by hand: raw scores -6, -4, -8, -inf at lengths 4, 1, 16, 0.
+    alpha = 0.5: -6/2 = -3, -4/1 = -4, -8/4 = -2, -inf  -> order 2, 0, 1, 3.
+    alpha = 2:   -6/16 = -0.375, -4, -8/256 = -0.03125 -> order 2, 0, 1, 3;  alpha = 0: raw order 1, 0, 2, 3.
+    A dropped exponent (alpha taken as 1: -1.5, -4, -0.5) gives other values; an inverted one (multiplying
+    by len^alpha) reverses the order."""
+    for alpha, want_order, want in ((0.5, [2, 0, 1, 3], [-2.0, -3.0, -4.0, -np.inf]),
+                                    (2.0, [2, 0, 1, 3], [-0.03125, -0.375, -4.0, -np.inf]),
+                                    (0.0, [1, 0, 2, 3], [-4.0, -6.0, -8.0, -np.inf])):
+        hp = S.HParams(n_enc=1, n_dec=1, d_model=16, n_heads=2, d_ffn=32, vocab=12, max_pos=32, length_penalty=alpha)
+        m = O.Model(S.make_blob(hp), ctype=np.float64)
+        assert m.alpha == np.float32(alpha)
+        st = O.DecodeState(m, [3], 4, 20)
+        st.score[0] = [-6.0, -4.0, -8.0, -np.inf]
+        st.len[:] = [4, 1, 16, 0]
+        for r, n in enumerate(st.len):
+            st.tokens[r, 1:n + 1] = 4 + r
+        ids, ln, fs = O.finalize(m, st)
+        assert list(ln[0]) == [int(st.len[j]) for j in want_order]
+        np.testing.assert_allclose(fs[0], want, rtol=1e-12)
+        for i, j in enumerate(want_order):
+            assert (ids[0, i, :ln[0, i]] == 4 + j).all() and (ids[0, i, ln[0, i]:] == m.pad).all()
+
+
+def test_length_penalty_changes_the_winner_of_a_translation():
+    """Whole translations with alpha = 0.4 and alpha = 1.6 on the same weights: the search itself (raw
+    cumulative log-probabilities) is the same, the final ranking is score / len^alpha recomputed by hand."""
+    hp0 = S.HParams(n_enc=1, n_dec=1, d_model=16, n_heads=2, d_ffn=32, vocab=12, max_pos=32, cap_extra=3)
+    w = S.custom(hp0, [2, 5, 3], beam=4, max_len=9, std=0.6)
+    finals = {}
+    for alpha in (0.4, 1.6):
+        hp = S.HParams(**{**hp0.__dict__, "length_penalty": alpha})
+        m = O.Model(S.make_blob(hp, std=0.6), ctype=np.float64)
+        (ids, ln, fs), st = O.translate(m, w.src_ids, w.src_lens, 4, 9)
+        finals[alpha] = (st.score.copy(), st.len.copy())
+        want = st.score / st.len.reshape(3, 4).astype(np.float64) ** np.float64(np.float32(alpha))
+        for b in range(3):
+            np.testing.assert_allclose(fs[b], np.sort(want[b])[::-1], rtol=1e-12)
+    assert np.array_equal(finals[0.4][0], finals[1.6][0]) and np.array_equal(finals[0.4][1], finals[1.6][1])
