@@ -246,7 +246,9 @@ def main() -> int:
                            flops_per_launch=fl, bytes_per_launch=by, tflops=fl / us / 1e6, gbs=by / us / 1e3)
     ridge = PEAK_F16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     for name, d in table.items():
-        mfma = name.startswith("gemm") and d["flops_per_launch"] / max(d["bytes_per_launch"], 1.0) >= ridge
+        # a product makes 2 M FLOP per weight element = M FLOP per weight byte (fp16): above the ridge of
+        # peak FLOP/s over peak B/s it is held against the matrix cores, below it against the weight stream
+        mfma = name.startswith("gemm") and B * k >= ridge
         d["bound"] = "mfma" if mfma else "hbm"
         d["frac"] = d["tflops"] / PEAK_F16_TFLOPS if mfma else d["gbs"] / PEAK_HBM_GBS
     dom = max(table, key=lambda n: table[n]["total_ms"])
