@@ -352,6 +352,153 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
 }
 
 // ---------------------------------------------------------------------------------------------
+// Large products (vocabulary logits from 65 rows up, encoder and prefill layers): the same scheme with
+// 64x32 .. 128x64 wave tiles and the k-loop ordered for overlap -- a k-tile's first fragments are read and
+// its first matrix-core step issued BEFORE the next tile's LDS writes, and the global loads of the tile
+// after that follow the second step, so that the LDS pipe works on writes while the matrix cores run
+// (written in front of the multiplies, as in the kernel above, the writes of eight wavefronts queue ahead
+// of every wavefront's first fragment read: 613 -> 690 TFLOP/s at 4096^3 with 128x128 tiles, and with
+// 256x256 tiles of eight 128x64 wave tiles -- 96 B of LDS reads per clock and CU at full matrix-core rate
+// instead of 192 -- 870-920).  K a multiple of BK; D register stages of global loads.
+template <int BM, int BN, int BK, int WM, int WN, int D, typename OutT>
+__global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_large_kernel(const half_t* __restrict__ A, const half_t* __restrict__ B,
+                                                       int M, int N, int K, const int32_t* __restrict__ tpos,
+                                                       const half_t* __restrict__ bias, int act, int vec_ok,
+                                                       GemmOut out) {
+  constexpr int LDK = BK + 8;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int VPR = BK / 8;
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
+  constexpr int AV = BM * VPR / NT, BV = BN * VPR / NT;
+  constexpr int KS = BK / 16;
+  static_assert(D == 2 && KS >= 2 && AV >= 1 && BV >= 1, "two register stages, two LDS buffers");
+  extern __shared__ __attribute__((aligned(16))) half_t lds_tiles[];
+  half_t(*As)[BM * LDK] = reinterpret_cast<half_t(*)[BM * LDK]>(lds_tiles);
+  half_t(*Bs)[BN * LDK] = reinterpret_cast<half_t(*)[BN * LDK]>(lds_tiles + 2 * BM * LDK);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long tp = tpos ? *tpos : 0;
+  const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN, total = mt * nt;
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int m0 = (id % mt) * BM, n0 = (id / mt) * BN;
+  const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
+  const int nk = K / BK;
+  half8_t ra[D][AV], rb[D][BV];
+  auto gload = [&](half8_t(&a)[AV], half8_t(&b)[BV], int k0) {
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
+      a[i] = *reinterpret_cast<const half8_t*>(A + (size_t)min(m0 + row, M - 1) * K + k0 + kc);
+    }
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
+      b[i] = *reinterpret_cast<const half8_t*>(B + (size_t)min(n0 + row, N - 1) * K + k0 + kc);
+    }
+  };
+  auto sstore = [&](const half8_t(&a)[AV], const half8_t(&b)[BV], int buf) {
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
+      *reinterpret_cast<half8_t*>(&As[buf][row * LDK + kc]) = a[i];
+    }
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+      int v = tid + i * NT, row = v / VPR, kc = (v % VPR) * 8;
+      *reinterpret_cast<half8_t*>(&Bs[buf][row * LDK + kc]) = b[i];
+    }
+  };
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  half8_t af[2][TM], bf[2][TN];
+  auto frags = [&](int buf, int s, int slot) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      af[slot][i] = *reinterpret_cast<const half8_t*>(&As[buf][(wm + i * 32 + fr) * LDK + s * 16 + fk]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      bf[slot][j] = *reinterpret_cast<const half8_t*>(&Bs[buf][(wn + j * 32 + fr) * LDK + s * 16 + fk]);
+  };
+  auto mfmas = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
+  // this lane's bias values, requested behind the first tiles
+  float bv[TN][4][4];
+  {
+    const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 7) == 0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int n4 = n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4;
+        if (!bias) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = 0.f;
+        } else if (bias_vec && n4 + 3 < N) {
+          const half4_t b4 = *reinterpret_cast<const half4_t*>(bias + n4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = (float)b4[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][vg][e] = (float)bias[min(n4 + e, N - 1)];
+        }
+      }
+  }
+  sstore(ra[0], rb[0], 0);
+  gload(ra[0], rb[0], min(D, nk - 1) * BK);
+  __syncthreads();
+  // iteration kt: tile kt is in LDS buffer kt & 1, register slot (kt + 1) % D holds tile kt + 1
+  for (int it = 0; it < nk; it += D) {
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      const int kt = it + s;
+      if (kt >= nk) break;
+      const int buf = s & 1, sn = (s + 1) % D;
+      const bool more = kt + 1 < nk;
+      frags(buf, 0, 0);
+#pragma unroll
+      for (int q = 0; q < KS; ++q) {
+        if (q + 1 < KS) frags(buf, q + 1, (q + 1) & 1);
+        mfmas(q & 1);
+        if (q == 0 && more) sstore(ra[sn], rb[sn], buf ^ 1);
+        if (q == 1 && more) gload(ra[sn], rb[sn], min(kt + 1 + D, nk - 1) * BK);   // past the end: redundant, never used
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm + i * 32 + (lane & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int n = n0 + wn + j * 32 + vg * 8 + (lane >> 5) * 4;
+        if (n >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = activate(acc[i][j][vg * 4 + e] + bv[j][vg][e], act);
+        store4<OutT, false>(out, m, n, v, M, N, vec_ok, 0, tp);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Weights in fragment order, for the skinny kernels below.  Read from row-major rows, an MFMA
 // weight fragment is 16 bytes from each of 32 rows: 32 cache lines per load instruction, of which
 // the texture path retires few per clock.  Stored as [column block of 32][k-step of 16][lane][8]
@@ -754,6 +901,26 @@ static void launch_tiles(Kern kern, size_t lds, dim3 grid, int threads, hipStrea
   kern<<<grid, dim3(threads), lds, s>>>(A, B, M, N, K, (int)grid.y, out.tpos, bias, act, vec_ok, out);
 }
 
+template <int BM, int BN, int BK, int WM, int WN>
+static void run_f16_large(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
+                          int K, int act, int vec_ok, hipStream_t s) {
+  dim3 grid(((N + BN - 1) / BN) * ((M + BM - 1) / BM));
+  constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
+  // LDS above the default 64 KB limit is opted into once per kernel
+  if (out.f32_out) {
+    auto kern = gemm_f16_large_kernel<BM, BN, BK, WM, WN, 2, float>;
+    static bool raised = false;
+    if (!raised) { (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); raised = true; }
+    kern<<<grid, dim3(NT), lds, s>>>(A, B, M, N, K, out.tpos, bias, act, vec_ok, out);
+  } else {
+    auto kern = gemm_f16_large_kernel<BM, BN, BK, WM, WN, 2, half_t>;
+    static bool raised = false;
+    if (!raised) { (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); raised = true; }
+    kern<<<grid, dim3(NT), lds, s>>>(A, B, M, N, K, out.tpos, bias, act, vec_ok, out);
+  }
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int D, int KG = 1>
 static void run_f16(const half_t* A, const half_t* B, const half_t* bias, const GemmOut& out, int M, int N,
                     int K, int act, int vec_ok, hipStream_t s) {
@@ -857,11 +1024,17 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     else run_skinny<false, half_t>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
-  else if (tiles128 >= 200)
-    // 128x128 tiles (72 KB of LDS, two workgroups per CU), eight wavefronts of 64x32 each: measured
-    // ahead of four wavefronts of 64x64 on every shape that has this many tiles (vocabulary
-    // product from 65 rows up, encoder products), behind the smaller tiles below that
-    run_f16<128, 128, 64, 64, 32, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);
+  else if (tiles128 >= 200 && K % 64 == 0) {
+    // enough 128x128 tiles to fill the chip (vocabulary product from 65 rows up, encoder and prefill
+    // layers).  256x256 tiles (144 KB of LDS, eight wavefronts of 128x64) once there are about as many of
+    // those as CUs and more: half the LDS reads per FLOP (vocabulary product at 512 rows 54 -> 48 us,
+    // 4096^3 613 -> 870 TFLOP/s); otherwise 128x128 tiles (72 KB, two workgroups per CU, eight wavefronts
+    // of 64x32)
+    const long tiles256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles256 >= 256) run_f16_large<256, 256, 64, 128, 64>(a, b, bi, out, M, N, K, act, vec_ok, s);
+    else run_f16_large<128, 128, 64, 64, 32>(a, b, bi, out, M, N, K, act, vec_ok, s);
+  } else if (tiles128 >= 200)
+    run_f16<128, 128, 64, 64, 32, 2>(a, b, bi, out, M, N, K, act, vec_ok, s);   // ragged k
   else if ((long)((M + 63) / 64) * ((N + 63) / 64) > 256)
     // more 64x64 tiles than CUs: eight wavefronts on a 64x128 tile move fewer operand bytes per FLOP
     // into the CU and keep its LDS pipe as busy as two four-wave workgroups would
