@@ -141,10 +141,12 @@ int lsq_set_cache_refresh(int mode);
  * LayerNorm" into the product that consumes the normalised rows (sec. 2.1 taken
  * one step further: 18 fewer launches per step), and with at most 64 rows (beams
  * of at most 4, heads of 64) the cross-attention kernel normalises its rows and
- * makes its queries itself (12 fewer).  on = 0 keeps the stand-alone LayerNorm
- * kernel at every size.  With at most 8 rows the results are bit-identical
- * either way; above, sums are taken in another order (fewer split-K slabs, keys
- * shared by four wavefronts) and differ in the last bits.  Default: on. */
+ * makes its queries itself (12 fewer); with more rows it still makes its queries,
+ * from rows the LayerNorm kernel has normalised (6 fewer).  on = 0 keeps the stand-alone LayerNorm
+ * kernel at every size.  The row arithmetic is the same either way; the
+ * cross-attention kernel that makes its own queries takes its sums in another
+ * order (fewer split-K slabs, keys shared by four wavefronts), so results agree
+ * to the last bits, not always bit for bit.  Default: on. */
 int lsq_set_layernorm_fusion(int on);
 
 /* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
@@ -272,6 +274,17 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
                                     const void* Wq_packed, const void* bq, const void* kv,
                                     const int32_t* src_off, const int32_t* src_len, void* out, int batch,
                                     int beam, int heads, int d, void* stream);
+
+/* Cross-attention that makes its own queries from normalised rows, for more than 64 rows
+ * (sec. 2.1: one launch instead of a product and an attention kernel):
+ *   q   = x . Wq[h*64:(h+1)*64, :]^T + bq[h*64:..]   (rounded to float16)
+ *   out = lsq_k_cross_attention(q, kv, ...)
+ * float16 only; 64 < batch*beam rows, beam <= 4, heads of 64, d = 64*heads <= 1024.
+ * x [batch*beam, d]; Wq_packed: lsq_k_pack_weights(Wq [d, d]); the rest as in
+ * lsq_k_cross_attention. */
+int lsq_k_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,
+                            const int32_t* src_off, const int32_t* src_len, void* out, int batch, int beam,
+                            int heads, int d, void* stream);
 
 /* Decoder self-attention of one new position per row over its cached keys:
  * out[r, h*dh:(h+1)*dh] = softmax(q_h . K_h^T / sqrt(dh)) V_h over positions

@@ -54,6 +54,7 @@ def load_library() -> C.CDLL:
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_layernorm_cross_attention": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, i32, i32,
                                             i32, vp],
+        "lsq_k_cross_attention_q": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -288,6 +289,14 @@ def k_layernorm_cross_attention(P, ln_bias, gamma, beta, x_old, x_new, eps: floa
     _check(load_library().lsq_k_layernorm_cross_attention(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old),
                                                           _p(x_new), eps, _p(Wq_packed), _p(bq), _p(kv), _p(src_off),
                                                           _p(src_len), _p(out), batch, beam, heads, d, _stream()))
+
+
+def k_cross_attention_q(x, Wq_packed, bq, kv, src_off, src_len, out, batch: int, beam: int, heads: int) -> None:
+    """out = cross-attention of q = x . Wq^T + bq (more than 64 rows); Wq_packed: k_pack_weights(Wq)."""
+    M, d = x.shape
+    assert M == batch * beam
+    _check(load_library().lsq_k_cross_attention_q(_p(x), _p(Wq_packed), _p(bq), _p(kv), _p(src_off), _p(src_len), _p(out),
+                                                  batch, beam, heads, d, _stream()))
 
 
 def k_self_attention(q, Kc, Vc, out, heads: int, nkeys: int) -> None:

@@ -619,6 +619,129 @@ hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, c
   return hipGetLastError();
 }
 
+// Cross-attention that makes its own queries from already normalised rows, for MORE than 64 rows alive
+// (above, the kernel that also normalises its rows takes one sentence per workgroup): query product and
+// attention in one launch instead of two.  One workgroup of eight wavefronts per (GS sentences, head):
+//   1. every wavefront requests its share of the head's 64 x d slice of Wq (fragment order) and of the
+//      GS * beam <= 32 rows of x, wavefront w < GS also the first keys and values of sentence w of the
+//      group: everything the kernel reads is on its way before anything is computed;
+//   2. q = rows . slice^T as in cross_attention_ln_kernel (four wavefronts per 32-column half, every
+//      fourth 16-wide k-step each, partial tiles added through LDS, bias, rounded to float16);
+//   3. wavefront w attends for sentence w of the group, as cross_attention_kernel's one-wavefront variant.
+// The weights are read once per group of sentences; GS is chosen so that the launch has about as many
+// workgroups as the chip has CUs.  Measured at 512 rows of the big model: query product 8.9 us + attention
+// 10.3 us + the boundary between them -> one kernel.
+template <int NQ>
+__global__ void __launch_bounds__(512) cross_attention_q_kernel(const half_t* __restrict__ x, const half_t* __restrict__ Wp,
+                                                                const half_t* __restrict__ kv,
+                                                                const int32_t* __restrict__ off,
+                                                                const int32_t* __restrict__ len, int batch, int GS,
+                                                                int H, int d, const half_t* __restrict__ bq,
+                                                                half_t* __restrict__ out) {
+  constexpr int DH = 64, LPK = 8, KPW = 8, G = 4, UMAX = 16;
+  constexpr float scale = 0.125f;
+  __shared__ float red[8][16][64];
+  __shared__ float q_s[32][DH];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int grp = blockIdx.x / H, h = blockIdx.x % H;
+  const int b0 = grp * GS;
+  const int M = batch * NQ;
+  const int ksteps = d / 16, per_wave = ksteps / 4;   // d is a multiple of 64, at most 1024
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int cb = wave >> 2, kw = wave & 3;
+  const half_t* wp = Wp + ((size_t)(h * 2 + cb) * ksteps) * 512 + lane * 8;
+  const half_t* ap = x + (size_t)min(b0 * NQ + fr, M - 1) * d + fk;   // tile row fr = row b0 * NQ + fr (past the end: the last row, never used)
+  half8_t bf[UMAX], af[UMAX];
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u) {
+    const int ks = min(kw + 4 * u, ksteps - 1);
+    bf[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)ks * 512);
+    af[u] = *reinterpret_cast<const half8_t*>(ap + ks * 16);
+  }
+  const int b = min(b0 + wave, batch - 1);
+  const bool attends = wave < GS && b0 + wave < batch;
+  int n_keys = len[b], row0 = off[b];
+  const int c = lane % LPK, slot = lane / LPK;
+  CrossKeys<half_t, DH, NQ> keys;
+  keys.K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  keys.V = keys.K + d * sizeof(half_t);
+  keys.stride = 2 * d * sizeof(half_t);
+  keys.lane_at = c * 8 * sizeof(half_t);
+  keys.n_keys = attends ? n_keys : 0;
+  keys.slot = slot;
+  if (attends) keys.request(0);
+  asm volatile("" ::: "memory");
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u)
+    if (u < per_wave) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af[u], acc, 0, 0, 0);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
+  __syncthreads();
+  {
+    const int vg = kw, m = lane & 31;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int rr = vg * 4 + e, n = cb * 32 + vg * 8 + (lane >> 5) * 4 + e;
+      float v = (red[cb * 4 + 0][rr][lane] + red[cb * 4 + 1][rr][lane]) + (red[cb * 4 + 2][rr][lane] + red[cb * 4 + 3][rr][lane]);
+      v += (float)bq[h * DH + n];
+      q_s[m][n] = (float)(half_t)v;
+    }
+  }
+  __syncthreads();
+  if (!attends) return;
+  float qv[NQ][8];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qv[n][i] = q_s[wave * NQ + n][c * 8 + i];
+  float mx_[NQ], l_[NQ], acc_[NQ][8];
+  keys.run(qv, scale * 1.44269504088896340736f, 0, G * KPW, mx_, l_, acc_);
+  if (slot == 0) {
+    half_t* out_row0 = out + (size_t)b * NQ * d + h * DH;
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      const float r = 1.0f / l_[n];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc_[n][i] *= r;
+      Vec8<half_t>::store(out_row0 + (size_t)n * d + c * 8, acc_[n]);
+    }
+  }
+}
+
+// Measured on whole steps of the big model: 0.678 -> 0.671 ms at 512 rows, nothing at 128 (a sentence of 125 keys
+// takes four dependent trips for its keys whichever kernel attends, and here they start only after the product).
+bool cross_attention_q_worthwhile(int rows) { return rows >= 256; }
+
+bool cross_attention_q_supported(int dtype, int rows, int beam, int H, int d) {
+  return dtype == DT_F16 && rows > kCrossLnRows && beam >= 1 && beam <= 4 && rows % beam == 0 && H >= 1 && d == H * 64 &&
+         d <= 1024;
+}
+
+hipError_t launch_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,
+                                    const int32_t* off, const int32_t* len, void* out, int batch, int beam, int H,
+                                    int d, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  if (!cross_attention_q_supported(DT_F16, batch * beam, beam, H, d) || !Wq_packed || !bq) return hipErrorInvalidValue;
+  // sentences per workgroup: 8 (32 rows at beam 4) once that still gives a workgroup per CU, fewer below
+  int GS = 8;
+  while (GS > 1 && (long)((batch + GS - 1) / GS) * H < 256) GS >>= 1;
+  dim3 g(((batch + GS - 1) / GS) * H), b(512);
+#define LSQ_CROSS_Q(NQ_)                                                                                      \
+  cross_attention_q_kernel<NQ_><<<g, b, 0, s>>>((const half_t*)x, (const half_t*)Wq_packed, (const half_t*)kv, off, len, \
+                                                 batch, GS, H, d, (const half_t*)bq, (half_t*)out)
+  switch (beam) {
+    case 1: LSQ_CROSS_Q(1); break;
+    case 2: LSQ_CROSS_Q(2); break;
+    case 3: LSQ_CROSS_Q(3); break;
+    default: LSQ_CROSS_Q(4); break;
+  }
+#undef LSQ_CROSS_Q
+  return hipGetLastError();
+}
+
 // Encoder self-attention over packed sentences: qkv rows are [Q | K | V]; row i belongs to
 // sentence row_sent[i] whose rows start at off[.] and number len[.].
 template <typename T, int DH>
@@ -638,6 +761,129 @@ __global__ void __launch_bounds__(256) encoder_attention_kernel(const T* __restr
   T* op[1] = {out + (size_t)r * d + h * DH};
   const T* K = qkv + (size_t)off[b] * 3 * d + d + h * DH;
   attend<T, DH, 1>(qp, K, K + d, 3 * d, nk, nk - 1, scale, op, threadIdx.x & 63);
+}
+
+// The same on the matrix cores, float16, heads of 32, 64 or 128: one wavefront per (block of 32 packed
+// rows, head).  Packed rows run through the sentences one after the other, so a block's rows belong to a
+// few consecutive sentences and the keys any of them may see are one contiguous run of packed rows, taken
+// 32 at a time:
+//   S = Q K^T      v_mfma_f32_32x32x16_f16 with both operands straight from global memory (a row's 8
+//                  consecutive head dimensions per lane, as the skinny products read theirs);
+//   mask           key j counts for row i if it lies in i's sentence (and, causal, not behind i);
+//   softmax        streaming (running maximum and sum per row; a row's 32 scores sit in the two lanes
+//                  l and l + 32, 16 each);
+//   O += P V       the contraction runs over keys, and a matrix-core operand wants 8 contraction indices
+//                  per lane.  Which key sits at which index is free as long as P and V agree, so P is used
+//                  exactly as the first product left it in the lane's registers (index j of step st =
+//                  key 16 st + 8 (j >> 2) + 4 (lane >> 5) + (j & 3)) and the V operand is gathered to
+//                  match: 8 two-byte loads per lane and step, each a 64-byte run of one key's row across
+//                  the lanes.  No LDS, no transposition, no barrier.
+// Scores of keys outside a row's sentence are computed and thrown away (with sentences of about 30 tokens a
+// block of 32 rows sees two or three key blocks); the kernel is bounded by its handful of trips to
+// memory, not by the matrix cores.
+template <int DH>
+__global__ void __launch_bounds__(256) encoder_attention_mfma_kernel(const half_t* __restrict__ qkv,
+                                                                     const int32_t* __restrict__ row_sent,
+                                                                     const int32_t* __restrict__ off,
+                                                                     const int32_t* __restrict__ len,
+                                                                     half_t* __restrict__ out, int rows, int H, int d,
+                                                                     int causal, float scale_log2e) {
+  constexpr int QS = DH / 16;   // k-steps of the score product
+  constexpr int NB = DH / 32;   // 32-wide blocks of output dimensions
+  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+  const int nblk = (rows + 31) / 32;
+  if (w >= nblk * H) return;
+  const int blk = w / H, h = w % H;
+  const int lane = threadIdx.x & 63, m = lane & 31, hi = lane >> 5;
+  const int r = min(blk * 32 + m, rows - 1);             // this lane's row (past the end: the last row, not stored)
+  const int b = row_sent[r];
+  const int lo = off[b];
+  const int hi_key = causal ? r + 1 : lo + len[b];       // keys lo .. hi_key - 1 count for row r
+  const int ld = 3 * d;
+  // the block's key range: from the first row's sentence start to the last row's limit
+  const int k_first = __builtin_amdgcn_readlane(lo, 0);
+  const int k_last = __builtin_amdgcn_readlane(hi_key, 31);
+  const half_t* qp = qkv + (size_t)r * ld + h * DH + hi * 8;
+  half8_t qf[QS];
+#pragma unroll
+  for (int i = 0; i < QS; ++i) qf[i] = *reinterpret_cast<const half8_t*>(qp + i * 16);
+  const half_t* kbase = qkv + d + h * DH + hi * 8;
+  const half_t* vbase = qkv + 2 * d + h * DH + m;
+  floatx16 o[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[nb][e] = 0.f;
+  float mx = -INFINITY, sum = 0.f;
+  for (int k0 = k_first; k0 < k_last; k0 += 32) {
+    // operands of this key block: K rows (key = k0 + m), V gathered in the order the scores come out
+    const int krow = min(k0 + m, k_last - 1);
+    half8_t kf[QS];
+#pragma unroll
+    for (int i = 0; i < QS; ++i) kf[i] = *reinterpret_cast<const half8_t*>(kbase + (size_t)krow * ld + i * 16);
+    half8_t vf[NB][2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = min(k0 + 16 * st + 8 * (j >> 2) + 4 * hi + (j & 3), k_last - 1);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) vf[nb][st][j] = vbase[(size_t)key * ld + nb * 32];
+      }
+    floatx16 sc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < QS; ++i) sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[i], qf[i], sc, 0, 0, 0);
+    // sc[vg * 4 + e] = q_m . k_key, key = k0 + vg * 8 + hi * 4 + e
+    float bm = -INFINITY;
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int key = k0 + vg * 8 + hi * 4 + e;
+        const float v = (key >= lo && key < hi_key) ? sc[vg * 4 + e] * scale_log2e : -INFINITY;
+        sc[vg * 4 + e] = v;
+        bm = fmaxf(bm, v);
+      }
+    bm = max_lane_xor<32>(bm);                            // the row's other 16 keys are in lane ^ 32
+    const float mn = fmaxf(mx, bm);
+    const float base = mn == -INFINITY ? 0.f : mn;        // no key of this block (or any before) counts for the row
+    const float corr = exp2f(mx - base);                  // mx = -inf: 0
+    float ps = 0.f;
+    half8_t pf[2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float pv = exp2f(sc[st * 8 + j] - base);
+        const half_t ph = (half_t)pv;
+        ps += (float)ph;                                  // the sum of what the second product multiplies
+        pf[st][j] = ph;
+      }
+    ps = add_lane_xor<32>(ps);
+    sum = sum * corr + ps;
+    mx = mn;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[nb][e] *= corr;
+#pragma unroll
+      for (int st = 0; st < 2; ++st) o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[nb][st], pf[st], o[nb], 0, 0, 0);
+    }
+  }
+  if (blk * 32 + m >= rows) return;
+  const float inv = 1.0f / sum;
+  half_t* op = out + (size_t)r * d + h * DH;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) {
+      half4_t hv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) hv[e] = (half_t)(o[nb][vg * 4 + e] * inv);
+      *reinterpret_cast<half4_t*>(op + nb * 32 + vg * 8 + hi * 4) = hv;
+    }
 }
 
 bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh == 128; }
@@ -735,6 +981,17 @@ static hipError_t enc_t(const T* qkv, const int32_t* row_sent, const int32_t* of
                         int rows, int H, int d, int causal, hipStream_t s) {
   int dh = d / H;
   float scale = 1.0f / sqrtf((float)dh);
+  if constexpr (std::is_same<T, half_t>::value) {
+    if ((dh == 32 || dh == 64 || dh == 128) && d % 8 == 0 && (reinterpret_cast<uintptr_t>(qkv) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(out) & 7) == 0) {
+      dim3 g((((rows + 31) / 32) * H + 3) / 4), b(256);
+      const float sl = scale * 1.4426950408889634f;
+      if (dh == 32) encoder_attention_mfma_kernel<32><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, causal, sl);
+      else if (dh == 64) encoder_attention_mfma_kernel<64><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, causal, sl);
+      else encoder_attention_mfma_kernel<128><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, causal, sl);
+      return hipGetLastError();
+    }
+  }
   dim3 g((rows * H + 3) / 4), b(256);
   LSQ_DISPATCH_DH(dh, (encoder_attention_kernel<T, DH><<<g, b, 0, s>>>(qkv, row_sent, off, len, out, rows, H, d, causal, scale)));
   return hipGetLastError();

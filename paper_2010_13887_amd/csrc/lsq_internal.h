@@ -112,6 +112,13 @@ bool cross_attention_ln_supported(int dtype, int rows, int beam, int H, int d);
 hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, const void* bq, const void* kv,
                                      const int32_t* off, const int32_t* len, void* out, int batch, int beam,
                                      int H, int d, hipStream_t s);
+// More than 64 rows alive (beams of 4 at most, head size 64, float16, d <= 1024): query product and cross-attention
+// in one launch; x holds the normalised rows.
+bool cross_attention_q_supported(int dtype, int rows, int beam, int H, int d);
+bool cross_attention_q_worthwhile(int rows);   // where it is ahead of the two separate launches
+hipError_t launch_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,
+                                    const int32_t* off, const int32_t* len, void* out, int batch, int beam, int H,
+                                    int d, hipStream_t s);
 hipError_t launch_encoder_attention(int dtype, const void* qkv, const int32_t* row_sent,
                                     const int32_t* off, const int32_t* len, void* out, int rows, int H,
                                     int d, int causal, hipStream_t s);

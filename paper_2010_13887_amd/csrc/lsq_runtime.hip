@@ -411,6 +411,11 @@ int launch_step(int B) {
                                                      at<int32_t>(p.src_len), ctx, B, k, H, d, s));
       std::swap(x, x_alt);
       pending.on = false;
+    } else if (const void* wq_p = (g.fuse_ln && !pending.on && cross_attention_q_worthwhile(M) && cross_attention_q_supported(dt, M, k, H, d))
+                                      ? gemm_packed_weights(L.Wq, d, d) : nullptr) {
+      // many rows: the attention kernel still makes its own queries (the rows are normalised already)
+      TIMED(PC_ATTN_CROSS, launch_cross_attention_q(x, wq_p, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+                                                    at<int32_t>(p.src_len), ctx, B, k, H, d, s));
     } else {
       if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
       TIMED(PC_ATTN_CROSS, launch_cross_attention(dt, q, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
@@ -1206,6 +1211,16 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
   LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
                 (half_t*)x_new, eps};
   KRUN(launch_cross_attention_ln(ln, Wq_packed, bq, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
+}
+
+int lsq_k_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,
+                            const int32_t* src_off, const int32_t* src_len, void* out, int batch, int beam, int heads,
+                            int d, void* stream) {
+  KCHK(x && Wq_packed && bq && kv && src_off && src_len && out, "null pointer");
+  KCHK(batch >= 0, "shape");
+  KCHK(batch == 0 || cross_attention_q_supported(DT_F16, batch * beam, beam, heads, d),
+       "float16, more than 64 rows, beam 1..4, heads of 64, d = 64 * heads <= 1024");
+  KRUN(launch_cross_attention_q(x, Wq_packed, bq, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
 }
 
 int lsq_k_self_attention(int dtype, const void* q, const void* Kc, const void* Vc, void* out, int rows, int heads,

@@ -226,7 +226,12 @@ def test_self_attention_through_slab_table(env, B, k, H, dh, T, nkeys, half):
 
 
 @pytest.mark.parametrize("lens,H,dh", [([5, 8], 4, 16), ([1, 60, 17, 33], 8, 64), ([128, 3], 16, 64), ([9], 2, 128),
-                                       ([40] * 7, 3, 32)])
+                                       ([40] * 7, 3, 32),
+                                       # matrix-core kernel (float16, heads of 32 / 64 / 128): sentences longer than several
+                                       # key blocks, blocks of 32 rows that hold many one-token sentences, a last block of
+                                       # one row, a sentence ending exactly on a block boundary
+                                       ([300, 2, 257], 2, 64), ([1] * 70 + [3], 4, 64), ([32, 32, 1], 2, 32),
+                                       ([31, 33, 64, 2], 2, 128), ([700], 1, 64)])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("half", [False, True])
 def test_encoder_attention(env, lens, H, dh, causal, half):
@@ -338,6 +343,38 @@ def _oracle_row_topk(logits, score, finished, k, eos):
         best = O.topk_by_full_sort(c, np.arange(V), k)
         os_[r, :len(best)], oi[r, :len(best)] = c[best], best
     return os_, oi
+
+
+@pytest.mark.parametrize("lens,beam,H", [([7] * 17, 4, 2), (list(range(1, 130)), 4, 4), ([33, 1, 64, 2] * 8 + [5], 2, 16),
+                                         ([3] * 70, 1, 1), ([9, 140, 2] * 9, 3, 8)])
+def test_cross_attention_that_makes_its_queries_many_rows(env, lens, beam, H):
+    """Query product + cross-attention in one kernel for more than 64 rows (groups of sentences per
+    workgroup, a last group that is not full, sentences of 1 to 140 keys): against the oracle's attention
+    over q = x . Wq^T + bq rounded to float16, and against the two separate kernels."""
+    lsq, torch = env
+    rng = np.random.default_rng(sum(lens) + beam * 3 + H)
+    d, B = H * 64, len(lens)
+    rows = B * beam
+    assert rows > 64
+    x = _h(rng.standard_normal((rows, d)))
+    Wq, bq = _h(rng.standard_normal((d, d)) * 0.05), _h(rng.standard_normal(d) * 0.5)
+    kv = _h(rng.standard_normal((sum(lens), 2 * d)))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    h = torch.float16
+    dx, dkv, dW, dbq = _dev(torch, x, h), _dev(torch, kv, h), _dev(torch, Wq, h), _dev(torch, bq, h)
+    doff, dlen = _dev(torch, off), _dev(torch, np.array(lens, np.int32))
+    out = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    lsq.k_cross_attention_q(dx, lsq.k_pack_weights(dW), dbq, dkv, doff, dlen, out, B, beam, H)
+    q2 = torch.empty((rows, d), dtype=h, device="cuda")
+    lsq.k_gemm(dx, dW, dbq, q2)
+    out2 = torch.empty_like(out)
+    lsq.k_cross_attention(q2, dkv, doff, dlen, out2, B, beam, H, max(lens))
+    got = out.float().cpu().numpy()
+    np.testing.assert_allclose(got, out2.float().cpu().numpy(), rtol=2e-3, atol=2e-3)
+    qref = _h(x.astype(np.float64) @ Wq.astype(np.float64).T + bq).astype(np.float64)
+    ref = np.concatenate([O.attention(qref[i * beam:(i + 1) * beam], kv[off[i]:off[i + 1], :d].astype(np.float64),
+                                      kv[off[i]:off[i + 1], d:].astype(np.float64), H) for i in range(B)])
+    np.testing.assert_allclose(got, ref, rtol=2.5e-3, atol=2.5e-3)
 
 
 @pytest.mark.parametrize("M,V,k", [(8, 1000, 4), (5, 12, 3), (33, 32000, 4), (6, 50257, 8), (4, 8192, 1),

@@ -52,6 +52,20 @@ def draw(seed):
                 groups=int(rng.choice(groups)) if groups else 1, strength=float(rng.choice([0.0, 0.5, 2.0])))
 
 
+F32_STATS = dict(runs=0, steps=0, over=0, over_ceiling=0, worst_bound=0.0, worst_ratio=0.0)
+
+
+def _collect(res, w):
+    if w.hp.dtype != 0:
+        return
+    F32_STATS["runs"] += 1
+    F32_STATS["steps"] += res["steps"]
+    F32_STATS["over"] += res["f32_steps_over"]
+    F32_STATS["over_ceiling"] += res["f32_steps_over_ceiling"]
+    F32_STATS["worst_bound"] = max(F32_STATS["worst_bound"], res["f32_worst_bound"])
+    F32_STATS["worst_ratio"] = max(F32_STATS["worst_ratio"], res["f32_worst_ratio"])
+
+
 # 597: beams of 8 over 37 tokens; a sentence finishes in an order that the comparison took over from the library
 # within its band, and must then be left alone by both sides while the other sentences go on
 @pytest.mark.parametrize("seed", list(range(48)) + [597])
@@ -67,6 +81,7 @@ def test_random_configuration_matches_oracle(lsq, seed):
             res = lockstep_diverse(lsq, eng, blob, w, c["groups"], c["strength"])
         else:
             res = lockstep(lsq, eng, blob, w)
+        _collect(res, w)
         caps = np.minimum(w.src_lens + w.hp.cap_extra, w.max_len)
         assert res["steps"] <= int(caps.max())
         ids, lens, _ = eng.get_beams()
@@ -103,7 +118,20 @@ def test_random_decoder_only_configuration_matches_oracle(lsq, seed):
     blob = w.blob(ln_jitter=0.1)
     with lsq.Engine(blob, w.batch + spare, 1, w.max_len) as eng:
         res = lockstep_gpt(lsq, eng, blob, w)
+        _collect(res, w)
         assert res["steps"] == w.hp.cap_extra
         ids, lens, _ = eng.get_beams()
         assert (lens[:, 0] == w.hp.cap_extra).all()
         assert np.array_equal(ids[:, 0, :w.hp.cap_extra], res["state"].tokens[:, int(w.src_lens[0]):int(w.src_lens[0]) + w.hp.cap_extra])
+
+
+def test_float32_bound_statistics(lsq):
+    """How often the float32 models above needed more than the stated 1e-4 (see parity.Float32Shadow), and how far the
+    library's logit error ever was from plain numpy float32's at the same step.  Runs after the configurations
+    (same module); the numbers are those quoted in the design notes."""
+    print("float32 models of the random configurations:", F32_STATS, flush=True)
+    if F32_STATS["runs"] == 0:
+        pytest.skip("the random configurations were deselected")
+    assert F32_STATS["worst_ratio"] <= 4.0                                     # measured: 2.53
+    assert F32_STATS["over_ceiling"] <= 0.08 * F32_STATS["steps"] + 2      # measured: 48 of 891 steps
+    assert F32_STATS["over"] <= 0.5 * F32_STATS["steps"] + 2
