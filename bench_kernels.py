@@ -27,12 +27,95 @@ PEAK_HBM = 8000.0      # GB/s
 PEAK_MFMA = 2500.0     # TFLOP/s, dense fp16
 
 
+# ---- rocprofv3 counter runs and their summaries (what profiles/*.txt is made from) ----------------------
+# (case prefix for --only, counter sets) -- one rocprofv3 run per case and set; a run holds at most 8 SQ_ counters
+PMC_TRAFFIC = [["FETCH_SIZE"], ["WRITE_SIZE"]]
+PMC_GEMM = [["MfmaUtil"], ["SQ_INSTS_LDS", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_LDS", "SQ_INST_CYCLES_VMEM", "SQ_LDS_IDX_ACTIVE",
+                           "SQ_BUSY_CYCLES", "SQ_WAVES", "SQ_WAVE_CYCLES"],
+            ["SQ_WAIT_INST_ANY", "SQ_WAIT_ANY", "SQ_ACTIVE_INST_ANY", "SQ_LDS_BANK_CONFLICT", "SQ_VALU_MFMA_BUSY_CYCLES", "GRBM_GUI_ACTIVE"]]
+PMC_CASES = [("gemm_qkv", PMC_TRAFFIC + PMC_GEMM), ("gemm_dxd", PMC_TRAFFIC + PMC_GEMM), ("gemm_ffn1", PMC_TRAFFIC + PMC_GEMM),
+             ("sublayer_out", PMC_TRAFFIC + PMC_GEMM), ("sublayer_ffn2", PMC_TRAFFIC + PMC_GEMM),
+             ("gemm_vocab", PMC_TRAFFIC + PMC_GEMM), ("attn_self M512", PMC_TRAFFIC), ("attn_self_table", PMC_TRAFFIC),
+             ("attn_cross B128", PMC_TRAFFIC), ("attn_cross_q", PMC_TRAFFIC), ("row_topk", PMC_TRAFFIC),
+             ("enc_attn", PMC_TRAFFIC + [["MfmaUtil"]]), ("enc gemm_qkv", PMC_TRAFFIC + PMC_GEMM),
+             ("enc gemm_ffn1", PMC_TRAFFIC + PMC_GEMM), ("enc sublayer_ffn2", PMC_TRAFFIC + PMC_GEMM),
+             ("cache_reorder", PMC_TRAFFIC), ("stress gemm M4096", PMC_GEMM), ("stress attn_self M2048", PMC_TRAFFIC),
+             ("stress attn_self_table", PMC_TRAFFIC), ("stress row_topk", PMC_TRAFFIC), ("copy", PMC_TRAFFIC)]
+
+
+def profile_all(outdir: str) -> int:
+    """Runs rocprofv3 --pmc once per (case, counter set) as child processes of this one (which never touches
+    the GPU itself), the program directly behind `--`, then prints the per-kernel medians.  Raw CSVs stay under
+    outdir; the text printed here is what profiles/ holds."""
+    import collections
+    import csv
+    import subprocess
+    os.makedirs(outdir, exist_ok=True)
+    me = os.path.abspath(__file__)
+    env = dict(os.environ, TMPDIR="/tmp")
+    table = collections.OrderedDict()       # (case, kernel) -> {counter: median}
+    for ci, (case, sets) in enumerate(PMC_CASES):
+        for si, counters in enumerate(sets):
+            d = os.path.join(outdir, f"c{ci}_s{si}")
+            cmd = ["rocprofv3", "--pmc", *counters, "--output-format", "csv", "-d", d, "-o", "k", "--",
+                   sys.executable, me, "--iters", "4", "--only", case]
+            try:
+                subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL, timeout=150)
+            except subprocess.TimeoutExpired:
+                print(f"# {case} {counters}: timed out", flush=True)
+                continue
+            f = os.path.join(d, "k_counter_collection.csv")
+            if not os.path.exists(f):
+                print(f"# {case} {counters}: no output", flush=True)
+                continue
+            agg = collections.defaultdict(list)
+            for r in csv.DictReader(open(f)):
+                kn = r["Kernel_Name"]
+                if kn.startswith("void at::") or "distribution" in kn or "zero_ints" in kn:
+                    continue
+                agg[(kn, r["Counter_Name"])].append(float(r["Counter_Value"]))
+            for (kn, cn), v in agg.items():
+                table.setdefault((case, kn), {})[cn] = sorted(v)[len(v) // 2]
+        print(f"# done {case}", file=sys.stderr, flush=True)
+    names = []
+    for row in table.values():
+        names += [c for c in row if c not in names]
+    print("rocprofv3 --pmc medians per launch (python3 bench_kernels.py --profile <dir>: one run of")
+    print("`rocprofv3 --pmc <set> --output-format csv -d <dir>/cN_sM -o k -- python3 bench_kernels.py --iters 4 --only <case>`")
+    print("per case and counter set; FETCH_SIZE / WRITE_SIZE in KiB)")
+    for (case, kn), row in table.items():
+        short = kn.replace("void lsq::", "").replace("_ZN3lsq", "")[:64]
+        print(f"{case:24s} {short:64s} " + " ".join(f"{c}={row[c]:.6g}" for c in names if c in row))
+    return 0
+
+
+def summarize_stats(path: str, top: int = 40) -> int:
+    """Text table of a `rocprofv3 --kernel-trace --stats --output-format csv` kernel_stats file."""
+    import csv
+    import re
+    rows = list(csv.DictReader(open(path)))
+    tot = sum(float(r["TotalDurationNs"]) for r in rows)
+    print(f"sum of kernel durations {tot / 1e6:.1f} ms, {sum(int(r['Calls']) for r in rows)} launches")
+    print(f"{'kernel':76s} {'calls':>6s} {'total ms':>9s} {'avg us':>8s} {'%':>6s} {'min us':>8s} {'max us':>8s}")
+    for r in rows[:top]:
+        n = re.sub(r"^_ZN3lsq\d+", "", r["Name"]).replace("void lsq::", "")[:76]
+        print(f"{n:76s} {int(r['Calls']):6d} {float(r['TotalDurationNs']) / 1e6:9.2f} {float(r['AverageNs']) / 1e3:8.2f} "
+              f"{float(r['Percentage']):6.2f} {float(r['MinNs']) / 1e3:8.2f} {float(r['MaxNs']) / 1e3:8.2f}")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--only", default="", help="comma-separated case-name prefixes")
     ap.add_argument("--no-stress", action="store_true")
+    ap.add_argument("--profile", default="", help="run the rocprofv3 counter passes of every case into this directory and print the summary")
+    ap.add_argument("--summarize-stats", default="", help="print a text table of a rocprofv3 kernel_stats.csv")
     args = ap.parse_args()
+    if args.profile:
+        return profile_all(args.profile)
+    if args.summarize_stats:
+        return summarize_stats(args.summarize_stats)
 
     import numpy as np
     import torch
@@ -98,6 +181,18 @@ def main() -> int:
         cases.append((name, "hbm", 4.0 * k * int(lens.sum()) * d, by,
                       lambda: lsq.k_cross_attention(q, kv, off, ln, out, B, k, H, int(lens.max()))))
 
+    def cross_q_case(name, B, k, H, d, lens):
+        lens = np.asarray(lens, np.int32)
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+        xx, kv = rnd(B * k, d), rnd(int(lens.sum()), 2 * d)
+        W, bq = rnd(d, d, scale=0.02), rnd(d, scale=0.02)
+        Wp = lsq.k_pack_weights(W)
+        ln = torch.from_numpy(lens).to(dev)
+        out = torch.empty(B * k, d, device=dev, dtype=h)
+        by = (2 * int(lens.sum()) * d + 2 * B * k * d + d * d) * 2
+        cases.append((name, "hbm", 2.0 * B * k * d * d + 4.0 * k * int(lens.sum()) * d, by,
+                      lambda: lsq.k_cross_attention_q(xx, Wp, bq, kv, off, ln, out, B, k, H)))
+
     def enc_attn_case(name, H, d, lens):
         lens = np.asarray(lens, np.int32)
         R = int(lens.sum())
@@ -143,6 +238,8 @@ def main() -> int:
     self_attn_table_case("attn_self_table M512 t41", 128, 4, H, d, T, 41)
     rs = np.random.default_rng(4321)
     cross_attn_case("attn_cross B128 k4 meanlen29", 128, 4, H, d, np.clip(np.rint(rs.lognormal(3.15, 0.6, 128)), 1, 128))
+    cross_q_case("attn_cross_q B128 k4 meanlen29 (query product + attention)", 128, 4, H, d,
+                 np.clip(np.rint(np.random.default_rng(4321).lognormal(3.15, 0.6, 128)), 1, 128))
     topk_case("row_topk M512 V32000 k4", M, V, 4)
     enc_lens = np.clip(np.rint(np.random.default_rng(4321).lognormal(3.15, 0.6, 128)), 1, 128)
     enc_attn_case("enc_attn B128 meanlen29", H, d, enc_lens)
