@@ -160,6 +160,15 @@ int lsq_set_layernorm_fusion(int on);
  * (which fails with LSQ_E_ARG otherwise).  Encoder-decoder models only. */
 int lsq_set_diversity(int groups, float strength);
 
+/* Debug aid for the shared memory plan (sec. 2.3): with canaries on, lsq_workspace_bytes / lsq_init put a
+ * 256-byte red zone, filled with a pattern, behind every region of the workspace (weights, caches, beam state,
+ * each of the decoder's intermediates, the end of the workspace).  Set before lsq_workspace_bytes; LSQ_E_STATE
+ * once a model is loaded.  lsq_debug_check_canaries waits for the stream and returns how many zones no longer
+ * hold the pattern (0 = no kernel wrote outside its region); the zones behind the decoder's intermediates are
+ * checked from the end of lsq_encode on (the encoder's intermediates share those bytes before).  Default: off. */
+int lsq_set_canaries(int on);
+int lsq_debug_check_canaries(void);
+
 /* Number of decode steps taken since the last lsq_encode. */
 int lsq_step_index(void);
 

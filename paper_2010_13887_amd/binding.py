@@ -51,6 +51,8 @@ def load_library() -> C.CDLL:
         "lsq_set_cache_refresh": [i32],
         "lsq_set_diversity": [i32, f32],
         "lsq_set_layernorm_fusion": [i32],
+        "lsq_set_canaries": [i32],
+        "lsq_debug_check_canaries": [],
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_layernorm_cross_attention": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, i32, i32,
                                             i32, vp],
@@ -143,6 +145,16 @@ def lsq_set_graphs(on: bool) -> None:
 def lsq_set_layernorm_fusion(on: bool) -> None:
     """LayerNorm inside the consuming product when at most 8 rows are alive (default on)."""
     _check(load_library().lsq_set_layernorm_fusion(int(on)))
+
+
+def lsq_set_canaries(on: bool) -> None:
+    """Red zones behind every region of the workspace, from the next lsq_workspace_bytes / lsq_init on (debug aid)."""
+    _check(load_library().lsq_set_canaries(int(on)))
+
+
+def lsq_debug_check_canaries() -> int:
+    """How many red zones have been written to (0 = none)."""
+    return _check(load_library().lsq_debug_check_canaries())
 
 
 def lsq_set_diversity(groups: int = 1, strength: float = 0.0) -> None:

@@ -169,7 +169,16 @@ struct DecLayer {
 // Byte offsets into the workspace.  Everything is sized for max_batch / beam / max_len once;
 // encoder intermediates and decoder intermediates are never live together and share `scratch`,
 // and inside the decoder the FFN activation and the logits share bytes as well.
+// Debug aid for the memory plan (sec. 2.3: buffers that share one arena are exactly where an overrun or a wrong
+// lifetime would hide): with canaries on, every region of the plan is followed by a 256-byte red zone filled
+// with a pattern; lsq_debug_check_canaries says how many have been touched.
+bool g_canaries = false;
+constexpr size_t kCanaryBytes = 256;
+constexpr unsigned char kCanaryByte = 0xA5;
+
 struct Plan {
+  std::vector<size_t> canaries;       // red zones behind the regions that live as long as the model
+  std::vector<size_t> dec_canaries;   // ... behind the decoder's intermediates (valid from the end of lsq_encode on)
   size_t weights, wpacked, pe, cache, cross, score, tokens, len, fin, parent, anc, pen_tok, pen_n, cand_plain, cap, order, src_off, src_len, active, step_state,
       cand_score, cand_idx, out_ids, out_lens, out_scores, scratch, total;
   // encoder view of scratch
@@ -185,7 +194,12 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   const size_t esz = hp.dtype == DT_F16 ? 2 : 4;
   const size_t M = (size_t)B * k, R = (size_t)B * T, d = hp.d, F = hp.F, V = hp.V;
   size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += up(bytes);
+    if (g_canaries) { p.canaries.push_back(off); off += kCanaryBytes; }
+    return o;
+  };
   p.weights = take(weight_bytes);
   p.wpacked = take(packed_weight_bytes(hp));
   p.pe = take((size_t)T * d * 4);
@@ -222,7 +236,12 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.e_y = etake(R * d * esz);     // pre-LN models: normalised copy of the residual stream   // e_tmp: one fp32 slab (no split-K at encoder sizes)
   // decoder phase
   size_t q = p.scratch;
-  auto dtake = [&](size_t bytes) { size_t o = q; q += up(bytes); return o; };
+  auto dtake = [&](size_t bytes) {
+    size_t o = q;
+    q += up(bytes);
+    if (g_canaries) { p.dec_canaries.push_back(q); q += kCanaryBytes; }
+    return o;
+  };
   p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
   p.d_tmp = dtake(kMaxSplits * M * d * 4);   // fp32 partial-sum slabs of the split-K GEMMs
   p.d_y = dtake(M * d * esz);
@@ -230,7 +249,9 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
+  if (g_canaries) { p.dec_canaries.push_back(q); q += kCanaryBytes; }
   p.total = std::max(e, q);
+  if (g_canaries) { p.total = up(p.total); p.canaries.push_back(p.total); p.total += kCanaryBytes; }   // the end of the workspace
   return p;
 }
 
@@ -645,6 +666,7 @@ int encode_gpt(const int32_t* ids, const int32_t* lens, int batch, int stride) {
                             x, y, (float*)tmp, R, d, F, 1, s)) return rc;
     }
   }
+  for (size_t c : p.dec_canaries) HIPCHK(hipMemsetAsync(g.ws + c, kCanaryByte, kCanaryBytes, s));
   g.batch = batch;
   g.rows_enc = R;
   g.prompt_len = P;
@@ -763,6 +785,8 @@ int lsq_init(const void* weights, size_t weights_bytes, int max_batch, int beam,
     if (e != hipSuccess) return fail(LSQ_E_HIP, "position table upload failed: %s", hipGetErrorString(e));
   }
 
+  for (size_t c : plan.canaries) HIPCHK(hipMemsetAsync(g.ws + c, kCanaryByte, kCanaryBytes, g.stream));
+  HIPCHK(hipStreamSynchronize(g.stream));
   g.pinned_ints = (size_t)3 * max_batch * max_len + 4 * (size_t)max_batch + 2 + (size_t)max_batch * (max_len + 2) + 8;
   HIPCHK(hipHostMalloc((void**)&g.pinned, g.pinned_ints * 4, hipHostMallocDefault));
 
@@ -899,6 +923,7 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
                            at<int32_t>(p.active), at<int32_t>(p.step_state), g.anc_on ? at<int32_t>(p.anc) : nullptr,
                            at<int32_t>(p.pen_n), batch, g.beam, g.beam / g.groups, g.max_len, hp.bos,
                            hp.pad, s));
+  for (size_t c : p.dec_canaries) HIPCHK(hipMemsetAsync(g.ws + c, kCanaryByte, kCanaryBytes, s));
   g.batch = batch;
   g.rows_enc = (int)R;
   g.src_longest = *std::max_element(src_lens, src_lens + batch);
@@ -982,6 +1007,28 @@ int lsq_set_cache_refresh(int mode) {
 }
 
 int lsq_step_index(void) { return g.state >= 3 ? g.t : 0; }
+
+int lsq_set_canaries(int on) {
+  if (g.state >= 2) return fail(LSQ_E_STATE, "a model is loaded: the memory plan is fixed; call lsq_free first");
+  g_canaries = on != 0;
+  return LSQ_OK;
+}
+
+int lsq_debug_check_canaries(void) {
+  if (g.state < 2) return fail(LSQ_E_STATE, "lsq_init has not been called");
+  HIPCHK(hipStreamSynchronize(g.stream));
+  std::vector<size_t> zones = g.plan.canaries;
+  if (g.state >= 3) zones.insert(zones.end(), g.plan.dec_canaries.begin(), g.plan.dec_canaries.end());
+  std::vector<unsigned char> host(kCanaryBytes);
+  int damaged = 0;
+  for (size_t c : zones) {
+    HIPCHK(hipMemcpy(host.data(), g.ws + c, kCanaryBytes, hipMemcpyDeviceToHost));
+    bool ok = true;
+    for (unsigned char v : host) ok = ok && v == kCanaryByte;
+    damaged += ok ? 0 : 1;
+  }
+  return damaged;
+}
 
 int lsq_get_beams(int32_t* out_ids, int32_t* out_lens, float* out_scores) {
   if (g.state < 3) return fail(LSQ_E_STATE, "lsq_encode has not been called");

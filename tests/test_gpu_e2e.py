@@ -230,3 +230,41 @@ def test_edge_shapes_match_oracle(lsq, beam, lens, vocab, cap_extra, max_len, dt
         ids, out_lens, scores = eng.get_beams()
         assert ((out_lens >= 0) & (out_lens <= max_len)).all()
         assert ((ids >= 0) & (ids < vocab)).all()
+
+
+def test_no_kernel_writes_outside_its_region(lsq):
+    """Red zones behind every region of the workspace (weights, caches, beam state, each decoder intermediate, the
+    end) stay untouched through whole translations -- float32 and float16 models, both cache-refresh modes, a
+    decoder-only model, ragged sizes, a batch smaller than the maximum -- and a byte written into one is seen."""
+    cases = []
+    w = S.workload("tiny")
+    cases.append((w, w.blob(), {}))
+    hp = S.HParams(n_enc=2, n_dec=2, d_model=128, n_heads=2, d_ffn=264, vocab=1003, max_pos=64, dtype=1, cap_extra=4)
+    w = S.custom(hp, [3, 17, 9, 1, 12, 6, 11], beam=4, max_len=20, std=0.05)
+    cases.append((w, w.blob(ln_jitter=0.1), {}))
+    cases.append((w, w.blob(ln_jitter=0.1), dict(refresh=lsq.REFRESH_MOVE)))
+    hp = S.HParams(arch=1, n_enc=0, n_dec=2, d_model=96, n_heads=3, d_ffn=136, vocab=301, max_pos=64, act=1, norm=1,
+                   dtype=1, sample_topk=5, cap_extra=7)
+    w = S.custom(hp, [6] * 5, beam=1, max_len=14, std=0.08)
+    cases.append((w, w.blob(ln_jitter=0.1), {}))
+    try:
+        lsq.lsq_set_canaries(True)
+        for w, blob, opt in cases:
+            lsq.lsq_set_cache_refresh(opt.get("refresh", lsq.REFRESH_TABLE))
+            with lsq.Engine(blob, w.batch + 2, w.beam, w.max_len) as eng:
+                assert lsq.lsq_debug_check_canaries() == 0
+                for _ in range(2):
+                    eng.translate(w.src_ids, w.src_lens, sync_every=3)
+                    assert lsq.lsq_debug_check_canaries() == 0
+                eng.encode(w.src_ids[:1], w.src_lens[:1])
+                eng.decode_steps(2)
+                assert lsq.lsq_debug_check_canaries() == 0
+                eng.workspace[-1] = 0                        # the last byte of the workspace lies in the last red zone
+                assert lsq.lsq_debug_check_canaries() == 1
+        with pytest.raises(lsq.LsqError):
+            with lsq.Engine(cases[0][1], 2, 4, 8):
+                lsq.lsq_set_canaries(False)                  # the plan of a loaded model is fixed
+    finally:
+        lsq.lsq_free()
+        lsq.lsq_set_canaries(False)
+        lsq.lsq_set_cache_refresh(lsq.REFRESH_TABLE)
