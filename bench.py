@@ -56,7 +56,7 @@ PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 TRAFFIC_CASES = {
     "gemm_qkv": ["gemm_qkv"], "gemm_dxd": ["gemm_dxd"], "gemm_ffn1": ["gemm_ffn1"],
     "gemm_out": ["sublayer_out"], "gemm_ffn2": ["sublayer_ffn2"],
-    "gemm_vocab": ["gemm_vocab"], "attn_self": ["attn_self_table"], "attn_cross": ["attn_cross"],
+    "gemm_vocab": ["gemm_vocab"], "attn_self": ["attn_self_table"], "attn_cross": ["attn_cross B128"], "attn_cross_q": ["attn_cross_q"],
     "row_topk": ["row_topk"], "cache_reorder": ["cache_reorder"],
 }
 
@@ -70,7 +70,7 @@ def measured_traffic(cls):
     total, found = 0.0, False
     for line in open(path):
         m = re.match(r"(\S.{25}) (\S.{47}) +([\d.]+) +([\d.]+)\s*$", line)
-        if m and m.group(1).strip() in cases and "rocclr" not in m.group(2) and not m.group(2).startswith("add_layernorm"):
+        if m and any(m.group(1).strip().startswith(c) for c in cases) and "rocclr" not in m.group(2) and not m.group(2).startswith("add_layernorm"):
             total += (float(m.group(3)) + float(m.group(4))) * 1e6
             found = True
     return total if found else None
@@ -97,6 +97,8 @@ def class_work(name, hp, B, k, t_mean, s_mean):
         return (4.0 * M * t_mean * d, (2 * M * t_mean * d + 2 * M * d) * es)
     if name == "attn_cross":     # encoder K and V once per sentence (shared by its beams)
         return (4.0 * M * s_mean * d, (2 * B * s_mean * d + 2 * M * d) * es)
+    if name == "attn_cross_q":   # the same plus the query product: Wq and the normalised rows in
+        return (2.0 * M * d * d + 4.0 * M * s_mean * d, (2 * B * s_mean * d + 3 * M * d + d * d) * es)
     if name == "add_layernorm":
         return (8.0 * M * d, 3 * M * d * es)
     if name == "embed":

@@ -50,6 +50,7 @@ def profile_all(outdir: str) -> int:
     import collections
     import csv
     import subprocess
+    outdir = os.path.abspath(outdir)
     os.makedirs(outdir, exist_ok=True)
     me = os.path.abspath(__file__)
     env = dict(os.environ, TMPDIR="/tmp")
@@ -77,15 +78,60 @@ def profile_all(outdir: str) -> int:
             for (kn, cn), v in agg.items():
                 table.setdefault((case, kn), {})[cn] = sorted(v)[len(v) // 2]
         print(f"# done {case}", file=sys.stderr, flush=True)
-    names = []
-    for row in table.values():
-        names += [c for c in row if c not in names]
-    print("rocprofv3 --pmc medians per launch (python3 bench_kernels.py --profile <dir>: one run of")
-    print("`rocprofv3 --pmc <set> --output-format csv -d <dir>/cN_sM -o k -- python3 bench_kernels.py --iters 4 --only <case>`")
-    print("per case and counter set; FETCH_SIZE / WRITE_SIZE in KiB)")
     for (case, kn), row in table.items():
-        short = kn.replace("void lsq::", "").replace("_ZN3lsq", "")[:64]
-        print(f"{case:24s} {short:64s} " + " ".join(f"{c}={row[c]:.6g}" for c in names if c in row))
+        print(f"# raw {case:24s} {kn[:64]:64s} " + " ".join(f"{c}={v:.6g}" for c, v in row.items()), file=sys.stderr)
+    print_pmc_tables(table)
+    return 0
+
+
+def print_pmc_tables(table) -> None:
+    """table: (case, kernel) -> {counter: median per launch}.  Prints the HBM-traffic table (FETCH_SIZE / WRITE_SIZE
+    scaled by what the same counters read for a 1 GiB -> 1 GiB copy) and the matrix-core / LDS table."""
+    noise = ("pack_weights", "__amd_rocclr_copyBuffer", "zero_ints")
+    rows = [(c, k, r) for (c, k), r in table.items() if c == "copy" and "rocclr" in k or not any(n in k for n in noise)]
+    copy = next((r for c, k, r in rows if c == "copy" and "FETCH_SIZE" in r), None)
+    fr = (1 << 30) / (copy["FETCH_SIZE"] * 1024) if copy else 2.0
+    fw = (1 << 30) / (copy["WRITE_SIZE"] * 1024) if copy else 1.0
+    print("HBM traffic per launch: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB), medians over the launches of a case,")
+    print(f"scaled by the same counters' readings for a 1 GiB -> 1 GiB copy (reads x {fr:.2f}, writes x {fw:.2f}).")
+    print("command: python3 bench_kernels.py --profile <dir>   (one `rocprofv3 --pmc <counter> --output-format csv -d <dir>/cN_sM")
+    print("-o k -- python3 bench_kernels.py --iters 4 --only <case>` per case and counter)")
+    print()
+    print(f"{'case':26s} {'kernel':48s} {'read MB':>9s} {'write MB':>9s}")
+    for c, k, r in rows:
+        if "FETCH_SIZE" in r and "WRITE_SIZE" in r:
+            short = k.replace("void lsq::", "").lstrip("0123456789")[:48]
+            print(f"{c:26s} {short:48s} {fr * r['FETCH_SIZE'] * 1024 / 1e6:9.1f} {fw * r['WRITE_SIZE'] * 1024 / 1e6:9.1f}")
+    print()
+    print("Matrix cores and LDS of the product kernels (same command; counter sets MfmaUtil | SQ_INSTS_LDS SQ_WAIT_INST_LDS")
+    print("SQ_ACTIVE_INST_LDS SQ_INST_CYCLES_VMEM SQ_LDS_IDX_ACTIVE SQ_BUSY_CYCLES SQ_WAVES SQ_WAVE_CYCLES | SQ_WAIT_INST_ANY SQ_WAIT_ANY")
+    print("SQ_ACTIVE_INST_ANY SQ_LDS_BANK_CONFLICT SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE).  MfmaUtil = SQ_VALU_MFMA_BUSY_CYCLES /")
+    print("(GRBM_GUI_ACTIVE x SIMDs) in %; the wait columns are shares of SQ_WAVE_CYCLES (wavefront-cycles): waiting to issue an LDS")
+    print("instruction, waiting to issue any instruction, waiting in s_waitcnt; LDS instr = SQ_INSTS_LDS per launch.")
+    print()
+    print(f"{'case':22s} {'kernel':44s} {'MfmaUtil%':>9s} {'wait LDS':>9s} {'wait issue':>10s} {'wait cnt':>9s} {'LDS instr':>10s} {'bank confl':>10s}")
+    for c, k, r in rows:
+        if "MfmaUtil" in r and r.get("SQ_WAVE_CYCLES"):
+            wc = r["SQ_WAVE_CYCLES"]
+            short = k.replace("void lsq::", "").lstrip("0123456789")[:44]
+            print(f"{c:22s} {short:44s} {r['MfmaUtil']:9.2f} {r.get('SQ_WAIT_INST_LDS', 0) / wc:9.3f} {r.get('SQ_WAIT_INST_ANY', 0) / wc:10.3f} "
+                  f"{r.get('SQ_WAIT_ANY', 0) / wc:9.3f} {r.get('SQ_INSTS_LDS', 0):10.0f} {r.get('SQ_LDS_BANK_CONFLICT', 0):10.0f}")
+        elif "MfmaUtil" in r:
+            short = k.replace("void lsq::", "").lstrip("0123456789")[:44]
+            print(f"{c:22s} {short:44s} {r['MfmaUtil']:9.2f}")
+
+
+def format_pmc(path: str) -> int:
+    """Re-prints the tables from the raw `case kernel COUNTER=value ...` lines of an earlier --profile run."""
+    import collections
+    table = collections.OrderedDict()
+    for line in open(path):
+        if "=" not in line or line.startswith("#") or line.startswith("`"):
+            continue
+        case, rest = line[:24].strip(), line[25:]
+        kernel, vals = rest[:64].strip(), rest[64:].split()
+        table[(case, kernel)] = {v.split("=")[0]: float(v.split("=")[1]) for v in vals if "=" in v}
+    print_pmc_tables(table)
     return 0
 
 
@@ -110,10 +156,13 @@ def main() -> int:
     ap.add_argument("--only", default="", help="comma-separated case-name prefixes")
     ap.add_argument("--no-stress", action="store_true")
     ap.add_argument("--profile", default="", help="run the rocprofv3 counter passes of every case into this directory and print the summary")
+    ap.add_argument("--format-pmc", default="", help="print the tables from the raw counter lines an earlier --profile run printed")
     ap.add_argument("--summarize-stats", default="", help="print a text table of a rocprofv3 kernel_stats.csv")
     args = ap.parse_args()
     if args.profile:
         return profile_all(args.profile)
+    if args.format_pmc:
+        return format_pmc(args.format_pmc)
     if args.summarize_stats:
         return summarize_stats(args.summarize_stats)
 

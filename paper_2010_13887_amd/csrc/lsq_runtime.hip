@@ -40,11 +40,11 @@ int fail(int code, const char* fmt, ...) {
 // per kernel class.  Events come from a host-side pool that only grows.
 enum ProfClass {
   PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
-  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_COUNT
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
                                           "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
-                                          "beam_refine", "cache_reorder", "gemm_out"};
+                                          "beam_refine", "cache_reorder", "gemm_out", "attn_cross_q"};
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
@@ -435,7 +435,7 @@ int launch_step(int B) {
     } else if (const void* wq_p = (g.fuse_ln && !pending.on && cross_attention_q_worthwhile(M) && cross_attention_q_supported(dt, M, k, H, d))
                                       ? gemm_packed_weights(L.Wq, d, d) : nullptr) {
       // many rows: the attention kernel still makes its own queries (the rows are normalised already)
-      TIMED(PC_ATTN_CROSS, launch_cross_attention_q(x, wq_p, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+      TIMED(PC_ATTN_CROSS_Q, launch_cross_attention_q(x, wq_p, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                     at<int32_t>(p.src_len), ctx, B, k, H, d, s));
     } else {
       if (int rc = product(PC_GEMM_DD, L.Wq, L.bq, plain_out(q, d), d, 0)) return rc;
