@@ -149,6 +149,14 @@ int lsq_set_cache_refresh(int mode);
  * to the last bits, not always bit for bit.  Default: on. */
 int lsq_set_layernorm_fusion(int on);
 
+/* Few rows alive (float16 encoder-decoder models with heads of 64, beam <= 4, d = 256 or 512: with
+ * wider models the separate kernels are faster): each attention sublayer of a decoder layer runs as one launch up to its output
+ * projection (sec. 2.1 taken further; lsq_k_self_attention_block, lsq_k_cross_attention_block)
+ * while at most max_rows rows are alive.  0 switches this off; default and largest value 64.  Same
+ * tokens as the separate kernels; scores equal to float16 rounding (other summation orders).  Also
+ * off when lsq_set_layernorm_fusion(0).  May be called at any time. */
+int lsq_set_attention_blocks(int max_rows);
+
 /* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
  * al. 2016, Hamming diversity).  The beam is split into `groups` groups of
  * beam / groups hypotheses; at every step the groups of a sentence choose in
@@ -283,6 +291,38 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
                                     const void* Wq_packed, const void* bq, const void* kv,
                                     const int32_t* src_off, const int32_t* src_len, void* out, int batch,
                                     int beam, int heads, int d, void* stream);
+
+/* The self-attention sublayer of a decoder layer up to its output projection in one launch, for
+ * at most 64 rows (sec. 2.1 taken further: the products join the fused kernels where a step is a
+ * chain of launch latencies).  For every sentence b, head h and row r of b:
+ *   rows      = LN(x_old + sum_s P[s] + ln_bias) * gamma + beta   (splits 1..4; written to x_new)
+ *               or x_old as it is                                  (splits 0; x_new and P unused)
+ *   [q|k|v]   = rows . Wqkv[{0,d,2d} + h*64 .. +63, :]^T + bqkv[..]   (rounded to float16)
+ *   Kc, Vc[r, nkeys, h*64..] = k, v
+ *   ctx       = softmax(q . K^T / 8) V over positions 0..nkeys of r's history, rounded to float16
+ *               (position j < nkeys: slab (r - r % beam) + slab_table[r*(T+1) + j], or slab r when
+ *               slab_table is NULL; position nkeys: the new k, v)
+ *   P_out[h][r][:] = ctx . Wo[:, h*64 .. h*64+63]^T   (float; the sum over h is ctx_all . Wo^T)
+ * float16 only; beam 1..4, heads of 64, d = 64*heads a multiple of 256, at most 1024.
+ * Wqkv_packed, Wo_packed: lsq_k_pack_weights of Wqkv [3d, d] and Wo [d, d]; Kc, Vc [rows, T, d];
+ * P float [splits, rows, d]; P_out float [heads, rows, d]; 0 <= nkeys < T.  All device, 16-byte
+ * aligned.  Positions beyond nkeys may be read and are discarded. */
+int lsq_k_self_attention_block(const float* P, int splits, const void* ln_bias, const void* gamma,
+                               const void* beta, const void* x_old, void* x_new, float eps,
+                               const void* Wqkv_packed, const void* bqkv, const void* Wo_packed, void* Kc,
+                               void* Vc, const int32_t* slab_table, int nkeys, float* P_out, int batch,
+                               int beam, int heads, int d, int T, void* stream);
+
+/* The cross-attention sublayer up to its output projection in one launch, for at most 64 rows:
+ * lsq_k_layernorm_cross_attention with 1..16 slabs behind the LayerNorm (the block above leaves
+ * one per head) whose context rows are multiplied by the head's 64 columns of Wo:
+ *   P_out[h][r][:] = ctx[r, h*64..+63] . Wo[:, h*64 .. h*64+63]^T   (float [heads, rows, d]).
+ * Same limits as lsq_k_self_attention_block. */
+int lsq_k_cross_attention_block(const float* P, int splits, const void* ln_bias, const void* gamma,
+                                const void* beta, const void* x_old, void* x_new, float eps,
+                                const void* Wq_packed, const void* bq, const void* Wo_packed,
+                                const void* kv, const int32_t* src_off, const int32_t* src_len,
+                                float* P_out, int batch, int beam, int heads, int d, void* stream);
 
 /* Cross-attention that makes its own queries from normalised rows, for more than 64 rows
  * (sec. 2.1: one launch instead of a product and an attention kernel):

@@ -51,12 +51,17 @@ def load_library() -> C.CDLL:
         "lsq_set_cache_refresh": [i32],
         "lsq_set_diversity": [i32, f32],
         "lsq_set_layernorm_fusion": [i32],
+        "lsq_set_attention_blocks": [i32],
         "lsq_set_canaries": [i32],
         "lsq_debug_check_canaries": [],
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_layernorm_cross_attention": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, i32, i32,
                                             i32, vp],
         "lsq_k_cross_attention_q": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_self_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32,
+                                       i32, i32, vp],
+        "lsq_k_cross_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32,
+                                        vp],
         "lsq_debug_read": [i32, vp, sz],
         "lsq_profile_enable": [i32],
         "lsq_profile_classes": [],
@@ -145,6 +150,11 @@ def lsq_set_graphs(on: bool) -> None:
 def lsq_set_layernorm_fusion(on: bool) -> None:
     """LayerNorm inside the consuming product when at most 8 rows are alive (default on)."""
     _check(load_library().lsq_set_layernorm_fusion(int(on)))
+
+
+def lsq_set_attention_blocks(max_rows: int) -> None:
+    """Attention sublayers as one launch each while at most max_rows rows are alive (0: off; default 64)."""
+    _check(load_library().lsq_set_attention_blocks(int(max_rows)))
 
 
 def lsq_set_canaries(on: bool) -> None:
@@ -301,6 +311,29 @@ def k_layernorm_cross_attention(P, ln_bias, gamma, beta, x_old, x_new, eps: floa
     _check(load_library().lsq_k_layernorm_cross_attention(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old),
                                                           _p(x_new), eps, _p(Wq_packed), _p(bq), _p(kv), _p(src_off),
                                                           _p(src_len), _p(out), batch, beam, heads, d, _stream()))
+
+
+def k_self_attention_block(P, ln_bias, gamma, beta, x_old, x_new, eps: float, Wqkv_packed, bqkv, Wo_packed, Kc, Vc,
+                           slab_table, nkeys: int, P_out, batch: int, beam: int, heads: int) -> None:
+    """Self-attention sublayer up to the output projection's per-head partial sums P_out [heads, rows, d]; P None: the
+    rows are x_old as they are.  Kc, Vc [rows, T, d] receive the new position at index nkeys."""
+    M, d = x_old.shape
+    splits = 0 if P is None else P.shape[0]
+    assert M == batch * beam and tuple(P_out.shape) == (heads, M, d)
+    _check(load_library().lsq_k_self_attention_block(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old), _p(x_new),
+                                                     eps, _p(Wqkv_packed), _p(bqkv), _p(Wo_packed), _p(Kc), _p(Vc),
+                                                     _p(slab_table), nkeys, _p(P_out), batch, beam, heads, d, Kc.shape[1],
+                                                     _stream()))
+
+
+def k_cross_attention_block(P, ln_bias, gamma, beta, x_old, x_new, eps: float, Wq_packed, bq, Wo_packed, kv, src_off,
+                            src_len, P_out, batch: int, beam: int, heads: int) -> None:
+    """Cross-attention sublayer up to the output projection's per-head partial sums P_out [heads, rows, d]."""
+    splits, M, d = P.shape
+    assert M == batch * beam and tuple(P_out.shape) == (heads, M, d)
+    _check(load_library().lsq_k_cross_attention_block(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old), _p(x_new),
+                                                      eps, _p(Wq_packed), _p(bq), _p(Wo_packed), _p(kv), _p(src_off),
+                                                      _p(src_len), _p(P_out), batch, beam, heads, d, _stream()))
 
 
 def k_cross_attention_q(x, Wq_packed, bq, kv, src_off, src_len, out, batch: int, beam: int, heads: int) -> None:

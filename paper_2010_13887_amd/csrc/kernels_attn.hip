@@ -742,6 +742,516 @@ hipError_t launch_cross_attention_q(const void* x, const void* Wq_packed, const 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Whole attention sublayers in one launch (paper sec. 2.1: fewer kernels between the products, taken
+// to the point where the products themselves join in), for the last sentences of a batch and for
+// small batches, where a step is a chain of launches that each cost their latency.  A workgroup owns a
+// (sentence, head): it streams that head's slices of the weights itself, so nothing it needs comes
+// from another workgroup of the same launch, and what it leaves is the head's share of the output
+// projection as one float32 slab per head; whoever consumes the sublayer adds the H slabs, the
+// projection's bias and the residual, and normalises (the next block below, or the LayerNorm kernel).
+
+// a <- P[0] + P[1] + ... + P[S-1] at one 8-element column, slabs `slab` floats apart, added in index
+// order (as add_partials does for up to 4)
+template <int CH>
+__device__ __forceinline__ void sum_slabs(const float* __restrict__ P, size_t slab, int S, float (&a)[8]) {
+  for (int s0 = 0; s0 < S; s0 += CH) {
+    float prt[CH][8];
+#pragma unroll
+    for (int sp = 0; sp < CH; ++sp)
+      if (s0 + sp < S) Vec8<float>::load(P + (size_t)(s0 + sp) * slab, prt[sp]);
+#pragma unroll
+    for (int sp = 0; sp < CH; ++sp)
+      if (s0 + sp < S) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = (s0 + sp == 0) ? prt[sp][i] : __fadd_rn(a[i], prt[sp][i]);
+      }
+  }
+}
+
+// Row `r` of LayerNorm(x_old + (sum of the slabs + bias)) * g + b by one wavefront, into LDS (and to
+// x_new when `keep`); ln.splits == 0: the row is x_old as it is.  d <= 1024.  CH: slabs requested together.
+template <int CH>
+__device__ __forceinline__ void block_row(const LnInput& ln, int r, int M, int d, int lane, bool keep,
+                                          half_t* __restrict__ dst) {
+  constexpr int NV = 2;
+  const size_t slab = (size_t)M * d;
+  if (ln.splits == 0) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int cc = (j * 64 + lane) * 8;
+      if (cc < d) *reinterpret_cast<half8_t*>(dst + cc) = *reinterpret_cast<const half8_t*>(ln.x_old + (size_t)r * d + cc);
+    }
+    return;
+  }
+  float v[NV][8], gv[NV][8], bv[NV][8];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int cc = (j * 64 + lane) * 8;
+    if (cc < d) {
+      float t[8], a[8];
+      Vec8<half_t>::load(ln.bias + cc, t);
+      Vec8<half_t>::load(ln.x_old + (size_t)r * d + cc, v[j]);
+      Vec8<half_t>::load(ln.g + cc, gv[j]);
+      Vec8<half_t>::load(ln.b + cc, bv[j]);
+      sum_slabs<CH>(ln.P + (size_t)r * d + cc, slab, ln.splits, a);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[j][i] = __fadd_rn(v[j][i], __fadd_rn(a[i], t[i]));
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
+    }
+  }
+  float o[NV][8];
+  layernorm_row<NV>(v, gv, bv, d, ln.eps, lane, o);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int cc = (j * 64 + lane) * 8;
+    if (cc < d) {
+      Vec8<half_t>::store(dst + cc, o[j]);
+      if (keep) Vec8<half_t>::store(ln.x_new + (size_t)r * d + cc, o[j]);
+    }
+  }
+}
+
+// The head's share of an output projection: P_out[h][r][:] = ctx[r, 0..63] . Wo[:, h*64 .. h*64+63]^T for
+// the NQ rows in ctx_s (float16, LDS).  fo holds this wavefront's fragments of the slice: out blocks
+// wave*nb + i (i < nb = d/256), k-steps h*4 + kq (kq < 4) at fo[i*4 + kq].
+template <int NQ>
+__device__ __forceinline__ void block_out_projection(const half8_t (&fo)[16], const half_t (&ctx_s)[NQ][64 + 8], int wave,
+                                                     int lane, int nb, int h, int row0, int M, int d,
+                                                     float* __restrict__ P_out) {
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const half_t* cr = &ctx_s[min(fr, NQ - 1)][fk];
+  half8_t af[4];
+#pragma unroll
+  for (int kq = 0; kq < 4; ++kq) af[kq] = *reinterpret_cast<const half8_t*>(cr + kq * 16);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (i < nb) {
+      floatx16 acc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+      for (int kq = 0; kq < 4; ++kq) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fo[i * 4 + kq], af[kq], acc, 0, 0, 0);
+      if (fr < NQ) {
+        float* dst = P_out + ((size_t)h * M + row0 + fr) * d + (wave * nb + i) * 32 + (lane >> 5) * 4;
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          floatx4 o = {acc[vg * 4 + 0], acc[vg * 4 + 1], acc[vg * 4 + 2], acc[vg * 4 + 3]};
+          *reinterpret_cast<floatx4*>(dst + vg * 8) = o;
+        }
+      }
+    }
+}
+
+template <int NQ>
+__device__ __forceinline__ void block_request_out_fragments(half8_t (&fo)[16], const half_t* __restrict__ Wo, int wave,
+                                                            int lane, int nb, int h, int ksteps) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (i < nb) {
+#pragma unroll
+      for (int kq = 0; kq < 4; ++kq)
+        fo[i * 4 + kq] = *reinterpret_cast<const half8_t*>(Wo + ((size_t)(wave * nb + i) * ksteps + h * 4 + kq) * 512 + lane * 8);
+    }
+}
+
+// Self-attention sublayer up to the output projection's partial sums.  Workgroup (sentence b, head h),
+// eight wavefronts:
+//   1. requests before anything is computed: the slab numbers of each attending wavefront's first trip
+//      through the history (speculatively, as attend_partial does; its keys and values follow after
+//      step 2); the NQ rows' LayerNorm inputs; the first 32 k-steps of the head's 192 x d slice of
+//      Wqkv (fragment order; wavefronts 0..5 each own 32 of the 192 columns over all of k);
+//   2. wavefronts 6 and 7 normalise the NQ rows into LDS (head 0 also to x_new);
+//   3. q, k, v of the new position: bias added, rounded to float16, kept in LDS; k and v also go to
+//      position `nkeys` of the rows' slabs.  While the last fragments are multiplied the head's 64
+//      k-columns of Wo are requested;
+//   4. every row's history (positions 0..nkeys-1, through the slab table when there is one) is shared
+//      by NSH wavefronts; the new position's key and value come from LDS; partial softmax sums are
+//      merged through LDS and the context rounded to float16;
+//   5. the head's share of the output projection (above).
+template <int NQ, bool TABLE>
+__global__ void __launch_bounds__(512) self_block_kernel(const half_t* __restrict__ Wqkv, const half_t* __restrict__ Wo,
+                                                         const int32_t* __restrict__ anc,
+                                                         const int32_t* __restrict__ tp, int nkeys_base, int H, int d,
+                                                         int T_, int M, half_t* __restrict__ Kc,
+                                                         half_t* __restrict__ Vc, const half_t* __restrict__ bqkv,
+                                                         LnInput ln, float* __restrict__ P_out) {
+  constexpr int DH = 64, LPK = 8, KPI = 8, U = 4;
+  constexpr int NSH = NQ <= 2 ? 4 : 2;   // wavefronts that share a row's history
+  using raw_t = half8_t;
+  __shared__ __attribute__((aligned(16))) half_t a_rows[NQ][1024 + 8];
+  __shared__ float qkv_s[3][NQ][DH];
+  __shared__ float part[NQ][NSH][LPK][10];
+  __shared__ __attribute__((aligned(16))) half_t ctx_s[NQ][DH + 8];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int ksteps = d / 16, nb = d / 256;
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int nkeys = nkeys_base + (tp ? *tp : 0);   // cached positions; the new one gets this index
+  // --- 1a. the history stream of this wavefront: row an, every NSH-th position from ash
+  const int an = wave % NQ, ash = wave / NQ;
+  const bool attends = ash < NSH;
+  const int g = lane / LPK, c = lane % LPK;
+  const int step = KPI * NSH;
+  const int jfirst = ash + g * NSH;
+  const int r_att = b * NQ + an;
+  const size_t hbase = (size_t)(TABLE ? b * NQ : r_att) * T_ * d + h * DH;
+  const char* Kb = reinterpret_cast<const char*>(Kc + hbase);
+  const char* Vb = reinterpret_cast<const char*>(Vc + hbase);
+  const int32_t* slot = TABLE ? anc + (size_t)r_att * (T_ + 1) : nullptr;
+  const int slot_stride = T_ * d, slot_max = NQ - 1;
+  int sl[U];
+  raw_t kn[U], vn[U];
+  auto request_slots = [&](int jb, int last) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) sl[u] = TABLE ? slot[min(jb + u * step, last)] : 0;
+  };
+  auto request = [&](int jb, int last) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned at = ((TABLE ? min(max(sl[u], 0), slot_max) * slot_stride : 0) + min(jb + u * step, last) * d + c * 8) *
+                          (unsigned)sizeof(half_t);
+      kn[u] = *reinterpret_cast<const raw_t*>(Kb + at);
+      vn[u] = *reinterpret_cast<const raw_t*>(Vb + at);
+    }
+  };
+  const int jcap = T_ - 1;
+  if (attends) request_slots(jfirst, jcap);
+  // --- 1b/2. LayerNorm inputs are requested (and awaited) by the wavefronts that normalise
+  // --- 1c. weight fragments: wavefront (part, column half) = (wave >> 1, wave & 1) for wave < 6
+  const bool multiplies = wave < 6;
+  const int prt_ = wave >> 1, cb = wave & 1;
+  const half_t* wp = Wqkv + ((size_t)((prt_ * d) / 32 + h * 2 + cb) * ksteps) * 512 + lane * 8;
+  half8_t f0[16], f1[16];
+  half4_t bias4[4];
+  if (multiplies) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) f0[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(u, ksteps - 1) * 512);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) f1[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(16 + u, ksteps - 1) * 512);
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg)
+      bias4[vg] = *reinterpret_cast<const half4_t*>(bqkv + prt_ * d + h * DH + cb * 32 + vg * 8 + (lane >> 5) * 4);
+  } else {
+    block_request_out_fragments<NQ>(f0, Wo, wave, lane, nb, h, ksteps);
+  }
+  asm volatile("" ::: "memory");
+  // the two wavefronts that multiply nothing normalise
+  if (wave >= 6)
+    for (int n = wave - 6; n < NQ; n += 2) block_row<4>(ln, b * NQ + n, M, d, lane, h == 0, a_rows[n]);
+  __syncthreads();
+  // the first trip through the history is not needed before the products are done: requested here,
+  // where the registers of the LayerNorm are free again
+  if (attends) {
+    request(jfirst, jcap);
+    request_slots(jfirst + U * step, jcap);
+  }
+  asm volatile("" ::: "memory");
+  // --- 3. the new position's q, k, v
+  if (multiplies) {
+    floatx16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    const half_t* ar = &a_rows[min(fr, NQ - 1)][fk];
+    auto multiply = [&](const half8_t (&f)[16], int ks0) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (ks0 + u < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[u], *reinterpret_cast<const half8_t*>(ar + (ks0 + u) * 16), acc, 0, 0, 0);
+    };
+    multiply(f0, 0);
+    if (ksteps > 32) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) f0[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(32 + u, ksteps - 1) * 512);
+    } else {
+      block_request_out_fragments<NQ>(f0, Wo, wave, lane, nb, h, ksteps);
+    }
+    multiply(f1, 16);
+    if (ksteps > 48) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) f1[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(48 + u, ksteps - 1) * 512);
+    }
+    if (ksteps > 32) {
+      multiply(f0, 32);
+      block_request_out_fragments<NQ>(f0, Wo, wave, lane, nb, h, ksteps);
+    }
+    if (ksteps > 48) multiply(f1, 48);
+    if (fr < NQ) {
+      const int r = b * NQ + fr;
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int col = cb * 32 + vg * 8 + (lane >> 5) * 4;
+        half4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o[e] = (half_t)(acc[vg * 4 + e] + (float)bias4[vg][e]);
+          qkv_s[prt_][fr][col + e] = (float)o[e];
+        }
+        if (prt_ >= 1) *reinterpret_cast<half4_t*>((prt_ == 1 ? Kc : Vc) + ((size_t)r * T_ + nkeys) * d + h * DH + col) = o;
+      }
+    }
+  }
+  __syncthreads();
+  // --- 4. attention
+  if (attends) {
+    constexpr float qscale = 0.125f * 1.44269504088896340736f;   // scores in units of log 2
+    float q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = qkv_s[0][an][c * 8 + i];
+    float m = -INFINITY, l = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    int jb = jfirst;
+    bool speculative = true;
+    do {
+      float kv[U][8], vv[U][8];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        Vec8<half_t>::unpack(kn[u], kv[u]);
+        Vec8<half_t>::unpack(vn[u], vv[u]);
+      }
+      if (speculative) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (jb + u * step >= nkeys) {   // read from beyond the history: may be anything
+#pragma unroll
+            for (int i = 0; i < 8; ++i) vv[u][i] = 0.f;
+          }
+      }
+      const int jn = jb + U * step;
+      if (jn < nkeys) {   // the next trip, requested before this one's arithmetic
+        request(jn, nkeys - 1);
+        request_slots(jn + U * step, nkeys - 1);
+      }
+      float sc[U], mx = m;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += q[i] * kv[u][i];
+        s = group_sum<LPK>(s) * qscale;
+        sc[u] = (jb + u * step < nkeys) ? s : -INFINITY;
+        mx = fmaxf(mx, sc[u]);
+      }
+      const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+      m = mx;
+      l *= corr;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] *= corr;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = sc[u] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sc[u] - mx);
+        l += p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += p * vv[u][i];
+      }
+      jb = jn;
+      speculative = false;
+    } while (jb < nkeys);
+    {
+      // the new position: its key and value never left the workgroup; counted once, by the first key
+      // slot of the row's first wavefront
+      float s = 0.f, vt[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { s += q[i] * qkv_s[1][an][c * 8 + i]; vt[i] = qkv_s[2][an][c * 8 + i]; }
+      s = group_sum<LPK>(s) * qscale;
+      const float st = (ash == 0 && g == 0) ? s : -INFINITY;
+      const float mx = fmaxf(m, st);
+      const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+      const float p = st == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st - mx);
+      m = mx;
+      l = l * corr + p;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + p * vt[i];
+    }
+    // the key slots of the wavefront, then (through LDS) the wavefronts of the row
+    float mx = m;
+    for_lane_bits<LPK>([&](auto bit) { mx = max_lane_xor<decltype(bit)::value>(mx); });
+    const float c1 = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+    l *= c1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= c1;
+    for_lane_bits<LPK>([&](auto bit) {
+      constexpr int O = decltype(bit)::value;
+      l = add_lane_xor<O>(l);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = add_lane_xor<O>(acc[i]);
+    });
+    if (g == 0) {
+      part[an][ash][c][0] = mx;
+      part[an][ash][c][1] = l;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part[an][ash][c][2 + i] = acc[i];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < NQ * LPK) {
+    const int n = threadIdx.x / LPK, cc = threadIdx.x % LPK;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NSH; ++w) mx = fmaxf(mx, part[n][w][cc][0]);   // finite: the first wavefront saw the new position
+    float sum = 0.f, o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < NSH; ++w) {
+      const float mw = part[n][w][cc][0];
+      const float cw = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);
+      sum += part[n][w][cc][1] * cw;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o8[i] += part[n][w][cc][2 + i] * cw;
+    }
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o8[i] *= inv;
+    Vec8<half_t>::store(&ctx_s[n][cc * 8], o8);
+  }
+  __syncthreads();
+  // --- 5. the head's share of the output projection
+  block_out_projection<NQ>(f0, ctx_s, wave, lane, nb, h, b * NQ, M, d, P_out);
+}
+
+// Cross-attention sublayer up to the output projection's partial sums: cross_attention_ln_kernel (its
+// steps 1-4, with up to 16 slabs behind the LayerNorm: the self-attention block above leaves one per
+// head) whose context rows stay in LDS and are multiplied by the head's 64 k-columns of Woc.
+template <int NQ>
+__global__ void __launch_bounds__(512) cross_block_kernel(const half_t* __restrict__ Wp, const half_t* __restrict__ Wo,
+                                                          const half_t* __restrict__ kv,
+                                                          const int32_t* __restrict__ off,
+                                                          const int32_t* __restrict__ len, int H, int d, int M,
+                                                          LnInput ln, const half_t* __restrict__ bq,
+                                                          float* __restrict__ P_out) {
+  constexpr int DH = 64, LPK = 8, KPW = 8, G = 4, UMAX = 16;
+  constexpr float scale = 0.125f;
+  __shared__ __attribute__((aligned(16))) half_t a_rows[NQ][1024 + 8];
+  __shared__ float red[8][16][64];
+  __shared__ float q_s[NQ][DH];
+  __shared__ float part[4][NQ][DH + 2];
+  __shared__ __attribute__((aligned(16))) half_t ctx_s[NQ][DH + 8];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int ksteps = d / 16, per_wave = ksteps / 4, nb = d / 256;
+  const int fr = lane & 31, fk = (lane >> 5) * 8;
+  const int cb = wave >> 2, kw = wave & 3;
+  const half_t* wp = Wp + ((size_t)(h * 2 + cb) * ksteps) * 512 + lane * 8;
+  half8_t bf[UMAX];
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u) bf[u] = *reinterpret_cast<const half8_t*>(wp + (size_t)min(kw + 4 * u, ksteps - 1) * 512);
+  int n_keys = len[b], row0 = off[b];
+  asm volatile("" : "+s"(n_keys), "+s"(row0));
+  const int c = lane % LPK, slot = lane / LPK;
+  CrossKeys<half_t, DH, NQ> keys;
+  keys.K = reinterpret_cast<const char*>(kv + (size_t)row0 * 2 * d + h * DH);
+  keys.V = keys.K + d * sizeof(half_t);
+  keys.stride = 2 * d * sizeof(half_t);
+  keys.lane_at = c * 8 * sizeof(half_t);
+  keys.n_keys = n_keys;
+  keys.slot = slot;
+  const int jfirst = wave < 4 ? wave * G * KPW : 0x7fffffff;
+  if (jfirst < n_keys) keys.request(jfirst);
+  asm volatile("" ::: "memory");
+  if (wave < NQ) block_row<8>(ln, b * NQ + wave, M, d, lane, h == 0, a_rows[wave]);
+  __syncthreads();
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  const half_t* ar = &a_rows[min(fr, NQ - 1)][fk];
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u)
+    if (u < per_wave) {
+      const half8_t af = *reinterpret_cast<const half8_t*>(ar + (kw + 4 * u) * 16);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[u], af, acc, 0, 0, 0);
+    }
+  block_request_out_fragments<NQ>(bf, Wo, wave, lane, nb, h, ksteps);   // travel while the wavefronts attend
+#pragma unroll
+  for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
+  __syncthreads();
+  {
+    const int vg = kw, m = lane & 31;
+    if (m < NQ) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int rr = vg * 4 + e, n = cb * 32 + vg * 8 + (lane >> 5) * 4 + e;
+        float x = (red[cb * 4 + 0][rr][lane] + red[cb * 4 + 1][rr][lane]) + (red[cb * 4 + 2][rr][lane] + red[cb * 4 + 3][rr][lane]);
+        x += (float)bq[h * DH + n];
+        q_s[m][n] = (float)(half_t)x;
+      }
+    }
+  }
+  __syncthreads();
+  float qv[NQ][8];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qv[n][i] = q_s[n][c * 8 + i];
+  float mx_[NQ], l_[NQ], acc_[NQ][8];
+  keys.run(qv, scale * 1.44269504088896340736f, jfirst, 4 * G * KPW, mx_, l_, acc_);
+  if (wave < 4) cross_deposit<DH, NQ>(part, wave, lane, mx_, l_, acc_);
+  __syncthreads();
+  cross_finish<half_t, DH, NQ>(part, wave, lane, &ctx_s[0][0], DH + 8);
+  __syncthreads();
+  block_out_projection<NQ>(bf, ctx_s, wave, lane, nb, h, b * NQ, M, d, P_out);
+}
+
+constexpr int kBlockRows = 64;
+
+bool attention_blocks_supported(int dtype, int rows, int beam, int H, int d) {
+  return dtype == DT_F16 && rows >= 1 && rows <= kBlockRows && beam >= 1 && beam <= 4 && rows % beam == 0 && H >= 1 &&
+         d == H * 64 && d % 256 == 0 && d <= 1024;
+}
+
+hipError_t launch_self_block(const LnInput& ln, const void* Wqkv_packed, const void* bqkv, const void* Wo_packed,
+                             void* Kc, void* Vc, const int32_t* anc, const int32_t* tp, int nkeys_base, float* P_out,
+                             int batch, int beam, int H, int d, int T, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  if (!attention_blocks_supported(DT_F16, batch * beam, beam, H, d) || !Wqkv_packed || !bqkv || !Wo_packed || !Kc || !Vc ||
+      !P_out || ln.splits < 0 || ln.splits > 4 || !ln.x_old || (ln.splits > 0 && (ln.x_old == ln.x_new || !ln.x_new)) ||
+      (long)beam * T * d * 2 > 0x7fffffffL)
+    return hipErrorInvalidValue;
+  dim3 g(batch * H), b(512);
+  const int M = batch * beam;
+#define LSQ_SELF_BLOCK(NQ_)                                                                                          \
+  do {                                                                                                               \
+    if (anc)                                                                                                         \
+      self_block_kernel<NQ_, true><<<g, b, 0, s>>>((const half_t*)Wqkv_packed, (const half_t*)Wo_packed, anc, tp,    \
+                                                   nkeys_base, H, d, T, M, (half_t*)Kc, (half_t*)Vc,                \
+                                                   (const half_t*)bqkv, ln, P_out);                                  \
+    else                                                                                                             \
+      self_block_kernel<NQ_, false><<<g, b, 0, s>>>((const half_t*)Wqkv_packed, (const half_t*)Wo_packed, anc, tp,   \
+                                                    nkeys_base, H, d, T, M, (half_t*)Kc, (half_t*)Vc,               \
+                                                    (const half_t*)bqkv, ln, P_out);                                 \
+  } while (0)
+  switch (beam) {
+    case 1: LSQ_SELF_BLOCK(1); break;
+    case 2: LSQ_SELF_BLOCK(2); break;
+    case 3: LSQ_SELF_BLOCK(3); break;
+    default: LSQ_SELF_BLOCK(4); break;
+  }
+#undef LSQ_SELF_BLOCK
+  return hipGetLastError();
+}
+
+hipError_t launch_cross_block(const LnInput& ln, const void* Wq_packed, const void* bq, const void* Wo_packed,
+                              const void* kv, const int32_t* off, const int32_t* len, float* P_out, int batch, int beam,
+                              int H, int d, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  if (!attention_blocks_supported(DT_F16, batch * beam, beam, H, d) || !Wq_packed || !bq || !Wo_packed || !P_out ||
+      ln.splits < 1 || ln.splits > 16 || !ln.x_old || !ln.x_new || ln.x_old == ln.x_new)
+    return hipErrorInvalidValue;
+  dim3 g(batch * H), b(512);
+  const int M = batch * beam;
+#define LSQ_CROSS_BLOCK(NQ_)                                                                                       \
+  cross_block_kernel<NQ_><<<g, b, 0, s>>>((const half_t*)Wq_packed, (const half_t*)Wo_packed, (const half_t*)kv, off, len, \
+                                          H, d, M, ln, (const half_t*)bq, P_out)
+  switch (beam) {
+    case 1: LSQ_CROSS_BLOCK(1); break;
+    case 2: LSQ_CROSS_BLOCK(2); break;
+    case 3: LSQ_CROSS_BLOCK(3); break;
+    default: LSQ_CROSS_BLOCK(4); break;
+  }
+#undef LSQ_CROSS_BLOCK
+  return hipGetLastError();
+}
+
 // Encoder self-attention over packed sentences: qkv rows are [Q | K | V]; row i belongs to
 // sentence row_sent[i] whose rows start at off[.] and number len[.].
 template <typename T, int DH>

@@ -179,7 +179,7 @@ template <typename T>
 static hipError_t add_layernorm_partials_t(T* x, T* y, const float* P, int splits, const T* bias, const T* g,
                                            const T* b, int rows, int d, float eps, hipStream_t s) {
   const bool pre = y != nullptr;
-  if ((d & 7) != 0 || d > 4096 || (splits != 0 && splits != 1 && splits != 2 && splits != 4 && splits != 8) ||
+  if ((d & 7) != 0 || d > 4096 || (splits != 0 && splits != 1 && splits != 2 && splits != 4 && splits != 8 && !(splits == 16 && y == nullptr)) ||
       (splits == 0 && !pre)) {
     if (pre) return hipErrorInvalidValue;   // pre-LN models need d % 8 == 0, d <= 4096, 0/1/2/4/8 slabs
     dim3 grid((rows + 3) / 4), blk(256);
@@ -199,6 +199,7 @@ static hipError_t add_layernorm_partials_t(T* x, T* y, const float* P, int split
     case 1: return add_layernorm_partials_s<T, 1, false>(x, y, P, bias, g, b, rows, d, eps, s);
     case 2: return add_layernorm_partials_s<T, 2, false>(x, y, P, bias, g, b, rows, d, eps, s);
     case 4: return add_layernorm_partials_s<T, 4, false>(x, y, P, bias, g, b, rows, d, eps, s);
+    case 16: return add_layernorm_partials_s<T, 16, false>(x, y, P, bias, g, b, rows, d, eps, s);   // one slab per head
     default: return add_layernorm_partials_s<T, 8, false>(x, y, P, bias, g, b, rows, d, eps, s);
   }
 }

@@ -108,6 +108,16 @@ hipError_t launch_cross_attention(int dtype, const void* q, const void* kv, cons
 // + bq for the head it serves, from the fragment-ordered copy of Wq (gemm_packed_weights), instead
 // of a product kernel of 32 workgroups followed by an attention kernel.  The workgroups of head 0
 // write the normalised rows to ln.x_new.
+// Attention sublayers in one launch each, for at most 64 rows (kernels_attn.hip): self_block = [LayerNorm] + QKV slice +
+// cache append + self-attention + the head's share of the output projection; cross_block = LayerNorm + query slice +
+// cross-attention + the head's share of the output projection.  P_out: [H][batch*beam][d] float partial sums.
+bool attention_blocks_supported(int dtype, int rows, int beam, int H, int d);
+hipError_t launch_self_block(const LnInput& ln, const void* Wqkv_packed, const void* bqkv, const void* Wo_packed,
+                             void* Kc, void* Vc, const int32_t* anc, const int32_t* tp, int nkeys_base, float* P_out,
+                             int batch, int beam, int H, int d, int T, hipStream_t s);
+hipError_t launch_cross_block(const LnInput& ln, const void* Wq_packed, const void* bq, const void* Wo_packed,
+                              const void* kv, const int32_t* off, const int32_t* len, float* P_out, int batch, int beam,
+                              int H, int d, hipStream_t s);
 bool cross_attention_ln_supported(int dtype, int rows, int beam, int H, int d);
 hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, const void* bq, const void* kv,
                                      const int32_t* off, const int32_t* len, void* out, int batch, int beam,

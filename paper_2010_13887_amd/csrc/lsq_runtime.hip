@@ -40,11 +40,12 @@ int fail(int code, const char* fmt, ...) {
 // per kernel class.  Events come from a host-side pool that only grows.
 enum ProfClass {
   PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
-  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_COUNT
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_SELF_BLOCK, PC_CROSS_BLOCK, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
                                           "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
-                                          "beam_refine", "cache_reorder", "gemm_out", "attn_cross_q"};
+                                          "beam_refine", "cache_reorder", "gemm_out", "attn_cross_q", "self_block",
+                                          "cross_block"};
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
@@ -83,6 +84,7 @@ hipError_t prof_mark(hipStream_t s, int c, bool start) {
 constexpr size_t kAlign = 256;
 constexpr size_t kMaxSplits = 8;        // fp32 partial-sum slabs a split-K product may leave
 constexpr int kMaxSplitsFusedLn = 4;    // ... when the consuming product adds them itself
+constexpr size_t kBlockRowsMax = 64;    // most rows the attention blocks (attention_blocks_supported) take
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct HParams {
@@ -184,7 +186,7 @@ struct Plan {
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
-  size_t d_x, d_q, d_ctx, d_tmp, d_ffn, d_logits, d_y, e_y, d_x2;
+  size_t d_x, d_q, d_ctx, d_tmp, d_tmp2, d_ffn, d_logits, d_y, e_y, d_x2;
 };
 
 size_t packed_weight_bytes(const HParams& hp);
@@ -243,7 +245,11 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
     return o;
   };
   p.d_x = dtake(M * d * esz); p.d_q = dtake(M * d * esz); p.d_ctx = dtake(M * d * esz);
-  p.d_tmp = dtake(kMaxSplits * M * d * 4);   // fp32 partial-sum slabs of the split-K GEMMs
+  // fp32 partial-sum slabs: of the split-K GEMMs, or one per head from the attention blocks (few rows), which
+  // read one set while they write the other
+  const size_t head_slabs = (size_t)hp.H * std::min<size_t>(M, kBlockRowsMax) * d * 4;
+  p.d_tmp = dtake(std::max(kMaxSplits * M * d * 4, head_slabs));
+  p.d_tmp2 = dtake(std::max<size_t>(std::min<size_t>(M, kBlockRowsMax) * kMaxSplits * d * 4, head_slabs));
   p.d_y = dtake(M * d * esz);
   p.d_x2 = dtake(M * d * esz);   // second hidden-state buffer for products that normalise their own input
   p.d_ffn = q;
@@ -301,6 +307,7 @@ struct Ctx {
   int refresh_mode = 1;   // how the next lsq_encode keeps the cache in step with the beams: 0 move rows, 1 slab table
   bool anc_on = false;    // this translation uses the slab table
   bool fuse_ln = true;    // few rows alive: LayerNorm inside the product that consumes it
+  int block_rows = 64;    // ... and whole attention sublayers in one launch up to this many rows
   int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
@@ -388,12 +395,22 @@ int launch_step(int B) {
   // the other.  `pending` carries what that product needs.
   const bool fuse = g.fuse_ln && gemm_ln_supported(dt, M, d);
   char* x_alt = g.ws + p.d_x2;
+  // Few rows alive: each attention sublayer is one launch up to its output projection, which it leaves as one
+  // slab of partial sums per head (kernels_attn.hip).  The blocks read their LayerNorm's slabs from one set and
+  // write theirs to the other.
+  // Measured on whole translations: ahead for d = 512 at every row count up to 64 (Transformer-base, 32 rows:
+  // 27.07 -> 25.70 ms under beam search, 27.88 -> 24.97 ms sampled), behind for d = 1024, where a workgroup has
+  // to stream 512 KB of weight slices through one CU (batch 32 of the big model: 49.3 -> 49.7..50.4 ms whatever
+  // the row limit).
+  const bool blocks = g.fuse_ln && d <= 512 && attention_blocks_supported(dt, M, k, H, d) && M <= g.block_rows;
+  float* slabs = (float*)tmp;
+  float* slabs_alt = (float*)(g.ws + p.d_tmp2);
   struct { bool on; int S; const void* bias; const void* gain; const void* shift; } pending = {false, 0, nullptr, nullptr, nullptr};
   auto close_sublayer = [&](int cls, const void* in, const void* W, const void* bias, const void* gain, const void* shift,
                             int K, bool defer) -> int {
-    if (!defer) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, (float*)tmp, M, d, K, kMaxSplits, s);
+    if (!defer) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, slabs, M, d, K, kMaxSplits, s);
     const int S = std::min(gemm_partial_splits(dt, M, d, K), kMaxSplitsFusedLn);
-    TIMED(cls, launch_gemm_partials(dt, in, W, (float*)tmp, M, d, K, S, s));
+    TIMED(cls, launch_gemm_partials(dt, in, W, slabs, M, d, K, S, s));
     pending = {true, S, bias, gain, shift};
     return LSQ_OK;
   };
@@ -402,7 +419,7 @@ int launch_step(int B) {
       TIMED(cls, launch_gemm(dt, x, W, bias, o, M, N, d, act, s));
       return LSQ_OK;
     }
-    LnInput ln = {(const float*)tmp, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
+    LnInput ln = {slabs, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
                   (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
     TIMED(cls, launch_gemm_ln(ln, W, bias, o, M, N, d, act, s));
     std::swap(x, x_alt);
@@ -413,6 +430,27 @@ int launch_step(int B) {
     const DecLayer& L = g.dec[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
     char* Vc = Kc + slab;
+    if (blocks) {
+      const void *wqkv_p = gemm_packed_weights(L.Wqkv, 3 * d, d), *wo_p = gemm_packed_weights(L.Wo, d, d);
+      const void *wq_p = gemm_packed_weights(L.Wq, d, d), *woc_p = gemm_packed_weights(L.Woc, d, d);
+      if (!wqkv_p || !wo_p || !wq_p || !woc_p) return fail(LSQ_E_STATE, "fragment-ordered weights missing");
+      LnInput ln = {slabs, pending.on ? pending.S : 0, (const half_t*)pending.bias, (const half_t*)pending.gain,
+                    (const half_t*)pending.shift, (const half_t*)x, pending.on ? (half_t*)x_alt : nullptr, hp.eps};
+      TIMED(PC_SELF_BLOCK, launch_self_block(ln, wqkv_p, L.bqkv, wo_p, Kc, Vc, anc, step, 0, slabs_alt, B, k, H, d, T, s));
+      if (pending.on) std::swap(x, x_alt);
+      pending.on = false;
+      std::swap(slabs, slabs_alt);
+      LnInput ln1 = {slabs, H, (const half_t*)L.bo, (const half_t*)L.ln1g, (const half_t*)L.ln1b, (const half_t*)x,
+                     (half_t*)x_alt, hp.eps};
+      TIMED(PC_CROSS_BLOCK, launch_cross_block(ln1, wq_p, L.bq, woc_p, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
+                                               at<int32_t>(p.src_len), slabs_alt, B, k, H, d, s));
+      std::swap(x, x_alt);
+      std::swap(slabs, slabs_alt);
+      TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, nullptr, slabs, H, L.boc, L.ln2g, L.ln2b, M, d, hp.eps, s));
+      if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
+      if (int rc = close_sublayer(PC_GEMM_FFN2, ffn, L.W2, L.b2, L.ln3g, L.ln3b, F, true)) return rc;
+      continue;
+    }
     GemmOut o = plain_out(q, d);        // Q | K | V: Q to the activation buffer, K and V to cache position t
     o.ptr[1] = Kc; o.ptr[2] = Vc;
     o.ld[1] = (long)T * d; o.ld[2] = (long)T * d;
@@ -426,7 +464,7 @@ int launch_step(int B) {
     const void* wq_packed = pending.on ? wq_for_ln : nullptr;
     if (wq_packed) {
       // few rows: the attention kernel normalises its rows and makes its queries itself
-      LnInput ln = {(const float*)tmp, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
+      LnInput ln = {slabs, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
                     (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
       TIMED(PC_ATTN_CROSS, launch_cross_attention_ln(ln, wq_packed, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                      at<int32_t>(p.src_len), ctx, B, k, H, d, s));
@@ -452,7 +490,7 @@ int launch_step(int B) {
     // The vocabulary product does not take the last LayerNorm along: with it the kernel needs 240
     // registers, half of its 1000 workgroups wait for the other half, and the 64 MB of the
     // embedding stream in two rounds (19.4 us against 3 + 13.5 for the two kernels; same bits)
-    TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, nullptr, (float*)tmp, pending.S, pending.bias, pending.gain,
+    TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, nullptr, slabs, pending.S, pending.bias, pending.gain,
                                                       pending.shift, M, d, hp.eps, s));
     pending.on = false;
   }
@@ -992,6 +1030,18 @@ int lsq_set_layernorm_fusion(int on) {
   return LSQ_OK;
 }
 
+int lsq_set_attention_blocks(int max_rows) {
+  if (max_rows < 0 || max_rows > (int)kBlockRowsMax) return fail(LSQ_E_ARG, "max_rows %d outside [0, %d]", max_rows, (int)kBlockRowsMax);
+  if (max_rows != g.block_rows) {   // captured steps hold the other variant's launches
+    if (g.stream) (void)hipStreamSynchronize(g.stream);
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
+  }
+  g.block_rows = max_rows;
+  return LSQ_OK;
+}
+
 int lsq_set_diversity(int groups, float strength) {
   if (groups < 1 || groups > LSQ_MAX_BEAM) return fail(LSQ_E_ARG, "groups %d outside [1, %d]", groups, LSQ_MAX_BEAM);
   if (!(strength >= 0.f)) return fail(LSQ_E_ARG, "diversity strength must be >= 0");
@@ -1258,6 +1308,38 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
   LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
                 (half_t*)x_new, eps};
   KRUN(launch_cross_attention_ln(ln, Wq_packed, bq, kv, src_off, src_len, out, batch, beam, heads, d, (hipStream_t)stream));
+}
+
+int lsq_k_self_attention_block(const float* P, int splits, const void* ln_bias, const void* gamma, const void* beta,
+                               const void* x_old, void* x_new, float eps, const void* Wqkv_packed, const void* bqkv,
+                               const void* Wo_packed, void* Kc, void* Vc, const int32_t* slab_table, int nkeys,
+                               float* P_out, int batch, int beam, int heads, int d, int T, void* stream) {
+  KCHK(x_old && Wqkv_packed && bqkv && Wo_packed && Kc && Vc && P_out, "null pointer");
+  KCHK(splits >= 0 && splits <= 4, "0..4 slabs");
+  KCHK(splits == 0 || (P && ln_bias && gamma && beta && x_new && x_new != x_old), "LayerNorm inputs; x_new must not be x_old");
+  KCHK(batch >= 0 && T >= 1 && nkeys >= 0 && nkeys < T, "nkeys outside [0, T)");
+  KCHK(batch == 0 || attention_blocks_supported(DT_F16, batch * beam, beam, heads, d),
+       "float16, at most 64 rows, beam 1..4, heads of 64, d = 64 * heads a multiple of 256 up to 1024");
+  LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
+                (half_t*)x_new, eps};
+  KRUN(launch_self_block(ln, Wqkv_packed, bqkv, Wo_packed, Kc, Vc, slab_table, nullptr, nkeys, P_out, batch, beam, heads, d,
+                         T, (hipStream_t)stream));
+}
+
+int lsq_k_cross_attention_block(const float* P, int splits, const void* ln_bias, const void* gamma, const void* beta,
+                                const void* x_old, void* x_new, float eps, const void* Wq_packed, const void* bq,
+                                const void* Wo_packed, const void* kv, const int32_t* src_off, const int32_t* src_len,
+                                float* P_out, int batch, int beam, int heads, int d, void* stream) {
+  KCHK(P && ln_bias && gamma && beta && x_old && x_new && Wq_packed && bq && Wo_packed && kv && src_off && src_len && P_out,
+       "null pointer");
+  KCHK(x_old != x_new, "x_new must not be x_old");
+  KCHK(batch >= 0 && splits >= 1 && splits <= 16, "1..16 slabs");
+  KCHK(batch == 0 || attention_blocks_supported(DT_F16, batch * beam, beam, heads, d),
+       "float16, at most 64 rows, beam 1..4, heads of 64, d = 64 * heads a multiple of 256 up to 1024");
+  LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
+                (half_t*)x_new, eps};
+  KRUN(launch_cross_block(ln, Wq_packed, bq, Wo_packed, kv, src_off, src_len, P_out, batch, beam, heads, d,
+                          (hipStream_t)stream));
 }
 
 int lsq_k_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,

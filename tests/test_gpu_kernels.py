@@ -330,6 +330,115 @@ def test_cross_attention_that_makes_its_queries(env, lens, beam, H, splits):
     np.testing.assert_allclose(qf, _h(rows_ref) @ Wq.astype(np.float64).T + bq, rtol=4e-3, atol=4e-3 * (1 + np.abs(qf).max()))
 
 
+def _ln_rows(x, P, lb, g, b):
+    """The oracle's LayerNorm of x + (slabs + bias), float64."""
+    return O.layer_norm(x.astype(np.float64) + (P.astype(np.float64).sum(0) + lb), g.astype(np.float64), b.astype(np.float64), 1e-5)
+
+
+@pytest.mark.parametrize("B,beam,H,T,nkeys,splits,table", [
+    (1, 4, 16, 60, 0, 0, True),       # first step: no history, rows taken as they are
+    (1, 4, 16, 180, 171, 4, True),    # one sentence of the big model deep into a translation
+    (3, 4, 8, 70, 33, 2, True),       # base model shape
+    (16, 4, 16, 50, 17, 1, True),     # the most rows the kernel takes
+    (5, 3, 4, 40, 39, 3, False),      # the cache's last position, rows that keep their own slab, beam 3
+    (7, 2, 12, 90, 64, 4, True),      # four wavefronts per row
+    (9, 1, 8, 130, 129, 2, False),    # beam 1
+])
+def test_self_attention_block(env, B, beam, H, T, nkeys, splits, table):
+    """[LayerNorm +] QKV slice + cache append + self-attention + per-head output projection in one launch: every
+    stage against the oracle, stage by stage from the values the kernel itself stored before it."""
+    lsq, torch = env
+    rng = np.random.default_rng(B * 131 + beam * 17 + H + nkeys)
+    d, rows = H * 64, B * beam
+    h = torch.float16
+    x = _h(rng.standard_normal((rows, d)) * (2 if splits else 1))
+    lb, g, b = _h(rng.standard_normal(d) * 0.3), _h(1 + 0.3 * rng.standard_normal(d)), _h(0.3 * rng.standard_normal(d))
+    P = (rng.standard_normal((max(splits, 1), rows, d)) * 0.5).astype(np.float32)
+    Wqkv, bqkv = _h(rng.standard_normal((3 * d, d)) * 0.05), _h(rng.standard_normal(3 * d) * 0.5)
+    Wo = _h(rng.standard_normal((d, d)) * 0.05)
+    Kc, Vc = _h(rng.standard_normal((rows, T, d))), _h(rng.standard_normal((rows, T, d)))
+    Kc[:, nkeys:], Vc[:, nkeys:] = np.nan, np.nan           # what lies beyond the history may be read, and must not matter
+    slab = rng.integers(0, beam, size=(rows, T + 1)).astype(np.int32)
+    slab[:, nkeys:] = rng.choice([1 << 20, -5, beam, -(1 << 30)], size=(rows, T + 1 - nkeys))
+    dK, dV = _dev(torch, Kc, h), _dev(torch, Vc, h)
+    dx, dP = _dev(torch, x, h), _dev(torch, P)
+    x_new = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    P_out = torch.full((H, rows, d), 7.0, dtype=torch.float32, device="cuda")
+    dWqkv, dWo = _dev(torch, Wqkv, h), _dev(torch, Wo, h)
+    lsq.k_self_attention_block(dP if splits else None, _dev(torch, lb, h), _dev(torch, g, h), _dev(torch, b, h), dx,
+                               x_new if splits else None, 1e-5, lsq.k_pack_weights(dWqkv), _dev(torch, bqkv, h),
+                               lsq.k_pack_weights(dWo), dK, dV, _dev(torch, slab) if table else None, nkeys, P_out, B, beam, H)
+    assert torch.equal(dx, _dev(torch, x, h))
+    # 1. the normalised rows
+    if splits:
+        got_rows = x_new.float().cpu().numpy()
+        np.testing.assert_allclose(got_rows, _ln_rows(x, P[:splits], lb, g, b), rtol=2e-3, atol=2e-3)
+    else:
+        got_rows = x
+    # 2. k and v of the new position, written to the cache at index nkeys and nowhere else
+    qkv = got_rows.astype(np.float64) @ Wqkv.astype(np.float64).T + bqkv
+    gK, gV = dK.float().cpu().numpy(), dV.float().cpu().numpy()
+    tol = 4e-3 * (1 + np.abs(qkv).max())
+    np.testing.assert_allclose(gK[:, nkeys], qkv[:, d:2 * d], rtol=4e-3, atol=tol)
+    np.testing.assert_allclose(gV[:, nkeys], qkv[:, 2 * d:], rtol=4e-3, atol=tol)
+    keep = np.ones(T, bool)
+    keep[nkeys] = False
+    assert np.array_equal(gK[:, keep], Kc[:, keep], equal_nan=True) and np.array_equal(gV[:, keep], Vc[:, keep], equal_nan=True)
+    # 3. attention over the history (through the table) plus the new position, with the kernel's own k and v there
+    q = _h(qkv[:, :d])
+    j = np.arange(nkeys)
+    ctx = np.empty((rows, d))
+    for r in range(rows):
+        src = (r - r % beam + slab[r, :nkeys]) if table else np.full(nkeys, r)
+        Kr = np.concatenate([Kc[src, j], gK[r:r + 1, nkeys]]).astype(np.float64)
+        Vr = np.concatenate([Vc[src, j], gV[r:r + 1, nkeys]]).astype(np.float64)
+        ctx[r] = O.attention(q[r:r + 1].astype(np.float64), Kr, Vr, H)[0]
+    # 4. the heads' shares of the output projection: each slab and their sum
+    got = P_out.cpu().numpy().astype(np.float64)
+    ref = np.stack([ctx[:, hh * 64:(hh + 1) * 64] @ Wo[:, hh * 64:(hh + 1) * 64].astype(np.float64).T for hh in range(H)])
+    scale = np.abs(ref).max()
+    # (a query that rounds to the neighbouring float16 value moves a score by up to 1e-3 * |k|)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=6e-3 * scale)
+    np.testing.assert_allclose(got.sum(0), ctx @ Wo.astype(np.float64).T, rtol=0, atol=6e-3 * np.abs(ref.sum(0)).max())
+
+
+@pytest.mark.parametrize("lens,beam,H,splits", [([5], 4, 16, 16), ([130, 7], 4, 16, 16), ([33, 60, 2], 3, 8, 8), ([1, 2, 90, 49], 2, 4, 4),
+                                               ([257], 1, 12, 12), ([40, 40, 41, 200, 9, 64, 64, 3], 1, 16, 1),
+                                               ([7, 50, 33, 3, 90, 12, 28, 28, 61, 5, 17, 44, 2, 130, 29, 30], 4, 16, 16)])
+def test_cross_attention_block(env, lens, beam, H, splits):
+    """LayerNorm over per-head slabs + query slice + cross-attention + per-head output projection in one launch."""
+    lsq, torch = env
+    rng = np.random.default_rng(sum(lens) * 5 + beam + H)
+    d, B = H * 64, len(lens)
+    rows = B * beam
+    h = torch.float16
+    x = _h(rng.standard_normal((rows, d)) * 2)
+    P = (rng.standard_normal((splits, rows, d)) * 0.3).astype(np.float32)
+    lb, g, b = _h(rng.standard_normal(d) * 0.3), _h(1 + 0.3 * rng.standard_normal(d)), _h(0.3 * rng.standard_normal(d))
+    Wq, bq = _h(rng.standard_normal((d, d)) * 0.05), _h(rng.standard_normal(d) * 0.5)
+    Wo = _h(rng.standard_normal((d, d)) * 0.05)
+    kv = _h(rng.standard_normal((sum(lens), 2 * d)))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    dx = _dev(torch, x, h)
+    x_new = torch.full((rows, d), 7.0, dtype=h, device="cuda")
+    P_out = torch.full((H, rows, d), 7.0, dtype=torch.float32, device="cuda")
+    lsq.k_cross_attention_block(_dev(torch, P), _dev(torch, lb, h), _dev(torch, g, h), _dev(torch, b, h), dx, x_new, 1e-5,
+                                lsq.k_pack_weights(_dev(torch, Wq, h)), _dev(torch, bq, h),
+                                lsq.k_pack_weights(_dev(torch, Wo, h)), _dev(torch, kv, h), _dev(torch, off),
+                                _dev(torch, np.array(lens, np.int32)), P_out, B, beam, H)
+    assert torch.equal(dx, _dev(torch, x, h))
+    got_rows = x_new.float().cpu().numpy()
+    np.testing.assert_allclose(got_rows, _ln_rows(x, P, lb, g, b), rtol=2e-3, atol=2e-3)
+    q = _h(got_rows.astype(np.float64) @ Wq.astype(np.float64).T + bq)
+    ctx = np.concatenate([O.attention(q[i * beam:(i + 1) * beam].astype(np.float64),
+                                      kv[off[i]:off[i + 1], :d].astype(np.float64),
+                                      kv[off[i]:off[i + 1], d:].astype(np.float64), H) for i in range(B)])
+    got = P_out.cpu().numpy().astype(np.float64)
+    ref = np.stack([ctx[:, hh * 64:(hh + 1) * 64] @ Wo[:, hh * 64:(hh + 1) * 64].astype(np.float64).T for hh in range(H)])
+    np.testing.assert_allclose(got, ref, rtol=0, atol=6e-3 * np.abs(ref).max())
+    np.testing.assert_allclose(got.sum(0), ctx @ Wo.astype(np.float64).T, rtol=0, atol=6e-3 * np.abs(ref.sum(0)).max())
+
+
 def _oracle_row_topk(logits, score, finished, k, eos):
     """Per row: the oracle's candidate scores and a full sort."""
     M, V = logits.shape
