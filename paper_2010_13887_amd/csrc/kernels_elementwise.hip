@@ -5,24 +5,7 @@
 namespace lsq {
 
 // ---------------------------------------------------------------------------------------------
-// x[r,:] = store(E[id_r,:] * sqrt(d) + PE[pos_r,:]).  Product and sum are rounded separately
-// (no fused multiply-add) so the fp32 value before storage is the textbook one.
-template <typename T>
-__device__ __forceinline__ void embed_row(const T* __restrict__ e, const float* __restrict__ pe,
-                                          T* __restrict__ x, int d, float scale, int lane, int nl) {
-  if ((d & 7) == 0) {
-    for (int c = lane * 8; c < d; c += nl * 8) {
-      float v[8];
-      Vec8<T>::load(e + c, v);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = __fadd_rn(__fmul_rn(v[i], scale), pe[c + i]);
-      Vec8<T>::store(x + c, v);
-    }
-  } else {
-    for (int c = lane; c < d; c += nl) x[c] = (T)__fadd_rn(__fmul_rn((float)e[c], scale), pe[c]);
-  }
-}
-
+// Token embedding + position: embed_row (lsq_internal.h) over the rows of a launch.
 template <typename T>
 __global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ E, const float* __restrict__ pe,
                                                          const int32_t* __restrict__ ids,
@@ -86,11 +69,13 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
                                                                      const float* __restrict__ P,
                                                                      const T* __restrict__ bias,
                                                                      const T* __restrict__ g, const T* __restrict__ b,
-                                                                     int rows, int d, float eps) {
+                                                                     int rows, int d, float eps,
+                                                                     const T* __restrict__ x_in) {
   int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);   // one wavefront per row, 1..4 rows per workgroup
   if (r >= rows) return;
   int lane = threadIdx.x & 63;
   T* xr = x + (size_t)r * d;
+  const T* xi = x_in ? x_in + (size_t)r * d : xr;   // the residual may come from another buffer (x is then only written)
   const size_t slab = (size_t)rows * d;
   float v[NV][8], gv[NV][8], bv[NV][8];
 #pragma unroll
@@ -101,7 +86,7 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_kernel(T* __restri
 #pragma unroll
       for (int s = 0; s < S; ++s) Vec8<float>::load(P + s * slab + (size_t)r * d + c, part[s]);   // all in flight
       if (S > 0) Vec8<T>::load(bias + c, t);
-      Vec8<T>::load(xr + c, v[j]);
+      Vec8<T>::load(xi + c, v[j]);
       Vec8<T>::load(g + c, gv[j]);      // gain and shift too: one round trip to memory in all
       Vec8<T>::load(b + c, bv[j]);
       if (S > 0) {
@@ -132,16 +117,17 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_generic_kernel(T* 
                                                                              const T* __restrict__ bias,
                                                                              const T* __restrict__ g,
                                                                              const T* __restrict__ b, int rows, int d,
-                                                                             float eps) {
+                                                                             float eps, const T* __restrict__ x_in) {
   int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
   int lane = threadIdx.x & 63;
   T* xr = x + (size_t)r * d;
+  const T* xi = x_in ? x_in + (size_t)r * d : xr;
   const size_t slab = (size_t)rows * d;
   auto val = [&](int c) {
     float a = P[(size_t)r * d + c];
     for (int s = 1; s < splits; ++s) a += P[s * slab + (size_t)r * d + c];
-    return (float)xr[c] + (a + (float)bias[c]);
+    return (float)xi[c] + (a + (float)bias[c]);
   };
   float sum = 0.f;
   for (int c = lane; c < d; c += 64) sum += val(c);
@@ -157,7 +143,7 @@ __global__ void __launch_bounds__(256) add_layernorm_partials_generic_kernel(T* 
 
 template <typename T, int S, bool PRE>
 static hipError_t add_layernorm_partials_s(T* x, T* y, const float* P, const T* bias, const T* g, const T* b,
-                                           int rows, int d, float eps, hipStream_t s) {
+                                           int rows, int d, float eps, hipStream_t s, const T* x_in) {
   // Decoding sizes: a workgroup per row, so that the rows spread over as many CUs as there are rows
   // (a CU takes in its rows' slabs at a fixed rate; measured on whole steps against four rows per
   // workgroup: 0.461 -> 0.449 ms with 8 slabs of 32 rows, 0.492 -> 0.490 with 2 slabs of 512 rows).
@@ -165,55 +151,56 @@ static hipError_t add_layernorm_partials_s(T* x, T* y, const float* P, const T* 
   const int rpw = rows <= 2048 ? 1 : 4;
   dim3 grid((rows + rpw - 1) / rpw), blk(64 * rpw);
   if (d <= 512)
-    add_layernorm_partials_kernel<T, 1, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 1, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps, x_in);
   else if (d <= 1024)
-    add_layernorm_partials_kernel<T, 2, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 2, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps, x_in);
   else if (d <= 2048)
-    add_layernorm_partials_kernel<T, 4, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 4, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps, x_in);
   else
-    add_layernorm_partials_kernel<T, 8, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps);
+    add_layernorm_partials_kernel<T, 8, S, PRE><<<grid, blk, 0, s>>>(x, y, P, bias, g, b, rows, d, eps, x_in);
   return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t add_layernorm_partials_t(T* x, T* y, const float* P, int splits, const T* bias, const T* g,
-                                           const T* b, int rows, int d, float eps, hipStream_t s) {
+                                           const T* b, int rows, int d, float eps, hipStream_t s, const T* x_in) {
   const bool pre = y != nullptr;
   if ((d & 7) != 0 || d > 4096 || (splits != 0 && splits != 1 && splits != 2 && splits != 4 && splits != 8 && !(splits == 16 && y == nullptr)) ||
       (splits == 0 && !pre)) {
     if (pre) return hipErrorInvalidValue;   // pre-LN models need d % 8 == 0, d <= 4096, 0/1/2/4/8 slabs
     dim3 grid((rows + 3) / 4), blk(256);
-    add_layernorm_partials_generic_kernel<T><<<grid, blk, 0, s>>>(x, P, splits, bias, g, b, rows, d, eps);
+    add_layernorm_partials_generic_kernel<T><<<grid, blk, 0, s>>>(x, P, splits, bias, g, b, rows, d, eps, x_in);
     return hipGetLastError();
   }
   if (pre) {
     switch (splits) {
-      case 0: return add_layernorm_partials_s<T, 0, true>(x, y, P, bias, g, b, rows, d, eps, s);
-      case 1: return add_layernorm_partials_s<T, 1, true>(x, y, P, bias, g, b, rows, d, eps, s);
-      case 2: return add_layernorm_partials_s<T, 2, true>(x, y, P, bias, g, b, rows, d, eps, s);
-      case 4: return add_layernorm_partials_s<T, 4, true>(x, y, P, bias, g, b, rows, d, eps, s);
-      default: return add_layernorm_partials_s<T, 8, true>(x, y, P, bias, g, b, rows, d, eps, s);
+      case 0: return add_layernorm_partials_s<T, 0, true>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+      case 1: return add_layernorm_partials_s<T, 1, true>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+      case 2: return add_layernorm_partials_s<T, 2, true>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+      case 4: return add_layernorm_partials_s<T, 4, true>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+      default: return add_layernorm_partials_s<T, 8, true>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
     }
   }
   switch (splits) {
-    case 1: return add_layernorm_partials_s<T, 1, false>(x, y, P, bias, g, b, rows, d, eps, s);
-    case 2: return add_layernorm_partials_s<T, 2, false>(x, y, P, bias, g, b, rows, d, eps, s);
-    case 4: return add_layernorm_partials_s<T, 4, false>(x, y, P, bias, g, b, rows, d, eps, s);
-    case 16: return add_layernorm_partials_s<T, 16, false>(x, y, P, bias, g, b, rows, d, eps, s);   // one slab per head
-    default: return add_layernorm_partials_s<T, 8, false>(x, y, P, bias, g, b, rows, d, eps, s);
+    case 1: return add_layernorm_partials_s<T, 1, false>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+    case 2: return add_layernorm_partials_s<T, 2, false>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+    case 4: return add_layernorm_partials_s<T, 4, false>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
+    case 16: return add_layernorm_partials_s<T, 16, false>(x, y, P, bias, g, b, rows, d, eps, s, x_in);   // one slab per head
+    default: return add_layernorm_partials_s<T, 8, false>(x, y, P, bias, g, b, rows, d, eps, s, x_in);
   }
 }
 
 // y == nullptr: post-LN (x <- LN(x + sublayer)); y != nullptr: pre-LN (x <- x + sublayer, y <- LN(x)).
 hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const float* P, int splits, const void* bias,
-                                         const void* g, const void* b, int rows, int d, float eps, hipStream_t s) {
+                                         const void* g, const void* b, int rows, int d, float eps, hipStream_t s,
+                                         const void* x_in) {
   if (rows <= 0) return hipSuccess;
-  if (splits < 0) return hipErrorInvalidValue;
+  if (splits < 0 || (x_in && (y || x_in == x))) return hipErrorInvalidValue;   // a separate residual input: post-LN only
   if (dtype == DT_F16)
     return add_layernorm_partials_t<half_t>((half_t*)x, (half_t*)y, P, splits, (const half_t*)bias,
-                                            (const half_t*)g, (const half_t*)b, rows, d, eps, s);
+                                            (const half_t*)g, (const half_t*)b, rows, d, eps, s, (const half_t*)x_in);
   return add_layernorm_partials_t<float>((float*)x, (float*)y, P, splits, (const float*)bias, (const float*)g,
-                                         (const float*)b, rows, d, eps, s);
+                                         (const float*)b, rows, d, eps, s, (const float*)x_in);
 }
 
 // Prefill of a decoder-only model: copies the K and V thirds of packed [rows, 3d] projections into

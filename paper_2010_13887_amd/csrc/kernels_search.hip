@@ -300,6 +300,51 @@ hipError_t launch_row_topk(int dtype, const void* logits, const float* score, co
   return row_topk_t<float>((const float*)logits, score, fin, M, V, k, eos, raw, out_score, out_idx, s, gr);
 }
 
+// x[base + i] = E[tok[i]] * scale + pe[pos] for the k rows of a sentence (tok[i] < 0: row left alone), by one
+// wavefront: the rows' 16-byte chunks are dealt out over the lanes and requested eight per lane at a time, so the
+// k gathers travel together instead of one row after the other.  The arithmetic is embed_row's.
+template <typename T>
+__device__ __forceinline__ void next_input_rows(const NextInput& nx, const int* tok, int base, int k, int pos, int lane) {
+  const int d = nx.d;
+  const T* E = (const T*)nx.E;
+  T* x = (T*)nx.x;
+  const float* pe = nx.pe + (size_t)pos * d;
+  if ((d & 7) != 0) {
+    for (int i = 0; i < k; ++i)
+      if (tok[i] >= 0) embed_row<T>(E + (size_t)tok[i] * d, pe, x + (size_t)(base + i) * d, d, nx.scale, lane, 64);
+    return;
+  }
+  using raw_t = typename Vec8<T>::raw_t;
+  constexpr int U = 8;
+  const int cpr = d >> 3, total = k * cpr;
+  for (int u0 = 0; u0 < total; u0 += 64 * U) {
+    raw_t e[U];
+    floatx4 pa[U], pb[U];
+    int row[U], col[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = u0 + u * 64 + lane;
+      const int i = min(idx, total - 1) / cpr;
+      col[u] = (min(idx, total - 1) - i * cpr) * 8;
+      row[u] = (idx < total && tok[i] >= 0) ? base + i : -1;
+      e[u] = Vec8<T>::load_raw(E + (size_t)max(tok[i], 0) * d + col[u]);
+      pa[u] = *reinterpret_cast<const floatx4*>(pe + col[u]);
+      pb[u] = *reinterpret_cast<const floatx4*>(pe + col[u] + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float v[8];
+      Vec8<T>::unpack(e[u], v);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        v[c] = __fadd_rn(__fmul_rn(v[c], nx.scale), pa[u][c]);
+        v[4 + c] = __fadd_rn(__fmul_rn(v[4 + c], nx.scale), pb[u][c]);
+      }
+      if (row[u] >= 0) Vec8<T>::store(x + (size_t)row[u] * d + col[u], v);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // One wavefront per sentence (per group of a sentence under diverse beam search: k is then the
 // group width, the group's rows start at beam slot goff of the sentence's k_all).  Lane c < k*k owns
@@ -312,8 +357,8 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
                                                          const int32_t* __restrict__ cap,
                                                          int32_t* __restrict__ active, int k, int V, int T1,
                                                          int t_base, int32_t* __restrict__ step_state, int eos,
-                                                         int32_t* __restrict__ anc, SearchGroups gr) {
-  __shared__ int sh_parent[LSQ_MAX_BEAM_];
+                                                         int32_t* __restrict__ anc, SearchGroups gr, NextInput nx) {
+  __shared__ int sh_parent[LSQ_MAX_BEAM_], sh_tok[LSQ_MAX_BEAM_];
   __shared__ int sh_unfinished, sh_taken;
   const int b = blockIdx.x, lane = threadIdx.x;
   const int t = t_base + (step_state ? step_state[0] : 0);
@@ -321,6 +366,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   const int k_all = gr.k_all > 1 ? gr.k_all : k;           // rows of a sentence (k_all == 1: no groups)
   const int base = b * k_all + gr.goff;                    // first row of this group
   if (lane == 0) { sh_unfinished = 0; sh_taken = 0; }
+  if (lane < LSQ_MAX_BEAM_) sh_tok[lane] = -1;
   // Everything the kernel reads is requested here, before any of it is used (one trip to memory
   // instead of one per phase): the candidates, the state of the beam a candidate continues (lane
   // c continues beam c / k whatever its rank turns out to be), the sentence's length cap and this
@@ -385,6 +431,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   if (win) {
     const int row = base + rank;
     int nlen = plen, nfin = pfin;
+    sh_tok[rank] = pfin ? eos : tok;   // what the row feeds the decoder next (a finished row: anything valid)
     if (!pfin) {
       nlen = plen + 1;
       tokens[(size_t)row * T1 + nlen] = tok;
@@ -402,6 +449,12 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     if (!nfin) sh_unfinished = 1;
   }
   __syncthreads();
+  // The next step's decoder input of these rows (one launch less per step).  A row that no candidate won
+  // (fewer live candidates than beams) embeds nothing: it is dead and stays so.
+  if (nx.E && t + 1 < T1 - 1) {
+    if (nx.dtype == DT_F16) next_input_rows<half_t>(nx, sh_tok, base, k, t + 1, lane);
+    else next_input_rows<float>(nx, sh_tok, base, k, t + 1, lane);
+  }
   if (gr.pen_n && lane == 0) gr.pen_n[b] = gr.last ? 0 : gr.pen_n[b] + sh_taken;
   if (!gr.last) return;
   // the sentence is still active if any hypothesis of any group is unfinished (the other groups'
@@ -425,13 +478,13 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
                               int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
                               int32_t* active, int batch, int k, int V, int T, int t_base, int32_t* step_state,
-                              int eos, int32_t* anc, hipStream_t s, const SearchGroups& gr) {
+                              int eos, int32_t* anc, hipStream_t s, const SearchGroups& gr, const NextInput& nx) {
   if (batch <= 0) return hipSuccess;
   if (k < 1 || k > LSQ_MAX_BEAM_) return hipErrorInvalidValue;
   if (gr.k_all > 1 && (gr.kg != k || gr.k_all % k != 0 || gr.k_all > LSQ_MAX_BEAM_ || gr.goff % k != 0 || gr.goff + k > gr.k_all))
     return hipErrorInvalidValue;
   beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
-                                          k, V, T + 1, t_base, step_state, eos, anc, gr);
+                                          k, V, T + 1, t_base, step_state, eos, anc, gr, nx);
   return hipGetLastError();
 }
 

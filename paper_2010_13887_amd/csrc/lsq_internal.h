@@ -88,9 +88,10 @@ hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const in
                              float scale, hipStream_t s);
 hipError_t launch_scatter_kv(int dtype, const void* qkv, const int32_t* sent, const int32_t* pos, void* Kc,
                              void* Vc, int rows, int d, int T, hipStream_t s);
+// x_in (post-LN only): the residual is read from there instead of x, which is then only written
 hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const float* P, int splits,
                                          const void* bias, const void* g, const void* b, int rows, int d,
-                                         float eps, hipStream_t s);
+                                         float eps, hipStream_t s, const void* x_in = nullptr);
 
 // nkeys = nkeys_base + (tp ? *tp : 0), with *tp read on the device.  anc != null: position j of row
 // r's history is in slab (r / beam) * beam + anc[r * anc_ld + j] instead of slab r.
@@ -169,11 +170,21 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
 // [batch*k, T+1] is gathered by parent like the token histories, and entry t+1 of every row is set
 // to the row's own beam index.
 // groups given (kg < k_all): k is the group width kg, candidates are [rows, kg]; see SearchGroups.
+// The next step's decoder input, left behind by the kernel that settles the step's tokens:
+// x[row] = E[last token of row] * scale + pe[t + 1] (E == nullptr: not asked for).
+struct NextInput {
+  const void* E;
+  const float* pe;
+  void* x;
+  int d, dtype;
+  float scale;
+};
+inline NextInput no_next_input() { return NextInput{nullptr, nullptr, nullptr, 0, 0, 0.f}; }
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score,
                               int32_t* tokens, int32_t* len, int32_t* fin, int32_t* parent,
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
                               int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
-                              const SearchGroups& groups = one_group());
+                              const SearchGroups& groups = one_group(), const NextInput& next = no_next_input());
 // npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
                                 int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,
@@ -333,6 +344,24 @@ template <> struct Vec8<float> {
     *reinterpret_cast<floatx4*>(p + 4) = b;
   }
 };
+
+// x[r,:] = store(E[id_r,:] * sqrt(d) + PE[pos_r,:]).  Product and sum are rounded separately
+// (no fused multiply-add) so the fp32 value before storage is the textbook one.
+template <typename T>
+__device__ __forceinline__ void embed_row(const T* __restrict__ e, const float* __restrict__ pe,
+                                          T* __restrict__ x, int d, float scale, int lane, int nl) {
+  if ((d & 7) == 0) {
+    for (int c = lane * 8; c < d; c += nl * 8) {
+      float v[8];
+      Vec8<T>::load(e + c, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = __fadd_rn(__fmul_rn(v[i], scale), pe[c + i]);
+      Vec8<T>::store(x + c, v);
+    }
+  } else {
+    for (int c = lane; c < d; c += nl) x[c] = (T)__fadd_rn(__fmul_rn((float)e[c], scale), pe[c]);
+  }
+}
 
 // LayerNorm of one row held by one wavefront: lane l owns elements (j*64 + l)*8 .. +7 of the row for
 // j < NV (those at or beyond d are absent).  v comes in as the row, leaves centred; o = g * (v * rstd) + b.

@@ -186,7 +186,7 @@ struct Plan {
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
-  size_t d_x, d_q, d_ctx, d_tmp, d_tmp2, d_ffn, d_logits, d_y, e_y, d_x2;
+  size_t d_x, d_q, d_ctx, d_tmp, d_tmp2, d_ffn, d_logits, d_y, e_y, d_x2, d_x0;
 };
 
 size_t packed_weight_bytes(const HParams& hp);
@@ -252,6 +252,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.d_tmp2 = dtake(std::max<size_t>(std::min<size_t>(M, kBlockRowsMax) * kMaxSplits * d * 4, head_slabs));
   p.d_y = dtake(M * d * esz);
   p.d_x2 = dtake(M * d * esz);   // second hidden-state buffer for products that normalise their own input
+  p.d_x0 = dtake(M * d * esz);   // decoder input of the next step, left by the kernel that settles this step's tokens
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
@@ -362,11 +363,11 @@ int check_limits(int max_batch, int beam, int max_len, const HParams& hp) {
 // Post-LN (y == nullptr): x <- LN(x + in.W^T + bias).  Pre-LN (y given): x <- x + in.W^T + bias and
 // y <- LN(x) with the NEXT sublayer's gain and shift.
 int sublayer(int cls, const void* in, const void* W, const void* bias, const void* g_, const void* b_, void* x,
-             void* y, float* partials, int M, int d, int K, int max_splits, hipStream_t s) {
+             void* y, float* partials, int M, int d, int K, int max_splits, hipStream_t s, const void* x_in = nullptr) {
   const HParams& hp = g.hp;
   int S = std::min(gemm_partial_splits(hp.dtype, M, d, K), max_splits);
   TIMED(cls, launch_gemm_partials(hp.dtype, in, W, partials, M, d, K, S, s));
-  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(hp.dtype, x, y, partials, S, bias, g_, b_, M, d, hp.eps, s));
+  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(hp.dtype, x, y, partials, S, bias, g_, b_, M, d, hp.eps, s, x_in));
   return LSQ_OK;
 }
 
@@ -382,19 +383,30 @@ int launch_step(int B) {
   const int dt = hp.dtype, d = hp.d, F = hp.F, V = hp.V, H = hp.H, k = g.beam, T = g.max_len;
   const int M = B * k, M_max = g.max_batch * k;
   const size_t es = esz();
-  char* x = g.ws + p.d_x; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
+  char* const x_home = g.ws + p.d_x;
+  // Under beam search the step's decoder input waits in a buffer of its own (the re-rank kernel of the step before
+  // wrote it while this step's final hidden rows were still to be read); it is only read, by the first sublayer,
+  // whose LayerNorm leaves the residual stream in the usual two buffers.  Sampling decoding embeds in place.
+  char* const x0 = hp.sample_topk > 0 ? x_home : g.ws + p.d_x0;
+  char* x = x0; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
   int32_t* step = at<int32_t>(p.step_state);
   int32_t* anc = g.anc_on ? at<int32_t>(p.anc) : nullptr;
   const size_t slab = (size_t)M_max * T * d * es;   // one layer's K (or V) cache
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
-  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
+  // Under beam search the decoder input of this step is already there: the re-rank kernel of the step before
+  // (lsq_encode for the first step) wrote it.  Sampling decoding embeds here.
+  if (hp.sample_topk > 0)
+    TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
+  char* x_alt = g.ws + p.d_x2;
+  const NextInput next = {g.E, at<float>(p.pe), g.ws + p.d_x0, d, dt, sqrtf((float)d)};
+  // after a swap of the two hidden-state buffers: the input buffer never becomes one of them
+  auto swapped = [&]() { if (x_alt == x0 && x0 != x_home) x_alt = x_home; };
   // With very few rows alive a sublayer's "add the partial sums, the bias and the residual, then
   // LayerNorm" is not a kernel of its own: the product that consumes the normalised rows does it
   // on its way in, reading the residual from one hidden-state buffer and leaving the new rows in
   // the other.  `pending` carries what that product needs.
   const bool fuse = g.fuse_ln && gemm_ln_supported(dt, M, d);
-  char* x_alt = g.ws + p.d_x2;
   // Few rows alive: each attention sublayer is one launch up to its output projection, which it leaves as one
   // slab of partial sums per head (kernels_attn.hip).  The blocks read their LayerNorm's slabs from one set and
   // write theirs to the other.
@@ -408,7 +420,13 @@ int launch_step(int B) {
   struct { bool on; int S; const void* bias; const void* gain; const void* shift; } pending = {false, 0, nullptr, nullptr, nullptr};
   auto close_sublayer = [&](int cls, const void* in, const void* W, const void* bias, const void* gain, const void* shift,
                             int K, bool defer) -> int {
-    if (!defer) return sublayer(cls, in, W, bias, gain, shift, x, nullptr, slabs, M, d, K, kMaxSplits, s);
+    if (!defer) {
+      if (x == x0 && x0 != x_home) {   // the first sublayer of a step: residual from the input buffer, rows to the stream's own
+        x = x_home;
+        return sublayer(cls, in, W, bias, gain, shift, x, nullptr, slabs, M, d, K, kMaxSplits, s, x0);
+      }
+      return sublayer(cls, in, W, bias, gain, shift, x, nullptr, slabs, M, d, K, kMaxSplits, s);
+    }
     const int S = std::min(gemm_partial_splits(dt, M, d, K), kMaxSplitsFusedLn);
     TIMED(cls, launch_gemm_partials(dt, in, W, slabs, M, d, K, S, s));
     pending = {true, S, bias, gain, shift};
@@ -422,7 +440,7 @@ int launch_step(int B) {
     LnInput ln = {slabs, pending.S, (const half_t*)pending.bias, (const half_t*)pending.gain,
                   (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
     TIMED(cls, launch_gemm_ln(ln, W, bias, o, M, N, d, act, s));
-    std::swap(x, x_alt);
+    std::swap(x, x_alt); swapped();
     pending.on = false;
     return LSQ_OK;
   };
@@ -437,14 +455,14 @@ int launch_step(int B) {
       LnInput ln = {slabs, pending.on ? pending.S : 0, (const half_t*)pending.bias, (const half_t*)pending.gain,
                     (const half_t*)pending.shift, (const half_t*)x, pending.on ? (half_t*)x_alt : nullptr, hp.eps};
       TIMED(PC_SELF_BLOCK, launch_self_block(ln, wqkv_p, L.bqkv, wo_p, Kc, Vc, anc, step, 0, slabs_alt, B, k, H, d, T, s));
-      if (pending.on) std::swap(x, x_alt);
+      if (pending.on) { std::swap(x, x_alt); swapped(); }
       pending.on = false;
       std::swap(slabs, slabs_alt);
       LnInput ln1 = {slabs, H, (const half_t*)L.bo, (const half_t*)L.ln1g, (const half_t*)L.ln1b, (const half_t*)x,
                      (half_t*)x_alt, hp.eps};
       TIMED(PC_CROSS_BLOCK, launch_cross_block(ln1, wq_p, L.bq, woc_p, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                at<int32_t>(p.src_len), slabs_alt, B, k, H, d, s));
-      std::swap(x, x_alt);
+      std::swap(x, x_alt); swapped();
       std::swap(slabs, slabs_alt);
       TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, nullptr, slabs, H, L.boc, L.ln2g, L.ln2b, M, d, hp.eps, s));
       if (int rc = product(PC_GEMM_FFN1, L.W1, L.b1, plain_out(ffn, F), F, 1)) return rc;
@@ -468,7 +486,7 @@ int launch_step(int B) {
                     (const half_t*)pending.shift, (const half_t*)x, (half_t*)x_alt, hp.eps};
       TIMED(PC_ATTN_CROSS, launch_cross_attention_ln(ln, wq_packed, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
                                                      at<int32_t>(p.src_len), ctx, B, k, H, d, s));
-      std::swap(x, x_alt);
+      std::swap(x, x_alt); swapped();
       pending.on = false;
     } else if (const void* wq_p = (g.fuse_ln && !pending.on && cross_attention_q_worthwhile(M) && cross_attention_q_supported(dt, M, k, H, d))
                                       ? gemm_packed_weights(L.Wq, d, d) : nullptr) {
@@ -494,7 +512,7 @@ int launch_step(int B) {
                                                       pending.shift, M, d, hp.eps, s));
     pending.on = false;
   }
-  g.hidden_in_alt = (x != g.ws + p.d_x);   // which of the two hidden-state buffers the last LayerNorm wrote
+  g.hidden_in_alt = (x != x_home);   // which of the two hidden-state buffers the last LayerNorm wrote
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   if (hp.sample_topk > 0) {
     // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
@@ -518,7 +536,7 @@ int launch_step(int B) {
       TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                                           at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                                           at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, kg, V,
-                                          T, 0, step, hp.eos, anc, s, gr));
+                                          T, 0, step, hp.eos, anc, s, gr, next));
     }
     if (!anc)
       TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
@@ -533,7 +551,7 @@ int launch_step(int B) {
   TIMED(PC_REFINE, launch_beam_refine(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<float>(p.score),
                             at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                             at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T, 0,
-                            step, hp.eos, anc, s));
+                            step, hp.eos, anc, s, one_group(), next));
   if (!anc)
     TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
                                            0, step, T, s));
@@ -961,6 +979,10 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
                            at<int32_t>(p.active), at<int32_t>(p.step_state), g.anc_on ? at<int32_t>(p.anc) : nullptr,
                            at<int32_t>(p.pen_n), batch, g.beam, g.beam / g.groups, g.max_len, hp.bos,
                            hp.pad, s));
+  // the first step's decoder input (BOS at position 0); later ones are left by each step's re-rank kernel
+  if (hp.sample_topk == 0)
+    HIPCHK(launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), g.ws + p.d_x0,
+                             batch * g.beam, d, g.max_len, at<int32_t>(p.step_state), sqrtf((float)d), s));
   for (size_t c : p.dec_canaries) HIPCHK(hipMemsetAsync(g.ws + c, kCanaryByte, kCanaryBytes, s));
   g.batch = batch;
   g.rows_enc = (int)R;
