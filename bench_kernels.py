@@ -39,7 +39,8 @@ PMC_CASES = [("gemm_qkv", PMC_TRAFFIC + PMC_GEMM), ("gemm_dxd", PMC_TRAFFIC + PM
              ("attn_cross B128", PMC_TRAFFIC), ("attn_cross_q", PMC_TRAFFIC), ("row_topk", PMC_TRAFFIC),
              ("enc_attn", PMC_TRAFFIC + [["MfmaUtil"]]), ("enc gemm_qkv", PMC_TRAFFIC + PMC_GEMM),
              ("enc gemm_ffn1", PMC_TRAFFIC + PMC_GEMM), ("enc sublayer_ffn2", PMC_TRAFFIC + PMC_GEMM),
-             ("cache_reorder", PMC_TRAFFIC), ("stress gemm M4096", PMC_GEMM), ("stress attn_self M2048", PMC_TRAFFIC),
+             ("cache_reorder", PMC_TRAFFIC), ("self_block", PMC_TRAFFIC), ("cross_block", PMC_TRAFFIC),
+             ("stress gemm M4096", PMC_GEMM), ("stress attn_self M2048", PMC_TRAFFIC),
              ("stress attn_self_table", PMC_TRAFFIC), ("stress row_topk", PMC_TRAFFIC), ("copy", PMC_TRAFFIC)]
 
 
@@ -76,7 +77,9 @@ def profile_all(outdir: str) -> int:
                     continue
                 agg[(kn, r["Counter_Name"])].append(float(r["Counter_Value"]))
             for (kn, cn), v in agg.items():
-                table.setdefault((case, kn), {})[cn] = sorted(v)[len(v) // 2]
+                # the calibration copy: the runtime's copy kernel also serves the small host-to-device copies of the
+                # set-up, so the 1 GiB launches are the largest readings, not the median
+                table.setdefault((case, kn), {})[cn] = max(v) if case == "copy" else sorted(v)[len(v) // 2]
         print(f"# done {case}", file=sys.stderr, flush=True)
     for (case, kn), row in table.items():
         print(f"# raw {case:24s} {kn[:64]:64s} " + " ".join(f"{c}={v:.6g}" for c, v in row.items()), file=sys.stderr)
@@ -242,6 +245,38 @@ def main() -> int:
         cases.append((name, "hbm", 2.0 * B * k * d * d + 4.0 * k * int(lens.sum()) * d, by,
                       lambda: lsq.k_cross_attention_q(xx, Wp, bq, kv, off, ln, out, B, k, H)))
 
+    def self_block_case(name, B, k, H, d, T, nkeys):
+        # one attention sublayer of a decoder layer in one launch (models up to d = 512, at most 64 rows)
+        M_ = B * k
+        xx, x_new = rnd(M_, d), torch.empty(M_, d, device=dev, dtype=h)
+        P = torch.randn(2, M_, d, device=dev, dtype=torch.float32, generator=g) * 0.3
+        lb, gm, bt = rnd(d, scale=0.02), rnd(d) * 0 + 1, rnd(d, scale=0.02)
+        Wqkv, bqkv, Wo = rnd(3 * d, d, scale=0.02), rnd(3 * d, scale=0.02), rnd(d, d, scale=0.02)
+        Wp, Wop = lsq.k_pack_weights(Wqkv), lsq.k_pack_weights(Wo)
+        Kc, Vc = rnd(M_, T, d), rnd(M_, T, d)
+        slab = torch.randint(0, k, (M_, T + 1), device=dev, dtype=torch.int32, generator=g)
+        P_out = torch.empty(H, M_, d, device=dev, dtype=torch.float32)
+        by = 4 * d * d * 2 + 2 * M_ * nkeys * d * 2 + (2 + H) * M_ * d * 4
+        cases.append((name, "hbm", 2.0 * M_ * 4 * d * d + 4.0 * M_ * nkeys * d, by,
+                      lambda: lsq.k_self_attention_block(P, lb, gm, bt, xx, x_new, 1e-5, Wp, bqkv, Wop, Kc, Vc, slab, nkeys,
+                                                         P_out, B, k, H)))
+
+    def cross_block_case(name, B, k, H, d, lens):
+        lens = np.asarray(lens, np.int32)
+        M_ = B * k
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+        xx, x_new, kv = rnd(M_, d), torch.empty(M_, d, device=dev, dtype=h), rnd(int(lens.sum()), 2 * d)
+        P = torch.randn(H, M_, d, device=dev, dtype=torch.float32, generator=g) * 0.3
+        lb, gm, bt = rnd(d, scale=0.02), rnd(d) * 0 + 1, rnd(d, scale=0.02)
+        Wq, bq, Wo = rnd(d, d, scale=0.02), rnd(d, scale=0.02), rnd(d, d, scale=0.02)
+        Wp, Wop = lsq.k_pack_weights(Wq), lsq.k_pack_weights(Wo)
+        ln = torch.from_numpy(lens).to(dev)
+        P_out = torch.empty(H, M_, d, device=dev, dtype=torch.float32)
+        by = 2 * d * d * 2 + 2 * int(lens.sum()) * d * 2 + 2 * H * M_ * d * 4
+        cases.append((name, "hbm", 2.0 * M_ * 2 * d * d + 4.0 * k * int(lens.sum()) * d, by,
+                      lambda: lsq.k_cross_attention_block(P, lb, gm, bt, xx, x_new, 1e-5, Wp, bq, Wop, kv, off, ln, P_out,
+                                                          B, k, H)))
+
     def enc_attn_case(name, H, d, lens):
         lens = np.asarray(lens, np.int32)
         R = int(lens.sum())
@@ -296,6 +331,9 @@ def main() -> int:
     gemm_case("enc gemm_ffn1 M3660 N4096 K1024", 3660, F, d, relu=True)
     sublayer_case("enc sublayer_ffn2 M3660 d1024 K4096", 3660, d, F)
     reorder_case("cache_reorder L12 B128 k4 t41 (3 of 4 rows move)", 2 * L, 128, 4, T, d, 41)
+    self_block_case("self_block base B8 k4 d512 t40 (LN + QKV + append + attention + out-proj share)", 8, 4, 8, 512, 110, 40)
+    cross_block_case("cross_block base B8 k4 d512 meanlen35 (LN + Q + attention + out-proj share)", 8, 4, 8, 512,
+                     np.random.default_rng(4321).integers(10, 61, 8))
     if not args.no_stress:
         gemm_case("stress gemm M4096 N4096 K4096", 4096, 4096, 4096)
         gemm_case("stress gemm_vocab M4096 N32000 K1024 f32out", 4096, V, d, out_f32=True)
