@@ -80,16 +80,16 @@ def test_prompt_of_one_token_and_errors(lsq):
 @pytest.mark.parametrize("name", ["gpt2s", "gpt2s_k32p75"])
 def test_gpt2_small_shape(lsq, name):
     """The GPT-2-small-shaped workload (batch 32, prompt 64, top-8 sampling; or top-32 with a 0.75 nucleus):
-    6 steps in lock-step with the oracle, then the remaining steps without per-step waits; a second run is
+    40 steps in lock-step with the oracle, then the remaining steps without per-step waits; a second run is
     bit-identical."""
     w = S.workload(name)
     blob = w.blob()
     with lsq.Engine(blob, w.batch, 1, w.max_len) as eng:
-        res = lockstep_gpt(lsq, eng, blob, w, n_steps=6, verbose=True)
+        res = lockstep_gpt(lsq, eng, blob, w, n_steps=40, verbose=True)
         # random weights give nearly flat logits: most draws sit within the fp16 band of a rank swap or an
         # edge and are checked on the library's own logits instead (exactly, inside lockstep_gpt)
         if name == "gpt2s":      # with 32 candidates of a random model no draw is clear of the fp16 band: own-logit checks only
-            assert res["strict"] >= 0.25 * 6 * w.batch, res
+            assert res["strict"] >= 0.25 * 40 * w.batch, res
         while eng.decode_steps(32) > 0:
             pass
         assert lsq.lsq_step_index() == 128
