@@ -56,8 +56,8 @@ PEAK_F16_TFLOPS = 2500.0       # dense fp16 MFMA
 TRAFFIC_CASES = {
     "gemm_qkv": ["gemm_qkv"], "gemm_dxd": ["gemm_dxd"], "gemm_ffn1": ["gemm_ffn1"],
     "gemm_out": ["sublayer_out"], "gemm_ffn2": ["sublayer_ffn2"],
-    "gemm_vocab": ["gemm_vocab"], "attn_self": ["attn_self_table"], "attn_cross": ["attn_cross B128"], "attn_cross_q": ["attn_cross_q"],
-    "row_topk": ["row_topk"], "cache_reorder": ["cache_reorder"],
+    "gemm_vocab": ["gemm_logits"], "attn_self": ["attn_self_table"], "attn_cross": ["attn_cross B128"], "attn_cross_q": ["attn_cross_q"],
+    "row_topk": ["row_topk M512"], "row_topk_groups": ["row_topk_groups"], "cache_reorder": ["cache_reorder"],
 }
 
 
@@ -105,6 +105,8 @@ def class_work(name, hp, B, k, t_mean, s_mean):
         return (2.0 * M * d, 2 * M * d * es)
     if name == "row_topk":       # logits read once
         return (4.0 * M * V, M * V * 4)
+    if name == "row_topk_groups":   # the group statistics of the row, the logits of the k groups that reach the threshold
+        return (0.0, M * (((V + 31) // 32) * 8 + k * 32 * 4 + k * 8))
     if name == "beam_refine":
         return (0.0, M * max(k, hp.sample_topk) * 8)
     if name == "cache_reorder":  # whole live cache gathered: read + write, all layers, K and V

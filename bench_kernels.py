@@ -36,7 +36,8 @@ PMC_GEMM = [["MfmaUtil"], ["SQ_INSTS_LDS", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_L
 PMC_CASES = [("gemm_qkv", PMC_TRAFFIC + PMC_GEMM), ("gemm_dxd", PMC_TRAFFIC + PMC_GEMM), ("gemm_ffn1", PMC_TRAFFIC + PMC_GEMM),
              ("sublayer_out", PMC_TRAFFIC + PMC_GEMM), ("sublayer_ffn2", PMC_TRAFFIC + PMC_GEMM),
              ("gemm_vocab", PMC_TRAFFIC + PMC_GEMM), ("attn_self M512", PMC_TRAFFIC), ("attn_self_table", PMC_TRAFFIC),
-             ("attn_cross B128", PMC_TRAFFIC), ("attn_cross_q", PMC_TRAFFIC), ("row_topk", PMC_TRAFFIC),
+             ("attn_cross B128", PMC_TRAFFIC), ("attn_cross_q", PMC_TRAFFIC), ("row_topk M512", PMC_TRAFFIC),
+             ("gemm_logits", PMC_TRAFFIC + PMC_GEMM), ("row_topk_groups", PMC_TRAFFIC),
              ("enc_attn", PMC_TRAFFIC + [["MfmaUtil"]]), ("enc gemm_qkv", PMC_TRAFFIC + PMC_GEMM),
              ("enc gemm_ffn1", PMC_TRAFFIC + PMC_GEMM), ("enc sublayer_ffn2", PMC_TRAFFIC + PMC_GEMM),
              ("cache_reorder", PMC_TRAFFIC), ("self_block", PMC_TRAFFIC), ("cross_block", PMC_TRAFFIC),
@@ -298,6 +299,22 @@ def main() -> int:
         oi = torch.empty(M, k, device=dev, dtype=torch.int32)
         cases.append((name, "hbm", 4.0 * M * V, M * V * 4, lambda: lsq.k_row_topk(logits, score, fin, k, 2, os_, oi)))
 
+    def logits_stats_case(name, M, V, K, k):
+        # the logit product with the retrieve stage's group statistics, and the retrieve kernel that works from them
+        A, B = rnd(M, K), rnd(V, K, scale=0.02)
+        C = torch.empty(M, V, device=dev, dtype=torch.float32)
+        st = torch.empty(M, (V + 31) // 32, 2, device=dev, dtype=torch.float32)
+        score = -torch.rand(M, device=dev, generator=g) * 40
+        fin = torch.zeros(M, device=dev, dtype=torch.int32)
+        os_ = torch.empty(M, k, device=dev, dtype=torch.float32)
+        oi = torch.empty(M, k, device=dev, dtype=torch.int32)
+        by = (M * K + V * K) * 2 + M * V * 4 + M * ((V + 31) // 32) * 8
+        cases.append((f"gemm_logits M{M} N{V} K{K} f32out + group statistics", "mfma", 2.0 * M * V * K, by,
+                      lambda: lsq.k_gemm_logits(A, B, C, st)))
+        lsq.k_gemm_logits(A, B, C, st)
+        cases.append((name, "hbm", 0.0, M * ((V + 31) // 32) * 8 + M * k * 32 * 4,
+                      lambda: lsq.k_row_topk_groups(C, st, score, fin, k, 2, os_, oi)))
+
     def reorder_case(name, layers, B, k, T, d, npos):
         cache = rnd(layers, B * k, T, d)
         # every sentence: beams 1..k-1 take beam 0's history (k-1 rows move, 1 row is read)
@@ -325,6 +342,7 @@ def main() -> int:
     cross_q_case("attn_cross_q B128 k4 meanlen29 (query product + attention)", 128, 4, H, d,
                  np.clip(np.rint(np.random.default_rng(4321).lognormal(3.15, 0.6, 128)), 1, 128))
     topk_case("row_topk M512 V32000 k4", M, V, 4)
+    logits_stats_case("row_topk_groups M512 V32000 k4 (from the product's group statistics)", M, V, d, 4)
     enc_lens = np.clip(np.rint(np.random.default_rng(4321).lognormal(3.15, 0.6, 128)), 1, 128)
     enc_attn_case("enc_attn B128 meanlen29", H, d, enc_lens)
     gemm_case("enc gemm_qkv M3660 N3072 K1024", 3660, 3 * d, d)

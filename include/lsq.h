@@ -157,6 +157,14 @@ int lsq_set_layernorm_fusion(int on);
  * off when lsq_set_layernorm_fusion(0).  May be called at any time. */
 int lsq_set_attention_blocks(int max_rows);
 
+/* Plain beam search of float16 models: the logit product also leaves, for every row and every 32
+ * consecutive tokens, the largest logit and the sum of exponentials, and the retrieve stage (sec.
+ * 2.2) takes its threshold and the softmax normaliser from those and reads only the logits of the
+ * groups that reach the threshold (lsq_k_gemm_logits, lsq_k_row_topk_groups).  Default on; 0: the
+ * retrieve kernel reads every row in full.  Same tokens; scores equal to the rounding of the
+ * normaliser.  May be called at any time. */
+int lsq_set_topk_statistics(int on);
+
 /* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
  * al. 2016, Hamming diversity).  The beam is split into `groups` groups of
  * beam / groups hypotheses; at every step the groups of a sentence choose in
@@ -372,6 +380,24 @@ int lsq_k_encoder_attention(int dtype, const void* qkv, const int32_t* row_seq, 
  * slots (idx -1).  score float32, finished int32. */
 int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int32_t* finished,
                    int M, int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream);
+
+/* Vocabulary logits with the retrieve stage's group statistics (paper sec. 2.2, made where the
+ * logits are made): C [M,N] float = A [M,K] . B [N,K]^T (float16 operands, float32 accumulators,
+ * nothing rounded) and, for every row m and every group g of 32 consecutive columns,
+ *   stats[(m * G + g) * 2 + 0] = largest C[m, n] of the group,
+ *   stats[(m * G + g) * 2 + 1] = sum over the group of exp(C[m, n] - largest),   G = ceil(N / 32).
+ * Only for shapes whose kernel writes them: lsq_k_gemm_logits_supported(M, N, K) != 0 (at most 64
+ * rows with K a multiple of 16; more rows when N is large and K a multiple of 64), else
+ * LSQ_E_ARG.  All device pointers, 16-byte aligned; stats M * G * 2 floats. */
+int lsq_k_gemm_logits(const void* A, const void* B, void* C, float* stats, int M, int N, int K, void* stream);
+int lsq_k_gemm_logits_supported(int M, int N, int K);
+
+/* lsq_k_row_topk (beam search: dtype float32 logits, raw == 0) computed from the statistics
+ * above: the normaliser from the G pairs, the threshold R = k-th largest group maximum (as a
+ * candidate score), and only the logits of groups that reach R are read.  Same outputs as
+ * lsq_k_row_topk up to the rounding of the normaliser; k at most the beam limit. */
+int lsq_k_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* finished,
+                          int M, int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream);
 
 /* Re-rank stage: per sentence the k best of its k*k row candidates by
  * (score descending, beam*V+token ascending); updates score, tokens [M,T+1],

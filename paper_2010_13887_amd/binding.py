@@ -52,12 +52,16 @@ def load_library() -> C.CDLL:
         "lsq_set_diversity": [i32, f32],
         "lsq_set_layernorm_fusion": [i32],
         "lsq_set_attention_blocks": [i32],
+        "lsq_set_topk_statistics": [i32],
         "lsq_set_canaries": [i32],
         "lsq_debug_check_canaries": [],
         "lsq_k_layernorm_gemm": [i32, vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_layernorm_cross_attention": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, i32, i32,
                                             i32, vp],
         "lsq_k_cross_attention_q": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
+        "lsq_k_gemm_logits": [vp, vp, vp, vp, i32, i32, i32, vp],
+        "lsq_k_gemm_logits_supported": [i32, i32, i32],
+        "lsq_k_row_topk_groups": [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
         "lsq_k_self_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32,
                                        i32, i32, vp],
         "lsq_k_cross_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32,
@@ -155,6 +159,11 @@ def lsq_set_layernorm_fusion(on: bool) -> None:
 def lsq_set_attention_blocks(max_rows: int) -> None:
     """Attention sublayers as one launch each while at most max_rows rows are alive (0: off; default 64)."""
     _check(load_library().lsq_set_attention_blocks(int(max_rows)))
+
+
+def lsq_set_topk_statistics(on: bool) -> None:
+    """Retrieve stage from the logit product's group statistics (default on)."""
+    _check(load_library().lsq_set_topk_statistics(int(on)))
 
 
 def lsq_set_canaries(on: bool) -> None:
@@ -334,6 +343,25 @@ def k_cross_attention_block(P, ln_bias, gamma, beta, x_old, x_new, eps: float, W
     _check(load_library().lsq_k_cross_attention_block(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old), _p(x_new),
                                                       eps, _p(Wq_packed), _p(bq), _p(Wo_packed), _p(kv), _p(src_off),
                                                       _p(src_len), _p(P_out), batch, beam, heads, d, _stream()))
+
+
+def k_gemm_logits(A, B, C_out, stats) -> None:
+    """C_out [M,N] float32 = A . B^T with (largest, sum of exp(value - largest)) of every (row, 32-column group) in
+    stats [M, ceil(N/32), 2]."""
+    M, K = A.shape
+    N = B.shape[0]
+    assert tuple(stats.shape) == (M, (N + 31) // 32, 2)
+    _check(load_library().lsq_k_gemm_logits(_p(A), _p(B), _p(C_out), _p(stats), M, N, K, _stream()))
+
+
+def k_gemm_logits_supported(M: int, N: int, K: int) -> bool:
+    return bool(load_library().lsq_k_gemm_logits_supported(M, N, K))
+
+
+def k_row_topk_groups(logits, stats, score, finished, k: int, eos: int, out_score, out_idx) -> None:
+    M, V = logits.shape
+    _check(load_library().lsq_k_row_topk_groups(_p(logits), _p(stats), _p(score), _p(finished), M, V, k, eos,
+                                                _p(out_score), _p(out_idx), _stream()))
 
 
 def k_cross_attention_q(x, Wq_packed, bq, kv, src_off, src_len, out, batch: int, beam: int, heads: int) -> None:

@@ -496,6 +496,40 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_large_ker
       }
     }
   }
+  if constexpr (std::is_same<OutT, float>::value) {
+    // (largest, sum of exponentials) of every (row, 32-column group): a wave tile holds a group's 32 columns of a
+    // row in the two lanes (m, half 0) and (m, half 1)
+    if (out.stats) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm + i * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int nb = n0 + wn + j * 32;
+          if (nb >= N) continue;   // the same in every lane
+          float x[16], mx = -INFINITY;
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int n = nb + vg * 8 + (lane >> 5) * 4 + e;
+              x[vg * 4 + e] = n < N ? activate(acc[i][j][vg * 4 + e] + bv[j][vg][e], act) : -INFINITY;
+              mx = fmaxf(mx, x[vg * 4 + e]);
+            }
+          mx = max_lane_xor<32>(mx);   // finite: column nb exists
+          float z = 0.f;
+#pragma unroll
+          for (int q = 0; q < 16; ++q) z += __expf(x[q] - mx);
+          z = add_lane_xor<32>(z);
+          if (lane < 32 && m < M) {
+            float* st = out.stats + ((size_t)m * out.stats_groups + nb / 32) * 2;
+            st[0] = mx;
+            st[1] = z;
+          }
+        }
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -614,11 +648,13 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
   // thread (vg = wave, lane) finishes the four outputs m = i*32 + (lane & 31), n = n0 + vg*8 + (lane>>5)*4 + 0..3
   const int vg = wave;
   const int n = n0 + vg * 8 + (lane >> 5) * 4;
-  if (n >= N) return;
+  constexpr bool kStats = !SPLIT && std::is_same<OutT, float>::value;
+  __shared__ float st_m[kStats ? 4 : 1][TM][32], st_z[kStats ? 4 : 1][TM][32];
+  const bool stats = kStats && out.stats != nullptr;   // the same in every thread
+  if (n >= N && !stats) return;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = i * 32 + (lane & 31);
-    if (m >= M) continue;
     float v[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -627,7 +663,41 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
       if (!SPLIT && bias) v[e] += (float)bias[min(n + e, N - 1)];
       v[e] = activate(v[e], act);
     }
-    store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
+    if (m < M && n < N) store4<OutT, SPLIT>(out, m, n, v, M, N, vec_ok, (int)blockIdx.y, tp);
+    if constexpr (kStats) {
+      if (stats) {
+        // (largest, sum of exponentials) of the workgroup's 32 columns, row by row: this thread's four
+        // columns, the other half of the lanes, then (through LDS) the four wavefronts
+        float mx = -INFINITY, z = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < N) mx = fmaxf(mx, v[e]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < N) z += __expf(v[e] - mx);
+        const float m2 = lane_xor<32>(mx), z2 = lane_xor<32>(z);
+        merge_stat(mx, z, m2, z2);
+        if (lane < 32) { st_m[wave][i][lane] = mx; st_z[wave][i][lane] = z; }
+      }
+    }
+  }
+  if constexpr (kStats) {
+    if (stats) {
+      __syncthreads();   // every thread of the workgroup gets here (no early return on this path)
+      if (wave == 0 && lane < 32) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = i * 32 + lane;
+          if (m >= M) continue;
+          float mx = st_m[0][i][lane], z = st_z[0][i][lane];
+#pragma unroll
+          for (int w = 1; w < 4; ++w) merge_stat(mx, z, st_m[w][i][lane], st_z[w][i][lane]);
+          float* st = out.stats + ((size_t)m * out.stats_groups + blockIdx.x) * 2;
+          st[0] = mx;
+          st[1] = z;
+        }
+      }
+    }
   }
 }
 
@@ -977,12 +1047,21 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   return hipGetLastError();
 }
 
+// mirrors launch_gemm's choice of kernel below: the skinny kernels and the large-tile kernel fill GemmOut::stats
+bool gemm_writes_stats(int dtype, int M, int N, int K) {
+  if (dtype != DT_F16 || M <= 0 || N <= 0 || K <= 0 || K % 8 != 0) return false;
+  if (M <= kSkinnyRows) return K % 16 == 0;
+  return (long)((M + 127) / 128) * ((N + 127) / 128) >= 200 && K % 64 == 0;
+}
+
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
                        int N, int K, int act /* activation: 0 none, 1 ReLU, 2 tanh-GELU */, hipStream_t s,
                        bool b_packed) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K <= 0) return hipErrorInvalidValue;
   if (b_packed && !(dtype == DT_F16 && M <= kSkinnyRows && K % 16 == 0)) return hipErrorInvalidValue;
+  if (out.stats && !(out.f32_out && gemm_writes_stats(dtype, M, N, K) && out.stats_groups >= (N + 31) / 32))
+    return hipErrorInvalidValue;
   if (dtype == DT_F32) {
     if (K % 8 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0) {
       int nseg = (N + out.seg_n - 1) / out.seg_n;

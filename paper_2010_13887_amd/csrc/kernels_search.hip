@@ -273,6 +273,173 @@ row_topk_kernel(const T* __restrict__ logits,
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The retrieve stage (paper sec. 2.2) from group statistics that the logit product left behind: for every
+// row and every group of 32 consecutive tokens the pair (largest logit, sum of exp(logit - largest)).
+// One wavefront per row:
+//   * softmax normaliser of the row from the G pairs (no pass over the logits);
+//   * candidate value of every group's best token, cand = score + ((x - max) - log sum), the same
+//     arithmetic as row_topk_kernel token by token (monotone in x, so it is the group's best cand);
+//   * R = the k-th largest of those: k distinct tokens reach R, so every token of the row's exact
+//     top k has cand >= R, and such tokens only sit in groups whose best reaches R -- the paper's
+//     threshold with the product's column groups as the "random" groups;
+//   * only those groups' logits are read (k groups of 32 unless values tie), tokens with cand >= R
+//     are ranked exactly by (cand descending, token ascending).
+// Rows where more than QMAX groups or CMAX tokens reach R (long runs of equal logits) fall back to k
+// exact rounds over the whole row.  Same output as row_topk_kernel (beam search, no groups, not raw).
+template <int GPL>
+__global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __restrict__ logits,
+                                                              const float* __restrict__ stats,
+                                                              const float* __restrict__ score,
+                                                              const int32_t* __restrict__ fin, int M, int V, int G,
+                                                              int k, int eos, float* __restrict__ out_score,
+                                                              int32_t* __restrict__ out_idx) {
+  constexpr int QMAX = 64, CMAX = 128;
+  __shared__ int ql[4][QMAX];
+  __shared__ float cs[4][CMAX];
+  __shared__ int ci[4][CMAX];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= M) return;
+  const float bs = score[r];
+  const int f = fin[r];
+  // the row's statistics, requested before anything is decided
+  float gm[GPL], gz[GPL];
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) {
+    const int g = q * 64 + lane;
+    if (g < G) {
+      const float2 t = *reinterpret_cast<const float2*>(stats + ((size_t)r * G + g) * 2);
+      gm[q] = t.x; gz[q] = t.y;
+    } else {
+      gm[q] = -INFINITY; gz[q] = 0.f;
+    }
+  }
+  float* os = out_score + (size_t)r * k;
+  int32_t* oi = out_idx + (size_t)r * k;
+  if (f) {   // a finished hypothesis offers itself once
+    if (lane < k) { os[lane] = lane == 0 ? bs : -INFINITY; oi[lane] = lane == 0 ? eos : -1; }
+    return;
+  }
+  if (bs == -INFINITY) {   // every candidate is -inf: the order is by token alone
+    if (lane < k) { os[lane] = -INFINITY; oi[lane] = lane < V ? lane : -1; }
+    return;
+  }
+  float m = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) m = fmaxf(m, gm[q]);
+  m = wave_max(m);
+  float zt = 0.f;
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) zt += gz[q] * __expf(gm[q] - m);   // a group that does not exist: 0 * exp(-inf) = 0
+  zt = wave_sum(zt);
+  const float logz = logf(zt);
+  auto cand_of = [&](float x) { return __fadd_rn(bs, __fsub_rn(__fsub_rn(x, m), logz)); };
+  float cg[GPL], work[GPL];
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) {
+    cg[q] = (q * 64 + lane < G) ? cand_of(gm[q]) : -INFINITY;
+    work[q] = cg[q];
+  }
+  // R: the k-th largest group value, counted with multiplicity (fewer than k groups: -inf, every token passes)
+  float R = INFINITY;
+  for (int round = 0; round < k; ++round) {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < GPL; ++q) lm = fmaxf(lm, work[q]);
+    const float wm = wave_max(lm);
+    R = wm;
+    if (wm == -INFINITY) break;
+    const unsigned long long holders = __ballot(lm == wm);
+    if (lane == __builtin_ctzll(holders)) {   // one instance leaves, in one lane
+      bool gone = false;
+#pragma unroll
+      for (int q = 0; q < GPL; ++q)
+        if (!gone && work[q] == wm) { work[q] = -INFINITY; gone = true; }
+    }
+  }
+  // the groups that reach R
+  int nq = 0;
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) {
+    const bool in = q * 64 + lane < G && cg[q] >= R;
+    const unsigned long long mask = __ballot(in);
+    if (in) {
+      const int at = nq + __popcll(mask & ((1ull << lane) - 1ull));
+      if (at < QMAX) ql[wave][at] = q * 64 + lane;
+    }
+    nq += __popcll(mask);
+  }
+  __builtin_amdgcn_wave_barrier();   // the list is read by other lanes of this wavefront (LDS keeps a wavefront's order)
+  const float* row = logits + (size_t)r * V;
+  int nc = 0;
+  if (nq <= QMAX) {
+    // two groups per pass: lanes 0-31 one, lanes 32-63 the next
+    for (int p0 = 0; p0 < nq && nc <= CMAX; p0 += 2) {
+      const int gi = p0 + (lane >> 5);
+      const int v = gi < nq ? ql[wave][gi] * 32 + (lane & 31) : V;
+      const float c = v < V ? cand_of(row[v]) : -INFINITY;
+      const bool in = v < V && c >= R;
+      const unsigned long long mask = __ballot(in);
+      if (in) {
+        const int at = nc + __popcll(mask & ((1ull << lane) - 1ull));
+        if (at < CMAX) { cs[wave][at] = c; ci[wave][at] = v; }
+      }
+      nc += __popcll(mask);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (nq <= QMAX && nc <= CMAX) {
+    for (int c = lane; c < nc; c += 64) {
+      const float sc = cs[wave][c];
+      const int v = ci[wave][c];
+      int rank = 0;
+      for (int o = 0; o < nc; ++o) rank += precedes(cs[wave][o], ci[wave][o], sc, v) ? 1 : 0;
+      if (rank < k) { os[rank] = sc; oi[rank] = v; }
+    }
+    if (lane >= nc && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
+    return;
+  }
+  // exact fallback: k rounds over the whole row, each the best token strictly after the previous winner
+  float ps = INFINITY;
+  int pi = -1;
+  for (int round = 0; round < k; ++round) {
+    float bsc = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int v = lane; v < V; v += 64) {
+      const float c = cand_of(row[v]);
+      if (precedes(ps, pi, c, v) && (bi == 0x7fffffff || precedes(c, v, bsc, bi))) { bsc = c; bi = v; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float s2 = __shfl_xor(bsc, o, kWave);
+      const int i2 = __shfl_xor(bi, o, kWave);
+      if (i2 != 0x7fffffff && (bi == 0x7fffffff || precedes(s2, i2, bsc, bi))) { bsc = s2; bi = i2; }
+    }
+    if (bi == 0x7fffffff) {
+      if (lane == 0) { os[round] = -INFINITY; oi[round] = -1; }
+    } else {
+      if (lane == 0) { os[round] = bsc; oi[round] = bi; }
+      ps = bsc;
+      pi = bi;
+    }
+  }
+}
+
+bool topk_groups_supported(int V, int k) { return V >= 1 && V <= 65536 && k >= 1 && k <= LSQ_MAX_BEAM_; }
+
+hipError_t launch_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* fin, int M,
+                                  int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (!topk_groups_supported(V, k) || !stats) return hipErrorInvalidValue;
+  const int G = (V + 31) / 32;
+  dim3 g((M + 3) / 4), b(256);
+  if (G <= 64 * 4) row_topk_groups_kernel<4><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
+  else if (G <= 64 * 16) row_topk_groups_kernel<16><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
+  else row_topk_groups_kernel<32><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
+  return hipGetLastError();
+}
+
 bool topk_supported(int V) { return V >= 1 && V <= 65536; }
 
 template <typename T>

@@ -30,6 +30,12 @@ struct GemmOut {
   // read on the device (the decode-step counter), so the same launch serves every step.
   const int32_t* tpos;
   long tmul[3];
+  // Optional, fp32 output of a float16 product only (vocabulary logits): for every row and every group of 32
+  // consecutive output columns the pair (largest value, sum of exp(value - largest)) at
+  // stats[(m * stats_groups + n / 32) * 2]: the group maxima of the retrieve stage (paper sec. 2.2) and the
+  // softmax normaliser, taken where the logits are made.  Only the kernels gemm_writes_stats names fill it.
+  float* stats;
+  int stats_groups;
 };
 
 inline GemmOut plain_out(void* c, int N) {
@@ -40,6 +46,7 @@ inline GemmOut plain_out(void* c, int N) {
   o.f32_out = 0;
   o.tpos = nullptr;
   o.tmul[0] = o.tmul[1] = o.tmul[2] = 0;
+  o.stats = nullptr; o.stats_groups = 0;
   return o;
 }
 
@@ -47,6 +54,9 @@ inline GemmOut plain_out(void* c, int N) {
 // act: 0 none, 1 ReLU, 2 tanh-GELU
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out,
                        int M, int N, int K, int act, hipStream_t s, bool b_packed = false);
+
+// whether launch_gemm's kernel for this shape fills out.stats (float16 operands, fp32 output)
+bool gemm_writes_stats(int dtype, int M, int N, int K);
 
 int gemm_partial_splits(int dtype, int M, int N, int K);
 
@@ -170,6 +180,11 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
 // [batch*k, T+1] is gathered by parent like the token histories, and entry t+1 of every row is set
 // to the row's own beam index.
 // groups given (kg < k_all): k is the group width kg, candidates are [rows, kg]; see SearchGroups.
+// row_topk for plain beam search from the logit product's group statistics (GemmOut::stats): same output, the
+// logits of only the groups that can hold a top-k token are read
+bool topk_groups_supported(int V, int k);
+hipError_t launch_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* fin, int M,
+                                  int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s);
 // The next step's decoder input, left behind by the kernel that settles the step's tokens:
 // x[row] = E[last token of row] * scale + pe[t + 1] (E == nullptr: not asked for).
 struct NextInput {
@@ -399,6 +414,13 @@ __device__ __forceinline__ void layernorm_row(float (&v)[NV][8], const float (&g
       // instead of twice, in one kernel and not in the other
       asm volatile("" : "+v"(o[j][i]));
     }
+}
+
+// Softmax statistics of two sets of values merged: (max, sum of exp(value - max)).  A set without values is (-inf, 0).
+__device__ __forceinline__ void merge_stat(float& m, float& z, float m2, float z2) {
+  const float mn = fmaxf(m, m2);
+  if (mn != -INFINITY) z = z * __expf(m - mn) + z2 * __expf(m2 - mn);
+  m = mn;
 }
 
 // v <- v + ((p[0] + p[1] + ... + p[S-1]) + t), slabs added in index order, nothing contracted

@@ -40,12 +40,12 @@ int fail(int code, const char* fmt, ...) {
 // per kernel class.  Events come from a host-side pool that only grows.
 enum ProfClass {
   PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
-  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_SELF_BLOCK, PC_CROSS_BLOCK, PC_COUNT
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_SELF_BLOCK, PC_CROSS_BLOCK, PC_ROW_TOPK_GROUPS, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
                                           "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
                                           "beam_refine", "cache_reorder", "gemm_out", "attn_cross_q", "self_block",
-                                          "cross_block"};
+                                          "cross_block", "row_topk_groups"};
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
@@ -186,7 +186,7 @@ struct Plan {
   // encoder view of scratch
   size_t e_ids, e_pos, e_sent, e_x, e_qkv, e_ctx, e_tmp, e_ffn;
   // decoder view of scratch
-  size_t d_x, d_q, d_ctx, d_tmp, d_tmp2, d_ffn, d_logits, d_y, e_y, d_x2, d_x0;
+  size_t d_x, d_q, d_ctx, d_tmp, d_tmp2, d_ffn, d_logits, d_y, e_y, d_x2, d_x0, d_stats;
 };
 
 size_t packed_weight_bytes(const HParams& hp);
@@ -253,6 +253,7 @@ Plan make_plan(const HParams& hp, size_t weight_bytes, int B, int k, int T) {
   p.d_y = dtake(M * d * esz);
   p.d_x2 = dtake(M * d * esz);   // second hidden-state buffer for products that normalise their own input
   p.d_x0 = dtake(M * d * esz);   // decoder input of the next step, left by the kernel that settles this step's tokens
+  p.d_stats = dtake(M * ((V + 31) / 32) * 2 * 4);   // (largest, sum of exponentials) of every 32 logits of a row
   p.d_ffn = q;
   p.d_logits = q;
   q += up(std::max(M * F * esz, M * V * 4));   // logits stay fp32 whatever the model dtype
@@ -309,6 +310,7 @@ struct Ctx {
   bool anc_on = false;    // this translation uses the slab table
   bool fuse_ln = true;    // few rows alive: LayerNorm inside the product that consumes it
   int block_rows = 64;    // ... and whole attention sublayers in one launch up to this many rows
+  bool topk_stats = true; // beam search: retrieve from the logit product's group statistics
   int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
@@ -513,6 +515,12 @@ int launch_step(int B) {
     pending.on = false;
   }
   g.hidden_in_alt = (x != x_home);   // which of the two hidden-state buffers the last LayerNorm wrote
+  // Plain beam search: the logit product also leaves (largest, sum of exponentials) of every 32 logits of a row,
+  // and the retrieve kernel works from those instead of reading the rows (sec. 2.2, with the product's column
+  // groups as the groups)
+  const bool from_stats = g.topk_stats && hp.sample_topk == 0 && g.groups == 1 && topk_groups_supported(V, k) &&
+                          gemm_writes_stats(dt, M, V, d);
+  if (from_stats) { lo.stats = at<float>(p.d_stats); lo.stats_groups = (V + 31) / 32; }
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   if (hp.sample_topk > 0) {
     // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
@@ -543,8 +551,12 @@ int launch_step(int B) {
                                              0, step, T, s));
     return LSQ_OK;
   }
-  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
-                         at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+  if (from_stats)
+    TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), at<float>(p.score), at<int32_t>(p.fin),
+                                              M, V, k, hp.eos, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+  else
+    TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
+                                       at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
   // refine gathers the token histories (and the slab table, when the cache is refreshed through
   // it) by parent and advances the device-side step counter when its last workgroup finishes, so a
   // reorder kernel that follows reads t + 1 = the number of cache positions to move
@@ -1052,6 +1064,17 @@ int lsq_set_layernorm_fusion(int on) {
   return LSQ_OK;
 }
 
+int lsq_set_topk_statistics(int on) {
+  if ((on != 0) != g.topk_stats) {   // captured steps hold the other variant's launches
+    if (g.stream) (void)hipStreamSynchronize(g.stream);
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
+  }
+  g.topk_stats = on != 0;
+  return LSQ_OK;
+}
+
 int lsq_set_attention_blocks(int max_rows) {
   if (max_rows < 0 || max_rows > (int)kBlockRowsMax) return fail(LSQ_E_ARG, "max_rows %d outside [0, %d]", max_rows, (int)kBlockRowsMax);
   if (max_rows != g.block_rows) {   // captured steps hold the other variant's launches
@@ -1416,6 +1439,26 @@ int lsq_k_beam_refine_table(const float* cand_score, const int32_t* cand_idx, fl
   KCHK(batch >= 0 && k >= 1 && k <= LSQ_MAX_BEAM && V >= k && T >= 1 && t >= 0 && t < T, "shape");
   KRUN(launch_beam_refine(cand_score, cand_idx, score, tokens, len, finished, parent, cap, active, batch, k, V, T, t,
                           nullptr, eos, slab, (hipStream_t)stream));
+}
+
+int lsq_k_gemm_logits(const void* A, const void* B, void* C, float* stats, int M, int N, int K, void* stream) {
+  KCHK(A && B && C && stats, "null pointer");
+  KCHK(M >= 0 && N >= 1 && K >= 1, "shape");
+  KCHK(M == 0 || gemm_writes_stats(DT_F16, M, N, K), "no kernel with group statistics for this shape");
+  GemmOut o = plain_out(C, N);
+  o.f32_out = 1;
+  o.stats = stats;
+  o.stats_groups = (N + 31) / 32;
+  KRUN(launch_gemm(DT_F16, A, B, nullptr, o, M, N, K, 0, (hipStream_t)stream));
+}
+
+int lsq_k_gemm_logits_supported(int M, int N, int K) { return gemm_writes_stats(DT_F16, M, N, K) ? 1 : 0; }
+
+int lsq_k_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* finished, int M,
+                          int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream) {
+  KCHK(logits && stats && score && finished && out_score && out_idx, "null pointer");
+  KCHK(M >= 0 && topk_groups_supported(V, k), "V in [1, 65536], k in [1, beam limit]");
+  KRUN(launch_row_topk_groups(logits, stats, score, finished, M, V, k, eos, out_score, out_idx, (hipStream_t)stream));
 }
 
 int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,

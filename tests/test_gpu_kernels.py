@@ -522,6 +522,80 @@ def test_row_topk(env, M, V, k, case):
     np.testing.assert_allclose(got_s[both], ref_s[both], rtol=1e-5, atol=1e-5)
 
 
+@pytest.mark.parametrize("M,N,K", [(4, 1000, 64), (33, 32000, 512), (64, 5000, 1024), (8, 37, 16), (65, 32000, 1024),
+                                   (512, 32000, 1024), (130, 26000, 64), (300, 50257, 768 - 768 % 64), (1, 32, 16)])
+def test_logit_product_group_statistics(env, M, N, K):
+    """The logit product's (largest, sum of exponentials) per row and 32-column group, against numpy on the logits
+    the same launch wrote (which are checked against the float64 product)."""
+    lsq, torch = env
+    assert lsq.k_gemm_logits_supported(M, N, K)
+    rng = np.random.default_rng(M + N + K)
+    A, B = _h(rng.standard_normal((M, K))), _h(rng.standard_normal((N, K)) * 0.2)
+    G = (N + 31) // 32
+    C = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    st = torch.full((M, G, 2), 7.0, dtype=torch.float32, device="cuda")
+    lsq.k_gemm_logits(_dev(torch, A, torch.float16), _dev(torch, B, torch.float16), C, st)
+    got, gst = C.cpu().numpy(), st.cpu().numpy()
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6 * (np.abs(A) @ np.abs(B).T).max())
+    pad = np.full((M, G * 32), -np.inf)
+    pad[:, :N] = got
+    grp = pad.reshape(M, G, 32)
+    gmax = grp.max(-1)
+    assert np.array_equal(gst[..., 0], gmax.astype(np.float32))              # the stored logits' own maxima, bit for bit
+    np.testing.assert_allclose(gst[..., 1], np.exp(grp - gmax[..., None]).sum(-1), rtol=2e-6)
+
+
+@pytest.mark.parametrize("M,V,k", [(8, 1000, 4), (5, 12, 3), (33, 32000, 4), (6, 50257, 8), (4, 8192, 1), (3, 8200, 5),
+                                   (2, 65536, 4), (7, 2048, 4), (9, 5, 5), (130, 32000, 4), (3, 33, 2)])
+@pytest.mark.parametrize("case", ["random", "ties", "all_equal", "dead_and_finished", "one_group_holds_all"])
+def test_row_topk_from_group_statistics(env, M, V, k, case):
+    """The retrieve kernel that works from the logit product's group statistics: the same candidates as the kernel
+    that reads the whole row, and the oracle's."""
+    lsq, torch = env
+    rng = np.random.default_rng(M + V + k)
+    logits = (rng.standard_normal((M, V)) * 0.7).astype(np.float32)
+    score = -(rng.random(M) * 50).astype(np.float32)
+    fin = np.zeros(M, np.int32)
+    if case == "ties":
+        logits = np.round(logits * 2) / 2
+    elif case == "all_equal":
+        logits[:] = 0.125                              # every group reaches the threshold: the exact fallback
+    elif case == "dead_and_finished":
+        score[::2] = -np.inf
+        fin[1::3] = 1
+    elif case == "one_group_holds_all":
+        at = (V // 2) // 32 * 32
+        logits[:, at:at + min(32, V - at)] += 9.0      # the k best of every row sit in one group
+    eos = 2
+    G = (V + 31) // 32
+    pad = np.full((M, G * 32), -np.inf, np.float32)
+    pad[:, :V] = logits
+    grp = pad.reshape(M, G, 32)
+    gmax = grp.max(-1)
+    stats = np.stack([gmax, np.exp(grp - gmax[..., None]).sum(-1)], axis=-1).astype(np.float32)
+    dl, ds, df = _dev(torch, logits), _dev(torch, score), _dev(torch, fin)
+    os_ = torch.zeros(M, k, dtype=torch.float32, device="cuda")
+    oi = torch.zeros(M, k, dtype=torch.int32, device="cuda")
+    lsq.k_row_topk_groups(dl, _dev(torch, stats), ds, df, k, eos, os_, oi)
+    os2 = torch.zeros(M, k, dtype=torch.float32, device="cuda")
+    oi2 = torch.zeros(M, k, dtype=torch.int32, device="cuda")
+    lsq.k_row_topk(dl, ds, df, k, eos, os2, oi2)
+    got_s, got_i = os_.cpu().numpy(), oi.cpu().numpy()
+    ref_s, ref_i = _oracle_row_topk(logits, score, fin, k, eos)
+    if case in ("random", "one_group_holds_all"):
+        c = np.sort(-(score[:, None] + O.log_softmax(logits.astype(np.float64))), axis=1)[:, :k + 1]
+        clear = (np.diff(c, axis=1) > 1e-4).all(axis=1) | ~np.isfinite(c).all(axis=1)
+        assert clear.mean() > 0.5
+        assert np.array_equal(got_i[clear], ref_i[clear]) and np.array_equal(got_i[clear], oi2.cpu().numpy()[clear])
+    else:
+        assert np.array_equal(got_i, ref_i) and np.array_equal(got_i, oi2.cpu().numpy())
+    both = np.isfinite(ref_s)
+    assert np.array_equal(np.isfinite(got_s), both)
+    np.testing.assert_allclose(got_s[both], ref_s[both], rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose(got_s[both], os2.cpu().numpy()[both], rtol=2e-6, atol=2e-6)
+
+
 def _state(rng, B, k, V, T, t, eos, finished_frac):
     M = B * k
     tokens = rng.integers(4, V, size=(M, T + 1)).astype(np.int32)
