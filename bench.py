@@ -109,6 +109,8 @@ def class_work(name, hp, B, k, t_mean, s_mean):
         return (0.0, M * (((V + 31) // 32) * 8 + k * 32 * 4 + k * 8))
     if name == "beam_refine":
         return (0.0, M * max(k, hp.sample_topk) * 8)
+    if name == "retrieve_rerank":   # both stages in one launch, plus the next step's input rows (embedding in, row out)
+        return (0.0, M * (((V + 31) // 32) * 8 + k * 32 * 4) + 2 * M * d * es)
     if name == "cache_reorder":  # whole live cache gathered: read + write, all layers, K and V
         return (0.0, 2.0 * (2 * L * M * t_mean * d * es))
     return (0.0, 0.0)

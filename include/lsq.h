@@ -160,10 +160,12 @@ int lsq_set_attention_blocks(int max_rows);
 /* Plain beam search of float16 models: the logit product also leaves, for every row and every 32
  * consecutive tokens, the largest logit and the sum of exponentials, and the retrieve stage (sec.
  * 2.2) takes its threshold and the softmax normaliser from those and reads only the logits of the
- * groups that reach the threshold (lsq_k_gemm_logits, lsq_k_row_topk_groups).  Default on; 0: the
- * retrieve kernel reads every row in full.  Same tokens; scores equal to the rounding of the
- * normaliser.  May be called at any time. */
-int lsq_set_topk_statistics(int on);
+ * groups that reach the threshold (lsq_k_gemm_logits, lsq_k_row_topk_groups).
+ * mode 1 (default): so, with retrieve and re-rank in one launch; 2: so, as two launches; 0: the
+ * retrieve kernel reads every row in full.  Same tokens in all modes; scores of mode 0 differ
+ * from the others by the rounding of the normaliser, modes 1 and 2 are bit-identical.  May be
+ * called at any time. */
+int lsq_set_topk_statistics(int mode);
 
 /* Diverse beam search (named among the search methods of sec. 3.4; Vijayakumar et
  * al. 2016, Hamming diversity).  The beam is split into `groups` groups of

@@ -161,9 +161,10 @@ def lsq_set_attention_blocks(max_rows: int) -> None:
     _check(load_library().lsq_set_attention_blocks(int(max_rows)))
 
 
-def lsq_set_topk_statistics(on: bool) -> None:
-    """Retrieve stage from the logit product's group statistics (default on)."""
-    _check(load_library().lsq_set_topk_statistics(int(on)))
+def lsq_set_topk_statistics(mode: int) -> None:
+    """Retrieve stage from the logit product's group statistics: 1 (default) in one launch with the re-rank stage,
+    2 as a launch of its own, 0 off (every row read in full)."""
+    _check(load_library().lsq_set_topk_statistics(int(mode)))
 
 
 def lsq_set_canaries(on: bool) -> None:

@@ -287,20 +287,16 @@ row_topk_kernel(const T* __restrict__ logits,
 //     are ranked exactly by (cand descending, token ascending).
 // Rows where more than QMAX groups or CMAX tokens reach R (long runs of equal logits) fall back to k
 // exact rounds over the whole row.  Same output as row_topk_kernel (beam search, no groups, not raw).
+constexpr int kTopkGroupsQ = 64, kTopkGroupsC = 128;   // groups / tokens that may reach the threshold before the fallback
+
+// One row by one wavefront; ql, cs, ci: the wavefront's own LDS lists (kTopkGroupsQ, kTopkGroupsC entries); os, oi:
+// where the k pairs go (global memory or LDS).
 template <int GPL>
-__global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __restrict__ logits,
-                                                              const float* __restrict__ stats,
-                                                              const float* __restrict__ score,
-                                                              const int32_t* __restrict__ fin, int M, int V, int G,
-                                                              int k, int eos, float* __restrict__ out_score,
-                                                              int32_t* __restrict__ out_idx) {
-  constexpr int QMAX = 64, CMAX = 128;
-  __shared__ int ql[4][QMAX];
-  __shared__ float cs[4][CMAX];
-  __shared__ int ci[4][CMAX];
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + wave;
-  if (r >= M) return;
+__device__ __forceinline__ void topk_groups_row(const float* __restrict__ logits, const float* __restrict__ stats,
+                                                const float* __restrict__ score, const int32_t* __restrict__ fin,
+                                                int r, int V, int G, int k, int eos, float* os, int32_t* oi, int lane,
+                                                int* ql_w, float* cs_w, int* ci_w) {
+  constexpr int QMAX = kTopkGroupsQ, CMAX = kTopkGroupsC;
   const float bs = score[r];
   const int f = fin[r];
   // the row's statistics, requested before anything is decided
@@ -315,8 +311,6 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
       gm[q] = -INFINITY; gz[q] = 0.f;
     }
   }
-  float* os = out_score + (size_t)r * k;
-  int32_t* oi = out_idx + (size_t)r * k;
   if (f) {   // a finished hypothesis offers itself once
     if (lane < k) { os[lane] = lane == 0 ? bs : -INFINITY; oi[lane] = lane == 0 ? eos : -1; }
     return;
@@ -366,7 +360,7 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
     const unsigned long long mask = __ballot(in);
     if (in) {
       const int at = nq + __popcll(mask & ((1ull << lane) - 1ull));
-      if (at < QMAX) ql[wave][at] = q * 64 + lane;
+      if (at < QMAX) ql_w[at] = q * 64 + lane;
     }
     nq += __popcll(mask);
   }
@@ -377,13 +371,13 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
     // two groups per pass: lanes 0-31 one, lanes 32-63 the next
     for (int p0 = 0; p0 < nq && nc <= CMAX; p0 += 2) {
       const int gi = p0 + (lane >> 5);
-      const int v = gi < nq ? ql[wave][gi] * 32 + (lane & 31) : V;
+      const int v = gi < nq ? ql_w[gi] * 32 + (lane & 31) : V;
       const float c = v < V ? cand_of(row[v]) : -INFINITY;
       const bool in = v < V && c >= R;
       const unsigned long long mask = __ballot(in);
       if (in) {
         const int at = nc + __popcll(mask & ((1ull << lane) - 1ull));
-        if (at < CMAX) { cs[wave][at] = c; ci[wave][at] = v; }
+        if (at < CMAX) { cs_w[at] = c; ci_w[at] = v; }
       }
       nc += __popcll(mask);
     }
@@ -391,10 +385,10 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
   __builtin_amdgcn_wave_barrier();
   if (nq <= QMAX && nc <= CMAX) {
     for (int c = lane; c < nc; c += 64) {
-      const float sc = cs[wave][c];
-      const int v = ci[wave][c];
+      const float sc = cs_w[c];
+      const int v = ci_w[c];
       int rank = 0;
-      for (int o = 0; o < nc; ++o) rank += precedes(cs[wave][o], ci[wave][o], sc, v) ? 1 : 0;
+      for (int o = 0; o < nc; ++o) rank += precedes(cs_w[o], ci_w[o], sc, v) ? 1 : 0;
       if (rank < k) { os[rank] = sc; oi[rank] = v; }
     }
     if (lane >= nc && lane < k) { os[lane] = -INFINITY; oi[lane] = -1; }   // vocabulary smaller than k
@@ -424,6 +418,23 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
       pi = bi;
     }
   }
+}
+
+template <int GPL>
+__global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __restrict__ logits,
+                                                              const float* __restrict__ stats,
+                                                              const float* __restrict__ score,
+                                                              const int32_t* __restrict__ fin, int M, int V, int G,
+                                                              int k, int eos, float* __restrict__ out_score,
+                                                              int32_t* __restrict__ out_idx) {
+  __shared__ int ql[4][kTopkGroupsQ];
+  __shared__ float cs[4][kTopkGroupsC];
+  __shared__ int ci[4][kTopkGroupsC];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= M) return;
+  topk_groups_row<GPL>(logits, stats, score, fin, r, V, G, k, eos, out_score + (size_t)r * k, out_idx + (size_t)r * k, lane,
+                       ql[wave], cs[wave], ci[wave]);
 }
 
 bool topk_groups_supported(int V, int k) { return V >= 1 && V <= 65536 && k >= 1 && k <= LSQ_MAX_BEAM_; }
@@ -516,18 +527,30 @@ __device__ __forceinline__ void next_input_rows(const NextInput& nx, const int* 
 // One wavefront per sentence (per group of a sentence under diverse beam search: k is then the
 // group width, the group's rows start at beam slot goff of the sentence's k_all).  Lane c < k*k owns
 // survivor (beam c / k of the group, slot c % k).
-__global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict__ cand_score,
-                                                         const int32_t* __restrict__ cand_idx,
-                                                         float* __restrict__ score, int32_t* __restrict__ tokens,
-                                                         int32_t* __restrict__ len, int32_t* __restrict__ fin,
-                                                         int32_t* __restrict__ parent,
-                                                         const int32_t* __restrict__ cap,
-                                                         int32_t* __restrict__ active, int k, int V, int T1,
-                                                         int t_base, int32_t* __restrict__ step_state, int eos,
-                                                         int32_t* __restrict__ anc, SearchGroups gr, NextInput nx) {
-  __shared__ int sh_parent[LSQ_MAX_BEAM_], sh_tok[LSQ_MAX_BEAM_];
-  __shared__ int sh_unfinished, sh_taken;
-  const int b = blockIdx.x, lane = threadIdx.x;
+// ALONE: the wavefront is the whole workgroup (its barriers are the workgroup's); otherwise other wavefronts of the
+// workgroup have finished their part and this one orders its own LDS and memory traffic.
+template <bool ALONE>
+__device__ __forceinline__ void rerank_sync() {
+  if constexpr (ALONE) {
+    __syncthreads();
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  }
+}
+
+// cand_score / cand_idx: the sentence's k*k survivors at [(row - first row of the launch's unit) ...]: pointers to the
+// pairs of row `base` (global memory, or LDS when the retrieve stage ran in the same workgroup).
+template <bool ALONE>
+__device__ __forceinline__ void rerank_sentence(const float* cand_score_b, const int32_t* cand_idx_b, const float* plain_b,
+                                                float* __restrict__ score, int32_t* __restrict__ tokens,
+                                                int32_t* __restrict__ len, int32_t* __restrict__ fin,
+                                                int32_t* __restrict__ parent, const int32_t* __restrict__ cap,
+                                                int32_t* __restrict__ active, int k, int V, int T1, int t_base,
+                                                int32_t* __restrict__ step_state, int eos, int32_t* __restrict__ anc,
+                                                const SearchGroups& gr, const NextInput& nx, int b, int lane,
+                                                int* sh_parent, int* sh_tok, int& sh_unfinished, int& sh_taken) {
   const int t = t_base + (step_state ? step_state[0] : 0);
   const int kk = k * k;
   const int k_all = gr.k_all > 1 ? gr.k_all : k;           // rows of a sentence (k_all == 1: no groups)
@@ -543,9 +566,9 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   // histories (both discarded below), so every load can leave before the step counter has arrived.
   const int cl = min(lane, kk - 1);
   const int j = cl / k;
-  float s = cand_score[(size_t)base * k + cl];
-  float plain = gr.out_plain ? gr.out_plain[(size_t)base * k + cl] : s;
-  int tok = cand_idx[(size_t)base * k + cl];
+  float s = cand_score_b[cl];
+  float plain = plain_b ? plain_b[cl] : s;
+  int tok = cand_idx_b[cl];
   const int plen = len[base + j], pfin = fin[base + j];
   const int cap_b = cap[b];
   int p = lane;
@@ -573,7 +596,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   }
   const bool win = flat >= 0 && rank < k;
   if (win) sh_parent[rank] = j;
-  __syncthreads();
+  rerank_sync<ALONE>();
   // token histories, positions 0..t, and the table that says which slab holds position p of each
   // history (cache refreshing without moving the cache; position t+1 is written by the row
   // itself): every lane has all k beams of a position, then writes those that change
@@ -594,7 +617,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     if (p <= t && p < T1) fetch();   // a history longer than 64 positions: one more trip per 64
   }
   if (anc && lane < k && t + 1 < T1) anc[(size_t)(base + lane) * T1 + t + 1] = gr.goff + lane;
-  __syncthreads();
+  rerank_sync<ALONE>();
   if (win) {
     const int row = base + rank;
     int nlen = plen, nfin = pfin;
@@ -615,7 +638,7 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
     parent[row] = gr.goff + j;
     if (!nfin) sh_unfinished = 1;
   }
-  __syncthreads();
+  rerank_sync<ALONE>();
   // The next step's decoder input of these rows (one launch less per step).  A row that no candidate won
   // (fewer live candidates than beams) embeds nothing: it is dead and stays so.
   if (nx.E && t + 1 < T1 - 1) {
@@ -642,6 +665,50 @@ __global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict
   }
 }
 
+__global__ void __launch_bounds__(64) beam_refine_kernel(const float* __restrict__ cand_score,
+                                                         const int32_t* __restrict__ cand_idx,
+                                                         float* __restrict__ score, int32_t* __restrict__ tokens,
+                                                         int32_t* __restrict__ len, int32_t* __restrict__ fin,
+                                                         int32_t* __restrict__ parent,
+                                                         const int32_t* __restrict__ cap,
+                                                         int32_t* __restrict__ active, int k, int V, int T1,
+                                                         int t_base, int32_t* __restrict__ step_state, int eos,
+                                                         int32_t* __restrict__ anc, SearchGroups gr, NextInput nx) {
+  __shared__ int sh_parent[LSQ_MAX_BEAM_], sh_tok[LSQ_MAX_BEAM_];
+  __shared__ int sh_unfinished, sh_taken;
+  const int b = blockIdx.x;
+  const int k_all = gr.k_all > 1 ? gr.k_all : k;
+  const size_t first = ((size_t)b * k_all + gr.goff) * k;   // the pairs of the unit's first row
+  rerank_sentence<true>(cand_score + first, cand_idx + first, gr.out_plain ? gr.out_plain + first : nullptr, score, tokens, len,
+                        fin, parent, cap, active, k, V, T1, t_base, step_state, eos, anc, gr, nx, b, (int)threadIdx.x,
+                        sh_parent, sh_tok, sh_unfinished, sh_taken);
+}
+
+// Retrieve and re-rank in one launch (plain beam search from the logit product's group statistics): a workgroup
+// per sentence, wavefront w retrieves row w's k best into LDS, the first wavefront then re-ranks the sentence.
+template <int GPL>
+__global__ void __launch_bounds__(64 * LSQ_MAX_BEAM_) retrieve_rerank_kernel(
+    const float* __restrict__ logits, const float* __restrict__ stats, float* __restrict__ score, int32_t* __restrict__ tokens,
+    int32_t* __restrict__ len, int32_t* __restrict__ fin, int32_t* __restrict__ parent, const int32_t* __restrict__ cap,
+    int32_t* __restrict__ active, int k, int V, int G, int T1, int32_t* __restrict__ step_state, int eos,
+    int32_t* __restrict__ anc, NextInput nx) {
+  __shared__ int ql[LSQ_MAX_BEAM_][kTopkGroupsQ];
+  __shared__ float cs[LSQ_MAX_BEAM_][kTopkGroupsC];
+  __shared__ int ci[LSQ_MAX_BEAM_][kTopkGroupsC];
+  __shared__ float cand_s[LSQ_MAX_BEAM_ * LSQ_MAX_BEAM_];
+  __shared__ int cand_i[LSQ_MAX_BEAM_ * LSQ_MAX_BEAM_];
+  __shared__ int sh_parent[LSQ_MAX_BEAM_], sh_tok[LSQ_MAX_BEAM_];
+  __shared__ int sh_unfinished, sh_taken;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int b = blockIdx.x;
+  topk_groups_row<GPL>(logits, stats, score, fin, b * k + wave, V, G, k, eos, cand_s + wave * k, cand_i + wave * k, lane,
+                       ql[wave], cs[wave], ci[wave]);
+  __syncthreads();   // blockDim.x = 64 k: every wavefront has a row
+  if (wave != 0) return;
+  rerank_sentence<false>(cand_s, cand_i, nullptr, score, tokens, len, fin, parent, cap, active, k, V, T1, 0, step_state, eos,
+                         anc, one_group(), nx, b, lane, sh_parent, sh_tok, sh_unfinished, sh_taken);
+}
+
 hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens,
                               int32_t* len, int32_t* fin, int32_t* parent, const int32_t* cap,
                               int32_t* active, int batch, int k, int V, int T, int t_base, int32_t* step_state,
@@ -652,6 +719,24 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
     return hipErrorInvalidValue;
   beam_refine_kernel<<<batch, 64, 0, s>>>(cand_score, cand_idx, score, tokens, len, fin, parent, cap, active,
                                           k, V, T + 1, t_base, step_state, eos, anc, gr, nx);
+  return hipGetLastError();
+}
+
+hipError_t launch_retrieve_rerank(const float* logits, const float* stats, float* score, int32_t* tokens, int32_t* len,
+                                  int32_t* fin, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
+                                  int V, int T, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
+                                  const NextInput& nx) {
+  if (batch <= 0) return hipSuccess;
+  if (!topk_groups_supported(V, k) || !stats || !step_state) return hipErrorInvalidValue;
+  const int G = (V + 31) / 32;
+  dim3 g(batch), b(64 * k);
+#define LSQ_RR(GPL_)                                                                                                     \
+  retrieve_rerank_kernel<GPL_><<<g, b, 0, s>>>(logits, stats, score, tokens, len, fin, parent, cap, active, k, V, G, T + 1, \
+                                               step_state, eos, anc, nx)
+  if (G <= 64 * 4) LSQ_RR(4);
+  else if (G <= 64 * 16) LSQ_RR(16);
+  else LSQ_RR(32);
+#undef LSQ_RR
   return hipGetLastError();
 }
 

@@ -159,7 +159,7 @@ struct SearchGroups {
   int last;   // the last group of the step: counts active sentences, advances the step, clears pen_n
 };
 // no groups: every row is its own unit for the retrieve kernel, a sentence's k rows one unit for the re-rank kernel
-inline SearchGroups one_group() { return SearchGroups{1, 1, 0, nullptr, nullptr, 0, 0.f, nullptr, 1}; }
+__host__ __device__ inline SearchGroups one_group() { return SearchGroups{1, 1, 0, nullptr, nullptr, 0, 0.f, nullptr, 1}; }
 
 // raw != 0: rank the logits themselves (score and fin are ignored, may be null).  M counts the rows
 // this launch works on (sentences * groups.kg).
@@ -200,6 +200,11 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
                               int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
                               const SearchGroups& groups = one_group(), const NextInput& next = no_next_input());
+// launch_row_topk_groups and launch_beam_refine (no groups, device-side step counter) in one launch
+hipError_t launch_retrieve_rerank(const float* logits, const float* stats, float* score, int32_t* tokens, int32_t* len,
+                                  int32_t* fin, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
+                                  int V, int T, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
+                                  const NextInput& next = no_next_input());
 // npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
                                 int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,

@@ -40,12 +40,12 @@ int fail(int code, const char* fmt, ...) {
 // per kernel class.  Events come from a host-side pool that only grows.
 enum ProfClass {
   PC_EMBED, PC_GEMM_QKV, PC_ATTN_SELF, PC_GEMM_DD, PC_LAYERNORM, PC_ATTN_CROSS, PC_GEMM_FFN1, PC_GEMM_FFN2,
-  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_SELF_BLOCK, PC_CROSS_BLOCK, PC_ROW_TOPK_GROUPS, PC_COUNT
+  PC_GEMM_VOCAB, PC_ROW_TOPK, PC_REFINE, PC_REORDER, PC_GEMM_OUT, PC_ATTN_CROSS_Q, PC_SELF_BLOCK, PC_CROSS_BLOCK, PC_ROW_TOPK_GROUPS, PC_RETRIEVE_RERANK, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"embed", "gemm_qkv", "attn_self", "gemm_dxd", "add_layernorm",
                                           "attn_cross", "gemm_ffn1", "gemm_ffn2", "gemm_vocab", "row_topk",
                                           "beam_refine", "cache_reorder", "gemm_out", "attn_cross_q", "self_block",
-                                          "cross_block", "row_topk_groups"};
+                                          "cross_block", "row_topk_groups", "retrieve_rerank"};
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;   // pairs: [2i] start, [2i+1] stop
@@ -311,6 +311,7 @@ struct Ctx {
   bool fuse_ln = true;    // few rows alive: LayerNorm inside the product that consumes it
   int block_rows = 64;    // ... and whole attention sublayers in one launch up to this many rows
   bool topk_stats = true; // beam search: retrieve from the logit product's group statistics
+  bool merge_rerank = true;   // ... and in the same launch as the re-rank stage
   int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
@@ -546,6 +547,17 @@ int launch_step(int B) {
                                           at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, kg, V,
                                           T, 0, step, hp.eos, anc, s, gr, next));
     }
+    if (!anc)
+      TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
+                                             0, step, T, s));
+    return LSQ_OK;
+  }
+  if (from_stats && g.merge_rerank) {
+    // retrieve and re-rank in one launch
+    TIMED(PC_RETRIEVE_RERANK, launch_retrieve_rerank((const float*)logits, at<float>(p.d_stats), at<float>(p.score),
+                                                     at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
+                                                     at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T,
+                                                     step, hp.eos, anc, s, next));
     if (!anc)
       TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
                                              0, step, T, s));
@@ -1064,14 +1076,17 @@ int lsq_set_layernorm_fusion(int on) {
   return LSQ_OK;
 }
 
-int lsq_set_topk_statistics(int on) {
-  if ((on != 0) != g.topk_stats) {   // captured steps hold the other variant's launches
+int lsq_set_topk_statistics(int mode) {
+  if (mode < 0 || mode > 2) return fail(LSQ_E_ARG, "mode %d outside [0, 2]", mode);
+  const bool stats = mode != 0, merge = mode == 1;
+  if (stats != g.topk_stats || merge != g.merge_rerank) {   // captured steps hold the other variant's launches
     if (g.stream) (void)hipStreamSynchronize(g.stream);
     for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
     g.graphs.clear();
     g.graph_hidden_in_alt.clear();
   }
-  g.topk_stats = on != 0;
+  g.topk_stats = stats;
+  g.merge_rerank = merge;
   return LSQ_OK;
 }
 

@@ -215,23 +215,26 @@ def test_layernorm_fusion_agrees_with_standalone_kernel(lsq, n_dec):
 def test_retrieve_from_group_statistics_agrees_with_full_rows(lsq, vocab, beam):
     """Retrieve stage from the logit product's group statistics (default) against the kernel that reads every
     row: the same tokens and lengths, scores equal to the rounding of the normaliser; a batch that shrinks from
-    more than 64 rows (large-tile product) to a few (skinny product) on its way."""
+    more than 64 rows (large-tile product) to a few (skinny product) on its way; retrieve and re-rank as one launch
+    (default) and as two."""
     hp = S.HParams(n_enc=1, n_dec=2, d_model=128, n_heads=2, d_ffn=256, vocab=vocab, max_pos=64, dtype=1, cap_extra=9)
     lens = [2 + (7 * i) % 19 for i in range(23)]
     w = S.custom(hp, lens, beam=beam, max_len=29, std=0.05)
     blob = w.blob(ln_jitter=0.1)
     out = {}
     try:
-        for on in (False, True):
-            lsq.lsq_set_topk_statistics(on)
+        for mode in (0, 2, 1):
+            lsq.lsq_set_topk_statistics(mode)
             with lsq.Engine(blob, 23, beam, 29) as eng:
-                out[on] = eng.translate(w.src_ids, w.src_lens, sync_every=3)
-                if on:
+                out[mode] = eng.translate(w.src_ids, w.src_lens, sync_every=3)
+                if mode:
                     res = lockstep(lsq, eng, blob, w)
                     _final_check(lsq, eng, blob, w, res)
     finally:
-        lsq.lsq_set_topk_statistics(True)
-    (ids0, lens0, sc0), (ids1, lens1, sc1) = out[False], out[True]
+        lsq.lsq_set_topk_statistics(1)
+    for a, b in zip(out[1], out[2]):
+        assert np.array_equal(a, b)                      # one launch or two: the same bits
+    (ids0, lens0, sc0), (ids1, lens1, sc1) = out[0], out[1]
     same = (ids0 == ids1).all(axis=-1)
     assert same.mean() >= 0.95 and np.array_equal(lens0[same], lens1[same])   # a near-tie may flip on the last bit
     np.testing.assert_allclose(sc0[same], sc1[same], rtol=0, atol=2e-5)
