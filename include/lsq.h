@@ -394,12 +394,14 @@ int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int3
 int lsq_k_gemm_logits(const void* A, const void* B, void* C, float* stats, int M, int N, int K, void* stream);
 int lsq_k_gemm_logits_supported(int M, int N, int K);
 
-/* lsq_k_row_topk (beam search: dtype float32 logits, raw == 0) computed from the statistics
- * above: the normaliser from the G pairs, the threshold R = k-th largest group maximum (as a
- * candidate score), and only the logits of groups that reach R are read.  Same outputs as
- * lsq_k_row_topk up to the rounding of the normaliser; k at most the beam limit. */
+/* lsq_k_row_topk on float32 logits computed from the statistics above: the normaliser from the G
+ * pairs, the threshold R = k-th largest group maximum (as a candidate score), and only the
+ * logits of groups that reach R are read.  raw == 0: beam search, k at most the beam limit, same
+ * outputs as lsq_k_row_topk up to the rounding of the normaliser.  raw != 0 (sampling): the k <=
+ * 32 largest logits themselves, score and finished unused (may be NULL). */
 int lsq_k_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* finished,
-                          int M, int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream);
+                          int M, int V, int k, int eos, int raw, float* out_score, int32_t* out_idx,
+                          void* stream);
 
 /* Re-rank stage: per sentence the k best of its k*k row candidates by
  * (score descending, beam*V+token ascending); updates score, tokens [M,T+1],

@@ -61,7 +61,7 @@ def load_library() -> C.CDLL:
         "lsq_k_cross_attention_q": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp],
         "lsq_k_gemm_logits": [vp, vp, vp, vp, i32, i32, i32, vp],
         "lsq_k_gemm_logits_supported": [i32, i32, i32],
-        "lsq_k_row_topk_groups": [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp],
+        "lsq_k_row_topk_groups": [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp],
         "lsq_k_self_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32,
                                        i32, i32, vp],
         "lsq_k_cross_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32,
@@ -359,9 +359,9 @@ def k_gemm_logits_supported(M: int, N: int, K: int) -> bool:
     return bool(load_library().lsq_k_gemm_logits_supported(M, N, K))
 
 
-def k_row_topk_groups(logits, stats, score, finished, k: int, eos: int, out_score, out_idx) -> None:
+def k_row_topk_groups(logits, stats, score, finished, k: int, eos: int, out_score, out_idx, raw: bool = False) -> None:
     M, V = logits.shape
-    _check(load_library().lsq_k_row_topk_groups(_p(logits), _p(stats), _p(score), _p(finished), M, V, k, eos,
+    _check(load_library().lsq_k_row_topk_groups(_p(logits), _p(stats), _p(score), _p(finished), M, V, k, eos, int(raw),
                                                 _p(out_score), _p(out_idx), _stream()))
 
 

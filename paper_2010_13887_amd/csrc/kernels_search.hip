@@ -295,10 +295,11 @@ template <int GPL>
 __device__ __forceinline__ void topk_groups_row(const float* __restrict__ logits, const float* __restrict__ stats,
                                                 const float* __restrict__ score, const int32_t* __restrict__ fin,
                                                 int r, int V, int G, int k, int eos, float* os, int32_t* oi, int lane,
-                                                int* ql_w, float* cs_w, int* ci_w) {
+                                                int* ql_w, float* cs_w, int* ci_w, int raw = 0) {
   constexpr int QMAX = kTopkGroupsQ, CMAX = kTopkGroupsC;
-  const float bs = score[r];
-  const int f = fin[r];
+  // raw (sampling): the k largest logits themselves, no score, no normaliser, no finished rows
+  const float bs = raw ? 0.f : score[r];
+  const int f = raw ? 0 : fin[r];
   // the row's statistics, requested before anything is decided
   float gm[GPL], gz[GPL];
 #pragma unroll
@@ -328,30 +329,23 @@ __device__ __forceinline__ void topk_groups_row(const float* __restrict__ logits
   for (int q = 0; q < GPL; ++q) zt += gz[q] * __expf(gm[q] - m);   // a group that does not exist: 0 * exp(-inf) = 0
   zt = wave_sum(zt);
   const float logz = logf(zt);
-  auto cand_of = [&](float x) { return __fadd_rn(bs, __fsub_rn(__fsub_rn(x, m), logz)); };
-  float cg[GPL], work[GPL];
+  auto cand_of = [&](float x) { return raw ? x : __fadd_rn(bs, __fsub_rn(__fsub_rn(x, m), logz)); };
+  float cg[GPL];
 #pragma unroll
-  for (int q = 0; q < GPL; ++q) {
-    cg[q] = (q * 64 + lane < G) ? cand_of(gm[q]) : -INFINITY;
-    work[q] = cg[q];
+  for (int q = 0; q < GPL; ++q) cg[q] = (q * 64 + lane < G) ? cand_of(gm[q]) : -INFINITY;
+  // R: every lane's best group value is the value of a distinct token; the k-th largest of those 64 is
+  // reached by k tokens, so it is a valid threshold (at most the k-th largest group value, and close to it
+  // when there are many more groups than k).  Ranked by (value, lane): 64 broadcasts, whatever k.
+  float lm = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < GPL; ++q) lm = fmaxf(lm, cg[q]);
+  int lrank = 0;
+#pragma unroll
+  for (int c = 0; c < 64; ++c) {
+    const float o = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lm), c));
+    lrank += (o > lm || (o == lm && c < lane)) ? 1 : 0;
   }
-  // R: the k-th largest group value, counted with multiplicity (fewer than k groups: -inf, every token passes)
-  float R = INFINITY;
-  for (int round = 0; round < k; ++round) {
-    float lm = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < GPL; ++q) lm = fmaxf(lm, work[q]);
-    const float wm = wave_max(lm);
-    R = wm;
-    if (wm == -INFINITY) break;
-    const unsigned long long holders = __ballot(lm == wm);
-    if (lane == __builtin_ctzll(holders)) {   // one instance leaves, in one lane
-      bool gone = false;
-#pragma unroll
-      for (int q = 0; q < GPL; ++q)
-        if (!gone && work[q] == wm) { work[q] = -INFINITY; gone = true; }
-    }
-  }
+  const float R = wave_max(lrank == k - 1 ? lm : -INFINITY);   // fewer than k groups: -inf, every token passes
   // the groups that reach R
   int nq = 0;
 #pragma unroll
@@ -368,18 +362,28 @@ __device__ __forceinline__ void topk_groups_row(const float* __restrict__ logits
   const float* row = logits + (size_t)r * V;
   int nc = 0;
   if (nq <= QMAX) {
-    // two groups per pass: lanes 0-31 one, lanes 32-63 the next
-    for (int p0 = 0; p0 < nq && nc <= CMAX; p0 += 2) {
-      const int gi = p0 + (lane >> 5);
-      const int v = gi < nq ? ql_w[gi] * 32 + (lane & 31) : V;
-      const float c = v < V ? cand_of(row[v]) : -INFINITY;
-      const bool in = v < V && c >= R;
-      const unsigned long long mask = __ballot(in);
-      if (in) {
-        const int at = nc + __popcll(mask & ((1ull << lane) - 1ull));
-        if (at < CMAX) { cs_w[at] = c; ci_w[at] = v; }
+    // two groups per pass (lanes 0-31 one, lanes 32-63 the next), the logits of PB passes requested together
+    constexpr int PB = 8;
+    for (int p0 = 0; p0 < nq && nc <= CMAX; p0 += 2 * PB) {
+      float xs[PB];
+      int vs[PB];
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const int gi = p0 + 2 * u + (lane >> 5);
+        vs[u] = gi < nq ? ql_w[min(gi, QMAX - 1)] * 32 + (lane & 31) : V;
+        xs[u] = row[min(vs[u], V - 1)];
       }
-      nc += __popcll(mask);
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const float c = cand_of(xs[u]);
+        const bool in = vs[u] < V && c >= R;
+        const unsigned long long mask = __ballot(in);
+        if (in) {
+          const int at = nc + __popcll(mask & ((1ull << lane) - 1ull));
+          if (at < CMAX) { cs_w[at] = c; ci_w[at] = vs[u]; }
+        }
+        nc += __popcll(mask);
+      }
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -426,7 +430,7 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
                                                               const float* __restrict__ score,
                                                               const int32_t* __restrict__ fin, int M, int V, int G,
                                                               int k, int eos, float* __restrict__ out_score,
-                                                              int32_t* __restrict__ out_idx) {
+                                                              int32_t* __restrict__ out_idx, int raw) {
   __shared__ int ql[4][kTopkGroupsQ];
   __shared__ float cs[4][kTopkGroupsC];
   __shared__ int ci[4][kTopkGroupsC];
@@ -434,20 +438,23 @@ __global__ void __launch_bounds__(256) row_topk_groups_kernel(const float* __res
   const int r = blockIdx.x * 4 + wave;
   if (r >= M) return;
   topk_groups_row<GPL>(logits, stats, score, fin, r, V, G, k, eos, out_score + (size_t)r * k, out_idx + (size_t)r * k, lane,
-                       ql[wave], cs[wave], ci[wave]);
+                       ql[wave], cs[wave], ci[wave], raw);
 }
 
-bool topk_groups_supported(int V, int k) { return V >= 1 && V <= 65536 && k >= 1 && k <= LSQ_MAX_BEAM_; }
+// beam search: k up to the beam limit; raw (sampling): up to the top-k limit (k rounds find the threshold)
+bool topk_groups_supported(int V, int k, int raw) {
+  return V >= 1 && V <= 65536 && k >= 1 && k <= (raw ? LSQ_MAX_TOPK_ : LSQ_MAX_BEAM_) && k <= kTopkGroupsQ;
+}
 
 hipError_t launch_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* fin, int M,
-                                  int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s) {
+                                  int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  if (!topk_groups_supported(V, k) || !stats) return hipErrorInvalidValue;
+  if (!topk_groups_supported(V, k, raw) || !stats || (!raw && (!score || !fin))) return hipErrorInvalidValue;
   const int G = (V + 31) / 32;
   dim3 g((M + 3) / 4), b(256);
-  if (G <= 64 * 4) row_topk_groups_kernel<4><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
-  else if (G <= 64 * 16) row_topk_groups_kernel<16><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
-  else row_topk_groups_kernel<32><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx);
+  if (G <= 64 * 4) row_topk_groups_kernel<4><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx, raw);
+  else if (G <= 64 * 16) row_topk_groups_kernel<16><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx, raw);
+  else row_topk_groups_kernel<32><<<g, b, 0, s>>>(logits, stats, score, fin, M, V, G, k, eos, out_score, out_idx, raw);
   return hipGetLastError();
 }
 
@@ -727,7 +734,7 @@ hipError_t launch_retrieve_rerank(const float* logits, const float* stats, float
                                   int V, int T, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
                                   const NextInput& nx) {
   if (batch <= 0) return hipSuccess;
-  if (!topk_groups_supported(V, k) || !stats || !step_state) return hipErrorInvalidValue;
+  if (!topk_groups_supported(V, k, 0) || !stats || !step_state) return hipErrorInvalidValue;
   const int G = (V + 31) / 32;
   dim3 g(batch), b(64 * k);
 #define LSQ_RR(GPL_)                                                                                                     \

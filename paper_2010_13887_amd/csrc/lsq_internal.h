@@ -180,11 +180,11 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
 // [batch*k, T+1] is gathered by parent like the token histories, and entry t+1 of every row is set
 // to the row's own beam index.
 // groups given (kg < k_all): k is the group width kg, candidates are [rows, kg]; see SearchGroups.
-// row_topk for plain beam search from the logit product's group statistics (GemmOut::stats): same output, the
-// logits of only the groups that can hold a top-k token are read
-bool topk_groups_supported(int V, int k);
+// row_topk (plain beam search, or raw: the k largest logits for sampling) from the logit product's group
+// statistics (GemmOut::stats): same output, the logits of only the groups that can hold a top-k token are read
+bool topk_groups_supported(int V, int k, int raw);
 hipError_t launch_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* fin, int M,
-                                  int V, int k, int eos, float* out_score, int32_t* out_idx, hipStream_t s);
+                                  int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, hipStream_t s);
 // The next step's decoder input, left behind by the kernel that settles the step's tokens:
 // x[row] = E[last token of row] * scale + pe[t + 1] (E == nullptr: not asked for).
 struct NextInput {

@@ -519,14 +519,20 @@ int launch_step(int B) {
   // Plain beam search: the logit product also leaves (largest, sum of exponentials) of every 32 logits of a row,
   // and the retrieve kernel works from those instead of reading the rows (sec. 2.2, with the product's column
   // groups as the groups)
-  const bool from_stats = g.topk_stats && hp.sample_topk == 0 && g.groups == 1 && topk_groups_supported(V, k) &&
-                          gemm_writes_stats(dt, M, V, d);
+  const bool sampling = hp.sample_topk > 0;
+  const bool from_stats = g.topk_stats && g.groups == 1 && gemm_writes_stats(dt, M, V, d) &&
+                          topk_groups_supported(V, sampling ? hp.sample_topk : k, sampling ? 1 : 0);
   if (from_stats) { lo.stats = at<float>(p.d_stats); lo.stats_groups = (V + 31) / 32; }
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   if (hp.sample_topk > 0) {
     // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
-    TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, hp.sample_topk, hp.eos, 1,
-                                       at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+    if (from_stats)
+      TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), nullptr, nullptr, M, V,
+                                                       hp.sample_topk, hp.eos, 1, at<float>(p.cand_score),
+                                                       at<int32_t>(p.cand_idx), s));
+    else
+      TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, hp.sample_topk, hp.eos, 1,
+                                         at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
     TIMED(PC_REFINE, launch_sample(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<int32_t>(p.tokens),
                                    at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M,
                                    hp.sample_topk, hp.topp, T, (unsigned long long)hp.seed, 0, s, at<int32_t>(p.fin),
@@ -565,7 +571,7 @@ int launch_step(int B) {
   }
   if (from_stats)
     TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), at<float>(p.score), at<int32_t>(p.fin),
-                                              M, V, k, hp.eos, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+                                              M, V, k, hp.eos, 0, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
   else
     TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, at<float>(p.score), at<int32_t>(p.fin), M, V, k, hp.eos, 0,
                                        at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
@@ -615,9 +621,16 @@ int launch_step_gpt(int B) {
   }
   GemmOut lo = plain_out(logits, V);
   lo.f32_out = 1;
+  // the k largest logits of a row from the product's group statistics (as under beam search, without a normaliser)
+  const bool from_stats = g.topk_stats && gemm_writes_stats(dt, M, V, d) && topk_groups_supported(V, ks, 1);
+  if (from_stats) { lo.stats = at<float>(p.d_stats); lo.stats_groups = (V + 31) / 32; }
   TIMED(PC_GEMM_VOCAB, launch_gemm(dt, y, g.E, nullptr, lo, M, V, d, 0, s));
-  TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, ks, hp.eos, 1, at<float>(p.cand_score),
-                                     at<int32_t>(p.cand_idx), s));
+  if (from_stats)
+    TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), nullptr, nullptr, M, V, ks,
+                                                     hp.eos, 1, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
+  else
+    TIMED(PC_ROW_TOPK, launch_row_topk(DT_F32, logits, nullptr, nullptr, M, V, ks, hp.eos, 1, at<float>(p.cand_score),
+                                       at<int32_t>(p.cand_idx), s));
   TIMED(PC_REFINE, launch_sample(at<float>(p.cand_score), at<int32_t>(p.cand_idx), at<int32_t>(p.tokens),
                                  at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, ks, hp.topp, T,
                                  (unsigned long long)hp.seed, hp.cap_extra, s));
@@ -1470,10 +1483,10 @@ int lsq_k_gemm_logits(const void* A, const void* B, void* C, float* stats, int M
 int lsq_k_gemm_logits_supported(int M, int N, int K) { return gemm_writes_stats(DT_F16, M, N, K) ? 1 : 0; }
 
 int lsq_k_row_topk_groups(const float* logits, const float* stats, const float* score, const int32_t* finished, int M,
-                          int V, int k, int eos, float* out_score, int32_t* out_idx, void* stream) {
-  KCHK(logits && stats && score && finished && out_score && out_idx, "null pointer");
-  KCHK(M >= 0 && topk_groups_supported(V, k), "V in [1, 65536], k in [1, beam limit]");
-  KRUN(launch_row_topk_groups(logits, stats, score, finished, M, V, k, eos, out_score, out_idx, (hipStream_t)stream));
+                          int V, int k, int eos, int raw, float* out_score, int32_t* out_idx, void* stream) {
+  KCHK(logits && stats && out_score && out_idx && (raw || (score && finished)), "null pointer");
+  KCHK(M >= 0 && topk_groups_supported(V, k, raw ? 1 : 0), "V in [1, 65536], k in [1, beam limit] (raw: [1, 32])");
+  KRUN(launch_row_topk_groups(logits, stats, score, finished, M, V, k, eos, raw ? 1 : 0, out_score, out_idx, (hipStream_t)stream));
 }
 
 int lsq_k_beam_refine(const float* cand_score, const int32_t* cand_idx, float* score, int32_t* tokens, int32_t* len,

@@ -596,6 +596,34 @@ def test_row_topk_from_group_statistics(env, M, V, k, case):
     np.testing.assert_allclose(got_s[both], os2.cpu().numpy()[both], rtol=2e-6, atol=2e-6)
 
 
+@pytest.mark.parametrize("M,V,k", [(32, 50257, 8), (32, 32000, 32), (5, 1000, 32), (6, 40, 32), (3, 50257, 1), (70, 8200, 16)])
+@pytest.mark.parametrize("case", ["random", "ties", "all_equal"])
+def test_largest_logits_from_group_statistics(env, M, V, k, case):
+    """Sampling's candidates (the k largest logits, value descending, token ascending) from the group statistics."""
+    lsq, torch = env
+    rng = np.random.default_rng(M + V + k + 1)
+    logits = (rng.standard_normal((M, V)) * 0.7).astype(np.float32)
+    if case == "ties":
+        logits = np.round(logits * 2) / 2
+    elif case == "all_equal":
+        logits[:] = -0.5
+    G = (V + 31) // 32
+    pad = np.full((M, G * 32), -np.inf, np.float32)
+    pad[:, :V] = logits
+    grp = pad.reshape(M, G, 32)
+    gmax = grp.max(-1)
+    stats = np.stack([gmax, np.exp(grp - gmax[..., None]).sum(-1)], axis=-1).astype(np.float32)
+    os_ = torch.zeros(M, k, dtype=torch.float32, device="cuda")
+    oi = torch.zeros(M, k, dtype=torch.int32, device="cuda")
+    lsq.k_row_topk_groups(_dev(torch, logits), _dev(torch, stats), None, None, k, 2, os_, oi, raw=True)
+    got_s, got_i = os_.cpu().numpy(), oi.cpu().numpy()
+    kk = min(k, V)
+    order = np.lexsort((np.broadcast_to(np.arange(V), (M, V)), -logits), axis=1)[:, :kk]
+    assert np.array_equal(got_i[:, :kk], order)
+    assert np.array_equal(got_s[:, :kk], np.take_along_axis(logits, order, 1))
+    assert (got_i[:, kk:] == -1).all() and np.isneginf(got_s[:, kk:]).all()
+
+
 def _state(rng, B, k, V, T, t, eos, finished_frac):
     M = B * k
     tokens = rng.integers(4, V, size=(M, T + 1)).astype(np.int32)
