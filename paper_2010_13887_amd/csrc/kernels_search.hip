@@ -280,13 +280,15 @@ row_topk_kernel(const T* __restrict__ logits,
 //   * softmax normaliser of the row from the G pairs (no pass over the logits);
 //   * candidate value of every group's best token, cand = score + ((x - max) - log sum), the same
 //     arithmetic as row_topk_kernel token by token (monotone in x, so it is the group's best cand);
-//   * R = the k-th largest of those: k distinct tokens reach R, so every token of the row's exact
-//     top k has cand >= R, and such tokens only sit in groups whose best reaches R -- the paper's
-//     threshold with the product's column groups as the "random" groups;
+//   * R = the k-th largest of the 64 lanes' best group values (each lane holds every 64th group): k distinct
+//     tokens reach R, so every token of the row's exact top k has cand >= R, and such tokens only sit
+//     in groups whose best reaches R -- the paper's threshold with the product's column groups as
+//     the "random" groups;
 //   * only those groups' logits are read (k groups of 32 unless values tie), tokens with cand >= R
 //     are ranked exactly by (cand descending, token ascending).
 // Rows where more than QMAX groups or CMAX tokens reach R (long runs of equal logits) fall back to k
-// exact rounds over the whole row.  Same output as row_topk_kernel (beam search, no groups, not raw).
+// exact rounds over the whole row.  Same output as row_topk_kernel (no diverse groups); raw: the k largest
+// logits themselves (sampling), no score, no normaliser.
 constexpr int kTopkGroupsQ = 64, kTopkGroupsC = 128;   // groups / tokens that may reach the threshold before the fallback
 
 // One row by one wavefront; ql, cs, ci: the wavefront's own LDS lists (kTopkGroupsQ, kTopkGroupsC entries); os, oi:
@@ -698,7 +700,7 @@ __global__ void __launch_bounds__(64 * LSQ_MAX_BEAM_) retrieve_rerank_kernel(
     const float* __restrict__ logits, const float* __restrict__ stats, float* __restrict__ score, int32_t* __restrict__ tokens,
     int32_t* __restrict__ len, int32_t* __restrict__ fin, int32_t* __restrict__ parent, const int32_t* __restrict__ cap,
     int32_t* __restrict__ active, int k, int V, int G, int T1, int32_t* __restrict__ step_state, int eos,
-    int32_t* __restrict__ anc, NextInput nx) {
+    int32_t* __restrict__ anc, NextInput nx, float* __restrict__ cand_out_s, int32_t* __restrict__ cand_out_i) {
   __shared__ int ql[LSQ_MAX_BEAM_][kTopkGroupsQ];
   __shared__ float cs[LSQ_MAX_BEAM_][kTopkGroupsC];
   __shared__ int ci[LSQ_MAX_BEAM_][kTopkGroupsC];
@@ -711,6 +713,10 @@ __global__ void __launch_bounds__(64 * LSQ_MAX_BEAM_) retrieve_rerank_kernel(
   topk_groups_row<GPL>(logits, stats, score, fin, b * k + wave, V, G, k, eos, cand_s + wave * k, cand_i + wave * k, lane,
                        ql[wave], cs[wave], ci[wave]);
   __syncthreads();   // blockDim.x = 64 k: every wavefront has a row
+  if (cand_out_s && (int)threadIdx.x < k * k) {   // the survivors, for whoever inspects them afterwards
+    cand_out_s[(size_t)b * k * k + threadIdx.x] = cand_s[threadIdx.x];
+    cand_out_i[(size_t)b * k * k + threadIdx.x] = cand_i[threadIdx.x];
+  }
   if (wave != 0) return;
   rerank_sentence<false>(cand_s, cand_i, nullptr, score, tokens, len, fin, parent, cap, active, k, V, T1, 0, step_state, eos,
                          anc, one_group(), nx, b, lane, sh_parent, sh_tok, sh_unfinished, sh_taken);
@@ -732,14 +738,14 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
 hipError_t launch_retrieve_rerank(const float* logits, const float* stats, float* score, int32_t* tokens, int32_t* len,
                                   int32_t* fin, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
                                   int V, int T, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
-                                  const NextInput& nx) {
+                                  const NextInput& nx, float* cand_score, int32_t* cand_idx) {
   if (batch <= 0) return hipSuccess;
   if (!topk_groups_supported(V, k, 0) || !stats || !step_state) return hipErrorInvalidValue;
   const int G = (V + 31) / 32;
   dim3 g(batch), b(64 * k);
 #define LSQ_RR(GPL_)                                                                                                     \
   retrieve_rerank_kernel<GPL_><<<g, b, 0, s>>>(logits, stats, score, tokens, len, fin, parent, cap, active, k, V, G, T + 1, \
-                                               step_state, eos, anc, nx)
+                                               step_state, eos, anc, nx, cand_score, cand_idx)
   if (G <= 64 * 4) LSQ_RR(4);
   else if (G <= 64 * 16) LSQ_RR(16);
   else LSQ_RR(32);
@@ -903,6 +909,45 @@ __device__ __forceinline__ unsigned philox4x32_10_first(unsigned c0, unsigned c1
 // the sentence's cap finishes one; the uniform number is that of the sentence's place in the
 // caller's batch (order[r]); active[t] counts the sentences still unfinished after the step.
 // Decoder-only models (fin == nullptr): every row draws at every step, n_new tokens in all.
+// One row's draw from its k ranked candidates (global memory or LDS) by one thread; returns whether the row is
+// still unfinished (always false for decoder-only models, which count differently) and the token through tok_out.
+__device__ __forceinline__ bool sample_row(const float* cl, const int32_t* ci, int r, int32_t* __restrict__ tokens,
+                                           int32_t* __restrict__ len, float* __restrict__ logp, int k, float topp, int T1,
+                                           unsigned seed_lo, unsigned seed_hi, int pos, int t, int32_t* __restrict__ fin,
+                                           const int32_t* __restrict__ cap, const int32_t* __restrict__ order, int eos,
+                                           int& tok_out) {
+  float e[LSQ_MAX_TOPK_], cum[LSQ_MAX_TOPK_];
+  const float l0 = cl[0];
+  float run = 0.f;
+  for (int j = 0; j < k; ++j) {
+    e[j] = expf(cl[j] - l0);
+    run += e[j];
+    cum[j] = run;
+  }
+  // nucleus inside the candidates: the shortest ranked prefix whose mass reaches topp of the total
+  int n = k;
+  if (topp < 1.0f) {
+    const float thresh = __fmul_rn(topp, run);
+    n = 1;
+    while (n < k && !(cum[n - 1] >= thresh)) ++n;
+  }
+  const float total = cum[n - 1];
+  const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)(order ? order[r] : r), 0u, 0u, seed_lo, seed_hi);
+  const float u = (float)(word >> 8) * 5.9604644775390625e-08f;   // 2^-24
+  const float target = __fmul_rn(u, total);
+  int j = 0;
+  while (j < n - 1 && !(cum[j] > target)) ++j;
+  const int tok = ci[j];
+  tokens[(size_t)r * T1 + pos + 1] = tok;
+  len[r] = pos + 1;
+  logp[r] += logf(e[j] / total);
+  tok_out = tok;
+  if (!fin) return false;
+  const bool unfinished = !(tok == eos || pos + 1 >= cap[r]);
+  fin[r] = unfinished ? 0 : 1;
+  return unfinished;
+}
+
 __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ cand_logit,
                                                     const int32_t* __restrict__ cand_idx,
                                                     int32_t* __restrict__ tokens, int32_t* __restrict__ len,
@@ -914,42 +959,76 @@ __global__ void __launch_bounds__(64) sample_kernel(const float* __restrict__ ca
   const int r = blockIdx.x * 64 + threadIdx.x;
   const int pos = step_state[0], t = pos - step_state[2];   // position of the token just fed; step index
   bool unfinished = false;
-  if (r < rows && !(fin && fin[r])) {
-    float e[LSQ_MAX_TOPK_], cum[LSQ_MAX_TOPK_];
-    const float l0 = cand_logit[(size_t)r * k];
-    float run = 0.f;
-    for (int j = 0; j < k; ++j) {
-      e[j] = expf(cand_logit[(size_t)r * k + j] - l0);
-      run += e[j];
-      cum[j] = run;
-    }
-    // nucleus inside the candidates: the shortest ranked prefix whose mass reaches topp of the total
-    int n = k;
-    if (topp < 1.0f) {
-      const float thresh = __fmul_rn(topp, run);
-      n = 1;
-      while (n < k && !(cum[n - 1] >= thresh)) ++n;
-    }
-    const float total = cum[n - 1];
-    const unsigned word = philox4x32_10_first((unsigned)t, (unsigned)(order ? order[r] : r), 0u, 0u, seed_lo, seed_hi);
-    const float u = (float)(word >> 8) * 5.9604644775390625e-08f;   // 2^-24
-    const float target = __fmul_rn(u, total);
-    int j = 0;
-    while (j < n - 1 && !(cum[j] > target)) ++j;
-    const int tok = cand_idx[(size_t)r * k + j];
-    tokens[(size_t)r * T1 + pos + 1] = tok;
-    len[r] = pos + 1;
-    logp[r] += logf(e[j] / total);
-    if (fin) {
-      unfinished = !(tok == eos || pos + 1 >= cap[r]);
-      fin[r] = unfinished ? 0 : 1;
-    }
-  }
+  int tok;
+  if (r < rows && !(fin && fin[r]))
+    unfinished = sample_row(cand_logit + (size_t)r * k, cand_idx + (size_t)r * k, r, tokens, len, logp, k, topp, T1, seed_lo,
+                            seed_hi, pos, t, fin, cap, order, eos, tok);
   const int alive = __popcll(__ballot(unfinished));
   if (threadIdx.x == 0) {
     if (fin && alive) atomicAdd(active + t, alive);
     __threadfence();
     if (atomicAdd(&step_state[1], 1) == (int)gridDim.x - 1) {
+      step_state[1] = 0;
+      if (!fin) active[t] = (t + 1 < n_new) ? rows : 0;
+      step_state[0] = pos + 1;
+    }
+  }
+}
+
+// Retrieve (the k largest logits from the logit product's group statistics) and draw in one launch: a wavefront
+// per row, four rows per workgroup; the candidates stay in LDS, the first lane draws.  nx.E given (encoder-decoder
+// models): the row's next decoder input is written as well (a finished row: nothing; its logits are not used).
+template <int GPL>
+__global__ void __launch_bounds__(256) retrieve_sample_kernel(const float* __restrict__ logits, const float* __restrict__ stats,
+                                                              int32_t* __restrict__ tokens, int32_t* __restrict__ len,
+                                                              float* __restrict__ logp, int32_t* __restrict__ active,
+                                                              int32_t* __restrict__ step_state, int rows, int V, int G, int k,
+                                                              float topp, int T1, unsigned seed_lo, unsigned seed_hi,
+                                                              int n_new, int32_t* __restrict__ fin,
+                                                              const int32_t* __restrict__ cap,
+                                                              const int32_t* __restrict__ order, int eos, NextInput nx,
+                                                              float* __restrict__ cand_out_s, int32_t* __restrict__ cand_out_i) {
+  __shared__ int ql[4][kTopkGroupsQ];
+  __shared__ float cs[4][kTopkGroupsC];
+  __shared__ int ci[4][kTopkGroupsC];
+  __shared__ float cand_s[4][LSQ_MAX_TOPK_];
+  __shared__ int cand_i[4][LSQ_MAX_TOPK_];
+  __shared__ int next_tok[4];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= rows) return;
+  const int pos = step_state[0], t = pos - step_state[2];
+  const bool done = fin && fin[r];   // the same in every lane
+  if (!done) {
+    topk_groups_row<GPL>(logits, stats, nullptr, nullptr, r, V, G, k, eos, cand_s[wave], cand_i[wave], lane, ql[wave], cs[wave],
+                         ci[wave], 1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  }
+  if (!done && cand_out_s && lane < k) {   // the candidates, for whoever inspects them afterwards
+    cand_out_s[(size_t)r * k + lane] = cand_s[wave][lane];
+    cand_out_i[(size_t)r * k + lane] = cand_i[wave][lane];
+  }
+  bool unfinished = false;
+  if (lane == 0) {
+    int tok = -1;
+    if (!done)
+      unfinished = sample_row(cand_s[wave], cand_i[wave], r, tokens, len, logp, k, topp, T1, seed_lo, seed_hi, pos, t, fin, cap,
+                              order, eos, tok);
+    next_tok[wave] = tok;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  if (nx.E && pos + 1 < T1 - 1) {
+    if (nx.dtype == DT_F16) next_input_rows<half_t>(nx, &next_tok[wave], r, 1, pos + 1, lane);
+    else next_input_rows<float>(nx, &next_tok[wave], r, 1, pos + 1, lane);
+  }
+  if (lane == 0) {
+    if (fin && unfinished) atomicAdd(active + t, 1);
+    __threadfence();
+    if (atomicAdd(&step_state[1], 1) == rows - 1) {   // one count per row: the last row advances the position
       step_state[1] = 0;
       if (!fin) active[t] = (t + 1 < n_new) ? rows : 0;
       step_state[0] = pos + 1;
@@ -966,6 +1045,25 @@ hipError_t launch_sample(const float* cand_logit, const int32_t* cand_idx, int32
   sample_kernel<<<(rows + 63) / 64, 64, 0, s>>>(cand_logit, cand_idx, tokens, len, logp, active, step_state, rows, k,
                                                 topp, T + 1, (unsigned)(seed & 0xFFFFFFFFull), (unsigned)(seed >> 32),
                                                 n_new, fin, cap, order, eos);
+  return hipGetLastError();
+}
+
+hipError_t launch_retrieve_sample(const float* logits, const float* stats, int32_t* tokens, int32_t* len, float* logp,
+                                  int32_t* active, int32_t* step_state, int rows, int V, int k, float topp, int T,
+                                  unsigned long long seed, int n_new, hipStream_t s, int32_t* fin, const int32_t* cap,
+                                  const int32_t* order, int eos, const NextInput& nx, float* cand_score, int32_t* cand_idx) {
+  if (rows <= 0) return hipSuccess;
+  if (!topk_groups_supported(V, k, 1) || !stats || !(topp > 0.f) || (fin && !cap)) return hipErrorInvalidValue;
+  const int G = (V + 31) / 32;
+  dim3 g((rows + 3) / 4), b(256);
+  const unsigned lo = (unsigned)(seed & 0xFFFFFFFFull), hi = (unsigned)(seed >> 32);
+#define LSQ_RS(GPL_)                                                                                                    \
+  retrieve_sample_kernel<GPL_><<<g, b, 0, s>>>(logits, stats, tokens, len, logp, active, step_state, rows, V, G, k, topp, \
+                                               T + 1, lo, hi, n_new, fin, cap, order, eos, nx, cand_score, cand_idx)
+  if (G <= 64 * 4) LSQ_RS(4);
+  else if (G <= 64 * 16) LSQ_RS(16);
+  else LSQ_RS(32);
+#undef LSQ_RS
   return hipGetLastError();
 }
 

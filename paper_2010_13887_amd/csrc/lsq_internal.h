@@ -200,11 +200,19 @@ hipError_t launch_beam_refine(const float* cand_score, const int32_t* cand_idx, 
                               const int32_t* cap, int32_t* active, int batch, int k, int V, int T,
                               int t_base, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
                               const SearchGroups& groups = one_group(), const NextInput& next = no_next_input());
+// launch_row_topk_groups (raw) and launch_sample in one launch; next.E given: the rows' next decoder input as well
+hipError_t launch_retrieve_sample(const float* logits, const float* stats, int32_t* tokens, int32_t* len, float* logp,
+                                  int32_t* active, int32_t* step_state, int rows, int V, int k, float topp, int T,
+                                  unsigned long long seed, int n_new, hipStream_t s, int32_t* fin = nullptr,
+                                  const int32_t* cap = nullptr, const int32_t* order = nullptr, int eos = -1,
+                                  const NextInput& next = no_next_input(), float* cand_score = nullptr,
+                                  int32_t* cand_idx = nullptr);   // cand_*: the candidates are also left there
 // launch_row_topk_groups and launch_beam_refine (no groups, device-side step counter) in one launch
 hipError_t launch_retrieve_rerank(const float* logits, const float* stats, float* score, int32_t* tokens, int32_t* len,
                                   int32_t* fin, int32_t* parent, const int32_t* cap, int32_t* active, int batch, int k,
                                   int V, int T, int32_t* step_state, int eos, int32_t* anc, hipStream_t s,
-                                  const NextInput& next = no_next_input());
+                                  const NextInput& next = no_next_input(), float* cand_score = nullptr,
+                                  int32_t* cand_idx = nullptr);   // cand_*: the survivors are also left there
 // npos = npos_base + (tp ? *tp : 0); the grid covers npos_max positions
 hipError_t launch_cache_reorder(int dtype, void* cache, const int32_t* parent, int layers, int batch,
                                 int rows_total, int k, int T, int d, int npos_base, const int32_t* tp,

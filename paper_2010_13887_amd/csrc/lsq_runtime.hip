@@ -312,6 +312,7 @@ struct Ctx {
   int block_rows = 64;    // ... and whole attention sublayers in one launch up to this many rows
   bool topk_stats = true; // beam search: retrieve from the logit product's group statistics
   bool merge_rerank = true;   // ... and in the same launch as the re-rank stage
+  bool sample_fold = false;   // this translation (sampling decoding): retrieve, draw and next input in one launch at every step
   int groups_next = 1, groups = 1;          // diverse beam search: groups per sentence (next encode / this translation)
   float strength_next = 0.f, strength = 0.f;
   bool hidden_in_alt = false;   // the last step left its final hidden rows in the second buffer
@@ -390,7 +391,7 @@ int launch_step(int B) {
   // Under beam search the step's decoder input waits in a buffer of its own (the re-rank kernel of the step before
   // wrote it while this step's final hidden rows were still to be read); it is only read, by the first sublayer,
   // whose LayerNorm leaves the residual stream in the usual two buffers.  Sampling decoding embeds in place.
-  char* const x0 = hp.sample_topk > 0 ? x_home : g.ws + p.d_x0;
+  char* const x0 = (hp.sample_topk > 0 && !g.sample_fold) ? x_home : g.ws + p.d_x0;
   char* x = x0; char* q = g.ws + p.d_q; char* ctx = g.ws + p.d_ctx; char* tmp = g.ws + p.d_tmp;
   char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
   int32_t* step = at<int32_t>(p.step_state);
@@ -399,7 +400,7 @@ int launch_step(int B) {
   const size_t cross_l = (size_t)g.max_batch * g.max_len * 2 * d * es;
   // Under beam search the decoder input of this step is already there: the re-rank kernel of the step before
   // (lsq_encode for the first step) wrote it.  Sampling decoding embeds here.
-  if (hp.sample_topk > 0)
+  if (hp.sample_topk > 0 && !g.sample_fold)
     TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, sqrtf((float)d), s));
   char* x_alt = g.ws + p.d_x2;
   const NextInput next = {g.E, at<float>(p.pe), g.ws + p.d_x0, d, dt, sqrtf((float)d)};
@@ -520,12 +521,22 @@ int launch_step(int B) {
   // and the retrieve kernel works from those instead of reading the rows (sec. 2.2, with the product's column
   // groups as the groups)
   const bool sampling = hp.sample_topk > 0;
-  const bool from_stats = g.topk_stats && g.groups == 1 && gemm_writes_stats(dt, M, V, d) &&
-                          topk_groups_supported(V, sampling ? hp.sample_topk : k, sampling ? 1 : 0);
+  const bool from_stats = (sampling && g.sample_fold) ||
+                          (g.topk_stats && g.groups == 1 && gemm_writes_stats(dt, M, V, d) &&
+                           topk_groups_supported(V, sampling ? hp.sample_topk : k, sampling ? 1 : 0));
   if (from_stats) { lo.stats = at<float>(p.d_stats); lo.stats_groups = (V + 31) / 32; }
   if (int rc = product(PC_GEMM_VOCAB, g.E, nullptr, lo, V, 0)) return rc;
   if (hp.sample_topk > 0) {
     // sampling decoding (sec. 3.4): one hypothesis per sentence, nothing to re-rank or to refresh
+    if (g.sample_fold) {
+      // retrieve, draw and the next step's input in one launch
+      TIMED(PC_RETRIEVE_RERANK, launch_retrieve_sample((const float*)logits, at<float>(p.d_stats), at<int32_t>(p.tokens),
+                                                       at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, V,
+                                                       hp.sample_topk, hp.topp, T, (unsigned long long)hp.seed, 0, s,
+                                                       at<int32_t>(p.fin), at<int32_t>(p.cap), at<int32_t>(p.order), hp.eos, next,
+                                                       at<float>(p.cand_score), at<int32_t>(p.cand_idx)));
+      return LSQ_OK;
+    }
     if (from_stats)
       TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), nullptr, nullptr, M, V,
                                                        hp.sample_topk, hp.eos, 1, at<float>(p.cand_score),
@@ -563,7 +574,7 @@ int launch_step(int B) {
     TIMED(PC_RETRIEVE_RERANK, launch_retrieve_rerank((const float*)logits, at<float>(p.d_stats), at<float>(p.score),
                                                      at<int32_t>(p.tokens), at<int32_t>(p.len), at<int32_t>(p.fin),
                                                      at<int32_t>(p.parent), at<int32_t>(p.cap), at<int32_t>(p.active), B, k, V, T,
-                                                     step, hp.eos, anc, s, next));
+                                                     step, hp.eos, anc, s, next, at<float>(p.cand_score), at<int32_t>(p.cand_idx)));
     if (!anc)
       TIMED(PC_REORDER, launch_cache_reorder(dt, g.ws + p.cache, at<int32_t>(p.parent), 2 * hp.n_dec, B, M_max, k, T, d,
                                              0, step, T, s));
@@ -625,6 +636,13 @@ int launch_step_gpt(int B) {
   const bool from_stats = g.topk_stats && gemm_writes_stats(dt, M, V, d) && topk_groups_supported(V, ks, 1);
   if (from_stats) { lo.stats = at<float>(p.d_stats); lo.stats_groups = (V + 31) / 32; }
   TIMED(PC_GEMM_VOCAB, launch_gemm(dt, y, g.E, nullptr, lo, M, V, d, 0, s));
+  if (from_stats && g.merge_rerank) {
+    TIMED(PC_RETRIEVE_RERANK, launch_retrieve_sample((const float*)logits, at<float>(p.d_stats), at<int32_t>(p.tokens),
+                                                     at<int32_t>(p.len), at<float>(p.score), at<int32_t>(p.active), step, M, V, ks,
+                                                     hp.topp, T, (unsigned long long)hp.seed, hp.cap_extra, s, nullptr, nullptr, nullptr,
+                                                     -1, no_next_input(), at<float>(p.cand_score), at<int32_t>(p.cand_idx)));
+    return LSQ_OK;
+  }
   if (from_stats)
     TIMED(PC_ROW_TOPK_GROUPS, launch_row_topk_groups((const float*)logits, at<float>(p.d_stats), nullptr, nullptr, M, V, ks,
                                                      hp.eos, 1, at<float>(p.cand_score), at<int32_t>(p.cand_idx), s));
@@ -1017,7 +1035,20 @@ int lsq_encode(const int32_t* src_ids, const int32_t* src_lens, int batch, int s
                            at<int32_t>(p.pen_n), batch, g.beam, g.beam / g.groups, g.max_len, hp.bos,
                            hp.pad, s));
   // the first step's decoder input (BOS at position 0); later ones are left by each step's re-rank kernel
-  if (hp.sample_topk == 0)
+  // sampling decoding: one launch for retrieve + draw + next input when every row count of this translation has a
+  // logit product that leaves group statistics (decided here, for the whole translation)
+  bool fold = false;
+  if (hp.sample_topk > 0 && g.topk_stats && g.merge_rerank && topk_groups_supported(hp.V, hp.sample_topk, 1)) {
+    fold = true;
+    for (int m = 1; m <= batch * g.beam; ++m) fold = fold && gemm_writes_stats(dt, m, hp.V, d);
+  }
+  if (fold != g.sample_fold) {   // captured steps hold the other variant's launches
+    for (auto& kv : g.graphs) (void)hipGraphExecDestroy(kv.second);
+    g.graphs.clear();
+    g.graph_hidden_in_alt.clear();
+  }
+  g.sample_fold = fold;
+  if (hp.sample_topk == 0 || g.sample_fold)
     HIPCHK(launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), g.ws + p.d_x0,
                              batch * g.beam, d, g.max_len, at<int32_t>(p.step_state), sqrtf((float)d), s));
   for (size_t c : p.dec_canaries) HIPCHK(hipMemsetAsync(g.ws + c, kCanaryByte, kCanaryBytes, s));
