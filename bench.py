@@ -70,7 +70,8 @@ def measured_traffic(cls):
     total, found = 0.0, False
     for line in open(path):
         m = re.match(r"(\S.{25}) (\S.{47}) +([\d.]+) +([\d.]+)\s*$", line)
-        if m and any(m.group(1).strip().startswith(c) for c in cases) and "rocclr" not in m.group(2) and not m.group(2).startswith("add_layernorm"):
+        if (m and any(m.group(1).strip().startswith(c) for c in cases) and "rocclr" not in m.group(2)
+                and "add_layernorm" not in m.group(2) and (cls.startswith("gemm") or "gemm_f16" not in m.group(2))):
             total += (float(m.group(3)) + float(m.group(4))) * 1e6
             found = True
     return total if found else None

@@ -311,9 +311,14 @@ def main() -> int:
         by = (M * K + V * K) * 2 + M * V * 4 + M * ((V + 31) // 32) * 8
         cases.append((f"gemm_logits M{M} N{V} K{K} f32out + group statistics", "mfma", 2.0 * M * V * K, by,
                       lambda: lsq.k_gemm_logits(A, B, C, st)))
-        lsq.k_gemm_logits(A, B, C, st)
-        cases.append((name, "hbm", 0.0, M * ((V + 31) // 32) * 8 + M * k * 32 * 4,
-                      lambda: lsq.k_row_topk_groups(C, st, score, fin, k, 2, os_, oi)))
+        made = []
+
+        def retrieve():
+            if not made:                     # the logits and their statistics, once, when this case is run at all
+                lsq.k_gemm_logits(A, B, C, st)
+                made.append(1)
+            lsq.k_row_topk_groups(C, st, score, fin, k, 2, os_, oi)
+        cases.append((name, "hbm", 0.0, M * ((V + 31) // 32) * 8 + M * k * 32 * 4, retrieve))
 
     def reorder_case(name, layers, B, k, T, d, npos):
         cache = rnd(layers, B * k, T, d)
