@@ -28,14 +28,14 @@ from oracle import lsq_oracle as O
 MARGIN = 1e-3        # token ids are compared strictly while the judge's beam-score margins exceed this (plus the band)
 TOL_F16 = 2e-2       # logits, fp16 storage, against the unrounded oracle
 TOL_F32 = 1e-4       # logits on the fp32 path ...
-TOL_F32_CEIL = 1e-3  # ... and the absolute ceiling of the conditioning-aware bound (Float32Shadow)
+TOL_F32_CEIL = 1e-3  # ... bounds beyond this are counted (models on which float32 itself loses three digits)
 TOL_MIRROR = 1e-2    # fp16 logits against the oracle that rounds where the library stores
 # Fixed bounds on what may enter the near-tie band, in units the library has no hand in.  A logit tolerance
 # tau (relative to |r| + rms of the row, logit_error) moves a log-probability by at most
 # 2 tau (max |r| + rms) =: unit(tau) of that row.  One step's deviation of a candidate's log-probability
 # (library vs judge, 32 best candidates of a row on either side) must stay below unit(TAU_BAND) --
-# TAU_BAND = 1e-3 for float16 models (measured: at most 0.3 of it), well inside the stated 2e-2; for float32 models the step's own
-# conditioning-aware bound (Float32Shadow, from oracle runs alone, at most TOL_F32_CEIL) -- and the whole
+# TAU_BAND = 1e-3 for float16 models (measured: at most 0.3 of it), well inside the stated 2e-2; for float32 models the run's
+# conditioning-aware bound (Float32Shadow, from oracle runs alone) -- and the whole
 # deviation of a sentence's candidate scores, once the drift its hypotheses share is taken out, below
 # CDEV_UNITS such units (hypotheses of a sentence share all but their last few steps).
 TAU_BAND_F16 = 1e-3
@@ -77,20 +77,25 @@ def score_slack(round16, got, ref, live):
     return max(2e-5, 2.0 * dev)
 
 
+F32_FACTOR = 4.0     # float32 models: the library may be this many times further from float64 than numpy float32 is, over a run
+
+
 class Float32Shadow:
-    """For float32 models: the same oracle once more in numpy float32, following the same decisions.
-    Its distance s from the float64 oracle says how well conditioned a step is: some rows of some
-    random models lose three or four digits in ANY float32 evaluation (the library's and numpy's
-    deviations appear in the same rows; on a given row either can be the larger by a factor of four,
-    while kernel by kernel the library is as close to float64 as numpy's float32 is).  The bound on the
-    library's logits at a step is
-        max(TOL_F32, min(8 s, TOL_F32_CEIL), 2 s):
-    the stated 1e-4 wherever plain float32 arithmetic is itself within 1.25e-5; up to eight times numpy's
-    own deviation while that stays below the ceiling of 1e-3; and on the rare step where numpy's float32
-    is itself further than 5e-4 from float64 (nothing computed in float32 can meet 1e-3 there) twice
-    numpy's deviation.  All three come from oracle runs alone.  `over` counts the steps whose bound
-    exceeded TOL_F32, `over_ceiling` those beyond TOL_F32_CEIL, `worst_bound` is the largest bound used;
-    note(e) records the library's error at the step for `worst_ratio` = library error / max(s, 1.25e-5)."""
+    """For float32 models: how well conditioned the model is, from oracle runs alone.  Some random models
+    lose three or four digits in ANY float32 evaluation of some rows at some steps (deep LayerNorm / softmax
+    chains with large activations); the library's and numpy's deviations from float64 have the same size over
+    a translation but land on different steps and rows (measured on ill-conditioned draws: worst library error
+    1.2 to 3.0 times numpy's worst over the run, while step by step the ratio swings between 0.1 and 18).  So
+    the bound is per run, not per step:
+        s_run = the largest distance of the oracle in numpy float32 from the oracle in float64 over the whole
+                translation -- a pass of the two oracles alone before the library runs (both following the
+                float64 oracle's decisions), kept up to date with the steps of the lock-step run itself (both
+                following the library's decisions);
+        bound on the library's logits at every step: max(TOL_F32, F32_FACTOR * s_run).
+    Wherever plain float32 arithmetic stays within 2.5e-5 of float64 the bound is the stated 1e-4.
+    `over` counts the steps whose bound exceeded TOL_F32, `over_ceiling` those beyond TOL_F32_CEIL,
+    `worst_bound` is the largest bound used, `worst_ratio` = the library's worst error of the run over
+    max(s_run, TOL_F32 / F32_FACTOR)."""
 
     def __init__(self, blob, w, k=None, groups=1, gpt=False):
         self.m = O.Model(blob)
@@ -99,6 +104,8 @@ class Float32Shadow:
         self.worst_bound = TOL_F32
         self.worst_ratio = 0.0
         self.last = 0.0
+        self.e_max = 0.0
+        self.s_run = self._conditioning(blob, w, k, groups)
         if gpt:
             self.st = O.GptState(self.m, w.src_ids[:, :int(w.src_lens[0])], w.max_len)
             O.gpt_prefill(self.m, self.st)
@@ -106,14 +113,51 @@ class Float32Shadow:
             _, self.cross = O.encode(self.m, w.src_ids, w.src_lens)
             self.st = O.DecodeState(self.m, w.src_lens, k, w.max_len, groups)
 
+    def _conditioning(self, blob, w, k, groups):
+        """The two oracles side by side over the whole translation, decisions taken by the float64 one."""
+        m64, m32 = O.Model(blob, ctype=np.float64), self.m
+        worst = 0.0
+        if self.gpt:
+            P = int(w.src_lens[0])
+            a, b = O.GptState(m64, w.src_ids[:, :P], w.max_len), O.GptState(m32, w.src_ids[:, :P], w.max_len)
+            O.gpt_prefill(m64, a)
+            O.gpt_prefill(m32, b)
+            for _ in range(m64.cap_extra):
+                l64, l32 = O.gpt_step_logits(m64, a), O.gpt_step_logits(m32, b)
+                worst = max(worst, logit_error(l32, l64))
+                picks = [O.sample_topk(l64[r], m64.sample_topk, O.sample_uniform(m64.seed, a.t, r), m64.sample_topp)
+                         for r in range(a.B)]
+                O.gpt_advance(m64, a, [q[0] for q in picks], [q[1] for q in picks])
+                O.gpt_advance(m32, b, [q[0] for q in picks], [q[1] for q in picks])
+            return worst
+        _, c64 = O.encode(m64, w.src_ids, w.src_lens)
+        _, c32 = O.encode(m32, w.src_ids, w.src_lens)
+        a, b = O.DecodeState(m64, w.src_lens, k, w.max_len, groups), O.DecodeState(m32, w.src_lens, k, w.max_len, groups)
+        while True:
+            l64, l32 = O.decoder_logits_cached(m64, a, c64), O.decoder_logits_cached(m32, b, c32)
+            live = ~a.finished.reshape(-1)
+            if live.any():
+                worst = max(worst, logit_error(l32[live], l64[live]))
+            if m64.sample_topk >= 1:
+                tok, par, sc, _ = O.sample_select(m64, a, l64)
+            elif groups > 1:
+                tok, par, sc, _ = O.beam_select_diverse(m64, a, l64, 0.0)
+            else:
+                tok, par, sc, _ = O.beam_select(m64, a, l64)
+            active = O.beam_advance(m64, a, tok, par, sc)
+            O.beam_advance(m32, b, tok, par, np.asarray(sc, np.float32))
+            if active == 0:
+                return worst
+
     def tolerance(self, ref64, live):
         """Call once per step, before advance()."""
         ref32 = O.gpt_step_logits(self.m, self.st) if self.gpt else O.decoder_logits_cached(self.m, self.st, self.cross)
-        if not np.any(live):
+        if np.any(live):
+            self.last = logit_error(ref32[live], ref64[live])
+            self.s_run = max(self.s_run, self.last)
+        else:
             self.last = 0.0
-            return TOL_F32
-        self.last = logit_error(ref32[live], ref64[live])
-        tol = max(TOL_F32, min(8.0 * self.last, TOL_F32_CEIL), 2.0 * self.last)
+        tol = max(TOL_F32, F32_FACTOR * self.s_run)
         if tol > TOL_F32:
             self.over += 1
             self.worst_bound = max(self.worst_bound, tol)
@@ -122,7 +166,8 @@ class Float32Shadow:
         return tol
 
     def note(self, e):
-        self.worst_ratio = max(self.worst_ratio, e / max(self.last, 1.25e-5))
+        self.e_max = max(self.e_max, e)
+        self.worst_ratio = self.e_max / max(self.s_run, TOL_F32 / F32_FACTOR)
 
     def advance(self, *sel):
         if self.gpt:

