@@ -100,6 +100,11 @@ def class_work(name, hp, B, k, t_mean, s_mean):
         return (4.0 * M * s_mean * d, (2 * B * s_mean * d + 2 * M * d) * es)
     if name == "attn_cross_q":   # the same plus the query product: Wq and the normalised rows in
         return (2.0 * M * d * d + 4.0 * M * s_mean * d, (2 * B * s_mean * d + 3 * M * d + d * d) * es)
+    if name == "self_block":     # LayerNorm + QKV + append + attention + per-head output projection: the four d x d
+        # weight blocks once, the history once, two slabs in and one slab per head out
+        return (2.0 * M * 4 * d * d + 4.0 * M * t_mean * d, 4 * d * d * es + 2 * M * t_mean * d * es + (2 + hp.n_heads) * M * d * 4)
+    if name == "cross_block":    # LayerNorm over the head slabs + Q + attention + per-head output projection
+        return (2.0 * M * 2 * d * d + 4.0 * M * s_mean * d, 2 * d * d * es + 2 * B * s_mean * d * es + 2 * hp.n_heads * M * d * 4)
     if name == "add_layernorm":
         return (8.0 * M * d, 3 * M * d * es)
     if name == "embed":

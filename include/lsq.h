@@ -149,8 +149,8 @@ int lsq_set_cache_refresh(int mode);
  * to the last bits, not always bit for bit.  Default: on. */
 int lsq_set_layernorm_fusion(int on);
 
-/* Few rows alive (float16 encoder-decoder models with heads of 64, beam <= 4, d = 256 or 512: with
- * wider models the separate kernels are faster): each attention sublayer of a decoder layer runs as one launch up to its output
+/* Few rows alive (float16 models with heads of 64 and d = 256 or 512, beam <= 4: with wider models
+ * the separate kernels are faster): each attention sublayer of a decoder layer runs as one launch up to its output
  * projection (sec. 2.1 taken further; lsq_k_self_attention_block, lsq_k_cross_attention_block)
  * while at most max_rows rows are alive.  0 switches this off; default and largest value 64.  Same
  * tokens as the separate kernels; scores equal to float16 rounding (other summation orders).  Also
@@ -307,6 +307,8 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
  * chain of launch latencies).  For every sentence b, head h and row r of b:
  *   rows      = LN(x_old + sum_s P[s] + ln_bias) * gamma + beta   (splits 1..4; written to x_new)
  *               or x_old as it is                                  (splits 0; x_new and P unused)
+ *     pre_ln = 1 (pre-LN models): u = x_old + sum_s P[s] + ln_bias rounded to float16 is what x_new
+ *               receives, rows = LN(u) * gamma + beta; splits 0: rows = LN(x_old) * gamma + beta
  *   [q|k|v]   = rows . Wqkv[{0,d,2d} + h*64 .. +63, :]^T + bqkv[..]   (rounded to float16)
  *   Kc, Vc[r, nkeys, h*64..] = k, v
  *   ctx       = softmax(q . K^T / 8) V over positions 0..nkeys of r's history, rounded to float16
@@ -321,7 +323,7 @@ int lsq_k_self_attention_block(const float* P, int splits, const void* ln_bias, 
                                const void* beta, const void* x_old, void* x_new, float eps,
                                const void* Wqkv_packed, const void* bqkv, const void* Wo_packed, void* Kc,
                                void* Vc, const int32_t* slab_table, int nkeys, float* P_out, int batch,
-                               int beam, int heads, int d, int T, void* stream);
+                               int beam, int heads, int d, int T, int pre_ln, void* stream);
 
 /* The cross-attention sublayer up to its output projection in one launch, for at most 64 rows:
  * lsq_k_layernorm_cross_attention with 1..16 slabs behind the LayerNorm (the block above leaves

@@ -63,7 +63,7 @@ def load_library() -> C.CDLL:
         "lsq_k_gemm_logits_supported": [i32, i32, i32],
         "lsq_k_row_topk_groups": [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp],
         "lsq_k_self_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32,
-                                       i32, i32, vp],
+                                       i32, i32, i32, vp],
         "lsq_k_cross_attention_block": [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32,
                                         vp],
         "lsq_debug_read": [i32, vp, sz],
@@ -324,16 +324,16 @@ def k_layernorm_cross_attention(P, ln_bias, gamma, beta, x_old, x_new, eps: floa
 
 
 def k_self_attention_block(P, ln_bias, gamma, beta, x_old, x_new, eps: float, Wqkv_packed, bqkv, Wo_packed, Kc, Vc,
-                           slab_table, nkeys: int, P_out, batch: int, beam: int, heads: int) -> None:
+                           slab_table, nkeys: int, P_out, batch: int, beam: int, heads: int, pre_ln: bool = False) -> None:
     """Self-attention sublayer up to the output projection's per-head partial sums P_out [heads, rows, d]; P None: the
-    rows are x_old as they are.  Kc, Vc [rows, T, d] receive the new position at index nkeys."""
+    rows are x_old as they are (pre_ln: LayerNorm(x_old)).  Kc, Vc [rows, T, d] receive the new position at index nkeys."""
     M, d = x_old.shape
     splits = 0 if P is None else P.shape[0]
     assert M == batch * beam and tuple(P_out.shape) == (heads, M, d)
     _check(load_library().lsq_k_self_attention_block(_p(P), splits, _p(ln_bias), _p(gamma), _p(beta), _p(x_old), _p(x_new),
                                                      eps, _p(Wqkv_packed), _p(bqkv), _p(Wo_packed), _p(Kc), _p(Vc),
                                                      _p(slab_table), nkeys, _p(P_out), batch, beam, heads, d, Kc.shape[1],
-                                                     _stream()))
+                                                     int(bool(pre_ln)), _stream()))
 
 
 def k_cross_attention_block(P, ln_bias, gamma, beta, x_old, x_new, eps: float, Wq_packed, bq, Wo_packed, kv, src_off,

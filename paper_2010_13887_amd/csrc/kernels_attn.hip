@@ -771,12 +771,14 @@ __device__ __forceinline__ void sum_slabs(const float* __restrict__ P, size_t sl
 
 // Row `r` of LayerNorm(x_old + (sum of the slabs + bias)) * g + b by one wavefront, into LDS (and to
 // x_new when `keep`); ln.splits == 0: the row is x_old as it is.  d <= 1024.  CH: slabs requested together.
+// ln.pre (pre-LN models): the sum x_old + (slabs + bias), rounded to float16, is what x_new receives and what is
+// normalised, as in the stand-alone kernel; without slabs the row is LayerNorm(x_old) and nothing is kept.
 template <int CH>
 __device__ __forceinline__ void block_row(const LnInput& ln, int r, int M, int d, int lane, bool keep,
                                           half_t* __restrict__ dst) {
   constexpr int NV = 2;
   const size_t slab = (size_t)M * d;
-  if (ln.splits == 0) {
+  if (ln.splits == 0 && !ln.pre) {
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int cc = (j * 64 + lane) * 8;
@@ -790,13 +792,20 @@ __device__ __forceinline__ void block_row(const LnInput& ln, int r, int M, int d
     const int cc = (j * 64 + lane) * 8;
     if (cc < d) {
       float t[8], a[8];
-      Vec8<half_t>::load(ln.bias + cc, t);
+      if (ln.splits > 0) Vec8<half_t>::load(ln.bias + cc, t);
       Vec8<half_t>::load(ln.x_old + (size_t)r * d + cc, v[j]);
       Vec8<half_t>::load(ln.g + cc, gv[j]);
       Vec8<half_t>::load(ln.b + cc, bv[j]);
-      sum_slabs<CH>(ln.P + (size_t)r * d + cc, slab, ln.splits, a);
+      if (ln.splits > 0) {
+        sum_slabs<CH>(ln.P + (size_t)r * d + cc, slab, ln.splits, a);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[j][i] = __fadd_rn(v[j][i], __fadd_rn(a[i], t[i]));
+        for (int i = 0; i < 8; ++i) v[j][i] = __fadd_rn(v[j][i], __fadd_rn(a[i], t[i]));
+        if (ln.pre) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[j][i] = (float)(half_t)v[j][i];
+          if (keep) Vec8<half_t>::store(ln.x_new + (size_t)r * d + cc, v[j]);
+        }
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
@@ -809,7 +818,7 @@ __device__ __forceinline__ void block_row(const LnInput& ln, int r, int M, int d
     const int cc = (j * 64 + lane) * 8;
     if (cc < d) {
       Vec8<half_t>::store(dst + cc, o[j]);
-      if (keep) Vec8<half_t>::store(ln.x_new + (size_t)r * d + cc, o[j]);
+      if (keep && !ln.pre) Vec8<half_t>::store(ln.x_new + (size_t)r * d + cc, o[j]);
     }
   }
 }
@@ -1205,6 +1214,7 @@ hipError_t launch_self_block(const LnInput& ln, const void* Wqkv_packed, const v
   if (batch <= 0) return hipSuccess;
   if (!attention_blocks_supported(DT_F16, batch * beam, beam, H, d) || !Wqkv_packed || !bqkv || !Wo_packed || !Kc || !Vc ||
       !P_out || ln.splits < 0 || ln.splits > 4 || !ln.x_old || (ln.splits > 0 && (ln.x_old == ln.x_new || !ln.x_new)) ||
+      ((ln.splits > 0 || ln.pre) && (!ln.g || !ln.b)) || (ln.splits > 0 && (!ln.P || !ln.bias)) ||
       (long)beam * T * d * 2 > 0x7fffffffL)
     return hipErrorInvalidValue;
   dim3 g(batch * H), b(512);

@@ -190,6 +190,66 @@ static hipError_t add_layernorm_partials_t(T* x, T* y, const float* P, int split
   }
 }
 
+// Decoder-only models, first kernel of a step: x[r] = store(E[last token of r] * scale + pe[position]) and
+// y[r] = store(LN(x[r]) * g + b) in one launch (embed_last_kernel followed by the pre-LN kernel with no slabs: the same
+// arithmetic, LayerNorm sees the stored row).  One wavefront per row; d a multiple of 8, at most 64 * 8 * NV.
+template <typename T, int NV>
+__global__ void __launch_bounds__(64) embed_layernorm_kernel(const T* __restrict__ E, const float* __restrict__ pe,
+                                                             const int32_t* __restrict__ tokens,
+                                                             const int32_t* __restrict__ len, T* __restrict__ x,
+                                                             T* __restrict__ y, const T* __restrict__ g,
+                                                             const T* __restrict__ b, int rows, int d, int T1,
+                                                             const int32_t* __restrict__ tp, float scale, float eps) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  if (r >= rows) return;
+  const int t = *tp;
+  const int id = tokens[(size_t)r * T1 + len[r]];
+  const T* e = E + (size_t)id * d;
+  const float* per = pe + (size_t)t * d;
+  float v[NV][8], gv[NV][8], bv[NV][8];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = (j * 64 + lane) * 8;
+    if (c < d) {
+      Vec8<T>::load(e + c, v[j]);
+      Vec8<T>::load(g + c, gv[j]);
+      Vec8<T>::load(b + c, bv[j]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[j][i] = (float)(T)__fadd_rn(__fmul_rn(v[j][i], scale), per[c + i]);   // as embed_row stores it
+      Vec8<T>::store(x + (size_t)r * d + c, v[j]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { v[j][i] = 0.f; gv[j][i] = 0.f; bv[j][i] = 0.f; }
+    }
+  }
+  float o[NV][8];
+  layernorm_row<NV>(v, gv, bv, d, eps, lane, o);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = (j * 64 + lane) * 8;
+    if (c < d) Vec8<T>::store(y + (size_t)r * d + c, o[j]);
+  }
+}
+
+bool embed_layernorm_supported(int d) { return d % 8 == 0 && d <= 4096; }
+
+hipError_t launch_embed_layernorm(int dtype, const void* E, const float* pe, const int32_t* tokens, const int32_t* len,
+                                  void* x, void* y, const void* g, const void* b, int rows, int d, int T,
+                                  const int32_t* tp, float scale, float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (!embed_layernorm_supported(d)) return hipErrorInvalidValue;
+#define LSQ_EL(T_, NV_)                                                                                                   \
+  embed_layernorm_kernel<T_, NV_><<<rows, 64, 0, s>>>((const T_*)E, pe, tokens, len, (T_*)x, (T_*)y, (const T_*)g, (const T_*)b, \
+                                                      rows, d, T + 1, tp, scale, eps)
+  if (dtype == DT_F16) {
+    if (d <= 512) LSQ_EL(half_t, 1); else if (d <= 1024) LSQ_EL(half_t, 2); else if (d <= 2048) LSQ_EL(half_t, 4); else LSQ_EL(half_t, 8);
+  } else {
+    if (d <= 512) LSQ_EL(float, 1); else if (d <= 1024) LSQ_EL(float, 2); else if (d <= 2048) LSQ_EL(float, 4); else LSQ_EL(float, 8);
+  }
+#undef LSQ_EL
+  return hipGetLastError();
+}
+
 // y == nullptr: post-LN (x <- LN(x + sublayer)); y != nullptr: pre-LN (x <- x + sublayer, y <- LN(x)).
 hipError_t launch_add_layernorm_partials(int dtype, void* x, void* y, const float* P, int splits, const void* bias,
                                          const void* g, const void* b, int rows, int d, float eps, hipStream_t s,

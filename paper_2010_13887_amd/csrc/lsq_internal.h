@@ -83,6 +83,7 @@ struct LnInput {
   const half_t* x_old;
   half_t* x_new;
   float eps;
+  int pre;   // attention blocks only: pre-LN arithmetic (see block_row); the products take 0
 };
 bool gemm_ln_supported(int dtype, int M, int K);
 hipError_t launch_gemm_ln(const LnInput& ln, const void* B, const void* bias, const GemmOut& out, int M, int N,
@@ -96,6 +97,11 @@ hipError_t launch_embed_rows(int dtype, const void* E, const float* pe, const in
 hipError_t launch_embed_last(int dtype, const void* E, const float* pe, const int32_t* tokens,
                              const int32_t* len, void* x, int rows, int d, int T, const int32_t* tp,
                              float scale, hipStream_t s);
+// launch_embed_last followed by the pre-LN kernel without slabs (y = LN(x) * g + b), in one launch; same bits
+bool embed_layernorm_supported(int d);
+hipError_t launch_embed_layernorm(int dtype, const void* E, const float* pe, const int32_t* tokens, const int32_t* len,
+                                  void* x, void* y, const void* g, const void* b, int rows, int d, int T,
+                                  const int32_t* tp, float scale, float eps, hipStream_t s);
 hipError_t launch_scatter_kv(int dtype, const void* qkv, const int32_t* sent, const int32_t* pos, void* Kc,
                              void* Vc, int rows, int d, int T, hipStream_t s);
 // x_in (post-LN only): the residual is read from there instead of x, which is then only written

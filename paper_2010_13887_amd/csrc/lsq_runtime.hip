@@ -611,9 +611,54 @@ int launch_step_gpt(int B) {
   char* tmp = g.ws + p.d_tmp; char* ffn = g.ws + p.d_ffn; char* logits = g.ws + p.d_logits;
   int32_t* step = at<int32_t>(p.step_state);
   const size_t slab = (size_t)M_max * T * d * es;
-  TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, 1.0f, s));
-  TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, y, nullptr, 0, nullptr, g.gpt[0].ln1g, g.gpt[0].ln1b, M, d, hp.eps, s));
-  for (int l = 0; l < hp.n_dec; ++l) {
+  // Few rows, d <= 512: the attention sublayer of every block is one launch up to its output projection
+  // (kernels_attn.hip; a workgroup takes nq rows and one head), the LayerNorm kernel adds the per-head slabs, and
+  // the block of the next layer adds the FFN's partial sums on its way in.  Rows are independent here, so nq is
+  // free: one row per workgroup while that keeps the launch within one workgroup per CU, else two.
+  // Measured on whole translations (6 layers, prompt 64, 96 new tokens): d = 512, 8 / 32 / 64 rows: 16.18 -> 15.08,
+  // 18.06 -> 16.49, 23.51 -> 21.30 ms; d = 256, 32 rows: 16.59 -> 14.10 ms.  Behind at d = 768, where a workgroup
+  // streams 393 KB of weight slices through one CU (12 layers, 8 rows: 33.45 -> 35.03 ms; 32 rows: 0.427 -> 0.464 ms
+  // per step, the block at 15.7 us against 18.0 us for the four kernels it replaces, but 6.7 us instead of 3.9 for
+  // the LayerNorm over 12 slabs and the second FFN product held to 4 slabs).
+  int nq = 0;
+  if (g.fuse_ln && dt == DT_F16 && d <= 512 && M <= g.block_rows) {
+    if (attention_blocks_supported(dt, M, 1, H, d)) nq = 1;
+    if (M * H > 256 && M % 2 == 0 && attention_blocks_supported(dt, M, 2, H, d)) nq = 2;
+  }
+  if (nq) {
+    char* x_alt = g.ws + p.d_x2;
+    float* ffn_slabs = (float*)tmp;
+    float* head_slabs = (float*)(g.ws + p.d_tmp2);
+    TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, 1.0f, s));
+    int S = 0;                  // partial sums of the block before, still to be added to the residual stream
+    const void* pb = nullptr;   // ... and that product's bias
+    for (int l = 0; l < hp.n_dec; ++l) {
+      const GptLayer& L = g.gpt[l];
+      char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
+      char* Vc = Kc + slab;
+      const void *wqkv_p = gemm_packed_weights(L.Wqkv, 3 * d, d), *wo_p = gemm_packed_weights(L.Wo, d, d);
+      if (!wqkv_p || !wo_p) return fail(LSQ_E_STATE, "fragment-ordered weights missing");
+      LnInput ln = {ffn_slabs, S, (const half_t*)pb, (const half_t*)L.ln1g, (const half_t*)L.ln1b, (const half_t*)x,
+                    S ? (half_t*)x_alt : nullptr, hp.eps, 1};
+      TIMED(PC_SELF_BLOCK, launch_self_block(ln, wqkv_p, L.bqkv, wo_p, Kc, Vc, nullptr, step, 0, head_slabs, M / nq, nq, H, d, T, s));
+      if (S) std::swap(x, x_alt);
+      TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, y, head_slabs, H, L.bo, L.ln2g, L.ln2b, M, d, hp.eps, s));
+      TIMED(PC_GEMM_FFN1, launch_gemm(dt, y, L.W1, L.b1, plain_out(ffn, F), M, F, d, 2, s));
+      S = std::min(gemm_partial_splits(dt, M, d, F), kMaxSplitsFusedLn);
+      TIMED(PC_GEMM_FFN2, launch_gemm_partials(dt, ffn, L.W2, ffn_slabs, M, d, F, S, s));
+      pb = L.b2;
+    }
+    TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, y, ffn_slabs, S, pb, g.lnfg, g.lnfb, M, d, hp.eps, s));
+    g.hidden_in_alt = (x != g.ws + p.d_x);
+  } else if (g.fuse_ln && embed_layernorm_supported(d)) {
+    // the step's input rows and their first LayerNorm in one launch
+    TIMED(PC_EMBED, launch_embed_layernorm(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, y,
+                                           g.gpt[0].ln1g, g.gpt[0].ln1b, M, d, T, step, 1.0f, hp.eps, s));
+  } else {
+    TIMED(PC_EMBED, launch_embed_last(dt, g.E, at<float>(p.pe), at<int32_t>(p.tokens), at<int32_t>(p.len), x, M, d, T, step, 1.0f, s));
+    TIMED(PC_LAYERNORM, launch_add_layernorm_partials(dt, x, y, nullptr, 0, nullptr, g.gpt[0].ln1g, g.gpt[0].ln1b, M, d, hp.eps, s));
+  }
+  for (int l = 0; l < (nq ? 0 : hp.n_dec); ++l) {
     const GptLayer& L = g.gpt[l];
     char* Kc = g.ws + p.cache + (size_t)(2 * l) * slab;
     char* Vc = Kc + slab;
@@ -1417,15 +1462,17 @@ int lsq_k_layernorm_cross_attention(const float* P, int splits, const void* ln_b
 int lsq_k_self_attention_block(const float* P, int splits, const void* ln_bias, const void* gamma, const void* beta,
                                const void* x_old, void* x_new, float eps, const void* Wqkv_packed, const void* bqkv,
                                const void* Wo_packed, void* Kc, void* Vc, const int32_t* slab_table, int nkeys,
-                               float* P_out, int batch, int beam, int heads, int d, int T, void* stream) {
+                               float* P_out, int batch, int beam, int heads, int d, int T, int pre_ln, void* stream) {
   KCHK(x_old && Wqkv_packed && bqkv && Wo_packed && Kc && Vc && P_out, "null pointer");
   KCHK(splits >= 0 && splits <= 4, "0..4 slabs");
+  KCHK(pre_ln == 0 || pre_ln == 1, "pre_ln is 0 or 1");
   KCHK(splits == 0 || (P && ln_bias && gamma && beta && x_new && x_new != x_old), "LayerNorm inputs; x_new must not be x_old");
+  KCHK(!pre_ln || (gamma && beta), "pre-LN rows need gamma and beta");
   KCHK(batch >= 0 && T >= 1 && nkeys >= 0 && nkeys < T, "nkeys outside [0, T)");
   KCHK(batch == 0 || attention_blocks_supported(DT_F16, batch * beam, beam, heads, d),
        "float16, at most 64 rows, beam 1..4, heads of 64, d = 64 * heads a multiple of 256 up to 1024");
   LnInput ln = {P, splits, (const half_t*)ln_bias, (const half_t*)gamma, (const half_t*)beta, (const half_t*)x_old,
-                (half_t*)x_new, eps};
+                (half_t*)x_new, eps, pre_ln};
   KRUN(launch_self_block(ln, Wqkv_packed, bqkv, Wo_packed, Kc, Vc, slab_table, nullptr, nkeys, P_out, batch, beam, heads, d,
                          T, (hipStream_t)stream));
 }

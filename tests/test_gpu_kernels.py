@@ -335,18 +335,23 @@ def _ln_rows(x, P, lb, g, b):
     return O.layer_norm(x.astype(np.float64) + (P.astype(np.float64).sum(0) + lb), g.astype(np.float64), b.astype(np.float64), 1e-5)
 
 
-@pytest.mark.parametrize("B,beam,H,T,nkeys,splits,table", [
-    (1, 4, 16, 60, 0, 0, True),       # first step: no history, rows taken as they are
-    (1, 4, 16, 180, 171, 4, True),    # one sentence of the big model deep into a translation
-    (3, 4, 8, 70, 33, 2, True),       # base model shape
-    (16, 4, 16, 50, 17, 1, True),     # the most rows the kernel takes
-    (5, 3, 4, 40, 39, 3, False),      # the cache's last position, rows that keep their own slab, beam 3
-    (7, 2, 12, 90, 64, 4, True),      # four wavefronts per row
-    (9, 1, 8, 130, 129, 2, False),    # beam 1
+@pytest.mark.parametrize("B,beam,H,T,nkeys,splits,table,pre", [
+    (1, 4, 16, 60, 0, 0, True, False),       # first step: no history, rows taken as they are
+    (1, 4, 16, 180, 171, 4, True, False),    # one sentence of the big model deep into a translation
+    (3, 4, 8, 70, 33, 2, True, False),       # base model shape
+    (16, 4, 16, 50, 17, 1, True, False),     # the most rows the kernel takes
+    (5, 3, 4, 40, 39, 3, False, False),      # the cache's last position, rows that keep their own slab, beam 3
+    (7, 2, 12, 90, 64, 4, True, False),      # four wavefronts per row
+    (9, 1, 8, 130, 129, 2, False, False),    # beam 1
+    (16, 2, 12, 192, 100, 4, False, True),   # pre-LN model, GPT-2-small shape: rows in pairs
+    (8, 4, 12, 192, 63, 0, False, True),     # ... first layer: LayerNorm of the rows as they are
+    (31, 1, 8, 80, 79, 2, False, True),      # ... an odd row count
+    (16, 4, 4, 70, 0, 1, False, True),       # ... no history
 ])
-def test_self_attention_block(env, B, beam, H, T, nkeys, splits, table):
+def test_self_attention_block(env, B, beam, H, T, nkeys, splits, table, pre):
     """[LayerNorm +] QKV slice + cache append + self-attention + per-head output projection in one launch: every
-    stage against the oracle, stage by stage from the values the kernel itself stored before it."""
+    stage against the oracle, stage by stage from the values the kernel itself stored before it.  pre: the
+    arithmetic of pre-LN models (the residual sum is stored, its LayerNorm is multiplied)."""
     lsq, torch = env
     rng = np.random.default_rng(B * 131 + beam * 17 + H + nkeys)
     d, rows = H * 64, B * beam
@@ -367,10 +372,17 @@ def test_self_attention_block(env, B, beam, H, T, nkeys, splits, table):
     dWqkv, dWo = _dev(torch, Wqkv, h), _dev(torch, Wo, h)
     lsq.k_self_attention_block(dP if splits else None, _dev(torch, lb, h), _dev(torch, g, h), _dev(torch, b, h), dx,
                                x_new if splits else None, 1e-5, lsq.k_pack_weights(dWqkv), _dev(torch, bqkv, h),
-                               lsq.k_pack_weights(dWo), dK, dV, _dev(torch, slab) if table else None, nkeys, P_out, B, beam, H)
+                               lsq.k_pack_weights(dWo), dK, dV, _dev(torch, slab) if table else None, nkeys, P_out, B, beam, H,
+                               pre_ln=pre)
     assert torch.equal(dx, _dev(torch, x, h))
     # 1. the normalised rows
-    if splits:
+    if pre:
+        stream = x
+        if splits:   # the residual stream, stored; its LayerNorm is what the products see
+            stream = x_new.float().cpu().numpy()
+            np.testing.assert_allclose(stream, x.astype(np.float64) + (P[:splits].astype(np.float64).sum(0) + lb), rtol=1e-3, atol=1e-3)
+        got_rows = _h(O.layer_norm(stream.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5))
+    elif splits:
         got_rows = x_new.float().cpu().numpy()
         np.testing.assert_allclose(got_rows, _ln_rows(x, P[:splits], lb, g, b), rtol=2e-3, atol=2e-3)
     else:
