@@ -435,9 +435,11 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_large_ker
   };
 #pragma unroll
   for (int s = 0; s < D; ++s) gload(ra[s], rb[s], min(s, nk - 1) * BK);
-  // this lane's bias values, requested behind the first tiles
+  // this lane's bias values: requested behind the first tiles, or (eight accumulator tiles, which with them
+  // would not fit the 256 registers of two wavefronts per SIMD) after the k-loop
+  constexpr bool BIAS_LATE = TM * TN >= 8;
   float bv[TN][4][4];
-  {
+  auto load_bias = [&]() {
     const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 7) == 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -456,7 +458,8 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_large_ker
           for (int e = 0; e < 4; ++e) bv[j][vg][e] = (float)bias[min(n4 + e, N - 1)];
         }
       }
-  }
+  };
+  if (!BIAS_LATE) load_bias();
   sstore(ra[0], rb[0], 0);
   gload(ra[0], rb[0], min(D, nk - 1) * BK);
   __syncthreads();
@@ -479,6 +482,7 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN)) gemm_f16_large_ker
       __syncthreads();
     }
   }
+  if (BIAS_LATE) load_bias();
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wm + i * 32 + (lane & 31);
