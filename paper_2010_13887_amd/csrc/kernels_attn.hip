@@ -1417,8 +1417,12 @@ bool head_dim_supported(int dh) { return dh == 16 || dh == 32 || dh == 64 || dh 
     default: return hipErrorInvalidValue;         \
   }
 
-// up to this many (row, head) pairs a workgroup, not a wavefront, takes each pair
-constexpr int kSplitAttentionUnits = 2048;
+// up to this many (row, head) pairs a workgroup, not a wavefront, takes each pair: the launch would leave most of
+// the chip idle otherwise.  Beyond, one wavefront per pair with the beams of a sentence in one workgroup, which
+// fetches an ancestor they share once (whole translations of the big model, 16 heads: 32 sentences of beam 4 =
+// 2048 pairs 49.5 -> 46.3 ms, 16 sentences 41.7 -> 40.5 ms, the batch of 128 level, when the limit went from 2048
+// to 512 pairs; with no split at all the last sentences of a batch and 32 rows of 12 heads are 1-2 % slower)
+constexpr int kSplitAttentionUnits = 512;
 
 template <typename T>
 static hipError_t self_t(const T* q, const T* Kc, const T* Vc, T* out, int rows, int H, int d, int T_,
