@@ -707,6 +707,14 @@ __global__ void __launch_bounds__(256) gemm_f16_skinny_kernel(const half_t* __re
 
 constexpr int kSkinnyRows = 64;   // above this the LDS-tiled kernel is faster
 
+// Products with an epilogue (bias, activation, cache append, statistics): between 33 and 64 rows the skinny kernel's
+// two row blocks re-read the input rows in every 32-column workgroup, which from k = 768 on costs more than the
+// tiled kernels' LDS staging (per launch at 64 rows, skinny vs tiled: QKV of d = 1024 9.4 vs 8.0 us, of d = 768 8.4 vs
+// 7.4; FFN1 of d = 1024 9.4 vs 8.1; vocabulary 32000 x 1024 31.2 vs 23.0, 50257 x 768 53.0 vs 35.1; but FFN1 of
+// d = 512 6.5 vs 7.1, vocabulary 32000 x 512 16.7 vs 17.9).  Split-K partial products stay skinny up to 64 rows
+// (d x d: 4.5 vs 5.1-5.3 us).
+static bool skinny_rows(int M, int K) { return M <= 32 || (M <= kSkinnyRows && K < 768); }
+
 // k-steps requested per pass for a wavefront that owns `per_wave` of them: at most `cap`
 // (registers), and among the sizes built, the one that pads the last pass least.
 static int skinny_unroll(int per_wave, int cap) {
@@ -1054,7 +1062,7 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
 // mirrors launch_gemm's choice of kernel below: the skinny kernels and the large-tile kernel fill GemmOut::stats
 bool gemm_writes_stats(int dtype, int M, int N, int K) {
   if (dtype != DT_F16 || M <= 0 || N <= 0 || K <= 0 || K % 8 != 0) return false;
-  if (M <= kSkinnyRows) return K % 16 == 0;
+  if (M <= kSkinnyRows) return K % 16 == 0;   // the skinny kernel, or from 33 rows the large-tile kernel where it applies (launch_gemm)
   return (long)((M + 127) / 128) * ((N + 127) / 128) >= 200 && K % 64 == 0;
 }
 
@@ -1101,7 +1109,9 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (M <= kSkinnyRows && K % 16 == 0) {
+  // fragment-ordered weights are read by the skinny kernel only; of the others only the large-tile kernel leaves statistics
+  const bool large_ok = tiles128 >= 200 && K % 64 == 0;
+  if ((b_packed || skinny_rows(M, K) || (M <= kSkinnyRows && out.stats && !large_ok)) && K % 16 == 0) {
     const half_t* bpk = b_packed ? b : packed_of(B, N, K);
     if (out.f32_out) run_skinny<false, float>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
     else run_skinny<false, half_t>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);

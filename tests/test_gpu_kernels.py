@@ -122,7 +122,8 @@ def test_gemm_add_layernorm(env, rows, d, K, half):
 @pytest.mark.parametrize("f32_out", [False, True])
 def test_gemm_with_fragment_ordered_weights(env, M, N, K, f32_out):
     """lsq_k_pack_weights lays the matrix out exactly as documented, and a product that reads it gives
-    the same bits as the product that reads the row-major matrix (same fragments, same order)."""
+    the same bits as the product that reads the row-major matrix (same fragments, same order) wherever the
+    latter runs the same kernel: from 33 rows and k = 768 on it runs the tiled kernel (another summation order)."""
     lsq, torch = env
     rng = np.random.default_rng(M + N + K)
     A, W, bias = _h(rng.standard_normal((M, K))), _h(rng.standard_normal((N, K)) * 0.1), _h(rng.standard_normal(N))
@@ -139,7 +140,11 @@ def test_gemm_with_fragment_ordered_weights(env, M, N, K, f32_out):
     C2 = torch.full_like(C1, 9.0)
     lsq.k_gemm(dA, dW, dbias, C1, relu=True)
     lsq.k_gemm(dA, packed, dbias, C2, relu=True, packed=True)
-    assert torch.equal(C1, C2)
+    if M <= 32 or K < 768:
+        assert torch.equal(C1, C2)
+    else:
+        np.testing.assert_allclose(C1.double().cpu().numpy(), C2.double().cpu().numpy(), rtol=2e-3 if not f32_out else 1e-5,
+                                   atol=(2e-3 if not f32_out else 1e-5) * (1 + float(C2.abs().max())))
     want = np.maximum(A.astype(np.float64) @ W.astype(np.float64).T + bias, 0)
     np.testing.assert_allclose(C2.double().cpu().numpy(), want, rtol=2e-3 if not f32_out else 1e-5,
                                atol=(2e-3 if not f32_out else 1e-5) * (1 + np.abs(want).max()))
