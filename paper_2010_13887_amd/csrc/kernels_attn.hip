@@ -713,7 +713,23 @@ __global__ void __launch_bounds__(512) cross_attention_q_kernel(const half_t* __
 
 // Measured on whole steps of the big model: 0.678 -> 0.671 ms at 512 rows, nothing at 128 (a sentence of 125 keys
 // takes four dependent trips for its keys whichever kernel attends, and here they start only after the product).
-bool cross_attention_q_worthwhile(int rows) { return rows >= 256; }
+// sentences per workgroup: 8 (32 rows at beam 4) once that still gives a workgroup per CU, fewer below
+static int cross_q_group(int batch, int H) {
+  int GS = 8;
+  while (GS > 1 && (long)((batch + GS - 1) / GS) * H < 256) GS >>= 1;
+  return GS;
+}
+
+// Ahead of the two separate launches from 256 rows on, and below that where its workgroups, of at least two sentences
+// each, fill the CUs in one round (whole translations, 16 heads of the big model: 32 sentences = 256 workgroups
+// 46.2 -> 45.4 ms, 30 and 28 sentences level, 48 sentences = 384 workgroups 51.9 -> 54.4 ms, 20 sentences level;
+// 8 heads of d = 512, 32 sentences = 256 workgroups of one sentence: 34.7 -> 34.8 ms).
+bool cross_attention_q_worthwhile(int batch, int beam, int H) {
+  if (batch * beam >= 256) return true;
+  const int GS = cross_q_group(batch, H);
+  const long wgs = (long)((batch + GS - 1) / GS) * H;
+  return GS >= 2 && wgs >= 240 && wgs <= 256;
+}
 
 bool cross_attention_q_supported(int dtype, int rows, int beam, int H, int d) {
   return dtype == DT_F16 && rows > kCrossLnRows && beam >= 1 && beam <= 4 && rows % beam == 0 && H >= 1 && d == H * 64 &&
@@ -725,9 +741,7 @@ hipError_t launch_cross_attention_q(const void* x, const void* Wq_packed, const 
                                     int d, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   if (!cross_attention_q_supported(DT_F16, batch * beam, beam, H, d) || !Wq_packed || !bq) return hipErrorInvalidValue;
-  // sentences per workgroup: 8 (32 rows at beam 4) once that still gives a workgroup per CU, fewer below
-  int GS = 8;
-  while (GS > 1 && (long)((batch + GS - 1) / GS) * H < 256) GS >>= 1;
+  const int GS = cross_q_group(batch, H);
   dim3 g(((batch + GS - 1) / GS) * H), b(512);
 #define LSQ_CROSS_Q(NQ_)                                                                                      \
   cross_attention_q_kernel<NQ_><<<g, b, 0, s>>>((const half_t*)x, (const half_t*)Wq_packed, (const half_t*)kv, off, len, \

@@ -142,7 +142,7 @@ hipError_t launch_cross_attention_ln(const LnInput& ln, const void* Wq_packed, c
 // More than 64 rows alive (beams of 4 at most, head size 64, float16, d <= 1024): query product and cross-attention
 // in one launch; x holds the normalised rows.
 bool cross_attention_q_supported(int dtype, int rows, int beam, int H, int d);
-bool cross_attention_q_worthwhile(int rows);   // where it is ahead of the two separate launches
+bool cross_attention_q_worthwhile(int batch, int beam, int H);   // where it is ahead of the two separate launches
 hipError_t launch_cross_attention_q(const void* x, const void* Wq_packed, const void* bq, const void* kv,
                                     const int32_t* off, const int32_t* len, void* out, int batch, int beam, int H,
                                     int d, hipStream_t s);

@@ -492,7 +492,7 @@ int launch_step(int B) {
                                                      at<int32_t>(p.src_len), ctx, B, k, H, d, s));
       std::swap(x, x_alt); swapped();
       pending.on = false;
-    } else if (const void* wq_p = (g.fuse_ln && !pending.on && cross_attention_q_worthwhile(M) && cross_attention_q_supported(dt, M, k, H, d))
+    } else if (const void* wq_p = (g.fuse_ln && !pending.on && cross_attention_q_worthwhile(B, k, H) && cross_attention_q_supported(dt, M, k, H, d))
                                       ? gemm_packed_weights(L.Wq, d, d) : nullptr) {
       // many rows: the attention kernel still makes its own queries (the rows are normalised already)
       TIMED(PC_ATTN_CROSS_Q, launch_cross_attention_q(x, wq_p, L.bq, g.ws + p.cross + l * cross_l, at<int32_t>(p.src_off),
