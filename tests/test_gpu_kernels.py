@@ -30,7 +30,10 @@ def _h(a):       # round to fp16 and widen: the values an fp16 tensor holds
 
 @pytest.mark.parametrize("M,N,K", [(8, 192, 64), (33, 1000, 72), (130, 520, 256), (512, 1024, 1024),
                                    (512, 3072, 1024), (100, 1003, 264), (512, 32000, 1024), (1, 64, 8),
-                                   (700, 136, 4096)])
+                                   (700, 136, 4096),
+                                   # more than 256 tiles of 64x64, k a multiple of 64: tiles loaded straight into LDS;
+                                   # ragged rows and columns, fewer k-tiles than stages, unaligned output rows
+                                   (300, 4100, 128), (321, 3071, 64), (450, 2500, 1024), (257, 4224, 320)])
 @pytest.mark.parametrize("relu", [False, True])
 def test_gemm_fp16(env, M, N, K, relu):
     lsq, torch = env
