@@ -22,14 +22,19 @@ __device__ __forceinline__ float activate(float v, int act) {
   return v;
 }
 
+// four floats that are only 4-byte aligned: still one store instruction (the target allows dword-aligned
+// multi-dword accesses to global memory, and the compiler uses them for this type)
+struct __attribute__((packed, aligned(4))) float4_dword_aligned { float a, b, c, d; };
+
 // Stores four consecutive outputs (m, n..n+3) of a tile: split-K slab, vector, or element-wise
-// fallback for ragged / unaligned rows.
+// fallback for ragged / unaligned rows.  vec_ok: 1 = the four lie in one segment and are aligned to their size;
+// 2 = float output of a single segment whose rows are not 16-byte aligned (an odd vocabulary size).
 template <typename OutT, bool SPLIT>
 __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const float (&v)[4], int M, int N,
                                        int vec_ok, int slab, long tp) {
   if constexpr (SPLIT) {
     float* dst = reinterpret_cast<float*>(out.ptr[0]) + ((size_t)slab * M + m) * N + n;
-    if (vec_ok && n + 3 < N) {
+    if (vec_ok == 1 && n + 3 < N) {
       floatx4 f = {v[0], v[1], v[2], v[3]};
       *reinterpret_cast<floatx4*>(dst) = f;
     } else {
@@ -37,7 +42,11 @@ __device__ __forceinline__ void store4(const GemmOut& out, int m, int n, const f
       for (int e = 0; e < 4; ++e)
         if (n + e < N) dst[e] = v[e];
     }
-  } else if (vec_ok && n + 3 < N) {
+  } else if (vec_ok == 2 && n + 3 < N && sizeof(OutT) == 4) {
+    float* dst = reinterpret_cast<float*>(out.ptr[0]) + (long)m * out.ld[0] + tp * out.tmul[0] + n;
+    const float4_dword_aligned f = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<float4_dword_aligned*>(dst) = f;
+  } else if (vec_ok == 1 && n + 3 < N) {
     int s = n / out.seg_n;
     OutT* dst = reinterpret_cast<OutT*>(out.ptr[s]) + (long)m * out.ld[s] + tp * out.tmul[s] + (n - s * out.seg_n);
     if constexpr (sizeof(OutT) == 2) {
@@ -1261,6 +1270,8 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   int vec_ok = (out.seg_n % 4 == 0);
   for (int i = 0; i < nseg; ++i)
     if (out.ld[i] % 4 != 0 || out.tmul[i] % 4 != 0 || (reinterpret_cast<uintptr_t>(out.ptr[i]) & (out.f32_out ? 15 : 7)) != 0) vec_ok = 0;
+  // float rows of one segment that are not 16-byte aligned (an odd vocabulary size): dword-aligned vector stores
+  if (!vec_ok && out.f32_out && nseg == 1 && (reinterpret_cast<uintptr_t>(out.ptr[0]) & 3) == 0) vec_ok = 2;
   const half_t* a = (const half_t*)A;
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
