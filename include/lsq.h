@@ -390,9 +390,8 @@ int lsq_k_row_topk(int dtype, const void* logits, const float* score, const int3
  * nothing rounded) and, for every row m and every group g of 32 consecutive columns,
  *   stats[(m * G + g) * 2 + 0] = largest C[m, n] of the group,
  *   stats[(m * G + g) * 2 + 1] = sum over the group of exp(C[m, n] - largest),   G = ceil(N / 32).
- * Only for shapes whose kernel writes them: lsq_k_gemm_logits_supported(M, N, K) != 0 (at most 64
- * rows with K a multiple of 16; more rows when N is large and K a multiple of 64), else
- * LSQ_E_ARG.  All device pointers, 16-byte aligned; stats M * G * 2 floats. */
+ * lsq_k_gemm_logits_supported(M, N, K) != 0 says that the shape is taken (every float16 product
+ * kernel writes them: K a multiple of 8), else LSQ_E_ARG.  All device pointers, 16-byte aligned; stats M * G * 2 floats. */
 int lsq_k_gemm_logits(const void* A, const void* B, void* C, float* stats, int M, int N, int K, void* stream);
 int lsq_k_gemm_logits_supported(int M, int N, int K);
 

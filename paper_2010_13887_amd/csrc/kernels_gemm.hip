@@ -358,6 +358,40 @@ __global__ void __launch_bounds__(64 * (BM / WM) * (BN / WN) * KG) gemm_f16_kern
       }
     }
   }
+  if constexpr (std::is_same<OutT, float>::value && !SPLIT) {
+    // (largest, sum of exponentials) of every (row, 32-column group), as in the large-tile kernel below: a 32x32
+    // block holds a group's 32 columns of a row in the two lanes (m, half 0) and (m, half 1)
+    if (out.stats) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm + i * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int nb = n0 + wn + j * 32;
+          if (nb >= N) continue;   // the same in every lane
+          float x[16], mx = -INFINITY;
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int n = nb + vg * 8 + (lane >> 5) * 4 + e;
+              x[vg * 4 + e] = n < N ? activate(acc[i][j][vg * 4 + e] + bv[j][vg][e], act) : -INFINITY;
+              mx = fmaxf(mx, x[vg * 4 + e]);
+            }
+          mx = max_lane_xor<32>(mx);   // finite: column nb exists
+          float z = 0.f;
+#pragma unroll
+          for (int q = 0; q < 16; ++q) z += __expf(x[q] - mx);
+          z = add_lane_xor<32>(z);
+          if (lane < 32 && m < M) {
+            float* st = out.stats + ((size_t)m * out.stats_groups + nb / 32) * 2;
+            st[0] = mx;
+            st[1] = z;
+          }
+        }
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1224,11 +1258,9 @@ hipError_t launch_gemm_partials(int dtype, const void* A, const void* B, float* 
   return hipGetLastError();
 }
 
-// mirrors launch_gemm's choice of kernel below: the skinny kernels and the large-tile kernel fill GemmOut::stats
+// every float16 product kernel launch_gemm chooses for a float32 output can fill GemmOut::stats
 bool gemm_writes_stats(int dtype, int M, int N, int K) {
-  if (dtype != DT_F16 || M <= 0 || N <= 0 || K <= 0 || K % 8 != 0) return false;
-  if (M <= kSkinnyRows) return K % 16 == 0;   // the skinny kernel, or from 33 rows the large-tile kernel where it applies (launch_gemm)
-  return (long)((M + 127) / 128) * ((N + 127) / 128) >= 200 && K % 64 == 0;
+  return dtype == DT_F16 && M > 0 && N > 0 && K > 0 && K % 8 == 0;
 }
 
 hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias, const GemmOut& out, int M,
@@ -1276,14 +1308,20 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  // fragment-ordered weights are read by the skinny kernel only; of the others only the large-tile kernel leaves statistics
-  const bool large_ok = tiles128 >= 200 && K % 64 == 0;
-  if ((b_packed || skinny_rows(M, K) || (M <= kSkinnyRows && out.stats && !large_ok)) && K % 16 == 0) {
+  // A vocabulary-sized product of few rows (125 or more tiles of 128 columns) streams its weights best through the
+  // tiled kernel, whose workgroups share the staged input rows (weights from memory, 32 rows: 32000 x 1024 22.6 ->
+  // 14.4 us, 50257 x 768 31.9 -> 19.5 us, 32000 x 512 11.9 -> 9.2 us; 64 rows: 32000 x 1024 20.7 (large tiles) -> 16.1 us,
+  // 32000 x 512 16.5 -> 11.3 us; level at 4 and 8 rows): the skinny kernel's 1000-1571 workgroups of 32 columns each
+  // fetch the rows again and run in one and a half rounds.  Fragment-ordered weights are read by the skinny kernel only.
+  const bool wide = (N + 127) / 128 >= 125;
+  if ((b_packed || (skinny_rows(M, K) && !wide)) && K % 16 == 0) {
     const half_t* bpk = b_packed ? b : packed_of(B, N, K);
     if (out.f32_out) run_skinny<false, float>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
     else run_skinny<false, half_t>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
   } else if (M <= 32)
     run_f16<32, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
+  else if (M <= 64 && wide)
+    run_f16<64, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   else if (tiles128 >= 200 && K % 64 == 0) {
     // enough 128x128 tiles to fill the chip (vocabulary product from 65 rows up, encoder and prefill
     // layers).  256x256 tiles (144 KB of LDS, eight wavefronts of 128x64) once there are about as many of
@@ -1300,7 +1338,7 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
     // into the CU and keep its LDS pipe as busy as two four-wave workgroups would.  With k a multiple of 64 the
     // tiles go straight into LDS, five deep (in the step at 512 rows: QKV 12.9 -> 12.3 us, FFN1 13.2 -> 12.6 us;
     // the split-K products on 64x64 tiles lost 0.5 us with it and keep the register-staged kernel)
-    if (K % 64 == 0) run_f16_direct<64, 128, false, 5>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
+    if (K % 64 == 0 && !out.stats) run_f16_direct<64, 128, false, 5>(a, b, bi, out, M, N, K, act, vec_ok, 1, s);
     else run_f16<64, 128, 64, 32, 32, 4>(a, b, bi, out, M, N, K, act, vec_ok, s);
   }
   else if ((long)((M + 63) / 64) * ((N + 63) / 64) <= 128)

@@ -33,7 +33,7 @@ struct GemmOut {
   // Optional, fp32 output of a float16 product only (vocabulary logits): for every row and every group of 32
   // consecutive output columns the pair (largest value, sum of exp(value - largest)) at
   // stats[(m * stats_groups + n / 32) * 2]: the group maxima of the retrieve stage (paper sec. 2.2) and the
-  // softmax normaliser, taken where the logits are made.  Only the kernels gemm_writes_stats names fill it.
+  // softmax normaliser, taken where the logits are made.  Every float16 product kernel but the direct-to-LDS one fills it (gemm_writes_stats).
   float* stats;
   int stats_groups;
 };
