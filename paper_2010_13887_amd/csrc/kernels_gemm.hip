@@ -1308,12 +1308,14 @@ hipError_t launch_gemm(int dtype, const void* A, const void* B, const void* bias
   const half_t* b = (const half_t*)B;
   const half_t* bi = (const half_t*)bias;
   long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  // A vocabulary-sized product of few rows (125 or more tiles of 128 columns) streams its weights best through the
-  // tiled kernel, whose workgroups share the staged input rows (weights from memory, 32 rows: 32000 x 1024 22.6 ->
-  // 14.4 us, 50257 x 768 31.9 -> 19.5 us, 32000 x 512 11.9 -> 9.2 us; 64 rows: 32000 x 1024 20.7 (large tiles) -> 16.1 us,
-  // 32000 x 512 16.5 -> 11.3 us; level at 4 and 8 rows): the skinny kernel's 1000-1571 workgroups of 32 columns each
-  // fetch the rows again and run in one and a half rounds.  Fragment-ordered weights are read by the skinny kernel only.
-  const bool wide = (N + 127) / 128 >= 125;
+  // A vocabulary-sized product (125 or more tiles of 128 columns) of 33 to 64 rows runs the tiled kernel on 64x128
+  // tiles: whole translations of 16 sentences of the big model 39.5 -> 39.0 ms, level for d = 512 and 768.  Up to 32
+  // rows the skinny kernel stays: alone and with its weights coming from memory the tiled kernel is far ahead there
+  // (32 rows of 32000 x 1024: 22.6 -> 14.4 us, of 50257 x 768: 31.9 -> 19.5 us), but inside a step, where much of the
+  // embedding is still in the memory-side cache, it is level or behind (32 rows of 32000 x 512: 9.6 -> 12.0 us in the
+  // step; translations of Transformer-base 25.1 -> 25.6 ms, of the GPT-2-small shape 57.1 -> 56.8 ms).
+  // Fragment-ordered weights are read by the skinny kernel only.
+  const bool wide = (N + 127) / 128 >= 125 && M > 32;
   if ((b_packed || (skinny_rows(M, K) && !wide)) && K % 16 == 0) {
     const half_t* bpk = b_packed ? b : packed_of(B, N, K);
     if (out.f32_out) run_skinny<false, float>(a, b, bpk, bi, out, M, N, K, act, vec_ok, 1, s);
